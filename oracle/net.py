@@ -1,0 +1,172 @@
+"""Runs a synthetic integer network (workloads.nets) through the CPU oracle, and
+calibrates it.  TEST INFRASTRUCTURE (see oracle/icnn_oracle.c).
+
+`calibrate(net, seed)` walks the layers once over the calibration images and
+fixes every layer's integers from the statistics it sees (Section 3.3, Section
+4.1, Algorithm 2); `run(net, seed, calib)` then evaluates the network with
+those integers.  Both return every intermediate buffer so the HIP path can be
+compared layer by layer.
+"""
+from fractions import Fraction
+
+import numpy as np
+
+from workloads import nets as W
+from . import calibrate as K
+from . import oracle as O
+
+INPUT_RATIO = 256            # raw - 128 stands for a float input in [-0.5, 0.5)
+REGRESSION_LEVELS = 32       # 99.9th-percentile |residual| maps to this many pixel levels
+
+
+def _alloc(net, name, images):
+    b = net["buffers"][name]
+    shape = [min(b["shape"][0], images)] + b["shape"][1:]
+    return np.zeros(shape, dtype=np.int32 if b["dtype"] == "s32" else np.uint8)
+
+
+def _conv(op, bufs, w, bias, cal, out, out_mode=None, use_res=True):
+    om = op["out_mode"] if out_mode is None else out_mode
+    kw = dict(stride=op["stride"], pad=op["pad"], in_sub128=op["in_sub128"], cin=op["cin"],
+              out_mode=om, mul=cal.get("mul", 1), shift=cal.get("shift", 0),
+              bound_q=cal.get("bound_q", K.MAX_INT), lo=cal.get("lo", 0), hi=cal.get("hi", 255))
+    if op["res"] is not None and use_res:
+        kw.update(res=bufs[op["res"]], res_mode=op["res_mode"],
+                  res_mul=cal.get("res_mul", 1), res_shift=cal.get("res_shift", 0))
+    if out is None:
+        return O.conv2d(bufs[op["src"]], w, bias, **kw)
+    return O.conv2d(bufs[op["src"]], w, bias, out=out, out_c_offset=op["dst_c_offset"], **kw)
+
+
+def run(net, seed, calib, images=None, x_raw=None):
+    """Evaluate `net` with stored calibration integers; returns {buffer: array}."""
+    n_img = net["buffers"]["raw"]["shape"][0] if images is None else images
+    bufs = {"raw": W.input_tensor(net, seed, n_img) if x_raw is None else x_raw}
+    for op in net["ops"]:
+        if op["dst"] not in bufs:
+            bufs[op["dst"]] = _alloc(net, op["dst"], n_img)
+        if op["op"] == "conv":
+            _conv(op, bufs, W.weight_tensor(op, seed), W.bias_tensor(op, seed),
+                  calib["conv"][op["name"]], bufs[op["dst"]])
+        elif op["op"] == "maxpool":
+            bufs[op["dst"]] = O.maxpool2d(bufs[op["src"]], op["k"], op["stride"], op["pad"])
+        elif op["op"] == "avgpool":
+            c = calib["avgpool"][op["dst"]]
+            bufs[op["dst"]] = O.avgpool_global(bufs[op["src"]], c["mul"], c["shift"], c["bound_q"])
+        else:
+            raise ValueError(op["op"])
+    return bufs
+
+
+def calibrate(net, seed):
+    """Returns (calib, buffers on the calibration images).
+
+    calib = {"conv": {name: {...integers...}}, "avgpool": {dst: {...}}, "ratio": {...}}
+    """
+    n_img = net["calib_images"]
+    bufs = {"raw": W.input_tensor(net, seed, n_img)}
+    ratio = {"raw": Fraction(INPUT_RATIO)}      # ratio_V of every stored buffer
+    calib = {"conv": {}, "avgpool": {}}
+    ops = net["ops"]
+    i = 0
+    while i < len(ops):
+        op = ops[i]
+        if op["op"] == "maxpool":
+            bufs[op["dst"]] = O.maxpool2d(bufs[op["src"]], op["k"], op["stride"], op["pad"])
+            ratio[op["dst"]] = ratio[op["src"]]
+            i += 1
+            continue
+        if op["op"] == "avgpool":
+            _, h, w, _ = bufs[op["src"]].shape
+            m, s = K.mul_shift(h * w, 1)
+            calib["avgpool"][op["dst"]] = {"mul": m, "shift": s, "bound_q": K.MAX_INT}
+            bufs[op["dst"]] = O.avgpool_global(bufs[op["src"]], m, s, K.MAX_INT)
+            ratio[op["dst"]] = ratio[op["src"]]
+            i += 1
+            continue
+        # conv ops; the branches of one concatenation are calibrated together
+        group = [op]
+        if op["group"] is not None:
+            while i + len(group) < len(ops) and ops[i + len(group)].get("group") == op["group"]:
+                group.append(ops[i + len(group)])
+        wts = [W.weight_tensor(g, seed) for g in group]
+        bss = [W.bias_tensor(g, seed) for g in group]
+        ratio_y = [ratio[g["src"]] * Fraction(K.MAX_INT) / Fraction(W.float_weight_absmax(g, seed))
+                   for g in group]
+        if op["dst"] not in bufs:
+            bufs[op["dst"]] = _alloc(net, op["dst"], n_img)
+        if op["group"] is not None:
+            h_ri = []
+            for g, w, b in zip(group, wts, bss):
+                t = _conv(g, bufs, w, b, {}, None, out_mode="raw_s32")
+                h_ri.append(K.percentile_999(t))
+            params, r_min = K.sync_concat(h_ri, ratio_y)
+            for g, w, b, (m, s, bq), h in zip(group, wts, bss, params, h_ri):
+                cal = {"mul": m, "shift": s, "bound_q": bq, "h_ri": h}
+                calib["conv"][g["name"]] = cal
+                _conv(g, bufs, w, b, cal, bufs[g["dst"]])
+            ratio[op["dst"]] = r_min
+            i += len(group)
+            continue
+        w, b, ry = wts[0], bss[0], ratio_y[0]
+        cal = {}
+        if op["res_mode"] == "pre":
+            # first the main path alone fixes the skip rescale, then the merged sum fixes the bound
+            y = _conv(op, bufs, w, b, {}, None, out_mode="raw_s32", use_res=False)
+            h_main = K.percentile_999(y)
+            if op["res_dtype"] == "s32":
+                h_skip = K.percentile_999(bufs[op["res"]])
+            else:
+                h_skip = K.MAX_INT
+            cal["res_mul"], cal["res_shift"] = K.mul_shift(h_skip, h_main)
+        if op["out_mode"] == "raw_s32":
+            calib["conv"][op["name"]] = cal
+            _conv(op, bufs, w, b, cal, bufs[op["dst"]])
+            ratio[op["dst"]] = ry
+        elif op["role"] == "regression_out":
+            y = _conv(op, bufs, w, b, {}, None, out_mode="raw_s32", use_res=False)
+            h = K.percentile_999(y, absolute=True)
+            m, s = K.mul_shift(h, REGRESSION_LEVELS)
+            cal.update(mul=m, shift=s, lo=0, hi=255, res_mul=1, res_shift=0, h_ri=h)
+            calib["conv"][op["name"]] = cal
+            _conv(op, bufs, w, b, cal, bufs[op["dst"]])
+            ratio[op["dst"]] = Fraction(1)
+        else:
+            t = _conv(op, bufs, w, b, cal, None, out_mode="raw_s32")
+            h = K.percentile_999(t)
+            m, s = K.bound_params(h)
+            cal.update(mul=m, shift=s, bound_q=K.MAX_INT, h_ri=h)
+            calib["conv"][op["name"]] = cal
+            _conv(op, bufs, w, b, cal, bufs[op["dst"]])
+            ratio[op["dst"]] = ry * m / (1 << s)
+        i += 1
+    calib["ratio"] = {k: float(v) for k, v in ratio.items()}
+    return calib, bufs
+
+
+def stored_calib_path(cfg, seed):
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    return os.path.join(root, "workloads", "calib", "%s_seed%d.json" % (cfg, seed))
+
+
+def write_stored_calib(cfg, seed):
+    """Calibrate config `cfg` with the oracle and store the integers for bench and tests."""
+    import json
+    net = W.CONFIGS[cfg]()
+    calib, _ = calibrate(net, seed)
+    calib["net"] = net["name"]
+    calib["seed"] = seed
+    calib["written_by"] = "oracle/net.py write_stored_calib (calls only oracle/)"
+    path = stored_calib_path(cfg, seed)
+    with open(path, "w") as f:
+        json.dump(calib, f, indent=1, sort_keys=True)
+    return path
+
+
+if __name__ == "__main__":
+    import sys
+    import time
+    for name in sys.argv[1:] or ["cfg0", "cfg1", "cfg2", "cfg3", "cfg4"]:
+        t0 = time.time()
+        print(write_stored_calib(name, 0), "%.1fs" % (time.time() - t0), flush=True)
