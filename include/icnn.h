@@ -1,0 +1,199 @@
+/*
+ * icnn.h -- C boundary of the MI355X integer-only CNN inference library.
+ *
+ * The library implements the inference hot path of "Efficient
+ * Integer-Arithmetic-Only Convolutional Neural Networks": an 8-bit integer
+ * convolution layer with an integer-only epilogue, the rescaled feature-map
+ * addition used at residual merges, and concatenation of branches that carry
+ * different scales.
+ *
+ * Conventions shared by every entry point
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller; the library
+ *     never allocates, frees or keeps device memory.  Descriptor structs and the
+ *     small arrays of iconcat are HOST memory, read during the call only.
+ *   - Activations are NHWC, 8 bits per element.  "Channel pitch" (c_stride) is
+ *     the number of elements between consecutive pixels; it may exceed the
+ *     channel count so that a layer can read or write a slice of a wider buffer.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work and return; they never synchronise.
+ *   - Return value: 0 on success, a negative icnn_status otherwise.  Arguments
+ *     are checked on the host before anything is launched; a failed call has
+ *     enqueued nothing.  icnn_last_error() describes the last failure on the
+ *     calling thread.
+ *   - [x] below means round half up, floor(x + 1/2), for negative x too; a
+ *     shift of 0 adds no rounding term.  sat32() saturates to int32.
+ */
+#ifndef ICNN_H
+#define ICNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ICNN_OK = 0,
+    ICNN_E_NULL = -1,        /* a required pointer is NULL                        */
+    ICNN_E_SHAPE = -2,       /* sizes non-positive, inconsistent or too large     */
+    ICNN_E_PARAM = -3,       /* mul / shift / bound / mode outside its domain     */
+    ICNN_E_ALIGN = -4,       /* pointer or pitch alignment the library needs      */
+    ICNN_E_UNSUPPORTED = -5, /* valid request this build does not implement       */
+    ICNN_E_LAUNCH = -6       /* the HIP runtime refused a launch                  */
+} icnn_status;
+
+typedef enum { ICNN_U8 = 0, ICNN_S8 = 1, ICNN_S32 = 2 } icnn_dtype;
+
+typedef enum {
+    ICNN_OUT_BRELU_U8 = 0,   /* clamp to [0, bound_q], store uint8                */
+    ICNN_OUT_CLAMP_U8 = 1,   /* clamp to [lo, hi] within [0, 255], store uint8    */
+    ICNN_OUT_LINEAR_S8 = 2,  /* clamp to [-128, 127], store int8                  */
+    ICNN_OUT_RAW_S32 = 3     /* store T itself as int32: no requantisation        */
+} icnn_out_mode;
+
+typedef enum {
+    ICNN_RES_NONE = 0,
+    ICNN_RES_PRE = 1,        /* skip operand joins before BReLU / requantisation  */
+    ICNN_RES_POST = 2        /* skip operand joins after requantisation           */
+} icnn_res_mode;
+
+/*
+ * One quantised convolution layer (Section 3.1 and Figure 1: X_i, W_i, b_i, then
+ * BReLU and quantisation to V_i; Section 3.2.1: V = [Y * mul / 2^shift]; Section
+ * 3.3: the bound h_i corresponds to max_int = bound_q).
+ *
+ *   U[n,ho,wo,co] = sum_{kh,kw,ci} x(n, ho*stride_h - pad_h + kh, wo*stride_w - pad_w + kw, ci)
+ *                                  * W[co][kh][kw][ci]
+ *       x() is 0 outside the image; inside it is the stored byte read as uint8
+ *       (in_signed = 0), as int8 (in_signed = 1), or as uint8 minus 128
+ *       (in_sub128 = 1: the re-normalisation of a raw picture, Section 3.4.1).
+ *   Y = U + bias[co]
+ *   S = [res * res_mul / 2^res_shift]                       (res_mode != NONE)
+ *   T = sat32(Y + S) if res_mode == PRE, else Y             (Section 4.1: the skip
+ *       operand is rescaled to the main path's ratio and added before BReLU)
+ *   RAW_S32:  out = T
+ *   else:     Q = [T * mul / 2^shift];  if res_mode == POST: Q += S
+ *             out = clamp(Q, lo', hi')  with (lo', hi') = (0, bound_q), (lo, hi)
+ *             or (-128, 127) by out_mode.
+ * Clamping after requantisation equals BReLU before it, because the map is
+ * monotone and sends h_i to bound_q.
+ *
+ * out is NHWC [n, ho, wo, out_c_stride]; channel co is written at
+ * out_c_offset + co and no other element is touched, so several layers can fill
+ * disjoint channel ranges of one buffer (concatenation without a copy, the
+ * online half of Algorithm 2: each branch carries its own mul, shift, bound_q).
+ */
+typedef struct {
+    int32_t n, h, w, cin;          /* logical input shape                          */
+    int32_t in_c_stride;           /* channel pitch of x, >= cin                   */
+    int32_t in_signed;             /* 0: uint8 bytes, 1: int8 bytes                */
+    int32_t in_sub128;             /* 1: raw uint8 picture, use x - 128            */
+    int32_t cout, kh, kw;
+    int32_t stride_h, stride_w, pad_h, pad_w;
+    int32_t out_c_stride, out_c_offset;
+    int32_t mul, shift;            /* 1 <= mul < 2^31, 0 <= shift <= 62            */
+    int32_t bound_q;               /* 1..255; used by ICNN_OUT_BRELU_U8            */
+    int32_t lo, hi;                /* 0 <= lo <= hi <= 255; ICNN_OUT_CLAMP_U8 only */
+    int32_t out_mode;              /* icnn_out_mode                                */
+    int32_t res_mode;              /* icnn_res_mode                                */
+    int32_t res_dtype;             /* icnn_dtype of the skip operand               */
+    int32_t res_c_stride;          /* channel pitch of res, >= cout                */
+    int32_t res_mul, res_shift;    /* 1 <= res_mul < 2^31, 0 <= res_shift <= 62    */
+} icnn_conv_desc;
+
+/* Library version, major*10000 + minor*100 + patch. */
+int icnn_version(void);
+
+/* Message for the last negative return on this thread ("" if none).  The string
+ * is owned by the library and valid until the thread's next failing call. */
+const char *icnn_last_error(void);
+
+/* Host-only check of a descriptor: the same validation iconv2d_brelu performs,
+ * without touching the GPU.  Rejects, among others, kh*kw*cin > 65535 (beyond it
+ * the int32 accumulator is no longer provably safe) and unsigned inputs combined
+ * with bound semantics the int8 matrix cores cannot take (in_signed = 0 means the
+ * caller guarantees bytes <= 127, as produced by bound_q <= 127). */
+int iconv2d_validate(const icnn_conv_desc *desc);
+
+/* Output height and width of the layer (host only). */
+int iconv2d_out_hw(const icnn_conv_desc *desc, int32_t *ho, int32_t *wo);
+
+/* Bytes of device workspace iconv2d_brelu needs for this layer (may be 0). */
+int iconv2d_workspace_bytes(const icnn_conv_desc *desc, size_t *bytes);
+
+/* Bytes of the library's packed weight format for this layer. */
+int iconv2d_packed_weight_bytes(const icnn_conv_desc *desc, size_t *bytes);
+
+/* Reorders int8 weights [cout][kh][kw][cin] (device) into the packed format
+ * (device, 16-byte aligned, iconv2d_packed_weight_bytes bytes).  Done once per
+ * layer, outside the inference loop. */
+int iconv2d_prepack_weights(const icnn_conv_desc *desc, const int8_t *w_ohwi,
+                            void *w_packed, void *stream);
+
+/* The integer convolution layer defined above.  x: input activations; w_packed:
+ * from iconv2d_prepack_weights; bias: int32 [cout]; res: skip operand over the
+ * output pixels (NULL iff res_mode == NONE); y: output; workspace: at least
+ * iconv2d_workspace_bytes bytes (may be NULL when that is 0).
+ * Alignment: x, y and res 16-byte aligned with pitches that are multiples of 16
+ * select the vector paths; anything else takes slower element-wise paths with
+ * identical results. */
+int iconv2d_brelu(const icnn_conv_desc *desc, const void *x, const void *w_packed,
+                  const int32_t *bias, const void *res, void *y, void *workspace,
+                  void *stream);
+
+/*
+ * Rescaled feature-map addition (ratio synchronisation between feature maps,
+ * Sections 3.4.2 and 4.1), as a stand-alone pass over memory:
+ *   T   = sat32(a + [b * b_mul / 2^b_shift])
+ *   out = T                                   (ICNN_OUT_RAW_S32)
+ *       = clamp([T * mul / 2^shift], lo, hi)  (ICNN_OUT_CLAMP_U8: 0<=lo<=hi<=255;
+ *                                              ICNN_OUT_LINEAR_S8: range is [-128,127])
+ * a, b: count_pixels x c elements of a_dtype / b_dtype with the given pitches.
+ */
+typedef struct {
+    int64_t count_pixels;
+    int32_t c;
+    int32_t a_c_stride, b_c_stride, out_c_stride, out_c_offset;
+    int32_t a_dtype, b_dtype;      /* icnn_dtype                                   */
+    int32_t out_mode;              /* CLAMP_U8, LINEAR_S8 or RAW_S32               */
+    int32_t b_mul, b_shift, mul, shift, lo, hi;
+} icnn_add_desc;
+
+int iadd_rescale(const icnn_add_desc *desc, const void *a, const void *b, void *out,
+                 void *stream);
+
+/*
+ * Explicit concatenation on the channel axis with per-input ratio
+ * synchronisation (Algorithm 2, online half): input i (uint8, c_in[i] channels,
+ * pitch in_c_stride[i]) lands at channel offset c_in[0] + ... + c_in[i-1] as
+ *   clamp([in_i * mul[i] / 2^shift[i]], 0, bound_q).
+ * mul = 1, shift = 0 copies.  `in` is a host array of n_in device pointers; the
+ * other arrays are host arrays of n_in integers.  1 <= n_in <= 16.
+ */
+int iconcat(int32_t n_in, const void *const *in, const int32_t *c_in,
+            const int32_t *in_c_stride, const int32_t *mul, const int32_t *shift,
+            int32_t bound_q, int64_t count_pixels, void *out, int32_t out_c_stride,
+            void *stream);
+
+/* Max-pool on uint8 NHWC [n,h,w,c] (contiguous): the maximum over the window
+ * positions that fall inside the image (Section 4.1 mentions pooling layers in
+ * the integer ResNets; the maximum leaves the ratio unchanged). */
+int imaxpool2d_u8(int32_t n, int32_t h, int32_t w, int32_t c, int32_t k, int32_t stride,
+                  int32_t pad, const void *x, void *out, void *stream);
+
+/* Global average pool on uint8 NHWC [n,h,w,c] -> [n,c]:
+ *   out = clamp([sum_{h,w} x * mul / 2^shift], 0, bound_q),  mul / 2^shift ~ 1/(h*w). */
+int iavgpool_global_u8(int32_t n, int32_t h, int32_t w, int32_t c, int32_t mul,
+                       int32_t shift, int32_t bound_q, const void *x, void *out,
+                       void *stream);
+
+/* Re-normalisation of a raw uint8 picture as a stand-alone pass (Section 3.4.1):
+ * out[i] = x[i] - 128 stored as int8.  `count` elements; in place is allowed.
+ * (iconv2d_brelu can do the same on the fly with in_sub128 = 1.) */
+int irenormalize_u8(int64_t count, const void *x, void *out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ICNN_H */

@@ -1,0 +1,311 @@
+// C boundary: argument validation (host only, before any launch) and dispatch.
+#include "../../include/icnn.h"
+#include "icnn_device.h"
+
+#include <cstdarg>
+#include <cstdio>
+
+using namespace icnn;
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+struct ConvGeom {
+    int ho, wo, K, ksteps, chunks;
+    long long M;
+};
+
+int check_conv(const icnn_conv_desc *d, ConvGeom *g)
+{
+    if (!d) return fail(ICNN_E_NULL, "conv descriptor is NULL");
+    if (d->n < 1 || d->h < 1 || d->w < 1 || d->cin < 1 || d->cout < 1 || d->kh < 1 || d->kw < 1)
+        return fail(ICNN_E_SHAPE, "n, h, w, cin, cout, kh, kw must be >= 1");
+    if (d->stride_h < 1 || d->stride_w < 1 || d->pad_h < 0 || d->pad_w < 0)
+        return fail(ICNN_E_SHAPE, "stride must be >= 1 and pad >= 0");
+    if (d->h + 2LL * d->pad_h < d->kh || d->w + 2LL * d->pad_w < d->kw)
+        return fail(ICNN_E_SHAPE, "kernel larger than the padded image");
+    const int ho = (d->h + 2 * d->pad_h - d->kh) / d->stride_h + 1;
+    const int wo = (d->w + 2 * d->pad_w - d->kw) / d->stride_w + 1;
+    const long long K = (long long)d->kh * d->kw * d->cin;
+    if (K > 65535)
+        return fail(ICNN_E_SHAPE, "kh*kw*cin = %lld exceeds 65535: int32 accumulation not provably safe", K);
+    const long long M = (long long)d->n * ho * wo;
+    if (M > 0x7fffffffLL) return fail(ICNN_E_SHAPE, "n*ho*wo = %lld does not fit int32", M);
+    if (d->in_c_stride < d->cin) return fail(ICNN_E_SHAPE, "in_c_stride %d < cin %d", d->in_c_stride, d->cin);
+    if (d->out_c_offset < 0 || (long long)d->out_c_offset + d->cout > d->out_c_stride)
+        return fail(ICNN_E_SHAPE, "out_c_offset %d + cout %d exceeds out_c_stride %d", d->out_c_offset, d->cout,
+                    d->out_c_stride);
+    if ((d->in_signed != 0 && d->in_signed != 1) || (d->in_sub128 != 0 && d->in_sub128 != 1) ||
+        (d->in_signed && d->in_sub128))
+        return fail(ICNN_E_PARAM, "in_signed / in_sub128 must be 0 or 1 and not both 1");
+    if (d->out_mode < ICNN_OUT_BRELU_U8 || d->out_mode > ICNN_OUT_RAW_S32)
+        return fail(ICNN_E_PARAM, "unknown out_mode %d", d->out_mode);
+    if (d->res_mode < ICNN_RES_NONE || d->res_mode > ICNN_RES_POST)
+        return fail(ICNN_E_PARAM, "unknown res_mode %d", d->res_mode);
+    if (d->out_mode != ICNN_OUT_RAW_S32) {
+        if (d->mul < 1) return fail(ICNN_E_PARAM, "mul %d must be in [1, 2^31)", d->mul);
+        if (d->shift < 0 || d->shift > 62) return fail(ICNN_E_PARAM, "shift %d must be in [0, 62]", d->shift);
+    }
+    if (d->out_mode == ICNN_OUT_BRELU_U8 && (d->bound_q < 1 || d->bound_q > 255))
+        return fail(ICNN_E_PARAM, "bound_q %d must be in [1, 255]", d->bound_q);
+    if (d->out_mode == ICNN_OUT_CLAMP_U8 && (d->lo < 0 || d->hi > 255 || d->lo > d->hi))
+        return fail(ICNN_E_PARAM, "clamp range [%d, %d] must satisfy 0 <= lo <= hi <= 255", d->lo, d->hi);
+    if (d->res_mode != ICNN_RES_NONE) {
+        if (d->res_dtype < ICNN_U8 || d->res_dtype > ICNN_S32)
+            return fail(ICNN_E_PARAM, "unknown res_dtype %d", d->res_dtype);
+        if (d->res_c_stride < d->cout)
+            return fail(ICNN_E_SHAPE, "res_c_stride %d < cout %d", d->res_c_stride, d->cout);
+        if (d->res_mul < 1) return fail(ICNN_E_PARAM, "res_mul %d must be in [1, 2^31)", d->res_mul);
+        if (d->res_shift < 0 || d->res_shift > 62)
+            return fail(ICNN_E_PARAM, "res_shift %d must be in [0, 62]", d->res_shift);
+        if (d->res_mode == ICNN_RES_POST && d->out_mode == ICNN_OUT_RAW_S32)
+            return fail(ICNN_E_PARAM, "a skip operand after requantisation needs a requantised output");
+    }
+    if (g) {
+        g->ho = ho;
+        g->wo = wo;
+        g->K = (int)K;
+        g->M = M;
+        g->ksteps = (int)((K + kStepK - 1) / kStepK);
+        g->chunks = ((d->cout + kCoutPad - 1) / kCoutPad) * (kCoutPad / kChunkCout);
+    }
+    return ICNN_OK;
+}
+
+int check_requant(int mul, int shift, const char *what)
+{
+    if (mul < 1) return fail(ICNN_E_PARAM, "%s multiplier %d must be in [1, 2^31)", what, mul);
+    if (shift < 0 || shift > 62) return fail(ICNN_E_PARAM, "%s shift %d must be in [0, 62]", what, shift);
+    return ICNN_OK;
+}
+
+int launched(hipError_t e, const char *what)
+{
+    if (e == hipSuccess) return ICNN_OK;
+    return fail(ICNN_E_LAUNCH, "%s: %s", what, hipGetErrorString(e));
+}
+
+int dtype_bytes(int dt) { return dt == ICNN_S32 ? 4 : 1; }
+
+}  // namespace
+
+extern "C" {
+
+int icnn_version(void) { return 100; }
+
+const char *icnn_last_error(void) { return g_err; }
+
+int iconv2d_validate(const icnn_conv_desc *desc) { return check_conv(desc, nullptr); }
+
+int iconv2d_out_hw(const icnn_conv_desc *desc, int32_t *ho, int32_t *wo)
+{
+    ConvGeom g;
+    const int rc = check_conv(desc, &g);
+    if (rc) return rc;
+    if (!ho || !wo) return fail(ICNN_E_NULL, "ho / wo is NULL");
+    *ho = g.ho;
+    *wo = g.wo;
+    return ICNN_OK;
+}
+
+int iconv2d_workspace_bytes(const icnn_conv_desc *desc, size_t *bytes)
+{
+    const int rc = check_conv(desc, nullptr);
+    if (rc) return rc;
+    if (!bytes) return fail(ICNN_E_NULL, "bytes is NULL");
+    *bytes = 0;
+    return ICNN_OK;
+}
+
+int iconv2d_packed_weight_bytes(const icnn_conv_desc *desc, size_t *bytes)
+{
+    ConvGeom g;
+    const int rc = check_conv(desc, &g);
+    if (rc) return rc;
+    if (!bytes) return fail(ICNN_E_NULL, "bytes is NULL");
+    *bytes = (size_t)g.chunks * g.ksteps * kChunkBytes;
+    return ICNN_OK;
+}
+
+int iconv2d_prepack_weights(const icnn_conv_desc *desc, const int8_t *w_ohwi, void *w_packed, void *stream)
+{
+    ConvGeom g;
+    const int rc = check_conv(desc, &g);
+    if (rc) return rc;
+    if (!w_ohwi || !w_packed) return fail(ICNN_E_NULL, "weight pointer is NULL");
+    if (!aligned16(w_packed)) return fail(ICNN_E_ALIGN, "w_packed must be 16-byte aligned");
+    return launched(launch_prepack(w_ohwi, (uint8_t *)w_packed, desc->cout, g.K, g.chunks, g.ksteps,
+                                   (hipStream_t)stream),
+                    "prepack");
+}
+
+int iconv2d_brelu(const icnn_conv_desc *d, const void *x, const void *w_packed, const int32_t *bias,
+                  const void *res, void *y, void *workspace, void *stream)
+{
+    (void)workspace;
+    ConvGeom g;
+    const int rc = check_conv(d, &g);
+    if (rc) return rc;
+    if (!x || !w_packed || !bias || !y) return fail(ICNN_E_NULL, "x, w_packed, bias and y must not be NULL");
+    if (d->res_mode != ICNN_RES_NONE && !res) return fail(ICNN_E_NULL, "res is NULL but res_mode is set");
+    if (!aligned16(w_packed)) return fail(ICNN_E_ALIGN, "w_packed must be 16-byte aligned");
+    if ((uintptr_t)bias & 3) return fail(ICNN_E_ALIGN, "bias must be 4-byte aligned");
+    if (d->out_mode == ICNN_OUT_RAW_S32 && ((uintptr_t)y & 3)) return fail(ICNN_E_ALIGN, "int32 output must be 4-byte aligned");
+    if (d->res_mode != ICNN_RES_NONE && d->res_dtype == ICNN_S32 && ((uintptr_t)res & 3))
+        return fail(ICNN_E_ALIGN, "int32 skip operand must be 4-byte aligned");
+
+    ConvArgs a;
+    a.x = (const uint8_t *)x;
+    a.wp = (const uint8_t *)w_packed;
+    a.bias = bias;
+    a.res = d->res_mode != ICNN_RES_NONE ? res : nullptr;
+    a.out = y;
+    a.N = d->n; a.H = d->h; a.W = d->w; a.Cin = d->cin; a.in_cs = d->in_c_stride;
+    a.Cout = d->cout; a.KH = d->kh; a.KW = d->kw;
+    a.sh = d->stride_h; a.sw = d->stride_w; a.ph = d->pad_h; a.pw = d->pad_w;
+    a.Ho = g.ho; a.Wo = g.wo; a.M = (int)g.M; a.K = g.K; a.ksteps = g.ksteps; a.n_ct = 0;
+    a.out_cs = d->out_c_stride; a.out_co = d->out_c_offset;
+    a.mul = d->mul; a.shift = d->shift; a.out_mode = d->out_mode;
+    switch (d->out_mode) {
+    case ICNN_OUT_BRELU_U8: a.lo = 0; a.hi = d->bound_q; break;
+    case ICNN_OUT_CLAMP_U8: a.lo = d->lo; a.hi = d->hi; break;
+    default: a.lo = -128; a.hi = 127; break;
+    }
+    if (d->out_mode == ICNN_OUT_RAW_S32) { a.mul = 1; a.shift = 0; }
+    a.res_mode = d->res_mode; a.res_dtype = d->res_dtype; a.res_cs = d->res_c_stride;
+    a.res_mul = d->res_mode ? d->res_mul : 1; a.res_shift = d->res_mode ? d->res_shift : 0;
+    a.in_xor = d->in_sub128 ? 0x80808080u : 0u;
+    const int ob = d->out_mode == ICNN_OUT_RAW_S32 ? 4 : 1;
+    a.vec_out = aligned16(y) && ((long long)d->out_c_stride * ob) % 16 == 0 && ((long long)d->out_c_offset * ob) % 16 == 0;
+    a.vec_res = 0;
+    if (d->res_mode != ICNN_RES_NONE) {
+        const int rb = dtype_bytes(d->res_dtype);
+        a.vec_res = aligned16(res) && ((long long)d->res_c_stride * rb) % 16 == 0;
+    }
+    const bool vec_in = aligned16(x) && d->cin % 16 == 0 && d->in_c_stride % 16 == 0;
+    return launched(launch_conv(a, vec_in, (hipStream_t)stream), "iconv2d_brelu");
+}
+
+int iadd_rescale(const icnn_add_desc *d, const void *a, const void *b, void *out, void *stream)
+{
+    if (!d) return fail(ICNN_E_NULL, "add descriptor is NULL");
+    if (d->count_pixels < 0 || d->c < 0) return fail(ICNN_E_SHAPE, "count_pixels and c must be >= 0");
+    if (d->a_c_stride < d->c || d->b_c_stride < d->c || d->out_c_offset < 0 ||
+        (long long)d->out_c_offset + d->c > d->out_c_stride)
+        return fail(ICNN_E_SHAPE, "channel pitches must cover c (and out_c_offset + c)");
+    if (d->a_dtype < ICNN_U8 || d->a_dtype > ICNN_S32 || d->b_dtype < ICNN_U8 || d->b_dtype > ICNN_S32)
+        return fail(ICNN_E_PARAM, "unknown operand dtype");
+    if (d->out_mode != ICNN_OUT_CLAMP_U8 && d->out_mode != ICNN_OUT_LINEAR_S8 && d->out_mode != ICNN_OUT_RAW_S32)
+        return fail(ICNN_E_PARAM, "iadd_rescale out_mode must be CLAMP_U8, LINEAR_S8 or RAW_S32");
+    int rc = check_requant(d->b_mul, d->b_shift, "b");
+    if (rc) return rc;
+    if (d->out_mode != ICNN_OUT_RAW_S32 && (rc = check_requant(d->mul, d->shift, "output"))) return rc;
+    if (d->out_mode == ICNN_OUT_CLAMP_U8 && (d->lo < 0 || d->hi > 255 || d->lo > d->hi))
+        return fail(ICNN_E_PARAM, "clamp range [%d, %d] must satisfy 0 <= lo <= hi <= 255", d->lo, d->hi);
+    if (d->count_pixels == 0 || d->c == 0) return ICNN_OK;
+    if (!a || !b || !out) return fail(ICNN_E_NULL, "a, b and out must not be NULL");
+    if ((d->a_dtype == ICNN_S32 && ((uintptr_t)a & 3)) || (d->b_dtype == ICNN_S32 && ((uintptr_t)b & 3)) ||
+        (d->out_mode == ICNN_OUT_RAW_S32 && ((uintptr_t)out & 3)))
+        return fail(ICNN_E_ALIGN, "int32 tensors must be 4-byte aligned");
+    AddArgs k;
+    k.a = a; k.b = b; k.out = out; k.px = d->count_pixels; k.c = d->c;
+    k.a_cs = d->a_c_stride; k.b_cs = d->b_c_stride; k.out_cs = d->out_c_stride; k.out_co = d->out_c_offset;
+    k.a_dt = d->a_dtype; k.b_dt = d->b_dtype; k.out_mode = d->out_mode;
+    k.b_mul = d->b_mul; k.b_shift = d->b_shift;
+    k.mul = d->out_mode == ICNN_OUT_RAW_S32 ? 1 : d->mul;
+    k.shift = d->out_mode == ICNN_OUT_RAW_S32 ? 0 : d->shift;
+    k.lo = d->out_mode == ICNN_OUT_LINEAR_S8 ? -128 : d->lo;
+    k.hi = d->out_mode == ICNN_OUT_LINEAR_S8 ? 127 : d->hi;
+    const int ab = dtype_bytes(d->a_dtype), bb = dtype_bytes(d->b_dtype);
+    const int ob = d->out_mode == ICNN_OUT_RAW_S32 ? 4 : 1;
+    const bool vec = d->c % 16 == 0 && aligned16(a) && aligned16(b) && aligned16(out) &&
+                     ((long long)d->a_c_stride * ab) % 16 == 0 && ((long long)d->b_c_stride * bb) % 16 == 0 &&
+                     ((long long)d->out_c_stride * ob) % 16 == 0 && ((long long)d->out_c_offset * ob) % 16 == 0;
+    return launched(launch_add(k, vec, (hipStream_t)stream), "iadd_rescale");
+}
+
+int iconcat(int32_t n_in, const void *const *in, const int32_t *c_in, const int32_t *in_c_stride,
+            const int32_t *mul, const int32_t *shift, int32_t bound_q, int64_t count_pixels, void *out,
+            int32_t out_c_stride, void *stream)
+{
+    if (n_in < 1 || n_in > 16) return fail(ICNN_E_SHAPE, "n_in %d must be in [1, 16]", n_in);
+    if (!in || !c_in || !in_c_stride || !mul || !shift) return fail(ICNN_E_NULL, "an argument array is NULL");
+    if (count_pixels < 0) return fail(ICNN_E_SHAPE, "count_pixels must be >= 0");
+    if (bound_q < 1 || bound_q > 255) return fail(ICNN_E_PARAM, "bound_q %d must be in [1, 255]", bound_q);
+    long long total_c = 0;
+    for (int i = 0; i < n_in; ++i) {
+        if (c_in[i] < 0 || in_c_stride[i] < c_in[i]) return fail(ICNN_E_SHAPE, "input %d: bad channel count or pitch", i);
+        const int rc = check_requant(mul[i], shift[i], "concat input");
+        if (rc) return rc;
+        total_c += c_in[i];
+    }
+    if (total_c > out_c_stride) return fail(ICNN_E_SHAPE, "inputs have %lld channels, out_c_stride is %d", total_c, out_c_stride);
+    if (count_pixels == 0) return ICNN_OK;
+    if (!out) return fail(ICNN_E_NULL, "out is NULL");
+    for (int i = 0; i < n_in; ++i)
+        if (c_in[i] > 0 && !in[i]) return fail(ICNN_E_NULL, "input %d is NULL", i);
+    int off = 0;
+    for (int i = 0; i < n_in; ++i) {
+        const bool vec = c_in[i] % 16 == 0 && in_c_stride[i] % 16 == 0 && out_c_stride % 16 == 0 && off % 16 == 0 &&
+                         aligned16(in[i]) && aligned16(out);
+        const int rc = launched(launch_requant_copy((const uint8_t *)in[i], (uint8_t *)out, count_pixels, c_in[i],
+                                                    in_c_stride[i], out_c_stride, off, mul[i], shift[i], bound_q, vec,
+                                                    (hipStream_t)stream),
+                                "iconcat");
+        if (rc) return rc;
+        off += c_in[i];
+    }
+    return ICNN_OK;
+}
+
+int imaxpool2d_u8(int32_t n, int32_t h, int32_t w, int32_t c, int32_t k, int32_t stride, int32_t pad,
+                  const void *x, void *out, void *stream)
+{
+    if (n < 1 || h < 1 || w < 1 || c < 1 || k < 1 || stride < 1 || pad < 0 || h + 2 * pad < k || w + 2 * pad < k)
+        return fail(ICNN_E_SHAPE, "bad max-pool geometry");
+    if (pad >= k) return fail(ICNN_E_SHAPE, "pad must be smaller than the window");
+    if (!x || !out) return fail(ICNN_E_NULL, "x and out must not be NULL");
+    const int ho = (h + 2 * pad - k) / stride + 1, wo = (w + 2 * pad - k) / stride + 1;
+    const bool vec = c % 16 == 0 && aligned16(x) && aligned16(out);
+    return launched(launch_maxpool((const uint8_t *)x, (uint8_t *)out, n, h, w, c, k, stride, pad, ho, wo, vec,
+                                   (hipStream_t)stream),
+                    "imaxpool2d_u8");
+}
+
+int iavgpool_global_u8(int32_t n, int32_t h, int32_t w, int32_t c, int32_t mul, int32_t shift, int32_t bound_q,
+                       const void *x, void *out, void *stream)
+{
+    if (n < 1 || h < 1 || w < 1 || c < 1) return fail(ICNN_E_SHAPE, "n, h, w, c must be >= 1");
+    if ((long long)h * w > (1 << 23)) return fail(ICNN_E_SHAPE, "h*w too large for the pooled sum");
+    const int rc = check_requant(mul, shift, "average");
+    if (rc) return rc;
+    if (bound_q < 1 || bound_q > 255) return fail(ICNN_E_PARAM, "bound_q %d must be in [1, 255]", bound_q);
+    if (!x || !out) return fail(ICNN_E_NULL, "x and out must not be NULL");
+    return launched(launch_avgpool((const uint8_t *)x, (uint8_t *)out, n, h * w, c, mul, shift, bound_q,
+                                   (hipStream_t)stream),
+                    "iavgpool_global_u8");
+}
+
+int irenormalize_u8(int64_t count, const void *x, void *out, void *stream)
+{
+    if (count < 0) return fail(ICNN_E_SHAPE, "count must be >= 0");
+    if (count == 0) return ICNN_OK;
+    if (!x || !out) return fail(ICNN_E_NULL, "x and out must not be NULL");
+    const bool vec = count % 16 == 0 && aligned16(x) && aligned16(out);
+    return launched(launch_renorm((const uint8_t *)x, (uint8_t *)out, count, vec, (hipStream_t)stream),
+                    "irenormalize_u8");
+}
+
+}  // extern "C"

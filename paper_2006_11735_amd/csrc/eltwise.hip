@@ -1,0 +1,246 @@
+// Bandwidth-bound integer kernels: rescaled feature-map addition (Sections 3.4.2
+// and 4.1), explicit concatenation with per-branch requantisation (Algorithm 2,
+// online half), pooling, and the raw-picture re-normalisation (Section 3.4.1).
+// Vector paths move 16 elements per lane (one 128-bit access per 8-bit operand).
+#include "icnn_device.h"
+
+namespace icnn {
+
+__device__ __forceinline__ void unpack16(const void *p, size_t i, int dtype, int v[16])
+{
+    if (dtype == 2) {
+        const v4i *q = (const v4i *)((const int32_t *)p + i);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const v4i t = q[k];
+            v[4 * k] = t.x; v[4 * k + 1] = t.y; v[4 * k + 2] = t.z; v[4 * k + 3] = t.w;
+        }
+    } else {
+        const v4i t = *(const v4i *)((const uint8_t *)p + i);
+        const int wd[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int b8 = (wd[r >> 2] >> ((r & 3) * 8)) & 0xff;
+            v[r] = dtype == 1 ? (int)(int8_t)b8 : b8;
+        }
+    }
+}
+
+__device__ __forceinline__ v4i pack16(const int v[16])
+{
+    uint32_t wd[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int r = 0; r < 16; ++r) wd[r >> 2] |= (uint32_t)(v[r] & 0xff) << ((r & 3) * 8);
+    return v4i{(int)wd[0], (int)wd[1], (int)wd[2], (int)wd[3]};
+}
+
+__device__ __forceinline__ int add_one(int av, int bv, const AddArgs &a, bool raw)
+{
+    const int t = sat32((int64_t)av + rsr64((int64_t)bv * a.b_mul, a.b_shift));
+    if (raw) return t;
+    return clampi64(rsr64((int64_t)t * a.mul, a.shift), a.lo, a.hi);
+}
+
+// vector path: one lane = 16 consecutive channels of one pixel
+__global__ __launch_bounds__(256) void add_rescale_vec_kernel(const AddArgs a, int groups_per_px,
+                                                              long long total)
+{
+    const long long g = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (g >= total) return;
+    const long long px = g / groups_per_px;
+    const int c0 = (int)(g - px * groups_per_px) * 16;
+    int av[16], bv[16], ov[16];
+    unpack16(a.a, (size_t)px * a.a_cs + c0, a.a_dt, av);
+    unpack16(a.b, (size_t)px * a.b_cs + c0, a.b_dt, bv);
+    const bool raw = a.out_mode == 3;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) ov[r] = add_one(av[r], bv[r], a, raw);
+    const size_t oo = (size_t)px * a.out_cs + a.out_co + c0;
+    if (raw) {
+        v4i *op = (v4i *)((int32_t *)a.out + oo);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) op[k] = v4i{ov[4 * k], ov[4 * k + 1], ov[4 * k + 2], ov[4 * k + 3]};
+    } else {
+        *(v4i *)((uint8_t *)a.out + oo) = pack16(ov);
+    }
+}
+
+__global__ __launch_bounds__(256) void add_rescale_scalar_kernel(const AddArgs a, long long total)
+{
+    const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const long long px = e / a.c;
+    const int ch = (int)(e - px * a.c);
+    const int av = load_elem(a.a, (size_t)px * a.a_cs + ch, a.a_dt);
+    const int bv = load_elem(a.b, (size_t)px * a.b_cs + ch, a.b_dt);
+    const bool raw = a.out_mode == 3;
+    const int v = add_one(av, bv, a, raw);
+    const size_t oo = (size_t)px * a.out_cs + a.out_co + ch;
+    if (raw) ((int32_t *)a.out)[oo] = v;
+    else ((uint8_t *)a.out)[oo] = (uint8_t)v;
+}
+
+hipError_t launch_add(const AddArgs &a, bool vec, hipStream_t st)
+{
+    if (a.px == 0 || a.c == 0) return hipSuccess;
+    if (vec) {
+        const int gpp = a.c / 16;
+        const long long total = a.px * gpp;
+        hipLaunchKernelGGL(add_rescale_vec_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                           a, gpp, total);
+    } else {
+        const long long total = a.px * a.c;
+        hipLaunchKernelGGL(add_rescale_scalar_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                           st, a, total);
+    }
+    return hipGetLastError();
+}
+
+// out[px, out_co + ch] = clamp([in[px, ch] * mul / 2^shift], 0, bound)
+__global__ __launch_bounds__(256) void requant_copy_kernel(const uint8_t *__restrict__ in,
+                                                           uint8_t *__restrict__ out, long long total,
+                                                           int per_px, int in_cs, int out_cs, int out_co,
+                                                           int mul, int shift, int bound, int vec)
+{
+    const long long g = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (g >= total) return;
+    const long long px = g / per_px;
+    const int k = (int)(g - px * per_px);
+    if (vec) {
+        int v[16];
+        unpack16(in, (size_t)px * in_cs + k * 16, 0, v);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) v[r] = clampi64(rsr64((int64_t)v[r] * mul, shift), 0, bound);
+        *(v4i *)(out + (size_t)px * out_cs + out_co + k * 16) = pack16(v);
+    } else {
+        const int v = in[(size_t)px * in_cs + k];
+        out[(size_t)px * out_cs + out_co + k] = (uint8_t)clampi64(rsr64((int64_t)v * mul, shift), 0, bound);
+    }
+}
+
+hipError_t launch_requant_copy(const uint8_t *in, uint8_t *out, int64_t px, int c, int in_cs, int out_cs,
+                               int out_co, int mul, int shift, int bound, bool vec, hipStream_t st)
+{
+    if (px == 0 || c == 0) return hipSuccess;
+    const int per_px = vec ? c / 16 : c;
+    const long long total = (long long)px * per_px;
+    hipLaunchKernelGGL(requant_copy_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, in, out,
+                       total, per_px, in_cs, out_cs, out_co, mul, shift, bound, vec ? 1 : 0);
+    return hipGetLastError();
+}
+
+// max over the window positions inside the image; bytewise max of packed words
+__device__ __forceinline__ uint32_t max_u8x4(uint32_t x, uint32_t y)
+{
+    uint32_t r = 0;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const uint32_t xb = (x >> (8 * b)) & 0xff, yb = (y >> (8 * b)) & 0xff;
+        r |= (xb > yb ? xb : yb) << (8 * b);
+    }
+    return r;
+}
+
+__global__ __launch_bounds__(256) void maxpool_kernel(const uint8_t *__restrict__ x, uint8_t *__restrict__ out,
+                                                      long long total, int per_px, int h, int w, int c, int k,
+                                                      int stride, int pad, int ho_n, int wo_n, int vec)
+{
+    const long long g = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (g >= total) return;
+    long long px = g / per_px;
+    const int q = (int)(g - px * per_px);
+    const int wo = (int)(px % wo_n);
+    const long long t = px / wo_n;
+    const int ho = (int)(t % ho_n);
+    const long long n = t / ho_n;
+    if (vec) {
+        uint32_t m[4] = {0, 0, 0, 0};
+        for (int i = 0; i < k; ++i) {
+            const int hi = ho * stride - pad + i;
+            if ((unsigned)hi >= (unsigned)h) continue;
+            for (int j = 0; j < k; ++j) {
+                const int wi = wo * stride - pad + j;
+                if ((unsigned)wi >= (unsigned)w) continue;
+                const v4i v = *(const v4i *)(x + (((size_t)n * h + hi) * w + wi) * c + q * 16);
+                m[0] = max_u8x4(m[0], (uint32_t)v.x); m[1] = max_u8x4(m[1], (uint32_t)v.y);
+                m[2] = max_u8x4(m[2], (uint32_t)v.z); m[3] = max_u8x4(m[3], (uint32_t)v.w);
+            }
+        }
+        *(v4i *)(out + (size_t)px * c + q * 16) = v4i{(int)m[0], (int)m[1], (int)m[2], (int)m[3]};
+    } else {
+        int best = 0;
+        for (int i = 0; i < k; ++i) {
+            const int hi = ho * stride - pad + i;
+            if ((unsigned)hi >= (unsigned)h) continue;
+            for (int j = 0; j < k; ++j) {
+                const int wi = wo * stride - pad + j;
+                if ((unsigned)wi >= (unsigned)w) continue;
+                const int v = x[(((size_t)n * h + hi) * w + wi) * c + q];
+                best = v > best ? v : best;
+            }
+        }
+        out[(size_t)px * c + q] = (uint8_t)best;
+    }
+}
+
+hipError_t launch_maxpool(const uint8_t *x, uint8_t *out, int n, int h, int w, int c, int k, int stride,
+                          int pad, int ho, int wo, bool vec, hipStream_t st)
+{
+    const int per_px = vec ? c / 16 : c;
+    const long long total = (long long)n * ho * wo * per_px;
+    if (total == 0) return hipSuccess;
+    hipLaunchKernelGGL(maxpool_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, x, out, total,
+                       per_px, h, w, c, k, stride, pad, ho, wo, vec ? 1 : 0);
+    return hipGetLastError();
+}
+
+// one thread per (image, channel): consecutive lanes read consecutive channels
+__global__ __launch_bounds__(256) void avgpool_kernel(const uint8_t *__restrict__ x, uint8_t *__restrict__ out,
+                                                      long long total, int hw, int c, int mul, int shift,
+                                                      int bound)
+{
+    const long long g = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (g >= total) return;
+    const long long n = g / c;
+    const int ch = (int)(g - n * c);
+    const uint8_t *p = x + (size_t)n * hw * c + ch;
+    int64_t s = 0;
+    for (int i = 0; i < hw; ++i) s += p[(size_t)i * c];
+    out[g] = (uint8_t)clampi64(rsr64(s * mul, shift), 0, bound);
+}
+
+hipError_t launch_avgpool(const uint8_t *x, uint8_t *out, int n, int hw, int c, int mul, int shift, int bound,
+                          hipStream_t st)
+{
+    const long long total = (long long)n * c;
+    if (total == 0) return hipSuccess;
+    hipLaunchKernelGGL(avgpool_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, x, out, total,
+                       hw, c, mul, shift, bound);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void renorm_kernel(const uint8_t *__restrict__ x, uint8_t *__restrict__ out,
+                                                     long long count, int vec)
+{
+    const long long g = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (vec) {
+        if (g * 16 >= count) return;
+        v4i v = *(const v4i *)(x + g * 16);
+        v.x ^= 0x80808080; v.y ^= 0x80808080; v.z ^= 0x80808080; v.w ^= 0x80808080;
+        *(v4i *)(out + g * 16) = v;
+    } else {
+        if (g >= count) return;
+        out[g] = x[g] ^ 0x80;
+    }
+}
+
+hipError_t launch_renorm(const uint8_t *x, uint8_t *out, int64_t count, bool vec, hipStream_t st)
+{
+    if (count == 0) return hipSuccess;
+    const long long threads = vec ? count / 16 : count;
+    hipLaunchKernelGGL(renorm_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, x, out,
+                       (long long)count, vec ? 1 : 0);
+    return hipGetLastError();
+}
+
+}  // namespace icnn

@@ -1,0 +1,88 @@
+// Internal declarations shared by the library's translation units (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace icnn {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+// Packed weight format: the cout axis is cut into chunks of 32 output channels and
+// the K = kh*kw*cin axis (order kh, kw, ci) into steps of 64.  One (chunk, step) pair
+// is 2048 bytes: [k32 half][lane 0..63][16 bytes], exactly the A-operand fragments
+// of two v_mfma_i32_32x32x32_i8 issues.  Lane l carries matrix row l%32 and the 16
+// k-values (l/32)*16.. of its half.  Matrix row r of a chunk is output channel
+// 16*((r>>2)&1) + 4*(r>>3) + (r&3), which makes accumulator register i of a lane
+// in half h = l/32 hold channel 16*h + i: sixteen consecutive channels per lane.
+constexpr int kChunkCout = 32;
+constexpr int kStepK = 64;
+constexpr int kChunkBytes = 2048;
+constexpr int kCoutPad = 128;   // chunk count is padded so any cout tile can over-read
+
+struct ConvArgs {
+    const uint8_t *x;
+    const uint8_t *wp;
+    const int32_t *bias;
+    const void *res;
+    void *out;
+    int N, H, W, Cin, in_cs, Cout, KH, KW, sh, sw, ph, pw, Ho, Wo;
+    int M;        // output pixels N*Ho*Wo
+    int K;        // kh*kw*cin
+    int ksteps;   // ceil(K / 64)
+    int n_ct;     // cout tiles
+    int out_cs, out_co;
+    int mul, shift, lo, hi, out_mode;
+    int res_mode, res_dtype, res_cs, res_mul, res_shift;
+    uint32_t in_xor;   // 0x80808080 when the input is a raw picture (x - 128), else 0
+    int vec_out, vec_res;
+};
+
+// [v / 2^s], round half up; arithmetic shift floors for negative values.
+__device__ __forceinline__ int64_t rsr64(int64_t v, int s)
+{
+    return (v + ((int64_t(1) << s) >> 1)) >> s;
+}
+
+__device__ __forceinline__ int sat32(int64_t v)
+{
+    return v > INT32_MAX ? INT32_MAX : (v < INT32_MIN ? INT32_MIN : (int)v);
+}
+
+__device__ __forceinline__ int clampi64(int64_t v, int lo, int hi)
+{
+    return v < lo ? lo : (v > hi ? hi : (int)v);
+}
+
+__device__ __forceinline__ int load_elem(const void *p, size_t i, int dtype)
+{
+    if (dtype == 0) return ((const uint8_t *)p)[i];
+    if (dtype == 1) return ((const int8_t *)p)[i];
+    return ((const int32_t *)p)[i];
+}
+
+// launchers (host)
+hipError_t launch_conv(const ConvArgs &a, bool vec_in, hipStream_t st);
+hipError_t launch_prepack(const int8_t *w, uint8_t *wp, int Cout, int K, int chunks, int ksteps,
+                          hipStream_t st);
+
+struct AddArgs {
+    const void *a;
+    const void *b;
+    void *out;
+    int64_t px;
+    int c, a_cs, b_cs, out_cs, out_co, a_dt, b_dt, out_mode;
+    int b_mul, b_shift, mul, shift, lo, hi;
+};
+hipError_t launch_add(const AddArgs &a, bool vec, hipStream_t st);
+hipError_t launch_requant_copy(const uint8_t *in, uint8_t *out, int64_t px, int c, int in_cs,
+                               int out_cs, int out_co, int mul, int shift, int bound, bool vec,
+                               hipStream_t st);
+hipError_t launch_maxpool(const uint8_t *x, uint8_t *out, int n, int h, int w, int c, int k,
+                          int stride, int pad, int ho, int wo, bool vec, hipStream_t st);
+hipError_t launch_avgpool(const uint8_t *x, uint8_t *out, int n, int hw, int c, int mul, int shift,
+                          int bound, hipStream_t st);
+hipError_t launch_renorm(const uint8_t *x, uint8_t *out, int64_t count, bool vec, hipStream_t st);
+
+}  // namespace icnn

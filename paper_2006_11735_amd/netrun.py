@@ -1,0 +1,100 @@
+"""Runs a synthetic integer network (workloads.nets) on the GPU through the C
+boundary.  This is harness code: it owns the device buffers (torch tensors),
+prepacks the weights once, and then issues one library call per layer.  All
+arithmetic happens inside the library.
+"""
+import numpy as np
+import torch
+
+from workloads import nets as W
+from . import binding as B
+
+_OUT = {"brelu": B.ICNN_OUT_BRELU_U8, "clamp_u8": B.ICNN_OUT_CLAMP_U8,
+        "linear_s8": B.ICNN_OUT_LINEAR_S8, "raw_s32": B.ICNN_OUT_RAW_S32}
+_RES = {"none": B.ICNN_RES_NONE, "pre": B.ICNN_RES_PRE, "post": B.ICNN_RES_POST}
+_DT = {"u8": B.ICNN_U8, "s8": B.ICNN_S8, "s32": B.ICNN_S32}
+
+
+class GpuNet:
+    def __init__(self, net, seed, calib, images=None, device="cuda:0"):
+        if not torch.cuda.is_available():
+            raise RuntimeError("GpuNet needs a GPU: there is no CPU fallback")
+        self.net, self.seed, self.calib = net, seed, calib
+        self.device = torch.device(device)
+        n_full = net["buffers"]["raw"]["shape"][0]
+        self.images = n_full if images is None else min(images, n_full)
+        self.buf = {}
+        for name, b in net["buffers"].items():
+            shape = [self.images] + b["shape"][1:]
+            dt = torch.int32 if b["dtype"] == "s32" else torch.uint8
+            self.buf[name] = torch.zeros(shape, dtype=dt, device=self.device)
+        self.steps = []
+        for op in net["ops"]:
+            if op["op"] == "conv":
+                self.steps.append(self._prep_conv(op))
+            elif op["op"] == "maxpool":
+                n, h, w, c = self.buf[op["src"]].shape
+                args = (n, h, w, c, op["k"], op["stride"], op["pad"], self.buf[op["src"]], self.buf[op["dst"]])
+                self.steps.append(("maxpool", op, args))
+            elif op["op"] == "avgpool":
+                n, h, w, c = self.buf[op["src"]].shape
+                cal = calib["avgpool"][op["dst"]]
+                args = (n, h, w, c, cal["mul"], cal["shift"], cal["bound_q"], self.buf[op["src"]],
+                        self.buf[op["dst"]])
+                self.steps.append(("avgpool", op, args))
+            else:
+                raise ValueError(op["op"])
+        torch.cuda.synchronize(self.device)
+
+    def _prep_conv(self, op):
+        cal = self.calib["conv"][op["name"]]
+        src, dst = self.buf[op["src"]], self.buf[op["dst"]]
+        n, h, w, cbuf = src.shape
+        d = B.conv_desc(
+            n=n, h=h, w=w, cin=op["cin"], in_c_stride=cbuf, in_signed=0, in_sub128=int(op["in_sub128"]),
+            cout=op["cout"], kh=op["kh"], kw=op["kw"], stride_h=op["stride"], stride_w=op["stride"],
+            pad_h=op["pad"], pad_w=op["pad"], out_c_stride=dst.shape[3], out_c_offset=op["dst_c_offset"],
+            mul=cal.get("mul", 1), shift=cal.get("shift", 0), bound_q=cal.get("bound_q", 127),
+            lo=cal.get("lo", 0), hi=cal.get("hi", 255), out_mode=_OUT[op["out_mode"]],
+            res_mode=_RES[op["res_mode"]])
+        res = None
+        if op["res"] is not None:
+            res = self.buf[op["res"]]
+            d.res_dtype = _DT[op["res_dtype"]]
+            d.res_c_stride = res.shape[3]
+            d.res_mul, d.res_shift = cal.get("res_mul", 1), cal.get("res_shift", 0)
+        w_np = W.weight_tensor(op, self.seed)
+        w_dev = torch.from_numpy(w_np).to(self.device)
+        wp = torch.empty(B.iconv2d_packed_weight_bytes(d), dtype=torch.uint8, device=self.device)
+        B.iconv2d_prepack_weights(d, w_dev, wp)
+        bias = torch.from_numpy(W.bias_tensor(op, self.seed)).to(self.device)
+        ws_bytes = B.iconv2d_workspace_bytes(d)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device=self.device) if ws_bytes else None
+        torch.cuda.synchronize(self.device)       # w_dev may be released after the prepack ran
+        return ("conv", op, (d, src, wp, bias, res, dst, ws))
+
+    def set_input(self, x_raw=None):
+        if x_raw is None:
+            x_raw = W.input_tensor(self.net, self.seed, self.images)
+        self.buf["raw"].copy_(torch.from_numpy(np.ascontiguousarray(x_raw)).to(self.device))
+
+    def run(self, stream=None):
+        for kind, _, args in self.steps:
+            if kind == "conv":
+                B.iconv2d_brelu(*args, stream=stream)
+            elif kind == "maxpool":
+                B.imaxpool2d_u8(*args, stream=stream)
+            else:
+                B.iavgpool_global_u8(*args, stream=stream)
+
+    def run_step(self, i, stream=None):
+        kind, _, args = self.steps[i]
+        if kind == "conv":
+            B.iconv2d_brelu(*args, stream=stream)
+        elif kind == "maxpool":
+            B.imaxpool2d_u8(*args, stream=stream)
+        else:
+            B.iavgpool_global_u8(*args, stream=stream)
+
+    def result(self, name):
+        return self.buf[name].cpu().numpy()

@@ -1,0 +1,61 @@
+"""Helpers for the GPU parity tests: run one library call on numpy inputs."""
+import numpy as np
+import torch
+
+from paper_2006_11735_amd import binding as B
+
+DEV = "cuda:0"
+_OUT = {"brelu": B.ICNN_OUT_BRELU_U8, "clamp_u8": B.ICNN_OUT_CLAMP_U8,
+        "linear_s8": B.ICNN_OUT_LINEAR_S8, "raw_s32": B.ICNN_OUT_RAW_S32}
+_RES = {"none": B.ICNN_RES_NONE, "pre": B.ICNN_RES_PRE, "post": B.ICNN_RES_POST}
+_NPDT = {np.dtype(np.uint8): B.ICNN_U8, np.dtype(np.int8): B.ICNN_S8, np.dtype(np.int32): B.ICNN_S32}
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def gpu_conv2d(x, w, bias, *, stride=1, pad=0, mul=1, shift=0, bound_q=127, lo=0, hi=255,
+               out_mode="brelu", res=None, res_mode="none", res_mul=1, res_shift=0,
+               in_sub128=False, cin=None, out=None, out_c_offset=0, misalign=0):
+    """Same signature and result layout as oracle.conv2d, computed by the library.
+    `misalign` shifts x / out / res device addresses by that many bytes (scalar paths)."""
+    n, h, ww, cbuf = x.shape
+    cout, kh, kw, wc = w.shape
+    cin = wc if cin is None else cin
+    om = _OUT[out_mode]
+    odt = {B.ICNN_OUT_RAW_S32: np.int32, B.ICNN_OUT_LINEAR_S8: np.int8}.get(om, np.uint8)
+    d = B.conv_desc(n=n, h=h, w=ww, cin=cin, in_c_stride=cbuf, in_signed=int(x.dtype == np.int8),
+                    in_sub128=int(in_sub128), cout=cout, kh=kh, kw=kw, stride_h=stride, stride_w=stride,
+                    pad_h=pad, pad_w=pad, mul=mul, shift=shift, bound_q=bound_q, lo=lo, hi=hi,
+                    out_mode=om, res_mode=_RES[res_mode])
+    ho, wo = (h + 2 * pad - kh) // stride + 1, (ww + 2 * pad - kw) // stride + 1
+    if out is None:
+        out = np.zeros((n, ho, wo, out_c_offset + cout), dtype=odt)
+    d.out_c_stride, d.out_c_offset = out.shape[3], out_c_offset
+
+    def place(a):
+        """device copy of `a` whose first byte sits `misalign` bytes into an allocation"""
+        raw = np.ascontiguousarray(a).view(np.uint8).reshape(-1)
+        t = torch.zeros(raw.size + 64, dtype=torch.uint8, device=DEV)
+        t[misalign:misalign + raw.size] = torch.from_numpy(raw).to(DEV)
+        return t
+
+    xd = place(x)
+    od = place(out)
+    rd = None
+    if res is not None:
+        d.res_dtype, d.res_c_stride = _NPDT[res.dtype], res.shape[3]
+        d.res_mul, d.res_shift = res_mul, res_shift
+        rd = place(res)
+    wd = dev(w)
+    wp = torch.zeros(B.iconv2d_packed_weight_bytes(d), dtype=torch.uint8, device=DEV)
+    B.iconv2d_prepack_weights(d, wd, wp)
+    bd = dev(bias.astype(np.int32))
+    B.iconv2d_brelu(d, xd.data_ptr() + misalign, wp, bd, None if rd is None else rd.data_ptr() + misalign,
+                    od.data_ptr() + misalign, None)
+    torch.cuda.synchronize()
+    raw = od.cpu().numpy()
+    # guard bytes before and after the output must be untouched
+    assert (raw[:misalign] == 0).all() and (raw[misalign + out.nbytes:] == 0).all()
+    return raw[misalign:misalign + out.nbytes].view(odt).reshape(out.shape)

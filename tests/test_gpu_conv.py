@@ -1,0 +1,164 @@
+"""GPU parity: iconv2d_brelu against the CPU oracle, bit for bit, on seeded inputs.
+Shapes span several tiles, ragged pixel and channel tails, every kernel geometry of
+the five workloads, every input path (vector / element-wise) and every epilogue mode."""
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+def rnd(seed):
+    return np.random.default_rng(seed)
+
+
+def make(seed, n, h, w, cin, cout, k, raw=False, signed=False, cbuf=None):
+    g = rnd(seed)
+    cbuf = cin if cbuf is None else cbuf
+    if raw:
+        x = g.integers(0, 256, size=(n, h, w, cbuf), dtype=np.uint8)
+    elif signed:
+        x = g.integers(-128, 128, size=(n, h, w, cbuf), dtype=np.int8)
+    else:
+        x = g.integers(0, 128, size=(n, h, w, cbuf), dtype=np.uint8)
+    wt = g.integers(-127, 128, size=(cout, k, k, cin), dtype=np.int8)
+    b = g.integers(-4096, 4097, size=cout).astype(np.int32)
+    return x, wt, b
+
+
+def both(x, w, b, **kw):
+    from gpu_util import gpu_conv2d
+    mis = kw.pop("misalign", 0)
+    want = O.conv2d(x, w, b, **{k: (v.copy() if k == "out" else v) for k, v in kw.items()})
+    got = gpu_conv2d(x, w, b, misalign=mis, **kw)
+    return got, want
+
+
+SHAPES = [
+    # n, h, w, cin, cout, k, stride, pad
+    (1, 56, 56, 64, 64, 3, 1, 1),      # config 0
+    (2, 17, 23, 64, 64, 3, 1, 1),      # ragged pixel tail
+    (1, 20, 20, 128, 128, 3, 1, 1),    # 128-channel tile
+    (2, 14, 14, 256, 256, 3, 2, 1),    # stride 2
+    (1, 14, 14, 512, 128, 1, 1, 0),    # pointwise, deep K
+    (1, 15, 15, 64, 256, 1, 2, 0),     # strided projection
+    (1, 30, 34, 64, 32, 5, 1, 2),      # VRCNN 5x5 branch
+    (1, 30, 34, 64, 16, 3, 1, 1),      # narrow output
+    (1, 30, 34, 48, 16, 3, 1, 1),      # cin 48: K not a multiple of 64
+    (1, 30, 34, 48, 32, 1, 1, 0),
+    (1, 30, 34, 48, 1, 3, 1, 1),       # single output channel
+    (1, 33, 31, 1, 64, 3, 1, 1),       # single input channel (element-wise gather)
+    (1, 33, 31, 1, 64, 5, 1, 2),
+    (2, 37, 41, 3, 64, 7, 2, 3),       # stem
+    (3, 1, 1, 2048, 1000, 1, 1, 0),    # fully connected
+    (1, 9, 9, 16, 100, 3, 1, 1),       # cout not a multiple of 16
+    (1, 7, 7, 24, 40, 3, 1, 1),        # cin not a multiple of 16
+    (1, 5, 300, 32, 200, 1, 1, 0),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_raw_accumulator_and_requantised_output(shape):
+    n, h, w, cin, cout, k, stride, pad = shape
+    x, wt, b = make(hash(shape) % 1000, n, h, w, cin, cout, k, raw=(cin <= 3))
+    sub = cin <= 3
+    got, want = both(x, wt, b, stride=stride, pad=pad, in_sub128=sub, out_mode="raw_s32")
+    assert got.dtype == np.int32 and (got == want).all()
+    from oracle import calibrate as K
+    mul, shift = K.bound_params(K.percentile_999(want))
+    got, want = both(x, wt, b, stride=stride, pad=pad, in_sub128=sub, mul=mul, shift=shift, bound_q=127)
+    assert (got == want).all() and want.max() == 127 and want.min() == 0
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_config0_seeds(seed):
+    from workloads import nets as W
+    from oracle import net as ONet
+    net = W.CONFIGS["cfg0"]()
+    calib, bufs = ONet.calibrate(net, seed)
+    op = W.conv_ops(net)[0]
+    c = calib["conv"]["conv"]
+    from gpu_util import gpu_conv2d
+    got = gpu_conv2d(bufs["raw"], W.weight_tensor(op, seed), W.bias_tensor(op, seed), stride=1, pad=1,
+                     mul=c["mul"], shift=c["shift"], bound_q=c["bound_q"])
+    assert (got == bufs["out"]).all()
+
+
+def test_signed_input_and_int8_output():
+    x, wt, b = make(5, 1, 12, 12, 32, 48, 3, signed=True)
+    got, want = both(x, wt, b, stride=1, pad=1, mul=20000, shift=25, out_mode="linear_s8")
+    assert got.dtype == np.int8 and (got == want).all() and want.min() == -128 and want.max() == 127
+
+
+@pytest.mark.parametrize("res_kind", ["u8", "s8", "s32"])
+@pytest.mark.parametrize("cout", [64, 40])
+def test_skip_merge_before_requantisation(res_kind, cout):
+    x, wt, b = make(6, 2, 9, 11, 64, cout, 1)
+    g = rnd(60)
+    shape = (2, 9, 11, cout)
+    if res_kind == "u8":
+        r, rm, rs = g.integers(0, 128, size=shape, dtype=np.uint8), 18415, 5
+    elif res_kind == "s8":
+        r, rm, rs = g.integers(-128, 128, size=shape, dtype=np.int8), 18415, 5
+    else:
+        r, rm, rs = g.integers(-300000, 300000, size=shape).astype(np.int32), 20011, 15
+    kw = dict(res=r, res_mode="pre", res_mul=rm, res_shift=rs)
+    got, want = both(x, wt, b, out_mode="raw_s32", **kw)
+    assert (got == want).all()
+    got, want = both(x, wt, b, mul=23187, shift=25, bound_q=127, **kw)
+    assert (got == want).all() and want.max() == 127
+
+
+def test_skip_merge_saturates_to_int32():
+    x, wt, b = make(7, 1, 4, 4, 16, 16, 1)
+    r = np.full((1, 4, 4, 16), 2**31 - 1, np.int32)
+    r[0, 1] = -2**31
+    got, want = both(x, wt, b, out_mode="raw_s32", res=r, res_mode="pre", res_mul=3, res_shift=0)
+    assert (got == want).all() and want.max() == 2**31 - 1 and want.min() == -2**31
+
+
+def test_regression_output_adds_raw_picture_after_requantisation():
+    x, wt, b = make(8, 1, 21, 19, 64, 1, 3)
+    raw = rnd(80).integers(0, 256, size=(1, 21, 19, 1), dtype=np.uint8)
+    kw = dict(stride=1, pad=1, mul=20050, shift=20, out_mode="clamp_u8", lo=0, hi=255,
+              res=raw, res_mode="post", res_mul=1, res_shift=0)
+    got, want = both(x, wt, b, **kw)
+    assert (got == want).all() and want.min() == 0 and want.max() == 255
+
+
+def test_concat_by_channel_offset_touches_only_its_slice():
+    x, wt, b = make(9, 1, 10, 12, 64, 32, 5)
+    out = np.full((1, 10, 12, 48), 201, np.uint8)
+    got, want = both(x, wt, b, stride=1, pad=2, mul=30000, shift=28, bound_q=127, out=out, out_c_offset=0)
+    assert (got == want).all() and (got[..., 32:] == 201).all()
+    x2, wt2, b2 = make(10, 1, 10, 12, 64, 16, 3)
+    got, want = both(x2, wt2, b2, stride=1, pad=1, mul=18470, shift=27, bound_q=24, out=out, out_c_offset=32)
+    assert (got == want).all() and (got[..., :32] == 201).all() and got[..., 32:].max() == 24
+
+
+def test_channel_slice_of_a_wider_input_buffer():
+    x, wt, b = make(11, 1, 8, 8, 32, 16, 3, cbuf=48)
+    got, want = both(x, wt, b, stride=1, pad=1, cin=32, out_mode="raw_s32")
+    assert (got == want).all()
+    x, wt, b = make(12, 1, 8, 8, 20, 16, 3, cbuf=23)
+    got, want = both(x, wt, b, stride=1, pad=1, cin=20, out_mode="raw_s32")
+    assert (got == want).all()
+
+
+@pytest.mark.parametrize("mis", [1, 4])
+def test_unaligned_pointers_take_elementwise_paths_with_identical_results(mis):
+    x, wt, b = make(13, 1, 9, 9, 64, 64, 3)
+    r = rnd(130).integers(0, 128, size=(1, 9, 9, 64), dtype=np.uint8)
+    got, want = both(x, wt, b, stride=1, pad=1, mul=21000, shift=25, res=r, res_mode="pre",
+                     res_mul=9000, res_shift=3, misalign=mis)
+    assert (got == want).all()
+
+
+def test_extreme_requant_parameters():
+    x, wt, b = make(14, 1, 6, 6, 16, 16, 1)
+    for mul, shift in ((2**31 - 1, 62), (2**31 - 1, 40), (1, 0), (1, 1), (3, 62)):
+        got, want = both(x, wt, b, mul=mul, shift=shift, bound_q=255)
+        assert (got == want).all(), (mul, shift)
+        got, want = both(x, wt, b, mul=mul, shift=shift, out_mode="linear_s8")
+        assert (got == want).all(), (mul, shift)

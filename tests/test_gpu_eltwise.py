@@ -1,0 +1,112 @@
+"""GPU parity of the bandwidth-bound entry points against the CPU oracle (bit-exact)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+def rnd(seed):
+    return np.random.default_rng(seed)
+
+
+def tensor(g, shape, kind):
+    if kind == "u8":
+        return g.integers(0, 128, size=shape, dtype=np.uint8)
+    if kind == "s8":
+        return g.integers(-128, 128, size=shape, dtype=np.int8)
+    return g.integers(-400000, 400000, size=shape).astype(np.int32)
+
+
+@pytest.mark.parametrize("a_kind", ["u8", "s8", "s32"])
+@pytest.mark.parametrize("b_kind", ["u8", "s8", "s32"])
+@pytest.mark.parametrize("c", [64, 23])
+def test_add_rescale_all_operand_types(a_kind, b_kind, c):
+    from gpu_util import dev
+    from paper_2006_11735_amd import binding as B
+    g = rnd(len(a_kind) * 7 + len(b_kind) + c)
+    shape = (3, 11, 13, c)
+    a, b = tensor(g, shape, a_kind), tensor(g, shape, b_kind)
+    dt = {"u8": B.ICNN_U8, "s8": B.ICNN_S8, "s32": B.ICNN_S32}
+    px = 3 * 11 * 13
+    for out_mode, odt, kw in (("clamp_u8", np.uint8, dict(mul=23187, shift=24 if a_kind == "s32" else 9, lo=0, hi=127)),
+                              ("linear_s8", np.int8, dict(mul=3, shift=4)),
+                              ("raw_s32", np.int32, dict())):
+        want = O.add_rescale(a, b, b_mul=18415, b_shift=5, out_mode=out_mode, **kw)
+        d = B.add_desc(count_pixels=px, c=c, a_c_stride=c, b_c_stride=c, out_c_stride=c, a_dtype=dt[a_kind],
+                       b_dtype=dt[b_kind], b_mul=18415, b_shift=5,
+                       out_mode={"clamp_u8": B.ICNN_OUT_CLAMP_U8, "linear_s8": B.ICNN_OUT_LINEAR_S8,
+                                 "raw_s32": B.ICNN_OUT_RAW_S32}[out_mode], **kw)
+        out = torch.zeros(shape, dtype={np.uint8: torch.uint8, np.int8: torch.int8, np.int32: torch.int32}[odt],
+                          device="cuda:0")
+        B.iadd_rescale(d, dev(a), dev(b), out)
+        torch.cuda.synchronize()
+        assert (out.cpu().numpy() == want).all(), out_mode
+
+
+def test_add_rescale_channel_offset_and_empty():
+    from gpu_util import dev
+    from paper_2006_11735_amd import binding as B
+    g = rnd(3)
+    a, b = tensor(g, (50, 32), "s32"), tensor(g, (50, 32), "u8")
+    out = torch.full((50, 80), 77, dtype=torch.uint8, device="cuda:0")
+    d = B.add_desc(count_pixels=50, c=32, a_c_stride=32, b_c_stride=32, out_c_stride=80, out_c_offset=16,
+                   a_dtype=B.ICNN_S32, b_dtype=B.ICNN_U8, b_mul=18415, b_shift=5, mul=23187, shift=24, lo=0, hi=127)
+    B.iadd_rescale(d, dev(a), dev(b), out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    want = O.add_rescale(a, b, b_mul=18415, b_shift=5, mul=23187, shift=24, lo=0, hi=127)
+    assert (got[:, 16:48] == want).all() and (got[:, :16] == 77).all() and (got[:, 48:] == 77).all()
+    d.count_pixels = 0
+    B.iadd_rescale(d, None, None, None)              # empty input: nothing to do, no error
+
+
+@pytest.mark.parametrize("cs", [(32, 16), (5, 7, 4)])
+def test_concat_matches_oracle_and_numpy(cs):
+    from gpu_util import dev
+    from paper_2006_11735_amd import binding as B
+    g = rnd(4)
+    px = 301
+    xs = [g.integers(0, 128, size=(px, c), dtype=np.uint8) for c in cs]
+    muls, shifts = [20000 + 1000 * i for i in range(len(cs))], [14 + i for i in range(len(cs))]
+    for m, s in ((muls, shifts), ([1] * len(cs), [0] * len(cs))):
+        out = torch.zeros((px, sum(cs)), dtype=torch.uint8, device="cuda:0")
+        B.iconcat([dev(x) for x in xs], cs, cs, m, s, 100, px, out, sum(cs))
+        torch.cuda.synchronize()
+        assert (out.cpu().numpy() == O.concat(xs, m, s, 100)).all()
+    out = torch.zeros((px, sum(cs)), dtype=torch.uint8, device="cuda:0")
+    B.iconcat([dev(x) for x in xs], cs, cs, [1] * len(cs), [0] * len(cs), 127, px, out, sum(cs))
+    torch.cuda.synchronize()
+    assert (out.cpu().numpy() == np.concatenate(xs, axis=1)).all()
+
+
+@pytest.mark.parametrize("shape", [(2, 112, 112, 64, 3, 2, 1), (1, 9, 7, 5, 3, 2, 1), (1, 8, 8, 16, 2, 2, 0)])
+def test_maxpool(shape):
+    from gpu_util import dev
+    from paper_2006_11735_amd import binding as B
+    n, h, w, c, k, s, p = shape
+    x = rnd(5).integers(0, 128, size=(n, h, w, c), dtype=np.uint8)
+    want = O.maxpool2d(x, k, s, p)
+    out = torch.zeros(want.shape, dtype=torch.uint8, device="cuda:0")
+    B.imaxpool2d_u8(n, h, w, c, k, s, p, dev(x), out)
+    torch.cuda.synchronize()
+    assert (out.cpu().numpy() == want).all()
+
+
+def test_global_average_pool_and_renormalise():
+    from gpu_util import dev
+    from paper_2006_11735_amd import binding as B
+    x = rnd(6).integers(0, 128, size=(5, 7, 7, 2048), dtype=np.uint8)
+    want = O.avgpool_global(x, 21400, 20, 127)
+    out = torch.zeros((5, 1, 1, 2048), dtype=torch.uint8, device="cuda:0")
+    B.iavgpool_global_u8(5, 7, 7, 2048, 21400, 20, 127, dev(x), out)
+    torch.cuda.synchronize()
+    assert (out.cpu().numpy() == want).all()
+    for count in (4096, 1001):
+        raw = rnd(7).integers(0, 256, size=count, dtype=np.uint8)
+        o = torch.zeros(count, dtype=torch.uint8, device="cuda:0")
+        B.irenormalize_u8(count, dev(raw), o)
+        torch.cuda.synchronize()
+        assert (o.cpu().numpy().view(np.int8) == (raw.astype(np.int16) - 128)).all()

