@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the integer-only CNN hot path on one MI355X.
+
+A step is one pass of the whole ResNet-50-shaped integer network at batch 64
+(every conv with its fused integer epilogue, the skip merges, both pools and
+the fully connected layer) over synthetic inputs that already sit in HBM.
+Prints one JSON line on stdout; per-layer detail goes to stderr and, when the
+folder exists, to gpurun_out/bench_layers.json.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 5000.0     # MI355X dense int8 matrix-core peak, TOP/s
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def layer_work(net, op, images):
+    """Algorithmic ops and bytes of one conv launch (true sizes, input counted once)."""
+    n, ho, wo, _ = net["buffers"][op["dst"]]["shape"]
+    _, h, w, _ = net["buffers"][op["src"]]["shape"]
+    n = images
+    m = n * ho * wo
+    k = op["kh"] * op["kw"] * op["cin"]
+    ops = 2.0 * m * op["cout"] * k
+    out_b = 4 if op["out_mode"] == "raw_s32" else 1
+    byts = n * h * w * op["cin"] + k * op["cout"] + 4 * op["cout"] + m * op["cout"] * out_b
+    if op["res"] is not None:
+        byts += m * op["cout"] * (4 if op["res_dtype"] == "s32" else 1)
+    return ops, byts, m, k
+
+
+def cpu_baseline(net, calib, seed, budget_s=20.0):
+    """The oracle as it stands, timed on this host: images/s on a bounded sample."""
+    from oracle import net as ONet
+    from oracle import oracle as O
+    from workloads import nets as W
+    x = W.input_tensor(net, seed, 8)
+    t0 = time.time()
+    ONet.run(net, seed, calib, images=1, x_raw=x[:1])
+    t1 = time.time() - t0
+    k = int(max(1, min(8, budget_s // max(t1, 1e-3))))
+    t0 = time.time()
+    ONet.run(net, seed, calib, images=k, x_raw=x[:k])
+    dt = time.time() - t0
+    return {"value": k / dt, "unit": "images/s", "cores": O.num_threads(), "kind": "oracle",
+            "sample": "%d of the 64 images of the same ResNet-50-shaped batch, all layers, %.1f s" % (k, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="cfg3", help="workload (cfg3 = ResNet-50-shaped, batch 64)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layer-reps", type=int, default=20)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    import torch
+    from paper_2006_11735_amd.netrun import GpuNet
+    from workloads import nets as W
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU (there is no CPU fallback)")
+    torch.cuda.set_device(0)
+
+    net = W.CONFIGS[args.config]()
+    seed = 0
+    calib_path = os.path.join(ROOT, "workloads", "calib", "%s_seed%d.json" % (args.config, seed))
+    calib = json.load(open(calib_path))
+    images = net["buffers"]["raw"]["shape"][0]
+    g = GpuNet(net, seed, calib)
+    g.set_input()
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        g.run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        g.run()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    # ---- per-launch durations, measured with HIP events on the launch stream, in network
+    # order (so each layer sees the cache state its producer left behind)
+    nsteps = len(g.steps)
+    reps = max(1, args.layer_reps)
+    acc = [0.0] * nsteps
+    for _ in range(reps):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(nsteps + 1)]
+        ev[0].record()
+        for i in range(nsteps):
+            g.run_step(i)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        for i in range(nsteps):
+            acc[i] += ev[i].elapsed_time(ev[i + 1])
+    layer_ms = [a / reps for a in acc]
+
+    conv_ops = conv_ms = conv_bytes = 0.0
+    other_ms = 0.0
+    rows = []
+    for (kind, op, _), ms in zip(g.steps, layer_ms):
+        if kind != "conv":
+            other_ms += ms
+            rows.append({"name": op["dst"], "kind": kind, "ms": ms})
+            continue
+        ops, byts, m, k = layer_work(net, op, images)
+        conv_ops += ops
+        conv_ms += ms
+        conv_bytes += byts
+        tops = ops / (ms * 1e-3) / 1e12
+        attain = min(INT8_MFMA_PEAK_TOPS, ops / byts * HBM_PEAK_GBS / 1e3)
+        rows.append({"name": op["name"], "kind": "conv", "M": m, "N": op["cout"], "K": k, "ms": ms,
+                     "tops": tops, "pct_mfma_peak": 100 * tops / INT8_MFMA_PEAK_TOPS,
+                     "pct_attainable": 100 * tops / attain, "gbs": byts / (ms * 1e-3) / 1e9})
+    for r in rows:
+        if r["kind"] == "conv":
+            log("%-12s M=%-7d N=%-5d K=%-5d %8.1f us %7.1f TOP/s %5.1f%% peak %5.1f%% attainable %7.0f GB/s" % (
+                r["name"], r["M"], r["N"], r["K"], r["ms"] * 1e3, r["tops"], r["pct_mfma_peak"],
+                r["pct_attainable"], r["gbs"]))
+        else:
+            log("%-12s %-8s %8.1f us" % (r["name"], r["kind"], r["ms"] * 1e3))
+    conv_tops = conv_ops / (conv_ms * 1e-3) / 1e12
+    n_conv = sum(1 for r in rows if r["kind"] == "conv")
+    log("conv launches: %d, %.3f ms per step by events (whole step %.3f ms wall), %.1f TOP/s" % (
+        n_conv, conv_ms, ms_per_step, conv_tops))
+
+    result = {
+        "metric": "images/s ResNet-50-shaped b64 (int8 conv TOPS and % of int8 MFMA peak alongside)",
+        "value": images / (ms_per_step * 1e-3),
+        "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8 x int8 -> int32 accumulate, 64-bit integer requantisation",
+        "data": "synthetic",
+        "config": {"workload": "cfg3: ResNet-50-shaped integer inference, batch 64, 3x224x224 uint8 input, "
+                               "53 convs + FC, 16 skip merges, stored oracle-side calibration (seed 0)",
+                   "batch": images},
+        "conv_tops": conv_tops,
+        "pct_int8_mfma_peak": 100 * conv_tops / INT8_MFMA_PEAK_TOPS,
+        "whole_step_tops": conv_ops / (ms_per_step * 1e-3) / 1e12,
+        "roofline": {"kernel": "conv_igemm_kernel (all %d conv launches of a step, every tile shape)" % n_conv,
+                     "bound": "mfma", "achieved": conv_tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": conv_tops / INT8_MFMA_PEAK_TOPS, "traffic": None,
+                     "launches_per_step": n_conv, "avg_launch_us": conv_ms * 1e3 / n_conv,
+                     "algorithmic_gop_per_step": conv_ops / 1e9,
+                     "algorithmic_gb_per_step": conv_bytes / 1e9},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(net, calib, seed)
+    out_dir = os.path.join(ROOT, "gpurun_out")
+    if os.path.isdir(out_dir):
+        with open(os.path.join(out_dir, "bench_layers.json"), "w") as f:
+            json.dump({"result": result, "layers": rows}, f, indent=1)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

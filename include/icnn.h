@@ -68,7 +68,8 @@ typedef enum {
  *       x() is 0 outside the image; inside it is the stored byte read as uint8
  *       (in_signed = 0), as int8 (in_signed = 1), or as uint8 minus 128
  *       (in_sub128 = 1: the re-normalisation of a raw picture, Section 3.4.1).
- *   Y = U + bias[co]
+ *   Y = U + bias[co]                     (caller guarantees |bias[co]| <= 2^30, so that
+ *                                         Y always fits int32; kh*kw*cin <= 65535 bounds U)
  *   S = [res * res_mul / 2^res_shift]                       (res_mode != NONE)
  *   T = sat32(Y + S) if res_mode == PRE, else Y             (Section 4.1: the skip
  *       operand is rescaled to the main path's ratio and added before BReLU)

@@ -263,3 +263,11 @@ int orc_avgpool_global_u8(int32_t n, int32_t h, int32_t w, int32_t c, int32_t mu
         }
     return ORC_OK;
 }
+
+/* Threads the parallel loops above will use (for reporting beside timings). */
+#ifdef _OPENMP
+#include <omp.h>
+int orc_num_threads(void) { return omp_get_max_threads(); }
+#else
+int orc_num_threads(void) { return 1; }
+#endif

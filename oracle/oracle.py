@@ -73,6 +73,13 @@ def _mode(m, table):
     return table[m] if isinstance(m, str) else int(m)
 
 
+def num_threads():
+    """Threads the C oracle's parallel loops use."""
+    L = lib()
+    L.orc_num_threads.restype = C.c_int
+    return int(L.orc_num_threads())
+
+
 def rsr(v, s):
     """[v / 2^s], round half up."""
     return int(lib().orc_rsr(int(v), int(s)))

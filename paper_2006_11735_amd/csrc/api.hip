@@ -190,9 +190,37 @@ int iconv2d_brelu(const icnn_conv_desc *d, const void *x, const void *w_packed, 
     const int ob = d->out_mode == ICNN_OUT_RAW_S32 ? 4 : 1;
     a.vec_out = aligned16(y) && ((long long)d->out_c_stride * ob) % 16 == 0 && ((long long)d->out_c_offset * ob) % 16 == 0;
     a.vec_res = 0;
+    a.vec_bias = aligned16(bias) && d->cout % 16 == 0;
     if (d->res_mode != ICNN_RES_NONE) {
         const int rb = dtype_bytes(d->res_dtype);
         a.vec_res = aligned16(res) && ((long long)d->res_c_stride * rb) % 16 == 0;
+    }
+    {
+        // bytes of x up to the end of the last pixel's channel slice, and of the packed weights
+        const unsigned long long xb = ((unsigned long long)d->n * d->h * d->w - 1) * d->in_c_stride + d->cin;
+        const unsigned long long wb = (unsigned long long)g.chunks * g.ksteps * kChunkBytes;
+        a.x_bytes = xb > 0xffffffffull ? 0xffffffffu : (unsigned)xb;
+        a.wp_bytes = wb > 0xffffffffull ? 0xffffffffu : (unsigned)wb;
+        a.nstages = 0;
+        a.div_howo = a.div_wo = FastDiv{0, 0, 0};
+    }
+    a.n_tiles = a.per_xcd = 0;
+    a.rq_fast = 0;
+    a.mul_hi = 0;
+    if (d->out_mode != ICNN_OUT_RAW_S32 && a.shift >= 1 && a.shift <= 32 &&
+        ((long long)a.mul << (32 - a.shift)) <= 0x7fffffffLL) {
+        a.rq_fast = 1;
+        a.mul_hi = (int)((long long)a.mul << (32 - a.shift));
+    }
+    a.res_fast = 0;
+    if (d->res_mode != ICNN_RES_NONE && d->res_dtype != ICNN_S32 && a.res_shift <= 30 &&
+        255LL * a.res_mul + (1LL << a.res_shift) / 2 <= 0x7fffffffLL)
+        a.res_fast = 1;
+    a.epi_vec = a.vec_out && (d->res_mode == ICNN_RES_NONE || a.vec_res);
+    {
+        const int res_kind = d->res_mode == ICNN_RES_NONE ? 0 : (d->res_mode == ICNN_RES_PRE && a.res_fast ? 1 : 2);
+        const int rq_kind = d->out_mode == ICNN_OUT_RAW_S32 ? 0 : (a.rq_fast ? 1 : 2);
+        a.epi_mode = 3 * res_kind + rq_kind;
     }
     const bool vec_in = aligned16(x) && d->cin % 16 == 0 && d->in_c_stride % 16 == 0;
     return launched(launch_conv(a, vec_in, (hipStream_t)stream), "iconv2d_brelu");

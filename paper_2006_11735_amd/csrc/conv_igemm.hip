@@ -11,16 +11,419 @@
 // registers and stores 16 bytes per lane; int32 never reaches memory.
 //
 // One workgroup = 256 threads = 4 waves, tile BM output channels x BP pixels,
-// K advanced 64 at a time through double-buffered LDS.
+// K advanced 64 at a time.  Two kernels share the tile layout and the epilogue:
+//   conv_dlds_kernel  cin % 16 == 0, aligned: tiles go from global memory straight
+//                     into a ring of LDS stages (global_load_lds_dwordx4), several
+//                     stages in flight, one barrier per K step;
+//   conv_greg_kernel  any cin / alignment / raw-picture input: tiles are staged
+//                     through registers (double-buffered LDS).
 #include "icnn_device.h"
 
 namespace icnn {
 
-template <int BM, int BP, int WAVES_M, int WAVES_P, bool VEC>
-__global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a)
+// LDS tile layout of one K step (both kernels):
+//   A (weights): BM*64 bytes in packed-fragment order, i.e. a straight copy of
+//      BM/32 consecutive 2 KiB chunks of the packed weights.
+//   B (activations): BP rows of 64 bytes (one output pixel each); the 16-byte slot
+//      s of row r lives at slot s ^ ((r >> 2) & 3), which makes both the row-wise
+//      fill and the column-wise fragment reads free of bank conflicts.
+__device__ __forceinline__ int b_slot_offset(int row, int slot)
 {
-    constexpr int TM = BM / WAVES_M / 32;   // 32x32 tiles per wave along cout
-    constexpr int TP = BP / WAVES_P / 32;   // and along pixels
+    return row * 64 + ((slot ^ ((row >> 2) & 3)) << 4);
+}
+
+// ---------------------------------------------------------------- epilogue
+// Every call handles channels co0..co0+15 (co0 a multiple of 16) of output pixel p,
+// held in one lane's accumulator registers, which were initialised with the bias
+// (so they hold Y = U + b).  Then (Section 4.1)
+// the rescaled skip operand, then (Section 3.2.1) requantisation and the clamp.
+
+// any alignment, any tail: one element at a time, 64-bit arithmetic throughout
+__device__ __forceinline__ void epilogue_slow(const ConvArgs &a, const v16i &acc, int p, int co0, int nv)
+{
+    const size_t ro = (size_t)p * a.res_cs + co0;
+    const size_t oo = (size_t)p * a.out_cs + a.out_co + co0;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        if (r >= nv) break;
+        int64_t t = acc[r];
+        int64_t skip = 0;
+        if (a.res_mode != 0) skip = rsr64((int64_t)load_elem(a.res, ro + r, a.res_dtype) * a.res_mul, a.res_shift);
+        if (a.res_mode == 1) t += skip;
+        const int ti = sat32(t);
+        if (a.out_mode == 3) {
+            ((int32_t *)a.out)[oo + r] = ti;
+        } else {
+            int64_t q = rsr64((int64_t)ti * a.mul, a.shift);
+            if (a.res_mode == 2) q += skip;
+            ((uint8_t *)a.out)[oo + r] = (uint8_t)clampi64(q, a.lo, a.hi);
+        }
+    }
+}
+
+// vector path: all 16 channels valid, 16-byte aligned skip operand and output.
+// RES: 0 no skip operand; 1 8-bit operand joined before requantisation with a rescale
+//      that fits 32 bits; 2 anything else (int32 operand, wide multiplier, join after).
+// RQ:  0 raw int32 output; 1 requantisation as one 32x32->64 multiply-add whose high
+//      word is the result; 2 general 64-bit multiply, add, shift.
+template <int RES, int RQ>
+__device__ __forceinline__ void epilogue_vec(const ConvArgs &a, const v16i &acc, int p, int co0, const v4i &res8)
+{
+    int t[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t[r] = acc[r];
+    int rv[16];
+    if (RES != 0) {
+        if (RES == 2 && a.res_dtype == 2) {
+            const v4i *rp = (const v4i *)((const int32_t *)a.res + ((size_t)p * a.res_cs + co0));
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const v4i v = rp[q];
+                rv[4 * q] = v.x; rv[4 * q + 1] = v.y; rv[4 * q + 2] = v.z; rv[4 * q + 3] = v.w;
+            }
+        } else {
+            const int wd[4] = {res8.x, res8.y, res8.z, res8.w};
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int b8 = (wd[r >> 2] >> ((r & 3) * 8)) & 0xff;
+                rv[r] = a.res_dtype == 1 ? (int)(int8_t)b8 : b8;
+            }
+        }
+    }
+    if (RES == 1) {
+        const int half = (1 << a.res_shift) >> 1;
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            t[r] = __builtin_elementwise_add_sat(t[r], (rv[r] * a.res_mul + half) >> a.res_shift);
+    }
+    if (RES == 2 && a.res_mode == 1) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) t[r] = sat32((int64_t)t[r] + rsr64((int64_t)rv[r] * a.res_mul, a.res_shift));
+    }
+    const size_t oo = (size_t)p * a.out_cs + a.out_co + co0;
+    if (RQ == 0) {
+        v4i *op = (v4i *)((int32_t *)a.out + oo);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) op[q] = v4i{t[4 * q], t[4 * q + 1], t[4 * q + 2], t[4 * q + 3]};
+        return;
+    }
+    uint32_t wd[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        int v;
+        if (RQ == 1 && !(RES == 2)) {
+            // [t * mul / 2^shift] = high word of t * (mul << (32 - shift)) + 2^31   (1 <= shift <= 32)
+            const int q = (int)(((int64_t)t[r] * a.mul_hi + 0x80000000LL) >> 32);
+            v = min(max(q, a.lo), a.hi);
+        } else {
+            int64_t q = RQ == 1 ? (((int64_t)t[r] * a.mul_hi + 0x80000000LL) >> 32)
+                                : rsr64((int64_t)t[r] * a.mul, a.shift);
+            if (RES == 2 && a.res_mode == 2) q += rsr64((int64_t)rv[r] * a.res_mul, a.res_shift);
+            v = clampi64(q, a.lo, a.hi);
+        }
+        wd[r >> 2] |= (uint32_t)(v & 0xff) << ((r & 3) * 8);
+    }
+    *(v4i *)((uint8_t *)a.out + oo) = v4i{(int)wd[0], (int)wd[1], (int)wd[2], (int)wd[3]};
+}
+
+// Epilogue of a wave's TM x TP accumulator tiles; the mode switch is outside the
+// tile loops so each mode is straight-line code.
+template <int TM, int TP>
+__device__ __forceinline__ void epilogue_tiles(const ConvArgs &a, const v16i (&acc)[TM][TP], int co_wave, int pix_wave,
+                                               int lane)
+{
+    const int half = lane >> 5;
+    auto for_tiles = [&](auto fn) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int co0 = co_wave + i * 32 + half * 16;
+#pragma unroll
+            for (int j = 0; j < TP; ++j) {
+                const int p = pix_wave + j * 32 + (lane & 31);
+                if (co0 < a.Cout && p < a.M) fn(acc[i][j], p, co0, i, j);
+            }
+        }
+    };
+    // channel tails and unaligned tensors take the element-wise path for the whole call
+    if (!a.epi_vec || (a.Cout & 15)) {
+        for_tiles([&](const v16i &c, int p, int co0, int, int) {
+            epilogue_slow(a, c, p, co0, min(16, a.Cout - co0));
+        });
+        return;
+    }
+    // 8-bit skip operands of all tiles are fetched before the first store (stores may alias
+    // them as far as the compiler knows, which would otherwise serialise the fetches)
+    v4i res8[TM][TP];
+    if (a.res_mode != 0 && a.res_dtype != 2) {
+        for_tiles([&](const v16i &, int p, int co0, int i, int j) {
+            res8[i][j] = *(const v4i *)((const uint8_t *)a.res + ((size_t)p * a.res_cs + co0));
+        });
+    }
+    switch (a.epi_mode) {
+#define ICNN_EPI_CASE(RES, RQ)                                                                      \
+    case RES * 3 + RQ:                                                                              \
+        for_tiles([&](const v16i &c, int p, int co0, int i, int j) {                                \
+            epilogue_vec<RES, RQ>(a, c, p, co0, res8[i][j]);                                        \
+        });                                                                                         \
+        break;
+        ICNN_EPI_CASE(0, 0) ICNN_EPI_CASE(0, 1) ICNN_EPI_CASE(0, 2)
+        ICNN_EPI_CASE(1, 0) ICNN_EPI_CASE(1, 1) ICNN_EPI_CASE(1, 2)
+        ICNN_EPI_CASE(2, 0) ICNN_EPI_CASE(2, 1) ICNN_EPI_CASE(2, 2)
+#undef ICNN_EPI_CASE
+    default: break;
+    }
+}
+
+// Maps the hardware workgroup id to a tile.  Workgroups are dealt round-robin to the
+// 8 XCDs (each with its own L2); giving XCD x the contiguous tile range
+// [x*per_xcd, (x+1)*per_xcd) keeps the cout tiles of one pixel tile, and neighbouring
+// pixel tiles (shared halo rows), in one L2.  Returns false for padding workgroups.
+__device__ __forceinline__ bool tile_of_block(const ConvArgs &a, int &ct, int &pt)
+{
+    const int xcd = blockIdx.x & 7;
+    const int idx = blockIdx.x >> 3;
+    const int logical = xcd * a.per_xcd + idx;
+    if (logical >= a.n_tiles) return false;
+    ct = logical % a.n_ct;
+    pt = logical / a.n_ct;
+    return true;
+}
+
+// Accumulators start at the bias: register r of a lane in half h of tile row i holds
+// channel co_base + 32*i + 16*h + r (for every pixel tile j).
+template <int TM, int TP>
+__device__ __forceinline__ void init_acc_with_bias(const ConvArgs &a, int co_base, int half, v16i (&acc)[TM][TP])
+{
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int co0 = co_base + i * 32 + half * 16;
+        v16i b;
+        if (a.vec_bias) {
+            const v4i *bp = (const v4i *)(a.bias + min(co0, a.Cout - 16));
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const v4i v = bp[q];
+                b[4 * q] = v.x; b[4 * q + 1] = v.y; b[4 * q + 2] = v.z; b[4 * q + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) b[r] = a.bias[min(co0 + r, a.Cout - 1)];
+        }
+#pragma unroll
+        for (int j = 0; j < TP; ++j) acc[i][j] = b;
+    }
+}
+
+#define ICNN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | 0x0F70 | (((n) >> 4) << 14))
+
+// ------------------------------------------------- direct-to-LDS pipelined kernel
+// floor(n / d) for 0 <= n < 2^31 by multiply-high and shifts (Granlund & Montgomery's
+// round-up method); the host fills `FastDiv` for d.
+__device__ __forceinline__ int fast_div(int n, const FastDiv &d)
+{
+    const unsigned t = __umulhi((unsigned)n, d.mul);
+    return (int)((t + (((unsigned)n - t) >> d.s1)) >> d.s2);
+}
+
+// Tiles travel from global memory into LDS without passing through registers
+// (buffer_load_dwordx4 ... lds).  Every lane moves 16 bytes; a wave-wide copy fills
+// 1 KiB of consecutive LDS.  Out-of-image pieces (zero padding, the K tail, pixels
+// beyond the last one) are given a byte offset beyond the buffer's size: the
+// buffer unit returns zeros for those lanes, so padding costs one select.
+// MODE 0: 1x1 kernel, stride 1, no padding (input pixel = output pixel);
+// MODE 1: cin % 64 == 0 and kh*kw <= 32: a K step lies inside one tap, so the tap
+//         position is wave-uniform (scalar registers, one bit test per copy);
+// MODE 2: any cin % 16 == 0: every lane tracks the tap of its own 16-byte slot.
+template <int BM, int BP, int WAVES_M, int WAVES_P, int MODE>
+__global__ __launch_bounds__(256, 2) void conv_dlds_kernel(const ConvArgs a)
+{
+#if defined(__HIP_DEVICE_COMPILE__)   // the buffer-resource type exists in the device pass only
+    constexpr int TM = BM / WAVES_M / 32;
+    constexpr int TP = BP / WAVES_P / 32;
+    constexpr int A_BYTES = BM * kStepK;
+    constexpr int B_BYTES = BP * kStepK;
+    constexpr int STAGE = A_BYTES + B_BYTES;
+    constexpr int A_INSTR = BM / 16;                 // wave-wide 1 KiB copies per stage, whole workgroup
+    constexpr int NA = A_INSTR >= 4 ? A_INSTR / 4 : 1;   // per wave (narrow tiles repeat a copy)
+    constexpr int NB = BP / 64;                      // per wave
+    constexpr int LPS = NA + NB;                     // loads per stage per wave
+    constexpr unsigned OOB = 0x80000000u;            // beyond any buffer this kernel accepts (< 2 GiB)
+    static_assert(WAVES_M * WAVES_P == 4 && TM >= 1 && TP >= 1 && NB >= 1, "tile shape");
+
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];   // nstages * STAGE bytes
+
+    int ct, pt;
+    if (!tile_of_block(a, ct, pt)) return;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave % WAVES_M;
+    const int wp = wave / WAVES_M;
+    const int pix0 = pt * BP;
+    const int chunk0 = ct * (BM / 32);
+    const int nstages = a.nstages;
+
+    const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, a.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)a.wp, 0, a.wp_bytes, 0x00020000);
+
+    // A copy q of this wave covers packed pieces [64*m, 64*m + 64), m = (4*q + wave) % A_INSTR;
+    // its byte offset at K step s is a_off[q] + s * 2048
+    unsigned a_off[NA];
+    int a_lds[NA];
+#pragma unroll
+    for (int q = 0; q < NA; ++q) {
+        const int m = (4 * q + wave) % A_INSTR;
+        const int e = m * 64 + lane;
+        a_off[q] = (unsigned)(chunk0 + (e >> 7)) * (unsigned)a.ksteps * kChunkBytes + (unsigned)(e & 127) * 16;
+        a_lds[q] = m * 1024;
+    }
+    // B copy j of this wave covers rows 16*(4*j + wave) .. +16 of the tile; this lane fills physical
+    // slot lane & 3 of row 16*(4*j + wave) + (lane >> 2), i.e. logical slot ls (same for every j)
+    const int ls = (lane & 3) ^ ((lane >> 4) & 3);
+    unsigned b_off[NB];      // byte offset of the pixel's first tap (MODE 0, 1: plus the slot's 16*ls)
+    unsigned tapmask[NB];    // MODE 1: bit kh*KW + kw set when that tap lies inside the image
+    unsigned rowmask[NB];    // MODE 2: bit kh set when the input row of tap kh lies inside the image
+    unsigned colmask[NB];    // MODE 2: bit kw likewise for columns
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        const int p = pix0 + 16 * (4 * j + wave) + (lane >> 2);
+        const bool pv = p < a.M;
+        tapmask[j] = rowmask[j] = colmask[j] = 0;
+        if (MODE == 0) {
+            b_off[j] = pv ? (unsigned)p * (unsigned)a.in_cs + ls * 16 : OOB;
+        } else {
+            const int pc = pv ? p : 0;
+            const int n = fast_div(pc, a.div_howo);
+            const int r = pc - n * a.Ho * a.Wo;
+            const int ho = fast_div(r, a.div_wo);
+            const int wo = r - ho * a.Wo;
+            const int hi0 = ho * a.sh - a.ph, wi0 = wo * a.sw - a.pw;
+            // may be "negative" (wraps): only used together with a tap that is inside the image
+            b_off[j] = (unsigned)(((n * a.H + hi0) * a.W + wi0) * a.in_cs) + (MODE == 1 ? ls * 16 : 0);
+            unsigned rm = 0, cm = 0;
+            for (int k = 0; k < a.KH; ++k) rm |= (unsigned)((unsigned)(hi0 + k) < (unsigned)a.H) << k;
+            for (int k = 0; k < a.KW; ++k) cm |= (unsigned)((unsigned)(wi0 + k) < (unsigned)a.W) << k;
+            if (!pv) rm = 0;
+            if (MODE == 1) {
+                unsigned tmk = 0;
+                for (int k = 0; k < a.KH; ++k) tmk |= ((rm >> k) & 1u ? cm : 0u) << (k * a.KW);
+                tapmask[j] = tmk;
+            } else {
+                rowmask[j] = rm;
+                colmask[j] = cm;
+            }
+        }
+    }
+    // K-axis position: MODE 1 wave-uniform (skh, skw, sc0 = first channel of the step);
+    // MODE 2 per lane (kh, kw, ci of the lane's slot)
+    int skh = 0, skw = 0, sc0 = 0;
+    int kh = 0, kw = 0, ci = ls * 16;
+    if (MODE == 2) {
+        const int tap = ci / a.Cin;
+        ci -= tap * a.Cin;
+        kh = tap / a.KW;
+        kw = tap - kh * a.KW;
+    }
+
+    auto issue_stage = [&](int s, int buf) {
+        uint8_t *stage = lds + buf * STAGE;
+#pragma unroll
+        for (int q = 0; q < NA; ++q)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, (__attribute__((address_space(3))) void *)(stage + a_lds[q]),
+                                                     16, a_off[q], s * kChunkBytes, 0, 0);
+        if (MODE == 0) {
+            const bool kok = s * kStepK + ls * 16 < a.Cin;
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    rs_x, (__attribute__((address_space(3))) void *)(stage + A_BYTES + (4 * j + wave) * 1024), 16,
+                    kok ? b_off[j] : OOB, s * kStepK, 0, 0);
+        } else if (MODE == 1) {
+            const unsigned bit = 1u << (skh * a.KW + skw);
+            // added per lane (not as the scalar offset): b_off may have wrapped below zero and the
+            // buffer unit range-checks the vector offset alone
+            const unsigned soff = (unsigned)((skh * a.W + skw) * a.in_cs + sc0);
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    rs_x, (__attribute__((address_space(3))) void *)(stage + A_BYTES + (4 * j + wave) * 1024), 16,
+                    (tapmask[j] & bit) ? b_off[j] + soff : OOB, 0, 0, 0);
+            sc0 += kStepK;
+            if (sc0 == a.Cin) {
+                sc0 = 0;
+                if (++skw == a.KW) { skw = 0; ++skh; }
+            }
+        } else {
+            const unsigned tapoff = (unsigned)((kh * a.W + kw) * a.in_cs + ci);
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                const bool ok = ((rowmask[j] >> kh) & (colmask[j] >> kw) & 1u) != 0;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    rs_x, (__attribute__((address_space(3))) void *)(stage + A_BYTES + (4 * j + wave) * 1024), 16,
+                    ok ? b_off[j] + tapoff : OOB, 0, 0, 0);
+            }
+            ci += kStepK;
+            while (ci >= a.Cin) {
+                ci -= a.Cin;
+                if (++kw == a.KW) { kw = 0; ++kh; }
+            }
+        }
+    };
+
+    v16i acc[TM][TP];
+    init_acc_with_bias<TM, TP>(a, ct * BM + wm * TM * 32, lane >> 5, acc);
+
+    const int ksteps = a.ksteps;
+    for (int s = 0; s < nstages - 1; ++s) issue_stage(s, s);   // the host keeps nstages - 1 <= ksteps
+
+    // fragment read addresses inside a stage (A: straight; B: swizzled rows, one base per k half)
+    const int a_rd = wm * TM * 2048 + lane * 16;
+    const int b_rd0 = A_BYTES + b_slot_offset(wp * TP * 32 + (lane & 31), (lane >> 5));
+    const int b_rd1 = A_BYTES + b_slot_offset(wp * TP * 32 + (lane & 31), 2 + (lane >> 5));
+
+    int buf = 0;
+    for (int s = 0; s < ksteps; ++s) {
+        // stage s has landed once at most `later` younger stages' copies remain in flight
+        const int later = min(nstages - 2, ksteps - 1 - s);
+        asm volatile("" ::: "memory");
+        if (later >= 2) ICNN_WAIT_VMCNT(2 * LPS);
+        else if (later == 1) ICNN_WAIT_VMCNT(LPS);
+        else ICNN_WAIT_VMCNT(0);
+        __builtin_amdgcn_s_barrier();      // every wave's part of stage s is in LDS; stage s-1 is drained
+        asm volatile("" ::: "memory");
+        if (s + nstages - 1 < ksteps) {
+            int nb = buf + nstages - 1;
+            if (nb >= nstages) nb -= nstages;
+            issue_stage(s + nstages - 1, nb);
+        }
+        const uint8_t *S = lds + buf * STAGE;
+#pragma unroll
+        for (int kq = 0; kq < 2; ++kq) {
+            v4i af[TM], bf[TP];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) af[i] = *(const v4i *)(S + a_rd + (i * 2 + kq) * 1024);
+#pragma unroll
+            for (int j = 0; j < TP; ++j) bf[j] = *(const v4i *)(S + (kq ? b_rd1 : b_rd0) + j * 2048);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TP; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+        }
+        if (++buf == nstages) buf = 0;
+    }
+
+    epilogue_tiles<TM, TP>(a, acc, ct * BM + wm * TM * 32, pix0 + wp * TP * 32, lane);
+#endif
+}
+
+// ------------------------------------------------- register-staged general kernel
+template <int BM, int BP, int WAVES_M, int WAVES_P, bool VEC>
+__global__ __launch_bounds__(256) void conv_greg_kernel(const ConvArgs a)
+{
+    constexpr int TM = BM / WAVES_M / 32;
+    constexpr int TP = BP / WAVES_P / 32;
     constexpr int A_BYTES = BM * kStepK;
     constexpr int B_BYTES = BP * kStepK;
     constexpr int STAGE = A_BYTES + B_BYTES;
@@ -30,18 +433,18 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a)
 
     __shared__ __attribute__((aligned(16))) uint8_t lds[2 * STAGE];
 
+    int ct, pt;
+    if (!tile_of_block(a, ct, pt)) return;
+
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int wm = wave % WAVES_M;
     const int wp = wave / WAVES_M;
-    const int ct = blockIdx.x % a.n_ct;
-    const int pt = blockIdx.x / a.n_ct;
     const int pix0 = pt * BP;
     const int chunk0 = ct * (BM / 32);
 
-    // ---- gather bookkeeping: this thread always fills 16-byte slot `slot` of
-    // pixels (tid>>2) + 64*j of the tile.
+    // this thread always fills 16-byte slot `slot` of rows (tid>>2) + 64*j of the B tile
     const int slot = tid & 3;
     int hi0[NPB], wi0[NPB], nrow[NPB];
     bool pv[NPB];
@@ -59,7 +462,6 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a)
         wi0[j] = wo * a.sw - a.pw;
         nrow[j] = n * a.H;
     }
-    // position of this thread's slot on the K axis, kept as (kh, kw, ci)
     int kh = 0, kw = 0, ci = 0;
     if (VEC) {
         const int kk = slot * 16;
@@ -70,30 +472,26 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a)
     }
 
     v4i areg[NPA], breg[NPB];
+    bool bok[NPB];
 
     auto load_tiles = [&](int s) {
 #pragma unroll
         for (int i = 0; i < NPA; ++i) {
             const int e = tid + 256 * i;
             if (BM * 4 >= 256 * (i + 1) || e < BM * 4) {
-                const size_t off = ((size_t)(chunk0 + (e >> 7)) * a.ksteps + s) * kChunkBytes +
-                                   (size_t)(e & 127) * 16;
+                const size_t off = ((size_t)(chunk0 + (e >> 7)) * a.ksteps + s) * kChunkBytes + (size_t)(e & 127) * 16;
                 areg[i] = *(const v4i *)(a.wp + off);
             }
         }
         if (VEC) {
+            // branch-free: out-of-image pieces read offset 0 and are zeroed when stored to LDS
 #pragma unroll
             for (int j = 0; j < NPB; ++j) {
                 const int hi = hi0[j] + kh, wi = wi0[j] + kw;
-                const bool ok = pv[j] && kh < a.KH && (unsigned)hi < (unsigned)a.H &&
-                                (unsigned)wi < (unsigned)a.W;
-                v4i v = {0, 0, 0, 0};
-                if (ok) {
-                    const size_t off = ((size_t)(nrow[j] + hi) * a.W + wi) * a.in_cs + ci;
-                    v = *(const v4i *)(a.x + off);
-                    v.x ^= a.in_xor; v.y ^= a.in_xor; v.z ^= a.in_xor; v.w ^= a.in_xor;
-                }
-                breg[j] = v;
+                const bool ok = pv[j] && kh < a.KH && (unsigned)hi < (unsigned)a.H && (unsigned)wi < (unsigned)a.W;
+                const size_t off = ok ? ((size_t)(nrow[j] + hi) * a.W + wi) * a.in_cs + ci : 0;
+                breg[j] = *(const v4i *)(a.x + off);
+                bok[j] = ok;
             }
             ci += kStepK;
             while (ci >= a.Cin) {
@@ -123,6 +521,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a)
                     }
                 }
                 breg[j] = v4i{(int)wd[0], (int)wd[1], (int)wd[2], (int)wd[3]};
+                bok[j] = true;
             }
         }
     };
@@ -137,18 +536,17 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a)
         }
 #pragma unroll
         for (int j = 0; j < NPB; ++j) {
-            const int pl = (tid >> 2) + 64 * j;
-            *(v4i *)(B + pl * 64 + ((slot ^ ((pl >> 2) & 3)) << 4)) = breg[j];
+            v4i v = breg[j];
+            if (VEC) {
+                const int x = (int)a.in_xor;
+                v = bok[j] ? v4i{v.x ^ x, v.y ^ x, v.z ^ x, v.w ^ x} : v4i{0, 0, 0, 0};
+            }
+            *(v4i *)(B + b_slot_offset((tid >> 2) + 64 * j, slot)) = v;
         }
     };
 
     v16i acc[TM][TP];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TP; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+    init_acc_with_bias<TM, TP>(a, ct * BM + wm * TM * 32, lane >> 5, acc);
 
     load_tiles(0);
     store_tiles(0);
@@ -165,14 +563,10 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a)
         for (int kq = 0; kq < 2; ++kq) {
             v4i af[TM], bf[TP];
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-                af[i] = *(const v4i *)(A + ((wm * TM + i) * 2 + kq) * 1024 + lane * 16);
+            for (int i = 0; i < TM; ++i) af[i] = *(const v4i *)(A + ((wm * TM + i) * 2 + kq) * 1024 + lane * 16);
 #pragma unroll
-            for (int j = 0; j < TP; ++j) {
-                const int pl = (wp * TP + j) * 32 + (lane & 31);
-                const int sl = kq * 2 + (lane >> 5);
-                bf[j] = *(const v4i *)(B + pl * 64 + ((sl ^ ((pl >> 2) & 3)) << 4));
-            }
+            for (int j = 0; j < TP; ++j)
+                bf[j] = *(const v4i *)(B + b_slot_offset((wp * TP + j) * 32 + (lane & 31), kq * 2 + (lane >> 5)));
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -183,110 +577,87 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a)
         __syncthreads();
     }
 
-    // ---- epilogue on registers: bias, skip merge, requantise, clamp, store
-    const int half = lane >> 5;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int co0 = ct * BM + (wm * TM + i) * 32 + half * 16;
-        if (co0 >= a.Cout) continue;
-        const int nv = min(16, a.Cout - co0);
-        int bv[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) bv[r] = r < nv ? a.bias[co0 + r] : 0;
-#pragma unroll
-        for (int j = 0; j < TP; ++j) {
-            const int p = pix0 + (wp * TP + j) * 32 + (lane & 31);
-            if (p >= a.M) continue;
-            int t[16];
-            int64_t skip[16];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) t[r] = acc[i][j][r] + bv[r];
-            if (a.res_mode != 0) {
-                const size_t ro = (size_t)p * a.res_cs + co0;
-                int rv[16];
-                if (a.vec_res && nv == 16) {
-                    if (a.res_dtype == 2) {
-                        const v4i *rp = (const v4i *)((const int32_t *)a.res + ro);
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const v4i v = rp[q];
-                            rv[4 * q] = v.x; rv[4 * q + 1] = v.y; rv[4 * q + 2] = v.z; rv[4 * q + 3] = v.w;
-                        }
-                    } else {
-                        const v4i v = *(const v4i *)((const uint8_t *)a.res + ro);
-                        const int wd[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int b8 = (wd[r >> 2] >> ((r & 3) * 8)) & 0xff;
-                            rv[r] = a.res_dtype == 1 ? (int)(int8_t)b8 : b8;
-                        }
-                    }
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) rv[r] = r < nv ? load_elem(a.res, ro + r, a.res_dtype) : 0;
-                }
-#pragma unroll
-                for (int r = 0; r < 16; ++r) skip[r] = rsr64((int64_t)rv[r] * a.res_mul, a.res_shift);
-                if (a.res_mode == 1) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) t[r] = sat32((int64_t)t[r] + skip[r]);
-                }
-            }
-            const size_t oo = (size_t)p * a.out_cs + a.out_co + co0;
-            if (a.out_mode == 3) {
-                int32_t *op = (int32_t *)a.out + oo;
-                if (a.vec_out && nv == 16) {
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        ((v4i *)op)[q] = v4i{t[4 * q], t[4 * q + 1], t[4 * q + 2], t[4 * q + 3]};
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (r < nv) op[r] = t[r];
-                }
-            } else {
-                uint32_t wd[4] = {0, 0, 0, 0};
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    int64_t q = rsr64((int64_t)t[r] * a.mul, a.shift);
-                    if (a.res_mode == 2) q += skip[r];
-                    const int v = clampi64(q, a.lo, a.hi);
-                    wd[r >> 2] |= (uint32_t)(v & 0xff) << ((r & 3) * 8);
-                }
-                uint8_t *op = (uint8_t *)a.out + oo;
-                if (a.vec_out && nv == 16) {
-                    *(v4i *)op = v4i{(int)wd[0], (int)wd[1], (int)wd[2], (int)wd[3]};
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (r < nv) op[r] = (uint8_t)(wd[r >> 2] >> ((r & 3) * 8));
-                }
-            }
-        }
-    }
+    epilogue_tiles<TM, TP>(a, acc, ct * BM + wm * TM * 32, pix0 + wp * TP * 32, lane);
+}
+
+// ------------------------------------------------------------------ dispatch
+static bool finish_args(ConvArgs &a, int BM, int BP)
+{
+    a.n_ct = (a.Cout + BM - 1) / BM;
+    const long long tiles = (long long)a.n_ct * ((a.M + BP - 1) / BP);
+    if (tiles <= 0 || tiles > 0x7ffffff0LL) return false;
+    a.n_tiles = (int)tiles;
+    a.per_xcd = (int)((tiles + 7) / 8);
+    return true;
+}
+
+static FastDiv make_fast_div(unsigned d)
+{
+    // l = ceil(log2 d); mul = floor(2^32 * (2^l - d) / d) + 1; q = (t + ((n - t) >> min(l,1))) >> max(l-1,0)
+    FastDiv f;
+    unsigned l = 0;
+    while ((1ull << l) < d) ++l;
+    f.mul = (unsigned)(((1ull << 32) * ((1ull << l) - d)) / d + 1);
+    f.s1 = l < 1 ? l : 1;
+    f.s2 = l > 1 ? l - 1 : 0;
+    return f;
 }
 
 template <int BM, int BP, int WAVES_M, int WAVES_P>
-static hipError_t launch_cfg(const ConvArgs &a0, bool vec_in, hipStream_t st)
+static hipError_t launch_dlds(const ConvArgs &a0, int max_stages, hipStream_t st)
 {
     ConvArgs a = a0;
-    a.n_ct = (a.Cout + BM - 1) / BM;
-    const long long blocks = (long long)a.n_ct * ((a.M + BP - 1) / BP);
-    if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    if (vec_in)
-        hipLaunchKernelGGL((conv_igemm_kernel<BM, BP, WAVES_M, WAVES_P, true>), dim3((unsigned)blocks),
-                           dim3(256), 0, st, a);
+    if (!finish_args(a, BM, BP)) return hipErrorInvalidValue;
+    a.nstages = a.ksteps + 1 < max_stages ? a.ksteps + 1 : max_stages;
+    if (a.nstages < 2) a.nstages = 2;
+    a.div_howo = make_fast_div((unsigned)(a.Ho * a.Wo));
+    a.div_wo = make_fast_div((unsigned)a.Wo);
+    const size_t lds_bytes = (size_t)a.nstages * (BM + BP) * kStepK;
+    const bool pw = a.KH == 1 && a.KW == 1 && a.sh == 1 && a.sw == 1 && a.ph == 0 && a.pw == 0;
+    const dim3 grid(8u * a.per_xcd), block(256);
+    if (pw)
+        hipLaunchKernelGGL((conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 0>), grid, block, lds_bytes, st, a);
+    else if (a.Cin % 64 == 0 && a.KH * a.KW <= 32)
+        hipLaunchKernelGGL((conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 1>), grid, block, lds_bytes, st, a);
     else
-        hipLaunchKernelGGL((conv_igemm_kernel<BM, BP, WAVES_M, WAVES_P, false>), dim3((unsigned)blocks),
-                           dim3(256), 0, st, a);
+        hipLaunchKernelGGL((conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 2>), grid, block, lds_bytes, st, a);
+    return hipGetLastError();
+}
+
+template <int BM, int BP, int WAVES_M, int WAVES_P>
+static hipError_t launch_greg(const ConvArgs &a0, bool vec_in, hipStream_t st)
+{
+    ConvArgs a = a0;
+    if (!finish_args(a, BM, BP)) return hipErrorInvalidValue;
+    if (vec_in)
+        hipLaunchKernelGGL((conv_greg_kernel<BM, BP, WAVES_M, WAVES_P, true>), dim3(8u * a.per_xcd), dim3(256), 0,
+                           st, a);
+    else
+        hipLaunchKernelGGL((conv_greg_kernel<BM, BP, WAVES_M, WAVES_P, false>), dim3(8u * a.per_xcd), dim3(256), 0,
+                           st, a);
     return hipGetLastError();
 }
 
 hipError_t launch_conv(const ConvArgs &a, bool vec_in, hipStream_t st)
 {
-    if (a.Cout <= 32) return launch_cfg<32, 256, 1, 4>(a, vec_in, st);
-    if (a.Cout <= 64) return launch_cfg<64, 256, 1, 4>(a, vec_in, st);
-    return launch_cfg<128, 128, 2, 2>(a, vec_in, st);
+    // the direct-to-LDS kernel addresses x and the packed weights with 32-bit byte offsets
+    const bool direct = vec_in && a.in_xor == 0 && a.x_bytes < 0x7fffff00u && a.wp_bytes < 0x7fffff00u &&
+                        a.KH <= 31 && a.KW <= 31;
+    // wide tiles while they still give every CU a couple of workgroups, else narrower ones
+    const long long want = 512;
+    if (direct) {
+        if (a.Cout <= 32) return launch_dlds<32, 256, 1, 4>(a, 3, st);
+        if (a.Cout <= 64) {
+            if ((a.M + 255) / 256 >= want) return launch_dlds<64, 256, 1, 4>(a, 3, st);
+            return launch_dlds<64, 128, 1, 4>(a, 4, st);
+        }
+        const long long n_ct = (a.Cout + 127) / 128;
+        if (n_ct * ((a.M + 127) / 128) >= want) return launch_dlds<128, 128, 2, 2>(a, 4, st);
+        return launch_dlds<128, 64, 2, 2>(a, 4, st);
+    }
+    if (a.Cout <= 32) return launch_greg<32, 256, 1, 4>(a, vec_in, st);
+    if (a.Cout <= 64) return launch_greg<64, 256, 1, 4>(a, vec_in, st);
+    return launch_greg<128, 128, 2, 2>(a, vec_in, st);
 }
 
 // One thread per 16-byte piece of the packed weight format.

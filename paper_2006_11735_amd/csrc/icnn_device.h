@@ -21,6 +21,11 @@ constexpr int kStepK = 64;
 constexpr int kChunkBytes = 2048;
 constexpr int kCoutPad = 128;   // chunk count is padded so any cout tile can over-read
 
+// floor(n / d) by multiply-high: see fast_div()
+struct FastDiv {
+    unsigned mul, s1, s2;
+};
+
 struct ConvArgs {
     const uint8_t *x;
     const uint8_t *wp;
@@ -32,11 +37,23 @@ struct ConvArgs {
     int K;        // kh*kw*cin
     int ksteps;   // ceil(K / 64)
     int n_ct;     // cout tiles
+    int n_tiles;  // cout tiles x pixel tiles
+    int per_xcd;  // tiles handed to each of the 8 XCDs
+    unsigned x_bytes;     // extent of x the kernel may touch (direct-to-LDS kernel: < 2 GiB)
+    unsigned wp_bytes;    // extent of the packed weights
+    int nstages;          // LDS ring depth of the direct-to-LDS kernel
+    FastDiv div_howo, div_wo;
     int out_cs, out_co;
     int mul, shift, lo, hi, out_mode;
     int res_mode, res_dtype, res_cs, res_mul, res_shift;
     uint32_t in_xor;   // 0x80808080 when the input is a raw picture (x - 128), else 0
     int vec_out, vec_res;
+    int vec_bias; // bias is 16-byte aligned and cout % 16 == 0
+    int rq_fast;  // requantisation as one 32x32->64 multiply-add (mul_hi = mul << (32 - shift))
+    int mul_hi;
+    int res_fast; // 8-bit skip operand whose rescale fits 32 bits
+    int epi_vec;  // output (and skip operand) allow 16-byte accesses
+    int epi_mode; // 3 * RES + RQ of the vector epilogue
 };
 
 // [v / 2^s], round half up; arithmetic shift floors for negative values.
