@@ -25,6 +25,10 @@ bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 struct ConvGeom {
     int ho, wo, K, ksteps, chunks;
     long long M;
+    // small-cin layers (cin <= 4) run on a zero-bordered 4-channel copy of x in the workspace:
+    // rp = bytes of one kernel row there (kw * 4 rounded up to 16), hp x wp = its spatial size
+    int rp, hp, wp;
+    size_t ws_bytes;
 };
 
 int check_conv(const icnn_conv_desc *d, ConvGeom *g)
@@ -78,7 +82,19 @@ int check_conv(const icnn_conv_desc *d, ConvGeom *g)
         g->wo = wo;
         g->K = (int)K;
         g->M = M;
-        g->ksteps = (int)((K + kStepK - 1) / kStepK);
+        g->rp = g->hp = g->wp = 0;
+        g->ws_bytes = 0;
+        if (d->cin <= 4) {
+            g->rp = (d->kw * 4 + 15) / 16 * 16;
+            g->hp = d->h + 2 * d->pad_h;
+            const int need = (wo - 1) * d->stride_w + g->rp / 4;
+            g->wp = d->w + 2 * d->pad_w > need ? d->w + 2 * d->pad_w : need;
+            g->K = d->kh * g->rp;
+            const unsigned long long wsb = (unsigned long long)d->n * g->hp * g->wp * 4 + 64;
+            if (wsb > 0x7fffffffull) return fail(ICNN_E_SHAPE, "small-cin workspace of %llu bytes exceeds 2 GiB", wsb);
+            g->ws_bytes = (size_t)wsb;
+        }
+        g->ksteps = (g->K + kStepK - 1) / kStepK;
         g->chunks = ((d->cout + kCoutPad - 1) / kCoutPad) * (kCoutPad / kChunkCout);
     }
     return ICNN_OK;
@@ -122,10 +138,11 @@ int iconv2d_out_hw(const icnn_conv_desc *desc, int32_t *ho, int32_t *wo)
 
 int iconv2d_workspace_bytes(const icnn_conv_desc *desc, size_t *bytes)
 {
-    const int rc = check_conv(desc, nullptr);
+    ConvGeom g;
+    const int rc = check_conv(desc, &g);
     if (rc) return rc;
     if (!bytes) return fail(ICNN_E_NULL, "bytes is NULL");
-    *bytes = 0;
+    *bytes = g.ws_bytes;
     return ICNN_OK;
 }
 
@@ -146,18 +163,19 @@ int iconv2d_prepack_weights(const icnn_conv_desc *desc, const int8_t *w_ohwi, vo
     if (rc) return rc;
     if (!w_ohwi || !w_packed) return fail(ICNN_E_NULL, "weight pointer is NULL");
     if (!aligned16(w_packed)) return fail(ICNN_E_ALIGN, "w_packed must be 16-byte aligned");
-    return launched(launch_prepack(w_ohwi, (uint8_t *)w_packed, desc->cout, g.K, g.chunks, g.ksteps,
-                                   (hipStream_t)stream),
+    return launched(launch_prepack(w_ohwi, (uint8_t *)w_packed, desc->cout, g.K, g.chunks, g.ksteps, desc->kh,
+                                   desc->kw, desc->cin, g.rp, (hipStream_t)stream),
                     "prepack");
 }
 
 int iconv2d_brelu(const icnn_conv_desc *d, const void *x, const void *w_packed, const int32_t *bias,
                   const void *res, void *y, void *workspace, void *stream)
 {
-    (void)workspace;
     ConvGeom g;
     const int rc = check_conv(d, &g);
     if (rc) return rc;
+    if (g.ws_bytes && !workspace) return fail(ICNN_E_NULL, "this layer needs a workspace (iconv2d_workspace_bytes)");
+    if (g.ws_bytes && ((uintptr_t)workspace & 3)) return fail(ICNN_E_ALIGN, "workspace must be 4-byte aligned");
     if (!x || !w_packed || !bias || !y) return fail(ICNN_E_NULL, "x, w_packed, bias and y must not be NULL");
     if (d->res_mode != ICNN_RES_NONE && !res) return fail(ICNN_E_NULL, "res is NULL but res_mode is set");
     if (!aligned16(w_packed)) return fail(ICNN_E_ALIGN, "w_packed must be 16-byte aligned");
@@ -222,8 +240,20 @@ int iconv2d_brelu(const icnn_conv_desc *d, const void *x, const void *w_packed, 
         const int rq_kind = d->out_mode == ICNN_OUT_RAW_S32 ? 0 : (a.rq_fast ? 1 : 2);
         a.epi_mode = 3 * res_kind + rq_kind;
     }
+    if (g.rp) {
+        // small cin: pad and re-normalise x into the workspace, then run the layer as a kh x 1
+        // convolution with "rp channels" over that copy (see pad_small_cin_kernel)
+        const hipError_t e = launch_pad_small_cin(a.x, workspace, d->n, d->h, d->w, d->cin, d->in_c_stride, d->pad_h,
+                                                  d->pad_w, g.hp, g.wp, a.in_xor, (hipStream_t)stream);
+        if (e != hipSuccess) return launched(e, "iconv2d_brelu (input padding)");
+        a.x = (const uint8_t *)workspace;
+        a.H = g.hp; a.W = g.wp; a.Cin = g.rp; a.in_cs = 4; a.KW = 1; a.ph = 0; a.pw = 0;
+        a.in_xor = 0;
+        a.x_bytes = (unsigned)(g.ws_bytes - 64);
+        return launched(launch_conv(a, true, false, (hipStream_t)stream), "iconv2d_brelu");
+    }
     const bool vec_in = aligned16(x) && d->cin % 16 == 0 && d->in_c_stride % 16 == 0;
-    return launched(launch_conv(a, vec_in, (hipStream_t)stream), "iconv2d_brelu");
+    return launched(launch_conv(a, vec_in, vec_in, (hipStream_t)stream), "iconv2d_brelu");
 }
 
 int iadd_rescale(const icnn_add_desc *d, const void *a, const void *b, void *out, void *stream)

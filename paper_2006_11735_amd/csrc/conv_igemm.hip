@@ -21,6 +21,8 @@
 
 namespace icnn {
 
+typedef int v4i_a4 __attribute__((ext_vector_type(4), aligned(4)));   // 16-byte load, dword aligned
+
 // LDS tile layout of one K step (both kernels):
 //   A (weights): BM*64 bytes in packed-fragment order, i.e. a straight copy of
 //      BM/32 consecutive 2 KiB chunks of the packed weights.
@@ -490,7 +492,7 @@ __global__ __launch_bounds__(256) void conv_greg_kernel(const ConvArgs a)
                 const int hi = hi0[j] + kh, wi = wi0[j] + kw;
                 const bool ok = pv[j] && kh < a.KH && (unsigned)hi < (unsigned)a.H && (unsigned)wi < (unsigned)a.W;
                 const size_t off = ok ? ((size_t)(nrow[j] + hi) * a.W + wi) * a.in_cs + ci : 0;
-                breg[j] = *(const v4i *)(a.x + off);
+                breg[j] = *(const v4i_a4 *)(a.x + off);
                 bok[j] = ok;
             }
             ci += kStepK;
@@ -638,10 +640,10 @@ static hipError_t launch_greg(const ConvArgs &a0, bool vec_in, hipStream_t st)
     return hipGetLastError();
 }
 
-hipError_t launch_conv(const ConvArgs &a, bool vec_in, hipStream_t st)
+hipError_t launch_conv(const ConvArgs &a, bool vec_in, bool direct_ok, hipStream_t st)
 {
     // the direct-to-LDS kernel addresses x and the packed weights with 32-bit byte offsets
-    const bool direct = vec_in && a.in_xor == 0 && a.x_bytes < 0x7fffff00u && a.wp_bytes < 0x7fffff00u &&
+    const bool direct = direct_ok && a.in_xor == 0 && a.x_bytes < 0x7fffff00u && a.wp_bytes < 0x7fffff00u &&
                         a.KH <= 31 && a.KW <= 31;
     // wide tiles while they still give every CU a couple of workgroups, else narrower ones
     const long long want = 512;
@@ -660,9 +662,11 @@ hipError_t launch_conv(const ConvArgs &a, bool vec_in, hipStream_t st)
     return launch_greg<128, 128, 2, 2>(a, vec_in, st);
 }
 
-// One thread per 16-byte piece of the packed weight format.
+// One thread per 16-byte piece of the packed weight format.  rp == 0: K index k is
+// (kh, kw, ci) in that order.  rp > 0 (small-cin layout): k = kh * rp + kw * 4 + c with
+// channels padded to 4 and each kernel row padded to rp bytes; padding weights are 0.
 __global__ void prepack_kernel(const int8_t *__restrict__ w, uint8_t *__restrict__ wp, int Cout, int K,
-                               int ksteps, long long pieces)
+                               int ksteps, long long pieces, int KH, int KW, int Cin, int rp)
 {
     const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= pieces) return;
@@ -678,18 +682,57 @@ __global__ void prepack_kernel(const int8_t *__restrict__ w, uint8_t *__restrict
     if (co < Cout) {
         for (int b = 0; b < 16; ++b) {
             const int k = k0 + b;
-            if (k < K) wd[b >> 2] |= (uint32_t)(uint8_t)w[(size_t)co * K + k] << ((b & 3) * 8);
+            int v = 0;
+            if (rp == 0) {
+                if (k < K) v = (uint8_t)w[(size_t)co * K + k];
+            } else {
+                const int kh = k / rp, rem = k - kh * rp;
+                const int kw = rem >> 2, c = rem & 3;
+                if (kh < KH && kw < KW && c < Cin) v = (uint8_t)w[(((size_t)co * KH + kh) * KW + kw) * Cin + c];
+            }
+            wd[b >> 2] |= (uint32_t)v << ((b & 3) * 8);
         }
     }
     *(v4i *)(wp + e * 16) = v4i{(int)wd[0], (int)wd[1], (int)wd[2], (int)wd[3]};
 }
 
-hipError_t launch_prepack(const int8_t *w, uint8_t *wp, int Cout, int K, int chunks, int ksteps,
-                          hipStream_t st)
+hipError_t launch_prepack(const int8_t *w, uint8_t *wp, int Cout, int K, int chunks, int ksteps, int KH, int KW,
+                          int Cin, int rp, hipStream_t st)
 {
     const long long pieces = (long long)chunks * ksteps * 128;
     const unsigned blocks = (unsigned)((pieces + 255) / 256);
-    hipLaunchKernelGGL(prepack_kernel, dim3(blocks), dim3(256), 0, st, w, wp, Cout, K, ksteps, pieces);
+    hipLaunchKernelGGL(prepack_kernel, dim3(blocks), dim3(256), 0, st, w, wp, Cout, K, ksteps, pieces, KH, KW, Cin, rp);
+    return hipGetLastError();
+}
+
+// Small-cin layers (cin <= 4: pictures): copies x into a zero-bordered tensor with 4 channels
+// per pixel, [n][hp][wp][4] int8, applying the raw picture's "- 128" on the way.  The conv
+// then reads 16 contiguous bytes (4 taps x 4 channels) with no bounds checks.
+__global__ __launch_bounds__(256) void pad_small_cin_kernel(const uint8_t *__restrict__ x, uint32_t *__restrict__ out,
+                                                            long long total, int H, int W, int Cin, int in_cs, int ph,
+                                                            int pw, int Hp, int Wp, uint32_t in_xor)
+{
+    const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const int xp = (int)(e % Wp);
+    const long long t = e / Wp;
+    const int yp = (int)(t % Hp);
+    const long long n = t / Hp;
+    const int hi = yp - ph, wi = xp - pw;
+    uint32_t v = 0;
+    if ((unsigned)hi < (unsigned)H && (unsigned)wi < (unsigned)W) {
+        const uint8_t *p = x + (((size_t)n * H + hi) * W + wi) * in_cs;
+        for (int c = 0; c < Cin; ++c) v |= ((uint32_t)p[c] ^ (in_xor & 0xffu)) << (8 * c);
+    }
+    out[e] = v;
+}
+
+hipError_t launch_pad_small_cin(const uint8_t *x, void *out, int N, int H, int W, int Cin, int in_cs, int ph, int pw,
+                                int Hp, int Wp, uint32_t in_xor, hipStream_t st)
+{
+    const long long total = (long long)N * Hp * Wp;
+    hipLaunchKernelGGL(pad_small_cin_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, x, (uint32_t *)out,
+                       total, H, W, Cin, in_cs, ph, pw, Hp, Wp, in_xor);
     return hipGetLastError();
 }
 

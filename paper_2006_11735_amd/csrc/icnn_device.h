@@ -80,9 +80,12 @@ __device__ __forceinline__ int load_elem(const void *p, size_t i, int dtype)
 }
 
 // launchers (host)
-hipError_t launch_conv(const ConvArgs &a, bool vec_in, hipStream_t st);
-hipError_t launch_prepack(const int8_t *w, uint8_t *wp, int Cout, int K, int chunks, int ksteps,
-                          hipStream_t st);
+// vec_in: 16-byte pieces of x never straddle a tap (dword aligned); direct_ok: they are also 16-byte aligned
+hipError_t launch_conv(const ConvArgs &a, bool vec_in, bool direct_ok, hipStream_t st);
+hipError_t launch_prepack(const int8_t *w, uint8_t *wp, int Cout, int K, int chunks, int ksteps, int KH, int KW,
+                          int Cin, int rp, hipStream_t st);
+hipError_t launch_pad_small_cin(const uint8_t *x, void *out, int N, int H, int W, int Cin, int in_cs, int ph, int pw,
+                                int Hp, int Wp, uint32_t in_xor, hipStream_t st);
 
 struct AddArgs {
     const void *a;

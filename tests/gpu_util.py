@@ -52,8 +52,10 @@ def gpu_conv2d(x, w, bias, *, stride=1, pad=0, mul=1, shift=0, bound_q=127, lo=0
     wp = torch.zeros(B.iconv2d_packed_weight_bytes(d), dtype=torch.uint8, device=DEV)
     B.iconv2d_prepack_weights(d, wd, wp)
     bd = dev(bias.astype(np.int32))
+    ws_bytes = B.iconv2d_workspace_bytes(d)
+    ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=DEV) if ws_bytes else None
     B.iconv2d_brelu(d, xd.data_ptr() + misalign, wp, bd, None if rd is None else rd.data_ptr() + misalign,
-                    od.data_ptr() + misalign, None)
+                    od.data_ptr() + misalign, ws)
     torch.cuda.synchronize()
     raw = od.cpu().numpy()
     # guard bytes before and after the output must be untouched
