@@ -19,6 +19,8 @@
 //                     through registers (double-buffered LDS).
 #include "icnn_device.h"
 
+#include <cstdlib>
+
 namespace icnn {
 
 typedef int v4i_a4 __attribute__((ext_vector_type(4), aligned(4)));   // 16-byte load, dword aligned
@@ -191,29 +193,37 @@ __device__ __forceinline__ bool tile_of_block(const ConvArgs &a, int &ct, int &p
     return true;
 }
 
-// Accumulators start at the bias: register r of a lane in half h of tile row i holds
-// channel co_base + 32*i + 16*h + r (for every pixel tile j).
-template <int TM, int TP>
-__device__ __forceinline__ void init_acc_with_bias(const ConvArgs &a, int co_base, int half, v16i (&acc)[TM][TP])
+// Bias of the channels a lane owns: register r of a lane in half h of tile row i holds
+// channel co_base + 32*i + 16*h + r.  Accumulators start at these values.
+template <int TM>
+__device__ __forceinline__ void load_bias_rows(const ConvArgs &a, int co_base, int half, v16i (&b)[TM])
 {
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int co0 = co_base + i * 32 + half * 16;
-        v16i b;
         if (a.vec_bias) {
-            const v4i *bp = (const v4i *)(a.bias + min(co0, a.Cout - 16));
+            const v4i *bp = (const v4i *)(a.bias + max(0, min(co0, a.Cout - 16)));
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const v4i v = bp[q];
-                b[4 * q] = v.x; b[4 * q + 1] = v.y; b[4 * q + 2] = v.z; b[4 * q + 3] = v.w;
+                b[i][4 * q] = v.x; b[i][4 * q + 1] = v.y; b[i][4 * q + 2] = v.z; b[i][4 * q + 3] = v.w;
             }
         } else {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) b[r] = a.bias[min(co0 + r, a.Cout - 1)];
+            for (int r = 0; r < 16; ++r) b[i][r] = a.bias[min(co0 + r, a.Cout - 1)];
         }
-#pragma unroll
-        for (int j = 0; j < TP; ++j) acc[i][j] = b;
     }
+}
+
+template <int TM, int TP>
+__device__ __forceinline__ void init_acc_with_bias(const ConvArgs &a, int co_base, int half, v16i (&acc)[TM][TP])
+{
+    v16i b[TM];
+    load_bias_rows<TM>(a, co_base, half, b);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TP; ++j) acc[i][j] = b[i];
 }
 
 #define ICNN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | 0x0F70 | (((n) >> 4) << 14))
@@ -237,7 +247,7 @@ __device__ __forceinline__ int fast_div(int n, const FastDiv &d)
 //         position is wave-uniform (scalar registers, one bit test per copy);
 // MODE 2: any cin % 16 == 0: every lane tracks the tap of its own 16-byte slot.
 template <int BM, int BP, int WAVES_M, int WAVES_P, int MODE>
-__global__ __launch_bounds__(256, 2) void conv_dlds_kernel(const ConvArgs a)
+__global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void conv_dlds_kernel(const ConvArgs a)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the buffer-resource type exists in the device pass only
     constexpr int TM = BM / WAVES_M / 32;
@@ -254,32 +264,35 @@ __global__ __launch_bounds__(256, 2) void conv_dlds_kernel(const ConvArgs a)
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];   // nstages * STAGE bytes
 
+    // Persistent workgroups: this one handles tiles v = blockIdx.x, + gridDim.x, ...  (gridDim.x is a
+    // multiple of 8, so all of them map to the same XCD, see tile_of()).
+    int vtile = blockIdx.x;
     int ct, pt;
-    if (!tile_of_block(a, ct, pt)) return;
+    {
+        // XCD x owns the contiguous tile range [x*per_xcd, (x+1)*per_xcd); only its tail can be padding
+        const int logical = (vtile & 7) * a.per_xcd + (vtile >> 3);
+        if (logical >= a.n_tiles) return;
+    }
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int wm = wave % WAVES_M;
     const int wp = wave / WAVES_M;
-    const int pix0 = pt * BP;
-    const int chunk0 = ct * (BM / 32);
     const int nstages = a.nstages;
+    const int ksteps = a.ksteps;
+    const int depth = min(nstages - 1, ksteps);      // stages of a tile issued ahead of its K loop
 
     const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, a.x_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)a.wp, 0, a.wp_bytes, 0x00020000);
 
+    // ---- state of the tile whose stages are being issued ("load side")
     // A copy q of this wave covers packed pieces [64*m, 64*m + 64), m = (4*q + wave) % A_INSTR;
     // its byte offset at K step s is a_off[q] + s * 2048
     unsigned a_off[NA];
     int a_lds[NA];
 #pragma unroll
-    for (int q = 0; q < NA; ++q) {
-        const int m = (4 * q + wave) % A_INSTR;
-        const int e = m * 64 + lane;
-        a_off[q] = (unsigned)(chunk0 + (e >> 7)) * (unsigned)a.ksteps * kChunkBytes + (unsigned)(e & 127) * 16;
-        a_lds[q] = m * 1024;
-    }
+    for (int q = 0; q < NA; ++q) a_lds[q] = ((4 * q + wave) % A_INSTR) * 1024;
     // B copy j of this wave covers rows 16*(4*j + wave) .. +16 of the tile; this lane fills physical
     // slot lane & 3 of row 16*(4*j + wave) + (lane >> 2), i.e. logical slot ls (same for every j)
     const int ls = (lane & 3) ^ ((lane >> 4) & 3);
@@ -287,84 +300,104 @@ __global__ __launch_bounds__(256, 2) void conv_dlds_kernel(const ConvArgs a)
     unsigned tapmask[NB];    // MODE 1: bit kh*KW + kw set when that tap lies inside the image
     unsigned rowmask[NB];    // MODE 2: bit kh set when the input row of tap kh lies inside the image
     unsigned colmask[NB];    // MODE 2: bit kw likewise for columns
-#pragma unroll
-    for (int j = 0; j < NB; ++j) {
-        const int p = pix0 + 16 * (4 * j + wave) + (lane >> 2);
-        const bool pv = p < a.M;
-        tapmask[j] = rowmask[j] = colmask[j] = 0;
-        if (MODE == 0) {
-            b_off[j] = pv ? (unsigned)p * (unsigned)a.in_cs + ls * 16 : OOB;
-        } else {
-            const int pc = pv ? p : 0;
-            const int n = fast_div(pc, a.div_howo);
-            const int r = pc - n * a.Ho * a.Wo;
-            const int ho = fast_div(r, a.div_wo);
-            const int wo = r - ho * a.Wo;
-            const int hi0 = ho * a.sh - a.ph, wi0 = wo * a.sw - a.pw;
-            // may be "negative" (wraps): only used together with a tap that is inside the image
-            b_off[j] = (unsigned)(((n * a.H + hi0) * a.W + wi0) * a.in_cs) + (MODE == 1 ? ls * 16 : 0);
-            unsigned rm = 0, cm = 0;
-            for (int k = 0; k < a.KH; ++k) rm |= (unsigned)((unsigned)(hi0 + k) < (unsigned)a.H) << k;
-            for (int k = 0; k < a.KW; ++k) cm |= (unsigned)((unsigned)(wi0 + k) < (unsigned)a.W) << k;
-            if (!pv) rm = 0;
-            if (MODE == 1) {
-                unsigned tmk = 0;
-                for (int k = 0; k < a.KH; ++k) tmk |= ((rm >> k) & 1u ? cm : 0u) << (k * a.KW);
-                tapmask[j] = tmk;
-            } else {
-                rowmask[j] = rm;
-                colmask[j] = cm;
-            }
-        }
-    }
     // K-axis position: MODE 1 wave-uniform (skh, skw, sc0 = first channel of the step);
     // MODE 2 per lane (kh, kw, ci of the lane's slot)
     int skh = 0, skw = 0, sc0 = 0;
-    int kh = 0, kw = 0, ci = ls * 16;
+    int kh = 0, kw = 0, ci = 0;
+    int kh_init = 0, kw_init = 0, ci_init = ls * 16;
     if (MODE == 2) {
-        const int tap = ci / a.Cin;
-        ci -= tap * a.Cin;
-        kh = tap / a.KW;
-        kw = tap - kh * a.KW;
+        const int tap = ci_init / a.Cin;
+        ci_init -= tap * a.Cin;
+        kh_init = tap / a.KW;
+        kw_init = tap - kh_init * a.KW;
     }
 
-    auto issue_stage = [&](int s, int buf) {
-        uint8_t *stage = lds + buf * STAGE;
+    auto tile_of = [&](int v, int &ct, int &pt) {
+        // workgroups are dealt round-robin to the 8 XCDs; XCD x owns tiles [x*per_xcd, (x+1)*per_xcd)
+        const int logical = (v & 7) * a.per_xcd + (v >> 3);
+        ct = logical % a.n_ct;
+        pt = logical / a.n_ct;
+        return logical < a.n_tiles;
+    };
+
+    auto setup_load_side = [&](int ct, int pt) {
+        const int pix0 = pt * BP;
+        const int chunk0 = ct * (BM / 32);
 #pragma unroll
-        for (int q = 0; q < NA; ++q)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, (__attribute__((address_space(3))) void *)(stage + a_lds[q]),
-                                                     16, a_off[q], s * kChunkBytes, 0, 0);
+        for (int q = 0; q < NA; ++q) {
+            const int e = a_lds[q] / 16 + lane;
+            a_off[q] = (unsigned)(chunk0 + (e >> 7)) * (unsigned)ksteps * kChunkBytes + (unsigned)(e & 127) * 16;
+        }
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const int p = pix0 + 16 * (4 * j + wave) + (lane >> 2);
+            const bool pv = p < a.M;
+            tapmask[j] = rowmask[j] = colmask[j] = 0;
+            if (MODE == 0) {
+                b_off[j] = pv ? (unsigned)p * (unsigned)a.in_cs + ls * 16 : OOB;
+            } else {
+                const int pc = pv ? p : 0;
+                const int n = fast_div(pc, a.div_howo);
+                const int r = pc - n * a.Ho * a.Wo;
+                const int ho = fast_div(r, a.div_wo);
+                const int wo = r - ho * a.Wo;
+                const int hi0 = ho * a.sh - a.ph, wi0 = wo * a.sw - a.pw;
+                // may be "negative" (wraps): only used together with a tap that is inside the image
+                b_off[j] = (unsigned)(((n * a.H + hi0) * a.W + wi0) * a.in_cs) + (MODE == 1 ? ls * 16 : 0);
+                unsigned rm = 0, cm = 0;
+                for (int k = 0; k < a.KH; ++k) rm |= (unsigned)((unsigned)(hi0 + k) < (unsigned)a.H) << k;
+                for (int k = 0; k < a.KW; ++k) cm |= (unsigned)((unsigned)(wi0 + k) < (unsigned)a.W) << k;
+                if (!pv) rm = 0;
+                if (MODE == 1) {
+                    unsigned tmk = 0;
+                    for (int k = 0; k < a.KH; ++k) tmk |= ((rm >> k) & 1u ? cm : 0u) << (k * a.KW);
+                    tapmask[j] = tmk;
+                } else {
+                    rowmask[j] = rm;
+                    colmask[j] = cm;
+                }
+            }
+        }
+        skh = skw = sc0 = 0;
+        kh = kh_init; kw = kw_init; ci = ci_init;
+    };
+
+    // One stage = LPS wave-wide copies.  issue_copy(c, ...) issues copy c (A copies first, then B),
+    // advance_k() moves the K-axis position to the next stage; issue_stage() does a whole stage.
+    auto issue_copy = [&](int c, int s, uint8_t *stage) {
+        if (c < NA) {
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, (__attribute__((address_space(3))) void *)(stage + a_lds[c]),
+                                                     16, a_off[c], s * kChunkBytes, 0, 0);
+            return;
+        }
+        const int j = c - NA;
+        uint8_t *dst = stage + A_BYTES + (4 * j + wave) * 1024;
         if (MODE == 0) {
             const bool kok = s * kStepK + ls * 16 < a.Cin;
-#pragma unroll
-            for (int j = 0; j < NB; ++j)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                    rs_x, (__attribute__((address_space(3))) void *)(stage + A_BYTES + (4 * j + wave) * 1024), 16,
-                    kok ? b_off[j] : OOB, s * kStepK, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (__attribute__((address_space(3))) void *)dst, 16,
+                                                     kok ? b_off[j] : OOB, s * kStepK, 0, 0);
         } else if (MODE == 1) {
             const unsigned bit = 1u << (skh * a.KW + skw);
             // added per lane (not as the scalar offset): b_off may have wrapped below zero and the
             // buffer unit range-checks the vector offset alone
             const unsigned soff = (unsigned)((skh * a.W + skw) * a.in_cs + sc0);
-#pragma unroll
-            for (int j = 0; j < NB; ++j)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                    rs_x, (__attribute__((address_space(3))) void *)(stage + A_BYTES + (4 * j + wave) * 1024), 16,
-                    (tapmask[j] & bit) ? b_off[j] + soff : OOB, 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (__attribute__((address_space(3))) void *)dst, 16,
+                                                     (tapmask[j] & bit) ? b_off[j] + soff : OOB, 0, 0, 0);
+        } else {
+            const unsigned tapoff = (unsigned)((kh * a.W + kw) * a.in_cs + ci);
+            const bool ok = ((rowmask[j] >> kh) & (colmask[j] >> kw) & 1u) != 0;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (__attribute__((address_space(3))) void *)dst, 16,
+                                                     ok ? b_off[j] + tapoff : OOB, 0, 0, 0);
+        }
+    };
+    auto advance_k = [&]() {
+        if (MODE == 1) {
             sc0 += kStepK;
             if (sc0 == a.Cin) {
                 sc0 = 0;
                 if (++skw == a.KW) { skw = 0; ++skh; }
             }
-        } else {
-            const unsigned tapoff = (unsigned)((kh * a.W + kw) * a.in_cs + ci);
-#pragma unroll
-            for (int j = 0; j < NB; ++j) {
-                const bool ok = ((rowmask[j] >> kh) & (colmask[j] >> kw) & 1u) != 0;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                    rs_x, (__attribute__((address_space(3))) void *)(stage + A_BYTES + (4 * j + wave) * 1024), 16,
-                    ok ? b_off[j] + tapoff : OOB, 0, 0, 0);
-            }
+        } else if (MODE == 2) {
             ci += kStepK;
             while (ci >= a.Cin) {
                 ci -= a.Cin;
@@ -372,51 +405,105 @@ __global__ __launch_bounds__(256, 2) void conv_dlds_kernel(const ConvArgs a)
             }
         }
     };
-
-    v16i acc[TM][TP];
-    init_acc_with_bias<TM, TP>(a, ct * BM + wm * TM * 32, lane >> 5, acc);
-
-    const int ksteps = a.ksteps;
-    for (int s = 0; s < nstages - 1; ++s) issue_stage(s, s);   // the host keeps nstages - 1 <= ksteps
+    auto issue_stage = [&](int s, int buf) {
+        uint8_t *stage = lds + buf * STAGE;
+#pragma unroll
+        for (int c = 0; c < LPS; ++c) issue_copy(c, s, stage);
+        advance_k();
+    };
 
     // fragment read addresses inside a stage (A: straight; B: swizzled rows, one base per k half)
     const int a_rd = wm * TM * 2048 + lane * 16;
     const int b_rd0 = A_BYTES + b_slot_offset(wp * TP * 32 + (lane & 31), (lane >> 5));
     const int b_rd1 = A_BYTES + b_slot_offset(wp * TP * 32 + (lane & 31), 2 + (lane >> 5));
 
-    int buf = 0;
-    for (int s = 0; s < ksteps; ++s) {
-        // stage s has landed once at most `later` younger stages' copies remain in flight
-        const int later = min(nstages - 2, ksteps - 1 - s);
-        asm volatile("" ::: "memory");
-        if (later >= 2) ICNN_WAIT_VMCNT(2 * LPS);
-        else if (later == 1) ICNN_WAIT_VMCNT(LPS);
-        else ICNN_WAIT_VMCNT(0);
-        __builtin_amdgcn_s_barrier();      // every wave's part of stage s is in LDS; stage s-1 is drained
-        asm volatile("" ::: "memory");
-        if (s + nstages - 1 < ksteps) {
-            int nb = buf + nstages - 1;
-            if (nb >= nstages) nb -= nstages;
-            issue_stage(s + nstages - 1, nb);
-        }
-        const uint8_t *S = lds + buf * STAGE;
-#pragma unroll
-        for (int kq = 0; kq < 2; ++kq) {
-            v4i af[TM], bf[TP];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) af[i] = *(const v4i *)(S + a_rd + (i * 2 + kq) * 1024);
-#pragma unroll
-            for (int j = 0; j < TP; ++j) bf[j] = *(const v4i *)(S + (kq ? b_rd1 : b_rd0) + j * 2048);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TP; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
-        }
-        if (++buf == nstages) buf = 0;
+    // ---- first tile: its leading stages and its bias
+    tile_of(vtile, ct, pt);
+    setup_load_side(ct, pt);
+    int buf = 0;        // ring slot of the next K step to compute
+    int ibuf = 0;       // ring slot the next issued stage goes to
+    for (int s = 0; s < depth; ++s) {
+        issue_stage(s, ibuf);
+        if (++ibuf == nstages) ibuf = 0;
     }
+    v16i bias_next[TM];
+    load_bias_rows<TM>(a, ct * BM + wm * TM * 32, lane >> 5, bias_next);
 
-    epilogue_tiles<TM, TP>(a, acc, ct * BM + wm * TM * 32, pix0 + wp * TP * 32, lane);
+    for (;;) {
+        v16i acc[TM][TP];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TP; ++j) acc[i][j] = bias_next[i];
+
+        for (int s = 0; s < ksteps; ++s) {
+            // stage s has landed once at most `later` younger stages' copies remain in flight
+            const int later = min(depth - 1, ksteps - 1 - s);
+            asm volatile("" ::: "memory");
+            if (later >= 2) ICNN_WAIT_VMCNT(2 * LPS);
+            else if (later == 1) ICNN_WAIT_VMCNT(LPS);
+            else ICNN_WAIT_VMCNT(0);
+            __builtin_amdgcn_s_barrier();  // every wave's part of stage s is in LDS; the slot of step s-1 is drained
+            asm volatile("" ::: "memory");
+            // the copies of stage s + depth are issued between this step's MFMAs, so the matrix
+            // cores work while the wave computes addresses and the memory pipeline accepts them
+            const bool feed = s + depth < ksteps;
+            uint8_t *istage = lds + ibuf * STAGE;
+            const uint8_t *S = lds + buf * STAGE;
+            v4i af[2][TM], bf[2][TP];
+#pragma unroll
+            for (int kq = 0; kq < 2; ++kq) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) af[kq][i] = *(const v4i *)(S + a_rd + (i * 2 + kq) * 1024);
+#pragma unroll
+                for (int j = 0; j < TP; ++j) bf[kq][j] = *(const v4i *)(S + (kq ? b_rd1 : b_rd0) + j * 2048);
+            }
+            int c = 0;
+#pragma unroll
+            for (int kq = 0; kq < 2; ++kq)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TP; ++j) {
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[kq][i], bf[kq][j], acc[i][j], 0, 0, 0);
+                        if (c < LPS) {
+                            if (feed) issue_copy(c, s + depth, istage);
+                            ++c;
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    }
+#pragma unroll
+            for (int cc = 2 * TM * TP; cc < LPS; ++cc)     // narrow tiles: more copies than MFMAs
+                if (feed) issue_copy(cc, s + depth, istage);
+            if (feed) {
+                advance_k();
+                if (++ibuf == nstages) ibuf = 0;
+            }
+            if (++buf == nstages) buf = 0;
+        }
+
+        // ---- the next tile's leading stages and bias travel while this tile's epilogue runs.
+        // They go to ring slots other than the one of the last K step, which slower waves may
+        // still be reading (every wave has passed that step's barrier, so all older slots are free).
+        const int co_wave = ct * BM + wm * TM * 32;
+        const int pix_wave = pt * BP + wp * TP * 32;
+        vtile += gridDim.x;
+        const bool more = vtile < a.n_vtiles && tile_of(vtile, ct, pt);
+        if (more) {
+            setup_load_side(ct, pt);
+            for (int s = 0; s < depth; ++s) {
+                issue_stage(s, ibuf);
+                if (++ibuf == nstages) ibuf = 0;
+            }
+            load_bias_rows<TM>(a, ct * BM + wm * TM * 32, lane >> 5, bias_next);
+        }
+        epilogue_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane);
+        if (!more) break;
+        // Stores and loads retire out of order with respect to each other, so the counted waits of
+        // the next K loop are only valid once this tile's stores have drained.
+        asm volatile("" ::: "memory");
+        ICNN_WAIT_VMCNT(0);
+    }
 #endif
 }
 
@@ -606,24 +693,39 @@ static FastDiv make_fast_div(unsigned d)
 }
 
 template <int BM, int BP, int WAVES_M, int WAVES_P>
-static hipError_t launch_dlds(const ConvArgs &a0, int max_stages, hipStream_t st)
+static hipError_t launch_dlds(const ConvArgs &a0, int max_stages, int per_cu, hipStream_t st)
 {
     ConvArgs a = a0;
     if (!finish_args(a, BM, BP)) return hipErrorInvalidValue;
+    if (const char *e = getenv("ICNN_STAGES")) max_stages = atoi(e);   // tuning aid
     a.nstages = a.ksteps + 1 < max_stages ? a.ksteps + 1 : max_stages;
     if (a.nstages < 2) a.nstages = 2;
     a.div_howo = make_fast_div((unsigned)(a.Ho * a.Wo));
     a.div_wo = make_fast_div((unsigned)a.Wo);
     const size_t lds_bytes = (size_t)a.nstages * (BM + BP) * kStepK;
     const bool pw = a.KH == 1 && a.KW == 1 && a.sh == 1 && a.sw == 1 && a.ph == 0 && a.pw == 0;
-    const dim3 grid(8u * a.per_xcd), block(256);
-    if (pw)
-        hipLaunchKernelGGL((conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 0>), grid, block, lds_bytes, st, a);
-    else if (a.Cin % 64 == 0 && a.KH * a.KW <= 32)
-        hipLaunchKernelGGL((conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 1>), grid, block, lds_bytes, st, a);
-    else
-        hipLaunchKernelGGL((conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 2>), grid, block, lds_bytes, st, a);
-    return hipGetLastError();
+    const int mode = pw ? 0 : (a.Cin % 64 == 0 && a.KH * a.KW <= 32 ? 1 : 2);
+    // persistent workgroups: as many as fit on the chip at once (a multiple of 8, one share per XCD)
+    a.n_vtiles = 8 * a.per_xcd;
+    const int slots = 256 * per_cu;
+    const dim3 grid((unsigned)(a.n_vtiles < slots ? a.n_vtiles : slots)), block(256);
+    auto go = [&](auto kernel) -> hipError_t {
+        if (lds_bytes > 64 * 1024) {
+            // more than 64 KiB of dynamic LDS has to be allowed once per kernel
+            static bool raised = false;
+            if (!raised) {
+                const hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                         160 * 1024);
+                if (e != hipSuccess) return e;
+                raised = true;
+            }
+        }
+        hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, a);
+        return hipGetLastError();
+    };
+    if (mode == 0) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 0>);
+    if (mode == 1) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 1>);
+    return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 2>);
 }
 
 template <int BM, int BP, int WAVES_M, int WAVES_P>
@@ -640,22 +742,59 @@ static hipError_t launch_greg(const ConvArgs &a0, bool vec_in, hipStream_t st)
     return hipGetLastError();
 }
 
+// Tile shapes of the direct-to-LDS kernel: {cout tile, pixel tile, LDS stages, workgroups per CU}
+struct TileCfg {
+    int bm, bp, stages, per_cu;
+};
+static const TileCfg kTiles[] = {
+    {32, 256, 3, 2}, {64, 128, 4, 2}, {64, 256, 3, 2}, {128, 64, 4, 2}, {128, 128, 4, 2},
+};
+constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
+
+static hipError_t launch_tile(int t, const ConvArgs &a, hipStream_t st)
+{
+    switch (t) {
+    case 0: return launch_dlds<32, 256, 1, 4>(a, kTiles[0].stages, kTiles[0].per_cu, st);
+    case 1: return launch_dlds<64, 128, 1, 4>(a, kTiles[1].stages, kTiles[1].per_cu, st);
+    case 2: return launch_dlds<64, 256, 1, 4>(a, kTiles[2].stages, kTiles[2].per_cu, st);
+    case 3: return launch_dlds<128, 64, 2, 2>(a, kTiles[3].stages, kTiles[3].per_cu, st);
+    default: return launch_dlds<128, 128, 2, 2>(a, kTiles[4].stages, kTiles[4].per_cu, st);
+    }
+}
+
+// Estimated cycles of a launch with tile t: rounds of resident workgroups times the
+// time of one workgroup, whose K loop is bound either by the matrix cores or by
+// the L2 -> LDS traffic of its tiles (bytes per step = 64 * (bm + bp)).
+static double tile_cost(const TileCfg &c, const ConvArgs &a)
+{
+    const double tiles = (double)((a.Cout + c.bm - 1) / c.bm) * (double)((a.M + c.bp - 1) / c.bp);
+    const double slots = 256.0 * c.per_cu;
+    const double rounds = (double)(long long)((tiles + slots - 1) / slots);
+    const double resident = tiles < slots ? (tiles / 256.0 > 1 ? tiles / 256.0 : 1) : c.per_cu;   // per CU
+    const double mfma = (c.bm / 32) * (c.bp / 32) * 2 * 32.0 / 4;          // cycles per step if alone on the CU
+    const double l2 = 64.0 * (c.bm + c.bp) / 24.0;                         // at ~24 B/clk/CU from L2
+    const double step = resident * (mfma > l2 ? mfma : l2) + 150;
+    const double fixed = 2500 + 1.5 * c.bm * c.bp / 256 * 6;               // prologue + epilogue
+    return rounds * (a.ksteps * step + fixed);
+}
+
 hipError_t launch_conv(const ConvArgs &a, bool vec_in, bool direct_ok, hipStream_t st)
 {
     // the direct-to-LDS kernel addresses x and the packed weights with 32-bit byte offsets
     const bool direct = direct_ok && a.in_xor == 0 && a.x_bytes < 0x7fffff00u && a.wp_bytes < 0x7fffff00u &&
                         a.KH <= 31 && a.KW <= 31;
-    // wide tiles while they still give every CU a couple of workgroups, else narrower ones
-    const long long want = 512;
     if (direct) {
-        if (a.Cout <= 32) return launch_dlds<32, 256, 1, 4>(a, 3, st);
-        if (a.Cout <= 64) {
-            if ((a.M + 255) / 256 >= want) return launch_dlds<64, 256, 1, 4>(a, 3, st);
-            return launch_dlds<64, 128, 1, 4>(a, 4, st);
+        const char *env = getenv("ICNN_TILE");       // tuning aid: force one tile shape
+        const int forced = env ? atoi(env) : -1;
+        int best = -1;
+        double best_cost = 0;
+        for (int t = 0; t < kNumTiles; ++t) {
+            if (kTiles[t].bm / 2 >= a.Cout && t != 0) continue;          // more than half the cout tile empty
+            const double c = tile_cost(kTiles[t], a);
+            if (best < 0 || c < best_cost) { best = t; best_cost = c; }
         }
-        const long long n_ct = (a.Cout + 127) / 128;
-        if (n_ct * ((a.M + 127) / 128) >= want) return launch_dlds<128, 128, 2, 2>(a, 4, st);
-        return launch_dlds<128, 64, 2, 2>(a, 4, st);
+        if (forced >= 0 && forced < kNumTiles) best = forced;
+        return launch_tile(best, a, st);
     }
     if (a.Cout <= 32) return launch_greg<32, 256, 1, 4>(a, vec_in, st);
     if (a.Cout <= 64) return launch_greg<64, 256, 1, 4>(a, vec_in, st);

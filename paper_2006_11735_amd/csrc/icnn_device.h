@@ -39,6 +39,7 @@ struct ConvArgs {
     int n_ct;     // cout tiles
     int n_tiles;  // cout tiles x pixel tiles
     int per_xcd;  // tiles handed to each of the 8 XCDs
+    int n_vtiles; // 8 * per_xcd: tile slots including the padding ones
     unsigned x_bytes;     // extent of x the kernel may touch (direct-to-LDS kernel: < 2 GiB)
     unsigned wp_bytes;    // extent of the packed weights
     int nstages;          // LDS ring depth of the direct-to-LDS kernel
