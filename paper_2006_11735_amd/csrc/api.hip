@@ -286,6 +286,7 @@ int iadd_rescale(const icnn_add_desc *d, const void *a, const void *b, void *out
     k.shift = d->out_mode == ICNN_OUT_RAW_S32 ? 0 : d->shift;
     k.lo = d->out_mode == ICNN_OUT_LINEAR_S8 ? -128 : d->lo;
     k.hi = d->out_mode == ICNN_OUT_LINEAR_S8 ? 127 : d->hi;
+    k.mul_hi = 0;
     const int ab = dtype_bytes(d->a_dtype), bb = dtype_bytes(d->b_dtype);
     const int ob = d->out_mode == ICNN_OUT_RAW_S32 ? 4 : 1;
     const bool vec = d->c % 16 == 0 && aligned16(a) && aligned16(b) && aligned16(out) &&

@@ -98,7 +98,7 @@ __device__ __forceinline__ void epilogue_vec(const ConvArgs &a, const v16i &acc,
         const int half = (1 << a.res_shift) >> 1;
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-            t[r] = __builtin_elementwise_add_sat(t[r], (rv[r] * a.res_mul + half) >> a.res_shift);
+            t[r] = __builtin_elementwise_add_sat(t[r], (__mul24(rv[r], a.res_mul) + half) >> a.res_shift);   // res_mul < 2^23
     }
     if (RES == 2 && a.res_mode == 1) {
 #pragma unroll

@@ -41,21 +41,43 @@ __device__ __forceinline__ int add_one(int av, int bv, const AddArgs &a, bool ra
     return clampi64(rsr64((int64_t)t * a.mul, a.shift), a.lo, a.hi);
 }
 
-// vector path: one lane = 16 consecutive channels of one pixel
-__global__ __launch_bounds__(256) void add_rescale_vec_kernel(const AddArgs a, int groups_per_px,
-                                                              long long total)
+// vector path: one lane = 16 consecutive channels of one pixel.
+// FAST: b is 8 bits wide with a rescale that fits 32 bits (so b_mul < 2^23: a 24-bit multiply), and the output requantisation is one
+// 32x32->64 multiply-add whose high word is the result (same identities as the conv epilogue).
+template <bool FAST>
+__global__ __launch_bounds__(256) void add_rescale_vec_kernel(const AddArgs a, int groups_per_px, long long total)
 {
     const long long g = (long long)blockIdx.x * 256 + threadIdx.x;
     if (g >= total) return;
-    const long long px = g / groups_per_px;
-    const int c0 = (int)(g - px * groups_per_px) * 16;
+    size_t ao, bo, oo;
+    if (groups_per_px == 0) {
+        // all three tensors are dense: no pixel / channel split needed
+        ao = bo = oo = (size_t)g * 16;
+    } else {
+        long long px;
+        if (total < 0x7fffffffLL) px = (unsigned)g / (unsigned)groups_per_px;
+        else px = g / groups_per_px;
+        const int c0 = (int)(g - px * groups_per_px) * 16;
+        ao = (size_t)px * a.a_cs + c0;
+        bo = (size_t)px * a.b_cs + c0;
+        oo = (size_t)px * a.out_cs + a.out_co + c0;
+    }
     int av[16], bv[16], ov[16];
-    unpack16(a.a, (size_t)px * a.a_cs + c0, a.a_dt, av);
-    unpack16(a.b, (size_t)px * a.b_cs + c0, a.b_dt, bv);
+    unpack16(a.a, ao, a.a_dt, av);
+    unpack16(a.b, bo, a.b_dt, bv);
     const bool raw = a.out_mode == 3;
+    if (FAST) {
+        const int half = (1 << a.b_shift) >> 1;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) ov[r] = add_one(av[r], bv[r], a, raw);
-    const size_t oo = (size_t)px * a.out_cs + a.out_co + c0;
+        for (int r = 0; r < 16; ++r) {
+            const int t = __builtin_elementwise_add_sat(av[r], (__mul24(bv[r], a.b_mul) + half) >> a.b_shift);
+            const int q = (int)(((int64_t)t * a.mul_hi + 0x80000000LL) >> 32);
+            ov[r] = raw ? t : min(max(q, a.lo), a.hi);
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) ov[r] = add_one(av[r], bv[r], a, raw);
+    }
     if (raw) {
         v4i *op = (v4i *)((int32_t *)a.out + oo);
 #pragma unroll
@@ -84,10 +106,22 @@ hipError_t launch_add(const AddArgs &a, bool vec, hipStream_t st)
 {
     if (a.px == 0 || a.c == 0) return hipSuccess;
     if (vec) {
-        const int gpp = a.c / 16;
-        const long long total = a.px * gpp;
-        hipLaunchKernelGGL(add_rescale_vec_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                           a, gpp, total);
+        const bool dense = a.a_cs == a.c && a.b_cs == a.c && a.out_cs == a.c && a.out_co == 0;
+        const long long total = a.px * (a.c / 16);
+        const int gpp = dense ? 0 : a.c / 16;
+        // fast arithmetic when b is 8 bits with |255 * b_mul| + half < 2^31 and (raw output or
+        // 1 <= shift <= 32 with mul << (32 - shift) < 2^31)
+        const bool b_fast = a.b_dt != 2 && a.b_shift <= 30 && 255LL * a.b_mul + (1LL << a.b_shift) / 2 <= 0x7fffffffLL;
+        const bool q_fast = a.out_mode == 3 ||
+                            (a.shift >= 1 && a.shift <= 32 && ((long long)a.mul << (32 - a.shift)) <= 0x7fffffffLL);
+        const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+        if (b_fast && q_fast) {
+            AddArgs f = a;
+            f.mul_hi = a.out_mode == 3 ? 0 : (int)((long long)a.mul << (32 - a.shift));
+            hipLaunchKernelGGL(add_rescale_vec_kernel<true>, grid, block, 0, st, f, gpp, total);
+        } else {
+            hipLaunchKernelGGL(add_rescale_vec_kernel<false>, grid, block, 0, st, a, gpp, total);
+        }
     } else {
         const long long total = a.px * a.c;
         hipLaunchKernelGGL(add_rescale_scalar_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,

@@ -95,6 +95,7 @@ struct AddArgs {
     int64_t px;
     int c, a_cs, b_cs, out_cs, out_co, a_dt, b_dt, out_mode;
     int b_mul, b_shift, mul, shift, lo, hi;
+    int mul_hi;   // mul << (32 - shift) when the fast requantisation applies
 };
 hipError_t launch_add(const AddArgs &a, bool vec, hipStream_t st);
 hipError_t launch_requant_copy(const uint8_t *in, uint8_t *out, int64_t px, int c, int in_cs,
