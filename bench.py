@@ -25,8 +25,16 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def layer_work(net, op, images):
-    """Algorithmic ops and bytes of one conv launch (true sizes, input counted once)."""
+def layer_work(net, op, images, fused_proj=None):
+    """Algorithmic ops and bytes of one conv launch (true sizes, input counted once).  With a
+    projection fused into the launch, its ops, input and weights are added and the int32 skip
+    tensor is not counted (it never exists)."""
+    if fused_proj is not None:
+        main = dict(op, res=None)
+        o1, b1, m, k1 = layer_work(net, main, images)
+        proj = dict(fused_proj, out_mode="brelu")
+        o2, b2, _, k2 = layer_work(net, proj, images)
+        return o1 + o2, b1 + b2 - m * op["cout"], m, k1 + k2
     n, ho, wo, _ = net["buffers"][op["dst"]]["shape"]
     _, h, w, _ = net["buffers"][op["src"]]["shape"]
     n = images
@@ -158,17 +166,17 @@ def main():
     other_ms = 0.0
     rows = []
     for (kind, op, _), ms in zip(g.steps, layer_ms):
-        if kind != "conv":
+        if kind not in ("conv", "dual"):
             other_ms += ms
             rows.append({"name": op["dst"], "kind": kind, "ms": ms})
             continue
-        ops, byts, m, k = layer_work(net, op, images)
+        ops, byts, m, k = layer_work(net, op, images, g.fused_proj.get(op["name"]) if kind == "dual" else None)
         conv_ops += ops
         conv_ms += ms
         conv_bytes += byts
         tops = ops / (ms * 1e-3) / 1e12
         attain = min(INT8_MFMA_PEAK_TOPS, ops / byts * HBM_PEAK_GBS / 1e3)
-        rows.append({"name": op["name"], "kind": "conv", "M": m, "N": op["cout"], "K": k, "ms": ms,
+        rows.append({"name": op["name"] + ("+proj" if kind == "dual" else ""), "kind": "conv", "M": m, "N": op["cout"], "K": k, "ms": ms,
                      "tops": tops, "pct_mfma_peak": 100 * tops / INT8_MFMA_PEAK_TOPS,
                      "pct_attainable": 100 * tops / attain, "gbs": byts / (ms * 1e-3) / 1e9})
     for r in rows:
@@ -197,12 +205,13 @@ def main():
         "dtype": "int8",
         "data": "synthetic",
         "config": {"workload": "cfg3: ResNet-50-shaped integer inference, batch 64, 3x224x224 uint8 input, "
-                               "53 convs + FC, 16 skip merges, stored oracle-side calibration (seed 0)",
+                               "53 convs + FC, 16 skip merges (the 4 projection convs fused into their block's last conv), "
+                               "stored oracle-side calibration (seed 0)",
                    "batch": images},
         "conv_tops": conv_tops,
         "pct_int8_mfma_peak": 100 * conv_tops / INT8_MFMA_PEAK_TOPS,
         "whole_step_tops": conv_ops / (ms_per_step * 1e-3) / 1e12,
-        "roofline": {"kernel": "conv_igemm_kernel (all %d conv launches of a step, every tile shape)" % n_conv,
+        "roofline": {"kernel": "conv kernels (all %d conv launches of a step: conv_dlds / conv_dual / conv_greg, every tile shape)" % n_conv,
                      "bound": "mfma", "achieved": conv_tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": conv_tops / INT8_MFMA_PEAK_TOPS, "traffic": traffic,
                      "launches_per_step": n_conv, "avg_launch_us": conv_ms * 1e3 / n_conv,

@@ -144,6 +144,27 @@ int iconv2d_brelu(const icnn_conv_desc *desc, const void *x, const void *w_packe
                   void *stream);
 
 /*
+ * A residual block's last layer together with its projection skip, as one launch (Section
+ * 4.1, the skip connection "after convolution": the projection convolves the quantised block
+ * input, its int32 result is rescaled to the main path's ratio and added before BReLU).
+ * Result: exactly that of
+ *     iconv2d_brelu(proj, x_proj, w_proj_packed, bias_proj, NULL, tmp, ...);   // RAW_S32
+ *     iconv2d_brelu(main, x_main, w_main_packed, bias_main, tmp, y, ...);      // res = tmp
+ * without the int32 tensor tmp ever existing.  `main` must have res_mode = ICNN_RES_PRE and
+ * res_dtype = ICNN_S32 (its res_mul / res_shift rescale the projection); `proj` must have
+ * out_mode = ICNN_OUT_RAW_S32 and res_mode = ICNN_RES_NONE.  Both must be 1x1 convolutions
+ * without padding (any stride) with cin % 16 == 0 that produce the same n x ho x wo x cout;
+ * x, y and pitches 16-byte aligned.
+ * Contract: |bias| <= 2^28 for both layers.  With it the library proves from the layer sizes
+ * that Y_main + [Y_proj * res_mul / 2^res_shift] cannot leave int32; if it cannot prove that,
+ * or a shape restriction fails, the call returns ICNN_E_UNSUPPORTED having launched nothing, and
+ * the caller issues the two layers separately.
+ */
+int iconv2d_dual_brelu(const icnn_conv_desc *main_desc, const void *x_main, const void *w_main_packed,
+                       const int32_t *bias_main, const icnn_conv_desc *proj_desc, const void *x_proj,
+                       const void *w_proj_packed, const int32_t *bias_proj, void *y, void *stream);
+
+/*
  * Rescaled feature-map addition (ratio synchronisation between feature maps,
  * Sections 3.4.2 and 4.1), as a stand-alone pass over memory:
  *   T   = sat32(a + [b * b_mul / 2^b_shift])

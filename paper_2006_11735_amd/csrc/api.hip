@@ -168,14 +168,10 @@ int iconv2d_prepack_weights(const icnn_conv_desc *desc, const int8_t *w_ohwi, vo
                     "prepack");
 }
 
-int iconv2d_brelu(const icnn_conv_desc *d, const void *x, const void *w_packed, const int32_t *bias,
-                  const void *res, void *y, void *workspace, void *stream)
+// Validates pointers and fills the kernel arguments of one conv layer.
+static int fill_conv_args(const icnn_conv_desc *d, const ConvGeom &g, const void *x, const void *w_packed,
+                          const int32_t *bias, const void *res, void *y, ConvArgs &a)
 {
-    ConvGeom g;
-    const int rc = check_conv(d, &g);
-    if (rc) return rc;
-    if (g.ws_bytes && !workspace) return fail(ICNN_E_NULL, "this layer needs a workspace (iconv2d_workspace_bytes)");
-    if (g.ws_bytes && ((uintptr_t)workspace & 3)) return fail(ICNN_E_ALIGN, "workspace must be 4-byte aligned");
     if (!x || !w_packed || !bias || !y) return fail(ICNN_E_NULL, "x, w_packed, bias and y must not be NULL");
     if (d->res_mode != ICNN_RES_NONE && !res) return fail(ICNN_E_NULL, "res is NULL but res_mode is set");
     if (!aligned16(w_packed)) return fail(ICNN_E_ALIGN, "w_packed must be 16-byte aligned");
@@ -184,7 +180,6 @@ int iconv2d_brelu(const icnn_conv_desc *d, const void *x, const void *w_packed, 
     if (d->res_mode != ICNN_RES_NONE && d->res_dtype == ICNN_S32 && ((uintptr_t)res & 3))
         return fail(ICNN_E_ALIGN, "int32 skip operand must be 4-byte aligned");
 
-    ConvArgs a;
     a.x = (const uint8_t *)x;
     a.wp = (const uint8_t *)w_packed;
     a.bias = bias;
@@ -222,7 +217,7 @@ int iconv2d_brelu(const icnn_conv_desc *d, const void *x, const void *w_packed, 
         a.nstages = 0;
         a.div_howo = a.div_wo = FastDiv{0, 0, 0};
     }
-    a.n_tiles = a.per_xcd = 0;
+    a.n_tiles = a.per_xcd = a.n_vtiles = 0;
     a.rq_fast = 0;
     a.mul_hi = 0;
     if (d->out_mode != ICNN_OUT_RAW_S32 && a.shift >= 1 && a.shift <= 32 &&
@@ -240,6 +235,20 @@ int iconv2d_brelu(const icnn_conv_desc *d, const void *x, const void *w_packed, 
         const int rq_kind = d->out_mode == ICNN_OUT_RAW_S32 ? 0 : (a.rq_fast ? 1 : 2);
         a.epi_mode = 3 * res_kind + rq_kind;
     }
+    return ICNN_OK;
+}
+
+int iconv2d_brelu(const icnn_conv_desc *d, const void *x, const void *w_packed, const int32_t *bias,
+                  const void *res, void *y, void *workspace, void *stream)
+{
+    ConvGeom g;
+    int rc = check_conv(d, &g);
+    if (rc) return rc;
+    if (g.ws_bytes && !workspace) return fail(ICNN_E_NULL, "this layer needs a workspace (iconv2d_workspace_bytes)");
+    if (g.ws_bytes && ((uintptr_t)workspace & 3)) return fail(ICNN_E_ALIGN, "workspace must be 4-byte aligned");
+    ConvArgs a;
+    rc = fill_conv_args(d, g, x, w_packed, bias, res, y, a);
+    if (rc) return rc;
     if (g.rp) {
         // small cin: pad and re-normalise x into the workspace, then run the layer as a kh x 1
         // convolution with "rp channels" over that copy (see pad_small_cin_kernel)
@@ -254,6 +263,56 @@ int iconv2d_brelu(const icnn_conv_desc *d, const void *x, const void *w_packed, 
     }
     const bool vec_in = aligned16(x) && d->cin % 16 == 0 && d->in_c_stride % 16 == 0;
     return launched(launch_conv(a, vec_in, vec_in, (hipStream_t)stream), "iconv2d_brelu");
+}
+
+int iconv2d_dual_brelu(const icnn_conv_desc *m, const void *x_main, const void *w_main_packed,
+                       const int32_t *bias_main, const icnn_conv_desc *p, const void *x_proj,
+                       const void *w_proj_packed, const int32_t *bias_proj, void *y, void *stream)
+{
+    ConvGeom gm, gp;
+    int rc = check_conv(m, &gm);
+    if (rc) return rc;
+    rc = check_conv(p, &gp);
+    if (rc) return rc;
+    if (m->res_mode != ICNN_RES_PRE || m->res_dtype != ICNN_S32)
+        return fail(ICNN_E_PARAM, "main layer must describe an int32 skip operand joined before requantisation");
+    if (p->out_mode != ICNN_OUT_RAW_S32 || p->res_mode != ICNN_RES_NONE)
+        return fail(ICNN_E_PARAM, "projection layer must have a raw int32 output and no skip operand");
+    if (m->n != p->n || gm.ho != gp.ho || gm.wo != gp.wo || m->cout != p->cout)
+        return fail(ICNN_E_SHAPE, "main and projection layers must produce the same n x ho x wo x cout");
+    const icnn_conv_desc *both[2] = {m, p};
+    for (const icnn_conv_desc *d : both) {
+        if (d->kh != 1 || d->kw != 1 || d->pad_h != 0 || d->pad_w != 0 || d->cin % 16 != 0 || d->in_c_stride % 16 != 0 ||
+            d->in_sub128)
+            return fail(ICNN_E_UNSUPPORTED, "fused block needs 1x1 layers without padding, cin and pitch multiples of 16");
+    }
+    if (!aligned16(x_main) || !aligned16(x_proj) || !aligned16(y))
+        return fail(ICNN_E_UNSUPPORTED, "fused block needs 16-byte aligned tensors");
+    // |Y_proj| <= Kp*128*127 + 2^28, |Y_main| <= Km*128*127 + 2^28 under the bias contract
+    {
+        const long long yp = (long long)gp.K * 128 * 127 + (1LL << 28);
+        const long long ym = (long long)gm.K * 128 * 127 + (1LL << 28);
+        const __int128 s_max = (((__int128)yp * m->res_mul) >> m->res_shift) + 2;
+        if (s_max + ym > 0x7fffffffLL)
+            return fail(ICNN_E_UNSUPPORTED, "cannot prove that the merged sum stays inside int32 for these sizes");
+    }
+    ConvArgs a, b;
+    // the main layer's arguments without its skip operand (the projection is accumulated in registers)
+    icnn_conv_desc m0 = *m;
+    m0.res_mode = ICNN_RES_NONE;
+    rc = fill_conv_args(&m0, gm, x_main, w_main_packed, bias_main, nullptr, y, a);
+    if (rc) return rc;
+    int32_t dummy_out = 0;
+    rc = fill_conv_args(p, gp, x_proj, w_proj_packed, bias_proj, nullptr, &dummy_out, b);
+    if (rc) return rc;
+    if (a.x_bytes >= 0x7fffff00u || b.x_bytes >= 0x7fffff00u || a.wp_bytes >= 0x7fffff00u || b.wp_bytes >= 0x7fffff00u)
+        return fail(ICNN_E_UNSUPPORTED, "fused block needs tensors below 2 GiB");
+    ProjArgs q;
+    q.x = b.x; q.wp = b.wp; q.bias = b.bias;
+    q.H = p->h; q.W = p->w; q.Cin = p->cin; q.in_cs = p->in_c_stride; q.sh = p->stride_h; q.sw = p->stride_w;
+    q.ksteps = gp.ksteps; q.x_bytes = b.x_bytes; q.wp_bytes = b.wp_bytes;
+    q.res_mul = m->res_mul; q.res_shift = m->res_shift; q.vec_bias = b.vec_bias;
+    return launched(launch_conv_dual(a, q, (hipStream_t)stream), "iconv2d_dual_brelu");
 }
 
 int iadd_rescale(const icnn_add_desc *d, const void *a, const void *b, void *out, void *stream)

@@ -1,0 +1,238 @@
+// Residual block with a projection skip as ONE kernel (Section 4.1, "type 2": the skip
+// path convolves the quantised block input, its result is rescaled to the main path's ratio
+// and added before BReLU).  Both convolutions are 1x1 (any stride, no padding) and share the
+// output pixel grid and channel count, so they are two GEMMs into one accumulator tile:
+//
+//   phase P:  acc  = b_proj + Xp (*) Wp                       (int32, registers)
+//   between:  acc  = [acc * res_mul / 2^res_shift] + b_main   (64-bit multiply, registers)
+//   phase M:  acc += Xm (*) Wm
+//   epilogue: V = clamp([acc * mul / 2^shift], lo, hi)
+//
+// which equals sat32(Y_main + [Y_proj * res_mul / 2^res_shift]) exactly whenever that sum
+// cannot leave int32; the host proves this from the layer sizes and the bias contract before
+// launching (otherwise the caller runs the two layers separately).  The int32 projection tensor
+// never exists in memory.  Tile machinery as in conv_dlds_kernel (pointwise addressing).
+#include "conv_common.h"
+
+namespace icnn {
+
+template <int BM, int BP, int WAVES_M, int WAVES_P>
+__global__ __launch_bounds__(256, 2) void conv_dual_kernel(const ConvArgs a, const ProjArgs q)
+{
+#if defined(__HIP_DEVICE_COMPILE__)   // the buffer-resource type exists in the device pass only
+    constexpr int TM = BM / WAVES_M / 32;
+    constexpr int TP = BP / WAVES_P / 32;
+    constexpr int A_BYTES = BM * kStepK;
+    constexpr int B_BYTES = BP * kStepK;
+    constexpr int STAGE = A_BYTES + B_BYTES;
+    constexpr int A_INSTR = BM / 16;
+    constexpr int NA = A_INSTR >= 4 ? A_INSTR / 4 : 1;
+    constexpr int NB = BP / 64;
+    constexpr int LPS = NA + NB;
+    constexpr unsigned OOB = 0x80000000u;
+    static_assert(WAVES_M * WAVES_P == 4 && TM >= 1 && TP >= 1 && NB >= 1 && LPS <= 2 * TM * TP, "tile shape");
+
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+
+    int vtile = blockIdx.x;
+    int ct, pt;
+    {
+        const int logical = (vtile & 7) * a.per_xcd + (vtile >> 3);
+        if (logical >= a.n_tiles) return;
+    }
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave % WAVES_M;
+    const int wp = wave / WAVES_M;
+    const int nstages = a.nstages;
+    const int kp = q.ksteps, km = a.ksteps;
+    const int ksteps = kp + km;                       // projection steps first, then the main path
+    const int depth = min(nstages - 1, ksteps);
+
+    const __amdgpu_buffer_rsrc_t rs_xm = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, a.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_wm = __builtin_amdgcn_make_buffer_rsrc((void *)a.wp, 0, a.wp_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_xp = __builtin_amdgcn_make_buffer_rsrc((void *)q.x, 0, q.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_wp = __builtin_amdgcn_make_buffer_rsrc((void *)q.wp, 0, q.wp_bytes, 0x00020000);
+
+    unsigned a_off_m[NA], a_off_p[NA];
+    int a_lds[NA];
+#pragma unroll
+    for (int c = 0; c < NA; ++c) a_lds[c] = ((4 * c + wave) % A_INSTR) * 1024;
+    const int ls = (lane & 3) ^ ((lane >> 4) & 3);
+    unsigned b_off_m[NB], b_off_p[NB];
+
+    auto tile_of = [&](int v, int &ct_, int &pt_) {
+        const int logical = (v & 7) * a.per_xcd + (v >> 3);
+        ct_ = logical % a.n_ct;
+        pt_ = logical / a.n_ct;
+        return logical < a.n_tiles;
+    };
+    auto setup_load_side = [&](int ct_, int pt_) {
+        const int pix0 = pt_ * BP;
+        const int chunk0 = ct_ * (BM / 32);
+#pragma unroll
+        for (int c = 0; c < NA; ++c) {
+            const int e = a_lds[c] / 16 + lane;
+            const unsigned piece = (unsigned)(e & 127) * 16;
+            a_off_m[c] = (unsigned)(chunk0 + (e >> 7)) * (unsigned)km * kChunkBytes + piece;
+            a_off_p[c] = (unsigned)(chunk0 + (e >> 7)) * (unsigned)kp * kChunkBytes + piece;
+        }
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const int p = pix0 + 16 * (4 * j + wave) + (lane >> 2);
+            const bool pv = p < a.M;
+            const int pc = pv ? p : 0;
+            const int n = fast_div(pc, a.div_howo);
+            const int r = pc - n * a.Ho * a.Wo;
+            const int ho = fast_div(r, a.div_wo);
+            const int wo = r - ho * a.Wo;
+            b_off_m[j] = pv ? (unsigned)(((n * a.H + ho * a.sh) * a.W + wo * a.sw) * a.in_cs) + ls * 16 : OOB;
+            b_off_p[j] = pv ? (unsigned)(((n * q.H + ho * q.sh) * q.W + wo * q.sw) * q.in_cs) + ls * 16 : OOB;
+        }
+    };
+    auto issue_copy = [&](int c, int s, uint8_t *stage) {
+        const bool proj = s < kp;
+        const int sl = proj ? s : s - kp;
+        if (c < NA) {
+            if (proj)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_wp, (__attribute__((address_space(3))) void *)(stage + a_lds[c]),
+                                                         16, a_off_p[c], sl * kChunkBytes, 0, 0);
+            else
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_wm, (__attribute__((address_space(3))) void *)(stage + a_lds[c]),
+                                                         16, a_off_m[c], sl * kChunkBytes, 0, 0);
+            return;
+        }
+        const int j = c - NA;
+        uint8_t *dst = stage + A_BYTES + (4 * j + wave) * 1024;
+        const bool kok = sl * kStepK + ls * 16 < (proj ? q.Cin : a.Cin);
+        if (proj)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_xp, (__attribute__((address_space(3))) void *)dst, 16,
+                                                     kok ? b_off_p[j] : OOB, sl * kStepK, 0, 0);
+        else
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_xm, (__attribute__((address_space(3))) void *)dst, 16,
+                                                     kok ? b_off_m[j] : OOB, sl * kStepK, 0, 0);
+    };
+
+    const int a_rd = wm * TM * 2048 + lane * 16;
+    const int b_rd0 = A_BYTES + b_slot_offset(wp * TP * 32 + (lane & 31), (lane >> 5));
+    const int b_rd1 = A_BYTES + b_slot_offset(wp * TP * 32 + (lane & 31), 2 + (lane >> 5));
+
+    tile_of(vtile, ct, pt);
+    setup_load_side(ct, pt);
+    int buf = 0, ibuf = 0;
+    for (int s = 0; s < depth; ++s) {
+#pragma unroll
+        for (int c = 0; c < LPS; ++c) issue_copy(c, s, lds + ibuf * STAGE);
+        if (++ibuf == nstages) ibuf = 0;
+    }
+    ConvArgs pb = a;            // only .bias / .Cout / .vec_bias are read by load_bias_rows
+    pb.bias = q.bias;
+    pb.vec_bias = q.vec_bias;
+    v16i bias_next[TM];
+    load_bias_rows<TM>(pb, ct * BM + wm * TM * 32, lane >> 5, bias_next);
+
+    for (;;) {
+        v16i acc[TM][TP];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TP; ++j) acc[i][j] = bias_next[i];
+        v16i bias_main[TM];     // older than every copy issued below, so the counted waits stay valid
+        load_bias_rows<TM>(a, ct * BM + wm * TM * 32, lane >> 5, bias_main);
+
+        for (int s = 0; s < ksteps; ++s) {
+            const int later = min(depth - 1, ksteps - 1 - s);
+            asm volatile("" ::: "memory");
+            if (later >= 2) ICNN_WAIT_VMCNT(2 * LPS);
+            else if (later == 1) ICNN_WAIT_VMCNT(LPS);
+            else ICNN_WAIT_VMCNT(0);
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            const bool feed = s + depth < ksteps;
+            uint8_t *istage = lds + ibuf * STAGE;
+            const uint8_t *S = lds + buf * STAGE;
+            v4i af[2][TM], bf[2][TP];
+#pragma unroll
+            for (int kq = 0; kq < 2; ++kq) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) af[kq][i] = *(const v4i *)(S + a_rd + (i * 2 + kq) * 1024);
+#pragma unroll
+                for (int j = 0; j < TP; ++j) bf[kq][j] = *(const v4i *)(S + (kq ? b_rd1 : b_rd0) + j * 2048);
+            }
+            int c = 0;
+#pragma unroll
+            for (int kq = 0; kq < 2; ++kq)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TP; ++j) {
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[kq][i], bf[kq][j], acc[i][j], 0, 0, 0);
+                        if (c < LPS) {
+                            if (feed) issue_copy(c, s + depth, istage);
+                            ++c;
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    }
+            if (feed && ++ibuf == nstages) ibuf = 0;
+            if (++buf == nstages) buf = 0;
+            if (s == kp - 1) {
+                // the projection sum is complete: bring it to the main path's ratio, add the main bias
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TP; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            acc[i][j][r] = (int)rsr64((int64_t)acc[i][j][r] * q.res_mul, q.res_shift) + bias_main[i][r];
+            }
+        }
+
+        const int co_wave = ct * BM + wm * TM * 32;
+        const int pix_wave = pt * BP + wp * TP * 32;
+        vtile += gridDim.x;
+        const bool more = vtile < a.n_vtiles && tile_of(vtile, ct, pt);
+        if (more) {
+            setup_load_side(ct, pt);
+            for (int s = 0; s < depth; ++s) {
+#pragma unroll
+                for (int c = 0; c < LPS; ++c) issue_copy(c, s, lds + ibuf * STAGE);
+                if (++ibuf == nstages) ibuf = 0;
+            }
+            load_bias_rows<TM>(pb, ct * BM + wm * TM * 32, lane >> 5, bias_next);
+        }
+        epilogue_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane);
+        if (!more) break;
+        asm volatile("" ::: "memory");
+        ICNN_WAIT_VMCNT(0);     // stores retire out of order with loads: drain before counting again
+    }
+#endif
+}
+
+template <int BM, int BP, int WAVES_M, int WAVES_P>
+static hipError_t launch_dual_cfg(const ConvArgs &a0, const ProjArgs &q, hipStream_t st)
+{
+    ConvArgs a = a0;
+    if (!finish_args(a, BM, BP)) return hipErrorInvalidValue;
+    const int ksteps = a.ksteps + q.ksteps;
+    a.nstages = ksteps + 1 < 4 ? ksteps + 1 : 4;
+    if (a.nstages < 2) a.nstages = 2;
+    a.div_howo = make_fast_div((unsigned)(a.Ho * a.Wo));
+    a.div_wo = make_fast_div((unsigned)a.Wo);
+    const size_t lds_bytes = (size_t)a.nstages * (BM + BP) * kStepK;
+    a.n_vtiles = 8 * a.per_xcd;
+    const int slots = 256 * 2;
+    const dim3 grid((unsigned)(a.n_vtiles < slots ? a.n_vtiles : slots)), block(256);
+    hipLaunchKernelGGL((conv_dual_kernel<BM, BP, WAVES_M, WAVES_P>), grid, block, lds_bytes, st, a, q);
+    return hipGetLastError();
+}
+
+hipError_t launch_conv_dual(const ConvArgs &a, const ProjArgs &q, hipStream_t st)
+{
+    // narrow pixel tiles when the wide ones would leave most CUs without work
+    const long long wide = (long long)((a.Cout + 127) / 128) * ((a.M + 127) / 128);
+    if (wide >= 256) return launch_dual_cfg<128, 128, 2, 2>(a, q, st);
+    return launch_dual_cfg<128, 64, 2, 2>(a, q, st);
+}
+
+}  // namespace icnn

@@ -17,226 +17,13 @@
 //                     stages in flight, one barrier per K step;
 //   conv_greg_kernel  any cin / alignment / raw-picture input: tiles are staged
 //                     through registers (double-buffered LDS).
-#include "icnn_device.h"
+#include "conv_common.h"
 
 #include <cstdlib>
 
 namespace icnn {
 
-typedef int v4i_a4 __attribute__((ext_vector_type(4), aligned(4)));   // 16-byte load, dword aligned
-
-// LDS tile layout of one K step (both kernels):
-//   A (weights): BM*64 bytes in packed-fragment order, i.e. a straight copy of
-//      BM/32 consecutive 2 KiB chunks of the packed weights.
-//   B (activations): BP rows of 64 bytes (one output pixel each); the 16-byte slot
-//      s of row r lives at slot s ^ ((r >> 2) & 3), which makes both the row-wise
-//      fill and the column-wise fragment reads free of bank conflicts.
-__device__ __forceinline__ int b_slot_offset(int row, int slot)
-{
-    return row * 64 + ((slot ^ ((row >> 2) & 3)) << 4);
-}
-
-// ---------------------------------------------------------------- epilogue
-// Every call handles channels co0..co0+15 (co0 a multiple of 16) of output pixel p,
-// held in one lane's accumulator registers, which were initialised with the bias
-// (so they hold Y = U + b).  Then (Section 4.1)
-// the rescaled skip operand, then (Section 3.2.1) requantisation and the clamp.
-
-// any alignment, any tail: one element at a time, 64-bit arithmetic throughout
-__device__ __forceinline__ void epilogue_slow(const ConvArgs &a, const v16i &acc, int p, int co0, int nv)
-{
-    const size_t ro = (size_t)p * a.res_cs + co0;
-    const size_t oo = (size_t)p * a.out_cs + a.out_co + co0;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        if (r >= nv) break;
-        int64_t t = acc[r];
-        int64_t skip = 0;
-        if (a.res_mode != 0) skip = rsr64((int64_t)load_elem(a.res, ro + r, a.res_dtype) * a.res_mul, a.res_shift);
-        if (a.res_mode == 1) t += skip;
-        const int ti = sat32(t);
-        if (a.out_mode == 3) {
-            ((int32_t *)a.out)[oo + r] = ti;
-        } else {
-            int64_t q = rsr64((int64_t)ti * a.mul, a.shift);
-            if (a.res_mode == 2) q += skip;
-            ((uint8_t *)a.out)[oo + r] = (uint8_t)clampi64(q, a.lo, a.hi);
-        }
-    }
-}
-
-// vector path: all 16 channels valid, 16-byte aligned skip operand and output.
-// RES: 0 no skip operand; 1 8-bit operand joined before requantisation with a rescale
-//      that fits 32 bits; 2 anything else (int32 operand, wide multiplier, join after).
-// RQ:  0 raw int32 output; 1 requantisation as one 32x32->64 multiply-add whose high
-//      word is the result; 2 general 64-bit multiply, add, shift.
-template <int RES, int RQ>
-__device__ __forceinline__ void epilogue_vec(const ConvArgs &a, const v16i &acc, int p, int co0, const v4i &res8)
-{
-    int t[16];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) t[r] = acc[r];
-    int rv[16];
-    if (RES != 0) {
-        if (RES == 2 && a.res_dtype == 2) {
-            const v4i *rp = (const v4i *)((const int32_t *)a.res + ((size_t)p * a.res_cs + co0));
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const v4i v = rp[q];
-                rv[4 * q] = v.x; rv[4 * q + 1] = v.y; rv[4 * q + 2] = v.z; rv[4 * q + 3] = v.w;
-            }
-        } else {
-            const int wd[4] = {res8.x, res8.y, res8.z, res8.w};
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int b8 = (wd[r >> 2] >> ((r & 3) * 8)) & 0xff;
-                rv[r] = a.res_dtype == 1 ? (int)(int8_t)b8 : b8;
-            }
-        }
-    }
-    if (RES == 1) {
-        const int half = (1 << a.res_shift) >> 1;
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-            t[r] = __builtin_elementwise_add_sat(t[r], (__mul24(rv[r], a.res_mul) + half) >> a.res_shift);   // res_mul < 2^23
-    }
-    if (RES == 2 && a.res_mode == 1) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) t[r] = sat32((int64_t)t[r] + rsr64((int64_t)rv[r] * a.res_mul, a.res_shift));
-    }
-    const size_t oo = (size_t)p * a.out_cs + a.out_co + co0;
-    if (RQ == 0) {
-        v4i *op = (v4i *)((int32_t *)a.out + oo);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) op[q] = v4i{t[4 * q], t[4 * q + 1], t[4 * q + 2], t[4 * q + 3]};
-        return;
-    }
-    uint32_t wd[4] = {0, 0, 0, 0};
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        int v;
-        if (RQ == 1 && !(RES == 2)) {
-            // [t * mul / 2^shift] = high word of t * (mul << (32 - shift)) + 2^31   (1 <= shift <= 32)
-            const int q = (int)(((int64_t)t[r] * a.mul_hi + 0x80000000LL) >> 32);
-            v = min(max(q, a.lo), a.hi);
-        } else {
-            int64_t q = RQ == 1 ? (((int64_t)t[r] * a.mul_hi + 0x80000000LL) >> 32)
-                                : rsr64((int64_t)t[r] * a.mul, a.shift);
-            if (RES == 2 && a.res_mode == 2) q += rsr64((int64_t)rv[r] * a.res_mul, a.res_shift);
-            v = clampi64(q, a.lo, a.hi);
-        }
-        wd[r >> 2] |= (uint32_t)(v & 0xff) << ((r & 3) * 8);
-    }
-    *(v4i *)((uint8_t *)a.out + oo) = v4i{(int)wd[0], (int)wd[1], (int)wd[2], (int)wd[3]};
-}
-
-// Epilogue of a wave's TM x TP accumulator tiles; the mode switch is outside the
-// tile loops so each mode is straight-line code.
-template <int TM, int TP>
-__device__ __forceinline__ void epilogue_tiles(const ConvArgs &a, const v16i (&acc)[TM][TP], int co_wave, int pix_wave,
-                                               int lane)
-{
-    const int half = lane >> 5;
-    auto for_tiles = [&](auto fn) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int co0 = co_wave + i * 32 + half * 16;
-#pragma unroll
-            for (int j = 0; j < TP; ++j) {
-                const int p = pix_wave + j * 32 + (lane & 31);
-                if (co0 < a.Cout && p < a.M) fn(acc[i][j], p, co0, i, j);
-            }
-        }
-    };
-    // channel tails and unaligned tensors take the element-wise path for the whole call
-    if (!a.epi_vec || (a.Cout & 15)) {
-        for_tiles([&](const v16i &c, int p, int co0, int, int) {
-            epilogue_slow(a, c, p, co0, min(16, a.Cout - co0));
-        });
-        return;
-    }
-    // 8-bit skip operands of all tiles are fetched before the first store (stores may alias
-    // them as far as the compiler knows, which would otherwise serialise the fetches)
-    v4i res8[TM][TP];
-    if (a.res_mode != 0 && a.res_dtype != 2) {
-        for_tiles([&](const v16i &, int p, int co0, int i, int j) {
-            res8[i][j] = *(const v4i *)((const uint8_t *)a.res + ((size_t)p * a.res_cs + co0));
-        });
-    }
-    switch (a.epi_mode) {
-#define ICNN_EPI_CASE(RES, RQ)                                                                      \
-    case RES * 3 + RQ:                                                                              \
-        for_tiles([&](const v16i &c, int p, int co0, int i, int j) {                                \
-            epilogue_vec<RES, RQ>(a, c, p, co0, res8[i][j]);                                        \
-        });                                                                                         \
-        break;
-        ICNN_EPI_CASE(0, 0) ICNN_EPI_CASE(0, 1) ICNN_EPI_CASE(0, 2)
-        ICNN_EPI_CASE(1, 0) ICNN_EPI_CASE(1, 1) ICNN_EPI_CASE(1, 2)
-        ICNN_EPI_CASE(2, 0) ICNN_EPI_CASE(2, 1) ICNN_EPI_CASE(2, 2)
-#undef ICNN_EPI_CASE
-    default: break;
-    }
-}
-
-// Maps the hardware workgroup id to a tile.  Workgroups are dealt round-robin to the
-// 8 XCDs (each with its own L2); giving XCD x the contiguous tile range
-// [x*per_xcd, (x+1)*per_xcd) keeps the cout tiles of one pixel tile, and neighbouring
-// pixel tiles (shared halo rows), in one L2.  Returns false for padding workgroups.
-__device__ __forceinline__ bool tile_of_block(const ConvArgs &a, int &ct, int &pt)
-{
-    const int xcd = blockIdx.x & 7;
-    const int idx = blockIdx.x >> 3;
-    const int logical = xcd * a.per_xcd + idx;
-    if (logical >= a.n_tiles) return false;
-    ct = logical % a.n_ct;
-    pt = logical / a.n_ct;
-    return true;
-}
-
-// Bias of the channels a lane owns: register r of a lane in half h of tile row i holds
-// channel co_base + 32*i + 16*h + r.  Accumulators start at these values.
-template <int TM>
-__device__ __forceinline__ void load_bias_rows(const ConvArgs &a, int co_base, int half, v16i (&b)[TM])
-{
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int co0 = co_base + i * 32 + half * 16;
-        if (a.vec_bias) {
-            const v4i *bp = (const v4i *)(a.bias + max(0, min(co0, a.Cout - 16)));
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const v4i v = bp[q];
-                b[i][4 * q] = v.x; b[i][4 * q + 1] = v.y; b[i][4 * q + 2] = v.z; b[i][4 * q + 3] = v.w;
-            }
-        } else {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) b[i][r] = a.bias[min(co0 + r, a.Cout - 1)];
-        }
-    }
-}
-
-template <int TM, int TP>
-__device__ __forceinline__ void init_acc_with_bias(const ConvArgs &a, int co_base, int half, v16i (&acc)[TM][TP])
-{
-    v16i b[TM];
-    load_bias_rows<TM>(a, co_base, half, b);
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TP; ++j) acc[i][j] = b[i];
-}
-
-#define ICNN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | 0x0F70 | (((n) >> 4) << 14))
-
 // ------------------------------------------------- direct-to-LDS pipelined kernel
-// floor(n / d) for 0 <= n < 2^31 by multiply-high and shifts (Granlund & Montgomery's
-// round-up method); the host fills `FastDiv` for d.
-__device__ __forceinline__ int fast_div(int n, const FastDiv &d)
-{
-    const unsigned t = __umulhi((unsigned)n, d.mul);
-    return (int)((t + (((unsigned)n - t) >> d.s1)) >> d.s2);
-}
-
 // Tiles travel from global memory into LDS without passing through registers
 // (buffer_load_dwordx4 ... lds).  Every lane moves 16 bytes; a wave-wide copy fills
 // 1 KiB of consecutive LDS.  Out-of-image pieces (zero padding, the K tail, pixels
@@ -670,28 +457,6 @@ __global__ __launch_bounds__(256) void conv_greg_kernel(const ConvArgs a)
 }
 
 // ------------------------------------------------------------------ dispatch
-static bool finish_args(ConvArgs &a, int BM, int BP)
-{
-    a.n_ct = (a.Cout + BM - 1) / BM;
-    const long long tiles = (long long)a.n_ct * ((a.M + BP - 1) / BP);
-    if (tiles <= 0 || tiles > 0x7ffffff0LL) return false;
-    a.n_tiles = (int)tiles;
-    a.per_xcd = (int)((tiles + 7) / 8);
-    return true;
-}
-
-static FastDiv make_fast_div(unsigned d)
-{
-    // l = ceil(log2 d); mul = floor(2^32 * (2^l - d) / d) + 1; q = (t + ((n - t) >> min(l,1))) >> max(l-1,0)
-    FastDiv f;
-    unsigned l = 0;
-    while ((1ull << l) < d) ++l;
-    f.mul = (unsigned)(((1ull << 32) * ((1ull << l) - d)) / d + 1);
-    f.s1 = l < 1 ? l : 1;
-    f.s2 = l > 1 ? l - 1 : 0;
-    return f;
-}
-
 template <int BM, int BP, int WAVES_M, int WAVES_P>
 static hipError_t launch_dlds(const ConvArgs &a0, int max_stages, int per_cu, hipStream_t st)
 {

@@ -57,6 +57,18 @@ struct ConvArgs {
     int epi_mode; // 3 * RES + RQ of the vector epilogue
 };
 
+// Projection half of a fused type-2 residual block (see conv_dual.hip)
+struct ProjArgs {
+    const uint8_t *x;
+    const uint8_t *wp;
+    const int32_t *bias;
+    int H, W, Cin, in_cs, sh, sw;
+    int ksteps;
+    unsigned x_bytes, wp_bytes;
+    int res_mul, res_shift;
+    int vec_bias;
+};
+
 // [v / 2^s], round half up; arithmetic shift floors for negative values.
 __device__ __forceinline__ int64_t rsr64(int64_t v, int s)
 {
@@ -83,6 +95,7 @@ __device__ __forceinline__ int load_elem(const void *p, size_t i, int dtype)
 // launchers (host)
 // vec_in: 16-byte pieces of x never straddle a tap (dword aligned); direct_ok: they are also 16-byte aligned
 hipError_t launch_conv(const ConvArgs &a, bool vec_in, bool direct_ok, hipStream_t st);
+hipError_t launch_conv_dual(const ConvArgs &a, const ProjArgs &q, hipStream_t st);
 hipError_t launch_prepack(const int8_t *w, uint8_t *wp, int Cout, int K, int chunks, int ksteps, int KH, int KW,
                           int Cin, int rp, hipStream_t st);
 hipError_t launch_pad_small_cin(const uint8_t *x, void *out, int N, int H, int W, int Cin, int in_cs, int ph, int pw,

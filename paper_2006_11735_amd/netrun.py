@@ -16,7 +16,10 @@ _DT = {"u8": B.ICNN_U8, "s8": B.ICNN_S8, "s32": B.ICNN_S32}
 
 
 class GpuNet:
-    def __init__(self, net, seed, calib, images=None, device="cuda:0"):
+    def __init__(self, net, seed, calib, images=None, device="cuda:0", fuse=True):
+        """fuse: run a projection conv and the block's last conv that consumes it as one
+        iconv2d_dual_brelu launch where the library accepts that (the int32 skip buffer then
+        stays untouched)."""
         if not torch.cuda.is_available():
             raise RuntimeError("GpuNet needs a GPU: there is no CPU fallback")
         self.net, self.seed, self.calib = net, seed, calib
@@ -29,9 +32,25 @@ class GpuNet:
             dt = torch.int32 if b["dtype"] == "s32" else torch.uint8
             self.buf[name] = torch.zeros(shape, dtype=dt, device=self.device)
         self.steps = []
+        self.fused = []                     # names of int32 skip buffers that are never written
+        self.fused_proj = {}                # main conv name -> the projection op fused into it
+        pending = {}                        # skip buffer name -> prepared projection step
         for op in net["ops"]:
             if op["op"] == "conv":
-                self.steps.append(self._prep_conv(op))
+                step = self._prep_conv(op)
+                if fuse and op["role"] == "projection" and op["out_mode"] == "raw_s32":
+                    pending[op["dst"]] = step
+                    continue
+                if op["res"] in pending:
+                    proj = pending.pop(op["res"])
+                    dual = self._try_fuse(step, proj)
+                    if dual is not None:
+                        self.fused.append(op["res"])
+                        self.fused_proj[op["name"]] = proj[1]
+                        self.steps.append(dual)
+                        continue
+                    self.steps.append(proj)
+                self.steps.append(step)
             elif op["op"] == "maxpool":
                 n, h, w, c = self.buf[op["src"]].shape
                 args = (n, h, w, c, op["k"], op["stride"], op["pad"], self.buf[op["src"]], self.buf[op["dst"]])
@@ -73,6 +92,17 @@ class GpuNet:
         torch.cuda.synchronize(self.device)       # w_dev may be released after the prepack ran
         return ("conv", op, (d, src, wp, bias, res, dst, ws))
 
+    def _try_fuse(self, main, proj):
+        (dm, xm, wm, bm, _res, y, _ws), (dp, xp, wp, bp, _r, _sk, _w) = main[2], proj[2]
+        args = (dm, xm, wm, bm, dp, xp, wp, bp, y)
+        try:
+            B.iconv2d_dual_brelu(*args)     # also a warm-up launch
+        except B.IcnnError as e:
+            if e.code == B.ICNN_E_UNSUPPORTED:
+                return None
+            raise
+        return ("dual", main[1], args)
+
     def set_input(self, x_raw=None):
         if x_raw is None:
             x_raw = W.input_tensor(self.net, self.seed, self.images)
@@ -82,6 +112,8 @@ class GpuNet:
         for kind, _, args in self.steps:
             if kind == "conv":
                 B.iconv2d_brelu(*args, stream=stream)
+            elif kind == "dual":
+                B.iconv2d_dual_brelu(*args, stream=stream)
             elif kind == "maxpool":
                 B.imaxpool2d_u8(*args, stream=stream)
             else:
@@ -91,6 +123,8 @@ class GpuNet:
         kind, _, args = self.steps[i]
         if kind == "conv":
             B.iconv2d_brelu(*args, stream=stream)
+        elif kind == "dual":
+            B.iconv2d_dual_brelu(*args, stream=stream)
         elif kind == "maxpool":
             B.imaxpool2d_u8(*args, stream=stream)
         else:

@@ -162,3 +162,57 @@ def test_extreme_requant_parameters():
         assert (got == want).all(), (mul, shift)
         got, want = both(x, wt, b, mul=mul, shift=shift, out_mode="linear_s8")
         assert (got == want).all(), (mul, shift)
+
+
+@pytest.mark.parametrize("shape", [(2, 28, 28, 64, 256, 64, 1), (3, 14, 14, 512, 1024, 256, 2), (1, 9, 7, 128, 80, 48, 2),
+                                   (64, 7, 7, 1024, 2048, 512, 1)])
+def test_fused_projection_block_equals_the_two_layers(shape):
+    """iconv2d_dual_brelu == projection conv (raw int32) followed by the main conv that merges it."""
+    import torch
+    from gpu_util import dev
+    from paper_2006_11735_amd import binding as B
+    n, ho, wo, cin_p, cout, cin_m, stride = shape
+    g = rnd(sum(shape))
+    hp, wp_ = ho * stride, wo * stride
+    x_p = g.integers(0, 128, size=(n, hp, wp_, cin_p), dtype=np.uint8)      # block input
+    x_m = g.integers(0, 128, size=(n, ho, wo, cin_m), dtype=np.uint8)       # main path activation
+    w_p = g.integers(-127, 128, size=(cout, 1, 1, cin_p), dtype=np.int8)
+    w_m = g.integers(-127, 128, size=(cout, 1, 1, cin_m), dtype=np.int8)
+    b_p = g.integers(-4096, 4097, size=cout).astype(np.int32)
+    b_m = g.integers(-(1 << 27), 1 << 27, size=cout).astype(np.int32)       # close to the bias contract
+    res_mul, res_shift, mul, shift = 20011, 15, 23187, 27
+    y_p = O.conv2d(x_p, w_p, b_p, stride=stride, pad=0, out_mode="raw_s32")
+    want = O.conv2d(x_m, w_m, b_m, stride=1, pad=0, mul=mul, shift=shift, bound_q=127, res=y_p, res_mode="pre",
+                    res_mul=res_mul, res_shift=res_shift)
+    dm = B.conv_desc(n=n, h=ho, w=wo, cin=cin_m, in_c_stride=cin_m, cout=cout, kh=1, kw=1, out_c_stride=cout, mul=mul,
+                     shift=shift, bound_q=127, res_mode=B.ICNN_RES_PRE, res_dtype=B.ICNN_S32, res_c_stride=cout,
+                     res_mul=res_mul, res_shift=res_shift)
+    dp = B.conv_desc(n=n, h=hp, w=wp_, cin=cin_p, in_c_stride=cin_p, cout=cout, kh=1, kw=1, stride_h=stride,
+                     stride_w=stride, out_c_stride=cout, out_mode=B.ICNN_OUT_RAW_S32)
+    packs = []
+    for d, w in ((dm, w_m), (dp, w_p)):
+        pk = torch.zeros(B.iconv2d_packed_weight_bytes(d), dtype=torch.uint8, device="cuda:0")
+        B.iconv2d_prepack_weights(d, dev(w), pk)
+        packs.append(pk)
+    y = torch.zeros((n, ho, wo, cout), dtype=torch.uint8, device="cuda:0")
+    B.iconv2d_dual_brelu(dm, dev(x_m), packs[0], dev(b_m), dp, dev(x_p), packs[1], dev(b_p), y)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy()
+    assert (got == want).all() and want.max() == 127 and want.min() == 0
+
+
+def test_fused_block_refuses_what_it_cannot_prove_or_run():
+    from paper_2006_11735_amd import binding as B
+    dm = B.conv_desc(n=1, h=8, w=8, cin=64, in_c_stride=64, cout=64, kh=1, kw=1, out_c_stride=64, mul=20000, shift=24,
+                     res_mode=B.ICNN_RES_PRE, res_dtype=B.ICNN_S32, res_c_stride=64, res_mul=1 << 20, res_shift=2)
+    dp = B.conv_desc(n=1, h=8, w=8, cin=64, in_c_stride=64, cout=64, kh=1, kw=1, out_c_stride=64,
+                     out_mode=B.ICNN_OUT_RAW_S32)
+    with pytest.raises(B.IcnnError) as e:        # rescale by 2^18: the sum could leave int32
+        B.iconv2d_dual_brelu(dm, 4096, 8192, 12288, dp, 16384, 20480, 24576, 28672, stream=0)
+    assert e.value.code == B.ICNN_E_UNSUPPORTED
+    dm.res_mul, dm.res_shift = 20011, 15
+    dm.kh = dm.kw = 3
+    dm.pad_h = dm.pad_w = 1
+    with pytest.raises(B.IcnnError) as e:        # 3x3 main layer
+        B.iconv2d_dual_brelu(dm, 4096, 8192, 12288, dp, 16384, 20480, 24576, 28672, stream=0)
+    assert e.value.code == B.ICNN_E_UNSUPPORTED
