@@ -259,7 +259,7 @@ int iconv2d_brelu(const icnn_conv_desc *d, const void *x, const void *w_packed, 
         a.H = g.hp; a.W = g.wp; a.Cin = g.rp; a.in_cs = 4; a.KW = 1; a.ph = 0; a.pw = 0;
         a.in_xor = 0;
         a.x_bytes = (unsigned)(g.ws_bytes - 64);
-        return launched(launch_conv(a, true, false, (hipStream_t)stream), "iconv2d_brelu");
+        return launched(launch_conv(a, true, true, (hipStream_t)stream), "iconv2d_brelu");
     }
     const bool vec_in = aligned16(x) && d->cin % 16 == 0 && d->in_c_stride % 16 == 0;
     return launched(launch_conv(a, vec_in, vec_in, (hipStream_t)stream), "iconv2d_brelu");

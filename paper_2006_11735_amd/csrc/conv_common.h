@@ -210,6 +210,25 @@ __device__ __forceinline__ void init_acc_with_bias(const ConvArgs &a, int co_bas
 
 #define ICNN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | 0x0F70 | (((n) >> 4) << 14))
 
+// Waits until at most `later` stages' worth of this wave's copies (LPS each) are still in
+// flight; the count is an immediate of s_waitcnt (6 bits), hence the switch.
+template <int LPS>
+__device__ __forceinline__ void wait_stages_in_flight(int later)
+{
+    constexpr int kMax = 63 / LPS < 7 ? 63 / LPS : 7;
+    if (later > kMax) later = kMax;
+    switch (later) {
+    case 0: ICNN_WAIT_VMCNT(0); break;
+    case 1: ICNN_WAIT_VMCNT(LPS); break;
+    case 2: ICNN_WAIT_VMCNT(2 * LPS <= 63 ? 2 * LPS : 63); break;
+    case 3: ICNN_WAIT_VMCNT(3 * LPS <= 63 ? 3 * LPS : 63); break;
+    case 4: ICNN_WAIT_VMCNT(4 * LPS <= 63 ? 4 * LPS : 63); break;
+    case 5: ICNN_WAIT_VMCNT(5 * LPS <= 63 ? 5 * LPS : 63); break;
+    case 6: ICNN_WAIT_VMCNT(6 * LPS <= 63 ? 6 * LPS : 63); break;
+    default: ICNN_WAIT_VMCNT(7 * LPS <= 63 ? 7 * LPS : 63); break;
+    }
+}
+
 // floor(n / d) for 0 <= n < 2^31 by multiply-high and shifts (Granlund & Montgomery's
 // round-up method); the host fills `FastDiv` for d.
 __device__ __forceinline__ int fast_div(int n, const FastDiv &d)

@@ -14,6 +14,8 @@
 // never exists in memory.  Tile machinery as in conv_dlds_kernel (pointwise addressing).
 #include "conv_common.h"
 
+#include <type_traits>
+
 namespace icnn {
 
 template <int BM, int BP, int WAVES_M, int WAVES_P>
@@ -42,7 +44,7 @@ __global__ __launch_bounds__(256, 2) void conv_dual_kernel(const ConvArgs a, con
     }
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform
     const int wm = wave % WAVES_M;
     const int wp = wave / WAVES_M;
     const int nstages = a.nstages;
@@ -141,15 +143,16 @@ __global__ __launch_bounds__(256, 2) void conv_dual_kernel(const ConvArgs a, con
         v16i bias_main[TM];     // older than every copy issued below, so the counted waits stay valid
         load_bias_rows<TM>(a, ct * BM + wm * TM * 32, lane >> 5, bias_main);
 
-        for (int s = 0; s < ksteps; ++s) {
-            const int later = min(depth - 1, ksteps - 1 - s);
+        // One K step (see conv_dlds_kernel): FEED steps issue the copies of stage s + depth between
+        // their MFMAs and wait with a compile-time count; the last `depth` steps only drain the ring.
+        auto k_step = [&](int s, auto feed_tag, auto later_tag, int later) {
+            constexpr bool FEED = decltype(feed_tag)::value;
+            constexpr int LATER = decltype(later_tag)::value;
             asm volatile("" ::: "memory");
-            if (later >= 2) ICNN_WAIT_VMCNT(2 * LPS);
-            else if (later == 1) ICNN_WAIT_VMCNT(LPS);
-            else ICNN_WAIT_VMCNT(0);
+            if constexpr (LATER >= 0) ICNN_WAIT_VMCNT(LATER * LPS);
+            else wait_stages_in_flight<LPS>(later);
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-            const bool feed = s + depth < ksteps;
             uint8_t *istage = lds + ibuf * STAGE;
             const uint8_t *S = lds + buf * STAGE;
             v4i af[2][TM], bf[2][TP];
@@ -168,14 +171,14 @@ __global__ __launch_bounds__(256, 2) void conv_dual_kernel(const ConvArgs a, con
 #pragma unroll
                     for (int j = 0; j < TP; ++j) {
                         acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[kq][i], bf[kq][j], acc[i][j], 0, 0, 0);
-                        if (c < LPS) {
-                            if (feed) issue_copy(c, s + depth, istage);
+                        if (FEED && c < LPS) {
+                            issue_copy(c, s + depth, istage);
                             ++c;
                             __builtin_amdgcn_sched_barrier(0);
                         }
                     }
-            if (feed && ++ibuf == nstages) ibuf = 0;
-            if (++buf == nstages) buf = 0;
+            if (FEED) ibuf = ibuf + 1 == nstages ? 0 : ibuf + 1;
+            buf = buf + 1 == nstages ? 0 : buf + 1;
             if (s == kp - 1) {
                 // the projection sum is complete: bring it to the main path's ratio, add the main bias
 #pragma unroll
@@ -186,7 +189,14 @@ __global__ __launch_bounds__(256, 2) void conv_dual_kernel(const ConvArgs a, con
                         for (int r = 0; r < 16; ++r)
                             acc[i][j][r] = (int)rsr64((int64_t)acc[i][j][r] * q.res_mul, q.res_shift) + bias_main[i][r];
             }
-        }
+        };
+        const int main_steps = ksteps - depth;
+        if (depth == 3)
+            for (int s = 0; s < main_steps; ++s) k_step(s, std::true_type{}, std::integral_constant<int, 2>{}, 0);
+        else
+            for (int s = 0; s < main_steps; ++s) k_step(s, std::true_type{}, std::integral_constant<int, -1>{}, depth - 1);
+        for (int s = main_steps; s < ksteps; ++s)
+            k_step(s, std::false_type{}, std::integral_constant<int, -1>{}, ksteps - 1 - s);
 
         const int co_wave = ct * BM + wm * TM * 32;
         const int pix_wave = pt * BP + wp * TP * 32;
@@ -215,7 +225,8 @@ static hipError_t launch_dual_cfg(const ConvArgs &a0, const ProjArgs &q, hipStre
     ConvArgs a = a0;
     if (!finish_args(a, BM, BP)) return hipErrorInvalidValue;
     const int ksteps = a.ksteps + q.ksteps;
-    a.nstages = ksteps + 1 < 4 ? ksteps + 1 : 4;
+    const int max_stages = 4;
+    a.nstages = ksteps + 1 < max_stages ? ksteps + 1 : max_stages;
     if (a.nstages < 2) a.nstages = 2;
     a.div_howo = make_fast_div((unsigned)(a.Ho * a.Wo));
     a.div_wo = make_fast_div((unsigned)a.Wo);
@@ -223,6 +234,15 @@ static hipError_t launch_dual_cfg(const ConvArgs &a0, const ProjArgs &q, hipStre
     a.n_vtiles = 8 * a.per_xcd;
     const int slots = 256 * 2;
     const dim3 grid((unsigned)(a.n_vtiles < slots ? a.n_vtiles : slots)), block(256);
+    if (lds_bytes > 64 * 1024) {
+        static bool raised = false;                      // once per kernel: allow > 64 KiB dynamic LDS
+        if (!raised) {
+            const hipError_t e = hipFuncSetAttribute((const void *)conv_dual_kernel<BM, BP, WAVES_M, WAVES_P>,
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
     hipLaunchKernelGGL((conv_dual_kernel<BM, BP, WAVES_M, WAVES_P>), grid, block, lds_bytes, st, a, q);
     return hipGetLastError();
 }

@@ -20,6 +20,7 @@
 #include "conv_common.h"
 
 #include <cstdlib>
+#include <type_traits>
 
 namespace icnn {
 
@@ -63,7 +64,7 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps LDS targets in scalar registers
     const int wm = wave % WAVES_M;
     const int wp = wave / WAVES_M;
     const int nstages = a.nstages;
@@ -223,18 +224,17 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
 #pragma unroll
             for (int j = 0; j < TP; ++j) acc[i][j] = bias_next[i];
 
-        for (int s = 0; s < ksteps; ++s) {
-            // stage s has landed once at most `later` younger stages' copies remain in flight
-            const int later = min(depth - 1, ksteps - 1 - s);
+        // One K step: wait for its stage, barrier, fragments LDS -> registers, MFMAs.  FEED: the
+        // copies of stage s + depth are issued between the MFMAs, so the matrix cores work while
+        // the wave computes addresses and the memory pipeline accepts them.
+        auto k_step = [&](int s, auto feed_tag, auto later_tag, int later) {
+            constexpr bool FEED = decltype(feed_tag)::value;
+            constexpr int LATER = decltype(later_tag)::value;      // >= 0: known at compile time
             asm volatile("" ::: "memory");
-            if (later >= 2) ICNN_WAIT_VMCNT(2 * LPS);
-            else if (later == 1) ICNN_WAIT_VMCNT(LPS);
-            else ICNN_WAIT_VMCNT(0);
+            if constexpr (LATER >= 0) ICNN_WAIT_VMCNT(LATER * LPS);
+            else wait_stages_in_flight<LPS>(later);
             __builtin_amdgcn_s_barrier();  // every wave's part of stage s is in LDS; the slot of step s-1 is drained
             asm volatile("" ::: "memory");
-            // the copies of stage s + depth are issued between this step's MFMAs, so the matrix
-            // cores work while the wave computes addresses and the memory pipeline accepts them
-            const bool feed = s + depth < ksteps;
             uint8_t *istage = lds + ibuf * STAGE;
             const uint8_t *S = lds + buf * STAGE;
             v4i af[2][TM], bf[2][TP];
@@ -253,21 +253,31 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
 #pragma unroll
                     for (int j = 0; j < TP; ++j) {
                         acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[kq][i], bf[kq][j], acc[i][j], 0, 0, 0);
-                        if (c < LPS) {
-                            if (feed) issue_copy(c, s + depth, istage);
+                        if (FEED && c < LPS) {
+                            issue_copy(c, s + depth, istage);
                             ++c;
                             __builtin_amdgcn_sched_barrier(0);
                         }
                     }
+            if (FEED) {
 #pragma unroll
-            for (int cc = 2 * TM * TP; cc < LPS; ++cc)     // narrow tiles: more copies than MFMAs
-                if (feed) issue_copy(cc, s + depth, istage);
-            if (feed) {
+                for (int cc = 2 * TM * TP; cc < LPS; ++cc) issue_copy(cc, s + depth, istage);   // narrow tiles
                 advance_k();
-                if (++ibuf == nstages) ibuf = 0;
+                ibuf = ibuf + 1 == nstages ? 0 : ibuf + 1;
             }
-            if (++buf == nstages) buf = 0;
-        }
+            buf = buf + 1 == nstages ? 0 : buf + 1;
+        };
+        // steady state: every step feeds the ring and waits with depth - 1 younger stages in flight;
+        // the last `depth` steps only drain it
+        const int main_steps = ksteps - depth;
+        if (depth == 3)
+            for (int s = 0; s < main_steps; ++s) k_step(s, std::true_type{}, std::integral_constant<int, 2>{}, 0);
+        else if (depth == 2)
+            for (int s = 0; s < main_steps; ++s) k_step(s, std::true_type{}, std::integral_constant<int, 1>{}, 0);
+        else
+            for (int s = 0; s < main_steps; ++s) k_step(s, std::true_type{}, std::integral_constant<int, -1>{}, depth - 1);
+        for (int s = main_steps; s < ksteps; ++s)
+            k_step(s, std::false_type{}, std::integral_constant<int, -1>{}, ksteps - 1 - s);
 
         // ---- the next tile's leading stages and bias travel while this tile's epilogue runs.
         // They go to ring slots other than the one of the last K step, which slower waves may
