@@ -114,9 +114,31 @@ __device__ __forceinline__ void epilogue_vec(const ConvArgs &a, const v16i &acc,
 
 // Epilogue of a wave's TM x TP accumulator tiles; the mode switch is outside the
 // tile loops so each mode is straight-line code.
+// True when the call's skip operand is 8-bit and the vector epilogue handles it: then the operands of
+// a wave's tiles can be fetched ahead of the K loop (prefetch_res8) and handed to epilogue_tiles.
+__device__ __forceinline__ bool res8_applies(const ConvArgs &a)
+{
+    return a.epi_vec && !(a.Cout & 15) && a.res_mode != 0 && a.res_dtype != 2;
+}
+template <int TM, int TP>
+__device__ __forceinline__ void prefetch_res8(const ConvArgs &a, int co_wave, int pix_wave, int lane, v4i (&res8)[TM][TP])
+{
+    if (!res8_applies(a)) return;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int co0 = co_wave + i * 32 + (lane >> 5) * 16;
+#pragma unroll
+        for (int j = 0; j < TP; ++j) {
+            const int p = pix_wave + j * 32 + (lane & 31);
+            if (co0 < a.Cout && p < a.M)
+                res8[i][j] = *(const v4i *)((const uint8_t *)a.res + ((size_t)p * a.res_cs + co0));
+        }
+    }
+}
+// res8: the 8-bit skip operands fetched by prefetch_res8 for the same tile (ignored otherwise)
 template <int TM, int TP>
 __device__ __forceinline__ void epilogue_tiles(const ConvArgs &a, const v16i (&acc)[TM][TP], int co_wave, int pix_wave,
-                                               int lane)
+                                               int lane, const v4i (&res8)[TM][TP])
 {
     const int half = lane >> 5;
     auto for_tiles = [&](auto fn) {
@@ -137,14 +159,6 @@ __device__ __forceinline__ void epilogue_tiles(const ConvArgs &a, const v16i (&a
         });
         return;
     }
-    // 8-bit skip operands of all tiles are fetched before the first store (stores may alias
-    // them as far as the compiler knows, which would otherwise serialise the fetches)
-    v4i res8[TM][TP];
-    if (a.res_mode != 0 && a.res_dtype != 2) {
-        for_tiles([&](const v16i &, int p, int co0, int i, int j) {
-            res8[i][j] = *(const v4i *)((const uint8_t *)a.res + ((size_t)p * a.res_cs + co0));
-        });
-    }
     switch (a.epi_mode) {
 #define ICNN_EPI_CASE(RES, RQ)                                                                      \
     case RES * 3 + RQ:                                                                              \
@@ -159,7 +173,15 @@ __device__ __forceinline__ void epilogue_tiles(const ConvArgs &a, const v16i (&a
     default: break;
     }
 }
-
+// for callers without a K loop to hide the fetch behind: fetch, then finish
+template <int TM, int TP>
+__device__ __forceinline__ void epilogue_tiles(const ConvArgs &a, const v16i (&acc)[TM][TP], int co_wave, int pix_wave,
+                                               int lane)
+{
+    v4i res8[TM][TP];
+    prefetch_res8<TM, TP>(a, co_wave, pix_wave, lane, res8);
+    epilogue_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane, res8);
+}
 // Maps the hardware workgroup id to a tile.  Workgroups are dealt round-robin to the
 // 8 XCDs (each with its own L2); giving XCD x the contiguous tile range
 // [x*per_xcd, (x+1)*per_xcd) keeps the cout tiles of one pixel tile, and neighbouring

@@ -213,8 +213,8 @@ __global__ __launch_bounds__(256, 2) void conv_dual_kernel(const ConvArgs a, con
         }
         epilogue_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane);
         if (!more) break;
-        asm volatile("" ::: "memory");
-        ICNN_WAIT_VMCNT(0);     // stores retire out of order with loads: drain before counting again
+        // no drain: the stores are younger than the copies the next K loop waits for, and a counted
+        // wait only gets stricter with younger operations in flight
     }
 #endif
 }

@@ -223,6 +223,11 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TP; ++j) acc[i][j] = bias_next[i];
+        // an 8-bit skip operand travels while the K loop runs
+        const int co_wave = ct * BM + wm * TM * 32;
+        const int pix_wave = pt * BP + wp * TP * 32;
+        v4i res8[TM][TP];
+        prefetch_res8<TM, TP>(a, co_wave, pix_wave, lane, res8);
 
         // One K step: wait for its stage, barrier, fragments LDS -> registers, MFMAs.  FEED: the
         // copies of stage s + depth are issued between the MFMAs, so the matrix cores work while
@@ -278,12 +283,13 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
             for (int s = 0; s < main_steps; ++s) k_step(s, std::true_type{}, std::integral_constant<int, -1>{}, depth - 1);
         for (int s = main_steps; s < ksteps; ++s)
             k_step(s, std::false_type{}, std::integral_constant<int, -1>{}, ksteps - 1 - s);
+        // The last step waited for everything in flight (the skip operands included); saying so
+        // here costs nothing and spares the epilogue a wait that would also cover the copies below.
+        ICNN_WAIT_VMCNT(0);
 
         // ---- the next tile's leading stages and bias travel while this tile's epilogue runs.
         // They go to ring slots other than the one of the last K step, which slower waves may
         // still be reading (every wave has passed that step's barrier, so all older slots are free).
-        const int co_wave = ct * BM + wm * TM * 32;
-        const int pix_wave = pt * BP + wp * TP * 32;
         vtile += gridDim.x;
         const bool more = vtile < a.n_vtiles && tile_of(vtile, ct, pt);
         if (more) {
@@ -294,12 +300,12 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
             }
             load_bias_rows<TM>(a, ct * BM + wm * TM * 32, lane >> 5, bias_next);
         }
-        epilogue_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane);
+        epilogue_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane, res8);
         if (!more) break;
-        // Stores and loads retire out of order with respect to each other, so the counted waits of
-        // the next K loop are only valid once this tile's stores have drained.
-        asm volatile("" ::: "memory");
-        ICNN_WAIT_VMCNT(0);
+        // This tile's stores (and the skip operands of the next) are younger than the stage copies the
+        // next K loop waits for.  Loads retire in order among themselves, so a counted wait that leaves
+        // n operations in flight still proves every load older than the n youngest has landed: younger
+        // operations of any kind make the waits stricter, never unsafe, and no drain is needed here.
     }
 #endif
 }
