@@ -102,6 +102,8 @@ def main():
     ap.add_argument("--config", default="cfg3", help="workload (cfg3 = ResNet-50-shaped, batch 64)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layer-reps", type=int, default=20)
+    ap.add_argument("--per-channel", action="store_true",
+                    help="time the variant with one (mul, shift) per output channel instead of the per-layer workload")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 256 MiB device copies (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -118,6 +120,9 @@ def main():
     net = W.CONFIGS[args.config]()
     seed = 0
     calib_path = os.path.join(ROOT, "workloads", "calib", "%s_seed%d.json" % (args.config, seed))
+    pc_path = calib_path.replace(".json", "_pc.json")
+    if args.per_channel:
+        calib_path = pc_path
     calib = json.load(open(calib_path))
     images = net["buffers"]["raw"]["shape"][0]
     g = GpuNet(net, seed, calib)
@@ -165,8 +170,9 @@ def main():
     conv_ops = conv_ms = conv_bytes = 0.0
     other_ms = 0.0
     rows = []
-    for (kind, op, _), ms in zip(g.steps, layer_ms):
-        if kind not in ("conv", "dual"):
+    for step, ms in zip(g.steps, layer_ms):
+        kind, op = step[0], step[1]
+        if kind not in ("conv", "conv_pc", "dual"):
             other_ms += ms
             rows.append({"name": op["dst"], "kind": kind, "ms": ms})
             continue
@@ -218,6 +224,25 @@ def main():
                      "algorithmic_gop_per_step": conv_ops / 1e9,
                      "algorithmic_gb_per_step": conv_bytes / 1e9},
     }
+    if args.per_channel:
+        result["config"]["workload"] += "; per-output-channel requantisation (iconv2d_brelu_pc, type-2 blocks unfused)"
+    elif os.path.exists(pc_path):
+        # the same network with one (mul, shift) and skip rescale per output channel
+        g_pc = GpuNet(net, seed, json.load(open(pc_path)))
+        g_pc.set_input()
+        for _ in range(5):
+            g_pc.run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(30):
+            g_pc.run()
+        torch.cuda.synchronize()
+        ms_pc = (time.perf_counter() - t0) / 30 * 1e3
+        result["per_channel_variant"] = {"ms_per_step": ms_pc, "images_per_s": images / (ms_pc * 1e-3),
+                                         "launches_per_step": len(g_pc.steps),
+                                         "note": "iconv2d_brelu_pc on every BReLU layer; projection convs run unfused"}
+        log("per-channel variant: %.3f ms per step (%d launches)" % (ms_pc, len(g_pc.steps)))
+        del g_pc
     result["iadd_rescale"] = add_bandwidth(torch)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(net, calib, seed)

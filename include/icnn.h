@@ -144,6 +144,34 @@ int iconv2d_brelu(const icnn_conv_desc *desc, const void *x, const void *w_packe
                   void *stream);
 
 /*
+ * Per-output-channel requantisation (Section 3.4.3: with one weight step per output channel
+ * before batch normalisation is merged, every output channel has its own ratio, so the
+ * multiplier and shift of the requantisation equation of Section 3.2.1, and of the skip
+ * rescale of Section 4.1, become vectors over the output channels).
+ * Device arrays of cout int32 each, 4-byte aligned (16-byte alignment selects vector loads),
+ * owned by the caller and read during the call's kernels:
+ *   mul[c] in [1, 2^31-1], shift[c] in [0, 62]          (ignored for ICNN_OUT_RAW_S32)
+ *   res_mul[c], res_shift[c], same domains              (NULL iff res_mode == NONE)
+ * The values live in device memory, so the host cannot check their domains: values outside
+ * them give unspecified output bytes for that channel, never a fault.
+ */
+typedef struct {
+    const int32_t *mul;
+    const int32_t *shift;
+    const int32_t *res_mul;
+    const int32_t *res_shift;
+} icnn_channel_params;
+
+/* iconv2d_brelu with the layer's mul, shift, res_mul and res_shift replaced channel by channel
+ * by *pc (the descriptor's own four values must still be valid, e.g. 1 and 0, and are not
+ * used).  Everything else, including bound_q / lo / hi, the error codes and the alignment
+ * rules, is as for iconv2d_brelu.  A raw int32 output without a skip operand has nothing per
+ * channel and is rejected with ICNN_E_PARAM. */
+int iconv2d_brelu_pc(const icnn_conv_desc *desc, const void *x, const void *w_packed,
+                     const int32_t *bias, const icnn_channel_params *pc, const void *res,
+                     void *y, void *workspace, void *stream);
+
+/*
  * A residual block's last layer together with its projection skip, as one launch (Section
  * 4.1, the skip connection "after convolution": the projection convolves the quantised block
  * input, its int32 result is rescaled to the main path's ratio and added before BReLU).

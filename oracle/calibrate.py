@@ -62,6 +62,12 @@ def percentile_999(values, absolute=False):
     return max(1, int(np.partition(v, k)[k]))
 
 
+def percentile_999_per_channel(values, absolute=False):
+    """The same statistic for every channel (last axis) on its own."""
+    v = np.asarray(values)
+    return [percentile_999(v[..., c], absolute) for c in range(v.shape[-1])]
+
+
 def sync_concat(h_ri, ratio_y, max_int=MAX_INT):
     """Algorithm 2 for N branches given each branch's bound h_ri[i] (integer, in its
     own Y domain) and ratio_Y[i].  Returns per-branch (mul, shift, bound_q) and the

@@ -31,6 +31,13 @@
  *   - Pooling: max over the valid window; global average is a sum followed by
  *     the same multiply-shift-round-clamp with mul / 2^shift ~ 1 / (H*W).
  *
+ *   - Section 3.4.3 trains with one weight step per output channel before batch
+ *     normalisation is merged, which leaves every output channel with its own
+ *     ratio; orc_conv2d_pc therefore takes the requantisation pair (and the skip
+ *     rescale pair) per output channel.  The paper does not spell this out; the
+ *     arithmetic per channel is the per-layer one.  Pinned by running the
+ *     per-layer function once per channel.
+ *
  * Pins (tests marked "not gpu"): the rounding rule against exact rationals,
  * hand-computed cases, the convolution against a seven-loop brute force, a
  * float64 library convolution and an int64 matrix product, shifted-copy and
@@ -111,8 +118,14 @@ static void out_range(int out_mode, int bound_q, int lo, int hi, int64_t *rlo, i
  * out_c_stride; channel co lands at out_c_offset + co (this is how branches of
  * a concatenation share a buffer); elements are uint8, int8 or int32 by out_mode.
  */
-int orc_conv2d(const orc_conv_params *p, const void *x, const int8_t *w,
-               const int32_t *bias, const void *res, void *out)
+/*
+ * mul_c, shift_c, res_mul_c, res_shift_c: int32 [cout] each, or NULL to use the
+ * per-layer value of *p for that quantity (Section 3.4.3: per-channel ratios).
+ */
+int orc_conv2d_pc(const orc_conv_params *p, const void *x, const int8_t *w,
+                  const int32_t *bias, const void *res, void *out,
+                  const int32_t *mul_c, const int32_t *shift_c,
+                  const int32_t *res_mul_c, const int32_t *res_shift_c)
 {
     if (!p || !x || !w || !bias || !out) return ORC_E_ARG;
     if (p->res_mode != ORC_RES_NONE && !res) return ORC_E_ARG;
@@ -155,7 +168,8 @@ int orc_conv2d(const orc_conv_params *p, const void *x, const int8_t *w,
                     int64_t skip = 0;
                     if (p->res_mode != ORC_RES_NONE) {
                         int64_t r = load_elem(res, pix * p->res_c_stride + co, p->res_dtype);
-                        skip = orc_rsr(r * (int64_t)p->res_mul, p->res_shift);
+                        skip = orc_rsr(r * (int64_t)(res_mul_c ? res_mul_c[co] : p->res_mul),
+                                       res_shift_c ? res_shift_c[co] : p->res_shift);
                     }
                     int64_t t = (p->res_mode == ORC_RES_PRE) ? sat32(y + skip) : sat32(y);
                     const size_t oi = pix * p->out_c_stride + p->out_c_offset + co;
@@ -163,7 +177,7 @@ int orc_conv2d(const orc_conv_params *p, const void *x, const int8_t *w,
                         ((int32_t *)out)[oi] = (int32_t)t;
                         continue;
                     }
-                    int64_t q = orc_requant(t, p->mul, p->shift);
+                    int64_t q = orc_requant(t, mul_c ? mul_c[co] : p->mul, shift_c ? shift_c[co] : p->shift);
                     if (p->res_mode == ORC_RES_POST) q += skip;
                     q = clamp64(q, rlo, rhi);
                     if (p->out_mode == ORC_OUT_LINEAR_S8) ((int8_t *)out)[oi] = (int8_t)q;
@@ -173,6 +187,13 @@ int orc_conv2d(const orc_conv_params *p, const void *x, const int8_t *w,
         }
     }
     return status;
+}
+
+/* The per-layer form: one (mul, shift) and one skip rescale for all channels. */
+int orc_conv2d(const orc_conv_params *p, const void *x, const int8_t *w,
+               const int32_t *bias, const void *res, void *out)
+{
+    return orc_conv2d_pc(p, x, w, bias, res, out, NULL, NULL, NULL, NULL);
 }
 
 /*

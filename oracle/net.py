@@ -30,9 +30,13 @@ def _conv(op, bufs, w, bias, cal, out, out_mode=None, use_res=True):
     kw = dict(stride=op["stride"], pad=op["pad"], in_sub128=op["in_sub128"], cin=op["cin"],
               out_mode=om, mul=cal.get("mul", 1), shift=cal.get("shift", 0),
               bound_q=cal.get("bound_q", K.MAX_INT), lo=cal.get("lo", 0), hi=cal.get("hi", 255))
+    if "mul_c" in cal:
+        kw.update(mul_c=cal["mul_c"], shift_c=cal["shift_c"])
     if op["res"] is not None and use_res:
         kw.update(res=bufs[op["res"]], res_mode=op["res_mode"],
                   res_mul=cal.get("res_mul", 1), res_shift=cal.get("res_shift", 0))
+        if "res_mul_c" in cal:
+            kw.update(res_mul_c=cal["res_mul_c"], res_shift_c=cal["res_shift_c"])
     if out is None:
         return O.conv2d(bufs[op["src"]], w, bias, **kw)
     return O.conv2d(bufs[op["src"]], w, bias, out=out, out_c_offset=op["dst_c_offset"], **kw)
@@ -58,10 +62,14 @@ def run(net, seed, calib, images=None, x_raw=None):
     return bufs
 
 
-def calibrate(net, seed):
+def calibrate(net, seed, per_channel=False):
     """Returns (calib, buffers on the calibration images).
 
     calib = {"conv": {name: {...integers...}}, "avgpool": {dst: {...}}, "ratio": {...}}
+    per_channel: BReLU layers and their residual merges get one (mul, shift) and one skip
+    rescale per output channel ("mul_c", "shift_c", "res_mul_c", "res_shift_c"), each from
+    that channel's own statistic (Section 3.4.3: one weight step per output channel).
+    Concatenated branches, regression outputs and raw int32 outputs stay per layer.
     """
     n_img = net["calib_images"]
     bufs = {"raw": W.input_tensor(net, seed, n_img)}
@@ -119,6 +127,14 @@ def calibrate(net, seed):
             else:
                 h_skip = K.MAX_INT
             cal["res_mul"], cal["res_shift"] = K.mul_shift(h_skip, h_main)
+            if per_channel and op["out_mode"] == "brelu":
+                cout = y.shape[-1]
+                hm = K.percentile_999_per_channel(y)
+                hs = (K.percentile_999_per_channel(bufs[op["res"]][..., :cout]) if op["res_dtype"] == "s32"
+                      else [K.MAX_INT] * cout)
+                pairs = [K.mul_shift(a, b) for a, b in zip(hs, hm)]
+                cal["res_mul_c"] = [m for m, _ in pairs]
+                cal["res_shift_c"] = [s for _, s in pairs]
         if op["out_mode"] == "raw_s32":
             calib["conv"][op["name"]] = cal
             _conv(op, bufs, w, b, cal, bufs[op["dst"]])
@@ -136,6 +152,10 @@ def calibrate(net, seed):
             h = K.percentile_999(t)
             m, s = K.bound_params(h)
             cal.update(mul=m, shift=s, bound_q=K.MAX_INT, h_ri=h)
+            if per_channel:
+                pairs = [K.bound_params(hc) for hc in K.percentile_999_per_channel(t)]
+                cal["mul_c"] = [mc for mc, _ in pairs]
+                cal["shift_c"] = [sc for _, sc in pairs]
             calib["conv"][op["name"]] = cal
             _conv(op, bufs, w, b, cal, bufs[op["dst"]])
             ratio[op["dst"]] = ry * m / (1 << s)
@@ -144,29 +164,34 @@ def calibrate(net, seed):
     return calib, bufs
 
 
-def stored_calib_path(cfg, seed):
+def stored_calib_path(cfg, seed, per_channel=False):
     import os
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    return os.path.join(root, "workloads", "calib", "%s_seed%d.json" % (cfg, seed))
+    return os.path.join(root, "workloads", "calib", "%s_seed%d%s.json" % (cfg, seed, "_pc" if per_channel else ""))
 
 
-def write_stored_calib(cfg, seed):
+def write_stored_calib(cfg, seed, per_channel=False):
     """Calibrate config `cfg` with the oracle and store the integers for bench and tests."""
     import json
     net = W.CONFIGS[cfg]()
-    calib, _ = calibrate(net, seed)
+    calib, _ = calibrate(net, seed, per_channel)
     calib["net"] = net["name"]
     calib["seed"] = seed
     calib["written_by"] = "oracle/net.py write_stored_calib (calls only oracle/)"
-    path = stored_calib_path(cfg, seed)
+    path = stored_calib_path(cfg, seed, per_channel)
     with open(path, "w") as f:
-        json.dump(calib, f, indent=1, sort_keys=True)
+        if per_channel:
+            json.dump(calib, f, sort_keys=True, separators=(",", ":"))
+        else:
+            json.dump(calib, f, indent=1, sort_keys=True)
     return path
 
 
 if __name__ == "__main__":
     import sys
     import time
-    for name in sys.argv[1:] or ["cfg0", "cfg1", "cfg2", "cfg3", "cfg4"]:
+    # `python -m oracle.net [cfgN ...]` writes the per-layer files, `cfgN:pc` the per-channel one
+    for name in sys.argv[1:] or ["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "cfg3:pc"]:
         t0 = time.time()
-        print(write_stored_calib(name, 0), "%.1fs" % (time.time() - t0), flush=True)
+        cfg, _, kind = name.partition(":")
+        print(write_stored_calib(cfg, 0, kind == "pc"), "%.1fs" % (time.time() - t0), flush=True)

@@ -46,6 +46,8 @@ def lib():
         L.orc_requant.argtypes = [C.c_int64, C.c_int32, C.c_int32]
         L.orc_conv2d.restype = C.c_int
         L.orc_conv2d.argtypes = [C.POINTER(ConvParams)] + [C.c_void_p] * 5
+        L.orc_conv2d_pc.restype = C.c_int
+        L.orc_conv2d_pc.argtypes = [C.POINTER(ConvParams)] + [C.c_void_p] * 9
         L.orc_add_rescale.restype = C.c_int
         L.orc_add_rescale.argtypes = [C.c_int64, C.c_int32,
                                       C.c_void_p, C.c_int32, C.c_int32,
@@ -96,11 +98,14 @@ def conv_out_hw(h, w, kh, kw, stride, pad):
 
 def conv2d(x, w, bias, *, stride=1, pad=0, mul=1, shift=0, bound_q=127, lo=0, hi=255,
            out_mode="brelu", res=None, res_mode="none", res_mul=1, res_shift=0,
-           in_sub128=False, cin=None, out=None, out_c_offset=0):
+           in_sub128=False, cin=None, out=None, out_c_offset=0,
+           mul_c=None, shift_c=None, res_mul_c=None, res_shift_c=None):
     """One integer conv layer; returns the output buffer [N,Ho,Wo,Ctot].
 
     x: uint8 or int8 [N,H,W,Cbuf]; the first `cin` channels of each pixel are read.
     out: optional existing buffer whose channels out_c_offset..+cout are written.
+    mul_c, shift_c, res_mul_c, res_shift_c: optional int32 [cout] arrays that replace the
+    per-layer value of the same name channel by channel (Section 3.4.3).
     """
     x = np.ascontiguousarray(x)
     w = np.ascontiguousarray(w, dtype=np.int8)
@@ -135,7 +140,17 @@ def conv2d(x, w, bias, *, stride=1, pad=0, mul=1, shift=0, bound_q=127, lo=0, hi
         p.res_dtype, p.res_c_stride = _DT[res.dtype], res.shape[3]
         p.res_mul, p.res_shift = int(res_mul), int(res_shift)
         rp = _ptr(res)
-    rc = lib().orc_conv2d(C.byref(p), _ptr(x), _ptr(w), _ptr(bias), rp, _ptr(out))
+    pcs = []
+    for arr in (mul_c, shift_c, res_mul_c, res_shift_c):
+        if arr is not None:
+            arr = np.ascontiguousarray(arr, dtype=np.int32)
+            assert arr.shape == (cout,)
+        pcs.append(arr)
+    if any(a is not None for a in pcs):
+        rc = lib().orc_conv2d_pc(C.byref(p), _ptr(x), _ptr(w), _ptr(bias), rp, _ptr(out),
+                                 *[None if a is None else _ptr(a) for a in pcs])
+    else:
+        rc = lib().orc_conv2d(C.byref(p), _ptr(x), _ptr(w), _ptr(bias), rp, _ptr(out))
     if rc != 0:
         raise ArithmeticError("orc_conv2d failed: %d" % rc)
     return out

@@ -29,6 +29,10 @@ class icnn_add_desc(C.Structure):
         "a_dtype", "b_dtype", "out_mode", "b_mul", "b_shift", "mul", "shift", "lo", "hi")]
 
 
+class icnn_channel_params(C.Structure):
+    _fields_ = [(k, C.c_void_p) for k in ("mul", "shift", "res_mul", "res_shift")]
+
+
 class IcnnError(RuntimeError):
     def __init__(self, code, msg):
         super().__init__("icnn error %d: %s" % (code, msg))
@@ -49,6 +53,8 @@ _lib.iconv2d_workspace_bytes.argtypes = [C.POINTER(icnn_conv_desc), C.POINTER(C.
 _lib.iconv2d_packed_weight_bytes.argtypes = [C.POINTER(icnn_conv_desc), C.POINTER(C.c_size_t)]
 _lib.iconv2d_prepack_weights.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp]
 _lib.iconv2d_brelu.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.iconv2d_brelu_pc.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp, C.POINTER(icnn_channel_params), _vp, _vp, _vp,
+                                  _vp]
 _lib.iconv2d_dual_brelu.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp, C.POINTER(icnn_conv_desc), _vp, _vp, _vp,
                                     _vp, _vp]
 _lib.iadd_rescale.argtypes = [C.POINTER(icnn_add_desc), _vp, _vp, _vp, _vp]
@@ -60,7 +66,7 @@ _lib.irenormalize_u8.argtypes = [_i64, _vp, _vp, _vp]
 
 EXPORTS = ["icnn_version", "icnn_last_error", "iconv2d_validate", "iconv2d_out_hw",
            "iconv2d_workspace_bytes", "iconv2d_packed_weight_bytes", "iconv2d_prepack_weights",
-           "iconv2d_brelu", "iconv2d_dual_brelu", "iadd_rescale", "iconcat", "imaxpool2d_u8", "iavgpool_global_u8",
+           "iconv2d_brelu", "iconv2d_brelu_pc", "iconv2d_dual_brelu", "iadd_rescale", "iconcat", "imaxpool2d_u8", "iavgpool_global_u8",
            "irenormalize_u8"]
 
 
@@ -148,6 +154,18 @@ def iconv2d_prepack_weights(desc, w_ohwi, w_packed, stream=None):
 def iconv2d_brelu(desc, x, w_packed, bias, res, y, workspace=None, stream=None):
     return _check(_lib.iconv2d_brelu(C.byref(desc), _ptr(x), _ptr(w_packed), _ptr(bias), _ptr(res),
                                      _ptr(y), _ptr(workspace), _stream(stream)))
+
+
+def channel_params(mul=None, shift=None, res_mul=None, res_shift=None):
+    """icnn_channel_params over device int32 tensors (or addresses); the caller keeps them alive."""
+    pc = icnn_channel_params()
+    pc.mul, pc.shift, pc.res_mul, pc.res_shift = _ptr(mul), _ptr(shift), _ptr(res_mul), _ptr(res_shift)
+    return pc
+
+
+def iconv2d_brelu_pc(desc, x, w_packed, bias, pc, res, y, workspace=None, stream=None):
+    return _check(_lib.iconv2d_brelu_pc(C.byref(desc), _ptr(x), _ptr(w_packed), _ptr(bias), C.byref(pc), _ptr(res),
+                                        _ptr(y), _ptr(workspace), _stream(stream)))
 
 
 def iconv2d_dual_brelu(main_desc, x_main, w_main_packed, bias_main, proj_desc, x_proj, w_proj_packed, bias_proj, y,

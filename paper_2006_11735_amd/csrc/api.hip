@@ -218,6 +218,8 @@ static int fill_conv_args(const icnn_conv_desc *d, const ConvGeom &g, const void
         a.div_howo = a.div_wo = FastDiv{0, 0, 0};
     }
     a.n_tiles = a.per_xcd = a.n_vtiles = 0;
+    a.pc_mul = a.pc_shift = a.pc_res_mul = a.pc_res_shift = nullptr;
+    a.pc_vec = 0;
     a.rq_fast = 0;
     a.mul_hi = 0;
     if (d->out_mode != ICNN_OUT_RAW_S32 && a.shift >= 1 && a.shift <= 32 &&
@@ -238,8 +240,9 @@ static int fill_conv_args(const icnn_conv_desc *d, const ConvGeom &g, const void
     return ICNN_OK;
 }
 
-int iconv2d_brelu(const icnn_conv_desc *d, const void *x, const void *w_packed, const int32_t *bias,
-                  const void *res, void *y, void *workspace, void *stream)
+static int conv_layer(const icnn_conv_desc *d, const void *x, const void *w_packed, const int32_t *bias,
+                      const icnn_channel_params *pc, const void *res, void *y, void *workspace, void *stream,
+                      const char *what)
 {
     ConvGeom g;
     int rc = check_conv(d, &g);
@@ -249,20 +252,51 @@ int iconv2d_brelu(const icnn_conv_desc *d, const void *x, const void *w_packed, 
     ConvArgs a;
     rc = fill_conv_args(d, g, x, w_packed, bias, res, y, a);
     if (rc) return rc;
+    if (pc) {
+        const bool requant = d->out_mode != ICNN_OUT_RAW_S32;
+        const bool skip = d->res_mode != ICNN_RES_NONE;
+        if (requant && (!pc->mul || !pc->shift)) return fail(ICNN_E_NULL, "per-channel mul and shift must not be NULL");
+        if (skip && (!pc->res_mul || !pc->res_shift))
+            return fail(ICNN_E_NULL, "per-channel res_mul and res_shift must not be NULL when res_mode is set");
+        if (!requant && !skip) return fail(ICNN_E_PARAM, "a raw int32 output without a skip operand has no per-channel parameter");
+        a.pc_mul = requant ? pc->mul : nullptr;
+        a.pc_shift = requant ? pc->shift : nullptr;
+        a.pc_res_mul = skip ? pc->res_mul : nullptr;
+        a.pc_res_shift = skip ? pc->res_shift : nullptr;
+        a.pc_vec = 1;
+        const int32_t *arrs[4] = {a.pc_mul, a.pc_shift, a.pc_res_mul, a.pc_res_shift};
+        for (const int32_t *q : arrs) {
+            if ((uintptr_t)q & 3) return fail(ICNN_E_ALIGN, "per-channel arrays must be 4-byte aligned");
+            if (q && !aligned16(q)) a.pc_vec = 0;
+        }
+    }
     if (g.rp) {
         // small cin: pad and re-normalise x into the workspace, then run the layer as a kh x 1
         // convolution with "rp channels" over that copy (see pad_small_cin_kernel)
         const hipError_t e = launch_pad_small_cin(a.x, workspace, d->n, d->h, d->w, d->cin, d->in_c_stride, d->pad_h,
                                                   d->pad_w, g.hp, g.wp, a.in_xor, (hipStream_t)stream);
-        if (e != hipSuccess) return launched(e, "iconv2d_brelu (input padding)");
+        if (e != hipSuccess) return launched(e, what);
         a.x = (const uint8_t *)workspace;
         a.H = g.hp; a.W = g.wp; a.Cin = g.rp; a.in_cs = 4; a.KW = 1; a.ph = 0; a.pw = 0;
         a.in_xor = 0;
         a.x_bytes = (unsigned)(g.ws_bytes - 64);
-        return launched(launch_conv(a, true, true, (hipStream_t)stream), "iconv2d_brelu");
+        return launched(launch_conv(a, true, true, (hipStream_t)stream), what);
     }
     const bool vec_in = aligned16(x) && d->cin % 16 == 0 && d->in_c_stride % 16 == 0;
-    return launched(launch_conv(a, vec_in, vec_in, (hipStream_t)stream), "iconv2d_brelu");
+    return launched(launch_conv(a, vec_in, vec_in, (hipStream_t)stream), what);
+}
+
+int iconv2d_brelu(const icnn_conv_desc *d, const void *x, const void *w_packed, const int32_t *bias,
+                  const void *res, void *y, void *workspace, void *stream)
+{
+    return conv_layer(d, x, w_packed, bias, nullptr, res, y, workspace, stream, "iconv2d_brelu");
+}
+
+int iconv2d_brelu_pc(const icnn_conv_desc *d, const void *x, const void *w_packed, const int32_t *bias,
+                     const icnn_channel_params *pc, const void *res, void *y, void *workspace, void *stream)
+{
+    if (!pc) return fail(ICNN_E_NULL, "channel parameters are NULL");
+    return conv_layer(d, x, w_packed, bias, pc, res, y, workspace, stream, "iconv2d_brelu_pc");
 }
 
 int iconv2d_dual_brelu(const icnn_conv_desc *m, const void *x_main, const void *w_main_packed,

@@ -112,13 +112,89 @@ __device__ __forceinline__ void epilogue_vec(const ConvArgs &a, const v16i &acc,
     *(v4i *)((uint8_t *)a.out + oo) = v4i{(int)wd[0], (int)wd[1], (int)wd[2], (int)wd[3]};
 }
 
+// Per-output-channel parameters (Section 3.4.3: one weight step per output channel leaves every
+// channel its own ratio): channel c is requantised with (pc_mul[c], pc_shift[c]) and its skip
+// operand rescaled with (pc_res_mul[c], pc_res_shift[c]).  64-bit arithmetic throughout; vector
+// accesses when all 16 channels are valid and the tensors allow them.
+__device__ __forceinline__ void epilogue_pc(const ConvArgs &a, const v16i &acc, int p, int co0, int nv)
+{
+    const bool vec = a.epi_vec && nv == 16;
+    const bool pvec = a.pc_vec && nv == 16;
+    const size_t ro = (size_t)p * a.res_cs + co0;
+    const size_t oo = (size_t)p * a.out_cs + a.out_co + co0;
+    const bool requant = a.out_mode != 3;
+    uint32_t wd[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        int mu[4] = {1, 1, 1, 1}, sf[4] = {0, 0, 0, 0}, rmu[4] = {1, 1, 1, 1}, rsf[4] = {0, 0, 0, 0}, rv[4] = {0, 0, 0, 0};
+        const int c4 = co0 + 4 * g;
+        auto fetch4 = [&](const int32_t *src, int (&dst)[4]) {
+            if (pvec) {
+                const v4i v = *(const v4i *)(src + c4);
+                dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (4 * g + e < nv) dst[e] = src[c4 + e];
+            }
+        };
+        if (requant) { fetch4(a.pc_mul, mu); fetch4(a.pc_shift, sf); }
+        if (a.res_mode != 0) {
+            fetch4(a.pc_res_mul, rmu);
+            fetch4(a.pc_res_shift, rsf);
+            if (vec && a.res_dtype == 2) {
+                const v4i v = *(const v4i *)((const int32_t *)a.res + ro + 4 * g);
+                rv[0] = v.x; rv[1] = v.y; rv[2] = v.z; rv[3] = v.w;
+            } else if (vec) {
+                const int w4 = *(const int *)((const uint8_t *)a.res + ro + 4 * g);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int b8 = (w4 >> (8 * e)) & 0xff;
+                    rv[e] = a.res_dtype == 1 ? (int)(int8_t)b8 : b8;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (4 * g + e < nv) rv[e] = load_elem(a.res, ro + 4 * g + e, a.res_dtype);
+            }
+        }
+        int ti[4];
+        int qv[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            int64_t t = acc[4 * g + e];
+            const int64_t skip = a.res_mode != 0 ? rsr64((int64_t)rv[e] * rmu[e], rsf[e] & 63) : 0;
+            if (a.res_mode == 1) t += skip;
+            ti[e] = sat32(t);
+            int64_t q = rsr64((int64_t)ti[e] * mu[e], sf[e] & 63);
+            if (a.res_mode == 2) q += skip;
+            qv[e] = clampi64(q, a.lo, a.hi);
+            wd[g] |= (uint32_t)(qv[e] & 0xff) << (8 * e);
+        }
+        if (!requant) {
+            if (vec) {
+                *(v4i *)((int32_t *)a.out + oo + 4 * g) = v4i{ti[0], ti[1], ti[2], ti[3]};
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (4 * g + e < nv) ((int32_t *)a.out)[oo + 4 * g + e] = ti[e];
+            }
+        } else if (!vec) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (4 * g + e < nv) ((uint8_t *)a.out)[oo + 4 * g + e] = (uint8_t)qv[e];
+        }
+    }
+    if (requant && vec) *(v4i *)((uint8_t *)a.out + oo) = v4i{(int)wd[0], (int)wd[1], (int)wd[2], (int)wd[3]};
+}
+
 // Epilogue of a wave's TM x TP accumulator tiles; the mode switch is outside the
 // tile loops so each mode is straight-line code.
 // True when the call's skip operand is 8-bit and the vector epilogue handles it: then the operands of
 // a wave's tiles can be fetched ahead of the K loop (prefetch_res8) and handed to epilogue_tiles.
 __device__ __forceinline__ bool res8_applies(const ConvArgs &a)
 {
-    return a.epi_vec && !(a.Cout & 15) && a.res_mode != 0 && a.res_dtype != 2;
+    return a.epi_vec && !(a.Cout & 15) && a.res_mode != 0 && a.res_dtype != 2 && !a.pc_mul && !a.pc_res_mul;
 }
 template <int TM, int TP>
 __device__ __forceinline__ void prefetch_res8(const ConvArgs &a, int co_wave, int pix_wave, int lane, v4i (&res8)[TM][TP])
@@ -152,6 +228,10 @@ __device__ __forceinline__ void epilogue_tiles(const ConvArgs &a, const v16i (&a
             }
         }
     };
+    if (a.pc_mul || a.pc_res_mul) {
+        for_tiles([&](const v16i &c, int p, int co0, int, int) { epilogue_pc(a, c, p, co0, min(16, a.Cout - co0)); });
+        return;
+    }
     // channel tails and unaligned tensors take the element-wise path for the whole call
     if (!a.epi_vec || (a.Cout & 15)) {
         for_tiles([&](const v16i &c, int p, int co0, int, int) {

@@ -55,6 +55,10 @@ struct ConvArgs {
     int res_fast; // 8-bit skip operand whose rescale fits 32 bits
     int epi_vec;  // output (and skip operand) allow 16-byte accesses
     int epi_mode; // 3 * RES + RQ of the vector epilogue
+    // per-output-channel requantisation (all four null for the per-layer form): int32 [Cout] each;
+    // pc_res_* only with a skip operand.  pc_vec: every given array is 16-byte aligned.
+    const int32_t *pc_mul, *pc_shift, *pc_res_mul, *pc_res_shift;
+    int pc_vec;
 };
 
 // Projection half of a fused type-2 residual block (see conv_dual.hip)

@@ -43,7 +43,7 @@ class GpuNet:
                     continue
                 if op["res"] in pending:
                     proj = pending.pop(op["res"])
-                    dual = self._try_fuse(step, proj)
+                    dual = self._try_fuse(step, proj) if step[0] == "conv" else None
                     if dual is not None:
                         self.fused.append(op["res"])
                         self.fused_proj[op["name"]] = proj[1]
@@ -90,6 +90,18 @@ class GpuNet:
         ws_bytes = B.iconv2d_workspace_bytes(d)
         ws = torch.empty(ws_bytes, dtype=torch.uint8, device=self.device) if ws_bytes else None
         torch.cuda.synchronize(self.device)       # w_dev may be released after the prepack ran
+        if "mul_c" in cal or "res_mul_c" in cal:
+            # per-output-channel requantisation: the integers go to the device as they are
+            def col(key, fallback):
+                v = cal.get(key)
+                if v is None:
+                    v = [cal.get(fallback[0], fallback[1])] * op["cout"]
+                return torch.tensor(v, dtype=torch.int32, device=self.device)
+            arrs = [col("mul_c", ("mul", 1)), col("shift_c", ("shift", 0))]
+            if res is not None:
+                arrs += [col("res_mul_c", ("res_mul", 1)), col("res_shift_c", ("res_shift", 0))]
+            pc = B.channel_params(*arrs)
+            return ("conv_pc", op, (d, src, wp, bias, pc, res, dst, ws), arrs)
         return ("conv", op, (d, src, wp, bias, res, dst, ws))
 
     def _try_fuse(self, main, proj):
@@ -109,20 +121,15 @@ class GpuNet:
         self.buf["raw"].copy_(torch.from_numpy(np.ascontiguousarray(x_raw)).to(self.device))
 
     def run(self, stream=None):
-        for kind, _, args in self.steps:
-            if kind == "conv":
-                B.iconv2d_brelu(*args, stream=stream)
-            elif kind == "dual":
-                B.iconv2d_dual_brelu(*args, stream=stream)
-            elif kind == "maxpool":
-                B.imaxpool2d_u8(*args, stream=stream)
-            else:
-                B.iavgpool_global_u8(*args, stream=stream)
+        for i in range(len(self.steps)):
+            self.run_step(i, stream)
 
     def run_step(self, i, stream=None):
-        kind, _, args = self.steps[i]
+        kind, _, args = self.steps[i][:3]
         if kind == "conv":
             B.iconv2d_brelu(*args, stream=stream)
+        elif kind == "conv_pc":
+            B.iconv2d_brelu_pc(*args, stream=stream)
         elif kind == "dual":
             B.iconv2d_dual_brelu(*args, stream=stream)
         elif kind == "maxpool":

@@ -17,9 +17,12 @@ def dev(a):
 
 def gpu_conv2d(x, w, bias, *, stride=1, pad=0, mul=1, shift=0, bound_q=127, lo=0, hi=255,
                out_mode="brelu", res=None, res_mode="none", res_mul=1, res_shift=0,
-               in_sub128=False, cin=None, out=None, out_c_offset=0, misalign=0):
+               in_sub128=False, cin=None, out=None, out_c_offset=0, misalign=0,
+               mul_c=None, shift_c=None, res_mul_c=None, res_shift_c=None, pc_misalign=0):
     """Same signature and result layout as oracle.conv2d, computed by the library.
-    `misalign` shifts x / out / res device addresses by that many bytes (scalar paths)."""
+    `misalign` shifts x / out / res device addresses by that many bytes (scalar paths).
+    Any of mul_c .. res_shift_c (int32 [cout]) selects iconv2d_brelu_pc; `pc_misalign` (a multiple
+    of 4) shifts those arrays' device addresses."""
     n, h, ww, cbuf = x.shape
     cout, kh, kw, wc = w.shape
     cin = wc if cin is None else cin
@@ -54,8 +57,23 @@ def gpu_conv2d(x, w, bias, *, stride=1, pad=0, mul=1, shift=0, bound_q=127, lo=0
     bd = dev(bias.astype(np.int32))
     ws_bytes = B.iconv2d_workspace_bytes(d)
     ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=DEV) if ws_bytes else None
-    B.iconv2d_brelu(d, xd.data_ptr() + misalign, wp, bd, None if rd is None else rd.data_ptr() + misalign,
-                    od.data_ptr() + misalign, ws)
+    rptr = None if rd is None else rd.data_ptr() + misalign
+    if any(v is not None for v in (mul_c, shift_c, res_mul_c, res_shift_c)):
+        keep = []
+
+        def col(v, fallback):
+            if v is None:
+                v = np.full(cout, fallback, np.int32)
+            t = torch.zeros(cout + 16, dtype=torch.int32, device=DEV)
+            t[pc_misalign // 4:pc_misalign // 4 + cout] = torch.from_numpy(np.ascontiguousarray(v, dtype=np.int32)).to(DEV)
+            keep.append(t)
+            return t.data_ptr() + pc_misalign
+        pc = B.channel_params(col(mul_c, mul), col(shift_c, shift),
+                              col(res_mul_c, res_mul) if res is not None else None,
+                              col(res_shift_c, res_shift) if res is not None else None)
+        B.iconv2d_brelu_pc(d, xd.data_ptr() + misalign, wp, bd, pc, rptr, od.data_ptr() + misalign, ws)
+    else:
+        B.iconv2d_brelu(d, xd.data_ptr() + misalign, wp, bd, rptr, od.data_ptr() + misalign, ws)
     torch.cuda.synchronize()
     raw = od.cpu().numpy()
     # guard bytes before and after the output must be untouched

@@ -30,6 +30,10 @@ def make(seed, n, h, w, cin, cout, k, raw=False, signed=False, cbuf=None):
 def both(x, w, b, **kw):
     from gpu_util import gpu_conv2d
     mis = kw.pop("misalign", 0)
+    pcm = kw.pop("pc_misalign", 0)
+    if pcm:
+        want = O.conv2d(x, w, b, **{k: (v.copy() if k == "out" else v) for k, v in kw.items()})
+        return gpu_conv2d(x, w, b, misalign=mis, pc_misalign=pcm, **kw), want
     want = O.conv2d(x, w, b, **{k: (v.copy() if k == "out" else v) for k, v in kw.items()})
     got = gpu_conv2d(x, w, b, misalign=mis, **kw)
     return got, want
@@ -216,3 +220,88 @@ def test_fused_block_refuses_what_it_cannot_prove_or_run():
     with pytest.raises(B.IcnnError) as e:        # 3x3 main layer
         B.iconv2d_dual_brelu(dm, 4096, 8192, 12288, dp, 16384, 20480, 24576, 28672, stream=0)
     assert e.value.code == B.ICNN_E_UNSUPPORTED
+
+
+def channel_params(seed, cout, res=False):
+    """Per-channel integers in the calibrator's usual range, with a few extreme channels."""
+    g = rnd(seed)
+    kw = dict(mul_c=g.integers(1 << 14, 1 << 15, size=cout).astype(np.int32),
+              shift_c=g.integers(20, 28, size=cout).astype(np.int32))
+    kw["mul_c"][0], kw["shift_c"][0] = 1, 0
+    if cout > 3:
+        kw["mul_c"][1], kw["shift_c"][1] = 2**31 - 1, 62
+        kw["mul_c"][2], kw["shift_c"][2] = 2**31 - 1, 40
+        kw["mul_c"][3], kw["shift_c"][3] = 3, 1
+    if res:
+        kw["res_mul_c"] = g.integers(1, 1 << 16, size=cout).astype(np.int32)
+        kw["res_shift_c"] = g.integers(0, 12, size=cout).astype(np.int32)
+        kw["res_mul_c"][cout - 1], kw["res_shift_c"][cout - 1] = 2**31 - 1, 31
+    return kw
+
+
+@pytest.mark.parametrize("shape", [(2, 17, 23, 64, 64, 3, 1, 1), (1, 14, 14, 512, 128, 1, 1, 0), (1, 9, 9, 16, 100, 3, 1, 1),
+                                   (1, 30, 34, 48, 1, 3, 1, 1), (2, 37, 41, 3, 64, 7, 2, 3), (1, 7, 7, 24, 40, 3, 1, 1)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_per_channel_requantisation(shape):
+    n, h, w, cin, cout, k, stride, pad = shape
+    x, wt, b = make(20, n, h, w, cin, cout, k, raw=(cin == 3))
+    kw = dict(stride=stride, pad=pad, in_sub128=(cin == 3), bound_q=127, **channel_params(200, cout))
+    got, want = both(x, wt, b, **kw)
+    assert (got == want).all() and want.max() == 127
+    got, want = both(x, wt, b, out_mode="linear_s8", **kw)
+    assert (got == want).all() and want.min() < 0
+
+
+@pytest.mark.parametrize("res_kind", ["u8", "s8", "s32"])
+@pytest.mark.parametrize("cout", [64, 40])
+@pytest.mark.parametrize("res_mode", ["pre", "post"])
+def test_per_channel_skip_merge(res_kind, cout, res_mode):
+    x, wt, b = make(21, 2, 9, 11, 64, cout, 1)
+    g = rnd(210)
+    shape = (2, 9, 11, cout)
+    if res_kind == "u8":
+        r = g.integers(0, 128, size=shape, dtype=np.uint8)
+    elif res_kind == "s8":
+        r = g.integers(-128, 128, size=shape, dtype=np.int8)
+    else:
+        r = g.integers(-300000, 300000, size=shape).astype(np.int32)
+    pc = channel_params(211, cout, res=True)
+    got, want = both(x, wt, b, res=r, res_mode=res_mode, bound_q=127, **pc)
+    assert (got == want).all()
+    got, want = both(x, wt, b, res=r, res_mode=res_mode, out_mode="clamp_u8", lo=2, hi=251, **pc)
+    assert (got == want).all()
+    if res_mode == "pre":        # raw int32 output: only the skip rescale is per channel
+        got, want = both(x, wt, b, res=r, res_mode="pre", out_mode="raw_s32", res_mul_c=pc["res_mul_c"],
+                         res_shift_c=pc["res_shift_c"])
+        assert (got == want).all()
+
+
+def test_per_channel_unaligned_tensors_and_arrays():
+    x, wt, b = make(22, 1, 9, 9, 64, 64, 3)
+    r = rnd(220).integers(0, 128, size=(1, 9, 9, 64), dtype=np.uint8)
+    pc = channel_params(221, 64, res=True)
+    for mis, pcm in ((0, 4), (1, 0), (4, 8)):
+        got, want = both(x, wt, b, stride=1, pad=1, res=r, res_mode="pre", misalign=mis, pc_misalign=pcm, **pc)
+        assert (got == want).all(), (mis, pcm)
+
+
+def test_per_channel_argument_checks():
+    import torch
+    from paper_2006_11735_amd import binding as B
+    d = B.conv_desc(n=1, h=4, w=4, cin=16, in_c_stride=16, cout=16, kh=1, kw=1, out_c_stride=16)
+    t = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    i32 = torch.ones(16, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.IcnnError) as e:
+        B.iconv2d_brelu_pc(d, t, t, i32, B.channel_params(i32, None), None, t)
+    assert e.value.code == B.ICNN_E_NULL
+    with pytest.raises(B.IcnnError) as e:
+        B.iconv2d_brelu_pc(d, t, t, i32, B.channel_params(i32.data_ptr() + 2, i32), None, t)
+    assert e.value.code == B.ICNN_E_ALIGN
+    d.res_mode, d.res_c_stride = B.ICNN_RES_PRE, 16
+    with pytest.raises(B.IcnnError) as e:
+        B.iconv2d_brelu_pc(d, t, t, i32, B.channel_params(i32, i32), t, t)
+    assert e.value.code == B.ICNN_E_NULL
+    d.res_mode, d.out_mode = B.ICNN_RES_NONE, B.ICNN_OUT_RAW_S32
+    with pytest.raises(B.IcnnError) as e:
+        B.iconv2d_brelu_pc(d, t, t, i32, B.channel_params(i32, i32), None, t)
+    assert e.value.code == B.ICNN_E_PARAM

@@ -37,6 +37,53 @@ def test_small_vdsr_vrcnn_resnet(seed):
             compare_all(net, g, want)
 
 
+@pytest.mark.parametrize("seed", [0, 1])
+def test_small_resnet_with_per_channel_requantisation(seed):
+    # Section 3.4.3: every output channel its own (mul, shift) and skip rescale
+    from paper_2006_11735_amd.netrun import GpuNet
+    net = W.resnet(3, [2, 1, 1, 1], "tiny", image=64, calib_images=2, classes=10)
+    calib, _ = ONet.calibrate(net, seed, per_channel=True)
+    assert "mul_c" in calib["conv"]["stem"] and "res_mul_c" in calib["conv"]["s1b0_c3"]
+    want = ONet.run(net, seed, calib)
+    g = GpuNet(net, seed, calib)
+    assert any(st[0] == "conv_pc" for st in g.steps)
+    g.set_input()
+    g.run()
+    compare_all(net, g, want)
+
+
+def test_resnet50_shape_per_channel_batch_8():
+    from paper_2006_11735_amd.netrun import GpuNet
+    net = W.resnet(8, [3, 4, 6, 3], "r50b8", calib_images=2)
+    calib, _ = ONet.calibrate(net, 0, per_channel=True)
+    g = GpuNet(net, 0, calib)
+    g.set_input()
+    g.run()
+    x = W.input_tensor(net, 0)
+    for img in (0, 5):
+        want = ONet.run(net, 0, calib, images=1, x_raw=np.ascontiguousarray(x[img:img + 1]))
+        for name in net["buffers"]:
+            if name in g.fused:
+                continue
+            got = g.result(name)[img:img + 1]
+            assert (got == want[name]).all(), (img, name)
+
+
+def test_config3_per_channel_full_batch_sampled_images():
+    from paper_2006_11735_amd.netrun import GpuNet
+    net = W.CONFIGS["cfg3"]()
+    calib = json.load(open(ONet.stored_calib_path("cfg3", 0, per_channel=True)))
+    g = GpuNet(net, 0, calib)
+    g.set_input()
+    g.run()
+    x = W.input_tensor(net, 0)
+    for img in (1, 62):
+        want = ONet.run(net, 0, calib, images=1, x_raw=np.ascontiguousarray(x[img:img + 1]))
+        for name in net["buffers"]:
+            got = g.result(name)[img:img + 1]
+            assert (got == want[name]).all(), (img, name)
+
+
 def stored(cfg):
     return json.load(open(ONet.stored_calib_path(cfg, 0)))
 

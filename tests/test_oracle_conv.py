@@ -196,3 +196,46 @@ def test_accumulator_overflow_is_reported():
     w = np.full((1, 1, 1, 70000), 127, np.int8)
     with pytest.raises(ArithmeticError):
         O.conv2d(x, w, np.zeros(1, np.int32), out_mode="raw_s32")      # 255*127*70000 > 2^31
+
+
+def test_per_channel_requantisation_is_the_per_layer_one_channel_by_channel():
+    """Section 3.4.3 (one weight step per output channel): every channel carries its own
+    (mul, shift) and skip rescale.  Pinned three ways: numpy arithmetic on the library U,
+    the per-layer oracle run once per channel, and constant arrays == per-layer call."""
+    g = rnd(23)
+    x = g.integers(0, 128, size=(2, 7, 6, 12), dtype=np.uint8)
+    w = g.integers(-127, 128, size=(9, 3, 3, 12), dtype=np.int8)
+    b = g.integers(-4096, 4097, size=9).astype(np.int32)
+    mul_c = g.integers(1 << 14, 1 << 15, size=9).astype(np.int32)
+    shift_c = g.integers(20, 27, size=9).astype(np.int32)
+    shift_c[0], mul_c[0] = 0, 1                       # a shift of zero adds no rounding term
+    rmul_c = g.integers(1, 1 << 15, size=9).astype(np.int32)
+    rshift_c = g.integers(0, 9, size=9).astype(np.int32)
+    r8 = g.integers(0, 128, size=(2, 7, 6, 9), dtype=np.uint8)
+    y = library_u(x, w, 1, 1) + b
+    half = np.where(shift_c > 0, (1 << np.maximum(shift_c - 1, 0)), 0).astype(np.int64)
+    rhalf = np.where(rshift_c > 0, (1 << np.maximum(rshift_c - 1, 0)), 0).astype(np.int64)
+    skip = (r8.astype(np.int64) * rmul_c + rhalf) >> rshift_c
+    # no skip operand
+    v = O.conv2d(x, w, b, stride=1, pad=1, mul_c=mul_c, shift_c=shift_c)
+    assert (v == np.clip((y * mul_c + half) >> shift_c, 0, 127)).all()
+    # skip operand joined before and after requantisation
+    v_pre = O.conv2d(x, w, b, stride=1, pad=1, mul_c=mul_c, shift_c=shift_c, res=r8, res_mode="pre",
+                     res_mul_c=rmul_c, res_shift_c=rshift_c)
+    assert (v_pre == np.clip(((y + skip) * mul_c + half) >> shift_c, 0, 127)).all()
+    v_post = O.conv2d(x, w, b, stride=1, pad=1, mul_c=mul_c, shift_c=shift_c, res=r8, res_mode="post",
+                      res_mul_c=rmul_c, res_shift_c=rshift_c, out_mode="clamp_u8", lo=3, hi=250)
+    assert (v_post == np.clip(((y * mul_c + half) >> shift_c) + skip, 3, 250)).all()
+    # the per-layer function, one output channel at a time
+    for co in range(9):
+        one = O.conv2d(x, w[co:co + 1], b[co:co + 1], stride=1, pad=1, mul=int(mul_c[co]), shift=int(shift_c[co]),
+                       res=np.ascontiguousarray(r8[..., co:co + 1]), res_mode="pre",
+                       res_mul=int(rmul_c[co]), res_shift=int(rshift_c[co]))
+        assert (one[..., 0] == v_pre[..., co]).all()
+    # constant arrays are the per-layer call; a missing array falls back to the per-layer value
+    same = O.conv2d(x, w, b, stride=1, pad=1, mul_c=np.full(9, 23000, np.int32), shift_c=np.full(9, 24, np.int32))
+    assert (same == O.conv2d(x, w, b, stride=1, pad=1, mul=23000, shift=24)).all()
+    mixed = O.conv2d(x, w, b, stride=1, pad=1, mul_c=mul_c, shift=22, res=r8, res_mode="pre", res_mul=77,
+                     res_shift_c=rshift_c)
+    skip2 = (r8.astype(np.int64) * 77 + rhalf) >> rshift_c
+    assert (mixed == np.clip(((y + skip2) * mul_c + (1 << 21)) >> 22, 0, 127)).all()
