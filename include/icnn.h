@@ -148,8 +148,7 @@ int iconv2d_brelu(const icnn_conv_desc *desc, const void *x, const void *w_packe
  * before batch normalisation is merged, every output channel has its own ratio, so the
  * multiplier and shift of the requantisation equation of Section 3.2.1, and of the skip
  * rescale of Section 4.1, become vectors over the output channels).
- * Device arrays of cout int32 each, 4-byte aligned (16-byte alignment selects vector loads),
- * owned by the caller and read during the call's kernels:
+ * Device arrays of cout int32 each, 4-byte aligned, owned by the caller:
  *   mul[c] in [1, 2^31-1], shift[c] in [0, 62]          (ignored for ICNN_OUT_RAW_S32)
  *   res_mul[c], res_shift[c], same domains              (NULL iff res_mode == NONE)
  * The values live in device memory, so the host cannot check their domains: values outside
@@ -162,13 +161,24 @@ typedef struct {
     const int32_t *res_shift;
 } icnn_channel_params;
 
+/* Bytes of the packed form of a layer's per-channel parameters. */
+int iconv2d_packed_channel_params_bytes(const icnn_conv_desc *desc, size_t *bytes);
+
+/* Packs per-channel parameters (device arrays) into `packed` (device, 16-byte aligned,
+ * iconv2d_packed_channel_params_bytes bytes).  Like the weights, they are constants of the
+ * layer: done once, outside the inference loop.  The arrays may be released once the
+ * stream has run the call. */
+int iconv2d_prepack_channel_params(const icnn_conv_desc *desc, const icnn_channel_params *pc,
+                                   void *packed, void *stream);
+
 /* iconv2d_brelu with the layer's mul, shift, res_mul and res_shift replaced channel by channel
- * by *pc (the descriptor's own four values must still be valid, e.g. 1 and 0, and are not
- * used).  Everything else, including bound_q / lo / hi, the error codes and the alignment
- * rules, is as for iconv2d_brelu.  A raw int32 output without a skip operand has nothing per
- * channel and is rejected with ICNN_E_PARAM. */
+ * by the packed parameters (the descriptor's own four values must still be valid, e.g. 1 and
+ * 0, and are not used; out_mode and res_mode must be those the parameters were packed for).
+ * Everything else, including bound_q / lo / hi, the error codes and the alignment rules, is
+ * as for iconv2d_brelu.  A raw int32 output without a skip operand has nothing per channel
+ * and is rejected with ICNN_E_PARAM. */
 int iconv2d_brelu_pc(const icnn_conv_desc *desc, const void *x, const void *w_packed,
-                     const int32_t *bias, const icnn_channel_params *pc, const void *res,
+                     const int32_t *bias, const void *pc_packed, const void *res,
                      void *y, void *workspace, void *stream);
 
 /*

@@ -53,8 +53,9 @@ _lib.iconv2d_workspace_bytes.argtypes = [C.POINTER(icnn_conv_desc), C.POINTER(C.
 _lib.iconv2d_packed_weight_bytes.argtypes = [C.POINTER(icnn_conv_desc), C.POINTER(C.c_size_t)]
 _lib.iconv2d_prepack_weights.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp]
 _lib.iconv2d_brelu.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp, _vp, _vp, _vp, _vp]
-_lib.iconv2d_brelu_pc.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp, C.POINTER(icnn_channel_params), _vp, _vp, _vp,
-                                  _vp]
+_lib.iconv2d_packed_channel_params_bytes.argtypes = [C.POINTER(icnn_conv_desc), C.POINTER(C.c_size_t)]
+_lib.iconv2d_prepack_channel_params.argtypes = [C.POINTER(icnn_conv_desc), C.POINTER(icnn_channel_params), _vp, _vp]
+_lib.iconv2d_brelu_pc.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.iconv2d_dual_brelu.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp, C.POINTER(icnn_conv_desc), _vp, _vp, _vp,
                                     _vp, _vp]
 _lib.iadd_rescale.argtypes = [C.POINTER(icnn_add_desc), _vp, _vp, _vp, _vp]
@@ -66,7 +67,8 @@ _lib.irenormalize_u8.argtypes = [_i64, _vp, _vp, _vp]
 
 EXPORTS = ["icnn_version", "icnn_last_error", "iconv2d_validate", "iconv2d_out_hw",
            "iconv2d_workspace_bytes", "iconv2d_packed_weight_bytes", "iconv2d_prepack_weights",
-           "iconv2d_brelu", "iconv2d_brelu_pc", "iconv2d_dual_brelu", "iadd_rescale", "iconcat", "imaxpool2d_u8", "iavgpool_global_u8",
+           "iconv2d_brelu", "iconv2d_packed_channel_params_bytes", "iconv2d_prepack_channel_params", "iconv2d_brelu_pc",
+           "iconv2d_dual_brelu", "iadd_rescale", "iconcat", "imaxpool2d_u8", "iavgpool_global_u8",
            "irenormalize_u8"]
 
 
@@ -163,8 +165,18 @@ def channel_params(mul=None, shift=None, res_mul=None, res_shift=None):
     return pc
 
 
-def iconv2d_brelu_pc(desc, x, w_packed, bias, pc, res, y, workspace=None, stream=None):
-    return _check(_lib.iconv2d_brelu_pc(C.byref(desc), _ptr(x), _ptr(w_packed), _ptr(bias), C.byref(pc), _ptr(res),
+def iconv2d_packed_channel_params_bytes(desc):
+    b = C.c_size_t()
+    _check(_lib.iconv2d_packed_channel_params_bytes(C.byref(desc), C.byref(b)))
+    return b.value
+
+
+def iconv2d_prepack_channel_params(desc, pc, packed, stream=None):
+    return _check(_lib.iconv2d_prepack_channel_params(C.byref(desc), C.byref(pc), _ptr(packed), _stream(stream)))
+
+
+def iconv2d_brelu_pc(desc, x, w_packed, bias, pc_packed, res, y, workspace=None, stream=None):
+    return _check(_lib.iconv2d_brelu_pc(C.byref(desc), _ptr(x), _ptr(w_packed), _ptr(bias), _ptr(pc_packed), _ptr(res),
                                         _ptr(y), _ptr(workspace), _stream(stream)))
 
 

@@ -218,8 +218,8 @@ static int fill_conv_args(const icnn_conv_desc *d, const ConvGeom &g, const void
         a.div_howo = a.div_wo = FastDiv{0, 0, 0};
     }
     a.n_tiles = a.per_xcd = a.n_vtiles = 0;
-    a.pc_mul = a.pc_shift = a.pc_res_mul = a.pc_res_shift = nullptr;
-    a.pc_vec = 0;
+    a.pc = nullptr;
+    a.pc_fast_ok = 0;
     a.rq_fast = 0;
     a.mul_hi = 0;
     if (d->out_mode != ICNN_OUT_RAW_S32 && a.shift >= 1 && a.shift <= 32 &&
@@ -241,7 +241,7 @@ static int fill_conv_args(const icnn_conv_desc *d, const ConvGeom &g, const void
 }
 
 static int conv_layer(const icnn_conv_desc *d, const void *x, const void *w_packed, const int32_t *bias,
-                      const icnn_channel_params *pc, const void *res, void *y, void *workspace, void *stream,
+                      const void *pc, const void *res, void *y, void *workspace, void *stream,
                       const char *what)
 {
     ConvGeom g;
@@ -253,22 +253,12 @@ static int conv_layer(const icnn_conv_desc *d, const void *x, const void *w_pack
     rc = fill_conv_args(d, g, x, w_packed, bias, res, y, a);
     if (rc) return rc;
     if (pc) {
-        const bool requant = d->out_mode != ICNN_OUT_RAW_S32;
-        const bool skip = d->res_mode != ICNN_RES_NONE;
-        if (requant && (!pc->mul || !pc->shift)) return fail(ICNN_E_NULL, "per-channel mul and shift must not be NULL");
-        if (skip && (!pc->res_mul || !pc->res_shift))
-            return fail(ICNN_E_NULL, "per-channel res_mul and res_shift must not be NULL when res_mode is set");
-        if (!requant && !skip) return fail(ICNN_E_PARAM, "a raw int32 output without a skip operand has no per-channel parameter");
-        a.pc_mul = requant ? pc->mul : nullptr;
-        a.pc_shift = requant ? pc->shift : nullptr;
-        a.pc_res_mul = skip ? pc->res_mul : nullptr;
-        a.pc_res_shift = skip ? pc->res_shift : nullptr;
-        a.pc_vec = 1;
-        const int32_t *arrs[4] = {a.pc_mul, a.pc_shift, a.pc_res_mul, a.pc_res_shift};
-        for (const int32_t *q : arrs) {
-            if ((uintptr_t)q & 3) return fail(ICNN_E_ALIGN, "per-channel arrays must be 4-byte aligned");
-            if (q && !aligned16(q)) a.pc_vec = 0;
-        }
+        if (!aligned16(pc)) return fail(ICNN_E_ALIGN, "packed channel parameters must be 16-byte aligned");
+        if (d->out_mode == ICNN_OUT_RAW_S32 && d->res_mode == ICNN_RES_NONE)
+            return fail(ICNN_E_PARAM, "a raw int32 output without a skip operand has no per-channel parameter");
+        a.pc = (const int32_t *)pc;
+        a.pc_fast_ok = d->out_mode != ICNN_OUT_RAW_S32 && a.epi_vec &&
+                       (d->res_mode == ICNN_RES_NONE || (d->res_mode == ICNN_RES_PRE && d->res_dtype != ICNN_S32));
     }
     if (g.rp) {
         // small cin: pad and re-normalise x into the workspace, then run the layer as a kh x 1
@@ -292,11 +282,42 @@ int iconv2d_brelu(const icnn_conv_desc *d, const void *x, const void *w_packed, 
     return conv_layer(d, x, w_packed, bias, nullptr, res, y, workspace, stream, "iconv2d_brelu");
 }
 
-int iconv2d_brelu_pc(const icnn_conv_desc *d, const void *x, const void *w_packed, const int32_t *bias,
-                     const icnn_channel_params *pc, const void *res, void *y, void *workspace, void *stream)
+int iconv2d_packed_channel_params_bytes(const icnn_conv_desc *d, size_t *bytes)
 {
-    if (!pc) return fail(ICNN_E_NULL, "channel parameters are NULL");
-    return conv_layer(d, x, w_packed, bias, pc, res, y, workspace, stream, "iconv2d_brelu_pc");
+    ConvGeom g;
+    int rc = check_conv(d, &g);
+    if (rc) return rc;
+    if (!bytes) return fail(ICNN_E_NULL, "bytes is NULL");
+    *bytes = (size_t)((d->cout + 15) / 16) * kPcGroupInts * sizeof(int32_t);
+    return ICNN_OK;
+}
+
+int iconv2d_prepack_channel_params(const icnn_conv_desc *d, const icnn_channel_params *pc, void *packed, void *stream)
+{
+    ConvGeom g;
+    int rc = check_conv(d, &g);
+    if (rc) return rc;
+    if (!pc || !packed) return fail(ICNN_E_NULL, "channel parameters and packed buffer must not be NULL");
+    const bool requant = d->out_mode != ICNN_OUT_RAW_S32;
+    const bool skip = d->res_mode != ICNN_RES_NONE;
+    if (requant && (!pc->mul || !pc->shift)) return fail(ICNN_E_NULL, "per-channel mul and shift must not be NULL");
+    if (skip && (!pc->res_mul || !pc->res_shift))
+        return fail(ICNN_E_NULL, "per-channel res_mul and res_shift must not be NULL when res_mode is set");
+    if (!requant && !skip) return fail(ICNN_E_PARAM, "a raw int32 output without a skip operand has no per-channel parameter");
+    const int32_t *arrs[4] = {pc->mul, pc->shift, pc->res_mul, pc->res_shift};
+    for (const int32_t *q : arrs)
+        if ((uintptr_t)q & 3) return fail(ICNN_E_ALIGN, "per-channel arrays must be 4-byte aligned");
+    if (!aligned16(packed)) return fail(ICNN_E_ALIGN, "packed channel parameters must be 16-byte aligned");
+    return launched(launch_pc_prepack(requant ? pc->mul : nullptr, requant ? pc->shift : nullptr, skip ? pc->res_mul : nullptr,
+                                      skip ? pc->res_shift : nullptr, d->cout, (int32_t *)packed, (hipStream_t)stream),
+                    "iconv2d_prepack_channel_params");
+}
+
+int iconv2d_brelu_pc(const icnn_conv_desc *d, const void *x, const void *w_packed, const int32_t *bias,
+                     const void *pc_packed, const void *res, void *y, void *workspace, void *stream)
+{
+    if (!pc_packed) return fail(ICNN_E_NULL, "packed channel parameters are NULL");
+    return conv_layer(d, x, w_packed, bias, pc_packed, res, y, workspace, stream, "iconv2d_brelu_pc");
 }
 
 int iconv2d_dual_brelu(const icnn_conv_desc *m, const void *x_main, const void *w_main_packed,

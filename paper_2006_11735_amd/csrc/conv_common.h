@@ -112,36 +112,26 @@ __device__ __forceinline__ void epilogue_vec(const ConvArgs &a, const v16i &acc,
     *(v4i *)((uint8_t *)a.out + oo) = v4i{(int)wd[0], (int)wd[1], (int)wd[2], (int)wd[3]};
 }
 
-// Per-output-channel parameters (Section 3.4.3: one weight step per output channel leaves every
-// channel its own ratio): channel c is requantised with (pc_mul[c], pc_shift[c]) and its skip
-// operand rescaled with (pc_res_mul[c], pc_res_shift[c]).  64-bit arithmetic throughout; vector
-// accesses when all 16 channels are valid and the tensors allow them.
-__device__ __forceinline__ void epilogue_pc(const ConvArgs &a, const v16i &acc, int p, int co0, int nv)
+// ---- per-output-channel parameters (Section 3.4.3: one weight step per output channel leaves
+// every channel its own ratio): channel c is requantised with (pc_mul[c], pc_shift[c]) and its
+// skip operand rescaled with (pc_res_mul[c], pc_res_shift[c]).
+struct ChannelParams16 {       // the parameters of one lane's 16 channels
+    int mu[16], sf[16], rmu[16], rsf[16];
+};
+
+// any parameters, any alignment, any tail: 64-bit arithmetic, element by element
+__device__ __forceinline__ void epilogue_pc_slow(const ConvArgs &a, const v16i &acc, int p, int co0, int nv,
+                                                 const ChannelParams16 &c)
 {
     const bool vec = a.epi_vec && nv == 16;
-    const bool pvec = a.pc_vec && nv == 16;
     const size_t ro = (size_t)p * a.res_cs + co0;
     const size_t oo = (size_t)p * a.out_cs + a.out_co + co0;
     const bool requant = a.out_mode != 3;
     uint32_t wd[4] = {0, 0, 0, 0};
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-        int mu[4] = {1, 1, 1, 1}, sf[4] = {0, 0, 0, 0}, rmu[4] = {1, 1, 1, 1}, rsf[4] = {0, 0, 0, 0}, rv[4] = {0, 0, 0, 0};
-        const int c4 = co0 + 4 * g;
-        auto fetch4 = [&](const int32_t *src, int (&dst)[4]) {
-            if (pvec) {
-                const v4i v = *(const v4i *)(src + c4);
-                dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (4 * g + e < nv) dst[e] = src[c4 + e];
-            }
-        };
-        if (requant) { fetch4(a.pc_mul, mu); fetch4(a.pc_shift, sf); }
+        int rv[4] = {0, 0, 0, 0};
         if (a.res_mode != 0) {
-            fetch4(a.pc_res_mul, rmu);
-            fetch4(a.pc_res_shift, rsf);
             if (vec && a.res_dtype == 2) {
                 const v4i v = *(const v4i *)((const int32_t *)a.res + ro + 4 * g);
                 rv[0] = v.x; rv[1] = v.y; rv[2] = v.z; rv[3] = v.w;
@@ -162,11 +152,12 @@ __device__ __forceinline__ void epilogue_pc(const ConvArgs &a, const v16i &acc, 
         int qv[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            int64_t t = acc[4 * g + e];
-            const int64_t skip = a.res_mode != 0 ? rsr64((int64_t)rv[e] * rmu[e], rsf[e] & 63) : 0;
+            const int r = 4 * g + e;
+            int64_t t = acc[r];
+            const int64_t skip = a.res_mode != 0 ? rsr64((int64_t)rv[e] * c.rmu[r], c.rsf[r] & 63) : 0;
             if (a.res_mode == 1) t += skip;
             ti[e] = sat32(t);
-            int64_t q = rsr64((int64_t)ti[e] * mu[e], sf[e] & 63);
+            int64_t q = rsr64((int64_t)ti[e] * c.mu[r], c.sf[r] & 63);
             if (a.res_mode == 2) q += skip;
             qv[e] = clampi64(q, a.lo, a.hi);
             wd[g] |= (uint32_t)(qv[e] & 0xff) << (8 * e);
@@ -188,13 +179,99 @@ __device__ __forceinline__ void epilogue_pc(const ConvArgs &a, const v16i &acc, 
     if (requant && vec) *(v4i *)((uint8_t *)a.out + oo) = v4i{(int)wd[0], (int)wd[1], (int)wd[2], (int)wd[3]};
 }
 
+// Fast form, valid when every channel of the lane satisfies 1 <= shift <= 32 and
+// mul << (32 - shift) < 2^31 (then [t * mul / 2^shift] is the high word of t * (mul << (32 - shift)) + 2^31)
+// and, with RES, the skip operand is 8 bits wide, joins before requantisation and its rescale fits
+// 32 bits.  c.mu holds mul << (32 - shift), c.sf is unused, c.rmu / c.rsf as given.
+template <bool RES>
+__device__ __forceinline__ void epilogue_pc_fast(const ConvArgs &a, const v16i &acc, int p, int co0,
+                                                 const ChannelParams16 &c)
+{
+    int t[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t[r] = acc[r];
+    if (RES) {
+        const v4i res8 = *(const v4i *)((const uint8_t *)a.res + ((size_t)p * a.res_cs + co0));
+        const int w4[4] = {res8.x, res8.y, res8.z, res8.w};
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int b8 = (w4[r >> 2] >> ((r & 3) * 8)) & 0xff;
+            const int rv = a.res_dtype == 1 ? (int)(int8_t)b8 : b8;
+            const int half = (1 << c.rsf[r]) >> 1;
+            t[r] = __builtin_elementwise_add_sat(t[r], (__mul24(rv, c.rmu[r]) + half) >> c.rsf[r]);
+        }
+    }
+    uint32_t wd[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int q = (int)(((int64_t)t[r] * c.mu[r] + 0x80000000LL) >> 32);
+        const int v = min(max(q, a.lo), a.hi);
+        wd[r >> 2] |= (uint32_t)(v & 0xff) << ((r & 3) * 8);
+    }
+    *(v4i *)((uint8_t *)a.out + ((size_t)p * a.out_cs + a.out_co + co0)) = v4i{(int)wd[0], (int)wd[1], (int)wd[2], (int)wd[3]};
+}
+
+// Epilogue of a wave's tiles with per-channel parameters.  The packed parameters of a lane's 16
+// channels are loaded once per row of tiles; whether the fast form applies is decided for the whole
+// wave (it does for every layer a calibrator normally produces), so each form is straight-line code.
+template <int TM, int TP>
+__device__ __forceinline__ void epilogue_pc_tiles(const ConvArgs &a, const v16i (&acc)[TM][TP], int co_wave, int pix_wave,
+                                                  int lane)
+{
+    const bool skip = a.res_mode != 0;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int co0 = co_wave + i * 32 + (lane >> 5) * 16;
+        const int nv = min(16, a.Cout - co0);          // <= 0: this half of the wave has no channels here
+        ChannelParams16 c;
+        bool fast = true, preshifted = false;
+        if (nv > 0) {
+            const int32_t *g = a.pc + (size_t)(co0 >> 4) * kPcGroupInts;
+            auto fetch = [&](const int32_t *src, int (&dst)[16]) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const v4i v = *(const v4i *)(src + 4 * q);
+                    dst[4 * q] = v.x; dst[4 * q + 1] = v.y; dst[4 * q + 2] = v.z; dst[4 * q + 3] = v.w;
+                }
+            };
+            fetch(g, c.mu);
+            fetch(g + 16, c.sf);
+            if (skip) { fetch(g + 32, c.rmu); fetch(g + 48, c.rsf); }
+            preshifted = g[64] != 0;
+            fast = a.pc_fast_ok && nv == 16 && preshifted;
+        }
+        const bool wave_fast = __builtin_amdgcn_ballot_w64(!fast) == 0;
+        if (!wave_fast && preshifted) {
+            // the group was packed for the fast form but the wave takes the general one: undo the pre-shift
+#pragma unroll
+            for (int r = 0; r < 16; ++r) c.mu[r] = (int)((unsigned)c.mu[r] >> ((32 - c.sf[r]) & 31));
+        }
+        if (wave_fast) {
+#pragma unroll
+            for (int j = 0; j < TP; ++j) {
+                const int p = pix_wave + j * 32 + (lane & 31);
+                if (nv > 0 && p < a.M) {
+                    if (skip) epilogue_pc_fast<true>(a, acc[i][j], p, co0, c);
+                    else epilogue_pc_fast<false>(a, acc[i][j], p, co0, c);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < TP; ++j) {
+                const int p = pix_wave + j * 32 + (lane & 31);
+                if (nv > 0 && p < a.M) epilogue_pc_slow(a, acc[i][j], p, co0, nv, c);
+            }
+        }
+    }
+}
+
 // Epilogue of a wave's TM x TP accumulator tiles; the mode switch is outside the
 // tile loops so each mode is straight-line code.
 // True when the call's skip operand is 8-bit and the vector epilogue handles it: then the operands of
 // a wave's tiles can be fetched ahead of the K loop (prefetch_res8) and handed to epilogue_tiles.
 __device__ __forceinline__ bool res8_applies(const ConvArgs &a)
 {
-    return a.epi_vec && !(a.Cout & 15) && a.res_mode != 0 && a.res_dtype != 2 && !a.pc_mul && !a.pc_res_mul;
+    return a.epi_vec && !(a.Cout & 15) && a.res_mode != 0 && a.res_dtype != 2;
 }
 template <int TM, int TP>
 __device__ __forceinline__ void prefetch_res8(const ConvArgs &a, int co_wave, int pix_wave, int lane, v4i (&res8)[TM][TP])
@@ -228,10 +305,6 @@ __device__ __forceinline__ void epilogue_tiles(const ConvArgs &a, const v16i (&a
             }
         }
     };
-    if (a.pc_mul || a.pc_res_mul) {
-        for_tiles([&](const v16i &c, int p, int co0, int, int) { epilogue_pc(a, c, p, co0, min(16, a.Cout - co0)); });
-        return;
-    }
     // channel tails and unaligned tensors take the element-wise path for the whole call
     if (!a.epi_vec || (a.Cout & 15)) {
         for_tiles([&](const v16i &c, int p, int co0, int, int) {

@@ -34,7 +34,8 @@ namespace icnn {
 // MODE 1: cin % 64 == 0 and kh*kw <= 32: a K step lies inside one tap, so the tap
 //         position is wave-uniform (scalar registers, one bit test per copy);
 // MODE 2: any cin % 16 == 0: every lane tracks the tap of its own 16-byte slot.
-template <int BM, int BP, int WAVES_M, int WAVES_P, int MODE>
+// PC: requantisation and skip rescale per output channel (epilogue_pc_tiles)
+template <int BM, int BP, int WAVES_M, int WAVES_P, int MODE, bool PC>
 __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void conv_dlds_kernel(const ConvArgs a)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the buffer-resource type exists in the device pass only
@@ -227,7 +228,7 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
         const int co_wave = ct * BM + wm * TM * 32;
         const int pix_wave = pt * BP + wp * TP * 32;
         v4i res8[TM][TP];
-        prefetch_res8<TM, TP>(a, co_wave, pix_wave, lane, res8);
+        if constexpr (!PC) prefetch_res8<TM, TP>(a, co_wave, pix_wave, lane, res8);
 
         // One K step: wait for its stage, barrier, fragments LDS -> registers, MFMAs.  FEED: the
         // copies of stage s + depth are issued between the MFMAs, so the matrix cores work while
@@ -300,7 +301,8 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
             }
             load_bias_rows<TM>(a, ct * BM + wm * TM * 32, lane >> 5, bias_next);
         }
-        epilogue_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane, res8);
+        if constexpr (PC) epilogue_pc_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane);
+        else epilogue_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane, res8);
         if (!more) break;
         // This tile's stores (and the skip operands of the next) are younger than the stage copies the
         // next K loop waits for.  Loads retire in order among themselves, so a counted wait that leaves
@@ -311,7 +313,7 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
 }
 
 // ------------------------------------------------- register-staged general kernel
-template <int BM, int BP, int WAVES_M, int WAVES_P, bool VEC>
+template <int BM, int BP, int WAVES_M, int WAVES_P, bool VEC, bool PC>
 __global__ __launch_bounds__(256) void conv_greg_kernel(const ConvArgs a)
 {
     constexpr int TM = BM / WAVES_M / 32;
@@ -469,7 +471,8 @@ __global__ __launch_bounds__(256) void conv_greg_kernel(const ConvArgs a)
         __syncthreads();
     }
 
-    epilogue_tiles<TM, TP>(a, acc, ct * BM + wm * TM * 32, pix0 + wp * TP * 32, lane);
+    if constexpr (PC) epilogue_pc_tiles<TM, TP>(a, acc, ct * BM + wm * TM * 32, pix0 + wp * TP * 32, lane);
+    else epilogue_tiles<TM, TP>(a, acc, ct * BM + wm * TM * 32, pix0 + wp * TP * 32, lane);
 }
 
 // ------------------------------------------------------------------ dispatch
@@ -504,9 +507,14 @@ static hipError_t launch_dlds(const ConvArgs &a0, int max_stages, int per_cu, hi
         hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, a);
         return hipGetLastError();
     };
-    if (mode == 0) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 0>);
-    if (mode == 1) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 1>);
-    return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 2>);
+    if (a.pc) {
+        if (mode == 0) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 0, true>);
+        if (mode == 1) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 1, true>);
+        return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 2, true>);
+    }
+    if (mode == 0) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 0, false>);
+    if (mode == 1) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 1, false>);
+    return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 2, false>);
 }
 
 template <int BM, int BP, int WAVES_M, int WAVES_P>
@@ -514,12 +522,12 @@ static hipError_t launch_greg(const ConvArgs &a0, bool vec_in, hipStream_t st)
 {
     ConvArgs a = a0;
     if (!finish_args(a, BM, BP)) return hipErrorInvalidValue;
-    if (vec_in)
-        hipLaunchKernelGGL((conv_greg_kernel<BM, BP, WAVES_M, WAVES_P, true>), dim3(8u * a.per_xcd), dim3(256), 0,
-                           st, a);
-    else
-        hipLaunchKernelGGL((conv_greg_kernel<BM, BP, WAVES_M, WAVES_P, false>), dim3(8u * a.per_xcd), dim3(256), 0,
-                           st, a);
+    const bool pc = a.pc != nullptr;
+    const dim3 grid(8u * a.per_xcd), block(256);
+    if (vec_in && pc) hipLaunchKernelGGL((conv_greg_kernel<BM, BP, WAVES_M, WAVES_P, true, true>), grid, block, 0, st, a);
+    else if (vec_in) hipLaunchKernelGGL((conv_greg_kernel<BM, BP, WAVES_M, WAVES_P, true, false>), grid, block, 0, st, a);
+    else if (pc) hipLaunchKernelGGL((conv_greg_kernel<BM, BP, WAVES_M, WAVES_P, false, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((conv_greg_kernel<BM, BP, WAVES_M, WAVES_P, false, false>), grid, block, 0, st, a);
     return hipGetLastError();
 }
 
@@ -622,6 +630,44 @@ hipError_t launch_prepack(const int8_t *w, uint8_t *wp, int Cout, int K, int chu
     const long long pieces = (long long)chunks * ksteps * 128;
     const unsigned blocks = (unsigned)((pieces + 255) / 256);
     hipLaunchKernelGGL(prepack_kernel, dim3(blocks), dim3(256), 0, st, w, wp, Cout, K, ksteps, pieces, KH, KW, Cin, rp);
+    return hipGetLastError();
+}
+
+// Per-channel parameters -> packed groups of 16 channels (layout at kPcGroupInts).  One thread per
+// group.  A group takes the fast form when each of its channels has 1 <= shift <= 32 and
+// mul << (32 - shift) < 2^31 (then [t * mul / 2^shift] is the high word of t * (mul << (32 - shift)) + 2^31),
+// and, with a skip rescale, res_shift <= 30 and 255 * res_mul + half < 2^31 (8-bit operand, 32-bit
+// arithmetic).  Channels beyond cout get neutral parameters that never veto.
+__global__ __launch_bounds__(64) void pc_prepack_kernel(const int32_t *__restrict__ mul, const int32_t *__restrict__ shift,
+                                                        const int32_t *__restrict__ res_mul,
+                                                        const int32_t *__restrict__ res_shift, int cout, int groups,
+                                                        int32_t *__restrict__ packed)
+{
+    const int g = blockIdx.x * 64 + threadIdx.x;
+    if (g >= groups) return;
+    int32_t *o = packed + (size_t)g * kPcGroupInts;
+    bool fast = true;
+    for (int r = 0; r < 16; ++r) {
+        const int c = g * 16 + r;
+        const bool in = c < cout;
+        const int m = in && mul ? mul[c] : 1, s = in && shift ? shift[c] : 1;
+        const int rm = in && res_mul ? res_mul[c] : 1, rs = in && res_shift ? res_shift[c] : 0;
+        if (in && mul) fast = fast && s >= 1 && s <= 32 && m >= 1 && (long long)m << (32 - s) <= 0x7fffffffLL;
+        if (in && res_mul) fast = fast && rs >= 0 && rs <= 30 && rm >= 1 && 255LL * rm + ((1LL << rs) >> 1) <= 0x7fffffffLL;
+        o[r] = m; o[16 + r] = s; o[32 + r] = rm; o[48 + r] = rs;
+    }
+    if (fast)
+        for (int r = 0; r < 16; ++r) o[r] = (int32_t)((long long)o[r] << (32 - o[16 + r]));
+    o[64] = fast ? 1 : 0;
+    for (int r = 65; r < kPcGroupInts; ++r) o[r] = 0;
+}
+
+hipError_t launch_pc_prepack(const int32_t *mul, const int32_t *shift, const int32_t *res_mul, const int32_t *res_shift,
+                             int cout, int32_t *packed, hipStream_t st)
+{
+    const int groups = (cout + 15) / 16;
+    hipLaunchKernelGGL(pc_prepack_kernel, dim3((groups + 63) / 64), dim3(64), 0, st, mul, shift, res_mul, res_shift, cout,
+                       groups, packed);
     return hipGetLastError();
 }
 

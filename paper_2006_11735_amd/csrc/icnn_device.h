@@ -55,11 +55,17 @@ struct ConvArgs {
     int res_fast; // 8-bit skip operand whose rescale fits 32 bits
     int epi_vec;  // output (and skip operand) allow 16-byte accesses
     int epi_mode; // 3 * RES + RQ of the vector epilogue
-    // per-output-channel requantisation (all four null for the per-layer form): int32 [Cout] each;
-    // pc_res_* only with a skip operand.  pc_vec: every given array is 16-byte aligned.
-    const int32_t *pc_mul, *pc_shift, *pc_res_mul, *pc_res_shift;
-    int pc_vec;
+    // per-output-channel requantisation: packed parameters (kPcGroupInts int32 per 16 channels, see
+    // pc_prepack_kernel), null for the per-layer form.  pc_fast_ok: shape, alignment and skip operand
+    // allow the fast epilogue form where a group's parameters do.
+    const int32_t *pc;
+    int pc_fast_ok;
 };
+
+// Packed per-channel parameters, per group of 16 output channels: mul[16], shift[16], res_mul[16],
+// res_shift[16], then one flag word (1: every channel of the group takes the fast form, and mul[] then
+// holds mul << (32 - shift)), padded to 80 int32.
+constexpr int kPcGroupInts = 80;
 
 // Projection half of a fused type-2 residual block (see conv_dual.hip)
 struct ProjArgs {
@@ -102,6 +108,8 @@ hipError_t launch_conv(const ConvArgs &a, bool vec_in, bool direct_ok, hipStream
 hipError_t launch_conv_dual(const ConvArgs &a, const ProjArgs &q, hipStream_t st);
 hipError_t launch_prepack(const int8_t *w, uint8_t *wp, int Cout, int K, int chunks, int ksteps, int KH, int KW,
                           int Cin, int rp, hipStream_t st);
+hipError_t launch_pc_prepack(const int32_t *mul, const int32_t *shift, const int32_t *res_mul, const int32_t *res_shift,
+                             int cout, int32_t *packed, hipStream_t st);
 hipError_t launch_pad_small_cin(const uint8_t *x, void *out, int N, int H, int W, int Cin, int in_cs, int ph, int pw,
                                 int Hp, int Wp, uint32_t in_xor, hipStream_t st);
 

@@ -100,8 +100,10 @@ class GpuNet:
             arrs = [col("mul_c", ("mul", 1)), col("shift_c", ("shift", 0))]
             if res is not None:
                 arrs += [col("res_mul_c", ("res_mul", 1)), col("res_shift_c", ("res_shift", 0))]
-            pc = B.channel_params(*arrs)
-            return ("conv_pc", op, (d, src, wp, bias, pc, res, dst, ws), arrs)
+            pcp = torch.empty(B.iconv2d_packed_channel_params_bytes(d), dtype=torch.uint8, device=self.device)
+            B.iconv2d_prepack_channel_params(d, B.channel_params(*arrs), pcp)
+            torch.cuda.synchronize(self.device)   # the arrays may be released after the prepack ran
+            return ("conv_pc", op, (d, src, wp, bias, pcp, res, dst, ws))
         return ("conv", op, (d, src, wp, bias, res, dst, ws))
 
     def _try_fuse(self, main, proj):
@@ -125,7 +127,7 @@ class GpuNet:
             self.run_step(i, stream)
 
     def run_step(self, i, stream=None):
-        kind, _, args = self.steps[i][:3]
+        kind, _, args = self.steps[i]
         if kind == "conv":
             B.iconv2d_brelu(*args, stream=stream)
         elif kind == "conv_pc":

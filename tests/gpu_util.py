@@ -71,7 +71,9 @@ def gpu_conv2d(x, w, bias, *, stride=1, pad=0, mul=1, shift=0, bound_q=127, lo=0
         pc = B.channel_params(col(mul_c, mul), col(shift_c, shift),
                               col(res_mul_c, res_mul) if res is not None else None,
                               col(res_shift_c, res_shift) if res is not None else None)
-        B.iconv2d_brelu_pc(d, xd.data_ptr() + misalign, wp, bd, pc, rptr, od.data_ptr() + misalign, ws)
+        pcp = torch.zeros(B.iconv2d_packed_channel_params_bytes(d), dtype=torch.uint8, device=DEV)
+        B.iconv2d_prepack_channel_params(d, pc, pcp)
+        B.iconv2d_brelu_pc(d, xd.data_ptr() + misalign, wp, bd, pcp, rptr, od.data_ptr() + misalign, ws)
     else:
         B.iconv2d_brelu(d, xd.data_ptr() + misalign, wp, bd, rptr, od.data_ptr() + misalign, ws)
     torch.cuda.synchronize()

@@ -291,17 +291,27 @@ def test_per_channel_argument_checks():
     d = B.conv_desc(n=1, h=4, w=4, cin=16, in_c_stride=16, cout=16, kh=1, kw=1, out_c_stride=16)
     t = torch.zeros(4096, dtype=torch.uint8, device="cuda")
     i32 = torch.ones(16, dtype=torch.int32, device="cuda")
+    assert B.iconv2d_packed_channel_params_bytes(d) == 320
     with pytest.raises(B.IcnnError) as e:
-        B.iconv2d_brelu_pc(d, t, t, i32, B.channel_params(i32, None), None, t)
+        B.iconv2d_prepack_channel_params(d, B.channel_params(i32, None), t)
     assert e.value.code == B.ICNN_E_NULL
     with pytest.raises(B.IcnnError) as e:
-        B.iconv2d_brelu_pc(d, t, t, i32, B.channel_params(i32.data_ptr() + 2, i32), None, t)
+        B.iconv2d_prepack_channel_params(d, B.channel_params(i32.data_ptr() + 2, i32), t)
     assert e.value.code == B.ICNN_E_ALIGN
+    with pytest.raises(B.IcnnError) as e:
+        B.iconv2d_prepack_channel_params(d, B.channel_params(i32, i32), t.data_ptr() + 4)
+    assert e.value.code == B.ICNN_E_ALIGN
+    with pytest.raises(B.IcnnError) as e:
+        B.iconv2d_brelu_pc(d, t, t, i32, None, None, t)
+    assert e.value.code == B.ICNN_E_NULL
     d.res_mode, d.res_c_stride = B.ICNN_RES_PRE, 16
     with pytest.raises(B.IcnnError) as e:
-        B.iconv2d_brelu_pc(d, t, t, i32, B.channel_params(i32, i32), t, t)
+        B.iconv2d_prepack_channel_params(d, B.channel_params(i32, i32), t)
     assert e.value.code == B.ICNN_E_NULL
     d.res_mode, d.out_mode = B.ICNN_RES_NONE, B.ICNN_OUT_RAW_S32
     with pytest.raises(B.IcnnError) as e:
-        B.iconv2d_brelu_pc(d, t, t, i32, B.channel_params(i32, i32), None, t)
+        B.iconv2d_prepack_channel_params(d, B.channel_params(i32, i32), t)
+    assert e.value.code == B.ICNN_E_PARAM
+    with pytest.raises(B.IcnnError) as e:
+        B.iconv2d_brelu_pc(d, t, t, i32, t, None, t)
     assert e.value.code == B.ICNN_E_PARAM
