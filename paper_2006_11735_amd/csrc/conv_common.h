@@ -115,13 +115,10 @@ __device__ __forceinline__ void epilogue_vec(const ConvArgs &a, const v16i &acc,
 // ---- per-output-channel parameters (Section 3.4.3: one weight step per output channel leaves
 // every channel its own ratio): channel c is requantised with (pc_mul[c], pc_shift[c]) and its
 // skip operand rescaled with (pc_res_mul[c], pc_res_shift[c]).
-struct ChannelParams16 {       // the parameters of one lane's 16 channels
-    int mu[16], sf[16], rmu[16], rsf[16];
-};
-
-// any parameters, any alignment, any tail: 64-bit arithmetic, element by element
+// General form for one pixel's 16 channels (nv of them valid): any parameters, any alignment, any
+// tail; 64-bit arithmetic, four channels at a time.  g: the group's packed parameters.
 __device__ __forceinline__ void epilogue_pc_slow(const ConvArgs &a, const v16i &acc, int p, int co0, int nv,
-                                                 const ChannelParams16 &c)
+                                                 const int32_t *g)
 {
     const bool vec = a.epi_vec && nv == 16;
     const size_t ro = (size_t)p * a.res_cs + co0;
@@ -129,14 +126,16 @@ __device__ __forceinline__ void epilogue_pc_slow(const ConvArgs &a, const v16i &
     const bool requant = a.out_mode != 3;
     uint32_t wd[4] = {0, 0, 0, 0};
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
+    for (int q4 = 0; q4 < 4; ++q4) {
+        const v4i mu = *(const v4i *)(g + kPcMul + 4 * q4), sf = *(const v4i *)(g + kPcShift + 4 * q4);
+        const v4i rmu = *(const v4i *)(g + kPcResMul + 4 * q4), rsf = *(const v4i *)(g + kPcResShift + 4 * q4);
         int rv[4] = {0, 0, 0, 0};
         if (a.res_mode != 0) {
             if (vec && a.res_dtype == 2) {
-                const v4i v = *(const v4i *)((const int32_t *)a.res + ro + 4 * g);
+                const v4i v = *(const v4i *)((const int32_t *)a.res + ro + 4 * q4);
                 rv[0] = v.x; rv[1] = v.y; rv[2] = v.z; rv[3] = v.w;
             } else if (vec) {
-                const int w4 = *(const int *)((const uint8_t *)a.res + ro + 4 * g);
+                const int w4 = *(const int *)((const uint8_t *)a.res + ro + 4 * q4);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int b8 = (w4 >> (8 * e)) & 0xff;
@@ -145,75 +144,45 @@ __device__ __forceinline__ void epilogue_pc_slow(const ConvArgs &a, const v16i &
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    if (4 * g + e < nv) rv[e] = load_elem(a.res, ro + 4 * g + e, a.res_dtype);
+                    if (4 * q4 + e < nv) rv[e] = load_elem(a.res, ro + 4 * q4 + e, a.res_dtype);
             }
         }
         int ti[4];
         int qv[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const int r = 4 * g + e;
-            int64_t t = acc[r];
-            const int64_t skip = a.res_mode != 0 ? rsr64((int64_t)rv[e] * c.rmu[r], c.rsf[r] & 63) : 0;
+            int64_t t = acc[4 * q4 + e];
+            const int64_t skip = a.res_mode != 0 ? rsr64((int64_t)rv[e] * rmu[e], rsf[e] & 63) : 0;
             if (a.res_mode == 1) t += skip;
             ti[e] = sat32(t);
-            int64_t q = rsr64((int64_t)ti[e] * c.mu[r], c.sf[r] & 63);
+            int64_t q = rsr64((int64_t)ti[e] * mu[e], sf[e] & 63);
             if (a.res_mode == 2) q += skip;
             qv[e] = clampi64(q, a.lo, a.hi);
-            wd[g] |= (uint32_t)(qv[e] & 0xff) << (8 * e);
+            wd[q4] |= (uint32_t)(qv[e] & 0xff) << (8 * e);
         }
         if (!requant) {
             if (vec) {
-                *(v4i *)((int32_t *)a.out + oo + 4 * g) = v4i{ti[0], ti[1], ti[2], ti[3]};
+                *(v4i *)((int32_t *)a.out + oo + 4 * q4) = v4i{ti[0], ti[1], ti[2], ti[3]};
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    if (4 * g + e < nv) ((int32_t *)a.out)[oo + 4 * g + e] = ti[e];
+                    if (4 * q4 + e < nv) ((int32_t *)a.out)[oo + 4 * q4 + e] = ti[e];
             }
         } else if (!vec) {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                if (4 * g + e < nv) ((uint8_t *)a.out)[oo + 4 * g + e] = (uint8_t)qv[e];
+                if (4 * q4 + e < nv) ((uint8_t *)a.out)[oo + 4 * q4 + e] = (uint8_t)qv[e];
         }
     }
     if (requant && vec) *(v4i *)((uint8_t *)a.out + oo) = v4i{(int)wd[0], (int)wd[1], (int)wd[2], (int)wd[3]};
 }
 
-// Fast form, valid when every channel of the lane satisfies 1 <= shift <= 32 and
-// mul << (32 - shift) < 2^31 (then [t * mul / 2^shift] is the high word of t * (mul << (32 - shift)) + 2^31)
-// and, with RES, the skip operand is 8 bits wide, joins before requantisation and its rescale fits
-// 32 bits.  c.mu holds mul << (32 - shift), c.sf is unused, c.rmu / c.rsf as given.
-template <bool RES>
-__device__ __forceinline__ void epilogue_pc_fast(const ConvArgs &a, const v16i &acc, int p, int co0,
-                                                 const ChannelParams16 &c)
-{
-    int t[16];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) t[r] = acc[r];
-    if (RES) {
-        const v4i res8 = *(const v4i *)((const uint8_t *)a.res + ((size_t)p * a.res_cs + co0));
-        const int w4[4] = {res8.x, res8.y, res8.z, res8.w};
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int b8 = (w4[r >> 2] >> ((r & 3) * 8)) & 0xff;
-            const int rv = a.res_dtype == 1 ? (int)(int8_t)b8 : b8;
-            const int half = (1 << c.rsf[r]) >> 1;
-            t[r] = __builtin_elementwise_add_sat(t[r], (__mul24(rv, c.rmu[r]) + half) >> c.rsf[r]);
-        }
-    }
-    uint32_t wd[4] = {0, 0, 0, 0};
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int q = (int)(((int64_t)t[r] * c.mu[r] + 0x80000000LL) >> 32);
-        const int v = min(max(q, a.lo), a.hi);
-        wd[r >> 2] |= (uint32_t)(v & 0xff) << ((r & 3) * 8);
-    }
-    *(v4i *)((uint8_t *)a.out + ((size_t)p * a.out_cs + a.out_co + co0)) = v4i{(int)wd[0], (int)wd[1], (int)wd[2], (int)wd[3]};
-}
-
-// Epilogue of a wave's tiles with per-channel parameters.  The packed parameters of a lane's 16
-// channels are loaded once per row of tiles; whether the fast form applies is decided for the whole
-// wave (it does for every layer a calibrator normally produces), so each form is straight-line code.
+// Epilogue of a wave's tiles with per-channel parameters.  Whether the fast form applies is decided
+// for the whole wave and row of tiles (it does for every layer a calibrator normally produces), so
+// each form is straight-line code.  Fast form (see pc_prepack_kernel):
+//   out = clamp(hi32((clamp(t, ~T, T) << L) * M + 2^31), lo, hi),   t = sat32(acc + [skip * res_mul / 2^res_shift])
+// with an 8-bit skip operand whose rescale fits 32 bits.  Parameters are fetched four channels at a
+// time and used for all TP pixels of the row before the next four, which keeps the register need low.
 template <int TM, int TP>
 __device__ __forceinline__ void epilogue_pc_tiles(const ConvArgs &a, const v16i (&acc)[TM][TP], int co_wave, int pix_wave,
                                                   int lane)
@@ -223,50 +192,55 @@ __device__ __forceinline__ void epilogue_pc_tiles(const ConvArgs &a, const v16i 
     for (int i = 0; i < TM; ++i) {
         const int co0 = co_wave + i * 32 + (lane >> 5) * 16;
         const int nv = min(16, a.Cout - co0);          // <= 0: this half of the wave has no channels here
-        ChannelParams16 c;
-        bool fast = true, preshifted = false;
-        if (nv > 0) {
-            const int32_t *g = a.pc + (size_t)(co0 >> 4) * kPcGroupInts;
-            auto fetch = [&](const int32_t *src, int (&dst)[16]) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const v4i v = *(const v4i *)(src + 4 * q);
-                    dst[4 * q] = v.x; dst[4 * q + 1] = v.y; dst[4 * q + 2] = v.z; dst[4 * q + 3] = v.w;
-                }
-            };
-            fetch(g, c.mu);
-            fetch(g + 16, c.sf);
-            if (skip) { fetch(g + 32, c.rmu); fetch(g + 48, c.rsf); }
-            preshifted = g[64] != 0;
-            fast = a.pc_fast_ok && nv == 16 && preshifted;
-        }
+        const int32_t *g = a.pc + (size_t)(max(co0, 0) >> 4) * kPcGroupInts;
+        const bool fast = nv <= 0 || (a.pc_fast_ok && nv == 16 && g[kPcFlag] != 0);
         const bool wave_fast = __builtin_amdgcn_ballot_w64(!fast) == 0;
-        if (!wave_fast && preshifted) {
-            // the group was packed for the fast form but the wave takes the general one: undo the pre-shift
+        if (!wave_fast) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) c.mu[r] = (int)((unsigned)c.mu[r] >> ((32 - c.sf[r]) & 31));
+            for (int j = 0; j < TP; ++j) {
+                const int p = pix_wave + j * 32 + (lane & 31);
+                if (nv > 0 && p < a.M) epilogue_pc_slow(a, acc[i][j], p, co0, nv, g);
+            }
+            continue;
         }
-        if (wave_fast) {
+        if (nv <= 0) continue;
+        uint32_t wd[TP][4];
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const v4i M = *(const v4i *)(g + kPcM + 4 * q4), L = *(const v4i *)(g + kPcL + 4 * q4);
+            const v4i T = *(const v4i *)(g + kPcT + 4 * q4);
+            v4i rmu = {1, 1, 1, 1}, rsf = {0, 0, 0, 0};
+            if (skip) { rmu = *(const v4i *)(g + kPcResMul + 4 * q4); rsf = *(const v4i *)(g + kPcResShift + 4 * q4); }
 #pragma unroll
             for (int j = 0; j < TP; ++j) {
                 const int p = pix_wave + j * 32 + (lane & 31);
-                if (nv > 0 && p < a.M) {
-                    if (skip) epilogue_pc_fast<true>(a, acc[i][j], p, co0, c);
-                    else epilogue_pc_fast<false>(a, acc[i][j], p, co0, c);
+                int w4 = 0;
+                if (skip && p < a.M) w4 = *(const int *)((const uint8_t *)a.res + ((size_t)p * a.res_cs + co0 + 4 * q4));
+                uint32_t o = 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    int t = acc[i][j][4 * q4 + e];
+                    if (skip) {
+                        const int b8 = (w4 >> (8 * e)) & 0xff;
+                        const int rv = a.res_dtype == 1 ? (int)(int8_t)b8 : b8;
+                        t = __builtin_elementwise_add_sat(t, (__mul24(rv, rmu[e]) + ((1 << rsf[e]) >> 1)) >> rsf[e]);
+                    }
+                    const int tc = min(max(t, ~T[e]), T[e]) << L[e];
+                    const int q = (int)(((int64_t)tc * M[e] + 0x80000000LL) >> 32);
+                    o |= (uint32_t)(min(max(q, a.lo), a.hi) & 0xff) << (8 * e);
                 }
+                wd[j][q4] = o;
             }
-        } else {
+        }
 #pragma unroll
-            for (int j = 0; j < TP; ++j) {
-                const int p = pix_wave + j * 32 + (lane & 31);
-                if (nv > 0 && p < a.M) epilogue_pc_slow(a, acc[i][j], p, co0, nv, c);
-            }
+        for (int j = 0; j < TP; ++j) {
+            const int p = pix_wave + j * 32 + (lane & 31);
+            if (p < a.M)
+                *(v4i *)((uint8_t *)a.out + ((size_t)p * a.out_cs + a.out_co + co0)) =
+                    v4i{(int)wd[j][0], (int)wd[j][1], (int)wd[j][2], (int)wd[j][3]};
         }
     }
 }
-
-// Epilogue of a wave's TM x TP accumulator tiles; the mode switch is outside the
-// tile loops so each mode is straight-line code.
 // True when the call's skip operand is 8-bit and the vector epilogue handles it: then the operands of
 // a wave's tiles can be fetched ahead of the K loop (prefetch_res8) and handed to epilogue_tiles.
 __device__ __forceinline__ bool res8_applies(const ConvArgs &a)

@@ -634,10 +634,14 @@ hipError_t launch_prepack(const int8_t *w, uint8_t *wp, int Cout, int K, int chu
 }
 
 // Per-channel parameters -> packed groups of 16 channels (layout at kPcGroupInts).  One thread per
-// group.  A group takes the fast form when each of its channels has 1 <= shift <= 32 and
-// mul << (32 - shift) < 2^31 (then [t * mul / 2^shift] is the high word of t * (mul << (32 - shift)) + 2^31),
-// and, with a skip rescale, res_shift <= 30 and 255 * res_mul + half < 2^31 (8-bit operand, 32-bit
-// arithmetic).  Channels beyond cout get neutral parameters that never veto.
+// group.  Fast form of a channel with ratio r = mul / 2^shift:
+//   r < 1/2 (1 <= shift <= 32, mul << (32 - shift) < 2^31):  M = mul << (32 - shift), L = 0, no clamp of t;
+//   1/2 <= r: outputs saturate once |t| * r >= 257, so t is first clamped to |t| <= T = ceil(257 / r) + 1
+//   (the final clamp to the 8-bit range hides the difference), which leaves room to shift it left by
+//   L = floor(log2 r) + 2 and use M = mul << (30 - floor(log2 mul)) < 2^31; ratios of 2^10 and more all
+//   behave like 2^10.  Then [t * r] = hi32((t << L) * M + 2^31) exactly.
+// Tiny ratios with shift > 32 have no fast form.  A skip rescale is fast when res_shift <= 30 and
+// 255 * res_mul + half < 2^31 (8-bit operand, 32-bit arithmetic).  Channels beyond cout are neutral.
 __global__ __launch_bounds__(64) void pc_prepack_kernel(const int32_t *__restrict__ mul, const int32_t *__restrict__ shift,
                                                         const int32_t *__restrict__ res_mul,
                                                         const int32_t *__restrict__ res_shift, int cout, int groups,
@@ -650,16 +654,29 @@ __global__ __launch_bounds__(64) void pc_prepack_kernel(const int32_t *__restric
     for (int r = 0; r < 16; ++r) {
         const int c = g * 16 + r;
         const bool in = c < cout;
-        const int m = in && mul ? mul[c] : 1, s = in && shift ? shift[c] : 1;
+        int m = in && mul ? mul[c] : 1, s = in && shift ? shift[c] : 0;
         const int rm = in && res_mul ? res_mul[c] : 1, rs = in && res_shift ? res_shift[c] : 0;
-        if (in && mul) fast = fast && s >= 1 && s <= 32 && m >= 1 && (long long)m << (32 - s) <= 0x7fffffffLL;
+        int M = 0, L = 0, T = 0x7fffffff;
+        bool ok = m >= 1 && s >= 0 && s <= 62;
+        if (ok && s >= 1 && s <= 32 && ((long long)m << (32 - s)) <= 0x7fffffffLL) {
+            M = (int)((long long)m << (32 - s));
+        } else if (ok && s <= 31 && ((long long)m << 1) >= (1LL << s)) {
+            int mm = m, ss = s;
+            if (((long long)mm >> ss) >= 1024) { mm = 1024; ss = 0; }     // r >= 2^10 acts like 2^10
+            const int lg = 31 - __clz(mm);
+            L = lg - ss + 2;
+            M = mm << (30 - lg);
+            T = (int)((257LL * (1LL << ss) + mm - 1) / mm) + 1;
+        } else {
+            ok = false;
+        }
+        if (in && mul) fast = fast && ok;
         if (in && res_mul) fast = fast && rs >= 0 && rs <= 30 && rm >= 1 && 255LL * rm + ((1LL << rs) >> 1) <= 0x7fffffffLL;
-        o[r] = m; o[16 + r] = s; o[32 + r] = rm; o[48 + r] = rs;
+        o[kPcM + r] = M; o[kPcL + r] = L; o[kPcT + r] = T;
+        o[kPcMul + r] = m; o[kPcShift + r] = s; o[kPcResMul + r] = rm; o[kPcResShift + r] = rs;
     }
-    if (fast)
-        for (int r = 0; r < 16; ++r) o[r] = (int32_t)((long long)o[r] << (32 - o[16 + r]));
-    o[64] = fast ? 1 : 0;
-    for (int r = 65; r < kPcGroupInts; ++r) o[r] = 0;
+    o[kPcFlag] = fast ? 1 : 0;
+    for (int r = kPcFlag + 1; r < kPcGroupInts; ++r) o[r] = 0;
 }
 
 hipError_t launch_pc_prepack(const int32_t *mul, const int32_t *shift, const int32_t *res_mul, const int32_t *res_shift,

@@ -62,10 +62,14 @@ struct ConvArgs {
     int pc_fast_ok;
 };
 
-// Packed per-channel parameters, per group of 16 output channels: mul[16], shift[16], res_mul[16],
-// res_shift[16], then one flag word (1: every channel of the group takes the fast form, and mul[] then
-// holds mul << (32 - shift)), padded to 80 int32.
-constexpr int kPcGroupInts = 80;
+// Packed per-channel parameters, per group of 16 output channels, int32 each:
+//   [0,16) M  [16,32) L  [32,48) T     fast form: [t*mul/2^shift] after the clamp to the 8-bit output range
+//                                      equals hi32((clamp(t, ~T, T) << L) * M + 2^31)
+//   [48,64) mul  [64,80) shift         as given (general form)
+//   [80,96) res_mul  [96,112) res_shift
+//   [112] 1 when every channel of the group has a fast form (and an 8-bit skip rescale fits 32 bits)
+constexpr int kPcGroupInts = 128;
+constexpr int kPcM = 0, kPcL = 16, kPcT = 32, kPcMul = 48, kPcShift = 64, kPcResMul = 80, kPcResShift = 96, kPcFlag = 112;
 
 // Projection half of a fused type-2 residual block (see conv_dual.hip)
 struct ProjArgs {

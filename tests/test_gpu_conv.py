@@ -276,6 +276,42 @@ def test_per_channel_skip_merge(res_kind, cout, res_mode):
         assert (got == want).all()
 
 
+TRICKY = [(1, 0), (1, 1), (3, 1), (5, 3), (32512, 8), (2**31 - 1, 0), (2**31 - 1, 31), (2**31 - 1, 30), (2**20, 10),
+          (2**20 + 1, 10), (2**20 - 1, 10), (1023, 0), (1025, 0), (257, 0), (256, 0), (255, 0), (2**14, 15), (2**14 + 1, 15),
+          (2**14 - 1, 15), (2**30, 31), (2**30 + 1, 31), (2**30 - 1, 31), (127, 0), (3, 2), (2**31 - 1, 32), (2**31 - 1, 33),
+          (2**16, 32), (1, 32), (1, 31), (7, 62), (2**24 + 3, 20), (2**24 + 3, 25)]
+
+
+@pytest.mark.parametrize("small", [True, False])
+def test_per_channel_ratios_from_tiny_to_huge(small):
+    """Every form of the per-channel epilogue: ratios below one half, between one half and 2^10, beyond, and
+    shifts above 32, on accumulators that straddle every saturation threshold (small) or are large."""
+    g = rnd(230)
+    cout = 64
+    if small:
+        x = g.integers(0, 3, size=(1, 40, 50, 16), dtype=np.uint8)
+        wt = g.integers(-3, 4, size=(cout, 1, 1, 16), dtype=np.int8)
+        b = g.integers(-40, 41, size=cout).astype(np.int32)
+    else:
+        x, wt, b = make(231, 1, 40, 50, 16, cout, 1)
+    pairs = [TRICKY[i % len(TRICKY)] for i in range(cout)]
+    # groups 0 and 1 (channels 0..31) only get pairs that have a fast form, so whole waves take it
+    fastable = [p for p in TRICKY if p[1] <= 31 and not (p[1] >= 1 and (p[0] << (32 - p[1])) > 2**31 - 1 and 2 * p[0] < (1 << p[1]))
+                and p[1] <= 32]
+    fastable = [p for p in fastable if (1 <= p[1] <= 32 and (p[0] << (32 - p[1])) <= 2**31 - 1) or 2 * p[0] >= (1 << p[1])]
+    for i in range(32):
+        pairs[i] = fastable[i % len(fastable)]
+    mul_c = np.array([p[0] for p in pairs], np.int32)
+    shift_c = np.array([p[1] for p in pairs], np.int32)
+    for kw in (dict(bound_q=127), dict(bound_q=255), dict(out_mode="linear_s8"), dict(out_mode="clamp_u8", lo=7, hi=200)):
+        got, want = both(x, wt, b, mul_c=mul_c, shift_c=shift_c, **kw)
+        assert (got == want).all(), kw
+    r = g.integers(0, 128, size=(1, 40, 50, cout), dtype=np.uint8)
+    got, want = both(x, wt, b, mul_c=mul_c, shift_c=shift_c, res=r, res_mode="pre",
+                     res_mul_c=g.integers(1, 40, size=cout).astype(np.int32), res_shift_c=g.integers(0, 6, size=cout).astype(np.int32))
+    assert (got == want).all()
+
+
 def test_per_channel_unaligned_tensors_and_arrays():
     x, wt, b = make(22, 1, 9, 9, 64, 64, 3)
     r = rnd(220).integers(0, 128, size=(1, 9, 9, 64), dtype=np.uint8)
@@ -291,7 +327,7 @@ def test_per_channel_argument_checks():
     d = B.conv_desc(n=1, h=4, w=4, cin=16, in_c_stride=16, cout=16, kh=1, kw=1, out_c_stride=16)
     t = torch.zeros(4096, dtype=torch.uint8, device="cuda")
     i32 = torch.ones(16, dtype=torch.int32, device="cuda")
-    assert B.iconv2d_packed_channel_params_bytes(d) == 320
+    assert B.iconv2d_packed_channel_params_bytes(d) == 512
     with pytest.raises(B.IcnnError) as e:
         B.iconv2d_prepack_channel_params(d, B.channel_params(i32, None), t)
     assert e.value.code == B.ICNN_E_NULL
