@@ -3,6 +3,8 @@
 #pragma once
 #include "icnn_device.h"
 
+#include <type_traits>
+
 namespace icnn {
 
 typedef int v4i_a4 __attribute__((ext_vector_type(4), aligned(4)));   // 16-byte load, dword aligned
@@ -112,6 +114,13 @@ __device__ __forceinline__ void epilogue_vec(const ConvArgs &a, const v16i &acc,
     *(v4i *)((uint8_t *)a.out + oo) = v4i{(int)wd[0], (int)wd[1], (int)wd[2], (int)wd[3]};
 }
 
+// True when the call's skip operand is 8-bit and the vector epilogue handles it: then the operands of
+// a wave's tiles can be fetched ahead of the K loop (prefetch_res8) and handed to epilogue_tiles.
+__device__ __forceinline__ bool res8_applies(const ConvArgs &a)
+{
+    return a.epi_vec && !(a.Cout & 15) && a.res_mode != 0 && a.res_dtype != 2;
+}
+
 // ---- per-output-channel parameters (Section 3.4.3: one weight step per output channel leaves
 // every channel its own ratio): channel c is requantised with (pc_mul[c], pc_shift[c]) and its
 // skip operand rescaled with (pc_res_mul[c], pc_res_shift[c]).
@@ -177,24 +186,93 @@ __device__ __forceinline__ void epilogue_pc_slow(const ConvArgs &a, const v16i &
     if (requant && vec) *(v4i *)((uint8_t *)a.out + oo) = v4i{(int)wd[0], (int)wd[1], (int)wd[2], (int)wd[3]};
 }
 
-// Epilogue of a wave's tiles with per-channel parameters.  Whether the fast form applies is decided
-// for the whole wave and row of tiles (it does for every layer a calibrator normally produces), so
-// each form is straight-line code.  Fast form (see pc_prepack_kernel):
-//   out = clamp(hi32((clamp(t, ~T, T) << L) * M + 2^31), lo, hi),   t = sat32(acc + [skip * res_mul / 2^res_shift])
-// with an 8-bit skip operand whose rescale fits 32 bits.  Parameters are fetched four channels at a
-// time and used for all TP pixels of the row before the next four, which keeps the register need low.
+// One row of a wave's tiles (16 channels per lane, TP pixels) in the single-multiply form of
+// pc_prepack_kernel.  skip: an 8-bit skip operand joins before requantisation and its rescale fits 32
+// bits.  plain: no channel of the wave's groups needs the clamp, the pre-shift or the post-shift.  Both
+// are wave-uniform.  Parameters are fetched four channels at a time and used for all TP pixels before
+// the next four (registers are scarce here); the arithmetic variants branch inside that loop.
+template <int TP>
+__device__ __forceinline__ void epilogue_pc_row(const ConvArgs &a, const v16i (&acc)[TP], int co0, int pix_wave, int lane,
+                                                const int32_t *g, const v4i (&rw)[TP], bool skip, bool plain)
+{
+    uint32_t wd[TP][4];
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+        const v4i A = *(const v4i *)(g + kPcA + 4 * q4);
+        v4i L = {0, 0, 0, 0}, T = {0, 0, 0, 0}, C = {0, 0, 0, 0}, rmu = {1, 1, 1, 1}, rsf = {0, 0, 0, 0};
+        if (!plain) {
+            L = *(const v4i *)(g + kPcL + 4 * q4);
+            T = *(const v4i *)(g + kPcT + 4 * q4);
+            C = *(const v4i *)(g + kPcC + 4 * q4);
+        }
+        if (skip) { rmu = *(const v4i *)(g + kPcResMul + 4 * q4); rsf = *(const v4i *)(g + kPcResShift + 4 * q4); }
+        auto body = [&](auto res_tag, auto plain_tag) {
+            constexpr bool RES = decltype(res_tag)::value;
+            constexpr bool PLAIN = decltype(plain_tag)::value;
+#pragma unroll
+            for (int j = 0; j < TP; ++j) {
+                const int w4 = rw[j][q4];
+                uint32_t o = 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    int t = acc[j][4 * q4 + e];
+                    if (RES) {
+                        const int b8 = (w4 >> (8 * e)) & 0xff;
+                        const int rv = a.res_dtype == 1 ? (int)(int8_t)b8 : b8;
+                        t = __builtin_elementwise_add_sat(t, (__mul24(rv, rmu[e]) + ((1 << rsf[e]) >> 1)) >> rsf[e]);
+                    }
+                    int q;
+                    if (PLAIN) {
+                        q = (int)(((int64_t)t * A[e] + 0x80000000LL) >> 32);
+                    } else {
+                        const int tc = min(max(t, ~T[e]), T[e]) << L[e];
+                        q = (int)(((int64_t)tc * A[e] + ((int64_t)1 << (31 + C[e]))) >> 32) >> C[e];
+                    }
+                    o |= (uint32_t)(min(max(q, a.lo), a.hi) & 0xff) << (8 * e);
+                }
+                wd[j][q4] = o;
+            }
+        };
+        if (skip) {
+            if (plain) body(std::true_type{}, std::true_type{});
+            else body(std::true_type{}, std::false_type{});
+        } else {
+            if (plain) body(std::false_type{}, std::true_type{});
+            else body(std::false_type{}, std::false_type{});
+        }
+        __builtin_amdgcn_sched_barrier(0);     // keep the four parameter fetches apart
+    }
+#pragma unroll
+    for (int j = 0; j < TP; ++j) {
+        const int p = pix_wave + j * 32 + (lane & 31);
+        if (p < a.M)
+            *(v4i *)((uint8_t *)a.out + ((size_t)p * a.out_cs + a.out_co + co0)) =
+                v4i{(int)wd[j][0], (int)wd[j][1], (int)wd[j][2], (int)wd[j][3]};
+    }
+}
+
+// Epilogue of a wave's tiles with per-channel parameters.  The single-multiply form is used when the
+// call allows it (8-bit output, 16-byte accesses, no skip operand or an 8-bit one joined before
+// requantisation: a.pc_fast_ok), the lane's 16 channels are all valid and the skip rescale of its group
+// fits 32 bits; the decision is taken for the whole wave, so each form is straight-line code.
+// res8: the 8-bit skip operands fetched by prefetch_res8 for the same tile when res8_applies(a).
+// groups: packed parameters of the channel group that starts at channel co_base (a multiple of 16),
+// followed by those of the next groups (global memory or a copy in LDS).
 template <int TM, int TP>
 __device__ __forceinline__ void epilogue_pc_tiles(const ConvArgs &a, const v16i (&acc)[TM][TP], int co_wave, int pix_wave,
-                                                  int lane)
+                                                  int lane, const v4i (&res8)[TM][TP], const int32_t *groups, int co_base)
 {
     const bool skip = a.res_mode != 0;
+    const bool have_res8 = res8_applies(a);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int co0 = co_wave + i * 32 + (lane >> 5) * 16;
         const int nv = min(16, a.Cout - co0);          // <= 0: this half of the wave has no channels here
-        const int32_t *g = a.pc + (size_t)(max(co0, 0) >> 4) * kPcGroupInts;
-        const bool fast = nv <= 0 || (a.pc_fast_ok && nv == 16 && g[kPcFlag] != 0);
+        const int32_t *g = groups + ((co0 - co_base) >> 4) * kPcGroupInts;
+        const int flags = nv > 0 ? g[kPcFlags] : 3;
+        const bool fast = nv <= 0 || (a.pc_fast_ok && nv == 16 && (!skip || (flags & 1)));
         const bool wave_fast = __builtin_amdgcn_ballot_w64(!fast) == 0;
+        const bool wave_plain = __builtin_amdgcn_ballot_w64(!(flags & 2)) == 0;
         if (!wave_fast) {
 #pragma unroll
             for (int j = 0; j < TP; ++j) {
@@ -204,48 +282,15 @@ __device__ __forceinline__ void epilogue_pc_tiles(const ConvArgs &a, const v16i 
             continue;
         }
         if (nv <= 0) continue;
-        uint32_t wd[TP][4];
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            const v4i M = *(const v4i *)(g + kPcM + 4 * q4), L = *(const v4i *)(g + kPcL + 4 * q4);
-            const v4i T = *(const v4i *)(g + kPcT + 4 * q4);
-            v4i rmu = {1, 1, 1, 1}, rsf = {0, 0, 0, 0};
-            if (skip) { rmu = *(const v4i *)(g + kPcResMul + 4 * q4); rsf = *(const v4i *)(g + kPcResShift + 4 * q4); }
-#pragma unroll
-            for (int j = 0; j < TP; ++j) {
-                const int p = pix_wave + j * 32 + (lane & 31);
-                int w4 = 0;
-                if (skip && p < a.M) w4 = *(const int *)((const uint8_t *)a.res + ((size_t)p * a.res_cs + co0 + 4 * q4));
-                uint32_t o = 0;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    int t = acc[i][j][4 * q4 + e];
-                    if (skip) {
-                        const int b8 = (w4 >> (8 * e)) & 0xff;
-                        const int rv = a.res_dtype == 1 ? (int)(int8_t)b8 : b8;
-                        t = __builtin_elementwise_add_sat(t, (__mul24(rv, rmu[e]) + ((1 << rsf[e]) >> 1)) >> rsf[e]);
-                    }
-                    const int tc = min(max(t, ~T[e]), T[e]) << L[e];
-                    const int q = (int)(((int64_t)tc * M[e] + 0x80000000LL) >> 32);
-                    o |= (uint32_t)(min(max(q, a.lo), a.hi) & 0xff) << (8 * e);
-                }
-                wd[j][q4] = o;
-            }
-        }
+        v4i rw[TP];
 #pragma unroll
         for (int j = 0; j < TP; ++j) {
             const int p = pix_wave + j * 32 + (lane & 31);
-            if (p < a.M)
-                *(v4i *)((uint8_t *)a.out + ((size_t)p * a.out_cs + a.out_co + co0)) =
-                    v4i{(int)wd[j][0], (int)wd[j][1], (int)wd[j][2], (int)wd[j][3]};
+            rw[j] = have_res8 ? res8[i][j] : v4i{0, 0, 0, 0};
+            if (skip && !have_res8 && p < a.M) rw[j] = *(const v4i *)((const uint8_t *)a.res + ((size_t)p * a.res_cs + co0));
         }
+        epilogue_pc_row<TP>(a, acc[i], co0, pix_wave, lane, g, rw, skip, wave_plain);
     }
-}
-// True when the call's skip operand is 8-bit and the vector epilogue handles it: then the operands of
-// a wave's tiles can be fetched ahead of the K loop (prefetch_res8) and handed to epilogue_tiles.
-__device__ __forceinline__ bool res8_applies(const ConvArgs &a)
-{
-    return a.epi_vec && !(a.Cout & 15) && a.res_mode != 0 && a.res_dtype != 2;
 }
 template <int TM, int TP>
 __device__ __forceinline__ void prefetch_res8(const ConvArgs &a, int co_wave, int pix_wave, int lane, v4i (&res8)[TM][TP])

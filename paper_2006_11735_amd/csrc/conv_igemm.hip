@@ -74,6 +74,16 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
 
     const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, a.x_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)a.wp, 0, a.wp_bytes, 0x00020000);
+    // PC: the packed per-channel parameters of a tile's BM channels (PC_BYTES) are copied to LDS at
+    // the start of the tile and read from there by the epilogue.  Two slots alternate, so a wave that
+    // already started the next tile never overwrites what a slower wave's epilogue still reads (no wave
+    // gets two tiles ahead: every K loop has a barrier).
+    const __amdgpu_buffer_rsrc_t rs_pc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)a.pc, 0, PC ? ((a.Cout + 15) >> 4) * kPcGroupInts * 4 : 0, 0x00020000);
+    constexpr int PC_BYTES = (BM / 16) * kPcGroupInts * 4;
+    constexpr int PC_SLOT = (PC_BYTES + 1023) & ~1023;       // whole wave-wide copies
+    uint8_t *const pc_lds = lds + a.nstages * STAGE;
+    int pc_slot = 0;
 
     // ---- state of the tile whose stages are being issued ("load side")
     // A copy q of this wave covers packed pieces [64*m, 64*m + 64), m = (4*q + wave) % A_INSTR;
@@ -228,7 +238,18 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
         const int co_wave = ct * BM + wm * TM * 32;
         const int pix_wave = pt * BP + wp * TP * 32;
         v4i res8[TM][TP];
-        if constexpr (!PC) prefetch_res8<TM, TP>(a, co_wave, pix_wave, lane, res8);
+        prefetch_res8<TM, TP>(a, co_wave, pix_wave, lane, res8);
+        if constexpr (PC) {
+            pc_slot ^= 1;
+#pragma unroll
+            for (int c = 0; c * 4096 < PC_SLOT; ++c) {
+                const int o = c * 4096 + wave * 1024;
+                if (o < PC_SLOT)              // wave-uniform; lanes beyond the tile's parameters and groups beyond cout get zeros
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                        rs_pc, (__attribute__((address_space(3))) void *)(pc_lds + pc_slot * PC_SLOT + o), 16,
+                        o + lane * 16 < PC_BYTES ? (unsigned)(ct * PC_BYTES + o + lane * 16) : OOB, 0, 0, 0);
+            }
+        }
 
         // One K step: wait for its stage, barrier, fragments LDS -> registers, MFMAs.  FEED: the
         // copies of stage s + depth are issued between the MFMAs, so the matrix cores work while
@@ -301,7 +322,9 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
             }
             load_bias_rows<TM>(a, ct * BM + wm * TM * 32, lane >> 5, bias_next);
         }
-        if constexpr (PC) epilogue_pc_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane);
+        if constexpr (PC)
+            epilogue_pc_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane, res8,
+                                      (const int32_t *)(pc_lds + pc_slot * PC_SLOT), co_wave - wm * TM * 32);
         else epilogue_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane, res8);
         if (!more) break;
         // This tile's stores (and the skip operands of the next) are younger than the stage copies the
@@ -471,7 +494,12 @@ __global__ __launch_bounds__(256) void conv_greg_kernel(const ConvArgs a)
         __syncthreads();
     }
 
-    if constexpr (PC) epilogue_pc_tiles<TM, TP>(a, acc, ct * BM + wm * TM * 32, pix0 + wp * TP * 32, lane);
+    if constexpr (PC) {
+        v4i res8[TM][TP];
+        prefetch_res8<TM, TP>(a, ct * BM + wm * TM * 32, pix0 + wp * TP * 32, lane, res8);
+        epilogue_pc_tiles<TM, TP>(a, acc, ct * BM + wm * TM * 32, pix0 + wp * TP * 32, lane, res8,
+                                  a.pc + (size_t)(ct * BM >> 4) * kPcGroupInts, ct * BM);
+    }
     else epilogue_tiles<TM, TP>(a, acc, ct * BM + wm * TM * 32, pix0 + wp * TP * 32, lane);
 }
 
@@ -486,7 +514,8 @@ static hipError_t launch_dlds(const ConvArgs &a0, int max_stages, int per_cu, hi
     if (a.nstages < 2) a.nstages = 2;
     a.div_howo = make_fast_div((unsigned)(a.Ho * a.Wo));
     a.div_wo = make_fast_div((unsigned)a.Wo);
-    const size_t lds_bytes = (size_t)a.nstages * (BM + BP) * kStepK;
+    // per-channel kernels keep two copies of the tile's packed parameters behind the ring
+    const size_t lds_bytes = (size_t)a.nstages * (BM + BP) * kStepK + (a.pc ? 2 * (((BM / 16) * kPcGroupInts * 4 + 1023) & ~1023) : 0);
     const bool pw = a.KH == 1 && a.KW == 1 && a.sh == 1 && a.sw == 1 && a.ph == 0 && a.pw == 0;
     const int mode = pw ? 0 : (a.Cin % 64 == 0 && a.KH * a.KW <= 32 ? 1 : 2);
     // persistent workgroups: as many as fit on the chip at once (a multiple of 8, one share per XCD)
@@ -634,14 +663,17 @@ hipError_t launch_prepack(const int8_t *w, uint8_t *wp, int Cout, int K, int chu
 }
 
 // Per-channel parameters -> packed groups of 16 channels (layout at kPcGroupInts).  One thread per
-// group.  Fast form of a channel with ratio r = mul / 2^shift:
-//   r < 1/2 (1 <= shift <= 32, mul << (32 - shift) < 2^31):  M = mul << (32 - shift), L = 0, no clamp of t;
-//   1/2 <= r: outputs saturate once |t| * r >= 257, so t is first clamped to |t| <= T = ceil(257 / r) + 1
-//   (the final clamp to the 8-bit range hides the difference), which leaves room to shift it left by
-//   L = floor(log2 r) + 2 and use M = mul << (30 - floor(log2 mul)) < 2^31; ratios of 2^10 and more all
-//   behave like 2^10.  Then [t * r] = hi32((t << L) * M + 2^31) exactly.
-// Tiny ratios with shift > 32 have no fast form.  A skip rescale is fast when res_shift <= 30 and
-// 255 * res_mul + half < 2^31 (8-bit operand, 32-bit arithmetic).  Channels beyond cout are neutral.
+// group.  Requantisation of a channel with ratio r = mul / 2^shift as one 32x32 -> 64 bit multiply-add:
+//   shift >= 32:             A = mul, C = shift - 32:  hi32(t * mul + 2^(shift-1)) >> (shift - 32), exact
+//                            because floor(P / 2^shift) = floor(floor(P / 2^32) / 2^(shift-32));
+//   r < 1/2, shift in 1..31: A = mul << (32 - shift) < 2^31:  hi32(t * A + 2^31);
+//   r >= 1/2:                outputs saturate once |t| * r >= 257, so t is first clamped to |t| <= T =
+//                            ceil(257 / r) + 1 (the final clamp to the 8-bit range hides the difference),
+//                            which leaves room to shift it left by L = floor(log2 r) + 2 and use
+//                            A = mul << (30 - floor(log2 mul)) < 2^31; ratios of 2^10 and more all behave
+//                            like 2^10:  hi32((clamp(t) << L) * A + 2^31).
+// The clamp trick needs the 8-bit clamp to follow directly, so a skip operand joined after
+// requantisation takes the general form.  Channels beyond cout are neutral.
 __global__ __launch_bounds__(64) void pc_prepack_kernel(const int32_t *__restrict__ mul, const int32_t *__restrict__ shift,
                                                         const int32_t *__restrict__ res_mul,
                                                         const int32_t *__restrict__ res_shift, int cout, int groups,
@@ -650,33 +682,35 @@ __global__ __launch_bounds__(64) void pc_prepack_kernel(const int32_t *__restric
     const int g = blockIdx.x * 64 + threadIdx.x;
     if (g >= groups) return;
     int32_t *o = packed + (size_t)g * kPcGroupInts;
-    bool fast = true;
+    bool res_fast = true, plain = true;
     for (int r = 0; r < 16; ++r) {
         const int c = g * 16 + r;
         const bool in = c < cout;
-        int m = in && mul ? mul[c] : 1, s = in && shift ? shift[c] : 0;
+        int m = in && mul ? mul[c] : 1, s = in && shift ? shift[c] : 1;
         const int rm = in && res_mul ? res_mul[c] : 1, rs = in && res_shift ? res_shift[c] : 0;
-        int M = 0, L = 0, T = 0x7fffffff;
-        bool ok = m >= 1 && s >= 0 && s <= 62;
-        if (ok && s >= 1 && s <= 32 && ((long long)m << (32 - s)) <= 0x7fffffffLL) {
-            M = (int)((long long)m << (32 - s));
-        } else if (ok && s <= 31 && ((long long)m << 1) >= (1LL << s)) {
+        if (m < 1) m = 1;                       // outside the documented domain: unspecified result, no fault
+        s = s < 0 ? 0 : (s > 62 ? 62 : s);
+        int A, L = 0, T = 0x7fffffff, C = 0;
+        if (s >= 32) {
+            A = m;
+            C = s - 32;
+        } else if (s >= 1 && ((long long)m << (32 - s)) <= 0x7fffffffLL) {
+            A = (int)((long long)m << (32 - s));
+        } else {
             int mm = m, ss = s;
             if (((long long)mm >> ss) >= 1024) { mm = 1024; ss = 0; }     // r >= 2^10 acts like 2^10
             const int lg = 31 - __clz(mm);
             L = lg - ss + 2;
-            M = mm << (30 - lg);
+            A = mm << (30 - lg);
             T = (int)((257LL * (1LL << ss) + mm - 1) / mm) + 1;
-        } else {
-            ok = false;
         }
-        if (in && mul) fast = fast && ok;
-        if (in && res_mul) fast = fast && rs >= 0 && rs <= 30 && rm >= 1 && 255LL * rm + ((1LL << rs) >> 1) <= 0x7fffffffLL;
-        o[kPcM + r] = M; o[kPcL + r] = L; o[kPcT + r] = T;
+        if (in && mul) plain = plain && L == 0 && C == 0;
+        if (in && res_mul) res_fast = res_fast && rs >= 0 && rs <= 30 && rm >= 1 && 255LL * rm + ((1LL << rs) >> 1) <= 0x7fffffffLL;
+        o[kPcA + r] = A; o[kPcL + r] = L; o[kPcT + r] = T; o[kPcC + r] = C;
         o[kPcMul + r] = m; o[kPcShift + r] = s; o[kPcResMul + r] = rm; o[kPcResShift + r] = rs;
     }
-    o[kPcFlag] = fast ? 1 : 0;
-    for (int r = kPcFlag + 1; r < kPcGroupInts; ++r) o[r] = 0;
+    o[kPcFlags] = (res_fast ? 1 : 0) | (plain ? 2 : 0);
+    for (int r = kPcFlags + 1; r < kPcGroupInts; ++r) o[r] = 0;
 }
 
 hipError_t launch_pc_prepack(const int32_t *mul, const int32_t *shift, const int32_t *res_mul, const int32_t *res_shift,

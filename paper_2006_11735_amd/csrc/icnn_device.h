@@ -63,13 +63,16 @@ struct ConvArgs {
 };
 
 // Packed per-channel parameters, per group of 16 output channels, int32 each:
-//   [0,16) M  [16,32) L  [32,48) T     fast form: [t*mul/2^shift] after the clamp to the 8-bit output range
-//                                      equals hi32((clamp(t, ~T, T) << L) * M + 2^31)
-//   [48,64) mul  [64,80) shift         as given (general form)
-//   [80,96) res_mul  [96,112) res_shift
-//   [112] 1 when every channel of the group has a fast form (and an 8-bit skip rescale fits 32 bits)
-constexpr int kPcGroupInts = 128;
-constexpr int kPcM = 0, kPcL = 16, kPcT = 32, kPcMul = 48, kPcShift = 64, kPcResMul = 80, kPcResShift = 96, kPcFlag = 112;
+//   [0,16) A  [16,32) L  [32,48) T  [48,64) C     requantisation of channel c, exact for every valid
+//        (mul, shift):  [t*mul/2^shift], once clamped to the 8-bit output range, equals
+//        clamp( hi32((clamp(t, ~T, T) << L) * A + 2^(31+C)) >> C )
+//   [64,80) mul  [80,96) shift                   as given (general 64-bit form)
+//   [96,112) res_mul  [112,128) res_shift
+//   [128] flags: bit 0: the skip rescale of every channel of the group fits 32 bits for an 8-bit operand;
+//                bit 1: every channel has L = 0, C = 0 and no clamp of t (ratio below one half, shift <= 32)
+constexpr int kPcGroupInts = 144;
+constexpr int kPcA = 0, kPcL = 16, kPcT = 32, kPcC = 48, kPcMul = 64, kPcShift = 80, kPcResMul = 96, kPcResShift = 112,
+              kPcFlags = 128;
 
 // Projection half of a fused type-2 residual block (see conv_dual.hip)
 struct ProjArgs {

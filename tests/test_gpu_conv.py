@@ -327,7 +327,7 @@ def test_per_channel_argument_checks():
     d = B.conv_desc(n=1, h=4, w=4, cin=16, in_c_stride=16, cout=16, kh=1, kw=1, out_c_stride=16)
     t = torch.zeros(4096, dtype=torch.uint8, device="cuda")
     i32 = torch.ones(16, dtype=torch.int32, device="cuda")
-    assert B.iconv2d_packed_channel_params_bytes(d) == 512
+    assert B.iconv2d_packed_channel_params_bytes(d) == 576
     with pytest.raises(B.IcnnError) as e:
         B.iconv2d_prepack_channel_params(d, B.channel_params(i32, None), t)
     assert e.value.code == B.ICNN_E_NULL
