@@ -172,17 +172,17 @@ def main():
     rows = []
     for step, ms in zip(g.steps, layer_ms):
         kind, op = step[0], step[1]
-        if kind not in ("conv", "conv_pc", "dual"):
+        if kind not in ("conv", "conv_pc", "dual", "dual_pc"):
             other_ms += ms
             rows.append({"name": op["dst"], "kind": kind, "ms": ms})
             continue
-        ops, byts, m, k = layer_work(net, op, images, g.fused_proj.get(op["name"]) if kind == "dual" else None)
+        ops, byts, m, k = layer_work(net, op, images, g.fused_proj.get(op["name"]) if kind in ("dual", "dual_pc") else None)
         conv_ops += ops
         conv_ms += ms
         conv_bytes += byts
         tops = ops / (ms * 1e-3) / 1e12
         attain = min(INT8_MFMA_PEAK_TOPS, ops / byts * HBM_PEAK_GBS / 1e3)
-        rows.append({"name": op["name"] + ("+proj" if kind == "dual" else ""), "kind": "conv", "M": m, "N": op["cout"], "K": k, "ms": ms,
+        rows.append({"name": op["name"] + ("+proj" if kind in ("dual", "dual_pc") else ""), "kind": "conv", "M": m, "N": op["cout"], "K": k, "ms": ms,
                      "tops": tops, "pct_mfma_peak": 100 * tops / INT8_MFMA_PEAK_TOPS,
                      "pct_attainable": 100 * tops / attain, "gbs": byts / (ms * 1e-3) / 1e9})
     for r in rows:
@@ -225,7 +225,7 @@ def main():
                      "algorithmic_gb_per_step": conv_bytes / 1e9},
     }
     if args.per_channel:
-        result["config"]["workload"] += "; per-output-channel requantisation (iconv2d_brelu_pc, type-2 blocks unfused)"
+        result["config"]["workload"] += "; per-output-channel requantisation (iconv2d_brelu_pc, iconv2d_dual_brelu_pc)"
     elif os.path.exists(pc_path):
         # the same network with one (mul, shift) and skip rescale per output channel
         g_pc = GpuNet(net, seed, json.load(open(pc_path)))
@@ -240,7 +240,7 @@ def main():
         ms_pc = (time.perf_counter() - t0) / 30 * 1e3
         result["per_channel_variant"] = {"ms_per_step": ms_pc, "images_per_s": images / (ms_pc * 1e-3),
                                          "launches_per_step": len(g_pc.steps),
-                                         "note": "iconv2d_brelu_pc on every BReLU layer; projection convs run unfused"}
+                                         "note": "iconv2d_brelu_pc on every BReLU layer, iconv2d_dual_brelu_pc on the four projection blocks"}
         log("per-channel variant: %.3f ms per step (%d launches)" % (ms_pc, len(g_pc.steps)))
         del g_pc
     result["iadd_rescale"] = add_bandwidth(torch)

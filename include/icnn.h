@@ -202,6 +202,18 @@ int iconv2d_dual_brelu(const icnn_conv_desc *main_desc, const void *x_main, cons
                        const int32_t *bias_main, const icnn_conv_desc *proj_desc, const void *x_proj,
                        const void *w_proj_packed, const int32_t *bias_proj, void *y, void *stream);
 
+/* iconv2d_dual_brelu with the main layer's mul, shift, res_mul and res_shift per output channel
+ * (Section 3.4.3), taken from pc_packed_main = iconv2d_prepack_channel_params(main_desc, ...).
+ * The host cannot read the per-channel skip rescales, so the proof that the merged sum stays
+ * inside int32 uses main_desc->res_mul / 2^main_desc->res_shift as their upper bound: the
+ * caller must set that pair to (at least) the largest per-channel ratio
+ * res_mul[c] / 2^res_shift[c]; main_desc->mul and main_desc->shift are not used.  Otherwise as iconv2d_dual_brelu. */
+int iconv2d_dual_brelu_pc(const icnn_conv_desc *main_desc, const void *x_main,
+                          const void *w_main_packed, const int32_t *bias_main,
+                          const void *pc_packed_main, const icnn_conv_desc *proj_desc,
+                          const void *x_proj, const void *w_proj_packed,
+                          const int32_t *bias_proj, void *y, void *stream);
+
 /*
  * Rescaled feature-map addition (ratio synchronisation between feature maps,
  * Sections 3.4.2 and 4.1), as a stand-alone pass over memory:

@@ -130,8 +130,10 @@ def calibrate(net, seed, per_channel=False):
             if per_channel and op["out_mode"] == "brelu":
                 cout = y.shape[-1]
                 hm = K.percentile_999_per_channel(y)
-                hs = (K.percentile_999_per_channel(bufs[op["res"]][..., :cout]) if op["res_dtype"] == "s32"
-                      else [K.MAX_INT] * cout)
+                # an int32 skip operand is not clamped, so a channel is scaled by its magnitude (a channel
+                # whose values are mostly negative would otherwise get a bound of 1 and a huge rescale)
+                hs = (K.percentile_999_per_channel(bufs[op["res"]][..., :cout], absolute=True)
+                      if op["res_dtype"] == "s32" else [K.MAX_INT] * cout)
                 pairs = [K.mul_shift(a, b) for a, b in zip(hs, hm)]
                 cal["res_mul_c"] = [m for m, _ in pairs]
                 cal["res_shift_c"] = [s for _, s in pairs]

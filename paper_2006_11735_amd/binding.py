@@ -58,6 +58,8 @@ _lib.iconv2d_prepack_channel_params.argtypes = [C.POINTER(icnn_conv_desc), C.POI
 _lib.iconv2d_brelu_pc.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.iconv2d_dual_brelu.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp, C.POINTER(icnn_conv_desc), _vp, _vp, _vp,
                                     _vp, _vp]
+_lib.iconv2d_dual_brelu_pc.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp, _vp, C.POINTER(icnn_conv_desc), _vp, _vp,
+                                       _vp, _vp, _vp]
 _lib.iadd_rescale.argtypes = [C.POINTER(icnn_add_desc), _vp, _vp, _vp, _vp]
 _lib.iconcat.argtypes = [_i32, C.POINTER(_vp), C.POINTER(_i32), C.POINTER(_i32), C.POINTER(_i32),
                          C.POINTER(_i32), _i32, _i64, _vp, _i32, _vp]
@@ -68,7 +70,7 @@ _lib.irenormalize_u8.argtypes = [_i64, _vp, _vp, _vp]
 EXPORTS = ["icnn_version", "icnn_last_error", "iconv2d_validate", "iconv2d_out_hw",
            "iconv2d_workspace_bytes", "iconv2d_packed_weight_bytes", "iconv2d_prepack_weights",
            "iconv2d_brelu", "iconv2d_packed_channel_params_bytes", "iconv2d_prepack_channel_params", "iconv2d_brelu_pc",
-           "iconv2d_dual_brelu", "iadd_rescale", "iconcat", "imaxpool2d_u8", "iavgpool_global_u8",
+           "iconv2d_dual_brelu", "iconv2d_dual_brelu_pc", "iadd_rescale", "iconcat", "imaxpool2d_u8", "iavgpool_global_u8",
            "irenormalize_u8"]
 
 
@@ -185,6 +187,13 @@ def iconv2d_dual_brelu(main_desc, x_main, w_main_packed, bias_main, proj_desc, x
     return _check(_lib.iconv2d_dual_brelu(C.byref(main_desc), _ptr(x_main), _ptr(w_main_packed), _ptr(bias_main),
                                           C.byref(proj_desc), _ptr(x_proj), _ptr(w_proj_packed), _ptr(bias_proj),
                                           _ptr(y), _stream(stream)))
+
+
+def iconv2d_dual_brelu_pc(main_desc, x_main, w_main_packed, bias_main, pc_packed_main, proj_desc, x_proj, w_proj_packed,
+                          bias_proj, y, stream=None):
+    return _check(_lib.iconv2d_dual_brelu_pc(C.byref(main_desc), _ptr(x_main), _ptr(w_main_packed), _ptr(bias_main),
+                                             _ptr(pc_packed_main), C.byref(proj_desc), _ptr(x_proj), _ptr(w_proj_packed),
+                                             _ptr(bias_proj), _ptr(y), _stream(stream)))
 
 
 def iadd_rescale(desc, a, b, out, stream=None):

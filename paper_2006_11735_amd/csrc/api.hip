@@ -320,9 +320,9 @@ int iconv2d_brelu_pc(const icnn_conv_desc *d, const void *x, const void *w_packe
     return conv_layer(d, x, w_packed, bias, pc_packed, res, y, workspace, stream, "iconv2d_brelu_pc");
 }
 
-int iconv2d_dual_brelu(const icnn_conv_desc *m, const void *x_main, const void *w_main_packed,
-                       const int32_t *bias_main, const icnn_conv_desc *p, const void *x_proj,
-                       const void *w_proj_packed, const int32_t *bias_proj, void *y, void *stream)
+static int dual_layer(const icnn_conv_desc *m, const void *x_main, const void *w_main_packed,
+                      const int32_t *bias_main, const void *pc, const icnn_conv_desc *p, const void *x_proj,
+                      const void *w_proj_packed, const int32_t *bias_proj, void *y, void *stream, const char *what)
 {
     ConvGeom gm, gp;
     int rc = check_conv(m, &gm);
@@ -367,7 +367,30 @@ int iconv2d_dual_brelu(const icnn_conv_desc *m, const void *x_main, const void *
     q.H = p->h; q.W = p->w; q.Cin = p->cin; q.in_cs = p->in_c_stride; q.sh = p->stride_h; q.sw = p->stride_w;
     q.ksteps = gp.ksteps; q.x_bytes = b.x_bytes; q.wp_bytes = b.wp_bytes;
     q.res_mul = m->res_mul; q.res_shift = m->res_shift; q.vec_bias = b.vec_bias;
-    return launched(launch_conv_dual(a, q, (hipStream_t)stream), "iconv2d_dual_brelu");
+    if (pc) {
+        if (!aligned16(pc)) return fail(ICNN_E_ALIGN, "packed channel parameters must be 16-byte aligned");
+        if (m->out_mode == ICNN_OUT_RAW_S32) return fail(ICNN_E_UNSUPPORTED, "fused block with channel parameters needs an 8-bit output");
+        a.pc = (const int32_t *)pc;
+        a.pc_fast_ok = a.epi_vec;       // the main layer's arguments carry no skip operand here
+    }
+    return launched(launch_conv_dual(a, q, (hipStream_t)stream), what);
+}
+
+int iconv2d_dual_brelu(const icnn_conv_desc *m, const void *x_main, const void *w_main_packed,
+                       const int32_t *bias_main, const icnn_conv_desc *p, const void *x_proj,
+                       const void *w_proj_packed, const int32_t *bias_proj, void *y, void *stream)
+{
+    return dual_layer(m, x_main, w_main_packed, bias_main, nullptr, p, x_proj, w_proj_packed, bias_proj, y, stream,
+                      "iconv2d_dual_brelu");
+}
+
+int iconv2d_dual_brelu_pc(const icnn_conv_desc *m, const void *x_main, const void *w_main_packed,
+                          const int32_t *bias_main, const void *pc_packed_main, const icnn_conv_desc *p,
+                          const void *x_proj, const void *w_proj_packed, const int32_t *bias_proj, void *y, void *stream)
+{
+    if (!pc_packed_main) return fail(ICNN_E_NULL, "packed channel parameters are NULL");
+    return dual_layer(m, x_main, w_main_packed, bias_main, pc_packed_main, p, x_proj, w_proj_packed, bias_proj, y, stream,
+                      "iconv2d_dual_brelu_pc");
 }
 
 int iadd_rescale(const icnn_add_desc *d, const void *a, const void *b, void *out, void *stream)

@@ -12,13 +12,15 @@
 // cannot leave int32; the host proves this from the layer sizes and the bias contract before
 // launching (otherwise the caller runs the two layers separately).  The int32 projection tensor
 // never exists in memory.  Tile machinery as in conv_dlds_kernel (pointwise addressing).
+// PC: res_mul / res_shift and mul / shift per output channel (packed parameters, copied to LDS one
+// tile ahead so that they are in place from the first barrier of the tile's K loop on).
 #include "conv_common.h"
 
 #include <type_traits>
 
 namespace icnn {
 
-template <int BM, int BP, int WAVES_M, int WAVES_P>
+template <int BM, int BP, int WAVES_M, int WAVES_P, bool PC>
 __global__ __launch_bounds__(256, 2) void conv_dual_kernel(const ConvArgs a, const ProjArgs q)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the buffer-resource type exists in the device pass only
@@ -120,8 +122,27 @@ __global__ __launch_bounds__(256, 2) void conv_dual_kernel(const ConvArgs a, con
     const int b_rd0 = A_BYTES + b_slot_offset(wp * TP * 32 + (lane & 31), (lane >> 5));
     const int b_rd1 = A_BYTES + b_slot_offset(wp * TP * 32 + (lane & 31), 2 + (lane >> 5));
 
+    // PC: two LDS slots behind the ring take the packed parameters of the current and the next tile
+    constexpr int PC_BYTES = (BM / 16) * kPcGroupInts * 4;
+    constexpr int PC_SLOT = (PC_BYTES + 1023) & ~1023;
+    const __amdgpu_buffer_rsrc_t rs_pc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)a.pc, 0, PC ? ((a.Cout + 15) >> 4) * kPcGroupInts * 4 : 0, 0x00020000);
+    uint8_t *const pc_lds = lds + nstages * STAGE;
+    int pc_slot = 0;
+    auto issue_params = [&](int ct_, int slot) {
+#pragma unroll
+        for (int c = 0; c * 4096 < PC_SLOT; ++c) {
+            const int o = c * 4096 + wave * 1024;
+            if (o < PC_SLOT)          // wave-uniform; lanes beyond the tile's parameters and groups beyond cout get zeros
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    rs_pc, (__attribute__((address_space(3))) void *)(pc_lds + slot * PC_SLOT + o), 16,
+                    o + lane * 16 < PC_BYTES ? (unsigned)(ct_ * PC_BYTES + o + lane * 16) : OOB, 0, 0, 0);
+        }
+    };
+
     tile_of(vtile, ct, pt);
     setup_load_side(ct, pt);
+    if constexpr (PC) issue_params(ct, pc_slot);    // older than every stage copy: landed by the first counted wait
     int buf = 0, ibuf = 0;
     for (int s = 0; s < depth; ++s) {
 #pragma unroll
@@ -181,13 +202,33 @@ __global__ __launch_bounds__(256, 2) void conv_dual_kernel(const ConvArgs a, con
             buf = buf + 1 == nstages ? 0 : buf + 1;
             if (s == kp - 1) {
                 // the projection sum is complete: bring it to the main path's ratio, add the main bias
+                if constexpr (PC) {
+                    // every wave's parameter copy landed before this step's barrier (see issue_params)
+                    const int32_t *groups = (const int32_t *)(pc_lds + pc_slot * PC_SLOT);
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
+                    for (int i = 0; i < TM; ++i) {
+                        const int32_t *g = groups + (wm * TM * 2 + i * 2 + (lane >> 5)) * kPcGroupInts;
 #pragma unroll
-                    for (int j = 0; j < TP; ++j)
+                        for (int q4 = 0; q4 < 4; ++q4) {
+                            const v4i rmu = *(const v4i *)(g + kPcResMul + 4 * q4), rsf = *(const v4i *)(g + kPcResShift + 4 * q4);
 #pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            acc[i][j][r] = (int)rsr64((int64_t)acc[i][j][r] * q.res_mul, q.res_shift) + bias_main[i][r];
+                            for (int j = 0; j < TP; ++j)
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) {
+                                    const int r = 4 * q4 + e;
+                                    acc[i][j][r] = (int)rsr64((int64_t)acc[i][j][r] * rmu[e], rsf[e] & 63) + bias_main[i][r];
+                                }
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TP; ++j)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r)
+                                acc[i][j][r] = (int)rsr64((int64_t)acc[i][j][r] * q.res_mul, q.res_shift) + bias_main[i][r];
+                }
             }
         };
         const int main_steps = ksteps - depth;
@@ -204,6 +245,8 @@ __global__ __launch_bounds__(256, 2) void conv_dual_kernel(const ConvArgs a, con
         const bool more = vtile < a.n_vtiles && tile_of(vtile, ct, pt);
         if (more) {
             setup_load_side(ct, pt);
+            // the other slot: no wave reads it any more (all have passed this tile's barriers)
+            if constexpr (PC) issue_params(ct, pc_slot ^ 1);
             for (int s = 0; s < depth; ++s) {
 #pragma unroll
                 for (int c = 0; c < LPS; ++c) issue_copy(c, s, lds + ibuf * STAGE);
@@ -211,7 +254,18 @@ __global__ __launch_bounds__(256, 2) void conv_dual_kernel(const ConvArgs a, con
             }
             load_bias_rows<TM>(pb, ct * BM + wm * TM * 32, lane >> 5, bias_next);
         }
-        epilogue_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane);
+        if constexpr (PC) {
+            v4i no_res[TM][TP];     // the main layer's descriptor carries no skip operand here
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TP; ++j) no_res[i][j] = v4i{0, 0, 0, 0};
+            epilogue_pc_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane, no_res, (const int32_t *)(pc_lds + pc_slot * PC_SLOT),
+                                      co_wave - wm * TM * 32);
+            pc_slot ^= 1;
+        } else {
+            epilogue_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane);
+        }
         if (!more) break;
         // no drain: the stores are younger than the copies the next K loop waits for, and a counted
         // wait only gets stricter with younger operations in flight
@@ -219,7 +273,7 @@ __global__ __launch_bounds__(256, 2) void conv_dual_kernel(const ConvArgs a, con
 #endif
 }
 
-template <int BM, int BP, int WAVES_M, int WAVES_P>
+template <int BM, int BP, int WAVES_M, int WAVES_P, bool PC>
 static hipError_t launch_dual_cfg(const ConvArgs &a0, const ProjArgs &q, hipStream_t st)
 {
     ConvArgs a = a0;
@@ -230,20 +284,20 @@ static hipError_t launch_dual_cfg(const ConvArgs &a0, const ProjArgs &q, hipStre
     if (a.nstages < 2) a.nstages = 2;
     a.div_howo = make_fast_div((unsigned)(a.Ho * a.Wo));
     a.div_wo = make_fast_div((unsigned)a.Wo);
-    const size_t lds_bytes = (size_t)a.nstages * (BM + BP) * kStepK;
+    const size_t lds_bytes = (size_t)a.nstages * (BM + BP) * kStepK + (PC ? 2 * (((BM / 16) * kPcGroupInts * 4 + 1023) & ~1023) : 0);
     a.n_vtiles = 8 * a.per_xcd;
     const int slots = 256 * 2;
     const dim3 grid((unsigned)(a.n_vtiles < slots ? a.n_vtiles : slots)), block(256);
     if (lds_bytes > 64 * 1024) {
         static bool raised = false;                      // once per kernel: allow > 64 KiB dynamic LDS
         if (!raised) {
-            const hipError_t e = hipFuncSetAttribute((const void *)conv_dual_kernel<BM, BP, WAVES_M, WAVES_P>,
+            const hipError_t e = hipFuncSetAttribute((const void *)conv_dual_kernel<BM, BP, WAVES_M, WAVES_P, PC>,
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
             if (e != hipSuccess) return e;
             raised = true;
         }
     }
-    hipLaunchKernelGGL((conv_dual_kernel<BM, BP, WAVES_M, WAVES_P>), grid, block, lds_bytes, st, a, q);
+    hipLaunchKernelGGL((conv_dual_kernel<BM, BP, WAVES_M, WAVES_P, PC>), grid, block, lds_bytes, st, a, q);
     return hipGetLastError();
 }
 
@@ -251,8 +305,12 @@ hipError_t launch_conv_dual(const ConvArgs &a, const ProjArgs &q, hipStream_t st
 {
     // narrow pixel tiles when the wide ones would leave most CUs without work
     const long long wide = (long long)((a.Cout + 127) / 128) * ((a.M + 127) / 128);
-    if (wide >= 256) return launch_dual_cfg<128, 128, 2, 2>(a, q, st);
-    return launch_dual_cfg<128, 64, 2, 2>(a, q, st);
+    if (a.pc) {
+        if (wide >= 256) return launch_dual_cfg<128, 128, 2, 2, true>(a, q, st);
+        return launch_dual_cfg<128, 64, 2, 2, true>(a, q, st);
+    }
+    if (wide >= 256) return launch_dual_cfg<128, 128, 2, 2, false>(a, q, st);
+    return launch_dual_cfg<128, 64, 2, 2, false>(a, q, st);
 }
 
 }  // namespace icnn

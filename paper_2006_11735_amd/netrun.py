@@ -43,7 +43,7 @@ class GpuNet:
                     continue
                 if op["res"] in pending:
                     proj = pending.pop(op["res"])
-                    dual = self._try_fuse(step, proj) if step[0] == "conv" else None
+                    dual = self._try_fuse(step, proj)
                     if dual is not None:
                         self.fused.append(op["res"])
                         self.fused_proj[op["name"]] = proj[1]
@@ -102,20 +102,32 @@ class GpuNet:
                 arrs += [col("res_mul_c", ("res_mul", 1)), col("res_shift_c", ("res_shift", 0))]
             pcp = torch.empty(B.iconv2d_packed_channel_params_bytes(d), dtype=torch.uint8, device=self.device)
             B.iconv2d_prepack_channel_params(d, B.channel_params(*arrs), pcp)
+            if res is not None:
+                # the descriptor's own pair bounds the per-channel skip ratios (what the fused block's
+                # overflow proof needs; the plain per-channel call does not read it)
+                rm, rs = max(zip(cal["res_mul_c"], cal["res_shift_c"]), key=lambda t: t[0] / 2.0 ** t[1])
+                d.res_mul, d.res_shift = rm, rs
             torch.cuda.synchronize(self.device)   # the arrays may be released after the prepack ran
             return ("conv_pc", op, (d, src, wp, bias, pcp, res, dst, ws))
         return ("conv", op, (d, src, wp, bias, res, dst, ws))
 
     def _try_fuse(self, main, proj):
-        (dm, xm, wm, bm, _res, y, _ws), (dp, xp, wp, bp, _r, _sk, _w) = main[2], proj[2]
-        args = (dm, xm, wm, bm, dp, xp, wp, bp, y)
+        if proj[0] != "conv":
+            return None
+        dp, xp, wp, bp, _r, _sk, _w = proj[2]
+        if main[0] == "conv_pc":
+            dm, xm, wm, bm, pcp, _res, y, _ws = main[2]
+            kind, fn, args = "dual_pc", B.iconv2d_dual_brelu_pc, (dm, xm, wm, bm, pcp, dp, xp, wp, bp, y)
+        else:
+            dm, xm, wm, bm, _res, y, _ws = main[2]
+            kind, fn, args = "dual", B.iconv2d_dual_brelu, (dm, xm, wm, bm, dp, xp, wp, bp, y)
         try:
-            B.iconv2d_dual_brelu(*args)     # also a warm-up launch
+            fn(*args)                       # also a warm-up launch
         except B.IcnnError as e:
             if e.code == B.ICNN_E_UNSUPPORTED:
                 return None
             raise
-        return ("dual", main[1], args)
+        return (kind, main[1], args)
 
     def set_input(self, x_raw=None):
         if x_raw is None:
@@ -134,6 +146,8 @@ class GpuNet:
             B.iconv2d_brelu_pc(*args, stream=stream)
         elif kind == "dual":
             B.iconv2d_dual_brelu(*args, stream=stream)
+        elif kind == "dual_pc":
+            B.iconv2d_dual_brelu_pc(*args, stream=stream)
         elif kind == "maxpool":
             B.imaxpool2d_u8(*args, stream=stream)
         else:

@@ -205,6 +205,51 @@ def test_fused_projection_block_equals_the_two_layers(shape):
     assert (got == want).all() and want.max() == 127 and want.min() == 0
 
 
+@pytest.mark.parametrize("shape", [(2, 28, 28, 64, 256, 64, 1), (1, 9, 7, 128, 80, 48, 2)], ids=lambda s: "x".join(map(str, s)))
+def test_fused_projection_block_with_per_channel_parameters(shape):
+    """iconv2d_dual_brelu_pc == the two per-channel layers of the oracle (Sections 3.4.3 and 4.1)."""
+    import torch
+    from gpu_util import dev
+    from paper_2006_11735_amd import binding as B
+    n, ho, wo, cin_p, cout, cin_m, stride = shape
+    g = rnd(sum(shape) + 1)
+    hp, wp_ = ho * stride, wo * stride
+    x_p = g.integers(0, 128, size=(n, hp, wp_, cin_p), dtype=np.uint8)
+    x_m = g.integers(0, 128, size=(n, ho, wo, cin_m), dtype=np.uint8)
+    w_p = g.integers(-127, 128, size=(cout, 1, 1, cin_p), dtype=np.int8)
+    w_m = g.integers(-127, 128, size=(cout, 1, 1, cin_m), dtype=np.int8)
+    b_p = g.integers(-4096, 4097, size=cout).astype(np.int32)
+    b_m = g.integers(-(1 << 20), 1 << 20, size=cout).astype(np.int32)
+    rmul_c = g.integers(1 << 14, 1 << 15, size=cout).astype(np.int32)
+    rshift_c = g.integers(13, 17, size=cout).astype(np.int32)
+    pairs = [TRICKY[(3 * i) % len(TRICKY)] if i % 5 == 0 else (int(g.integers(1 << 14, 1 << 15)), int(g.integers(24, 29)))
+             for i in range(cout)]
+    mul_c = np.array([p[0] for p in pairs], np.int32)
+    shift_c = np.array([p[1] for p in pairs], np.int32)
+    y_p = O.conv2d(x_p, w_p, b_p, stride=stride, pad=0, out_mode="raw_s32")
+    want = O.conv2d(x_m, w_m, b_m, stride=1, pad=0, mul_c=mul_c, shift_c=shift_c, bound_q=127, res=y_p, res_mode="pre",
+                    res_mul_c=rmul_c, res_shift_c=rshift_c)
+    k = int(np.argmax(rmul_c / 2.0 ** rshift_c))
+    dm = B.conv_desc(n=n, h=ho, w=wo, cin=cin_m, in_c_stride=cin_m, cout=cout, kh=1, kw=1, out_c_stride=cout,
+                     bound_q=127, res_mode=B.ICNN_RES_PRE, res_dtype=B.ICNN_S32, res_c_stride=cout,
+                     res_mul=int(rmul_c[k]), res_shift=int(rshift_c[k]))
+    dp = B.conv_desc(n=n, h=hp, w=wp_, cin=cin_p, in_c_stride=cin_p, cout=cout, kh=1, kw=1, stride_h=stride,
+                     stride_w=stride, out_c_stride=cout, out_mode=B.ICNN_OUT_RAW_S32)
+    packs = []
+    for d, w in ((dm, w_m), (dp, w_p)):
+        pk = torch.zeros(B.iconv2d_packed_weight_bytes(d), dtype=torch.uint8, device="cuda:0")
+        B.iconv2d_prepack_weights(d, dev(w), pk)
+        packs.append(pk)
+    arrs = [dev(a) for a in (mul_c, shift_c, rmul_c, rshift_c)]
+    pcp = torch.zeros(B.iconv2d_packed_channel_params_bytes(dm), dtype=torch.uint8, device="cuda:0")
+    B.iconv2d_prepack_channel_params(dm, B.channel_params(*arrs), pcp)
+    y = torch.zeros((n, ho, wo, cout), dtype=torch.uint8, device="cuda:0")
+    B.iconv2d_dual_brelu_pc(dm, dev(x_m), packs[0], dev(b_m), pcp, dp, dev(x_p), packs[1], dev(b_p), y)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy()
+    assert (got == want).all() and want.max() == 127 and want.min() == 0
+
+
 def test_fused_block_refuses_what_it_cannot_prove_or_run():
     from paper_2006_11735_amd import binding as B
     dm = B.conv_desc(n=1, h=8, w=8, cin=64, in_c_stride=64, cout=64, kh=1, kw=1, out_c_stride=64, mul=20000, shift=24,

@@ -45,11 +45,13 @@ def test_small_resnet_with_per_channel_requantisation(seed):
     calib, _ = ONet.calibrate(net, seed, per_channel=True)
     assert "mul_c" in calib["conv"]["stem"] and "res_mul_c" in calib["conv"]["s1b0_c3"]
     want = ONet.run(net, seed, calib)
-    g = GpuNet(net, seed, calib)
-    assert any(st[0] == "conv_pc" for st in g.steps)
-    g.set_input()
-    g.run()
-    compare_all(net, g, want)
+    for fuse in (False, True):
+        g = GpuNet(net, seed, calib, fuse=fuse)
+        assert any(st[0] == "conv_pc" for st in g.steps)
+        assert any(st[0] == "dual_pc" for st in g.steps) == fuse      # the block whose sum provably fits int32
+        g.set_input()
+        g.run()
+        compare_all(net, g, want)
 
 
 def test_resnet50_shape_per_channel_batch_8():
@@ -80,8 +82,11 @@ def test_config3_per_channel_full_batch_sampled_images():
     for img in (1, 62):
         want = ONet.run(net, 0, calib, images=1, x_raw=np.ascontiguousarray(x[img:img + 1]))
         for name in net["buffers"]:
+            if name in g.fused:
+                continue
             got = g.result(name)[img:img + 1]
             assert (got == want[name]).all(), (img, name)
+    assert len(g.fused) == 4
 
 
 def stored(cfg):
