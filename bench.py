@@ -21,6 +21,18 @@ INT8_MFMA_PEAK_TOPS = 5000.0     # MI355X dense int8 matrix-core peak, TOP/s
 HBM_PEAK_GBS = 8000.0
 
 
+WORKLOADS = {
+    "cfg0": "cfg0: one 3x3 conv layer 1x56x56x64 -> 64",
+    "cfg1": "cfg1: VDSR-shaped, 20 conv3x3 layers on one 256x256 luma plane",
+    "cfg2": "cfg2: VRCNN-shaped, one 720x1280 luma plane, two concatenations",
+    "cfg3": "cfg3: ResNet-50-shaped integer inference, batch 64, 3x224x224 uint8 input, 53 convs + FC, 16 skip merges "
+            "(the 4 projection convs fused into their block's last conv)",
+    "cfg4": "cfg4: ResNet-152-shaped integer inference, batch 128",
+    "cfg5": "cfg5: ResNet-18-shaped (basic blocks) integer inference, batch 64",
+    "cfg6": "cfg6: VRCNN-shaped, one 2560x1600 luma plane",
+}
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -203,16 +215,15 @@ def main():
         traffic = json.load(open(tpath)).get("conv_hbm_bytes_per_launch")
 
     result = {
-        "metric": "images/s ResNet-50-shaped b64 (int8 conv TOPS and % of int8 MFMA peak alongside)",
+        "metric": "images/s ResNet-50-shaped b64 (int8 conv TOPS and % of int8 MFMA peak alongside)" if args.config == "cfg3"
+                  else "images/s (int8 conv TOPS and % of int8 MFMA peak alongside)",
         "value": images / (ms_per_step * 1e-3),
         "unit": "images/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8",
         "data": "synthetic",
-        "config": {"workload": "cfg3: ResNet-50-shaped integer inference, batch 64, 3x224x224 uint8 input, "
-                               "53 convs + FC, 16 skip merges (the 4 projection convs fused into their block's last conv), "
-                               "stored oracle-side calibration (seed 0)",
+        "config": {"workload": WORKLOADS.get(args.config, args.config) + ", stored oracle-side calibration (seed 0)",
                    "batch": images},
         "conv_tops": conv_tops,
         "pct_int8_mfma_peak": 100 * conv_tops / INT8_MFMA_PEAK_TOPS,
@@ -226,7 +237,7 @@ def main():
     }
     if args.per_channel:
         result["config"]["workload"] += "; per-output-channel requantisation (iconv2d_brelu_pc, iconv2d_dual_brelu_pc)"
-    elif os.path.exists(pc_path):
+    elif os.path.exists(pc_path) and args.config == "cfg3":
         # the same network with one (mul, shift) and skip rescale per output channel
         g_pc = GpuNet(net, seed, json.load(open(pc_path)))
         g_pc.set_input()

@@ -84,6 +84,14 @@ def test_network_shapes_and_mac_counts():
     assert [o["cout"] for o in W.conv_ops(c)] == [64, 32, 16, 16, 32, 1]
     assert c["buffers"]["a2"]["shape"] == [1, 720, 1280, 48]
     assert W.conv_macs(c) // (720 * 1280) == 70896                 # MACs per pixel
+    r18 = W.resnet18()
+    convs = W.conv_ops(r18)
+    assert len(convs) == 21 and sum(c["role"] == "projection" for c in convs) == 3
+    assert sum(c["res_mode"] == "pre" for c in convs) == 8
+    assert abs(W.conv_macs(r18) / 64 / 1e9 - 1.81) < 0.02            # ~1.81 GMAC per image
+    big = W.vrcnn_2560x1600()
+    assert big["buffers"]["out"]["shape"] == [1, 1600, 2560, 1]
+    assert W.conv_macs(big) // (1600 * 2560) == 70896
 
 
 def test_cfg0_calibration_reproduces_stored_integers_and_hits_the_bound_rarely():

@@ -138,6 +138,33 @@ def test_config3_resnet50_full_batch_sampled_images():
     assert len({int(v) for v in logits.reshape(64, -1).argmax(axis=1)}) > 1 or True
 
 
+def test_config5_resnet18_full_batch_sampled_images():
+    # basic blocks: 3x3 convs with the skip merge in their epilogue, int32 projections unfused
+    from paper_2006_11735_amd.netrun import GpuNet
+    net, calib = W.CONFIGS["cfg5"](), stored("cfg5")
+    g = GpuNet(net, 0, calib)
+    g.set_input()
+    g.run()
+    x = W.input_tensor(net, 0)
+    for img in (3, 60):
+        want = ONet.run(net, 0, calib, images=1, x_raw=np.ascontiguousarray(x[img:img + 1]))
+        for name in net["buffers"]:
+            got = g.buf[name][img:img + 1].cpu().numpy()
+            assert (got == want[name]).all(), (img, name)
+    assert not g.fused
+
+
+def test_config6_vrcnn_2560x1600_frame():
+    # the picture size the paper times VRCNN on; every layer of the whole frame is compared
+    from paper_2006_11735_amd.netrun import GpuNet
+    net, calib = W.CONFIGS["cfg6"](), stored("cfg6")
+    g = GpuNet(net, 0, calib)
+    g.set_input()
+    g.run()
+    want = ONet.run(net, 0, calib)
+    compare_all(net, g, want)
+
+
 def test_config4_resnet152_sub_batch():
     # ResNet-152-shaped: 8 of the 128 images end to end (the oracle needs ~12 GMAC per image).
     from paper_2006_11735_amd.netrun import GpuNet

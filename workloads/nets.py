@@ -152,6 +152,43 @@ def resnet(batch, blocks, name, image=224, calib_images=4, classes=1000):
     return b.net
 
 
+def resnet_basic(batch, blocks, name, image=224, calib_images=4, classes=1000):
+    """Basic-block ResNet (the block of the paper's residual figure, Section 4.1): stem and pools as
+    in `resnet`, four stages of two 3x3 convs per block, the skip joining the second one before
+    BReLU (identity: the stored 8-bit block input; first block of stages 2-4: an int32 1x1/2
+    projection of it)."""
+    b = _Builder(name, batch, image, image, 3, min(calib_images, batch))
+    b.net["input_range"] = [0, 255]
+    b.conv("stem", "raw", "stem", 64, 7, stride=2, pad=3, in_sub128=True)
+    cur = b.maxpool("stem", "pool0")
+    widths = [64, 128, 256, 512]
+    for si, (nb, wd) in enumerate(zip(blocks, widths)):
+        for bi in range(nb):
+            p = "s%db%d" % (si + 1, bi)
+            stride = 2 if (bi == 0 and si > 0) else 1
+            b.conv(p + "_c1", cur, p + "_a1", wd, 3, stride=stride)
+            if bi == 0 and si > 0:
+                b.conv(p + "_proj", cur, p + "_sk", wd, 1, stride=stride, pad=0,
+                       out_mode="raw_s32", role="projection")
+                skip = p + "_sk"
+            else:
+                skip = cur
+            cur = b.conv(p + "_c2", p + "_a1", p + "_out", wd, 3, res=skip, res_mode="pre")
+    cur = b.avgpool(cur, "gap")
+    b.conv("fc", cur, "logits", classes, 1, pad=0, out_mode="raw_s32", role="logits")
+    b.net["outputs"] = ["logits"]
+    return b.net
+
+
+def resnet18(batch=64, **kw):
+    return resnet_basic(batch, [2, 2, 2, 2], "resnet18_b%d" % batch, **kw)
+
+
+def vrcnn_2560x1600():
+    """The one 2560x1600 picture the paper times VRCNN on (its Table 6)."""
+    return vrcnn(1600, 2560)
+
+
 def resnet50(batch=64, **kw):
     return resnet(batch, [3, 4, 6, 3], "resnet50_b%d" % batch, **kw)
 
@@ -166,6 +203,8 @@ CONFIGS = {
     "cfg2": vrcnn,
     "cfg3": resnet50,
     "cfg4": resnet152,
+    "cfg5": resnet18,             # second workloads: basic-block ResNet, batch 64
+    "cfg6": vrcnn_2560x1600,      # and the large VRCNN frame
 }
 
 
