@@ -104,6 +104,16 @@ def test_global_average_pool_and_renormalise():
     B.iavgpool_global_u8(5, 7, 7, 2048, 21400, 20, 127, dev(x), out)
     torch.cuda.synchronize()
     assert (out.cpu().numpy() == want).all()
+    # ragged channel counts (one partly filled workgroup; the scalar kernel for c % 4 != 0), odd window sizes,
+    # values up to 255, a clamp that bites
+    for (n, h, w, c, mul, shift, bound) in ((3, 5, 6, 300, 17476, 19, 127), (2, 3, 3, 7, 29127, 18, 255), (1, 1, 1, 64, 1, 0, 90),
+                                            (2, 13, 11, 1028, 30000, 20, 127)):
+        x = rnd(60 + c).integers(0, 256, size=(n, h, w, c), dtype=np.uint8)
+        want = O.avgpool_global(x, mul, shift, bound)
+        out = torch.zeros((n, 1, 1, c), dtype=torch.uint8, device="cuda:0")
+        B.iavgpool_global_u8(n, h, w, c, mul, shift, bound, dev(x), out)
+        torch.cuda.synchronize()
+        assert (out.cpu().numpy() == want).all(), (n, h, w, c)
     for count in (4096, 1001):
         raw = rnd(7).integers(0, 256, size=count, dtype=np.uint8)
         o = torch.zeros(count, dtype=torch.uint8, device="cuda:0")
