@@ -187,7 +187,24 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const uint8_t *__restrict_
     const long long t = px / wo_n;
     const int ho = (int)(t % ho_n);
     const long long n = t / ho_n;
-    if (vec) {
+    if (vec && k == 3) {
+        // 3x3 window, branch-free: a position outside the image is replaced by the nearest one inside,
+        // which the window also contains, so the maximum is unchanged and all nine loads are independent
+        uint32_t m[4] = {0, 0, 0, 0};
+        const uint8_t *base = x + (size_t)n * h * w * c + q * 16;
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            const int hi = min(max(ho * stride - pad + i, 0), h - 1);
+#pragma unroll
+            for (int j = 0; j < 3; ++j) {
+                const int wi = min(max(wo * stride - pad + j, 0), w - 1);
+                const v4i v = *(const v4i *)(base + ((size_t)hi * w + wi) * c);
+                m[0] = max_u8x4(m[0], (uint32_t)v.x); m[1] = max_u8x4(m[1], (uint32_t)v.y);
+                m[2] = max_u8x4(m[2], (uint32_t)v.z); m[3] = max_u8x4(m[3], (uint32_t)v.w);
+            }
+        }
+        *(v4i *)(out + (size_t)px * c + q * 16) = v4i{(int)m[0], (int)m[1], (int)m[2], (int)m[3]};
+    } else if (vec) {
         uint32_t m[4] = {0, 0, 0, 0};
         for (int i = 0; i < k; ++i) {
             const int hi = ho * stride - pad + i;
