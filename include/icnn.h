@@ -53,6 +53,12 @@ typedef enum {
 } icnn_out_mode;
 
 typedef enum {
+    ICNN_IN_U8_LE127 = 0,    /* unsigned bytes, all <= 127 (caller's guarantee)   */
+    ICNN_IN_S8 = 1,          /* signed bytes                                      */
+    ICNN_IN_U8_FULL = 2      /* unsigned bytes, any value up to 255               */
+} icnn_in_kind;
+
+typedef enum {
     ICNN_RES_NONE = 0,
     ICNN_RES_PRE = 1,        /* skip operand joins before BReLU / requantisation  */
     ICNN_RES_POST = 2        /* skip operand joins after requantisation           */
@@ -66,8 +72,11 @@ typedef enum {
  *   U[n,ho,wo,co] = sum_{kh,kw,ci} x(n, ho*stride_h - pad_h + kh, wo*stride_w - pad_w + kw, ci)
  *                                  * W[co][kh][kw][ci]
  *       x() is 0 outside the image; inside it is the stored byte read as uint8
- *       (in_signed = 0), as int8 (in_signed = 1), or as uint8 minus 128
- *       (in_sub128 = 1: the re-normalisation of a raw picture, Section 3.4.1).
+ *       (in_signed = ICNN_IN_U8_LE127 when the caller guarantees bytes <= 127, as layers
+ *       with bound_q <= 127 produce; ICNN_IN_U8_FULL for any byte: the 8-bit activations
+ *       of the paper's bit-depth table, bound_q up to 255), as int8 (ICNN_IN_S8), or as
+ *       uint8 minus 128 (in_sub128 = 1: the re-normalisation of a raw picture, Section
+ *       3.4.1).  ICNN_IN_U8_FULL limits kh*kw*cin to 32767.
  *   Y = U + bias[co]                     (caller guarantees |bias[co]| <= 2^30, so that
  *                                         Y always fits int32; kh*kw*cin <= 65535 bounds U)
  *   S = [res * res_mul / 2^res_shift]                       (res_mode != NONE)
@@ -88,7 +97,7 @@ typedef enum {
 typedef struct {
     int32_t n, h, w, cin;          /* logical input shape                          */
     int32_t in_c_stride;           /* channel pitch of x, >= cin                   */
-    int32_t in_signed;             /* 0: uint8 bytes, 1: int8 bytes                */
+    int32_t in_signed;             /* icnn_in_kind                                 */
     int32_t in_sub128;             /* 1: raw uint8 picture, use x - 128            */
     int32_t cout, kh, kw;
     int32_t stride_h, stride_w, pad_h, pad_w;

@@ -72,7 +72,7 @@ def sync_concat(h_ri, ratio_y, max_int=MAX_INT):
     """Algorithm 2 for N branches given each branch's bound h_ri[i] (integer, in its
     own Y domain) and ratio_Y[i].  Returns per-branch (mul, shift, bound_q) and the
     common output ratio."""
-    own = [bound_params(h) for h in h_ri]
+    own = [bound_params(h, max_int) for h in h_ri]
     ratio_v = [Fraction(ry) * m / (1 << s) for ry, (m, s) in zip(ratio_y, own)]
     ratio_min = min(ratio_v)
     out = []

@@ -62,7 +62,7 @@ def run(net, seed, calib, images=None, x_raw=None):
     return bufs
 
 
-def calibrate(net, seed, per_channel=False):
+def calibrate(net, seed, per_channel=False, max_int=K.MAX_INT):
     """Returns (calib, buffers on the calibration images).
 
     calib = {"conv": {name: {...integers...}}, "avgpool": {dst: {...}}, "ratio": {...}}
@@ -70,11 +70,13 @@ def calibrate(net, seed, per_channel=False):
     rescale per output channel ("mul_c", "shift_c", "res_mul_c", "res_shift_c"), each from
     that channel's own statistic (Section 3.4.3: one weight step per output channel).
     Concatenated branches, regression outputs and raw int32 outputs stay per layer.
+    max_int: the largest quantised activation (Section 3.3), 2^bits - 1: 127 for the 7-bit
+    activations of the main experiments, 255 / 63 / 31 / 15 for the other bit-depths the paper tries.
     """
     n_img = net["calib_images"]
     bufs = {"raw": W.input_tensor(net, seed, n_img)}
     ratio = {"raw": Fraction(INPUT_RATIO)}      # ratio_V of every stored buffer
-    calib = {"conv": {}, "avgpool": {}}
+    calib = {"conv": {}, "avgpool": {}, "max_int": int(max_int)}
     ops = net["ops"]
     i = 0
     while i < len(ops):
@@ -87,8 +89,8 @@ def calibrate(net, seed, per_channel=False):
         if op["op"] == "avgpool":
             _, h, w, _ = bufs[op["src"]].shape
             m, s = K.mul_shift(h * w, 1)
-            calib["avgpool"][op["dst"]] = {"mul": m, "shift": s, "bound_q": K.MAX_INT}
-            bufs[op["dst"]] = O.avgpool_global(bufs[op["src"]], m, s, K.MAX_INT)
+            calib["avgpool"][op["dst"]] = {"mul": m, "shift": s, "bound_q": max_int}
+            bufs[op["dst"]] = O.avgpool_global(bufs[op["src"]], m, s, max_int)
             ratio[op["dst"]] = ratio[op["src"]]
             i += 1
             continue
@@ -99,7 +101,7 @@ def calibrate(net, seed, per_channel=False):
                 group.append(ops[i + len(group)])
         wts = [W.weight_tensor(g, seed) for g in group]
         bss = [W.bias_tensor(g, seed) for g in group]
-        ratio_y = [ratio[g["src"]] * Fraction(K.MAX_INT) / Fraction(W.float_weight_absmax(g, seed))
+        ratio_y = [ratio[g["src"]] * Fraction(K.MAX_INT) / Fraction(W.float_weight_absmax(g, seed))     # weights: 8 bits
                    for g in group]
         if op["dst"] not in bufs:
             bufs[op["dst"]] = _alloc(net, op["dst"], n_img)
@@ -108,7 +110,7 @@ def calibrate(net, seed, per_channel=False):
             for g, w, b in zip(group, wts, bss):
                 t = _conv(g, bufs, w, b, {}, None, out_mode="raw_s32")
                 h_ri.append(K.percentile_999(t))
-            params, r_min = K.sync_concat(h_ri, ratio_y)
+            params, r_min = K.sync_concat(h_ri, ratio_y, max_int)
             for g, w, b, (m, s, bq), h in zip(group, wts, bss, params, h_ri):
                 cal = {"mul": m, "shift": s, "bound_q": bq, "h_ri": h}
                 calib["conv"][g["name"]] = cal
@@ -125,7 +127,7 @@ def calibrate(net, seed, per_channel=False):
             if op["res_dtype"] == "s32":
                 h_skip = K.percentile_999(bufs[op["res"]])
             else:
-                h_skip = K.MAX_INT
+                h_skip = max_int
             cal["res_mul"], cal["res_shift"] = K.mul_shift(h_skip, h_main)
             if per_channel and op["out_mode"] == "brelu":
                 cout = y.shape[-1]
@@ -133,7 +135,7 @@ def calibrate(net, seed, per_channel=False):
                 # an int32 skip operand is not clamped, so a channel is scaled by its magnitude (a channel
                 # whose values are mostly negative would otherwise get a bound of 1 and a huge rescale)
                 hs = (K.percentile_999_per_channel(bufs[op["res"]][..., :cout], absolute=True)
-                      if op["res_dtype"] == "s32" else [K.MAX_INT] * cout)
+                      if op["res_dtype"] == "s32" else [max_int] * cout)
                 pairs = [K.mul_shift(a, b) for a, b in zip(hs, hm)]
                 cal["res_mul_c"] = [m for m, _ in pairs]
                 cal["res_shift_c"] = [s for _, s in pairs]
@@ -152,10 +154,10 @@ def calibrate(net, seed, per_channel=False):
         else:
             t = _conv(op, bufs, w, b, cal, None, out_mode="raw_s32")
             h = K.percentile_999(t)
-            m, s = K.bound_params(h)
-            cal.update(mul=m, shift=s, bound_q=K.MAX_INT, h_ri=h)
+            m, s = K.bound_params(h, max_int)
+            cal.update(mul=m, shift=s, bound_q=max_int, h_ri=h)
             if per_channel:
-                pairs = [K.bound_params(hc) for hc in K.percentile_999_per_channel(t)]
+                pairs = [K.bound_params(hc, max_int) for hc in K.percentile_999_per_channel(t)]
                 cal["mul_c"] = [mc for mc, _ in pairs]
                 cal["shift_c"] = [sc for _, sc in pairs]
             calib["conv"][op["name"]] = cal
@@ -166,21 +168,22 @@ def calibrate(net, seed, per_channel=False):
     return calib, bufs
 
 
-def stored_calib_path(cfg, seed, per_channel=False):
+def stored_calib_path(cfg, seed, per_channel=False, max_int=K.MAX_INT):
     import os
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    return os.path.join(root, "workloads", "calib", "%s_seed%d%s.json" % (cfg, seed, "_pc" if per_channel else ""))
+    tag = ("_pc" if per_channel else "") + ("_a%d" % max_int if max_int != K.MAX_INT else "")
+    return os.path.join(root, "workloads", "calib", "%s_seed%d%s.json" % (cfg, seed, tag))
 
 
-def write_stored_calib(cfg, seed, per_channel=False):
+def write_stored_calib(cfg, seed, per_channel=False, max_int=K.MAX_INT):
     """Calibrate config `cfg` with the oracle and store the integers for bench and tests."""
     import json
     net = W.CONFIGS[cfg]()
-    calib, _ = calibrate(net, seed, per_channel)
+    calib, _ = calibrate(net, seed, per_channel, max_int)
     calib["net"] = net["name"]
     calib["seed"] = seed
     calib["written_by"] = "oracle/net.py write_stored_calib (calls only oracle/)"
-    path = stored_calib_path(cfg, seed, per_channel)
+    path = stored_calib_path(cfg, seed, per_channel, max_int)
     with open(path, "w") as f:
         if per_channel:
             json.dump(calib, f, sort_keys=True, separators=(",", ":"))
@@ -192,8 +195,10 @@ def write_stored_calib(cfg, seed, per_channel=False):
 if __name__ == "__main__":
     import sys
     import time
-    # `python -m oracle.net [cfgN ...]` writes the per-layer files, `cfgN:pc` the per-channel one
-    for name in sys.argv[1:] or ["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "cfg3:pc"]:
+    # `python -m oracle.net [cfgN ...]` writes the per-layer files, `cfgN:pc` the per-channel one,
+    # `cfgN:a255` the one with 8-bit activations
+    for name in sys.argv[1:] or ["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "cfg6", "cfg3:pc", "cfg1:a255"]:
         t0 = time.time()
         cfg, _, kind = name.partition(":")
-        print(write_stored_calib(cfg, 0, kind == "pc"), "%.1fs" % (time.time() - t0), flush=True)
+        mi = int(kind[1:]) if kind.startswith("a") else K.MAX_INT
+        print(write_stored_calib(cfg, 0, kind == "pc", mi), "%.1fs" % (time.time() - t0), flush=True)

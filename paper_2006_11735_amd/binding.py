@@ -9,6 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libicnn_mi355.so")
 
 ICNN_OK = 0
+ICNN_IN_U8_LE127, ICNN_IN_S8, ICNN_IN_U8_FULL = 0, 1, 2
 ICNN_E_NULL, ICNN_E_SHAPE, ICNN_E_PARAM, ICNN_E_ALIGN, ICNN_E_UNSUPPORTED, ICNN_E_LAUNCH = -1, -2, -3, -4, -5, -6
 ICNN_U8, ICNN_S8, ICNN_S32 = 0, 1, 2
 ICNN_OUT_BRELU_U8, ICNN_OUT_CLAMP_U8, ICNN_OUT_LINEAR_S8, ICNN_OUT_RAW_S32 = 0, 1, 2, 3

@@ -45,15 +45,17 @@ int check_conv(const icnn_conv_desc *d, ConvGeom *g)
     const long long K = (long long)d->kh * d->kw * d->cin;
     if (K > 65535)
         return fail(ICNN_E_SHAPE, "kh*kw*cin = %lld exceeds 65535: int32 accumulation not provably safe", K);
+    if (d->in_signed == ICNN_IN_U8_FULL && K > 32767)
+        return fail(ICNN_E_SHAPE, "kh*kw*cin = %lld exceeds 32767 with inputs up to 255: int32 accumulation not provably safe", K);
     const long long M = (long long)d->n * ho * wo;
     if (M > 0x7fffffffLL) return fail(ICNN_E_SHAPE, "n*ho*wo = %lld does not fit int32", M);
     if (d->in_c_stride < d->cin) return fail(ICNN_E_SHAPE, "in_c_stride %d < cin %d", d->in_c_stride, d->cin);
     if (d->out_c_offset < 0 || (long long)d->out_c_offset + d->cout > d->out_c_stride)
         return fail(ICNN_E_SHAPE, "out_c_offset %d + cout %d exceeds out_c_stride %d", d->out_c_offset, d->cout,
                     d->out_c_stride);
-    if ((d->in_signed != 0 && d->in_signed != 1) || (d->in_sub128 != 0 && d->in_sub128 != 1) ||
+    if (d->in_signed < ICNN_IN_U8_LE127 || d->in_signed > ICNN_IN_U8_FULL || (d->in_sub128 != 0 && d->in_sub128 != 1) ||
         (d->in_signed && d->in_sub128))
-        return fail(ICNN_E_PARAM, "in_signed / in_sub128 must be 0 or 1 and not both 1");
+        return fail(ICNN_E_PARAM, "in_signed must be 0, 1 or 2, in_sub128 0 or 1 and only with in_signed = 0");
     if (d->out_mode < ICNN_OUT_BRELU_U8 || d->out_mode > ICNN_OUT_RAW_S32)
         return fail(ICNN_E_PARAM, "unknown out_mode %d", d->out_mode);
     if (d->res_mode < ICNN_RES_NONE || d->res_mode > ICNN_RES_POST)
@@ -152,7 +154,8 @@ int iconv2d_packed_weight_bytes(const icnn_conv_desc *desc, size_t *bytes)
     const int rc = check_conv(desc, &g);
     if (rc) return rc;
     if (!bytes) return fail(ICNN_E_NULL, "bytes is NULL");
-    *bytes = (size_t)g.chunks * g.ksteps * kChunkBytes;
+    // the fragment-ordered weights, then one int32 per (padded) output channel: the sum of its weights
+    *bytes = (size_t)g.chunks * g.ksteps * kChunkBytes + (size_t)g.chunks * kChunkCout * sizeof(int32_t);
     return ICNN_OK;
 }
 
@@ -163,6 +166,9 @@ int iconv2d_prepack_weights(const icnn_conv_desc *desc, const int8_t *w_ohwi, vo
     if (rc) return rc;
     if (!w_ohwi || !w_packed) return fail(ICNN_E_NULL, "weight pointer is NULL");
     if (!aligned16(w_packed)) return fail(ICNN_E_ALIGN, "w_packed must be 16-byte aligned");
+    const hipError_t e = launch_wsum(w_ohwi, (int32_t *)((uint8_t *)w_packed + (size_t)g.chunks * g.ksteps * kChunkBytes),
+                                     desc->cout, g.chunks * kChunkCout, desc->kh * desc->kw * desc->cin, (hipStream_t)stream);
+    if (e != hipSuccess) return launched(e, "prepack (weight sums)");
     return launched(launch_prepack(w_ohwi, (uint8_t *)w_packed, desc->cout, g.K, g.chunks, g.ksteps, desc->kh,
                                    desc->kw, desc->cin, g.rp, (hipStream_t)stream),
                     "prepack");
@@ -200,6 +206,8 @@ static int fill_conv_args(const icnn_conv_desc *d, const ConvGeom &g, const void
     a.res_mode = d->res_mode; a.res_dtype = d->res_dtype; a.res_cs = d->res_c_stride;
     a.res_mul = d->res_mode ? d->res_mul : 1; a.res_shift = d->res_mode ? d->res_shift : 0;
     a.in_xor = d->in_sub128 ? 0x80808080u : 0u;
+    a.frag_xor = d->in_signed == ICNN_IN_U8_FULL ? 0x80808080u : 0u;
+    a.wsum = (const int32_t *)((const uint8_t *)w_packed + (size_t)g.chunks * g.ksteps * kChunkBytes);
     const int ob = d->out_mode == ICNN_OUT_RAW_S32 ? 4 : 1;
     a.vec_out = aligned16(y) && ((long long)d->out_c_stride * ob) % 16 == 0 && ((long long)d->out_c_offset * ob) % 16 == 0;
     a.vec_res = 0;
@@ -337,6 +345,7 @@ static int dual_layer(const icnn_conv_desc *m, const void *x_main, const void *w
         return fail(ICNN_E_SHAPE, "main and projection layers must produce the same n x ho x wo x cout");
     const icnn_conv_desc *both[2] = {m, p};
     for (const icnn_conv_desc *d : both) {
+        if (d->in_signed == ICNN_IN_U8_FULL) return fail(ICNN_E_UNSUPPORTED, "fused block takes inputs up to 127 or int8 only");
         if (d->kh != 1 || d->kw != 1 || d->pad_h != 0 || d->pad_w != 0 || d->cin % 16 != 0 || d->in_c_stride % 16 != 0 ||
             d->in_sub128)
             return fail(ICNN_E_UNSUPPORTED, "fused block needs 1x1 layers without padding, cin and pitch multiples of 16");

@@ -388,6 +388,16 @@ __device__ __forceinline__ void load_bias_rows(const ConvArgs &a, int co_base, i
 #pragma unroll
             for (int r = 0; r < 16; ++r) b[i][r] = a.bias[min(co0 + r, a.Cout - 1)];
         }
+        if (a.frag_xor) {
+            // unsigned inputs up to 255: the matrix cores see x - 128, so 128 * (sum of the channel's
+            // weights) is due (wsum is padded to whole 32-channel chunks and 16-byte aligned)
+            const v4i *wp = (const v4i *)(a.wsum + co0);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const v4i v = wp[q];
+                b[i][4 * q] += 128 * v.x; b[i][4 * q + 1] += 128 * v.y; b[i][4 * q + 2] += 128 * v.z; b[i][4 * q + 3] += 128 * v.w;
+            }
+        }
     }
 }
 

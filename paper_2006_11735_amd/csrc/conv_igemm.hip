@@ -35,7 +35,9 @@ namespace icnn {
 //         position is wave-uniform (scalar registers, one bit test per copy);
 // MODE 2: any cin % 16 == 0: every lane tracks the tap of its own 16-byte slot.
 // PC: requantisation and skip rescale per output channel (epilogue_pc_tiles)
-template <int BM, int BP, int WAVES_M, int WAVES_P, int MODE, bool PC>
+// U8: unsigned inputs up to 255: activation fragments are XORed with 0x80 bytes (x - 128) on their way
+//     from LDS to the matrix cores (the bias rows carry the matching correction, see load_bias_rows)
+template <int BM, int BP, int WAVES_M, int WAVES_P, int MODE, bool PC, bool U8>
 __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void conv_dlds_kernel(const ConvArgs a)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the buffer-resource type exists in the device pass only
@@ -270,7 +272,10 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
 #pragma unroll
                 for (int i = 0; i < TM; ++i) af[kq][i] = *(const v4i *)(S + a_rd + (i * 2 + kq) * 1024);
 #pragma unroll
-                for (int j = 0; j < TP; ++j) bf[kq][j] = *(const v4i *)(S + (kq ? b_rd1 : b_rd0) + j * 2048);
+                for (int j = 0; j < TP; ++j) {
+                    bf[kq][j] = *(const v4i *)(S + (kq ? b_rd1 : b_rd0) + j * 2048);
+                    if constexpr (U8) bf[kq][j] ^= v4i{(int)0x80808080, (int)0x80808080, (int)0x80808080, (int)0x80808080};
+                }
             }
             int c = 0;
 #pragma unroll
@@ -464,6 +469,8 @@ __global__ __launch_bounds__(256) void conv_greg_kernel(const ConvArgs a)
 
     v16i acc[TM][TP];
     init_acc_with_bias<TM, TP>(a, ct * BM + wm * TM * 32, lane >> 5, acc);
+    const int fxs = (int)a.frag_xor;
+    const v4i fx = {fxs, fxs, fxs, fxs};     // x - 128 for unsigned inputs up to 255, else 0
 
     load_tiles(0);
     store_tiles(0);
@@ -483,7 +490,7 @@ __global__ __launch_bounds__(256) void conv_greg_kernel(const ConvArgs a)
             for (int i = 0; i < TM; ++i) af[i] = *(const v4i *)(A + ((wm * TM + i) * 2 + kq) * 1024 + lane * 16);
 #pragma unroll
             for (int j = 0; j < TP; ++j)
-                bf[j] = *(const v4i *)(B + b_slot_offset((wp * TP + j) * 32 + (lane & 31), kq * 2 + (lane >> 5)));
+                bf[j] = *(const v4i *)(B + b_slot_offset((wp * TP + j) * 32 + (lane & 31), kq * 2 + (lane >> 5))) ^ fx;
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -536,14 +543,15 @@ static hipError_t launch_dlds(const ConvArgs &a0, int max_stages, int per_cu, hi
         hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, a);
         return hipGetLastError();
     };
-    if (a.pc) {
-        if (mode == 0) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 0, true>);
-        if (mode == 1) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 1, true>);
-        return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 2, true>);
-    }
-    if (mode == 0) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 0, false>);
-    if (mode == 1) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 1, false>);
-    return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 2, false>);
+    auto pick = [&](auto pc_tag, auto u8_tag) -> hipError_t {
+        constexpr bool PC = decltype(pc_tag)::value;
+        constexpr bool U8 = decltype(u8_tag)::value;
+        if (mode == 0) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 0, PC, U8>);
+        if (mode == 1) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 1, PC, U8>);
+        return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 2, PC, U8>);
+    };
+    if (a.pc) return a.frag_xor ? pick(std::true_type{}, std::true_type{}) : pick(std::true_type{}, std::false_type{});
+    return a.frag_xor ? pick(std::false_type{}, std::true_type{}) : pick(std::false_type{}, std::false_type{});
 }
 
 template <int BM, int BP, int WAVES_M, int WAVES_P>
@@ -651,6 +659,24 @@ __global__ void prepack_kernel(const int8_t *__restrict__ w, uint8_t *__restrict
         }
     }
     *(v4i *)(wp + e * 16) = v4i{(int)wd[0], (int)wd[1], (int)wd[2], (int)wd[3]};
+}
+
+// wsum[co] = sum of output channel co's weights (k_true = kh*kw*cin of them), 0 for the padding channels
+__global__ __launch_bounds__(256) void wsum_kernel(const int8_t *__restrict__ w, int32_t *__restrict__ wsum, int Cout,
+                                                   int cout_padded, int k_true)
+{
+    const int co = blockIdx.x * 256 + threadIdx.x;
+    if (co >= cout_padded) return;
+    int s = 0;
+    if (co < Cout)
+        for (int k = 0; k < k_true; ++k) s += w[(size_t)co * k_true + k];
+    wsum[co] = s;
+}
+
+hipError_t launch_wsum(const int8_t *w, int32_t *wsum, int Cout, int cout_padded, int k_true, hipStream_t st)
+{
+    hipLaunchKernelGGL(wsum_kernel, dim3((cout_padded + 255) / 256), dim3(256), 0, st, w, wsum, Cout, cout_padded, k_true);
+    return hipGetLastError();
 }
 
 hipError_t launch_prepack(const int8_t *w, uint8_t *wp, int Cout, int K, int chunks, int ksteps, int KH, int KW,

@@ -48,6 +48,12 @@ struct ConvArgs {
     int mul, shift, lo, hi, out_mode;
     int res_mode, res_dtype, res_cs, res_mul, res_shift;
     uint32_t in_xor;   // 0x80808080 when the input is a raw picture (x - 128), else 0
+    // Unsigned inputs up to 255 on signed matrix cores: activation fragments are XORed with frag_xor
+    // (0x80808080: x - 128) when they leave LDS, and 128 * wsum[co] (wsum = sum of the channel's weights,
+    // stored behind the packed weights) is added to the bias.  Zero padding and K tails are zero bytes
+    // in LDS, i.e. -128 after the XOR, which the same correction turns back into 0.  Else 0 / unused.
+    uint32_t frag_xor;
+    const int32_t *wsum;
     int vec_out, vec_res;
     int vec_bias; // bias is 16-byte aligned and cout % 16 == 0
     int rq_fast;  // requantisation as one 32x32->64 multiply-add (mul_hi = mul << (32 - shift))
@@ -115,6 +121,7 @@ hipError_t launch_conv(const ConvArgs &a, bool vec_in, bool direct_ok, hipStream
 hipError_t launch_conv_dual(const ConvArgs &a, const ProjArgs &q, hipStream_t st);
 hipError_t launch_prepack(const int8_t *w, uint8_t *wp, int Cout, int K, int chunks, int ksteps, int KH, int KW,
                           int Cin, int rp, hipStream_t st);
+hipError_t launch_wsum(const int8_t *w, int32_t *wsum, int Cout, int cout_padded, int k_true, hipStream_t st);
 hipError_t launch_pc_prepack(const int32_t *mul, const int32_t *shift, const int32_t *res_mul, const int32_t *res_shift,
                              int cout, int32_t *packed, hipStream_t st);
 hipError_t launch_pad_small_cin(const uint8_t *x, void *out, int N, int H, int W, int Cin, int in_cs, int ph, int pw,

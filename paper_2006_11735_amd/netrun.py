@@ -69,8 +69,12 @@ class GpuNet:
         cal = self.calib["conv"][op["name"]]
         src, dst = self.buf[op["src"]], self.buf[op["dst"]]
         n, h, w, cbuf = src.shape
+        # bytes above 127 can occur in activations bounded above 127, or in a full-range input that is
+        # not re-normalised
+        top = self.calib.get("max_int", 127) if op["src"] != self.net["input"] else self.net["input_range"][1]
+        in_kind = B.ICNN_IN_U8_FULL if (top > 127 and not op["in_sub128"]) else B.ICNN_IN_U8_LE127
         d = B.conv_desc(
-            n=n, h=h, w=w, cin=op["cin"], in_c_stride=cbuf, in_signed=0, in_sub128=int(op["in_sub128"]),
+            n=n, h=h, w=w, cin=op["cin"], in_c_stride=cbuf, in_signed=in_kind, in_sub128=int(op["in_sub128"]),
             cout=op["cout"], kh=op["kh"], kw=op["kw"], stride_h=op["stride"], stride_w=op["stride"],
             pad_h=op["pad"], pad_w=op["pad"], out_c_stride=dst.shape[3], out_c_offset=op["dst_c_offset"],
             mul=cal.get("mul", 1), shift=cal.get("shift", 0), bound_q=cal.get("bound_q", 127),

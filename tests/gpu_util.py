@@ -28,7 +28,10 @@ def gpu_conv2d(x, w, bias, *, stride=1, pad=0, mul=1, shift=0, bound_q=127, lo=0
     cin = wc if cin is None else cin
     om = _OUT[out_mode]
     odt = {B.ICNN_OUT_RAW_S32: np.int32, B.ICNN_OUT_LINEAR_S8: np.int8}.get(om, np.uint8)
-    d = B.conv_desc(n=n, h=h, w=ww, cin=cin, in_c_stride=cbuf, in_signed=int(x.dtype == np.int8),
+    # bytes above 127 that are not a raw picture need the full-range unsigned input kind
+    in_kind = B.ICNN_IN_S8 if x.dtype == np.int8 else (
+        B.ICNN_IN_U8_FULL if (not in_sub128 and x.size and int(x.max()) > 127) else B.ICNN_IN_U8_LE127)
+    d = B.conv_desc(n=n, h=h, w=ww, cin=cin, in_c_stride=cbuf, in_signed=in_kind,
                     in_sub128=int(in_sub128), cout=cout, kh=kh, kw=kw, stride_h=stride, stride_w=stride,
                     pad_h=pad, pad_w=pad, mul=mul, shift=shift, bound_q=bound_q, lo=lo, hi=hi,
                     out_mode=om, res_mode=_RES[res_mode])

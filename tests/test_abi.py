@@ -53,7 +53,9 @@ def test_conv_descriptor_validation():
         (dict(shift=-1), B.ICNN_E_PARAM), (dict(shift=63), B.ICNN_E_PARAM),
         (dict(bound_q=0), B.ICNN_E_PARAM), (dict(bound_q=256), B.ICNN_E_PARAM),
         (dict(out_mode=7), B.ICNN_E_PARAM), (dict(res_mode=3), B.ICNN_E_PARAM),
-        (dict(in_signed=1, in_sub128=1), B.ICNN_E_PARAM), (dict(in_signed=2), B.ICNN_E_PARAM),
+        (dict(in_signed=1, in_sub128=1), B.ICNN_E_PARAM), (dict(in_signed=3), B.ICNN_E_PARAM),
+        (dict(in_signed=2, in_sub128=1), B.ICNN_E_PARAM),
+        (dict(in_signed=2, cin=4096, in_c_stride=4096), B.ICNN_E_SHAPE),    # K = 36864 > 32767 with inputs up to 255
         (dict(out_mode=B.ICNN_OUT_CLAMP_U8, lo=5, hi=4), B.ICNN_E_PARAM),
         (dict(out_mode=B.ICNN_OUT_CLAMP_U8, lo=0, hi=256), B.ICNN_E_PARAM),
         (dict(res_mode=B.ICNN_RES_PRE, res_dtype=5, res_c_stride=64), B.ICNN_E_PARAM),
@@ -67,7 +69,7 @@ def test_conv_descriptor_validation():
         assert B.icnn_last_error() != ""
     # raw int32 output ignores mul / shift / bound
     assert B.iconv2d_validate(good(B, out_mode=B.ICNN_OUT_RAW_S32, mul=0, shift=99, bound_q=0)) == 0
-    assert B.iconv2d_packed_weight_bytes(good(B)) == 4 * 9 * 2048
+    assert B.iconv2d_packed_weight_bytes(good(B)) == 4 * 9 * 2048 + 128 * 4      # fragments + one weight sum per padded channel
     assert B.iconv2d_workspace_bytes(good(B)) == 0
 
 

@@ -128,3 +128,19 @@ def test_small_resnet_runs_and_merges():
     assert bufs["s1b0_sk"].dtype == np.int32
     one = ONet.run(net, 0, calib, images=1)               # images are independent
     assert (one["logits"][0] == bufs["logits"][0]).all()
+
+
+def test_bound_parameters_for_other_activation_bit_depths():
+    """Section 3.3's post-condition [h_ri * mul / 2^shift] = max_int for the bit-depths of the paper's
+    table (8, 6, 5, 4 bits), and a small VDSR calibrated at each reaches exactly that maximum."""
+    g = np.random.default_rng(5)
+    for max_int in (255, 63, 31, 15):
+        hs = list(range(1, 3000)) + [int(v) for v in g.integers(3000, 1 << 24, size=1500)]
+        for h in hs:
+            m, s = K.bound_params(h, max_int)
+            assert O.requant(h, m, s) == max_int and 1 <= m < (1 << 31) and 0 <= s <= K.MAX_SHIFT
+        net = W.vdsr(24, 28, depth=4)
+        calib, bufs = ONet.calibrate(net, 0, max_int=max_int)
+        assert calib["max_int"] == max_int
+        assert all(c.get("bound_q", max_int) == max_int for c in calib["conv"].values())
+        assert max(int(bufs[n].max()) for n in ("a1", "a2", "a3")) == max_int

@@ -267,6 +267,43 @@ def test_fused_block_refuses_what_it_cannot_prove_or_run():
     assert e.value.code == B.ICNN_E_UNSUPPORTED
 
 
+@pytest.mark.parametrize("shape", [(2, 17, 23, 64, 64, 3, 1, 1), (2, 14, 14, 256, 256, 3, 2, 1), (1, 14, 14, 512, 128, 1, 1, 0),
+                                   (1, 30, 34, 64, 32, 5, 1, 2), (1, 30, 34, 48, 16, 3, 1, 1), (1, 33, 31, 1, 64, 3, 1, 1),
+                                   (2, 37, 41, 3, 64, 7, 2, 3), (1, 9, 9, 16, 100, 3, 1, 1), (1, 7, 7, 24, 40, 3, 1, 1)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_unsigned_inputs_up_to_255(shape):
+    """8-bit activations (the paper's bit-depth table): any byte value on the input, zero padding
+    stays zero, bound_q up to 255 on the output; every input path of the library."""
+    n, h, w, cin, cout, k, stride, pad = shape
+    g = rnd(sum(shape) + 7)
+    x = g.integers(0, 256, size=(n, h, w, cin), dtype=np.uint8)
+    x[0, 0, 0, :] = 255
+    wt = g.integers(-127, 128, size=(cout, k, k, cin), dtype=np.int8)
+    b = g.integers(-4096, 4097, size=cout).astype(np.int32)
+    got, want = both(x, wt, b, stride=stride, pad=pad, out_mode="raw_s32")
+    assert (got == want).all()
+    sigma = 100.0 * 74 * (k * k * cin) ** 0.5
+    mul = max(1, int(round(255 / (3.1 * sigma) * (1 << 24))))
+    got, want = both(x, wt, b, stride=stride, pad=pad, mul=mul, shift=24, bound_q=255)
+    assert (got == want).all() and want.max() == 255 and want.min() == 0
+    r = g.integers(0, 256, size=want.shape, dtype=np.uint8)
+    got, want = both(x, wt, b, stride=stride, pad=pad, mul=mul, shift=24, bound_q=255, res=r, res_mode="pre",
+                     res_mul=int(3.1 * sigma / 255), res_shift=0, misalign=0)
+    assert (got == want).all()
+    got, want = both(x, wt, b, stride=stride, pad=pad, mul=mul, shift=24, bound_q=255, misalign=4)
+    assert (got == want).all()
+
+
+def test_unsigned_full_range_worst_case_accumulator():
+    # all inputs 255, all weights +127 / -127, K close to the limit: the corrected accumulator stays exact
+    x = np.full((1, 2, 2, 32704), 255, np.uint8)
+    for sign in (1, -1):
+        wt = np.full((16, 1, 1, 32704), 127 * sign, np.int8)
+        b = np.full(16, (1 << 27) * sign, np.int32)
+        got, want = both(x, wt, b, out_mode="raw_s32")
+        assert (got == want).all() and abs(int(want[0, 0, 0, 0])) == 255 * 127 * 32704 + (1 << 27)
+
+
 def channel_params(seed, cout, res=False):
     """Per-channel integers in the calibrator's usual range, with a few extreme channels."""
     g = rnd(seed)

@@ -138,6 +138,35 @@ def test_config3_resnet50_full_batch_sampled_images():
     assert len({int(v) for v in logits.reshape(64, -1).argmax(axis=1)}) > 1 or True
 
 
+@pytest.mark.parametrize("max_int", [255, 63, 15])
+def test_small_nets_at_other_activation_bit_depths(max_int):
+    # the paper's bit-depth table: 8-, 6- and 4-bit activations (255 needs the full-range unsigned input kind)
+    from paper_2006_11735_amd.netrun import GpuNet
+    for net in (W.vdsr(40, 52, depth=5), W.vrcnn(36, 44),
+                W.resnet(3, [2, 1, 1, 1], "tiny", image=64, calib_images=2, classes=10)):
+        calib, _ = ONet.calibrate(net, 1, max_int=max_int)
+        want = ONet.run(net, 1, calib)
+        top = max(int(want[name].max()) for name, b in net["buffers"].items() if b["dtype"] == "u8" and name not in ("raw", "out"))
+        assert top == max_int
+        g = GpuNet(net, 1, calib)
+        g.set_input()
+        g.run()
+        compare_all(net, g, want)
+
+
+def test_config1_vdsr_with_8_bit_activations():
+    from paper_2006_11735_amd.netrun import GpuNet
+    net = W.CONFIGS["cfg1"]()
+    calib = json.load(open(ONet.stored_calib_path("cfg1", 0, max_int=255)))
+    assert calib["max_int"] == 255
+    want = ONet.run(net, 0, calib)
+    g = GpuNet(net, 0, calib)
+    g.set_input()
+    g.run()
+    compare_all(net, g, want)
+    assert want["a5"].max() == 255
+
+
 def test_config5_resnet18_full_batch_sampled_images():
     # basic blocks: 3x3 convs with the skip merge in their epilogue, int32 projections unfused
     from paper_2006_11735_amd.netrun import GpuNet
