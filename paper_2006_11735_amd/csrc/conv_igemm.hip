@@ -609,6 +609,9 @@ hipError_t launch_conv(const ConvArgs &a, bool vec_in, bool direct_ok, hipStream
     // the direct-to-LDS kernel addresses x and the packed weights with 32-bit byte offsets
     const bool direct = direct_ok && a.in_xor == 0 && a.x_bytes < 0x7fffff00u && a.wp_bytes < 0x7fffff00u &&
                         a.KH <= 31 && a.KW <= 31;
+    // one to four output channels: a lane per pixel and dot products beat tiles that are 7/8 padding
+    if (direct_ok && conv_narrow_applies(a) && !getenv("ICNN_NO_NARROW"))
+        return launch_conv_narrow(a, st);
     if (direct) {
         const char *env = getenv("ICNN_TILE");       // tuning aid: force one tile shape
         const int forced = env ? atoi(env) : -1;

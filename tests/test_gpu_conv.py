@@ -304,6 +304,44 @@ def test_unsigned_full_range_worst_case_accumulator():
         assert (got == want).all() and abs(int(want[0, 0, 0, 0])) == 255 * 127 * 32704 + (1 << 27)
 
 
+@pytest.mark.parametrize("cout", [1, 2, 3, 4])
+@pytest.mark.parametrize("geom", [(3, 1, 1, 48), (3, 1, 1, 64), (5, 1, 2, 32), (5, 2, 2, 64), (1, 1, 0, 16), (3, 2, 1, 32)], ids=lambda g: "k%ds%dp%dc%d" % g)
+def test_narrow_output_layers(cout, geom):
+    """One to four output channels (a single one on a large map takes the dot-product kernels, streaming
+    for 3x3 stride 1): every epilogue mode, every input kind."""
+    k, stride, pad, cin = geom
+    h, w = (521, 419) if cout == 1 else (21, 19)
+    x, wt, b = make(40 + cout, 2, h, w, cin, cout, k)
+    ho, wo = (h + 2 * pad - k) // stride + 1, (w + 2 * pad - k) // stride + 1
+    got, want = both(x, wt, b, stride=stride, pad=pad, out_mode="raw_s32")
+    assert (got == want).all()
+    got, want = both(x, wt, b, stride=stride, pad=pad, mul=20050, shift=24, bound_q=127)
+    assert (got == want).all() and want.max() > 0
+    g = rnd(400 + cout)
+    raw = g.integers(0, 256, size=(2, ho, wo, cout), dtype=np.uint8)
+    got, want = both(x, wt, b, stride=stride, pad=pad, mul=20050, shift=22, out_mode="clamp_u8", lo=0, hi=255,
+                     res=raw, res_mode="post", res_mul=1, res_shift=0)
+    assert (got == want).all()
+    r32 = g.integers(-300000, 300000, size=(2, ho, wo, cout)).astype(np.int32)
+    got, want = both(x, wt, b, stride=stride, pad=pad, mul=23187, shift=25, res=r32, res_mode="pre", res_mul=20011, res_shift=15)
+    assert (got == want).all()
+    # int8 input, raw picture input (zero padding after the "- 128"), full-range unsigned input
+    xs = g.integers(-128, 128, size=x.shape, dtype=np.int8)
+    got, want = both(xs, wt, b, stride=stride, pad=pad, out_mode="linear_s8", mul=20050, shift=24)
+    assert (got == want).all()
+    xr = g.integers(0, 256, size=x.shape, dtype=np.uint8)
+    got, want = both(xr, wt, b, stride=stride, pad=pad, in_sub128=True, out_mode="raw_s32")
+    assert (got == want).all()
+    got, want = both(xr, wt, b, stride=stride, pad=pad, out_mode="raw_s32")
+    assert (got == want).all()
+    # channel slice of a wider output buffer; unaligned input falls back to the tile kernels with the same result
+    out = np.full((2, ho, wo, 7), 99, np.uint8)
+    got, want = both(x, wt, b, stride=stride, pad=pad, mul=20050, shift=24, out=out, out_c_offset=2)
+    assert (got == want).all() and (got[..., :2] == 99).all() and (got[..., 2 + cout:] == 99).all()
+    got, want = both(x, wt, b, stride=stride, pad=pad, mul=20050, shift=24, misalign=4)
+    assert (got == want).all()
+
+
 def channel_params(seed, cout, res=False):
     """Per-channel integers in the calibrator's usual range, with a few extreme channels."""
     g = rnd(seed)
