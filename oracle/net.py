@@ -42,16 +42,17 @@ def _conv(op, bufs, w, bias, cal, out, out_mode=None, use_res=True):
     return O.conv2d(bufs[op["src"]], w, bias, out=out, out_c_offset=op["dst_c_offset"], **kw)
 
 
-def run(net, seed, calib, images=None, x_raw=None):
-    """Evaluate `net` with stored calibration integers; returns {buffer: array}."""
+def run(net, seed, calib, images=None, x_raw=None, weights=None):
+    """Evaluate `net` with stored calibration integers; returns {buffer: array}.
+    weights: optional {layer: (int8 weights, int32 bias)} replacing the seeded synthetic ones."""
     n_img = net["buffers"]["raw"]["shape"][0] if images is None else images
     bufs = {"raw": W.input_tensor(net, seed, n_img) if x_raw is None else x_raw}
     for op in net["ops"]:
         if op["dst"] not in bufs:
             bufs[op["dst"]] = _alloc(net, op["dst"], n_img)
         if op["op"] == "conv":
-            _conv(op, bufs, W.weight_tensor(op, seed), W.bias_tensor(op, seed),
-                  calib["conv"][op["name"]], bufs[op["dst"]])
+            w, b = weights[op["name"]] if weights is not None else (W.weight_tensor(op, seed), W.bias_tensor(op, seed))
+            _conv(op, bufs, w, b, calib["conv"][op["name"]], bufs[op["dst"]])
         elif op["op"] == "maxpool":
             bufs[op["dst"]] = O.maxpool2d(bufs[op["src"]], op["k"], op["stride"], op["pad"])
         elif op["op"] == "avgpool":

@@ -16,10 +16,12 @@ _DT = {"u8": B.ICNN_U8, "s8": B.ICNN_S8, "s32": B.ICNN_S32}
 
 
 class GpuNet:
-    def __init__(self, net, seed, calib, images=None, device="cuda:0", fuse=True):
+    def __init__(self, net, seed, calib, images=None, device="cuda:0", fuse=True, weights=None):
         """fuse: run a projection conv and the block's last conv that consumes it as one
         iconv2d_dual_brelu launch where the library accepts that (the int32 skip buffer then
-        stays untouched)."""
+        stays untouched).  weights: optional {layer: (int8 [cout,kh,kw,cin], int32 [cout])}, e.g.
+        from paper_2006_11735_amd.convert, instead of the seeded synthetic tensors."""
+        self.weights = weights
         if not torch.cuda.is_available():
             raise RuntimeError("GpuNet needs a GPU: there is no CPU fallback")
         self.net, self.seed, self.calib = net, seed, calib
@@ -86,11 +88,12 @@ class GpuNet:
             d.res_dtype = _DT[op["res_dtype"]]
             d.res_c_stride = res.shape[3]
             d.res_mul, d.res_shift = cal.get("res_mul", 1), cal.get("res_shift", 0)
-        w_np = W.weight_tensor(op, self.seed)
-        w_dev = torch.from_numpy(w_np).to(self.device)
+        w_np = self.weights[op["name"]][0] if self.weights is not None else W.weight_tensor(op, self.seed)
+        w_dev = torch.from_numpy(np.ascontiguousarray(w_np, dtype=np.int8)).to(self.device)
         wp = torch.empty(B.iconv2d_packed_weight_bytes(d), dtype=torch.uint8, device=self.device)
         B.iconv2d_prepack_weights(d, w_dev, wp)
-        bias = torch.from_numpy(W.bias_tensor(op, self.seed)).to(self.device)
+        b_np = self.weights[op["name"]][1] if self.weights is not None else W.bias_tensor(op, self.seed)
+        bias = torch.from_numpy(np.ascontiguousarray(b_np, dtype=np.int32)).to(self.device)
         ws_bytes = B.iconv2d_workspace_bytes(d)
         ws = torch.empty(ws_bytes, dtype=torch.uint8, device=self.device) if ws_bytes else None
         torch.cuda.synchronize(self.device)       # w_dev may be released after the prepack ran

@@ -167,6 +167,30 @@ def test_config1_vdsr_with_8_bit_activations():
     assert want["a5"].max() == 255
 
 
+@pytest.mark.parametrize("per_channel", [False, True])
+def test_converted_float_networks(per_channel):
+    """Networks produced by the offline float -> integer conversion (real weight distributions, folded
+    batch norms, synchronised ratios): the library's result equals the oracle's bit for bit, and both
+    track the float network."""
+    from paper_2006_11735_amd import convert as C
+    from paper_2006_11735_amd.netrun import GpuNet
+    from test_convert import float_params
+    for net, bn in ((W.vdsr(40, 52, depth=5), False), (W.vrcnn(36, 44), False),
+                    (W.resnet(4, [2, 1, 1, 1], "tiny", image=64, calib_images=4, classes=10), True),
+                    (W.resnet_basic(2, [1, 1, 1, 1], "tiny18", image=64, calib_images=2, classes=10), True)):
+        raw = W.input_tensor(net, 3)
+        calib, weights, info = C.convert(net, float_params(net, 5, bn), raw, per_channel=per_channel)
+        want = ONet.run(net, 0, calib, x_raw=raw, weights=weights)
+        g = GpuNet(net, 0, calib, weights=weights)
+        g.set_input(raw)
+        g.run()
+        compare_all(net, g, want)
+        out = net["outputs"][0]
+        r = info["ratio"][out]
+        err = np.abs(g.result(out).astype(np.float64) / r - info["float"][out])
+        assert err.mean() < 0.02 * np.abs(info["float"][out]).max()
+
+
 def test_config5_resnet18_full_batch_sampled_images():
     # basic blocks: 3x3 convs with the skip merge in their epilogue, int32 projections unfused
     from paper_2006_11735_amd.netrun import GpuNet
