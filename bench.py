@@ -72,10 +72,26 @@ def cpu_baseline(net, calib, seed, budget_s=20.0):
     t1 = (time.time() - t0) / 2
     k = int(max(1, min(n_all, budget_s // max(t1, 1e-3))))
     t0 = time.time()
-    ONet.run(net, seed, calib, images=k, x_raw=x[:k])
+    passes = 0
+    while passes == 0 or (time.time() - t0 < 10.0 and passes < 100):      # at least about ten seconds of work
+        ONet.run(net, seed, calib, images=k, x_raw=x[:k])
+        passes += 1
     dt = time.time() - t0
-    return {"value": k / dt, "unit": "images/s", "cores": O.num_threads(), "kind": "oracle",
-            "sample": "%d of the %d images of the same batch, every layer of the network, %.1f s" % (k, n_all, dt)}
+    return {"value": passes * k / dt, "unit": "images/s", "cores": O.num_threads(), "kind": "oracle",
+            "sample": "%d of the %d images of the same batch, every layer of the network, %d pass%s, %.1f s" % (
+                k, n_all, passes, "" if passes == 1 else "es", dt)}
+
+
+def _time_us(torch, fn, reps=20):
+    for _ in range(3):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps * 1e3
 
 
 def add_bandwidth(torch):
@@ -90,19 +106,43 @@ def add_bandwidth(torch):
         d = B.add_desc(count_pixels=px, c=c, a_c_stride=c, b_c_stride=c, out_c_stride=c, a_dtype=a_dt,
                        b_dtype=B.ICNN_U8, b_mul=18415, b_shift=5, mul=23187, shift=24 if a_dt == B.ICNN_S32 else 9,
                        lo=0, hi=127)
-        for _ in range(3):
-            B.iadd_rescale(d, a, b, o)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(20):
-            B.iadd_rescale(d, a, b, o)
-        e1.record()
-        torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) / 20 * 1e3
+        us = _time_us(torch, lambda: B.iadd_rescale(d, a, b, o))
         gbs = px * c * bytes_per / us / 1e3
         out[name] = {"elements": px * c, "us": us, "achieved_gbs": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
         log("iadd_rescale %-11s %d elements: %.1f us, %.0f GB/s (%.0f%% of %d GB/s)" % (
             name, px * c, us, gbs, 100 * gbs / HBM_PEAK_GBS, HBM_PEAK_GBS))
+    return out
+
+
+def other_bandwidth(torch):
+    """Achieved HBM bandwidth (algorithmic bytes / time) of the remaining memory-bound kernels, at the
+    sizes they have in the workloads."""
+    from paper_2006_11735_amd import binding as B
+    out = {}
+
+    def report(name, byts, us):
+        gbs = byts / us / 1e3
+        out[name] = {"algorithmic_bytes": byts, "us": us, "achieved_gbs": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+        log("%-38s %6.1f MB: %6.1f us, %5.0f GB/s (%.0f%% of %d GB/s)" % (name, byts / 1e6, us, gbs, 100 * gbs / HBM_PEAK_GBS,
+                                                                          HBM_PEAK_GBS))
+    x = torch.randint(0, 128, (64, 112, 112, 64), device="cuda").to(torch.uint8)
+    o = torch.empty((64, 56, 56, 64), dtype=torch.uint8, device="cuda")
+    report("imaxpool2d_u8 64x112x112x64 3x3/2", x.numel() + o.numel(),
+           _time_us(torch, lambda: B.imaxpool2d_u8(64, 112, 112, 64, 3, 2, 1, x, o)))
+    x = torch.randint(0, 128, (64, 7, 7, 2048), device="cuda").to(torch.uint8)
+    o = torch.empty((64, 1, 1, 2048), dtype=torch.uint8, device="cuda")
+    report("iavgpool_global_u8 64x7x7x2048", x.numel() + o.numel(),
+           _time_us(torch, lambda: B.iavgpool_global_u8(64, 7, 7, 2048, 21400, 20, 127, x, o)))
+    px = 720 * 1280
+    a = torch.randint(0, 128, (px, 32), device="cuda").to(torch.uint8)
+    b = torch.randint(0, 128, (px, 16), device="cuda").to(torch.uint8)
+    o = torch.empty((px, 48), dtype=torch.uint8, device="cuda")
+    report("iconcat 720x1280 32+16 channels", 2 * px * 48,
+           _time_us(torch, lambda: B.iconcat([a, b], [32, 16], [32, 16], [20000, 23000], [15, 15], 127, px, o, 48)))
+    n = 64 * 224 * 224 * 3
+    x = torch.randint(0, 256, (n,), device="cuda").to(torch.uint8)
+    o = torch.empty_like(x)
+    report("irenormalize_u8 64x224x224x3", 2 * n, _time_us(torch, lambda: B.irenormalize_u8(n, x, o)))
     return out
 
 
@@ -255,6 +295,7 @@ def main():
         log("per-channel variant: %.3f ms per step (%d launches)" % (ms_pc, len(g_pc.steps)))
         del g_pc
     result["iadd_rescale"] = add_bandwidth(torch)
+    result["bandwidth_kernels"] = other_bandwidth(torch)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(net, calib, seed)
     out_dir = os.path.join(ROOT, "gpurun_out")

@@ -598,7 +598,10 @@ static double tile_cost(const TileCfg &c, const ConvArgs &a)
     const double rounds = (double)(long long)((tiles + slots - 1) / slots);
     const double resident = tiles < slots ? (tiles / 256.0 > 1 ? tiles / 256.0 : 1) : c.per_cu;   // per CU
     const double mfma = (c.bm / 32) * (c.bp / 32) * 2 * 32.0 / 4;          // cycles per step if alone on the CU
-    const double l2 = 64.0 * (c.bm + c.bp) / 24.0;                         // at ~24 B/clk/CU from L2
+    // at ~24 B/clk/CU from L2; gathered activation pieces (taps, padding) cost a little more than the
+    // straight weight copies, which decides between transposed shapes (measured on 3x3 layers)
+    const bool pointwise = a.KH == 1 && a.KW == 1 && a.sh == 1 && a.sw == 1;
+    const double l2 = 64.0 * (c.bm + (pointwise ? 1.0 : 1.1) * c.bp) / 24.0;
     const double step = resident * (mfma > l2 ? mfma : l2) + 150;
     const double fixed = 2500 + 1.5 * c.bm * c.bp / 256 * 6;               // prologue + epilogue
     return rounds * (a.ksteps * step + fixed);
