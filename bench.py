@@ -156,6 +156,8 @@ def main():
     ap.add_argument("--layer-reps", type=int, default=20)
     ap.add_argument("--per-channel", action="store_true",
                     help="time the variant with one (mul, shift) per output channel instead of the per-layer workload")
+    ap.add_argument("--main-only", action="store_true",
+                    help="skip the per-channel variant and the stand-alone bandwidth kernels (clean kernel traces)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 256 MiB device copies (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -277,7 +279,7 @@ def main():
     }
     if args.per_channel:
         result["config"]["workload"] += "; per-output-channel requantisation (iconv2d_brelu_pc, iconv2d_dual_brelu_pc)"
-    elif os.path.exists(pc_path) and args.config == "cfg3":
+    elif os.path.exists(pc_path) and args.config == "cfg3" and not args.main_only:
         # the same network with one (mul, shift) and skip rescale per output channel
         g_pc = GpuNet(net, seed, json.load(open(pc_path)))
         g_pc.set_input()
@@ -294,8 +296,9 @@ def main():
                                          "note": "iconv2d_brelu_pc on every BReLU layer, iconv2d_dual_brelu_pc on the four projection blocks"}
         log("per-channel variant: %.3f ms per step (%d launches)" % (ms_pc, len(g_pc.steps)))
         del g_pc
-    result["iadd_rescale"] = add_bandwidth(torch)
-    result["bandwidth_kernels"] = other_bandwidth(torch)
+    if not args.main_only:
+        result["iadd_rescale"] = add_bandwidth(torch)
+        result["bandwidth_kernels"] = other_bandwidth(torch)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(net, calib, seed)
     out_dir = os.path.join(ROOT, "gpurun_out")

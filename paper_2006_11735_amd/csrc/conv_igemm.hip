@@ -667,21 +667,23 @@ __global__ void prepack_kernel(const int8_t *__restrict__ w, uint8_t *__restrict
     *(v4i *)(wp + e * 16) = v4i{(int)wd[0], (int)wd[1], (int)wd[2], (int)wd[3]};
 }
 
-// wsum[co] = sum of output channel co's weights (k_true = kh*kw*cin of them), 0 for the padding channels
-__global__ __launch_bounds__(256) void wsum_kernel(const int8_t *__restrict__ w, int32_t *__restrict__ wsum, int Cout,
-                                                   int cout_padded, int k_true)
+// wsum[co] = sum of output channel co's weights (k_true = kh*kw*cin of them), 0 for the padding channels.
+// One wave per channel.
+__global__ __launch_bounds__(64) void wsum_kernel(const int8_t *__restrict__ w, int32_t *__restrict__ wsum, int Cout,
+                                                  int k_true)
 {
-    const int co = blockIdx.x * 256 + threadIdx.x;
-    if (co >= cout_padded) return;
+    const int co = blockIdx.x, lane = threadIdx.x;
     int s = 0;
     if (co < Cout)
-        for (int k = 0; k < k_true; ++k) s += w[(size_t)co * k_true + k];
-    wsum[co] = s;
+        for (int k = lane; k < k_true; k += 64) s += w[(size_t)co * k_true + k];
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
+    if (lane == 0) wsum[co] = s;
 }
 
 hipError_t launch_wsum(const int8_t *w, int32_t *wsum, int Cout, int cout_padded, int k_true, hipStream_t st)
 {
-    hipLaunchKernelGGL(wsum_kernel, dim3((cout_padded + 255) / 256), dim3(256), 0, st, w, wsum, Cout, cout_padded, k_true);
+    hipLaunchKernelGGL(wsum_kernel, dim3(cout_padded), dim3(64), 0, st, w, wsum, Cout, k_true);
     return hipGetLastError();
 }
 
