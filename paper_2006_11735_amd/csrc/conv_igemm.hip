@@ -778,9 +778,79 @@ __global__ __launch_bounds__(256) void pad_small_cin_kernel(const uint8_t *__res
     out[e] = v;
 }
 
+// Same copy with the row and the image in the grid's y and z (no per-thread divisions) and four
+// pixels per thread (all their byte loads in flight together; the kernel is latency-bound otherwise)
+__global__ __launch_bounds__(256) void pad_small_cin_rows_kernel(const uint8_t *__restrict__ x, uint32_t *__restrict__ out,
+                                                                 int H, int W, int Cin, int in_cs, int ph, int pw, int Hp,
+                                                                 int Wp, uint32_t in_xor)
+{
+    const int xp0 = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (xp0 >= Wp) return;
+    const int yp = blockIdx.y, n = blockIdx.z;
+    const int hi = yp - ph;
+    const bool rowok = (unsigned)hi < (unsigned)H;
+    const uint8_t *row = x + ((size_t)n * H + (rowok ? hi : 0)) * W * in_cs;
+    const uint32_t m = in_xor & 0xffu;
+    uint32_t b[4][4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int wi = xp0 + u - pw;
+        const bool ok = rowok && (unsigned)wi < (unsigned)W;
+        const uint8_t *p = row + (size_t)(ok ? wi : 0) * in_cs;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) b[u][c] = (ok && c < Cin) ? ((uint32_t)p[c < Cin ? c : 0] ^ m) : 0u;
+    }
+    uint32_t *o = out + ((size_t)n * Hp + yp) * Wp + xp0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+        if (xp0 + u < Wp) o[u] = b[u][0] | (b[u][1] << 8) | (b[u][2] << 16) | (b[u][3] << 24);
+}
+
+// Dense three-channel pictures (cin = pitch = 3, W % 4 == 0, 4-byte aligned): a thread turns 12 input
+// bytes (three aligned dwords, coalesced across the wave) into four output pixels; byte loads cost
+// one address per lane and made the generic kernel address-bound.  Thread W/4 of a row writes the
+// left and right border, rows outside the image are all zero.
+__global__ __launch_bounds__(256) void pad_rgb_rows_kernel(const uint32_t *__restrict__ x, uint32_t *__restrict__ out, int H,
+                                                           int W, int ph, int pw, int Hp, int Wp, uint32_t in_xor)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    const int quads = W >> 2;
+    if (t > quads) return;
+    const int yp = blockIdx.y, n = blockIdx.z;
+    const int hi = yp - ph;
+    const bool rowok = (unsigned)hi < (unsigned)H;
+    uint32_t *o = out + ((size_t)n * Hp + yp) * Wp;
+    if (t == quads) {                               // borders
+        for (int c = 0; c < pw; ++c) o[c] = 0;
+        for (int c = pw + W; c < Wp; ++c) o[c] = 0;
+        return;
+    }
+    uint32_t d0 = 0, d1 = 0, d2 = 0;
+    if (rowok) {
+        const uint32_t *p = x + (((size_t)n * H + hi) * W * 3 >> 2) + 3 * t;
+        d0 = p[0] ^ in_xor; d1 = p[1] ^ in_xor; d2 = p[2] ^ in_xor;
+    }
+    // bytes r0 g0 b0 r1 | g1 b1 r2 g2 | b2 r3 g3 b3  ->  one dword per pixel, top byte zero
+    const uint32_t m = rowok ? 0x00ffffffu : 0u;
+    o[pw + 4 * t + 0] = d0 & m;
+    o[pw + 4 * t + 1] = ((d0 >> 24) | (d1 << 8)) & m;
+    o[pw + 4 * t + 2] = ((d1 >> 16) | (d2 << 16)) & m;
+    o[pw + 4 * t + 3] = (d2 >> 8) & m;
+}
+
 hipError_t launch_pad_small_cin(const uint8_t *x, void *out, int N, int H, int W, int Cin, int in_cs, int ph, int pw,
                                 int Hp, int Wp, uint32_t in_xor, hipStream_t st)
 {
+    if (Cin == 3 && in_cs == 3 && W % 4 == 0 && !((uintptr_t)x & 3) && Wp >= pw + W && N <= 65535 && Hp <= 65535) {
+        hipLaunchKernelGGL(pad_rgb_rows_kernel, dim3((unsigned)((W / 4 + 1 + 255) / 256), (unsigned)Hp, (unsigned)N), dim3(256), 0,
+                           st, (const uint32_t *)x, (uint32_t *)out, H, W, ph, pw, Hp, Wp, in_xor);
+        return hipGetLastError();
+    }
+    if (N <= 65535 && Hp <= 65535) {
+        hipLaunchKernelGGL(pad_small_cin_rows_kernel, dim3((unsigned)((Wp + 1023) / 1024), (unsigned)Hp, (unsigned)N), dim3(256),
+                           0, st, x, (uint32_t *)out, H, W, Cin, in_cs, ph, pw, Hp, Wp, in_xor);
+        return hipGetLastError();
+    }
     const long long total = (long long)N * Hp * Wp;
     hipLaunchKernelGGL(pad_small_cin_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, x, (uint32_t *)out,
                        total, H, W, Cin, in_cs, ph, pw, Hp, Wp, in_xor);
