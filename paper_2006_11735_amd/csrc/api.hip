@@ -235,15 +235,27 @@ static int fill_conv_args(const icnn_conv_desc *d, const ConvGeom &g, const void
         a.rq_fast = 1;
         a.mul_hi = (int)((long long)a.mul << (32 - a.shift));
     }
+    a.rq24 = a.t_hi = a.rnd = 0;
+    if (d->out_mode != ICNN_OUT_RAW_S32 && a.lo == 0 && a.hi >= 0 && a.shift >= 1 && a.shift <= 31 && a.mul >= 1 &&
+        a.mul < (1 << 24)) {
+        const long long half = 1LL << (a.shift - 1);
+        const long long num = ((long long)a.hi << a.shift) - half;
+        const long long t_hi = num <= 0 ? 0 : (num + a.mul - 1) / a.mul;
+        if (t_hi < (1 << 24) && t_hi * a.mul + half <= 0xffffffffLL && ((t_hi * a.mul + half) >> a.shift) == a.hi) {
+            a.rq24 = 1;
+            a.t_hi = (int)t_hi;
+            a.rnd = (int)half;
+        }
+    }
     a.res_fast = 0;
-    if (d->res_mode != ICNN_RES_NONE && d->res_dtype != ICNN_S32 && a.res_shift <= 30 &&
+    if (d->res_mode != ICNN_RES_NONE && d->res_dtype == ICNN_U8 && a.res_shift <= 30 &&
         255LL * a.res_mul + (1LL << a.res_shift) / 2 <= 0x7fffffffLL)
         a.res_fast = 1;
     a.epi_vec = a.vec_out && (d->res_mode == ICNN_RES_NONE || a.vec_res);
     {
         const int res_kind = d->res_mode == ICNN_RES_NONE ? 0 : (d->res_mode == ICNN_RES_PRE && a.res_fast ? 1 : 2);
-        const int rq_kind = d->out_mode == ICNN_OUT_RAW_S32 ? 0 : (a.rq_fast ? 1 : 2);
-        a.epi_mode = 3 * res_kind + rq_kind;
+        const int rq_kind = d->out_mode == ICNN_OUT_RAW_S32 ? 0 : (a.rq24 && res_kind != 2 ? 3 : (a.rq_fast ? 1 : 2));
+        a.epi_mode = 4 * res_kind + rq_kind;
     }
     return ICNN_OK;
 }

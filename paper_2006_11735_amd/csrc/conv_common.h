@@ -49,11 +49,48 @@ __device__ __forceinline__ void epilogue_slow(const ConvArgs &a, const v16i &acc
     }
 }
 
+// min(max(x, lo), hi) as one instruction (the compiler only fuses the pair when it can prove lo <= hi);
+// at most one of the three operands may live in a scalar register
+__device__ __forceinline__ int med3_v0s(int x, int hi_s)
+{
+    int r;
+    asm("v_med3_i32 %0, %1, 0, %2" : "=v"(r) : "v"(x), "s"(hi_s));
+    return r;
+}
+__device__ __forceinline__ int med3_vvs(int x, int lo_v, int hi_s)
+{
+    int r;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(lo_v), "s"(hi_s));
+    return r;
+}
+// the low bytes of four values as one word (three byte-permutes)
+__device__ __forceinline__ int pack_low_bytes(int v0, int v1, int v2, int v3)
+{
+    const uint32_t lo = __builtin_amdgcn_perm((uint32_t)v1, (uint32_t)v0, 0x0c0c0400u);
+    const uint32_t hi = __builtin_amdgcn_perm((uint32_t)v3, (uint32_t)v2, 0x0c0c0400u);
+    return (int)__builtin_amdgcn_perm(hi, lo, 0x05040100u);
+}
+
+// byte `pos` (1..3) of w = low byte of x >> sh; the other bytes of w are kept
+__device__ __forceinline__ void shift_into_byte(int &w, uint32_t x, int sh_v, int pos)
+{
+    if (pos == 1)
+        asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+            : "+v"(w) : "v"(sh_v), "v"(x));
+    else if (pos == 2)
+        asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+            : "+v"(w) : "v"(sh_v), "v"(x));
+    else
+        asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+            : "+v"(w) : "v"(sh_v), "v"(x));
+}
+
 // vector path: all 16 channels valid, 16-byte aligned skip operand and output.
-// RES: 0 no skip operand; 1 8-bit operand joined before requantisation with a rescale
-//      that fits 32 bits; 2 anything else (int32 operand, wide multiplier, join after).
+// RES: 0 no skip operand; 1 unsigned 8-bit operand joined before requantisation with a rescale
+//      that fits 32 bits; 2 anything else (signed or int32 operand, wide multiplier, join after).
 // RQ:  0 raw int32 output; 1 requantisation as one 32x32->64 multiply-add whose high
-//      word is the result; 2 general 64-bit multiply, add, shift.
+//      word is the result; 2 general 64-bit multiply, add, shift; 3 in 32 bits after clamping
+//      t to [0, t_hi] (see ConvArgs::rq24; never with RES 2).
 template <int RES, int RQ>
 __device__ __forceinline__ void epilogue_vec(const ConvArgs &a, const v16i &acc, int p, int co0, const v4i &res8)
 {
@@ -73,8 +110,8 @@ __device__ __forceinline__ void epilogue_vec(const ConvArgs &a, const v16i &acc,
             const int wd[4] = {res8.x, res8.y, res8.z, res8.w};
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int b8 = (wd[r >> 2] >> ((r & 3) * 8)) & 0xff;
-                rv[r] = a.res_dtype == 1 ? (int)(int8_t)b8 : b8;
+                const int b8 = (int)(((uint32_t)wd[r >> 2] >> ((r & 3) * 8)) & 0xffu);
+                rv[r] = RES == 2 && a.res_dtype == 1 ? (int)(int8_t)b8 : b8;
             }
         }
     }
@@ -95,23 +132,37 @@ __device__ __forceinline__ void epilogue_vec(const ConvArgs &a, const v16i &acc,
         for (int q = 0; q < 4; ++q) op[q] = v4i{t[4 * q], t[4 * q + 1], t[4 * q + 2], t[4 * q + 3]};
         return;
     }
-    uint32_t wd[4] = {0, 0, 0, 0};
+    if (RQ == 3) {
+        // clamp, multiply-add, then the shift writes its byte of the output word: three instructions per value
+        int w[4];
+        const int sh_v = a.shift;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const uint32_t tc = (uint32_t)med3_v0s(t[r], a.t_hi);
+            const uint32_t x = __umul24(tc, (uint32_t)a.mul) + (uint32_t)a.rnd;
+            if ((r & 3) == 0) w[r >> 2] = (int)(x >> a.shift);
+            else shift_into_byte(w[r >> 2], x, sh_v, r & 3);
+        }
+        *(v4i *)((uint8_t *)a.out + oo) = v4i{w[0], w[1], w[2], w[3]};
+        return;
+    }
+    int v[16];
+    const int lo_v = a.lo;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-        int v;
         if (RQ == 1 && !(RES == 2)) {
             // [t * mul / 2^shift] = high word of t * (mul << (32 - shift)) + 2^31   (1 <= shift <= 32)
             const int q = (int)(((int64_t)t[r] * a.mul_hi + 0x80000000LL) >> 32);
-            v = min(max(q, a.lo), a.hi);
+            v[r] = med3_vvs(q, lo_v, a.hi);
         } else {
             int64_t q = RQ == 1 ? (((int64_t)t[r] * a.mul_hi + 0x80000000LL) >> 32)
                                 : rsr64((int64_t)t[r] * a.mul, a.shift);
             if (RES == 2 && a.res_mode == 2) q += rsr64((int64_t)rv[r] * a.res_mul, a.res_shift);
-            v = clampi64(q, a.lo, a.hi);
+            v[r] = clampi64(q, a.lo, a.hi);
         }
-        wd[r >> 2] |= (uint32_t)(v & 0xff) << ((r & 3) * 8);
     }
-    *(v4i *)((uint8_t *)a.out + oo) = v4i{(int)wd[0], (int)wd[1], (int)wd[2], (int)wd[3]};
+    *(v4i *)((uint8_t *)a.out + oo) = v4i{pack_low_bytes(v[0], v[1], v[2], v[3]), pack_low_bytes(v[4], v[5], v[6], v[7]),
+                                          pack_low_bytes(v[8], v[9], v[10], v[11]), pack_low_bytes(v[12], v[13], v[14], v[15])};
 }
 
 // True when the call's skip operand is 8-bit and the vector epilogue handles it: then the operands of
@@ -333,13 +384,13 @@ __device__ __forceinline__ void epilogue_tiles(const ConvArgs &a, const v16i (&a
     }
     switch (a.epi_mode) {
 #define ICNN_EPI_CASE(RES, RQ)                                                                      \
-    case RES * 3 + RQ:                                                                              \
+    case RES * 4 + RQ:                                                                              \
         for_tiles([&](const v16i &c, int p, int co0, int i, int j) {                                \
             epilogue_vec<RES, RQ>(a, c, p, co0, res8[i][j]);                                        \
         });                                                                                         \
         break;
-        ICNN_EPI_CASE(0, 0) ICNN_EPI_CASE(0, 1) ICNN_EPI_CASE(0, 2)
-        ICNN_EPI_CASE(1, 0) ICNN_EPI_CASE(1, 1) ICNN_EPI_CASE(1, 2)
+        ICNN_EPI_CASE(0, 0) ICNN_EPI_CASE(0, 1) ICNN_EPI_CASE(0, 2) ICNN_EPI_CASE(0, 3)
+        ICNN_EPI_CASE(1, 0) ICNN_EPI_CASE(1, 1) ICNN_EPI_CASE(1, 2) ICNN_EPI_CASE(1, 3)
         ICNN_EPI_CASE(2, 0) ICNN_EPI_CASE(2, 1) ICNN_EPI_CASE(2, 2)
 #undef ICNN_EPI_CASE
     default: break;

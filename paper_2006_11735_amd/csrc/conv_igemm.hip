@@ -34,6 +34,9 @@ namespace icnn {
 // MODE 1: cin % 64 == 0 and kh*kw <= 32: a K step lies inside one tap, so the tap
 //         position is wave-uniform (scalar registers, one bit test per copy);
 // MODE 2: any cin % 16 == 0: every lane tracks the tap of its own 16-byte slot.
+// MODE 3: kernel kh x 1 without padding, cin % 16 == 0 (the padded small-cin layout, where "cin" is
+//         a kernel row of the picture): every piece lies inside the buffer, so a lane only adds its
+//         slot's offset for the K step to the pixel's; nothing to mask but pixels beyond the last.
 // PC: requantisation and skip rescale per output channel (epilogue_pc_tiles)
 // U8: unsigned inputs up to 255: activation fragments are XORed with 0x80 bytes (x - 128) on their way
 //     from LDS to the matrix cores (the bias rows carry the matching correction, see load_bias_rows)
@@ -106,6 +109,16 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
     int skh = 0, skw = 0, sc0 = 0;
     int kh = 0, kw = 0, ci = 0;
     int kh_init = 0, kw_init = 0, ci_init = ls * 16;
+    // MODE 3: u = index of the lane's 16-byte piece on the K axis, koff = its byte offset from the pixel's
+    // first byte: row u / rp16 of the kernel (rp16 = pieces per kernel row), piece u % rp16 of that row
+    const int rp16 = a.Cin >> 4;
+    const unsigned rp16_inv = MODE == 3 ? 65535u / (unsigned)rp16 + 1 : 0;   // u / rp16 = u * inv >> 16 for u < 2^16 / rp16
+    const unsigned row_bytes = (unsigned)(a.W * a.in_cs);
+    auto koff_of = [&](unsigned u) {
+        const unsigned row = (u * rp16_inv) >> 16;
+        return row * row_bytes + (u - row * (unsigned)rp16) * 16u;
+    };
+    unsigned ku = 0, koff = 0;
     if (MODE == 2) {
         const int tap = ci_init / a.Cin;
         ci_init -= tap * a.Cin;
@@ -136,6 +149,13 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
             tapmask[j] = rowmask[j] = colmask[j] = 0;
             if (MODE == 0) {
                 b_off[j] = pv ? (unsigned)p * (unsigned)a.in_cs + ls * 16 : OOB;
+            } else if (MODE == 3) {
+                const int n = fast_div(p, a.div_howo);
+                const int r = p - n * a.Ho * a.Wo;
+                const int ho = fast_div(r, a.div_wo);
+                const int wo = r - ho * a.Wo;
+                // OOB plus any K offset (< 2^31) stays beyond the buffer
+                b_off[j] = pv ? (unsigned)(((n * a.H + ho * a.sh) * a.W + wo * a.sw) * a.in_cs) : OOB;
             } else {
                 const int pc = pv ? p : 0;
                 const int n = fast_div(pc, a.div_howo);
@@ -161,6 +181,7 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
         }
         skh = skw = sc0 = 0;
         kh = kh_init; kw = kw_init; ci = ci_init;
+        if (MODE == 3) { ku = (unsigned)ls; koff = koff_of(ku); }
     };
 
     // One stage = LPS wave-wide copies.  issue_copy(c, ...) issues copy c (A copies first, then B),
@@ -184,6 +205,9 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
             const unsigned soff = (unsigned)((skh * a.W + skw) * a.in_cs + sc0);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (__attribute__((address_space(3))) void *)dst, 16,
                                                      (tapmask[j] & bit) ? b_off[j] + soff : OOB, 0, 0, 0);
+        } else if (MODE == 3) {
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (__attribute__((address_space(3))) void *)dst, 16,
+                                                     b_off[j] + koff, 0, 0, 0);
         } else {
             const unsigned tapoff = (unsigned)((kh * a.W + kw) * a.in_cs + ci);
             const bool ok = ((rowmask[j] >> kh) & (colmask[j] >> kw) & 1u) != 0;
@@ -198,6 +222,9 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
                 sc0 = 0;
                 if (++skw == a.KW) { skw = 0; ++skh; }
             }
+        } else if (MODE == 3) {
+            ku += 4;
+            koff = koff_of(ku);
         } else if (MODE == 2) {
             ci += kStepK;
             while (ci >= a.Cin) {
@@ -524,7 +551,10 @@ static hipError_t launch_dlds(const ConvArgs &a0, int max_stages, int per_cu, hi
     // per-channel kernels keep two copies of the tile's packed parameters behind the ring
     const size_t lds_bytes = (size_t)a.nstages * (BM + BP) * kStepK + (a.pc ? 2 * (((BM / 16) * kPcGroupInts * 4 + 1023) & ~1023) : 0);
     const bool pw = a.KH == 1 && a.KW == 1 && a.sh == 1 && a.sw == 1 && a.ph == 0 && a.pw == 0;
-    const int mode = pw ? 0 : (a.Cin % 64 == 0 && a.KH * a.KW <= 32 ? 1 : 2);
+    // kh x 1 kernels whose taps all lie inside the image: no masks (the padded small-cin layout)
+    const bool dense = a.KW == 1 && a.ph == 0 && a.pw == 0 && (a.Ho - 1) * a.sh + a.KH <= a.H && (a.Wo - 1) * a.sw + 1 <= a.W &&
+                       (long long)(a.K / 16 + 8) * (a.Cin / 16) < 65536;   // the kernel's u / rp16 by multiplication
+    const int mode = pw ? 0 : (a.Cin % 64 == 0 && a.KH * a.KW <= 32 ? 1 : (dense ? 3 : 2));
     // persistent workgroups: as many as fit on the chip at once (a multiple of 8, one share per XCD)
     a.n_vtiles = 8 * a.per_xcd;
     const int slots = 256 * per_cu;
@@ -548,6 +578,7 @@ static hipError_t launch_dlds(const ConvArgs &a0, int max_stages, int per_cu, hi
         constexpr bool U8 = decltype(u8_tag)::value;
         if (mode == 0) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 0, PC, U8>);
         if (mode == 1) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 1, PC, U8>);
+        if (mode == 3) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 3, PC, U8>);
         return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 2, PC, U8>);
     };
     if (a.pc) return a.frag_xor ? pick(std::true_type{}, std::true_type{}) : pick(std::true_type{}, std::false_type{});

@@ -58,9 +58,13 @@ struct ConvArgs {
     int vec_bias; // bias is 16-byte aligned and cout % 16 == 0
     int rq_fast;  // requantisation as one 32x32->64 multiply-add (mul_hi = mul << (32 - shift))
     int mul_hi;
-    int res_fast; // 8-bit skip operand whose rescale fits 32 bits
+    // requantisation in 32 bits: with lo = 0, clamping t to [0, t_hi] first (t_hi: the smallest t whose result is
+    // hi) leaves the result unchanged, and then t * mul + 2^(shift-1) fits 32 bits unsigned with both factors
+    // below 2^24, so one full-rate multiply-add and a shift finish it and no clamp of the result is needed
+    int rq24, t_hi, rnd;
+    int res_fast; // unsigned 8-bit skip operand whose rescale fits 32 bits
     int epi_vec;  // output (and skip operand) allow 16-byte accesses
-    int epi_mode; // 3 * RES + RQ of the vector epilogue
+    int epi_mode; // 4 * RES + RQ of the vector epilogue
     // per-output-channel requantisation: packed parameters (kPcGroupInts int32 per 16 channels, see
     // pc_prepack_kernel), null for the per-layer form.  pc_fast_ok: shape, alignment and skip operand
     // allow the fast epilogue form where a group's parameters do.
