@@ -278,7 +278,7 @@ static int conv_layer(const icnn_conv_desc *d, const void *x, const void *w_pack
             return fail(ICNN_E_PARAM, "a raw int32 output without a skip operand has no per-channel parameter");
         a.pc = (const int32_t *)pc;
         a.pc_fast_ok = d->out_mode != ICNN_OUT_RAW_S32 && a.epi_vec &&
-                       (d->res_mode == ICNN_RES_NONE || (d->res_mode == ICNN_RES_PRE && d->res_dtype != ICNN_S32));
+                       (d->res_mode == ICNN_RES_NONE || (d->res_mode == ICNN_RES_PRE && d->res_dtype == ICNN_U8));
     }
     if (g.rp) {
         // small cin: pad and re-normalise x into the workspace, then run the layer as a kh x 1

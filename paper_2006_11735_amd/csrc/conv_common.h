@@ -247,6 +247,7 @@ __device__ __forceinline__ void epilogue_pc_row(const ConvArgs &a, const v16i (&
                                                 const int32_t *g, const v4i (&rw)[TP], bool skip, bool plain)
 {
     uint32_t wd[TP][4];
+    const int lo_v = a.lo;
 #pragma unroll
     for (int q4 = 0; q4 < 4; ++q4) {
         const v4i A = *(const v4i *)(g + kPcA + 4 * q4);
@@ -262,14 +263,13 @@ __device__ __forceinline__ void epilogue_pc_row(const ConvArgs &a, const v16i (&
             constexpr bool PLAIN = decltype(plain_tag)::value;
 #pragma unroll
             for (int j = 0; j < TP; ++j) {
-                const int w4 = rw[j][q4];
-                uint32_t o = 0;
+                const uint32_t w4 = (uint32_t)rw[j][q4];
+                int v[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     int t = acc[j][4 * q4 + e];
                     if (RES) {
-                        const int b8 = (w4 >> (8 * e)) & 0xff;
-                        const int rv = a.res_dtype == 1 ? (int)(int8_t)b8 : b8;
+                        const int rv = (int)((w4 >> (8 * e)) & 0xffu);      // unsigned operands only (a.pc_fast_ok)
                         t = __builtin_elementwise_add_sat(t, (__mul24(rv, rmu[e]) + ((1 << rsf[e]) >> 1)) >> rsf[e]);
                     }
                     int q;
@@ -279,9 +279,9 @@ __device__ __forceinline__ void epilogue_pc_row(const ConvArgs &a, const v16i (&
                         const int tc = min(max(t, ~T[e]), T[e]) << L[e];
                         q = (int)(((int64_t)tc * A[e] + ((int64_t)1 << (31 + C[e]))) >> 32) >> C[e];
                     }
-                    o |= (uint32_t)(min(max(q, a.lo), a.hi) & 0xff) << (8 * e);
+                    v[e] = med3_vvs(q, lo_v, a.hi);
                 }
-                wd[j][q4] = o;
+                wd[j][q4] = (uint32_t)pack_low_bytes(v[0], v[1], v[2], v[3]);
             }
         };
         if (skip) {

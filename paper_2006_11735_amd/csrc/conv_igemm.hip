@@ -20,7 +20,9 @@
 #include "conv_common.h"
 
 #include <cstdlib>
+#include <mutex>
 #include <type_traits>
+#include <vector>
 
 namespace icnn {
 
@@ -538,6 +540,19 @@ __global__ __launch_bounds__(256) void conv_greg_kernel(const ConvArgs a)
 }
 
 // ------------------------------------------------------------------ dispatch
+// More than 64 KiB of dynamic LDS has to be allowed once per kernel function.
+hipError_t allow_large_lds(const void *kernel)
+{
+    static std::mutex lock;
+    static std::vector<const void *> done;
+    std::lock_guard<std::mutex> g(lock);
+    for (const void *k : done)
+        if (k == kernel) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e == hipSuccess) done.push_back(kernel);
+    return e;
+}
+
 template <int BM, int BP, int WAVES_M, int WAVES_P>
 static hipError_t launch_dlds(const ConvArgs &a0, int max_stages, int per_cu, hipStream_t st)
 {
@@ -561,14 +576,8 @@ static hipError_t launch_dlds(const ConvArgs &a0, int max_stages, int per_cu, hi
     const dim3 grid((unsigned)(a.n_vtiles < slots ? a.n_vtiles : slots)), block(256);
     auto go = [&](auto kernel) -> hipError_t {
         if (lds_bytes > 64 * 1024) {
-            // more than 64 KiB of dynamic LDS has to be allowed once per kernel
-            static bool raised = false;
-            if (!raised) {
-                const hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                         160 * 1024);
-                if (e != hipSuccess) return e;
-                raised = true;
-            }
+            const hipError_t e = allow_large_lds((const void *)kernel);
+            if (e != hipSuccess) return e;
         }
         hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, a);
         return hipGetLastError();
