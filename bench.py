@@ -270,7 +270,7 @@ def main():
         "conv_tops": conv_tops,
         "pct_int8_mfma_peak": 100 * conv_tops / INT8_MFMA_PEAK_TOPS,
         "whole_step_tops": conv_ops / (ms_per_step * 1e-3) / 1e12,
-        "roofline": {"kernel": "conv kernels (all %d conv launches of a step: conv_dlds / conv_dual / conv_greg, every tile shape)" % n_conv,
+        "roofline": {"kernel": "conv kernels (all %d conv launches of a step: conv_dlds / conv_halo / conv_dual / conv_greg, every tile shape)" % n_conv,
                      "bound": "mfma", "achieved": conv_tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": conv_tops / INT8_MFMA_PEAK_TOPS, "traffic": traffic,
                      "launches_per_step": n_conv, "avg_launch_us": conv_ms * 1e3 / n_conv,

@@ -203,6 +203,9 @@ static int fill_conv_args(const icnn_conv_desc *d, const ConvGeom &g, const void
     default: a.lo = -128; a.hi = 127; break;
     }
     if (d->out_mode == ICNN_OUT_RAW_S32) { a.mul = 1; a.shift = 0; }
+    // [t * 2m / 2^s] = [t * m / 2^(s-1)] for every t (numerator and denominator halve exactly): the smaller pair
+    // lets more layers requantise in 32 bits
+    while (a.shift >= 2 && a.mul != 0 && (a.mul & 1) == 0) { a.mul /= 2; --a.shift; }
     a.res_mode = d->res_mode; a.res_dtype = d->res_dtype; a.res_cs = d->res_c_stride;
     a.res_mul = d->res_mode ? d->res_mul : 1; a.res_shift = d->res_mode ? d->res_shift : 0;
     a.in_xor = d->in_sub128 ? 0x80808080u : 0u;
