@@ -476,10 +476,11 @@ static int halo_choice(const ConvArgs &a, int *rows)
     if (choice != 1 && choice != 2) return 0;
     const int bp = choice == 1 ? 128 : 256, bm = choice == 1 ? 128 : 64;
     *rows = halo_max_rows(a, bp);
-    const int pq = ((*rows + 63) / 64 + kHaloInst - 1) / kHaloInst;
+    int pq = ((*rows + 63) / 64 + kHaloInst - 1) / kHaloInst;
+    if (choice == 2 && pq < 2) pq = 2;    // the instantiations that exist (launch_conv_halo)
     const int npq = pq * kHaloInst;       // patch buffers are whole instalments
     const size_t lds = (size_t)kHaloStages * bm * kStepK + 2 * (size_t)npq * 4096 + (a.pc ? 2 * 5120 : 0);
-    if (pq > kHaloMaxPq || lds > 160 * 1024) return 0;
+    if (pq > (choice == 1 ? 2 : kHaloMaxPq) || lds > 160 * 1024) return 0;
     // One workgroup per compute unit: its epilogue is not hidden behind another workgroup's K loop, so layers with
     // several tiles per unit stay with the tap-by-tap kernel, which runs two workgroups per unit.
     const long long tiles = (long long)((a.Cout + bm - 1) / bm) * ((a.M + bp - 1) / bp);
@@ -499,15 +500,15 @@ hipError_t launch_conv_halo(const ConvArgs &a, hipStream_t st)
     int rows = 0;
     const int choice = halo_choice(a, &rows);
     const int pq = ((rows + 63) / 64 + kHaloInst - 1) / kHaloInst;
+    // (128 x 128 tiles with three copies per instalment would need more than 160 KiB of LDS; 256-pixel tiles
+    // never get by with one)
     if (choice == 1) {
         if (pq == 1) return launch_halo<128, 128, 2, 2, 1>(a, rows, st);
         if (pq == 2) return launch_halo<128, 128, 2, 2, 2>(a, rows, st);
-        return launch_halo<128, 128, 2, 2, 3>(a, rows, st);
     }
     if (choice == 2) {
-        if (pq == 1) return launch_halo<64, 256, 1, 4, 1>(a, rows, st);
-        if (pq == 2) return launch_halo<64, 256, 1, 4, 2>(a, rows, st);
-        return launch_halo<64, 256, 1, 4, 3>(a, rows, st);
+        if (pq <= 2) return launch_halo<64, 256, 1, 4, 2>(a, rows, st);
+        if (pq == 3) return launch_halo<64, 256, 1, 4, 3>(a, rows, st);
     }
     return hipErrorInvalidValue;
 }

@@ -471,3 +471,54 @@ def test_per_channel_argument_checks():
     with pytest.raises(B.IcnnError) as e:
         B.iconv2d_brelu_pc(d, t, t, i32, t, None, t)
     assert e.value.code == B.ICNN_E_PARAM
+
+
+# ---- 3x3 / stride 1 / padding 1 layers with cin >= 128 and at most 256 tiles take the kernel that keeps the
+# input patch in LDS (copy waves + multiply waves).  Shapes: several images per tile (7x7), rows and images
+# crossed inside a tile, an odd number of 64-channel slices (192), a ragged last tile, cout tails.
+PATCH_SHAPES = [(3, 14, 14, 128, 128, 3, 1, 1), (5, 7, 7, 192, 256, 3, 1, 1), (2, 14, 14, 256, 136, 3, 1, 1),
+                (1, 28, 28, 128, 80, 3, 1, 1), (2, 9, 13, 320, 128, 3, 1, 1), (1, 56, 56, 128, 128, 3, 1, 1),
+                (2, 20, 20, 128, 64, 3, 1, 1), (1, 33, 17, 192, 40, 3, 1, 1),
+                (1, 10, 100, 128, 128, 3, 1, 1), (1, 6, 256, 128, 144, 3, 1, 1), (1, 5, 250, 128, 48, 3, 1, 1)]   # wide rows: larger patches
+
+
+@pytest.mark.parametrize("shape", PATCH_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_patch_resident_3x3_kernel(shape):
+    n, h, w, cin, cout, k, stride, pad = shape
+    x, wt, b = make(31, n, h, w, cin, cout, k)
+    got, want = both(x, wt, b, stride=stride, pad=pad, out_mode="raw_s32")
+    assert (got == want).all()
+    sigma = 37.0 * 74 * (k * k * cin) ** 0.5
+    mul = max(1, int(round(127 / (3.0 * sigma) * (1 << 25))))
+    got, want = both(x, wt, b, stride=stride, pad=pad, mul=mul, shift=25)
+    assert (got == want).all() and want.max() == 127 and want.min() == 0
+    r = rnd(5).integers(0, 128, size=want.shape, dtype=np.uint8)
+    got, want = both(x, wt, b, stride=stride, pad=pad, mul=mul, shift=25, res=r, res_mode="pre",
+                     res_mul=int(3.0 * sigma / 127), res_shift=0)
+    assert (got == want).all()
+    # per-channel parameters, and a wider input buffer (channel slice)
+    got, want = both(x, wt, b, stride=stride, pad=pad, bound_q=127, **channel_params(77, cout))
+    assert (got == want).all()
+    xw = rnd(6).integers(0, 128, size=(n, h, w, cin + 64), dtype=np.uint8)
+    got, want = both(xw, wt, b, stride=stride, pad=pad, mul=mul, shift=25, cin=cin)
+    assert (got == want).all()
+    # 8-bit activations
+    x8 = rnd(8).integers(0, 256, size=(n, h, w, cin), dtype=np.uint8)
+    got, want = both(x8, wt, b, stride=stride, pad=pad, out_mode="raw_s32")
+    assert (got == want).all()
+    got, want = both(x8, wt, b, stride=stride, pad=pad, bound_q=255, **channel_params(78, cout))
+    assert (got == want).all()
+
+
+@pytest.mark.parametrize("shape", [(9, 28, 28, 128, 128, 3, 1, 1), (20, 14, 14, 192, 200, 3, 1, 1), (40, 7, 7, 128, 1024, 3, 1, 1)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_patch_resident_kernel_with_several_tiles_per_workgroup(shape, monkeypatch):
+    """More than 256 tiles: the library would pick the tap-by-tap kernel; the tuning switch forces the
+    patch-resident one, whose workgroups then walk several tiles (patch and fragment prefetch across tiles)."""
+    monkeypatch.setenv("ICNN_HALO_ALWAYS", "1")
+    n, h, w, cin, cout, k, stride, pad = shape
+    x, wt, b = make(32, n, h, w, cin, cout, k)
+    got, want = both(x, wt, b, stride=stride, pad=pad, out_mode="raw_s32")
+    assert (got == want).all()
+    got, want = both(x, wt, b, stride=stride, pad=pad, bound_q=127, **channel_params(79, cout))
+    assert (got == want).all()
