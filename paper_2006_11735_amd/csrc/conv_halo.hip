@@ -70,7 +70,7 @@ constexpr int halo_younger(int t, bool pnext, int NA, int PQ)
     return n;
 }
 
-template <int BM, int BP, int WAVES_M, int WAVES_P, int PQ, bool PC, bool U8>
+template <int BM, int BP, int WAVES_M, int WAVES_P, int PQ, bool U8>
 __global__ __launch_bounds__(512, 1) void conv_halo_kernel(const ConvArgs a, const HaloArgs h)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the buffer-resource type exists in the device pass only
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(512, 1) void conv_halo_kernel(const ConvArgs a, con
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     const int patch_bytes = h.npq * 4096;
-    uint8_t *const patch0 = lds + nstA * A_BYTES;    // two patch buffers, then the per-channel parameter slots
+    uint8_t *const patch0 = lds + nstA * A_BYTES;    // two patch buffers
 
     auto tile_of = [&](int v, int &ct, int &pt) {
         const int logical = (v & 7) * a.per_xcd + (v >> 3);
@@ -234,13 +234,6 @@ __global__ __launch_bounds__(512, 1) void conv_halo_kernel(const ConvArgs a, con
     const int wave = wave8;
     const int wm = wave % WAVES_M;
     const int wp = wave / WAVES_M;
-    const __amdgpu_buffer_rsrc_t rs_pc =
-        __builtin_amdgcn_make_buffer_rsrc((void *)a.pc, 0, PC ? ((a.Cout + 15) >> 4) * kPcGroupInts * 4 : 0, 0x00020000);
-    constexpr int PC_BYTES = (BM / 16) * kPcGroupInts * 4;
-    constexpr int PC_SLOT = (PC_BYTES + 1023) & ~1023;
-    uint8_t *const pc_lds = patch0 + 2 * patch_bytes;
-    int pc_slot = 0;
-
     const int a_rd = wm * TM * 2048 + lane * 16;
     // patch row of this lane's pixel j (centre tap) in tile pt_
     auto rel_of = [&](int pt_, int j) { return pi_of(pt_ * BP + wp * TP * 32 + j * 32 + (lane & 31)) - pi_base_of(pt_); };
@@ -303,18 +296,6 @@ __global__ __launch_bounds__(512, 1) void conv_halo_kernel(const ConvArgs a, con
         const int pix_wave = pt * BP + wp * TP * 32;
         v4i res8[TM][TP];
         prefetch_res8<TM, TP>(a, co_wave, pix_wave, lane, res8);
-        if constexpr (PC) {
-            // two alternating slots: no multiply wave gets two tiles ahead of another (barriers in between)
-            pc_slot ^= 1;
-#pragma unroll
-            for (int c = 0; c * 4096 < PC_SLOT; ++c) {
-                const int o = c * 4096 + wave * 1024;
-                if (o < PC_SLOT)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                        rs_pc, (__attribute__((address_space(3))) void *)(pc_lds + pc_slot * PC_SLOT + o), 16,
-                        o + lane * 16 < PC_BYTES ? (unsigned)(ct * PC_BYTES + o + lane * 16) : OOB, 0, 0, 0);
-            }
-        }
         int nct = 0, npt = 0;
         const bool more = v + (int)gridDim.x < a.n_vtiles && tile_of(v + (int)gridDim.x, nct, npt);
         int rel_next[TP];     // this lane's patch rows in the next tile
@@ -328,9 +309,6 @@ __global__ __launch_bounds__(512, 1) void conv_halo_kernel(const ConvArgs a, con
             constexpr int t2 = t == 8 ? 0 : t + 1;                     // tap of the next step
             const bool last_chunk = c + 1 == nchunks;
             asm volatile("" ::: "memory");
-            // the per-channel parameters are copied to LDS by all four multiply waves: each proves its part
-            // landed before the tile's last barrier, after which the epilogue may read all of it
-            if (PC && t == 8 && last_chunk) ICNN_WAIT_VMCNT(0);
             __builtin_amdgcn_s_barrier();      // the next step's stage (and patch) complete, see above
             asm volatile("" ::: "memory");
             const int toff2 = (t2 / 3 - 1) * h.wp2 + (t2 % 3 - 1);
@@ -392,15 +370,12 @@ __global__ __launch_bounds__(512, 1) void conv_halo_kernel(const ConvArgs a, con
                 for (int j = 0; j < TP; ++j) bf[0][kq][j] = bf[1][kq][j];
             }
         }
-        // skip operands and per-channel parameters (this wave's only loads) have landed
+        // the skip operands (this wave's only loads) have landed
         ICNN_WAIT_VMCNT(0);
 
         v += gridDim.x;
         if (more) load_bias_rows<TM>(a, nct * BM + wm * TM * 32, lane >> 5, bias_next);
-        if constexpr (PC)
-            epilogue_pc_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane, res8,
-                                      (const int32_t *)(pc_lds + pc_slot * PC_SLOT), co_wave - wm * TM * 32);
-        else epilogue_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane, res8);
+        epilogue_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane, res8);
         if (!more) break;
         ct = nct;
         pt = npt;
@@ -448,8 +423,7 @@ static hipError_t launch_halo(const ConvArgs &a0, int rows, hipStream_t st)
     a.nstages = kHaloStages;
     a.div_howo = make_fast_div((unsigned)(a.Ho * a.Wo));
     a.div_wo = make_fast_div((unsigned)a.Wo);
-    const size_t lds_bytes = (size_t)kHaloStages * BM * kStepK + 2 * (size_t)h.npq * 4096 +
-                             (a.pc ? 2 * (((BM / 16) * kPcGroupInts * 4 + 1023) & ~1023) : 0);
+    const size_t lds_bytes = (size_t)kHaloStages * BM * kStepK + 2 * (size_t)h.npq * 4096;
     if (h.npq > kHaloMaxNpq || lds_bytes > 160 * 1024) return hipErrorInvalidValue;
     a.n_vtiles = 8 * a.per_xcd;
     const dim3 grid((unsigned)(a.n_vtiles < 256 ? a.n_vtiles : 256)), block(512);
@@ -461,16 +435,17 @@ static hipError_t launch_halo(const ConvArgs &a0, int rows, hipStream_t st)
         hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, a, h);
         return hipGetLastError();
     };
-    if (a.pc) return a.frag_xor ? go(conv_halo_kernel<BM, BP, WAVES_M, WAVES_P, PQ, true, true>)
-                                : go(conv_halo_kernel<BM, BP, WAVES_M, WAVES_P, PQ, true, false>);
-    return a.frag_xor ? go(conv_halo_kernel<BM, BP, WAVES_M, WAVES_P, PQ, false, true>)
-                      : go(conv_halo_kernel<BM, BP, WAVES_M, WAVES_P, PQ, false, false>);
+    if (a.pc) return hipErrorInvalidValue;          // see halo_choice
+    return a.frag_xor ? go(conv_halo_kernel<BM, BP, WAVES_M, WAVES_P, PQ, true>)
+                      : go(conv_halo_kernel<BM, BP, WAVES_M, WAVES_P, PQ, false>);
 }
 
 // tile shape for a layer: 0 none (not applicable), 1: 128 x 128, 2: 64 x 256
 static int halo_choice(const ConvArgs &a, int *rows)
 {
-    if (!halo_shape_ok(a)) return 0;
+    // (per-channel parameters: the epilogue's registers do not fit beside two fragment sets; those layers keep
+    // the tap-by-tap kernel)
+    if (!halo_shape_ok(a) || a.pc) return 0;
     int choice = a.Cout > 64 ? 1 : 2;
     if (const char *e = getenv("ICNN_HALO_TILE")) choice = atoi(e);   // tuning aid
     if (choice != 1 && choice != 2) return 0;
@@ -479,13 +454,16 @@ static int halo_choice(const ConvArgs &a, int *rows)
     int pq = ((*rows + 63) / 64 + kHaloInst - 1) / kHaloInst;
     if (choice == 2 && pq < 2) pq = 2;    // the instantiations that exist (launch_conv_halo)
     const int npq = pq * kHaloInst;       // patch buffers are whole instalments
-    const size_t lds = (size_t)kHaloStages * bm * kStepK + 2 * (size_t)npq * 4096 + (a.pc ? 2 * 5120 : 0);
+    const size_t lds = (size_t)kHaloStages * bm * kStepK + 2 * (size_t)npq * 4096;
     if (pq > (choice == 1 ? 2 : kHaloMaxPq) || lds > 160 * 1024) return 0;
-    // One workgroup per compute unit: its epilogue is not hidden behind another workgroup's K loop, so layers with
-    // several tiles per unit stay with the tap-by-tap kernel, which runs two workgroups per unit.
-    const long long tiles = (long long)((a.Cout + bm - 1) / bm) * ((a.M + bp - 1) / bp);
-    // ... and a tile's K loop has to be long enough to pay for the patch set-up (measured: 9-step tiles lose)
-    if ((tiles > 256 || a.ksteps < 18) && !getenv("ICNN_HALO_ALWAYS")) return 0;
+    // One workgroup per compute unit: a tile's epilogue is not hidden behind another workgroup's K loop, so the
+    // K loop has to be long enough to pay for it and for the patch set-up (measured: 9-step tiles lose to the
+    // tap-by-tap kernel, 18 steps and more win, also with several tiles per workgroup)
+    if (a.ksteps < 18 && !getenv("ICNN_HALO_ALWAYS")) return 0;
+    if (const char *e = getenv("ICNN_HALO_MAX_TILES")) {           // tuning aid
+        const long long tiles = (long long)((a.Cout + bm - 1) / bm) * ((a.M + bp - 1) / bp);
+        if (tiles > atoi(e)) return 0;
+    }
     return choice;
 }
 
