@@ -456,14 +456,12 @@ static int halo_choice(const ConvArgs &a, int *rows)
     const int npq = pq * kHaloInst;       // patch buffers are whole instalments
     const size_t lds = (size_t)kHaloStages * bm * kStepK + 2 * (size_t)npq * 4096;
     if (pq > (choice == 1 ? 2 : kHaloMaxPq) || lds > 160 * 1024) return 0;
-    // One workgroup per compute unit: a tile's epilogue is not hidden behind another workgroup's K loop, so the
-    // K loop has to be long enough to pay for it and for the patch set-up (measured: 9-step tiles lose to the
-    // tap-by-tap kernel, 18 steps and more win, also with several tiles per workgroup)
-    if (a.ksteps < 18 && !getenv("ICNN_HALO_ALWAYS")) return 0;
-    if (const char *e = getenv("ICNN_HALO_MAX_TILES")) {           // tuning aid
-        const long long tiles = (long long)((a.Cout + bm - 1) / bm) * ((a.M + bp - 1) / bp);
-        if (tiles > atoi(e)) return 0;
-    }
+    // One workgroup per compute unit: a tile's epilogue is not hidden behind another workgroup's K loop.  Measured
+    // inside whole networks: the kernel wins where a workgroup has one tile and the K loop has 18 steps or more;
+    // with several tiles per workgroup it only ties with the tap-by-tap kernel (two workgroups per unit), and
+    // 9-step tiles lose.  ICNN_HALO_ALWAYS lifts both limits (tuning, tests of the multi-tile path).
+    const long long tiles = (long long)((a.Cout + bm - 1) / bm) * ((a.M + bp - 1) / bp);
+    if ((tiles > 256 || a.ksteps < 18) && !getenv("ICNN_HALO_ALWAYS")) return 0;
     return choice;
 }
 

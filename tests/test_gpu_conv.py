@@ -512,8 +512,10 @@ def test_patch_resident_3x3_kernel(shape):
 
 @pytest.mark.parametrize("shape", [(9, 28, 28, 128, 128, 3, 1, 1), (20, 14, 14, 192, 200, 3, 1, 1), (40, 7, 7, 128, 1024, 3, 1, 1)],
                          ids=lambda s: "x".join(map(str, s)))
-def test_patch_resident_kernel_with_several_tiles_per_workgroup(shape):
-    """More than 256 tiles: workgroups walk several tiles (patch and fragment prefetch across tiles)."""
+def test_patch_resident_kernel_with_several_tiles_per_workgroup(shape, monkeypatch):
+    """More than 256 tiles: the library would pick the tap-by-tap kernel; the tuning switch forces the
+    patch-resident one, whose workgroups then walk several tiles (patch and fragment prefetch across tiles)."""
+    monkeypatch.setenv("ICNN_HALO_ALWAYS", "1")
     n, h, w, cin, cout, k, stride, pad = shape
     x, wt, b = make(32, n, h, w, cin, cout, k)
     got, want = both(x, wt, b, stride=stride, pad=pad, out_mode="raw_s32")
