@@ -375,25 +375,29 @@ __device__ __forceinline__ void epilogue_tiles(const ConvArgs &a, const v16i (&a
             }
         }
     };
-    // channel tails and unaligned tensors take the element-wise path for the whole call
-    if (!a.epi_vec || (a.Cout & 15)) {
-        for_tiles([&](const v16i &c, int p, int co0, int, int) {
-            epilogue_slow(a, c, p, co0, min(16, a.Cout - co0));
-        });
-        return;
-    }
-    switch (a.epi_mode) {
+    // Unaligned tensors take the element-wise path for the whole call, and so do channel tails (cout % 16 != 0)
+    // together with a skip operand (prefetch_res8 does not serve them); otherwise only the last, partial group
+    // of 16 channels does.
+    const bool all_slow = !a.epi_vec || ((a.Cout & 15) && a.res_mode != 0);
+    if (!all_slow) {
+        switch (a.epi_mode) {
 #define ICNN_EPI_CASE(RES, RQ)                                                                      \
     case RES * 4 + RQ:                                                                              \
         for_tiles([&](const v16i &c, int p, int co0, int i, int j) {                                \
-            epilogue_vec<RES, RQ>(a, c, p, co0, res8[i][j]);                                        \
+            if (co0 + 16 <= a.Cout) epilogue_vec<RES, RQ>(a, c, p, co0, res8[i][j]);                \
         });                                                                                         \
         break;
-        ICNN_EPI_CASE(0, 0) ICNN_EPI_CASE(0, 1) ICNN_EPI_CASE(0, 2) ICNN_EPI_CASE(0, 3)
-        ICNN_EPI_CASE(1, 0) ICNN_EPI_CASE(1, 1) ICNN_EPI_CASE(1, 2) ICNN_EPI_CASE(1, 3)
-        ICNN_EPI_CASE(2, 0) ICNN_EPI_CASE(2, 1) ICNN_EPI_CASE(2, 2)
+            ICNN_EPI_CASE(0, 0) ICNN_EPI_CASE(0, 1) ICNN_EPI_CASE(0, 2) ICNN_EPI_CASE(0, 3)
+            ICNN_EPI_CASE(1, 0) ICNN_EPI_CASE(1, 1) ICNN_EPI_CASE(1, 2) ICNN_EPI_CASE(1, 3)
+            ICNN_EPI_CASE(2, 0) ICNN_EPI_CASE(2, 1) ICNN_EPI_CASE(2, 2)
 #undef ICNN_EPI_CASE
-    default: break;
+        default: break;
+        }
+    }
+    if (all_slow || (a.Cout & 15)) {
+        for_tiles([&](const v16i &c, int p, int co0, int, int) {
+            if (all_slow || co0 + 16 > a.Cout) epilogue_slow(a, c, p, co0, min(16, a.Cout - co0));
+        });
     }
 }
 // for callers without a K loop to hide the fetch behind: fetch, then finish

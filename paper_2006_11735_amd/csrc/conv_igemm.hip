@@ -655,6 +655,8 @@ hipError_t launch_conv(const ConvArgs &a, bool vec_in, bool direct_ok, hipStream
     // one to four output channels: a lane per pixel and dot products beat tiles that are 7/8 padding
     if (direct_ok && conv_narrow_applies(a) && !getenv("ICNN_NO_NARROW"))
         return launch_conv_narrow(a, st);
+    // the classifier: a few pixels, long K
+    if (direct_ok && conv_fc_applies(a) && !getenv("ICNN_NO_FC")) return launch_conv_fc(a, st);
     // 3x3 / stride 1 / padding 1 with cin % 64 == 0: the nine taps read one LDS copy of the input
     if (direct && !getenv("ICNN_NO_HALO") && !getenv("ICNN_TILE") && conv_halo_applies(a)) return launch_conv_halo(a, st);
     if (direct) {

@@ -124,6 +124,8 @@ __device__ __forceinline__ int load_elem(const void *p, size_t i, int dtype)
 hipError_t launch_conv(const ConvArgs &a, bool vec_in, bool direct_ok, hipStream_t st);
 hipError_t launch_conv_dual(const ConvArgs &a, const ProjArgs &q, hipStream_t st);
 hipError_t allow_large_lds(const void *kernel);   // > 64 KiB of dynamic LDS, once per kernel function
+bool conv_fc_applies(const ConvArgs &a);
+hipError_t launch_conv_fc(const ConvArgs &a, hipStream_t st);
 bool conv_halo_applies(const ConvArgs &a);
 hipError_t launch_conv_halo(const ConvArgs &a, hipStream_t st);
 bool conv_narrow_applies(const ConvArgs &a);
