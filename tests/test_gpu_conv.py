@@ -522,3 +522,26 @@ def test_patch_resident_kernel_with_several_tiles_per_workgroup(shape, monkeypat
     assert (got == want).all()
     got, want = both(x, wt, b, stride=stride, pad=pad, bound_q=127, **channel_params(79, cout))
     assert (got == want).all()
+
+
+# ---- pointwise layers on at most 64 pixels take the kernel whose eight waves split the K axis
+@pytest.mark.parametrize("shape", [(1, 1, 1, 512, 32), (33, 1, 1, 1088, 1000), (64, 1, 1, 2048, 1000), (2, 5, 6, 576, 48),
+                                   (7, 3, 3, 4096, 72)], ids=lambda s: "x".join(map(str, s)))
+def test_few_pixel_pointwise_kernel(shape):
+    n, h, w, cin, cout = shape
+    x, wt, b = make(41, n, h, w, cin, cout, 1)
+    got, want = both(x, wt, b, out_mode="raw_s32")
+    assert (got == want).all()
+    sigma = 37.0 * 74 * cin ** 0.5
+    mul = max(1, int(round(127 / (3.0 * sigma) * (1 << 25))))
+    got, want = both(x, wt, b, mul=mul, shift=25)
+    assert (got == want).all() and want.max() == 127
+    r = rnd(9).integers(-2**20, 2**20, size=want.shape).astype(np.int32)
+    got, want = both(x, wt, b, mul=mul, shift=25, res=r, res_mode="pre", res_mul=3, res_shift=1)
+    assert (got == want).all()
+    x8 = rnd(10).integers(0, 256, size=(n, h, w, cin), dtype=np.uint8)
+    got, want = both(x8, wt, b, out_mode="raw_s32")
+    assert (got == want).all()
+    xw = rnd(11).integers(0, 128, size=(n, h, w, cin + 16), dtype=np.uint8)      # channel slice of a wider buffer
+    got, want = both(xw, wt, b, out_mode="raw_s32", cin=cin)
+    assert (got == want).all()
