@@ -32,6 +32,9 @@ __global__ __launch_bounds__(64 * kFcWaves) void conv_fc_kernel(const ConvArgs a
     }
     const uint8_t *wbase = a.wp + (size_t)chunk * a.ksteps * kChunkBytes + lane * 16;
 
+    // the bias travels while the K loop runs (only wave 0 finishes the tile)
+    v16i bias[1];
+    if (wave == 0) load_bias_rows<1>(a, chunk * 32, half, bias);
     v16i acc[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j)
@@ -95,8 +98,6 @@ __global__ __launch_bounds__(64 * kFcWaves) void conv_fc_kernel(const ConvArgs a
     for (int q = 0; q < 4; ++q) part[0][wave * 4 + q][lane] = sum[q];
     __syncthreads();
     if (wave != 0) return;
-    v16i bias[1];
-    load_bias_rows<1>(a, chunk * 32, half, bias);
     v16i tot[1][2];
 #pragma unroll
     for (int j = 0; j < 2; ++j)
