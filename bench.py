@@ -104,8 +104,8 @@ def add_bandwidth(torch):
         b = torch.randint(0, 127, (px, c), device="cuda").to(torch.uint8)
         o = torch.empty((px, c), dtype=torch.uint8, device="cuda")
         d = B.add_desc(count_pixels=px, c=c, a_c_stride=c, b_c_stride=c, out_c_stride=c, a_dtype=a_dt,
-                       b_dtype=B.ICNN_U8, b_mul=18415, b_shift=5, mul=23187, shift=24 if a_dt == B.ICNN_S32 else 9,
-                       lo=0, hi=127)
+                       b_dtype=B.ICNN_U8, b_mul=18415, b_shift=5 if a_dt == B.ICNN_S32 else 14, mul=23187,
+                       shift=24 if a_dt == B.ICNN_S32 else 15, lo=0, hi=127)   # 8-bit maps: ratios near 1; accumulators: << 1
         us = _time_us(torch, lambda: B.iadd_rescale(d, a, b, o))
         gbs = px * c * bytes_per / us / 1e3
         out[name] = {"elements": px * c, "us": us, "achieved_gbs": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}

@@ -448,6 +448,7 @@ int iadd_rescale(const icnn_add_desc *d, const void *a, const void *b, void *out
     k.lo = d->out_mode == ICNN_OUT_LINEAR_S8 ? -128 : d->lo;
     k.hi = d->out_mode == ICNN_OUT_LINEAR_S8 ? 127 : d->hi;
     k.mul_hi = 0;
+    k.q24 = Rq24{0, 0, 0, 0, 0};
     const int ab = dtype_bytes(d->a_dtype), bb = dtype_bytes(d->b_dtype);
     const int ob = d->out_mode == ICNN_OUT_RAW_S32 ? 4 : 1;
     const bool vec = d->c % 16 == 0 && aligned16(a) && aligned16(b) && aligned16(out) &&
@@ -476,6 +477,29 @@ int iconcat(int32_t n_in, const void *const *in, const int32_t *c_in, const int3
     if (!out) return fail(ICNN_E_NULL, "out is NULL");
     for (int i = 0; i < n_in; ++i)
         if (c_in[i] > 0 && !in[i]) return fail(ICNN_E_NULL, "input %d is NULL", i);
+    {
+        // every branch aligned: one launch writes whole output rows (branches without channels are left out)
+        ConcatArgs k;
+        k.n_in = 0;
+        bool all_vec = out_c_stride % 16 == 0 && aligned16(out);
+        int end = 0;
+        for (int i = 0; i < n_in && all_vec; ++i) {
+            if (c_in[i] == 0) continue;
+            all_vec = c_in[i] % 16 == 0 && in_c_stride[i] % 16 == 0 && aligned16(in[i]);
+            const int j = k.n_in++;
+            end += c_in[i];
+            k.in[j] = (const uint8_t *)in[i]; k.c_end[j] = end; k.in_cs[j] = in_c_stride[i];
+            k.mul[j] = mul[i]; k.shift[j] = shift[i]; k.q[j] = make_rq24(mul[i], shift[i], bound_q);
+        }
+        if (all_vec && k.n_in >= 1) {
+            for (int j = k.n_in; j < 16; ++j) {
+                k.in[j] = nullptr; k.c_end[j] = end; k.in_cs[j] = 0; k.mul[j] = 1; k.shift[j] = 0; k.q[j] = Rq24{0, 0, 0, 0, 0};
+            }
+            k.out_cs = out_c_stride; k.bound = bound_q; k.out = (uint8_t *)out;
+            return launched(launch_concat_vec(k, count_pixels, (hipStream_t)stream), "iconcat");
+        }
+        if (all_vec) return ICNN_OK;     // no channels at all
+    }
     int off = 0;
     for (int i = 0; i < n_in; ++i) {
         const bool vec = c_in[i] % 16 == 0 && in_c_stride[i] % 16 == 0 && out_c_stride % 16 == 0 && off % 16 == 0 &&

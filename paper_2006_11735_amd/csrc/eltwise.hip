@@ -87,6 +87,83 @@ __global__ __launch_bounds__(256) void add_rescale_vec_kernel(const AddArgs a, i
     }
 }
 
+// byte `pos` (1..3) of w = low byte of x >> sh; the other bytes of w are kept
+__device__ __forceinline__ void shift_into_byte(int &w, uint32_t x, int sh_v, int pos)
+{
+    if (pos == 1)
+        asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+            : "+v"(w) : "v"(sh_v), "v"(x));
+    else if (pos == 2)
+        asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+            : "+v"(w) : "v"(sh_v), "v"(x));
+    else
+        asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+            : "+v"(w) : "v"(sh_v), "v"(x));
+}
+
+// four bytes of t (each already limited to q.t_hi or not), requantised in 32 bits (see Rq24)
+__device__ __forceinline__ int requant4_u24(const uint32_t (&t)[4], const Rq24 &q)
+{
+    int w = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const uint32_t x = __umul24(min(t[e], (uint32_t)q.t_hi), (uint32_t)q.mul) + (uint32_t)q.rnd;
+        if (e == 0) w = (int)(x >> q.shift);
+        else shift_into_byte(w, x, q.shift, e);
+    }
+    return w;
+}
+
+// Both operands unsigned 8-bit, 8-bit output clamped to [0, hi], multipliers that fit 24 bits (see
+// launch_add): t = a + [b * b_mul / 2^b_shift] is at most 255 + 2^30, never negative and never
+// saturates, and the requantisation runs in 32 bits.  About eight vector instructions per element, so
+// the kernel is bound by HBM and not by its arithmetic.
+constexpr int kGroupsPerLane = 4;   // 16-byte groups a lane handles: fewer, longer waves (the rate at which waves
+                                    // can be launched, not HBM, bounds a kernel whose lanes move 48 bytes each)
+
+__global__ __launch_bounds__(256) void add_u8_kernel(const AddArgs a, int groups_per_px, long long total)
+{
+    const long long g0 = (long long)blockIdx.x * (256 * kGroupsPerLane) + threadIdx.x;
+    v4i wa[kGroupsPerLane], wb[kGroupsPerLane];
+    size_t oo[kGroupsPerLane];
+#pragma unroll
+    for (int u = 0; u < kGroupsPerLane; ++u) {
+        const long long g = g0 + u * 256;
+        if (g >= total) break;
+        size_t ao, bo;
+        if (groups_per_px == 0) {
+            ao = bo = oo[u] = (size_t)g * 16;
+        } else {
+            long long px;
+            if (total < 0x7fffffffLL) px = (unsigned)g / (unsigned)groups_per_px;
+            else px = g / groups_per_px;
+            const int c0 = (int)(g - px * groups_per_px) * 16;
+            ao = (size_t)px * a.a_cs + c0;
+            bo = (size_t)px * a.b_cs + c0;
+            oo[u] = (size_t)px * a.out_cs + a.out_co + c0;
+        }
+        wa[u] = *(const v4i *)((const uint8_t *)a.a + ao);
+        wb[u] = *(const v4i *)((const uint8_t *)a.b + bo);
+    }
+    const uint32_t half = (1u << a.b_shift) >> 1;
+#pragma unroll
+    for (int u = 0; u < kGroupsPerLane; ++u) {
+        if (g0 + u * 256 >= total) break;
+        int w[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            uint32_t t[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t av = ((uint32_t)wa[u][k] >> (8 * e)) & 0xffu, bv = ((uint32_t)wb[u][k] >> (8 * e)) & 0xffu;
+                t[e] = av + ((__umul24(bv, (uint32_t)a.b_mul) + half) >> a.b_shift);
+            }
+            w[k] = requant4_u24(t, a.q24);
+        }
+        *(v4i *)((uint8_t *)a.out + oo[u]) = v4i{w[0], w[1], w[2], w[3]};
+    }
+}
+
 __global__ __launch_bounds__(256) void add_rescale_scalar_kernel(const AddArgs a, long long total)
 {
     const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
@@ -115,7 +192,16 @@ hipError_t launch_add(const AddArgs &a, bool vec, hipStream_t st)
         const bool q_fast = a.out_mode == 3 ||
                             (a.shift >= 1 && a.shift <= 32 && ((long long)a.mul << (32 - a.shift)) <= 0x7fffffffLL);
         const dim3 grid((unsigned)((total + 255) / 256)), block(256);
-        if (b_fast && q_fast) {
+        // both operands unsigned bytes, output clamped to [0, hi]: everything in 32 bits when the skip term stays
+        // below 2^30 and the requantisation pair fits 24 bits
+        const Rq24 q24 = make_rq24(a.mul, a.shift, a.hi);
+        if (a.a_dt == 0 && a.b_dt == 0 && a.out_mode != 3 && a.lo == 0 && b_fast && q24.ok &&
+            ((255LL * a.b_mul + (1LL << a.b_shift) / 2) >> a.b_shift) <= (1LL << 30)) {
+            AddArgs f = a;
+            f.q24 = q24;
+            const long long per_block = 256 * kGroupsPerLane;
+            hipLaunchKernelGGL(add_u8_kernel, dim3((unsigned)((total + per_block - 1) / per_block)), block, 0, st, f, gpp, total);
+        } else if (b_fast && q_fast) {
             AddArgs f = a;
             f.mul_hi = a.out_mode == 3 ? 0 : (int)((long long)a.mul << (32 - a.shift));
             hipLaunchKernelGGL(add_rescale_vec_kernel<true>, grid, block, 0, st, f, gpp, total);
@@ -134,13 +220,25 @@ hipError_t launch_add(const AddArgs &a, bool vec, hipStream_t st)
 __global__ __launch_bounds__(256) void requant_copy_kernel(const uint8_t *__restrict__ in,
                                                            uint8_t *__restrict__ out, long long total,
                                                            int per_px, int in_cs, int out_cs, int out_co,
-                                                           int mul, int shift, int bound, int vec)
+                                                           int mul, int shift, int bound, int vec, const Rq24 q24)
 {
     const long long g = (long long)blockIdx.x * 256 + threadIdx.x;
     if (g >= total) return;
     const long long px = g / per_px;
     const int k = (int)(g - px * per_px);
-    if (vec) {
+    if (vec && q24.ok) {
+        // the multiplier pair fits 24 bits: four instructions per byte
+        const v4i wi = *(const v4i *)(in + (size_t)px * in_cs + k * 16);
+        int w[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            uint32_t t[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) t[e] = ((uint32_t)wi[q] >> (8 * e)) & 0xffu;
+            w[q] = requant4_u24(t, q24);
+        }
+        *(v4i *)(out + (size_t)px * out_cs + out_co + k * 16) = v4i{w[0], w[1], w[2], w[3]};
+    } else if (vec) {
         int v[16];
         unpack16(in, (size_t)px * in_cs + k * 16, 0, v);
 #pragma unroll
@@ -159,7 +257,68 @@ hipError_t launch_requant_copy(const uint8_t *in, uint8_t *out, int64_t px, int 
     const int per_px = vec ? c / 16 : c;
     const long long total = (long long)px * per_px;
     hipLaunchKernelGGL(requant_copy_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, in, out,
-                       total, per_px, in_cs, out_cs, out_co, mul, shift, bound, vec ? 1 : 0);
+                       total, per_px, in_cs, out_cs, out_co, mul, shift, bound, vec ? 1 : 0, make_rq24(mul, shift, bound));
+    return hipGetLastError();
+}
+
+// Explicit concatenation, all branches in one launch: each output row is written once, whole.  The
+// branch of a lane's group is found by a scan over the (wave-uniform) branch table; its fields are picked
+// with selects, so the table stays in scalar registers.
+__global__ __launch_bounds__(256) void concat_vec_kernel(const ConcatArgs a, int groups_per_px, long long total)
+{
+    const long long g = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (g >= total) return;
+    long long px;
+    if (total < 0x7fffffffLL) px = (unsigned)g / (unsigned)groups_per_px;
+    else px = g / groups_per_px;
+    const int ch = (int)(g - px * groups_per_px) * 16;
+    const uint8_t *src = a.in[0];
+    int cs = a.in_cs[0], c0 = 0, mul = a.mul[0], shift = a.shift[0];
+    Rq24 q = a.q[0];
+    for (int i = 1; i < a.n_in; ++i) {
+        const bool later = ch >= a.c_end[i - 1];
+        src = later ? a.in[i] : src;
+        cs = later ? a.in_cs[i] : cs;
+        c0 = later ? a.c_end[i - 1] : c0;
+        mul = later ? a.mul[i] : mul;
+        shift = later ? a.shift[i] : shift;
+        q.ok = later ? a.q[i].ok : q.ok;
+        q.mul = later ? a.q[i].mul : q.mul;
+        q.shift = later ? a.q[i].shift : q.shift;
+        q.t_hi = later ? a.q[i].t_hi : q.t_hi;
+        q.rnd = later ? a.q[i].rnd : q.rnd;
+    }
+    const v4i wi = *(const v4i *)(src + (size_t)px * cs + (ch - c0));
+    int w[4];
+    if (q.ok) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            uint32_t t[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) t[e] = ((uint32_t)wi[k] >> (8 * e)) & 0xffu;
+            w[k] = requant4_u24(t, q);
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int v = (int)(((uint32_t)wi[k] >> (8 * e)) & 0xffu);
+                word |= (uint32_t)clampi64(rsr64((int64_t)v * mul, shift), 0, a.bound) << (8 * e);
+            }
+            w[k] = (int)word;
+        }
+    }
+    *(v4i *)(a.out + (size_t)px * a.out_cs + ch) = v4i{w[0], w[1], w[2], w[3]};
+}
+
+hipError_t launch_concat_vec(const ConcatArgs &a, int64_t px, hipStream_t st)
+{
+    const int c_total = a.c_end[a.n_in - 1];
+    if (px == 0 || c_total == 0) return hipSuccess;
+    const long long total = (long long)px * (c_total / 16);
+    hipLaunchKernelGGL(concat_vec_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a, c_total / 16, total);
     return hipGetLastError();
 }
 

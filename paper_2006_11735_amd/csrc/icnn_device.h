@@ -138,6 +138,26 @@ hipError_t launch_pc_prepack(const int32_t *mul, const int32_t *shift, const int
 hipError_t launch_pad_small_cin(const uint8_t *x, void *out, int N, int H, int W, int Cin, int in_cs, int ph, int pw,
                                 int Hp, int Wp, uint32_t in_xor, hipStream_t st);
 
+// [t * mul / 2^shift] clamped to [0, hi] for t >= 0 in 32 bits: with t first limited to t_hi, the
+// smallest t whose result reaches hi, t * mul + 2^(shift-1) stays below 2^32 with both factors below
+// 2^24 (one 24-bit multiply-add, one shift, no clamp of the result).  (mul, shift) are the caller's
+// pair with common factors of two removed, which changes no result.  ok = 0: the pair does not fit.
+struct Rq24 {
+    int ok, mul, shift, t_hi, rnd;
+};
+static inline Rq24 make_rq24(long long mul, int shift, int hi)
+{
+    Rq24 r = {0, 0, 0, 0, 0};
+    while (shift >= 2 && mul != 0 && (mul & 1) == 0) { mul /= 2; --shift; }
+    if (hi < 0 || shift < 1 || shift > 31 || mul < 1 || mul >= (1 << 24)) return r;
+    const long long half = 1LL << (shift - 1);
+    const long long num = ((long long)hi << shift) - half;
+    const long long t_hi = num <= 0 ? 0 : (num + mul - 1) / mul;
+    if (t_hi >= (1 << 24) || t_hi * mul + half > 0xffffffffLL || ((t_hi * mul + half) >> shift) != hi) return r;
+    r.ok = 1; r.mul = (int)mul; r.shift = shift; r.t_hi = (int)t_hi; r.rnd = (int)half;
+    return r;
+}
+
 struct AddArgs {
     const void *a;
     const void *b;
@@ -146,11 +166,23 @@ struct AddArgs {
     int c, a_cs, b_cs, out_cs, out_co, a_dt, b_dt, out_mode;
     int b_mul, b_shift, mul, shift, lo, hi;
     int mul_hi;   // mul << (32 - shift) when the fast requantisation applies
+    Rq24 q24;     // add_u8_kernel's requantisation
 };
 hipError_t launch_add(const AddArgs &a, bool vec, hipStream_t st);
 hipError_t launch_requant_copy(const uint8_t *in, uint8_t *out, int64_t px, int c, int in_cs,
                                int out_cs, int out_co, int mul, int shift, int bound, bool vec,
                                hipStream_t st);
+// All branches of a concatenation in one launch (every branch 16-byte aligned with channel counts and
+// pitches that are multiples of 16): a lane handles one 16-byte group of an output pixel.
+struct ConcatArgs {
+    const uint8_t *in[16];
+    int c_end[16];      // first output channel after branch i
+    int in_cs[16], mul[16], shift[16];
+    Rq24 q[16];
+    int n_in, out_cs, bound;
+    uint8_t *out;
+};
+hipError_t launch_concat_vec(const ConcatArgs &a, int64_t px, hipStream_t st);
 hipError_t launch_maxpool(const uint8_t *x, uint8_t *out, int n, int h, int w, int c, int k,
                           int stride, int pad, int ho, int wo, bool vec, hipStream_t st);
 hipError_t launch_avgpool(const uint8_t *x, uint8_t *out, int n, int hw, int c, int mul, int shift,

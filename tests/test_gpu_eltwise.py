@@ -120,3 +120,71 @@ def test_global_average_pool_and_renormalise():
         B.irenormalize_u8(count, dev(raw), o)
         torch.cuda.synchronize()
         assert (o.cpu().numpy().view(np.int8) == (raw.astype(np.int16) - 128)).all()
+
+
+ADD_U8_PARAMS = [
+    # b_mul, b_shift, mul, shift, hi
+    (18415, 5, 23187, 24, 127), (1, 0, 1, 1, 255), (1, 0, 3, 1, 255), ((1 << 23) - 1, 20, (1 << 24) - 1, 31, 255),
+    (40000, 7, 6 << 10, 22, 15), (255, 8, 52429, 19, 63), (8421504, 30, 1 << 20, 21, 200), (7, 1, 999983, 30, 127),
+    (1 << 22, 0, 5, 31, 255),        # skip term up to 2^30
+]
+
+
+@pytest.mark.parametrize("params", ADD_U8_PARAMS, ids=lambda p: "-".join(map(str, p)))
+@pytest.mark.parametrize("dense", [True, False])
+def test_add_of_two_unsigned_maps_in_32_bits(params, dense):
+    """The unsigned 8-bit + 8-bit -> 8-bit kernel over full-range bytes, multipliers at the limits of its 24-bit form."""
+    from gpu_util import dev
+    from paper_2006_11735_amd import binding as B
+    b_mul, b_shift, mul, shift, hi = params
+    g = rnd(sum(params))
+    px, c = 1111, 48
+    a = g.integers(0, 256, size=(px, c), dtype=np.uint8)
+    b = g.integers(0, 256, size=(px, c), dtype=np.uint8)
+    a[0, :4] = [0, 255, 0, 255]
+    b[0, :4] = [0, 0, 255, 255]
+    want = O.add_rescale(a, b, b_mul=b_mul, b_shift=b_shift, mul=mul, shift=shift, lo=0, hi=hi)
+    ocs, oco = (c, 0) if dense else (96, 32)
+    out = torch.full((px, ocs), 9, dtype=torch.uint8, device="cuda:0")
+    d = B.add_desc(count_pixels=px, c=c, a_c_stride=c, b_c_stride=c, out_c_stride=ocs, out_c_offset=oco, a_dtype=B.ICNN_U8,
+                   b_dtype=B.ICNN_U8, b_mul=b_mul, b_shift=b_shift, mul=mul, shift=shift, lo=0, hi=hi)
+    B.iadd_rescale(d, dev(a), dev(b), out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert (got[:, oco:oco + c] == want).all()
+    if not dense:
+        assert (got[:, :oco] == 9).all() and (got[:, oco + c:] == 9).all()
+
+
+@pytest.mark.parametrize("params", [(20000, 14, 100), (1, 1, 255), ((1 << 24) - 1, 31, 255), (3 << 20, 21, 15), (999983, 18, 63),
+                                    (1 << 24, 24, 127), (1 << 30, 31, 127)], ids=lambda p: "-".join(map(str, p)))
+def test_concat_requantisation_in_32_bits(params):
+    from gpu_util import dev
+    from paper_2006_11735_amd import binding as B
+    mul, shift, bound = params
+    g = rnd(sum(params))
+    px = 777
+    xs = [g.integers(0, 256, size=(px, c), dtype=np.uint8) for c in (32, 16)]
+    out = torch.zeros((px, 48), dtype=torch.uint8, device="cuda:0")
+    B.iconcat([dev(x) for x in xs], [32, 16], [32, 16], [mul, mul], [shift, shift], bound, px, out, 48)
+    torch.cuda.synchronize()
+    assert (out.cpu().numpy() == O.concat(xs, [mul, mul], [shift, shift], bound)).all()
+
+
+def test_concat_of_several_aligned_branches_in_one_launch():
+    """Branches of different widths and pitches, one without channels, one with a pair the 32-bit form does not take;
+    the output rows are wider than the concatenation and keep what lies beyond it."""
+    from gpu_util import dev
+    from paper_2006_11735_amd import binding as B
+    g = rnd(11)
+    px = 1234
+    cs, pitch = [48, 0, 16, 64], [64, 16, 16, 80]
+    muls, shifts = [20000, 5, 1, 3 << 20], [14, 3, 0, 22]
+    bufs = [g.integers(0, 256, size=(px, p), dtype=np.uint8) for p in pitch]
+    xs = [b[:, :c] for b, c in zip(bufs, cs)]
+    out = torch.full((px, 160), 201, dtype=torch.uint8, device="cuda:0")
+    B.iconcat([dev(b) for b in bufs], cs, pitch, muls, shifts, 127, px, out, 160)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    want = O.concat([x for x in xs if x.shape[1]], [m for m, c in zip(muls, cs) if c], [s for s, c in zip(shifts, cs) if c], 127)
+    assert (got[:, :128] == want).all() and (got[:, 128:] == 201).all()
