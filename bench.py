@@ -4,8 +4,8 @@
 A step is one pass of the whole ResNet-50-shaped integer network at batch 64
 (every conv with its fused integer epilogue, the skip merges, both pools and
 the fully connected layer) over synthetic inputs that already sit in HBM.
-Prints one JSON line on stdout; per-layer detail goes to stderr and, when the
-folder exists, to gpurun_out/bench_layers.json.
+Prints one JSON line on stdout; per-layer detail goes to stderr and, with
+--layers-json PATH, to that file.
 """
 import argparse
 import json
@@ -153,6 +153,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="cfg3", help="workload (cfg3 = ResNet-50-shaped, batch 64)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers-json", default=None, help="also write the per-layer table to this file")
     ap.add_argument("--layer-reps", type=int, default=20)
     ap.add_argument("--per-channel", action="store_true",
                     help="time the variant with one (mul, shift) per output channel instead of the per-layer workload")
@@ -301,9 +302,8 @@ def main():
         result["bandwidth_kernels"] = other_bandwidth(torch)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(net, calib, seed)
-    out_dir = os.path.join(ROOT, "gpurun_out")
-    if os.path.isdir(out_dir):
-        with open(os.path.join(out_dir, "bench_layers.json"), "w") as f:
+    if args.layers_json:
+        with open(args.layers_json, "w") as f:
             json.dump({"result": result, "layers": rows}, f, indent=1)
     print(json.dumps(result), flush=True)
 
