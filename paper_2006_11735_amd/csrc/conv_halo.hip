@@ -70,7 +70,10 @@ constexpr int halo_younger(int t, bool pnext, int NA, int PQ)
     return n;
 }
 
-template <int BM, int BP, int WAVES_M, int WAVES_P, int PQ, bool U8>
+// PC: per-output-channel requantisation (epilogue_pc_tiles, parameters read from global memory).  Its
+// registers do not fit beside the state a workgroup keeps for its next tile, so these instantiations
+// handle exactly one tile per workgroup (the launcher sees to it): everything about a next tile folds away.
+template <int BM, int BP, int WAVES_M, int WAVES_P, int PQ, bool PC, bool U8>
 __global__ __launch_bounds__(512, 1) void conv_halo_kernel(const ConvArgs a, const HaloArgs h)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the buffer-resource type exists in the device pass only
@@ -297,7 +300,7 @@ __global__ __launch_bounds__(512, 1) void conv_halo_kernel(const ConvArgs a, con
         v4i res8[TM][TP];
         prefetch_res8<TM, TP>(a, co_wave, pix_wave, lane, res8);
         int nct = 0, npt = 0;
-        const bool more = v + (int)gridDim.x < a.n_vtiles && tile_of(v + (int)gridDim.x, nct, npt);
+        const bool more = !PC && v + (int)gridDim.x < a.n_vtiles && tile_of(v + (int)gridDim.x, nct, npt);
         int rel_next[TP];     // this lane's patch rows in the next tile
 #pragma unroll
         for (int j = 0; j < TP; ++j) rel_next[j] = more ? rel_of(npt, j) : rel[j];
@@ -375,7 +378,9 @@ __global__ __launch_bounds__(512, 1) void conv_halo_kernel(const ConvArgs a, con
 
         v += gridDim.x;
         if (more) load_bias_rows<TM>(a, nct * BM + wm * TM * 32, lane >> 5, bias_next);
-        epilogue_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane, res8);
+        if constexpr (PC)
+            epilogue_pc_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane, res8, a.pc + (size_t)((ct * BM) >> 4) * kPcGroupInts, ct * BM);
+        else epilogue_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane, res8);
         if (!more) break;
         ct = nct;
         pt = npt;
@@ -435,17 +440,19 @@ static hipError_t launch_halo(const ConvArgs &a0, int rows, hipStream_t st)
         hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, a, h);
         return hipGetLastError();
     };
-    if (a.pc) return hipErrorInvalidValue;          // see halo_choice
-    return a.frag_xor ? go(conv_halo_kernel<BM, BP, WAVES_M, WAVES_P, PQ, true>)
-                      : go(conv_halo_kernel<BM, BP, WAVES_M, WAVES_P, PQ, false>);
+    if (a.pc) {
+        if (a.n_tiles > (int)grid.x) return hipErrorInvalidValue;          // one tile per workgroup, see halo_choice
+        return a.frag_xor ? go(conv_halo_kernel<BM, BP, WAVES_M, WAVES_P, PQ, true, true>)
+                          : go(conv_halo_kernel<BM, BP, WAVES_M, WAVES_P, PQ, true, false>);
+    }
+    return a.frag_xor ? go(conv_halo_kernel<BM, BP, WAVES_M, WAVES_P, PQ, false, true>)
+                      : go(conv_halo_kernel<BM, BP, WAVES_M, WAVES_P, PQ, false, false>);
 }
 
 // tile shape for a layer: 0 none (not applicable), 1: 128 x 128, 2: 64 x 256
 static int halo_choice(const ConvArgs &a, int *rows)
 {
-    // (per-channel parameters: the epilogue's registers do not fit beside two fragment sets; those layers keep
-    // the tap-by-tap kernel)
-    if (!halo_shape_ok(a) || a.pc) return 0;
+    if (!halo_shape_ok(a)) return 0;
     int choice = a.Cout > 64 ? 1 : 2;
     if (const char *e = getenv("ICNN_HALO_TILE")) choice = atoi(e);   // tuning aid
     if (choice != 1 && choice != 2) return 0;
@@ -462,6 +469,7 @@ static int halo_choice(const ConvArgs &a, int *rows)
     // 9-step tiles lose.  ICNN_HALO_ALWAYS lifts both limits (tuning, tests of the multi-tile path).
     const long long tiles = (long long)((a.Cout + bm - 1) / bm) * ((a.M + bp - 1) / bp);
     if ((tiles > 256 || a.ksteps < 18) && !getenv("ICNN_HALO_ALWAYS")) return 0;
+    if (a.pc && tiles > 256) return 0;       // per-channel instantiations: one tile per workgroup
     return choice;
 }
 

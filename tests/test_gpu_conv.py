@@ -545,3 +545,19 @@ def test_few_pixel_pointwise_kernel(shape):
     xw = rnd(11).integers(0, 128, size=(n, h, w, cin + 16), dtype=np.uint8)      # channel slice of a wider buffer
     got, want = both(xw, wt, b, out_mode="raw_s32", cin=cin)
     assert (got == want).all()
+
+
+@pytest.mark.parametrize("shape", PATCH_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("with_skip", [False, True])
+def test_patch_resident_kernel_with_per_channel_parameters(shape, with_skip):
+    """The patch-resident kernel's per-channel instantiations (one tile per workgroup), with and without an
+    8-bit skip operand, channel tails included."""
+    n, h, w, cin, cout, k, stride, pad = shape
+    raw = cin >= 128 and (cin // 64) % 2 == 1
+    x, wt, b = make(sum(shape) + 5, n, h, w, cin, cout, k, raw=raw)
+    pc = channel_params(sum(shape) + 6, cout, res=with_skip)
+    kw = dict(stride=stride, pad=pad, bound_q=127, **pc)
+    if with_skip:
+        kw.update(res=rnd(sum(shape) + 7).integers(0, 128, size=(n, h, w, cout), dtype=np.uint8), res_mode="pre")
+    got, want = both(x, wt, b, **kw)
+    assert (got == want).all() and len(np.unique(want)) > 16
