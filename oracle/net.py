@@ -158,7 +158,9 @@ def calibrate(net, seed, per_channel=False, max_int=K.MAX_INT):
             m, s = K.bound_params(h, max_int)
             cal.update(mul=m, shift=s, bound_q=max_int, h_ri=h)
             if per_channel:
-                pairs = [K.bound_params(hc, max_int) for hc in K.percentile_999_per_channel(t)]
+                # a channel without positive values in the sample (statistic 1, the floor) has no bound
+                # of its own: it keeps the layer's pair instead of a ratio of max_int per unit
+                pairs = [K.bound_params(hc, max_int) if hc > 1 else (m, s) for hc in K.percentile_999_per_channel(t)]
                 cal["mul_c"] = [mc for mc, _ in pairs]
                 cal["shift_c"] = [sc for _, sc in pairs]
             calib["conv"][op["name"]] = cal
