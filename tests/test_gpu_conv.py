@@ -561,3 +561,23 @@ def test_patch_resident_kernel_with_per_channel_parameters(shape, with_skip):
         kw.update(res=rnd(sum(shape) + 7).integers(0, 128, size=(n, h, w, cout), dtype=np.uint8), res_mode="pre")
     got, want = both(x, wt, b, **kw)
     assert (got == want).all() and len(np.unique(want)) > 16
+
+
+def test_random_requantisation_pairs_through_the_conv_epilogue():
+    """150 seeded (mul, shift, bound_q) triples around the limits of the epilogue's 32-bit and one-multiply forms,
+    half of them with an 8-bit skip operand and a random rescale; accumulators from -2^22 to 2^22."""
+    g = rnd(4242)
+    x = g.integers(0, 128, size=(2, 9, 7, 64), dtype=np.uint8)
+    wt = g.integers(-127, 128, size=(32, 1, 1, 64), dtype=np.int8)
+    b = (g.integers(-(1 << 22), 1 << 22, size=32)).astype(np.int32)
+    r = g.integers(0, 256, size=(2, 9, 7, 32), dtype=np.uint8)
+    for i in range(150):
+        shift = int(g.integers(0, 45))
+        bits = int(g.integers(1, 31))
+        mul = int(g.integers(1 << (bits - 1), 1 << bits))
+        kw = dict(mul=mul, shift=shift, bound_q=int(g.choice([1, 15, 63, 127, 255])))
+        if i % 2:
+            kw.update(res=r, res_mode="pre", res_mul=int(g.integers(1, 1 << int(g.integers(1, 24)))),
+                      res_shift=int(g.integers(0, 20)))
+        got, want = both(x, wt, b, **kw)
+        assert (got == want).all(), kw

@@ -188,3 +188,47 @@ def test_concat_of_several_aligned_branches_in_one_launch():
     got = out.cpu().numpy()
     want = O.concat([x for x in xs if x.shape[1]], [m for m, c in zip(muls, cs) if c], [s for s, c in zip(shifts, cs) if c], 127)
     assert (got[:, :128] == want).all() and (got[:, 128:] == 201).all()
+
+
+def test_every_byte_through_random_requantisation_pairs():
+    """iconcat's requantisation over all 256 input bytes for 300 seeded (mul, shift, bound) triples that straddle
+    the limits of the 32-bit form (multipliers around 2^24, shifts 0..40, bounds 1..255)."""
+    from gpu_util import dev
+    from paper_2006_11735_amd import binding as B
+    g = rnd(2024)
+    x = np.arange(256, dtype=np.uint8).reshape(16, 16)
+    xd = dev(x)
+    out = torch.zeros((16, 16), dtype=torch.uint8, device="cuda:0")
+    for _ in range(300):
+        shift = int(g.integers(0, 41))
+        bits = int(g.integers(1, 31))
+        mul = int(g.integers(1 << (bits - 1), 1 << bits)) if g.integers(0, 4) else int(1 << bits)
+        bound = int(g.choice([1, 15, 31, 63, 100, 127, 200, 255]))
+        B.iconcat([xd], [16], [16], [mul], [shift], bound, 16, out, 16)
+        torch.cuda.synchronize()
+        want = O.concat([x], [mul], [shift], bound)
+        assert (out.cpu().numpy() == want).all(), (mul, shift, bound)
+
+
+def test_every_pair_of_bytes_through_random_addition_parameters():
+    """iadd_rescale u8 + u8 -> u8 over all 65536 (a, b) byte pairs for 120 seeded parameter sets around the limits
+    of the 32-bit kernel (and beyond them, where the general kernel takes over)."""
+    from gpu_util import dev
+    from paper_2006_11735_amd import binding as B
+    g = rnd(2025)
+    a = np.repeat(np.arange(256, dtype=np.uint8), 256).reshape(4096, 16)
+    b = np.tile(np.arange(256, dtype=np.uint8), 256).reshape(4096, 16)
+    ad, bd = dev(a), dev(b)
+    out = torch.zeros((4096, 16), dtype=torch.uint8, device="cuda:0")
+    for _ in range(120):
+        b_shift = int(g.integers(0, 31))
+        b_mul = int(g.integers(1, 1 << int(g.integers(1, 25))))
+        shift = int(g.integers(0, 36))
+        mul = int(g.integers(1, 1 << int(g.integers(1, 27))))
+        hi = int(g.choice([1, 15, 63, 127, 128, 255]))
+        d = B.add_desc(count_pixels=4096, c=16, a_c_stride=16, b_c_stride=16, out_c_stride=16, a_dtype=B.ICNN_U8,
+                       b_dtype=B.ICNN_U8, b_mul=b_mul, b_shift=b_shift, mul=mul, shift=shift, lo=0, hi=hi)
+        B.iadd_rescale(d, ad, bd, out)
+        torch.cuda.synchronize()
+        want = O.add_rescale(a, b, b_mul=b_mul, b_shift=b_shift, mul=mul, shift=shift, lo=0, hi=hi)
+        assert (out.cpu().numpy() == want).all(), (b_mul, b_shift, mul, shift, hi)
