@@ -306,6 +306,10 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
                     if constexpr (U8) bf[kq][j] ^= v4i{(int)0x80808080, (int)0x80808080, (int)0x80808080, (int)0x80808080};
                 }
             }
+            // all fragment reads are issued before the first MFMA: left alone, the compiler of a kernel that is
+            // short of registers (the per-channel epilogue) reads each fragment just before its MFMA and
+            // waits for it there, eight times a step
+            __builtin_amdgcn_sched_barrier(0);
             int c = 0;
 #pragma unroll
             for (int kq = 0; kq < 2; ++kq)
