@@ -118,8 +118,9 @@ __device__ __forceinline__ int requant4_u24(const uint32_t (&t)[4], const Rq24 &
 // launch_add): t = a + [b * b_mul / 2^b_shift] is at most 255 + 2^30, never negative and never
 // saturates, and the requantisation runs in 32 bits.  About eight vector instructions per element, so
 // the kernel is bound by HBM and not by its arithmetic.
-constexpr int kGroupsPerLane = 4;   // 16-byte groups a lane handles: fewer, longer waves (the rate at which waves
-                                    // can be launched, not HBM, bounds a kernel whose lanes move 48 bytes each)
+constexpr int kGroupsPerLane = 4;   // 16-byte groups a lane handles, all eight loads issued before the first use
+                                    // (a quarter of the waves for the same bytes; measured equal to one group per
+                                    // lane on dense 50 MB tensors, kept for the loads in flight on small ones)
 
 __global__ __launch_bounds__(256) void add_u8_kernel(const AddArgs a, int groups_per_px, long long total)
 {
