@@ -858,10 +858,11 @@ __global__ __launch_bounds__(256) void pad_small_cin_rows_kernel(const uint8_t *
 // bytes (three aligned dwords, coalesced across the wave) into four output pixels; byte loads cost
 // one address per lane and made the generic kernel address-bound.  Thread W/4 of a row writes the
 // left and right border, rows outside the image are all zero.
-__global__ __launch_bounds__(256) void pad_rgb_rows_kernel(const uint32_t *__restrict__ x, uint32_t *__restrict__ out, int H,
-                                                           int W, int ph, int pw, int Hp, int Wp, uint32_t in_xor)
+typedef int v4i_dword_aligned __attribute__((ext_vector_type(4), aligned(4)));
+__global__ __launch_bounds__(64) void pad_rgb_rows_kernel(const uint32_t *__restrict__ x, uint32_t *__restrict__ out, int H,
+                                                          int W, int ph, int pw, int Hp, int Wp, uint32_t in_xor)
 {
-    const int t = blockIdx.x * 256 + threadIdx.x;
+    const int t = blockIdx.x * 64 + threadIdx.x;
     const int quads = W >> 2;
     if (t > quads) return;
     const int yp = blockIdx.y, n = blockIdx.z;
@@ -880,17 +881,16 @@ __global__ __launch_bounds__(256) void pad_rgb_rows_kernel(const uint32_t *__res
     }
     // bytes r0 g0 b0 r1 | g1 b1 r2 g2 | b2 r3 g3 b3  ->  one dword per pixel, top byte zero
     const uint32_t m = rowok ? 0x00ffffffu : 0u;
-    o[pw + 4 * t + 0] = d0 & m;
-    o[pw + 4 * t + 1] = ((d0 >> 24) | (d1 << 8)) & m;
-    o[pw + 4 * t + 2] = ((d1 >> 16) | (d2 << 16)) & m;
-    o[pw + 4 * t + 3] = (d2 >> 8) & m;
+    // one 16-byte store per thread (the left border makes it dword-aligned only)
+    *(v4i_dword_aligned *)(o + pw + 4 * t) = v4i_dword_aligned{(int)(d0 & m), (int)(((d0 >> 24) | (d1 << 8)) & m),
+                                                               (int)(((d1 >> 16) | (d2 << 16)) & m), (int)((d2 >> 8) & m)};
 }
 
 hipError_t launch_pad_small_cin(const uint8_t *x, void *out, int N, int H, int W, int Cin, int in_cs, int ph, int pw,
                                 int Hp, int Wp, uint32_t in_xor, hipStream_t st)
 {
     if (Cin == 3 && in_cs == 3 && W % 4 == 0 && !((uintptr_t)x & 3) && Wp >= pw + W && N <= 65535 && Hp <= 65535) {
-        hipLaunchKernelGGL(pad_rgb_rows_kernel, dim3((unsigned)((W / 4 + 1 + 255) / 256), (unsigned)Hp, (unsigned)N), dim3(256), 0,
+        hipLaunchKernelGGL(pad_rgb_rows_kernel, dim3((unsigned)((W / 4 + 1 + 63) / 64), (unsigned)Hp, (unsigned)N), dim3(64), 0,
                            st, (const uint32_t *)x, (uint32_t *)out, H, W, ph, pw, Hp, Wp, in_xor);
         return hipGetLastError();
     }
