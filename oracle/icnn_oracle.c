@@ -285,6 +285,14 @@ int orc_avgpool_global_u8(int32_t n, int32_t h, int32_t w, int32_t c, int32_t mu
     return ORC_OK;
 }
 
+/* Re-normalisation of a raw picture (Section 3.4.1): every uint8 sample minus 128, as int8. */
+int orc_renormalize_u8(int64_t count, const uint8_t *x, int8_t *out)
+{
+    if (count < 0 || (count > 0 && (!x || !out))) return ORC_E_ARG;
+    for (int64_t i = 0; i < count; ++i) out[i] = (int8_t)((int)x[i] - 128);
+    return ORC_OK;
+}
+
 /* Threads the parallel loops above will use (for reporting beside timings). */
 #ifdef _OPENMP
 #include <omp.h>

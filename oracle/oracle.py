@@ -63,6 +63,8 @@ def lib():
         L.orc_maxpool2d_u8.argtypes = [C.c_int32] * 7 + [C.c_void_p, C.c_void_p]
         L.orc_avgpool_global_u8.restype = C.c_int
         L.orc_avgpool_global_u8.argtypes = [C.c_int32] * 7 + [C.c_void_p, C.c_void_p]
+        L.orc_renormalize_u8.restype = C.c_int
+        L.orc_renormalize_u8.argtypes = [C.c_int64, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -215,5 +217,14 @@ def avgpool_global(x, mul, shift, bound_q=127):
     out = np.zeros((n, 1, 1, c), dtype=np.uint8)
     rc = lib().orc_avgpool_global_u8(n, h, w, c, int(mul), int(shift), int(bound_q),
                                      _ptr(x), _ptr(out))
+    assert rc == 0
+    return out
+
+
+def renormalize(x):
+    """Raw uint8 picture -> int8 samples x - 128 (Section 3.4.1)."""
+    x = np.ascontiguousarray(x, dtype=np.uint8)
+    out = np.zeros(x.shape, dtype=np.int8)
+    rc = lib().orc_renormalize_u8(x.size, _ptr(x), _ptr(out))
     assert rc == 0
     return out

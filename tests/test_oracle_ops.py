@@ -109,3 +109,19 @@ def test_global_average_against_rationals():
         want = min(127, math.floor(Fraction(int(s_) * mul, 1 << shift) + Fraction(1, 2)))
         assert int(q) == want
     assert np.abs(got.reshape(3, 6).astype(float) - sums / 49.0).max() <= 0.51
+
+
+def test_renormalise_is_minus_128_on_every_byte():
+    # Section 3.4.1: all 256 byte values against the closed form; as bytes it is a flip of the top bit; and a
+    # layer that re-normalises on the fly equals the same layer on the re-normalised picture
+    x = np.arange(256, dtype=np.uint8)
+    got = O.renormalize(x)
+    assert got.dtype == np.int8 and [int(v) for v in got] == [v - 128 for v in range(256)]
+    assert (got.view(np.uint8) == (x ^ 0x80)).all()
+    g = rnd(10)
+    raw = g.integers(0, 256, size=(1, 7, 9, 3), dtype=np.uint8)
+    w = g.integers(-127, 128, size=(5, 3, 3, 3), dtype=np.int8)
+    b = g.integers(-50, 50, size=5).astype(np.int32)
+    fly = O.conv2d(raw, w, b, stride=1, pad=1, in_sub128=True, out_mode="raw_s32")
+    pre = O.conv2d(O.renormalize(raw), w, b, stride=1, pad=1, out_mode="raw_s32")
+    assert (fly == pre).all()
