@@ -119,7 +119,9 @@ __device__ __forceinline__ void epilogue_vec(const ConvArgs &a, const v16i &acc,
         const int half = (1 << a.res_shift) >> 1;
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-            t[r] = __builtin_elementwise_add_sat(t[r], (__mul24(rv[r], a.res_mul) + half) >> a.res_shift);   // res_mul < 2^23
+            // unsigned operand and 255 * res_mul + half < 2^31 (the host's gate), so res_mul < 2^24: an unsigned
+            // 24-bit multiply (the signed one would read multipliers from 2^23 on as negative)
+            t[r] = __builtin_elementwise_add_sat(t[r], (int)((__umul24((uint32_t)rv[r], (uint32_t)a.res_mul) + (uint32_t)half) >> a.res_shift));
     }
     if (RES == 2 && a.res_mode == 1) {
 #pragma unroll
@@ -269,8 +271,10 @@ __device__ __forceinline__ void epilogue_pc_row(const ConvArgs &a, const v16i (&
                 for (int e = 0; e < 4; ++e) {
                     int t = acc[j][4 * q4 + e];
                     if (RES) {
-                        const int rv = (int)((w4 >> (8 * e)) & 0xffu);      // unsigned operands only (a.pc_fast_ok)
-                        t = __builtin_elementwise_add_sat(t, (__mul24(rv, rmu[e]) + ((1 << rsf[e]) >> 1)) >> rsf[e]);
+                        // unsigned operands only (a.pc_fast_ok) and 255 * rmu + half < 2^31 (group flag bit 0): an
+                        // unsigned 24-bit multiply whose sum stays below 2^31
+                        const uint32_t rv = (w4 >> (8 * e)) & 0xffu;
+                        t = __builtin_elementwise_add_sat(t, (int)((__umul24(rv, (uint32_t)rmu[e]) + ((1u << rsf[e]) >> 1)) >> rsf[e]));
                     }
                     int q;
                     if (PLAIN) {

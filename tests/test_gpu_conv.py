@@ -114,6 +114,25 @@ def test_skip_merge_before_requantisation(res_kind, cout):
     assert (got == want).all() and want.max() == 127
 
 
+@pytest.mark.parametrize("pair", [(8388608, 23), (8421504, 30), (8388607, 23), (8421504, 0)], ids=lambda p: "%dx2^-%d" % p)
+def test_skip_rescale_multipliers_of_24_bits(pair):
+    """Skip multipliers with bit 23 set are inside the documented domain and inside the 32-bit fast gate
+    (255 * res_mul + half < 2^31): the 24-bit multiply must read them as unsigned.  Per layer and per channel."""
+    rm, rs = pair
+    x, wt, b = make(66, 2, 9, 11, 64, 64, 1)
+    r = rnd(661).integers(0, 256, size=(2, 9, 11, 64), dtype=np.uint8)
+    mul, shift = (23187, 25) if rs else (3, 20)
+    kw = dict(res=r, res_mode="pre", res_mul=rm, res_shift=rs)
+    got, want = both(x, wt, b, out_mode="raw_s32", **kw)
+    assert (got == want).all() and want.max() > 0
+    got, want = both(x, wt, b, mul=mul, shift=shift, bound_q=127, **kw)
+    assert (got == want).all() and 0 < want.max() <= 127
+    got, want = both(x, wt, b, bound_q=127, res=r, res_mode="pre", mul_c=np.full(64, mul, np.int32),
+                     shift_c=np.full(64, shift, np.int32), res_mul_c=np.full(64, rm, np.int32),
+                     res_shift_c=np.full(64, rs, np.int32))
+    assert (got == want).all() and 0 < want.max() <= 127
+
+
 def test_skip_merge_saturates_to_int32():
     x, wt, b = make(7, 1, 4, 4, 16, 16, 1)
     r = np.full((1, 4, 4, 16), 2**31 - 1, np.int32)
@@ -512,16 +531,20 @@ def test_patch_resident_3x3_kernel(shape):
 
 @pytest.mark.parametrize("shape", [(9, 28, 28, 128, 128, 3, 1, 1), (20, 14, 14, 192, 200, 3, 1, 1), (40, 7, 7, 128, 1024, 3, 1, 1)],
                          ids=lambda s: "x".join(map(str, s)))
-def test_patch_resident_kernel_with_several_tiles_per_workgroup(shape, monkeypatch):
-    """More than 256 tiles: the library would pick the tap-by-tap kernel; the tuning switch forces the
+def test_patch_resident_kernel_with_several_tiles_per_workgroup(shape):
+    """More than 256 tiles: the library would pick the tap-by-tap kernel; the tuning override forces the
     patch-resident one, whose workgroups then walk several tiles (patch and fragment prefetch across tiles)."""
-    monkeypatch.setenv("ICNN_HALO_ALWAYS", "1")
-    n, h, w, cin, cout, k, stride, pad = shape
-    x, wt, b = make(32, n, h, w, cin, cout, k)
-    got, want = both(x, wt, b, stride=stride, pad=pad, out_mode="raw_s32")
-    assert (got == want).all()
-    got, want = both(x, wt, b, stride=stride, pad=pad, bound_q=127, **channel_params(79, cout))
-    assert (got == want).all()
+    from paper_2006_11735_amd import binding as B
+    B.icnn_set_tuning("halo_always", 1)
+    try:
+        n, h, w, cin, cout, k, stride, pad = shape
+        x, wt, b = make(32, n, h, w, cin, cout, k)
+        got, want = both(x, wt, b, stride=stride, pad=pad, out_mode="raw_s32")
+        assert (got == want).all()
+        got, want = both(x, wt, b, stride=stride, pad=pad, bound_q=127, **channel_params(79, cout))
+        assert (got == want).all()
+    finally:
+        B.icnn_set_tuning("reset")
 
 
 # ---- pointwise layers on at most 64 pixels take the kernel whose eight waves split the K axis

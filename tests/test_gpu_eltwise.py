@@ -119,7 +119,34 @@ def test_global_average_pool_and_renormalise():
         o = torch.zeros(count, dtype=torch.uint8, device="cuda:0")
         B.irenormalize_u8(count, dev(raw), o)
         torch.cuda.synchronize()
-        assert (o.cpu().numpy().view(np.int8) == (raw.astype(np.int16) - 128)).all()
+        assert (o.cpu().numpy().view(np.int8) == O.renormalize(raw)).all()
+
+
+@pytest.mark.parametrize("pair", [(8388608, 23), (8421504, 30), (8388607, 23)], ids=lambda p: "%dx2^-%d" % p)
+@pytest.mark.parametrize("a_kind", ["s32", "s8", "u8"])
+@pytest.mark.parametrize("b_kind", ["u8", "s8"])
+def test_add_rescale_multipliers_of_24_bits(pair, a_kind, b_kind):
+    """b multipliers with bit 23 set pass the 32-bit gate (255 * b_mul + half < 2^31); the signed 24-bit
+    multiply of the fast kernel must not take them."""
+    from gpu_util import dev
+    from paper_2006_11735_amd import binding as B
+    b_mul, b_shift = pair
+    g = rnd(sum(pair) + len(a_kind))
+    shape = (2, 9, 13, 32)
+    a, b = tensor(g, shape, a_kind), tensor(g, shape, b_kind)
+    if b_kind == "u8":
+        b = g.integers(0, 256, size=shape, dtype=np.uint8)
+    dt = {"u8": B.ICNN_U8, "s8": B.ICNN_S8, "s32": B.ICNN_S32}
+    for out_mode, tdt, kw in (("clamp_u8", torch.uint8, dict(mul=23187, shift=24 if a_kind == "s32" else 16, lo=0, hi=200)),
+                              ("raw_s32", torch.int32, dict())):
+        want = O.add_rescale(a, b, b_mul=b_mul, b_shift=b_shift, out_mode=out_mode, **kw)
+        d = B.add_desc(count_pixels=2 * 9 * 13, c=32, a_c_stride=32, b_c_stride=32, out_c_stride=32, a_dtype=dt[a_kind],
+                       b_dtype=dt[b_kind], b_mul=b_mul, b_shift=b_shift,
+                       out_mode={"clamp_u8": B.ICNN_OUT_CLAMP_U8, "raw_s32": B.ICNN_OUT_RAW_S32}[out_mode], **kw)
+        out = torch.zeros(shape, dtype=tdt, device="cuda:0")
+        B.iadd_rescale(d, dev(a), dev(b), out)
+        torch.cuda.synchronize()
+        assert (out.cpu().numpy() == want).all(), out_mode
 
 
 ADD_U8_PARAMS = [
