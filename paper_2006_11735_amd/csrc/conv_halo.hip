@@ -35,7 +35,6 @@
 // barrier counts match.
 #include "conv_common.h"
 
-#include <cstdlib>
 #include <type_traits>
 
 namespace icnn {
@@ -454,7 +453,7 @@ static int halo_choice(const ConvArgs &a, int *rows)
 {
     if (!halo_shape_ok(a)) return 0;
     int choice = a.Cout > 64 ? 1 : 2;
-    if (const char *e = getenv("ICNN_HALO_TILE")) choice = atoi(e);   // tuning aid
+    if (g_tuning.halo_tile) choice = g_tuning.halo_tile;
     if (choice != 1 && choice != 2) return 0;
     const int bp = choice == 1 ? 128 : 256, bm = choice == 1 ? 128 : 64;
     *rows = halo_max_rows(a, bp);
@@ -466,9 +465,9 @@ static int halo_choice(const ConvArgs &a, int *rows)
     // One workgroup per compute unit: a tile's epilogue is not hidden behind another workgroup's K loop.  Measured
     // inside whole networks: the kernel wins where a workgroup has one tile and the K loop has 18 steps or more;
     // with several tiles per workgroup it only ties with the tap-by-tap kernel (two workgroups per unit), and
-    // 9-step tiles lose.  ICNN_HALO_ALWAYS lifts both limits (tuning, tests of the multi-tile path).
+    // 9-step tiles lose.  The halo_always override lifts both limits.
     const long long tiles = (long long)((a.Cout + bm - 1) / bm) * ((a.M + bp - 1) / bp);
-    if ((tiles > 256 || a.ksteps < 18) && !getenv("ICNN_HALO_ALWAYS")) return 0;
+    if ((tiles > 256 || a.ksteps < 18) && !g_tuning.halo_always) return 0;
     if (a.pc && tiles > 256) return 0;       // per-channel instantiations: one tile per workgroup
     return choice;
 }

@@ -19,7 +19,6 @@
 //                     through registers (double-buffered LDS).
 #include "conv_common.h"
 
-#include <cstdlib>
 #include <mutex>
 #include <type_traits>
 #include <vector>
@@ -562,7 +561,7 @@ static hipError_t launch_dlds(const ConvArgs &a0, int max_stages, int per_cu, hi
 {
     ConvArgs a = a0;
     if (!finish_args(a, BM, BP)) return hipErrorInvalidValue;
-    if (const char *e = getenv("ICNN_STAGES")) max_stages = atoi(e);   // tuning aid
+    if (g_tuning.stages >= 2 && g_tuning.stages <= 6) max_stages = g_tuning.stages;
     a.nstages = a.ksteps + 1 < max_stages ? a.ksteps + 1 : max_stages;
     if (a.nstages < 2) a.nstages = 2;
     a.div_howo = make_fast_div((unsigned)(a.Ho * a.Wo));
@@ -657,15 +656,14 @@ hipError_t launch_conv(const ConvArgs &a, bool vec_in, bool direct_ok, hipStream
     const bool direct = direct_ok && a.in_xor == 0 && a.x_bytes < 0x7fffff00u && a.wp_bytes < 0x7fffff00u &&
                         a.KH <= 31 && a.KW <= 31;
     // one to four output channels: a lane per pixel and dot products beat tiles that are 7/8 padding
-    if (direct_ok && conv_narrow_applies(a) && !getenv("ICNN_NO_NARROW"))
+    if (direct_ok && conv_narrow_applies(a) && !g_tuning.no_narrow)
         return launch_conv_narrow(a, st);
     // the classifier: a few pixels, long K
-    if (direct_ok && conv_fc_applies(a) && !getenv("ICNN_NO_FC")) return launch_conv_fc(a, st);
+    if (direct_ok && conv_fc_applies(a) && !g_tuning.no_fc) return launch_conv_fc(a, st);
     // 3x3 / stride 1 / padding 1 with cin % 64 == 0: the nine taps read one LDS copy of the input
-    if (direct && !getenv("ICNN_NO_HALO") && !getenv("ICNN_TILE") && conv_halo_applies(a)) return launch_conv_halo(a, st);
+    if (direct && !g_tuning.no_halo && g_tuning.tile < 0 && conv_halo_applies(a)) return launch_conv_halo(a, st);
     if (direct) {
-        const char *env = getenv("ICNN_TILE");       // tuning aid: force one tile shape
-        const int forced = env ? atoi(env) : -1;
+        const int forced = g_tuning.tile;
         int best = -1;
         double best_cost = 0;
         for (int t = 0; t < kNumTiles; ++t) {

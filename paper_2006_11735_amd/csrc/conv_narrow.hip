@@ -259,7 +259,7 @@ hipError_t launch_conv_narrow(const ConvArgs &a0, hipStream_t st)
     const int S = a.Cin / 16, ppb = 4 * (64 / S);
     const int nco = a.Cout == 1 ? 1 : 4;
     const size_t lds = (size_t)a.KH * a.KW * S * nco * 16;
-    if (a.KH == 3 && a.KW == 3 && a.sh == 1 && a.sw == 1 && S <= 8 && !getenv("ICNN_NO_STREAM")) {
+    if (a.KH == 3 && a.KW == 3 && a.sh == 1 && a.sw == 1 && S <= 8 && !g_tuning.no_stream) {
         // row segments short enough to give the chip a few thousand waves, long enough to amortise the
         // two halo rows each segment re-reads
         const int strips = (a.Wo + 64 / S - 1) / (64 / S);

@@ -119,6 +119,20 @@ __device__ __forceinline__ int load_elem(const void *p, size_t i, int dtype)
     return ((const int32_t *)p)[i];
 }
 
+// Kernel-selection overrides (icnn_set_tuning): process-wide plain ints, read at every launch.  They change
+// which kernel runs, never a result.  -1 / 0 = the library's own choice.
+struct Tuning {
+    int tile = -1;         // force tile shape 0..4 of the direct-to-LDS kernel (also keeps 3x3 layers off the patch kernel)
+    int stages = 0;        // force the LDS ring depth of the direct-to-LDS kernel (2..6)
+    int no_narrow = 0;     // keep one-to-four-channel layers on the tile kernels
+    int no_fc = 0;         // keep few-pixel pointwise layers on the tile kernels
+    int no_halo = 0;       // keep 3x3 layers on the tap-by-tap kernel
+    int halo_tile = 0;     // patch-resident kernel: 1 = 128 x 128, 2 = 64 x 256
+    int halo_always = 0;   // patch-resident kernel also with several tiles per workgroup and short K loops
+    int no_stream = 0;     // single-channel 3x3 layers: lane-group kernel instead of the streaming one
+};
+extern Tuning g_tuning;
+
 // launchers (host)
 // vec_in: 16-byte pieces of x never straddle a tap (dword aligned); direct_ok: they are also 16-byte aligned
 hipError_t launch_conv(const ConvArgs &a, bool vec_in, bool direct_ok, hipStream_t st);
@@ -187,6 +201,8 @@ hipError_t launch_maxpool(const uint8_t *x, uint8_t *out, int n, int h, int w, i
                           int stride, int pad, int ho, int wo, bool vec, hipStream_t st);
 hipError_t launch_avgpool(const uint8_t *x, uint8_t *out, int n, int hw, int c, int mul, int shift,
                           int bound, hipStream_t st);
+hipError_t launch_mfma_loop(int blocks, int iters, int *sink, hipStream_t st);
+hipError_t launch_stream_copy(const void *src, void *dst, long long n16, hipStream_t st);
 hipError_t launch_renorm(const uint8_t *x, uint8_t *out, int64_t count, bool vec, hipStream_t st);
 
 }  // namespace icnn

@@ -121,3 +121,16 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     with pytest.raises(B.IcnnError) as e:
         B.irenormalize_u8(16, None, 4096, stream=0)
     assert e.value.code == B.ICNN_E_NULL
+
+
+def test_tuning_overrides_are_validated():
+    B = binding()
+    try:
+        B.icnn_set_tuning("tile", 3)
+        B.icnn_set_tuning("halo_always", 1)
+        for name, value in (("tile", 5), ("tile", -2), ("stages", 1), ("stages", 7), ("no_fc", 2), ("colour", 1)):
+            with pytest.raises(B.IcnnError) as e:
+                B.icnn_set_tuning(name, value)
+            assert e.value.code == B.ICNN_E_PARAM, (name, value)
+    finally:
+        B.icnn_set_tuning("reset")

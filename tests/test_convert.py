@@ -1,5 +1,5 @@
 """The offline float -> integer conversion (the paper's Algorithm 1 without its training steps):
-its integer helpers against the oracle-side calibrator and the paper's post-condition, batch-norm
+its integer helpers against exact rationals and the paper's post-condition, batch-norm
 folding against a library batch norm, the ratio bookkeeping at merges and concatenations, and the
 end-to-end property the method exists for: the integer network (run by the CPU oracle) tracks the
 BReLU-enabled float network to within a few quantisation steps."""
@@ -7,7 +7,6 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import calibrate as K
 from oracle import net as ONet
 from oracle import oracle as O
 from paper_2006_11735_amd import convert as C
@@ -31,15 +30,31 @@ def float_params(net, seed, bn=False):
     return prm
 
 
-def test_integer_helpers_agree_with_the_oracle_side_calibrator():
+def test_integer_helpers_against_exact_rationals_and_the_bound_condition():
+    """mul_shift: mul / 2^shift within 2^-15 of b / a (half a unit of a 15-bit multiplier), the multiplier has
+    15 significant bits and the shift is the smallest that gives them; bound_params: the post-condition of
+    Section 3.3, [h_ri * mul / 2^shift] = max_int, with a multiplier that stays next to the rounded ratio."""
+    from fractions import Fraction
     g = np.random.default_rng(1)
-    for _ in range(3000):
-        a, b = int(g.integers(1, 1 << 24)), int(g.integers(1, 1 << 24))
-        assert C.mul_shift(a, b) == K.mul_shift(a, b)
+    cases = [(int(g.integers(1, 1 << 24)), int(g.integers(1, 1 << 24))) for _ in range(3000)]
+    cases += [(1, 1), (127, 1), (1, 127), (3, 1 << 20), ((1 << 24) - 1, 1), (1, (1 << 24) - 1), (12345, 12345)]
+    for a, b in cases:
+        m, s = C.mul_shift(a, b)
+        ratio = Fraction(b, a)
+        assert 0 <= s <= 46 and 1 <= m < (1 << 31)
+        if s < 46 and m < (1 << 31) - 1:
+            assert m >= (1 << 14)
+            assert abs(Fraction(m, 1 << s) / ratio - 1) <= Fraction(1, 1 << 15), (a, b, m, s)
+            assert s == 0 or ratio * (1 << (s - 1)) + Fraction(1, 2) < (1 << 14), (a, b, m, s)     # smallest such shift
+            assert abs(Fraction(m) - ratio * (1 << s)) <= Fraction(1, 2)                                # rounded, not truncated
     for max_int in (127, 255, 15):
         for h in list(range(1, 600)) + [int(v) for v in g.integers(600, 1 << 24, size=600)]:
             m, s = C.bound_params(h, max_int)
-            assert (m, s) == K.bound_params(h, max_int) and O.requant(h, m, s) == max_int      # Section 3.3
+            assert O.requant(h, m, s) == max_int                                                        # Section 3.3
+            exact = (int(h) * m + ((1 << s) >> 1)) >> s                                                 # the same in big integers
+            assert exact == max_int
+            m0, s0 = C.mul_shift(h, max_int)
+            assert s == s0 and abs(m - m0) <= max(1, m0 >> 13), (h, max_int, m, m0)
     x = g.normal(0, 40, size=1000)
     assert (C.rhu(x) == np.floor(x + 0.5)).all() and C.rhu(-2.5) == -2 and C.rhu(2.5) == 3
 

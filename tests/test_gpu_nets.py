@@ -135,7 +135,6 @@ def test_config3_resnet50_full_batch_sampled_images():
     assert len(g.fused) == 4
     logits = g.result("logits")
     assert logits.dtype == np.int32 and logits.shape == (64, 1, 1, 1000)
-    assert len({int(v) for v in logits.reshape(64, -1).argmax(axis=1)}) > 1 or True
 
 
 @pytest.mark.parametrize("max_int", [255, 63, 15])
@@ -218,14 +217,23 @@ def test_config6_vrcnn_2560x1600_frame():
     compare_all(net, g, want)
 
 
-def test_config4_resnet152_sub_batch():
-    # ResNet-152-shaped: 8 of the 128 images end to end (the oracle needs ~12 GMAC per image).
+def test_config4_resnet152_full_batch_sampled_images():
+    # ResNet-152-shaped at its full batch of 128, i.e. the tile choices, persistent grids and pixel counts of the
+    # launch configuration that is timed; images are independent, so the oracle checks a sample of them on every
+    # buffer of every layer (about 12 GMAC per image).
     from paper_2006_11735_amd.netrun import GpuNet
     net, calib = W.CONFIGS["cfg4"](), stored("cfg4")
-    g = GpuNet(net, 0, calib, images=8)
+    g = GpuNet(net, 0, calib)
+    assert g.images == 128
     g.set_input()
     g.run()
-    want = ONet.run(net, 0, calib, images=2)
-    for name in net["buffers"]:
-        if name not in g.fused:
-            assert (g.buf[name][:2].cpu().numpy() == want[name]).all(), name
+    x = W.input_tensor(net, 0)
+    for img in (0, 77, 127):
+        want = ONet.run(net, 0, calib, images=1, x_raw=np.ascontiguousarray(x[img:img + 1]))
+        for name in net["buffers"]:
+            if name in g.fused:
+                continue
+            got = g.buf[name][img:img + 1].cpu().numpy()
+            assert (got == want[name]).all(), (img, name)
+    assert len(g.fused) == 4
+    assert g.result("logits").shape == (128, 1, 1, 1000)
