@@ -8,6 +8,8 @@ Prints one JSON line on stdout; per-layer detail goes to stderr and, with
 --layers-json PATH, to that file.
 """
 import argparse
+import glob
+import hashlib
 import json
 import os
 import sys
@@ -82,68 +84,173 @@ def cpu_baseline(net, calib, seed, budget_s=20.0):
                 k, n_all, passes, "" if passes == 1 else "es", dt)}
 
 
-def _time_us(torch, fn, reps=20):
-    for _ in range(3):
-        fn()
+def csrc_digest():
+    """Hash of the kernel sources: a byte-counter summary under profiles/ is only valid for the build it was taken on."""
+    h = hashlib.sha256()
+    for path in sorted(glob.glob(os.path.join(ROOT, "paper_2006_11735_amd", "csrc", "*"))):
+        h.update(os.path.basename(path).encode())
+        h.update(open(path, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def _time_us(torch, fns, reps=20):
+    """Average duration of a call.  fns: one callable, or several that are called in turn (the same kernel on
+    different buffers, so that no call finds its operands in the 256 MB last-level cache)."""
+    if callable(fns):
+        fns = [fns]
+    for f in fns[:3]:
+        f()
+    reps = max(reps, len(fns))
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
     e0.record()
-    for _ in range(reps):
-        fn()
+    for i in range(reps):
+        fns[i % len(fns)]()
     e1.record()
     torch.cuda.synchronize()
     return e0.elapsed_time(e1) / reps * 1e3
 
 
-def add_bandwidth(torch):
-    """Achieved HBM bandwidth of the stand-alone rescaled addition (3 and 6 bytes per element)."""
+COLD_BYTES = 1.5e9      # buffer sets a cold measurement rotates over: well beyond the 256 MB last-level cache
+
+
+def _sets(bytes_per_set):
+    return max(2, int(COLD_BYTES // bytes_per_set) + 1)
+
+
+def measured_peaks(torch):
+    """The two roofs as this machine delivers them: a register-only loop of the int8 matrix instruction and a
+    streaming device copy of 1 GiB (read + written bytes over time)."""
+    from paper_2006_11735_amd import binding as B
+    blocks, iters = 256 * 8, 4000
+    sink = torch.empty(blocks * 256, dtype=torch.int32, device="cuda")
+    us = _time_us(torch, lambda: B.icnn_peak_mfma_i8(blocks, iters, sink), reps=5)
+    tops = blocks * 4 * iters * 8 * 65536 / us / 1e6
+    n = 1 << 30
+    src = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+    us_c = _time_us(torch, lambda: B.icnn_peak_copy(src, dst, n), reps=5)
+    gbs = 2 * n / us_c / 1e3
+    log("measured roofs: int8 MFMA loop %.0f TOP/s (%.1f%% of nominal), 1 GiB copy %.0f GB/s (%.1f%% of nominal)" % (
+        tops, 100 * tops / INT8_MFMA_PEAK_TOPS, gbs, 100 * gbs / HBM_PEAK_GBS))
+    del src, dst
+    return tops, gbs
+
+
+def add_bandwidth(torch, copy_gbs):
+    """Achieved bandwidth of the stand-alone rescaled addition (3 and 6 bytes per element): cold = every call on
+    buffers no earlier call left in the last-level cache (the HBM figure); warm = one buffer set back to back."""
     from paper_2006_11735_amd import binding as B
     px, c = 64 * 56 * 56, 256
     out = {}
     for name, a_dt, a_torch, bytes_per in (("u8+u8->u8", B.ICNN_U8, torch.uint8, 3), ("s32+u8->u8", B.ICNN_S32, torch.int32, 6)):
-        a = torch.randint(0, 100, (px, c), device="cuda").to(a_torch)
-        b = torch.randint(0, 127, (px, c), device="cuda").to(torch.uint8)
-        o = torch.empty((px, c), dtype=torch.uint8, device="cuda")
         d = B.add_desc(count_pixels=px, c=c, a_c_stride=c, b_c_stride=c, out_c_stride=c, a_dtype=a_dt,
                        b_dtype=B.ICNN_U8, b_mul=18415, b_shift=5 if a_dt == B.ICNN_S32 else 14, mul=23187,
                        shift=24 if a_dt == B.ICNN_S32 else 15, lo=0, hi=127)   # 8-bit maps: ratios near 1; accumulators: << 1
-        us = _time_us(torch, lambda: B.iadd_rescale(d, a, b, o))
-        gbs = px * c * bytes_per / us / 1e3
-        out[name] = {"elements": px * c, "us": us, "achieved_gbs": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
-        log("iadd_rescale %-11s %d elements: %.1f us, %.0f GB/s (%.0f%% of %d GB/s)" % (
-            name, px * c, us, gbs, 100 * gbs / HBM_PEAK_GBS, HBM_PEAK_GBS))
+        sets = []
+        for _ in range(_sets(px * c * bytes_per)):
+            a = torch.randint(0, 100, (px, c), device="cuda").to(a_torch)
+            b = torch.randint(0, 127, (px, c), device="cuda").to(torch.uint8)
+            o = torch.empty((px, c), dtype=torch.uint8, device="cuda")
+            sets.append((a, b, o))
+        fns = [(lambda t=t: B.iadd_rescale(d, t[0], t[1], t[2])) for t in sets]
+        us = _time_us(torch, fns, reps=3 * len(fns))
+        us_warm = _time_us(torch, fns[0])
+        gbs, gbs_warm = px * c * bytes_per / us / 1e3, px * c * bytes_per / us_warm / 1e3
+        out[name] = {"elements": px * c, "us": us, "achieved_gbs": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS,
+                     "frac_of_measured_copy": gbs / copy_gbs, "buffer_sets": len(fns),
+                     "warm_us": us_warm, "warm_gbs_cache_assisted": gbs_warm}
+        log("iadd_rescale %-11s %d elements: cold %.1f us, %.0f GB/s (%.0f%% of %d GB/s, %.0f%% of the measured copy); "
+            "warm (cache-assisted) %.1f us, %.0f GB/s" % (name, px * c, us, gbs, 100 * gbs / HBM_PEAK_GBS, HBM_PEAK_GBS,
+                                                         100 * gbs / copy_gbs, us_warm, gbs_warm))
+        del sets, fns
     return out
 
 
-def other_bandwidth(torch):
-    """Achieved HBM bandwidth (algorithmic bytes / time) of the remaining memory-bound kernels, at the
-    sizes they have in the workloads."""
+def other_bandwidth(torch, copy_gbs):
+    """Achieved bandwidth (algorithmic bytes / time) of the remaining memory-bound kernels at the sizes they have in
+    the workloads, cold (rotating over buffer sets larger than the last-level cache) and warm."""
     from paper_2006_11735_amd import binding as B
     out = {}
 
-    def report(name, byts, us):
+    def report(name, byts, make):
+        sets = [make() for _ in range(_sets(byts))]
+        fns = [s_ for s_ in sets]
+        us = _time_us(torch, fns, reps=3 * len(fns))
+        us_warm = _time_us(torch, fns[0])
         gbs = byts / us / 1e3
-        out[name] = {"algorithmic_bytes": byts, "us": us, "achieved_gbs": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
-        log("%-38s %6.1f MB: %6.1f us, %5.0f GB/s (%.0f%% of %d GB/s)" % (name, byts / 1e6, us, gbs, 100 * gbs / HBM_PEAK_GBS,
-                                                                          HBM_PEAK_GBS))
-    x = torch.randint(0, 128, (64, 112, 112, 64), device="cuda").to(torch.uint8)
-    o = torch.empty((64, 56, 56, 64), dtype=torch.uint8, device="cuda")
-    report("imaxpool2d_u8 64x112x112x64 3x3/2", x.numel() + o.numel(),
-           _time_us(torch, lambda: B.imaxpool2d_u8(64, 112, 112, 64, 3, 2, 1, x, o)))
-    x = torch.randint(0, 128, (64, 7, 7, 2048), device="cuda").to(torch.uint8)
-    o = torch.empty((64, 1, 1, 2048), dtype=torch.uint8, device="cuda")
-    report("iavgpool_global_u8 64x7x7x2048", x.numel() + o.numel(),
-           _time_us(torch, lambda: B.iavgpool_global_u8(64, 7, 7, 2048, 21400, 20, 127, x, o)))
+        out[name] = {"algorithmic_bytes": byts, "us": us, "achieved_gbs": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS,
+                     "frac_of_measured_copy": gbs / copy_gbs, "buffer_sets": len(fns), "warm_us": us_warm,
+                     "warm_gbs_cache_assisted": byts / us_warm / 1e3}
+        log("%-38s %6.1f MB: cold %6.1f us, %5.0f GB/s (%.0f%% of %d GB/s, %.0f%% of the measured copy); warm %6.1f us" % (
+            name, byts / 1e6, us, gbs, 100 * gbs / HBM_PEAK_GBS, HBM_PEAK_GBS, 100 * gbs / copy_gbs, us_warm))
+
+    def maxpool():
+        x = torch.randint(0, 128, (64, 112, 112, 64), device="cuda").to(torch.uint8)
+        o = torch.empty((64, 56, 56, 64), dtype=torch.uint8, device="cuda")
+        return lambda: B.imaxpool2d_u8(64, 112, 112, 64, 3, 2, 1, x, o)
+    report("imaxpool2d_u8 64x112x112x64 3x3/2", 64 * 112 * 112 * 64 + 64 * 56 * 56 * 64, maxpool)
+
+    def avgpool():
+        x = torch.randint(0, 128, (64, 7, 7, 2048), device="cuda").to(torch.uint8)
+        o = torch.empty((64, 1, 1, 2048), dtype=torch.uint8, device="cuda")
+        return lambda: B.iavgpool_global_u8(64, 7, 7, 2048, 21400, 20, 127, x, o)
+    report("iavgpool_global_u8 64x7x7x2048", 64 * 49 * 2048 + 64 * 2048, avgpool)
     px = 720 * 1280
-    a = torch.randint(0, 128, (px, 32), device="cuda").to(torch.uint8)
-    b = torch.randint(0, 128, (px, 16), device="cuda").to(torch.uint8)
-    o = torch.empty((px, 48), dtype=torch.uint8, device="cuda")
-    report("iconcat 720x1280 32+16 channels", 2 * px * 48,
-           _time_us(torch, lambda: B.iconcat([a, b], [32, 16], [32, 16], [20000, 23000], [15, 15], 127, px, o, 48)))
-    n = 64 * 224 * 224 * 3
-    x = torch.randint(0, 256, (n,), device="cuda").to(torch.uint8)
-    o = torch.empty_like(x)
-    report("irenormalize_u8 64x224x224x3", 2 * n, _time_us(torch, lambda: B.irenormalize_u8(n, x, o)))
+
+    def concat():
+        a = torch.randint(0, 128, (px, 32), device="cuda").to(torch.uint8)
+        b = torch.randint(0, 128, (px, 16), device="cuda").to(torch.uint8)
+        o = torch.empty((px, 48), dtype=torch.uint8, device="cuda")
+        return lambda: B.iconcat([a, b], [32, 16], [32, 16], [20000, 23000], [15, 15], 127, px, o, 48)
+    report("iconcat 720x1280 32+16 channels", 2 * px * 48, concat)
+    for label, n in (("64x224x224x3", 64 * 224 * 224 * 3), ("128x224x224x3 x4 (77 MB)", 4 * 128 * 224 * 224 * 3)):
+        def renorm():
+            x = torch.randint(0, 256, (n,), device="cuda").to(torch.uint8)
+            o = torch.empty_like(x)
+            return lambda: B.irenormalize_u8(n, x, o)
+        report("irenormalize_u8 " + label, 2 * n, renorm)
     return out
+
+
+def summarise_pmc(config, fetch_csv, write_csv):
+    """HBM bytes per conv launch from two rocprofv3 --pmc runs.  The counters are in KiB per dispatch; each is scaled
+    by what it reads for stream_copy_kernel on 256 MiB (262144 KiB read, 262144 KiB written)."""
+    import collections
+    import csv
+
+    def load(path):
+        agg = collections.defaultdict(list)
+        for r in csv.DictReader(open(path)):
+            agg[r["Kernel_Name"].split("(")[0]].append(float(r["Counter_Value"]))
+        return agg
+    f, w = load(fetch_csv), load(write_csv)
+    scale = {}
+    for name, agg in (("fetch", f), ("write", w)):
+        ref = [v for k, vs in agg.items() if "stream_copy_kernel" in k for v in vs]
+        if not ref:
+            sys.exit("no stream_copy_kernel dispatch in the %s run: was --copy-calibration given?" % name)
+        scale[name] = 262144.0 / (sum(ref) / len(ref))
+    per_pass = {k: len(v) for k, v in f.items() if "maxpool" in k or "avgpool" in k}
+    passes = min(per_pass.values()) if per_pass else 1
+    # launches outside the passes (the fused block's warm-up launch at set-up) come first: drop them
+    for agg in (f, w):
+        for k in list(agg):
+            if "conv_" in k and len(agg[k]) % passes:
+                agg[k] = agg[k][len(agg[k]) % passes:]
+    conv_f = sum(sum(v) for k, v in f.items() if "conv_" in k)
+    conv_w = sum(sum(v) for k, v in w.items() if "conv_" in k)
+    n_f = sum(len(v) for k, v in f.items() if "conv_" in k)
+    rd, wr = conv_f * 1024 * scale["fetch"] / passes, conv_w * 1024 * scale["write"] / passes
+    out = {"conv_hbm_bytes_per_launch": (rd + wr) / (n_f / passes), "conv_hbm_read_bytes_per_step": rd,
+           "conv_hbm_write_bytes_per_step": wr, "conv_launches_per_step": n_f / passes,
+           "fetch_size_scale": scale["fetch"], "write_size_scale": scale["write"], "csrc_digest": csrc_digest(),
+           "kernels_kib_per_dispatch": {k: [len(f[k]), sum(f[k]) / len(f[k]), sum(w.get(k, [0])) / max(1, len(w.get(k, [0])))]
+                                        for k in sorted(f) if any(t in k for t in ("conv_", "pool", "pad_", "stream_copy"))}}
+    path = os.path.join(ROOT, "profiles", "traffic_%s.json" % config)
+    json.dump(out, open(path, "w"), indent=1)
+    print(json.dumps(out, indent=1))
+    print("written", path)
 
 
 def main():
@@ -160,8 +267,13 @@ def main():
     ap.add_argument("--main-only", action="store_true",
                     help="skip the per-channel variant and the stand-alone bandwidth kernels (clean kernel traces)")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run three plain 256 MiB device copies (reference for rocprofv3 byte counters)")
+                    help="also run three plain 256 MiB device copies (stream_copy_kernel: reference for rocprofv3 byte counters)")
+    ap.add_argument("--summarise-pmc", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"), default=None,
+                    help="no GPU work: turn the counter_collection.csv files of two rocprofv3 --pmc runs of "
+                         "`bench.py --copy-calibration --main-only` (FETCH_SIZE, then WRITE_SIZE) into profiles/traffic_<config>.json")
     args = ap.parse_args()
+    if args.summarise_pmc:
+        return summarise_pmc(args.config, *args.summarise_pmc)
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
 
@@ -185,10 +297,11 @@ def main():
     torch.cuda.synchronize()
 
     if args.copy_calibration:
+        from paper_2006_11735_amd import binding as B
         src = torch.zeros(1 << 28, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(src)
+            B.icnn_peak_copy(src, dst, 1 << 28)
         torch.cuda.synchronize()
         del src, dst
 
@@ -252,10 +365,16 @@ def main():
     log("conv launches: %d, %.3f ms per step (events, excess %.2f us/launch removed; whole step %.3f ms wall), %.1f TOP/s" % (
         n_conv, conv_ms, excess * 1e3, ms_per_step, conv_tops))
 
-    traffic = None
+    traffic, traffic_stale = None, None
     tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % args.config)
     if os.path.exists(tpath):          # HBM bytes per conv launch from the committed rocprofv3 --pmc summary
-        traffic = json.load(open(tpath)).get("conv_hbm_bytes_per_launch")
+        tj = json.load(open(tpath))
+        traffic = tj.get("conv_hbm_bytes_per_launch")
+        traffic_stale = tj.get("csrc_digest") != csrc_digest()     # counters were taken on other kernel sources
+        if traffic_stale:
+            log("note: %s was measured on other kernel sources than this build (traffic_stale)" % tpath)
+
+    peak_tops, copy_gbs = measured_peaks(torch)
 
     result = {
         "metric": "images/s ResNet-50-shaped b64 (int8 conv TOPS and % of int8 MFMA peak alongside)" if args.config == "cfg3"
@@ -273,7 +392,8 @@ def main():
         "whole_step_tops": conv_ops / (ms_per_step * 1e-3) / 1e12,
         "roofline": {"kernel": "conv kernels (all %d conv launches of a step: conv_dlds / conv_halo / conv_dual / conv_greg, every tile shape)" % n_conv,
                      "bound": "mfma", "achieved": conv_tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": conv_tops / INT8_MFMA_PEAK_TOPS, "traffic": traffic,
+                     "frac": conv_tops / INT8_MFMA_PEAK_TOPS, "traffic": traffic, "traffic_stale": traffic_stale,
+                     "peak_measured": peak_tops, "frac_of_peak_measured": conv_tops / peak_tops,
                      "launches_per_step": n_conv, "avg_launch_us": conv_ms * 1e3 / n_conv,
                      "algorithmic_gop_per_step": conv_ops / 1e9,
                      "algorithmic_gb_per_step": conv_bytes / 1e9},
@@ -297,9 +417,12 @@ def main():
                                          "note": "iconv2d_brelu_pc on every BReLU layer, iconv2d_dual_brelu_pc on the four projection blocks"}
         log("per-channel variant: %.3f ms per step (%d launches)" % (ms_pc, len(g_pc.steps)))
         del g_pc
+    result["hbm_copy_measured_gbs"] = copy_gbs
     if not args.main_only:
-        result["iadd_rescale"] = add_bandwidth(torch)
-        result["bandwidth_kernels"] = other_bandwidth(torch)
+        del g
+        torch.cuda.empty_cache()
+        result["iadd_rescale"] = add_bandwidth(torch, copy_gbs)
+        result["bandwidth_kernels"] = other_bandwidth(torch, copy_gbs)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(net, calib, seed)
     if args.layers_json:

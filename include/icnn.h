@@ -119,6 +119,18 @@ int icnn_version(void);
  * is owned by the library and valid until the thread's next failing call. */
 const char *icnn_last_error(void);
 
+/* Kernel-selection override, for sweeps and for tests that must reach a kernel the library would not pick
+ * for a small shape.  It changes which kernel computes a layer, never a result.  Process-wide, not
+ * synchronised: set it while no other thread is inside the library.  `name` (host string) and the values it takes:
+ *   "tile"        -1 library's choice; 0..4 force that tile shape of the tap-by-tap convolution kernel
+ *   "stages"      0 library's choice; 2..6 LDS ring depth of that kernel
+ *   "no_narrow", "no_fc", "no_halo", "no_stream"   1 keeps layers off the respective special kernel
+ *   "halo_tile"   0 library's choice; 1 = 128 x 128, 2 = 64 x 256 tiles of the patch-resident 3x3 kernel
+ *   "halo_always" 1 lets the patch-resident kernel take layers with several tiles per workgroup
+ *   "reset"       (value ignored) back to the library's choices
+ * Unknown names and values outside these ranges return ICNN_E_PARAM and change nothing. */
+int icnn_set_tuning(const char *name, int32_t value);
+
 /* Host-only check of a descriptor: the same validation iconv2d_brelu performs,
  * without touching the GPU.  Rejects, among others, kh*kw*cin > 65535 (beyond it
  * the int32 accumulator is no longer provably safe) and unsigned inputs combined
@@ -273,6 +285,18 @@ int iavgpool_global_u8(int32_t n, int32_t h, int32_t w, int32_t c, int32_t mul,
  * out[i] = x[i] - 128 stored as int8.  `count` elements; in place is allowed.
  * (iconv2d_brelu can do the same on the fly with in_sub128 = 1.) */
 int irenormalize_u8(int64_t count, const void *x, void *out, void *stream);
+
+/*
+ * Measurement aids: the two roofs a convolution layer is judged against, as they are on the machine at hand
+ * (nothing of the method is computed).  The caller times the launches.
+ * icnn_peak_mfma_i8: `blocks` workgroups of four waves, each wave issuing iters * 8 register-only
+ *   v_mfma_i32_32x32x32_i8 (65536 integer operations each): blocks * 4 * iters * 8 * 65536 operations in all.
+ *   sink: device, blocks * 256 int32, overwritten.
+ * icnn_peak_copy: dst[i] = src[i] over `bytes` bytes (device, 16-byte aligned, a multiple of 16; the ranges must
+ *   not overlap): bytes read plus bytes written.
+ */
+int icnn_peak_mfma_i8(int32_t blocks, int32_t iters, void *sink, void *stream);
+int icnn_peak_copy(const void *src, void *dst, size_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -48,6 +48,7 @@ _lib = C.CDLL(LIB_PATH)
 _vp, _i32, _i64 = C.c_void_p, C.c_int32, C.c_int64
 _lib.icnn_version.restype = C.c_int
 _lib.icnn_last_error.restype = C.c_char_p
+_lib.icnn_set_tuning.argtypes = [C.c_char_p, _i32]
 _lib.iconv2d_validate.argtypes = [C.POINTER(icnn_conv_desc)]
 _lib.iconv2d_out_hw.argtypes = [C.POINTER(icnn_conv_desc), C.POINTER(_i32), C.POINTER(_i32)]
 _lib.iconv2d_workspace_bytes.argtypes = [C.POINTER(icnn_conv_desc), C.POINTER(C.c_size_t)]
@@ -67,12 +68,14 @@ _lib.iconcat.argtypes = [_i32, C.POINTER(_vp), C.POINTER(_i32), C.POINTER(_i32),
 _lib.imaxpool2d_u8.argtypes = [_i32] * 7 + [_vp, _vp, _vp]
 _lib.iavgpool_global_u8.argtypes = [_i32] * 7 + [_vp, _vp, _vp]
 _lib.irenormalize_u8.argtypes = [_i64, _vp, _vp, _vp]
+_lib.icnn_peak_mfma_i8.argtypes = [_i32, _i32, _vp, _vp]
+_lib.icnn_peak_copy.argtypes = [_vp, _vp, C.c_size_t, _vp]
 
-EXPORTS = ["icnn_version", "icnn_last_error", "iconv2d_validate", "iconv2d_out_hw",
+EXPORTS = ["icnn_version", "icnn_last_error", "icnn_set_tuning", "iconv2d_validate", "iconv2d_out_hw",
            "iconv2d_workspace_bytes", "iconv2d_packed_weight_bytes", "iconv2d_prepack_weights",
            "iconv2d_brelu", "iconv2d_packed_channel_params_bytes", "iconv2d_prepack_channel_params", "iconv2d_brelu_pc",
            "iconv2d_dual_brelu", "iconv2d_dual_brelu_pc", "iadd_rescale", "iconcat", "imaxpool2d_u8", "iavgpool_global_u8",
-           "irenormalize_u8"]
+           "irenormalize_u8", "icnn_peak_mfma_i8", "icnn_peak_copy"]
 
 
 def _ptr(t):
@@ -105,6 +108,10 @@ def icnn_version():
 
 def icnn_last_error():
     return _lib.icnn_last_error().decode()
+
+
+def icnn_set_tuning(name, value=0):
+    return _check(_lib.icnn_set_tuning(name.encode(), int(value)))
 
 
 def conv_desc(**kw):
@@ -219,3 +226,11 @@ def iavgpool_global_u8(n, h, w, c, mul, shift, bound_q, x, out, stream=None):
 
 def irenormalize_u8(count, x, out, stream=None):
     return _check(_lib.irenormalize_u8(count, _ptr(x), _ptr(out), _stream(stream)))
+
+
+def icnn_peak_mfma_i8(blocks, iters, sink, stream=None):
+    return _check(_lib.icnn_peak_mfma_i8(int(blocks), int(iters), _ptr(sink), _stream(stream)))
+
+
+def icnn_peak_copy(src, dst, nbytes, stream=None):
+    return _check(_lib.icnn_peak_copy(_ptr(src), _ptr(dst), int(nbytes), _stream(stream)))

@@ -4,8 +4,13 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstring>
 
 using namespace icnn;
+
+namespace icnn {
+Tuning g_tuning;
+}
 
 namespace {
 
@@ -124,6 +129,30 @@ extern "C" {
 int icnn_version(void) { return 100; }
 
 const char *icnn_last_error(void) { return g_err; }
+
+int icnn_set_tuning(const char *name, int32_t value)
+{
+    if (!name) return fail(ICNN_E_NULL, "tuning name is NULL");
+    struct Entry { const char *name; int Tuning::*field; int lo, hi; };
+    static const Entry table[] = {
+        {"tile", &Tuning::tile, -1, 4},         {"stages", &Tuning::stages, 0, 6},
+        {"no_narrow", &Tuning::no_narrow, 0, 1}, {"no_fc", &Tuning::no_fc, 0, 1},
+        {"no_halo", &Tuning::no_halo, 0, 1},     {"halo_tile", &Tuning::halo_tile, 0, 2},
+        {"halo_always", &Tuning::halo_always, 0, 1}, {"no_stream", &Tuning::no_stream, 0, 1},
+    };
+    if (!strcmp(name, "reset")) {
+        g_tuning = Tuning();
+        return ICNN_OK;
+    }
+    for (const Entry &e : table)
+        if (!strcmp(name, e.name)) {
+            if (value < e.lo || value > e.hi || (e.field == &Tuning::stages && value == 1))
+                return fail(ICNN_E_PARAM, "tuning %s = %d outside [%d, %d]", name, value, e.lo, e.hi);
+            g_tuning.*(e.field) = value;
+            return ICNN_OK;
+        }
+    return fail(ICNN_E_PARAM, "unknown tuning name %s", name);
+}
 
 int iconv2d_validate(const icnn_conv_desc *desc) { return check_conv(desc, nullptr); }
 
@@ -367,10 +396,11 @@ static int dual_layer(const icnn_conv_desc *m, const void *x_main, const void *w
     }
     if (!aligned16(x_main) || !aligned16(x_proj) || !aligned16(y))
         return fail(ICNN_E_UNSUPPORTED, "fused block needs 16-byte aligned tensors");
-    // |Y_proj| <= Kp*128*127 + 2^28, |Y_main| <= Km*128*127 + 2^28 under the bias contract
+    // |Y_proj| <= Kp*128*128 + 2^28, |Y_main| <= Km*128*128 + 2^28 under the bias contract (int8 inputs and
+    // weights may both be -128)
     {
-        const long long yp = (long long)gp.K * 128 * 127 + (1LL << 28);
-        const long long ym = (long long)gm.K * 128 * 127 + (1LL << 28);
+        const long long yp = (long long)gp.K * 128 * 128 + (1LL << 28);
+        const long long ym = (long long)gm.K * 128 * 128 + (1LL << 28);
         const __int128 s_max = (((__int128)yp * m->res_mul) >> m->res_shift) + 2;
         if (s_max + ym > 0x7fffffffLL)
             return fail(ICNN_E_UNSUPPORTED, "cannot prove that the merged sum stays inside int32 for these sizes");
@@ -550,6 +580,22 @@ int irenormalize_u8(int64_t count, const void *x, void *out, void *stream)
     const bool vec = count % 16 == 0 && aligned16(x) && aligned16(out);
     return launched(launch_renorm((const uint8_t *)x, (uint8_t *)out, count, vec, (hipStream_t)stream),
                     "irenormalize_u8");
+}
+
+int icnn_peak_mfma_i8(int32_t blocks, int32_t iters, void *sink, void *stream)
+{
+    if (blocks < 1 || blocks > (1 << 20) || iters < 1) return fail(ICNN_E_SHAPE, "blocks must be in [1, 2^20] and iters >= 1");
+    if (!sink) return fail(ICNN_E_NULL, "sink is NULL");
+    if ((uintptr_t)sink & 3) return fail(ICNN_E_ALIGN, "sink must be 4-byte aligned");
+    return launched(launch_mfma_loop(blocks, iters, (int *)sink, (hipStream_t)stream), "icnn_peak_mfma_i8");
+}
+
+int icnn_peak_copy(const void *src, void *dst, size_t bytes, void *stream)
+{
+    if (bytes == 0) return ICNN_OK;
+    if (!src || !dst) return fail(ICNN_E_NULL, "src and dst must not be NULL");
+    if (!aligned16(src) || !aligned16(dst) || bytes % 16) return fail(ICNN_E_ALIGN, "src, dst and bytes must be multiples of 16");
+    return launched(launch_stream_copy(src, dst, (long long)(bytes / 16), (hipStream_t)stream), "icnn_peak_copy");
 }
 
 }  // extern "C"
