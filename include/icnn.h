@@ -165,6 +165,21 @@ int iconv2d_brelu(const icnn_conv_desc *desc, const void *x, const void *w_packe
                   void *stream);
 
 /*
+ * iconv2d_brelu for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and error codes as
+ * iconv2d_brelu, without `workspace`: layers that need one (iconv2d_workspace_bytes > 0, i.e. cin <= 4) keep their
+ * padded copy of x in a fixed array of ICNN_STATIC_WORKSPACE_BYTES bytes of device memory that the library's code
+ * object carries (each GPU the library runs on holds its own copy until the process ends).  A layer that needs more
+ * returns ICNN_E_SHAPE having launched nothing.  The call allocates and frees nothing, on the host or the device.
+ * Nothing in the array has to start at zero (every byte a layer reads it has written in the same call), but all
+ * calls on one GPU share it: calls that may overlap in time on one GPU (different streams, different threads)
+ * race on it and must be serialised by the caller.
+ */
+#define ICNN_STATIC_WORKSPACE_BYTES (16u << 20)
+int iconv2d_brelu_static_ws(const icnn_conv_desc *desc, const void *x, const void *w_packed,
+                            const int32_t *bias, const void *res, void *y, void *stream);
+
+/*
  * Per-output-channel requantisation (Section 3.4.3: with one weight step per output channel
  * before batch normalisation is merged, every output channel has its own ratio, so the
  * multiplier and shift of the requantisation equation of Section 3.2.1, and of the skip

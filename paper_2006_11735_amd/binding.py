@@ -55,6 +55,7 @@ _lib.iconv2d_workspace_bytes.argtypes = [C.POINTER(icnn_conv_desc), C.POINTER(C.
 _lib.iconv2d_packed_weight_bytes.argtypes = [C.POINTER(icnn_conv_desc), C.POINTER(C.c_size_t)]
 _lib.iconv2d_prepack_weights.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp]
 _lib.iconv2d_brelu.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.iconv2d_brelu_static_ws.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.iconv2d_packed_channel_params_bytes.argtypes = [C.POINTER(icnn_conv_desc), C.POINTER(C.c_size_t)]
 _lib.iconv2d_prepack_channel_params.argtypes = [C.POINTER(icnn_conv_desc), C.POINTER(icnn_channel_params), _vp, _vp]
 _lib.iconv2d_brelu_pc.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
@@ -73,7 +74,7 @@ _lib.icnn_peak_copy.argtypes = [_vp, _vp, C.c_size_t, _vp]
 
 EXPORTS = ["icnn_version", "icnn_last_error", "icnn_set_tuning", "iconv2d_validate", "iconv2d_out_hw",
            "iconv2d_workspace_bytes", "iconv2d_packed_weight_bytes", "iconv2d_prepack_weights",
-           "iconv2d_brelu", "iconv2d_packed_channel_params_bytes", "iconv2d_prepack_channel_params", "iconv2d_brelu_pc",
+           "iconv2d_brelu", "iconv2d_brelu_static_ws", "iconv2d_packed_channel_params_bytes", "iconv2d_prepack_channel_params", "iconv2d_brelu_pc",
            "iconv2d_dual_brelu", "iconv2d_dual_brelu_pc", "iadd_rescale", "iconcat", "imaxpool2d_u8", "iavgpool_global_u8",
            "irenormalize_u8", "icnn_peak_mfma_i8", "icnn_peak_copy"]
 
@@ -166,6 +167,14 @@ def iconv2d_prepack_weights(desc, w_ohwi, w_packed, stream=None):
 def iconv2d_brelu(desc, x, w_packed, bias, res, y, workspace=None, stream=None):
     return _check(_lib.iconv2d_brelu(C.byref(desc), _ptr(x), _ptr(w_packed), _ptr(bias), _ptr(res),
                                      _ptr(y), _ptr(workspace), _stream(stream)))
+
+
+ICNN_STATIC_WORKSPACE_BYTES = 16 << 20
+
+
+def iconv2d_brelu_static_ws(desc, x, w_packed, bias, res, y, stream=None):
+    return _check(_lib.iconv2d_brelu_static_ws(C.byref(desc), _ptr(x), _ptr(w_packed), _ptr(bias), _ptr(res),
+                                               _ptr(y), _stream(stream)))
 
 
 def channel_params(mul=None, shift=None, res_mul=None, res_shift=None):

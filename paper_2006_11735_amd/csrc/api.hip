@@ -5,6 +5,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 using namespace icnn;
 
@@ -332,6 +333,49 @@ int iconv2d_brelu(const icnn_conv_desc *d, const void *x, const void *w_packed, 
                   const void *res, void *y, void *workspace, void *stream)
 {
     return conv_layer(d, x, w_packed, bias, nullptr, res, y, workspace, stream, "iconv2d_brelu");
+}
+
+// ---- iconv2d_brelu for callers that cannot allocate: the workspace is a fixed array in device memory that the
+// code object itself carries (every GPU the library runs on holds its own copy until the process ends).
+constexpr size_t kStaticWsBytes = ICNN_STATIC_WORKSPACE_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticWsBytes];
+
+// In host code `scratch` is only a handle for the symbol, not a device address: the address on the current
+// device is asked for once per device and kept; kernels and copies only ever get that pointer.
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_lock;
+
+static int static_workspace(void **ptr)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(ICNN_E_LAUNCH, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(ICNN_E_UNSUPPORTED, "device index %d beyond %d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> g(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(ICNN_E_LAUNCH, "hipGetSymbolAddress(static workspace): %s", hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return ICNN_OK;
+}
+
+int iconv2d_brelu_static_ws(const icnn_conv_desc *d, const void *x, const void *w_packed, const int32_t *bias,
+                            const void *res, void *y, void *stream)
+{
+    ConvGeom g;
+    int rc = check_conv(d, &g);
+    if (rc) return rc;
+    if (g.ws_bytes > kStaticWsBytes)
+        return fail(ICNN_E_SHAPE, "this layer needs a workspace of %zu bytes; the static one holds %zu (use iconv2d_brelu)",
+                    g.ws_bytes, kStaticWsBytes);
+    void *ws = nullptr;
+    if (g.ws_bytes && (rc = static_workspace(&ws))) return rc;
+    return conv_layer(d, x, w_packed, bias, nullptr, res, y, ws, stream, "iconv2d_brelu_static_ws");
 }
 
 int iconv2d_packed_channel_params_bytes(const icnn_conv_desc *d, size_t *bytes)
