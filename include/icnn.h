@@ -251,6 +251,26 @@ int iconv2d_dual_brelu_pc(const icnn_conv_desc *main_desc, const void *x_main,
                           const int32_t *bias_proj, void *y, void *stream);
 
 /*
+ * A whole identity bottleneck block of a residual network as one launch (Section 4.1: the block's layers with the
+ * skip connection joining the last one before BReLU; Section 3.1 for each layer).  Result: exactly that of
+ *     iconv2d_brelu(c1, x,  w1_packed, bias1, NULL, t1, ...);     // 1x1, stride 1, no padding
+ *     iconv2d_brelu(c2, t1, w2_packed, bias2, NULL, t2, ...);     // 3x3, stride 1, padding 1
+ *     iconv2d_brelu(c3, t2, w3_packed, bias3, res,  y,  ...);     // 1x1; res: usually x itself
+ * without the middle tensors t1 and t2 ever existing in memory (every workgroup takes a spatial tile of the image
+ * through all three layers and recomputes the 3x3 layer's one-pixel halo of t1).  c1 and c2 must store unsigned
+ * bytes bounded by at most 127 (ICNN_OUT_BRELU_U8 or ICNN_OUT_CLAMP_U8) and take no skip operand; c3 may use any
+ * output mode and skip mode.  Shapes it takes: c1->cout = c2->cin = c2->cout = c3->cin in {64, 128}; c1->cin a
+ * multiple of 64 (at most 832 for a middle width of 64, 512 for 128); c3->cout a multiple of the middle width; all
+ * strides 1; inputs ICNN_IN_U8_LE127; x, y, res and their pitches 16-byte aligned.  The descriptors' pitches and
+ * offsets for t1 and t2 (c1->out_*, c2->in_c_stride, c2->out_*, c3->in_c_stride) are not used.  Anything else
+ * returns ICNN_E_UNSUPPORTED having launched nothing, and the caller issues the three layers separately.
+ */
+int iconv2d_bottleneck_brelu(const icnn_conv_desc *c1, const void *x, const void *w1_packed, const int32_t *bias1,
+                             const icnn_conv_desc *c2, const void *w2_packed, const int32_t *bias2,
+                             const icnn_conv_desc *c3, const void *w3_packed, const int32_t *bias3, const void *res,
+                             void *y, void *stream);
+
+/*
  * Rescaled feature-map addition (ratio synchronisation between feature maps,
  * Sections 3.4.2 and 4.1), as a stand-alone pass over memory:
  *   T   = sat32(a + [b * b_mul / 2^b_shift])

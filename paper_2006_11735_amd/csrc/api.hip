@@ -491,6 +491,60 @@ int iconv2d_dual_brelu_pc(const icnn_conv_desc *m, const void *x_main, const voi
                       "iconv2d_dual_brelu_pc");
 }
 
+int iconv2d_bottleneck_brelu(const icnn_conv_desc *c1, const void *x, const void *w1_packed, const int32_t *bias1,
+                             const icnn_conv_desc *c2, const void *w2_packed, const int32_t *bias2,
+                             const icnn_conv_desc *c3, const void *w3_packed, const int32_t *bias3, const void *res,
+                             void *y, void *stream)
+{
+    ConvGeom g1, g2, g3;
+    int rc = check_conv(c1, &g1);
+    if (rc) return rc;
+    if ((rc = check_conv(c2, &g2))) return rc;
+    if ((rc = check_conv(c3, &g3))) return rc;
+    const int mid = c1->cout, c = c1->cin;
+    const icnn_conv_desc *all[3] = {c1, c2, c3};
+    for (const icnn_conv_desc *d : all) {
+        if (d->n != c1->n || d->h != c1->h || d->w != c1->w)
+            return fail(ICNN_E_SHAPE, "the three layers of a block must share n, h, w");
+        if (d->in_signed != ICNN_IN_U8_LE127 || d->in_sub128)
+            return fail(ICNN_E_UNSUPPORTED, "fused block takes unsigned inputs up to 127 only");
+        if (d->stride_h != 1 || d->stride_w != 1) return fail(ICNN_E_UNSUPPORTED, "fused block needs stride 1");
+    }
+    if (c1->kh != 1 || c1->kw != 1 || c1->pad_h || c1->pad_w || c3->kh != 1 || c3->kw != 1 || c3->pad_h || c3->pad_w ||
+        c2->kh != 3 || c2->kw != 3 || c2->pad_h != 1 || c2->pad_w != 1)
+        return fail(ICNN_E_UNSUPPORTED, "fused block is 1x1, then 3x3 with padding 1, then 1x1");
+    if (c2->cin != mid || c2->cout != mid || c3->cin != mid)
+        return fail(ICNN_E_SHAPE, "the middle width of the three layers does not match");
+    for (const icnn_conv_desc *d : {c1, c2})
+        if ((d->out_mode != ICNN_OUT_BRELU_U8 && d->out_mode != ICNN_OUT_CLAMP_U8) || d->res_mode != ICNN_RES_NONE ||
+            (d->out_mode == ICNN_OUT_BRELU_U8 ? d->bound_q : d->hi) > 127)
+            return fail(ICNN_E_UNSUPPORTED, "the first two layers must store unsigned bytes up to 127 and take no skip operand");
+    if ((mid != 64 && mid != 128) || c % 64 != 0 || c3->cout % mid != 0 || c3->cout % 16 != 0)
+        return fail(ICNN_E_UNSUPPORTED, "fused block needs a middle width of 64 or 128, cin a multiple of 64 and cout a multiple of the middle width");
+    if (conv_block_lds_bytes(mid, c) > 160 * 1024)
+        return fail(ICNN_E_UNSUPPORTED, "the block's patch of %d input channels does not fit the on-chip memory", c);
+    if (!aligned16(x) || c1->in_c_stride % 16 != 0) return fail(ICNN_E_UNSUPPORTED, "fused block needs a 16-byte aligned input");
+    ConvArgs a1, a2, a3;
+    int32_t dummy = 0;         // the first two layers' outputs never reach memory
+    if ((rc = fill_conv_args(c1, g1, x, w1_packed, bias1, nullptr, &dummy, a1))) return rc;
+    if ((rc = fill_conv_args(c2, g2, x, w2_packed, bias2, nullptr, &dummy, a2))) return rc;
+    if ((rc = fill_conv_args(c3, g3, x, w3_packed, bias3, res, y, a3))) return rc;
+    if (!a3.epi_vec) return fail(ICNN_E_UNSUPPORTED, "fused block needs 16-byte aligned output and skip tensors");
+    if (!a1.vec_bias || !a2.vec_bias || !a3.vec_bias) return fail(ICNN_E_UNSUPPORTED, "fused block needs 16-byte aligned bias arrays");
+    if (a1.x_bytes >= 0x7fffff00u || a1.wp_bytes >= 0x7fffff00u || a2.wp_bytes >= 0x7fffff00u || a3.wp_bytes >= 0x7fffff00u)
+        return fail(ICNN_E_UNSUPPORTED, "fused block needs tensors below 2 GiB");
+    BlockArgs b;
+    b.x = (const uint8_t *)x; b.x_bytes = a1.x_bytes; b.x_cs = c1->in_c_stride;
+    b.N = c1->n; b.H = c1->h; b.W = c1->w;
+    if (!conv_block_tile(b.H, b.W, b)) return fail(ICNN_E_UNSUPPORTED, "no tile shape for this image");
+    const long long tiles = (long long)b.tiles_per_img * b.N;
+    if (tiles > 0x7fffffffLL || g1.M > 0x7fffffffLL) return fail(ICNN_E_SHAPE, "too many tiles");
+    b.n_tiles = (int)tiles;
+    b.k1 = c / 64;
+    b.nchunk3 = c3->cout / mid;
+    return launched(launch_conv_block(b, a1, a2, a3, (hipStream_t)stream), "iconv2d_bottleneck_brelu");
+}
+
 int iadd_rescale(const icnn_add_desc *d, const void *a, const void *b, void *out, void *stream)
 {
     if (!d) return fail(ICNN_E_NULL, "add descriptor is NULL");

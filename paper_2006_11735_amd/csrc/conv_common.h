@@ -85,6 +85,48 @@ __device__ __forceinline__ void shift_into_byte(int &w, uint32_t x, int sh_v, in
             : "+v"(w) : "v"(sh_v), "v"(x));
 }
 
+// Sixteen values t (bias and skip operand already in) -> sixteen requantised, clamped bytes as four words
+// (Section 3.2.1).  RQ as in epilogue_vec: 1 one 32x32->64 multiply-add whose high word is the result;
+// 2 general 64-bit multiply, add, shift; 3 in 32 bits after clamping t to [0, t_hi] (see ConvArgs::rq24).
+template <int RQ>
+__device__ __forceinline__ v4i requant16(const ConvArgs &a, const int (&t)[16])
+{
+    if (RQ == 3) {
+        // clamp, multiply-add, then the shift writes its byte of the output word: three instructions per value
+        int w[4];
+        const int sh_v = a.shift;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const uint32_t tc = (uint32_t)med3_v0s(t[r], a.t_hi);
+            const uint32_t x = __umul24(tc, (uint32_t)a.mul) + (uint32_t)a.rnd;
+            if ((r & 3) == 0) w[r >> 2] = (int)(x >> a.shift);
+            else shift_into_byte(w[r >> 2], x, sh_v, r & 3);
+        }
+        return v4i{w[0], w[1], w[2], w[3]};
+    }
+    int v[16];
+    const int lo_v = a.lo;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        if (RQ == 1) {
+            // [t * mul / 2^shift] = high word of t * (mul << (32 - shift)) + 2^31   (1 <= shift <= 32)
+            const int q = (int)(((int64_t)t[r] * a.mul_hi + 0x80000000LL) >> 32);
+            v[r] = med3_vvs(q, lo_v, a.hi);
+        } else {
+            v[r] = clampi64(rsr64((int64_t)t[r] * a.mul, a.shift), a.lo, a.hi);
+        }
+    }
+    return v4i{pack_low_bytes(v[0], v[1], v[2], v[3]), pack_low_bytes(v[4], v[5], v[6], v[7]),
+               pack_low_bytes(v[8], v[9], v[10], v[11]), pack_low_bytes(v[12], v[13], v[14], v[15])};
+}
+// the cheapest exact form the layer's parameters allow (wave-uniform choice)
+__device__ __forceinline__ v4i requant16_any(const ConvArgs &a, const int (&t)[16])
+{
+    if (a.rq24) return requant16<3>(a, t);
+    if (a.rq_fast) return requant16<1>(a, t);
+    return requant16<2>(a, t);
+}
+
 // vector path: all 16 channels valid, 16-byte aligned skip operand and output.
 // RES: 0 no skip operand; 1 unsigned 8-bit operand joined before requantisation with a rescale
 //      that fits 32 bits; 2 anything else (signed or int32 operand, wide multiplier, join after).
@@ -134,34 +176,16 @@ __device__ __forceinline__ void epilogue_vec(const ConvArgs &a, const v16i &acc,
         for (int q = 0; q < 4; ++q) op[q] = v4i{t[4 * q], t[4 * q + 1], t[4 * q + 2], t[4 * q + 3]};
         return;
     }
-    if (RQ == 3) {
-        // clamp, multiply-add, then the shift writes its byte of the output word: three instructions per value
-        int w[4];
-        const int sh_v = a.shift;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const uint32_t tc = (uint32_t)med3_v0s(t[r], a.t_hi);
-            const uint32_t x = __umul24(tc, (uint32_t)a.mul) + (uint32_t)a.rnd;
-            if ((r & 3) == 0) w[r >> 2] = (int)(x >> a.shift);
-            else shift_into_byte(w[r >> 2], x, sh_v, r & 3);
-        }
-        *(v4i *)((uint8_t *)a.out + oo) = v4i{w[0], w[1], w[2], w[3]};
+    if (RQ == 3 || (RQ == 1 && RES != 2)) {
+        *(v4i *)((uint8_t *)a.out + oo) = requant16<RQ>(a, t);
         return;
     }
     int v[16];
-    const int lo_v = a.lo;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-        if (RQ == 1 && !(RES == 2)) {
-            // [t * mul / 2^shift] = high word of t * (mul << (32 - shift)) + 2^31   (1 <= shift <= 32)
-            const int q = (int)(((int64_t)t[r] * a.mul_hi + 0x80000000LL) >> 32);
-            v[r] = med3_vvs(q, lo_v, a.hi);
-        } else {
-            int64_t q = RQ == 1 ? (((int64_t)t[r] * a.mul_hi + 0x80000000LL) >> 32)
-                                : rsr64((int64_t)t[r] * a.mul, a.shift);
-            if (RES == 2 && a.res_mode == 2) q += rsr64((int64_t)rv[r] * a.res_mul, a.res_shift);
-            v[r] = clampi64(q, a.lo, a.hi);
-        }
+        int64_t q = RQ == 1 ? (((int64_t)t[r] * a.mul_hi + 0x80000000LL) >> 32) : rsr64((int64_t)t[r] * a.mul, a.shift);
+        if (RES == 2 && a.res_mode == 2) q += rsr64((int64_t)rv[r] * a.res_mul, a.res_shift);
+        v[r] = clampi64(q, a.lo, a.hi);
     }
     *(v4i *)((uint8_t *)a.out + oo) = v4i{pack_low_bytes(v[0], v[1], v[2], v[3]), pack_low_bytes(v[4], v[5], v[6], v[7]),
                                           pack_low_bytes(v[8], v[9], v[10], v[11]), pack_low_bytes(v[12], v[13], v[14], v[15])};
@@ -402,6 +426,19 @@ __device__ __forceinline__ void epilogue_tiles(const ConvArgs &a, const v16i (&a
         for_tiles([&](const v16i &c, int p, int co0, int, int) {
             if (all_slow || co0 + 16 > a.Cout) epilogue_slow(a, c, p, co0, min(16, a.Cout - co0));
         });
+    }
+}
+// One pixel's 16 channels co0..co0+15 (all valid; the call allows 16-byte accesses: a.epi_vec) in the form the
+// host chose (a.epi_mode).  res8: the 8-bit skip operand's 16 bytes, when there is one.
+__device__ __forceinline__ void epilogue_px16(const ConvArgs &a, const v16i &acc, int p, int co0, const v4i &res8)
+{
+    switch (a.epi_mode) {
+#define ICNN_EPI_CASE(RES, RQ) case RES * 4 + RQ: epilogue_vec<RES, RQ>(a, acc, p, co0, res8); break;
+        ICNN_EPI_CASE(0, 0) ICNN_EPI_CASE(0, 1) ICNN_EPI_CASE(0, 2) ICNN_EPI_CASE(0, 3)
+        ICNN_EPI_CASE(1, 0) ICNN_EPI_CASE(1, 1) ICNN_EPI_CASE(1, 2) ICNN_EPI_CASE(1, 3)
+        ICNN_EPI_CASE(2, 0) ICNN_EPI_CASE(2, 1) ICNN_EPI_CASE(2, 2)
+#undef ICNN_EPI_CASE
+    default: break;
     }
 }
 // for callers without a K loop to hide the fetch behind: fetch, then finish

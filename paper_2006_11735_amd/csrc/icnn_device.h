@@ -96,6 +96,19 @@ struct ProjArgs {
     int vec_bias;
 };
 
+// A fused identity bottleneck block (see conv_block.hip): geometry shared by its three layers
+struct BlockArgs {
+    const uint8_t *x;
+    unsigned x_bytes;
+    int x_cs;
+    int N, H, W;
+    int TH, TW, PW;               // output tile and patch row width TW + 2
+    int tiles_x, tiles_per_img, n_tiles;
+    unsigned inv_tw, inv_pw;      // q / TW = q * inv_tw >> 16 for q < 128; row / PW likewise for row < 160
+    int k1;                       // K steps of the first layer: C / 64
+    int nchunk3;                  // output channel chunks of the last layer: C / MID
+};
+
 // [v / 2^s], round half up; arithmetic shift floors for negative values.
 __device__ __forceinline__ int64_t rsr64(int64_t v, int s)
 {
@@ -142,6 +155,9 @@ bool conv_fc_applies(const ConvArgs &a);
 hipError_t launch_conv_fc(const ConvArgs &a, hipStream_t st);
 bool conv_halo_applies(const ConvArgs &a);
 hipError_t launch_conv_halo(const ConvArgs &a, hipStream_t st);
+bool conv_block_tile(int H, int W, BlockArgs &g);
+size_t conv_block_lds_bytes(int mid, int c);
+hipError_t launch_conv_block(const BlockArgs &g, const ConvArgs &a1, const ConvArgs &a2, const ConvArgs &a3, hipStream_t st);
 bool conv_narrow_applies(const ConvArgs &a);
 hipError_t launch_conv_narrow(const ConvArgs &a, hipStream_t st);
 hipError_t launch_prepack(const int8_t *w, uint8_t *wp, int Cout, int K, int chunks, int ksteps, int KH, int KW,

@@ -16,10 +16,12 @@ _DT = {"u8": B.ICNN_U8, "s8": B.ICNN_S8, "s32": B.ICNN_S32}
 
 
 class GpuNet:
-    def __init__(self, net, seed, calib, images=None, device="cuda:0", fuse=True, weights=None):
+    def __init__(self, net, seed, calib, images=None, device="cuda:0", fuse=True, weights=None, fuse_blocks=None):
         """fuse: run a projection conv and the block's last conv that consumes it as one
         iconv2d_dual_brelu launch where the library accepts that (the int32 skip buffer then
-        stays untouched).  weights: optional {layer: (int8 [cout,kh,kw,cin], int32 [cout])}, e.g.
+        stays untouched).  fuse_blocks (default: as fuse): run an identity bottleneck block (1x1, 3x3, 1x1 with
+        the block input as skip operand) as one iconv2d_bottleneck_brelu launch where the library accepts
+        that (its two middle buffers then stay untouched).  weights: optional {layer: (int8 [cout,kh,kw,cin], int32 [cout])}, e.g.
         from paper_2006_11735_amd.convert, instead of the seeded synthetic tensors."""
         self.weights = weights
         if not torch.cuda.is_available():
@@ -36,6 +38,7 @@ class GpuNet:
         self.steps = []
         self.fused = []                     # names of int32 skip buffers that are never written
         self.fused_proj = {}                # main conv name -> the projection op fused into it
+        self.fused_block = {}               # last conv name -> (first, middle) conv ops fused into its launch
         pending = {}                        # skip buffer name -> prepared projection step
         for op in net["ops"]:
             if op["op"] == "conv":
@@ -65,7 +68,44 @@ class GpuNet:
                 self.steps.append(("avgpool", op, args))
             else:
                 raise ValueError(op["op"])
+        if fuse if fuse_blocks is None else fuse_blocks:
+            self._fuse_blocks()
         torch.cuda.synchronize(self.device)
+
+    def _fuse_blocks(self):
+        """Replaces every run of three per-layer conv steps that forms an identity bottleneck block by one fused step."""
+        readers = {}
+        for op in self.net["ops"]:
+            readers.setdefault(op["src"], []).append(op)
+            if op.get("res") is not None:
+                readers.setdefault(op["res"], []).append(op)
+        steps, i = [], 0
+        while i < len(self.steps):
+            trio = self.steps[i:i + 3]
+            if len(trio) == 3 and all(st[0] == "conv" for st in trio):
+                o1, o2, o3 = (st[1] for st in trio)
+                chain = (o2["src"] == o1["dst"] and o3["src"] == o2["dst"] and o3["res"] == o1["src"] and
+                         readers.get(o1["dst"]) == [o2] and readers.get(o2["dst"]) == [o3] and
+                         o1["dst"] not in self.net["outputs"] and o2["dst"] not in self.net["outputs"] and
+                         o1["dst_c_offset"] == 0 and o2["dst_c_offset"] == 0)
+                if chain:
+                    (d1, x, w1, b1, _r1, _y1, _ws1), (d2, _x2, w2, b2, _r2, _y2, _ws2), (d3, _x3, w3, b3, res, y, _ws3) = (
+                        st[2] for st in trio)
+                    args = (d1, x, w1, b1, d2, w2, b2, d3, w3, b3, res, y)
+                    try:
+                        B.iconv2d_bottleneck_brelu(*args)          # also a warm-up launch
+                    except B.IcnnError as e:
+                        if e.code != B.ICNN_E_UNSUPPORTED:
+                            raise
+                    else:
+                        self.fused += [o1["dst"], o2["dst"]]
+                        self.fused_block[o3["name"]] = (o1, o2)
+                        steps.append(("block", o3, args))
+                        i += 3
+                        continue
+            steps.append(self.steps[i])
+            i += 1
+        self.steps = steps
 
     def _prep_conv(self, op):
         cal = self.calib["conv"][op["name"]]
@@ -155,6 +195,8 @@ class GpuNet:
             B.iconv2d_dual_brelu(*args, stream=stream)
         elif kind == "dual_pc":
             B.iconv2d_dual_brelu_pc(*args, stream=stream)
+        elif kind == "block":
+            B.iconv2d_bottleneck_brelu(*args, stream=stream)
         elif kind == "maxpool":
             B.imaxpool2d_u8(*args, stream=stream)
         else:

@@ -1,0 +1,134 @@
+"""GPU parity of the fused identity bottleneck block (iconv2d_bottleneck_brelu) against the oracle's three
+separate layers, bit for bit: the two middle tensors never exist on the GPU, so the block's output is compared
+(the oracle computes the middle tensors itself)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import calibrate as K
+from oracle import oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+def rnd(seed):
+    return np.random.default_rng(seed)
+
+
+def run_block(seed, n, h, w, c, mid, *, skip="x", c3_mode="brelu", forms=("auto", "auto"), bound12=127, cbuf=None):
+    """Returns (gpu output, oracle output).  forms: how the first two layers requantise: "auto" = calibrated
+    15-bit multiplier (the 32-bit form), "hi" = a pair only the one-multiply form takes, "wide" = only the general form."""
+    from gpu_util import dev
+    from paper_2006_11735_amd import binding as B
+    g = rnd(seed)
+    cbuf = c if cbuf is None else cbuf
+    x = g.integers(0, 128, size=(n, h, w, cbuf), dtype=np.uint8)
+    w1 = g.integers(-127, 128, size=(mid, 1, 1, c), dtype=np.int8)
+    w2 = g.integers(-127, 128, size=(mid, 3, 3, mid), dtype=np.int8)
+    w3 = g.integers(-127, 128, size=(c, 1, 1, mid), dtype=np.int8)
+    b1, b2, b3 = (g.integers(-4096, 4097, size=k).astype(np.int32) for k in (mid, mid, c))
+
+    def pair(raw, form, bound):
+        m, s = K.bound_params(K.percentile_999(raw), bound)
+        if form == "hi":            # same ratio, multiplier of 29 bits: too wide for 24-bit factors, fine as a high-word multiply
+            return m << 14, s + 14
+        if form == "wide":          # shift beyond 32: general 64-bit form
+            return m << 16, s + 16 if s + 16 > 32 else 33
+        return m, s
+    t1_raw = O.conv2d(x, w1, b1, cin=c, out_mode="raw_s32")
+    m1, s1 = pair(t1_raw, forms[0], bound12)
+    t1 = O.conv2d(x, w1, b1, cin=c, mul=m1, shift=s1, bound_q=bound12)
+    t2_raw = O.conv2d(t1, w2, b2, pad=1, out_mode="raw_s32")
+    m2, s2 = pair(t2_raw, forms[1], bound12)
+    t2 = O.conv2d(t1, w2, b2, pad=1, mul=m2, shift=s2, bound_q=bound12)
+    kw3 = {}
+    res = None
+    if skip == "x":
+        res = np.ascontiguousarray(x[..., :c])
+    elif skip == "s32":
+        res = g.integers(-300000, 300000, size=(n, h, w, c)).astype(np.int32)
+    if res is not None:
+        y_main = O.conv2d(t2, w3, b3, out_mode="raw_s32")
+        rm, rs = K.mul_shift(127 if skip == "x" else 300000, K.percentile_999(y_main))
+        kw3.update(res=res, res_mode="pre", res_mul=rm, res_shift=rs)
+    t3_raw = O.conv2d(t2, w3, b3, out_mode="raw_s32", **kw3)
+    m3, s3 = K.bound_params(K.percentile_999(t3_raw), 127)
+    if c3_mode == "raw_s32":
+        want = t3_raw
+    elif c3_mode == "linear_s8":
+        want = O.conv2d(t2, w3, b3, mul=m3, shift=s3, out_mode="linear_s8", **kw3)
+    else:
+        want = O.conv2d(t2, w3, b3, mul=m3, shift=s3, bound_q=127, **kw3)
+
+    om = {"brelu": B.ICNN_OUT_BRELU_U8, "raw_s32": B.ICNN_OUT_RAW_S32, "linear_s8": B.ICNN_OUT_LINEAR_S8}[c3_mode]
+    d1 = B.conv_desc(n=n, h=h, w=w, cin=c, in_c_stride=cbuf, cout=mid, kh=1, kw=1, out_c_stride=mid, mul=m1, shift=s1, bound_q=bound12)
+    d2 = B.conv_desc(n=n, h=h, w=w, cin=mid, in_c_stride=mid, cout=mid, kh=3, kw=3, pad_h=1, pad_w=1, out_c_stride=mid, mul=m2,
+                     shift=s2, bound_q=bound12)
+    d3 = B.conv_desc(n=n, h=h, w=w, cin=mid, in_c_stride=mid, cout=c, kh=1, kw=1, out_c_stride=c, mul=m3, shift=s3, bound_q=127,
+                     out_mode=om)
+    if res is not None:
+        d3.res_mode, d3.res_c_stride = B.ICNN_RES_PRE, c
+        d3.res_dtype = B.ICNN_U8 if res.dtype == np.uint8 else B.ICNN_S32
+        d3.res_mul, d3.res_shift = rm, rs
+    packs = []
+    for d, wt in ((d1, w1), (d2, w2), (d3, w3)):
+        pk = torch.zeros(B.iconv2d_packed_weight_bytes(d), dtype=torch.uint8, device="cuda:0")
+        B.iconv2d_prepack_weights(d, dev(wt), pk)
+        packs.append(pk)
+    tdt = {np.dtype(np.uint8): torch.uint8, np.dtype(np.int8): torch.int8, np.dtype(np.int32): torch.int32}[want.dtype]
+    y = torch.zeros(want.shape, dtype=tdt, device="cuda:0")
+    xd = dev(x)
+    rd = None if res is None else (dev(res) if (skip != "x" or cbuf != c) else xd)
+    B.iconv2d_bottleneck_brelu(d1, xd, packs[0], dev(b1), d2, packs[1], dev(b2), d3, packs[2], dev(b3), rd, y)
+    torch.cuda.synchronize()
+    return y.cpu().numpy(), want
+
+
+BLOCKS = [
+    # n, h, w, c, mid
+    (2, 56, 56, 256, 64),        # stage-1 shape: 28 tiles per image, two workgroups per compute unit
+    (3, 28, 28, 512, 128),       # stage-2 shape
+    (1, 17, 23, 128, 64),        # ragged tiles on both axes
+    (2, 9, 30, 256, 128),
+    (1, 5, 6, 64, 64),           # image smaller than a tile
+    (5, 14, 14, 192, 64),        # three channel chunks in the last layer, three K steps in the first
+    (40, 14, 14, 256, 128),      # more tiles than resident workgroups: every workgroup walks several
+    (1, 1, 200, 128, 128),       # one image row
+    (1, 150, 1, 64, 64),         # one image column
+]
+
+
+@pytest.mark.parametrize("shape", BLOCKS, ids=lambda s: "x".join(map(str, s)))
+def test_fused_block_equals_three_layers(shape):
+    n, h, w, c, mid = shape
+    got, want = run_block(sum(shape), n, h, w, c, mid)
+    assert got.shape == want.shape
+    assert (got == want).all(), "%d of %d bytes differ" % (int((got != want).sum()), want.size)
+    assert want.max() == 127 and want.min() == 0
+
+
+@pytest.mark.parametrize("mid,c", [(64, 128), (128, 256)])
+def test_fused_block_output_and_skip_modes(mid, c):
+    for kw in (dict(skip=None), dict(skip="s32"), dict(c3_mode="raw_s32"), dict(c3_mode="linear_s8", skip=None),
+               dict(forms=("hi", "wide")), dict(forms=("wide", "hi")), dict(bound12=15), dict(cbuf=c + 64)):
+        got, want = run_block(7 + mid, 2, 11, 13, c, mid, **kw)
+        assert (got == want).all(), kw
+
+
+def test_fused_block_refuses_other_shapes():
+    from paper_2006_11735_amd import binding as B
+
+    def descs(**over):
+        base = dict(n=1, h=8, w=8, c=128, mid=64, stride=1, k2=3)
+        base.update(over)
+        c, mid = base["c"], base["mid"]
+        d1 = B.conv_desc(n=1, h=8, w=8, cin=c, in_c_stride=c, cout=mid, kh=1, kw=1, out_c_stride=mid, mul=20000, shift=24)
+        d2 = B.conv_desc(n=1, h=8, w=8, cin=mid, in_c_stride=mid, cout=mid, kh=base["k2"], kw=base["k2"], pad_h=base["k2"] // 2,
+                         pad_w=base["k2"] // 2, stride_h=base["stride"], stride_w=base["stride"], out_c_stride=mid, mul=20000, shift=24)
+        d3 = B.conv_desc(n=1, h=8, w=8, cin=mid, in_c_stride=mid, cout=c, kh=1, kw=1, out_c_stride=c, mul=20000, shift=24)
+        return d1, d2, d3
+    for over in (dict(mid=32), dict(mid=256, c=256), dict(stride=2), dict(k2=5), dict(c=96)):
+        d1, d2, d3 = descs(**over)
+        with pytest.raises(B.IcnnError) as e:
+            B.iconv2d_bottleneck_brelu(d1, 4096, 8192, 12288, d2, 16384, 20480, d3, 24576, 28672, None, 32768, stream=0)
+        assert e.value.code in (B.ICNN_E_UNSUPPORTED, B.ICNN_E_SHAPE), over

@@ -32,6 +32,7 @@ def test_small_vdsr_vrcnn_resnet(seed):
         for fuse in (False, True):
             g = GpuNet(net, seed, calib, fuse=fuse)
             assert bool(g.fused) == (fuse and net["name"] == "tiny")
+            assert bool(g.fused_block) == (fuse and net["name"] == "tiny")
             g.set_input()
             g.run()
             compare_all(net, g, want)
@@ -86,7 +87,7 @@ def test_config3_per_channel_full_batch_sampled_images():
                 continue
             got = g.result(name)[img:img + 1]
             assert (got == want[name]).all(), (img, name)
-    assert len(g.fused) == 4
+    assert len(g.fused_proj) == 4 and not g.fused_block       # per-channel layers are not taken by the block kernel
 
 
 def stored(cfg):
@@ -132,7 +133,8 @@ def test_config3_resnet50_full_batch_sampled_images():
                 continue
             got = g.buf[name][img:img + 1].cpu().numpy()
             assert (got == want[name]).all(), (img, name)
-    assert len(g.fused) == 4
+    # four projection blocks and the five identity blocks of stages 1 and 2 run as single launches
+    assert len(g.fused_proj) == 4 and len(g.fused_block) == 5 and len(g.fused) == 4 + 2 * 5
     logits = g.result("logits")
     assert logits.dtype == np.int32 and logits.shape == (64, 1, 1, 1000)
 
@@ -235,5 +237,5 @@ def test_config4_resnet152_full_batch_sampled_images():
                 continue
             got = g.buf[name][img:img + 1].cpu().numpy()
             assert (got == want[name]).all(), (img, name)
-    assert len(g.fused) == 4
+    assert len(g.fused_proj) == 4 and len(g.fused_block) == 2 + 7
     assert g.result("logits").shape == (128, 1, 1, 1000)
