@@ -15,16 +15,19 @@
 //
 // Eight waves with three roles:
 //   waves 0-3  multiply: read fragments from LDS, issue MFMAs, run the epilogues (phase 1 and 2 write LDS);
-//   waves 4-5  weights:  stream the A operand of every K step (MID rows x 64 bytes) through a ring of four LDS
-//              stages, three steps ahead, across phases and tiles;
+//   waves 4-5  weights:  stream the A operand of every K step (MID rows x 64 bytes) through a ring of six LDS
+//              stages, five steps ahead, across phases and tiles;
 //   waves 6-7  input:    copy the next tile's whole patch of x (all channels) into LDS while the current tile is
 //              in phases 2 and 3.
-// One workgroup barrier per K step plus one after each of the first two epilogues; all roles run the same loop
-// nest with workgroup-uniform bounds, so the barrier counts match.  Before the barrier of step g the weight waves
-// have waited for stage g (loads retire in order, and every stage is the same number of copies per wave, so the
-// wait count is a constant); after it they refill the slot of stage g - 1, which every multiply wave has finished
-// with (its MFMAs of step g - 1 are issued).  The input waves wait for everything they issued before a tile's
-// first barrier; they start overwriting the patch only after the barrier that follows phase 1's epilogue.
+// One workgroup barrier per K step, one before the first tile, one after phase 1's epilogue, one before and one
+// after phase 2's (b overwrites a); all roles run the same loop nest with workgroup-uniform bounds, so the barrier
+// counts match.  The multiply waves fetch the fragments of step g + 1 while they multiply step g's: the weight
+// fragments right after barrier g, the activation fragments one by one, each into the registers of the fragment
+// whose only MFMA has just been issued.  So before barrier g the weight waves have waited for stage g + 1 (loads
+// retire in order and every stage is the same number of copies per wave: the wait count is a constant), and after
+// it they refill the slot of stage g - 1, whose fragments every multiply wave has multiplied.  The input waves wait
+// for everything they issued before a tile's first barrier; they start overwriting the patch only after the
+// barrier that follows phase 1's epilogue.
 #include "conv_common.h"
 
 #include <type_traits>
@@ -33,8 +36,8 @@ namespace icnn {
 
 constexpr int kBlkRows = 160;        // patch rows: five pixel groups of 32
 constexpr int kBlkPix = 128;         // output pixel slots of a tile: four groups
-constexpr int kBlkStages = 4;        // weight ring
-[[maybe_unused]] constexpr int kBlkDepth = kBlkStages - 1;
+constexpr int kBlkStages = 6;        // weight ring
+[[maybe_unused]] constexpr int kBlkDepth = kBlkStages - 1;      // stages issued ahead of the step being multiplied
 
 // fn(integral_constant<int, 0>) ... fn(integral_constant<int, N - 1>): a loop the compiler cannot leave rolled
 // (register arrays indexed inside it stay in registers)
@@ -47,10 +50,10 @@ __device__ __forceinline__ void static_for(F &&fn)
     }
 }
 
-// the biases of channels co0 .. co0 + 15 (16-byte aligned: the host requires aligned bias arrays here)
-__device__ __forceinline__ v16i bias16(const int32_t *bias, int co0)
+// sixteen consecutive int32 of the bias table in LDS
+__device__ __forceinline__ v16i bias16(const int32_t *tab)
 {
-    const v4i *bp = (const v4i *)(bias + co0);
+    const v4i *bp = (const v4i *)tab;
     v16i b;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -59,6 +62,19 @@ __device__ __forceinline__ v16i bias16(const int32_t *bias, int co0)
     }
     return b;
 }
+
+// Development aid, compiled in with -DICNN_BLOCK_TRACE only: multiply wave 0 of one workgroup stamps the clock
+// at the marked points; icnn_debug_trace() copies the stamps out.
+#ifdef ICNN_BLOCK_TRACE
+__device__ unsigned long long g_blk_trace[4096];
+#define BLK_TR(k)                                                                                                  \
+    do {                                                                                                           \
+        if (blockIdx.x == 3 && wave8 == 0 && lane == 0 && trn < 4000)                                              \
+            g_blk_trace[trn++] = ((unsigned long long)(k) << 56) | (__builtin_amdgcn_s_memtime() & 0xffffffffffffffULL); \
+    } while (0)
+#else
+#define BLK_TR(k)
+#endif
 
 template <int MG>                    // MID / 32: 2 (two workgroups per compute unit) or 4
 __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const BlockArgs g, const ConvArgs a1, const ConvArgs a2,
@@ -71,13 +87,23 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
     constexpr int TP2 = 4 / WP;                      // ... in phases 2 and 3 (four in all)
     constexpr int SLICE_A = kBlkRows * 64;           // one 64-channel slice of the patch
     constexpr int SLICE_B = kBlkPix * 64;
+    constexpr int MID = MG * 32;
+    constexpr int NS = kBlkStages;
+    // AHEAD: the multiply waves fetch step g + 1's fragments while they multiply step g's.  The 64-wide variant runs
+    // two workgroups per compute unit inside 128 registers, where the second fragment set does not fit: it fetches a
+    // step's fragments after the step's barrier and leaves the waiting to the other workgroup (measured: 59 us per
+    // 64 x 56 x 56 x 256 block against 75 us with the fetch ahead and spills, or with one workgroup per unit).
+    constexpr bool AHEAD = MG == 4;
     constexpr unsigned OOB = 0x80000000u;
 
+    // LDS: weight ring | patch of x (k1 slices) | patch of a (s2 slices; later b on the tile, s2 slices) | biases
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
-    const int k1 = g.k1, s2 = MG / 2, k3 = MG / 2, nchunk3 = g.nchunk3;
-    uint8_t *const xbuf = lds + kBlkStages * ASZ;
+    const int k1 = g.k1, nchunk3 = g.nchunk3;
+    constexpr int s2 = MG / 2, k3 = MG / 2;
+    uint8_t *const xbuf = lds + NS * ASZ;
     uint8_t *const abuf = xbuf + k1 * SLICE_A;
-    uint8_t *const bbuf = abuf + s2 * SLICE_A;
+    uint8_t *const bbuf = abuf;                      // b overwrites a once every wave has left phase 2
+    int32_t *const btab = (int32_t *)(abuf + s2 * SLICE_A);        // [MID] layer 1, [MID] layer 2, [C] layer 3
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -96,14 +122,16 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
     };
-    // after an epilogue that wrote LDS with ordinary stores: they have to be complete before the barrier lets
-    // other waves read them (s_waitcnt lgkmcnt(0); the copy waves' barriers need nothing of the kind)
+    // after LDS was written with ordinary stores: they have to be complete before the barrier lets other waves read
+    // them (s_waitcnt lgkmcnt(0); the copy waves' barriers need nothing of the kind)
     auto sync_lds_written = [&]() {
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(0xC07F);
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
     };
+    // Barriers of a workgroup, executed by all eight waves: one before the first tile, then per tile: k1 steps, one after
+    // phase 1's epilogue, 9 * s2 steps, one before and one after phase 2's epilogue, nchunk3 * k3 steps.
 
     if (wave8 >= 6) {
         // ------------------------------------------------------------------ input waves
@@ -137,6 +165,9 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
         };
         setup(blockIdx.x);
         issue_patch();
+        asm volatile("" ::: "memory");
+        ICNN_WAIT_VMCNT(0);
+        sync();                                       // the first tile's patch is in LDS
         for (int v = blockIdx.x; v < n_tiles; v += gridDim.x) {
             asm volatile("" ::: "memory");
             ICNN_WAIT_VMCNT(0);                       // this tile's patch is in LDS
@@ -146,9 +177,7 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
                 setup(v + (int)gridDim.x);
                 issue_patch();
             }
-            for (int s = 0; s < 9 * s2; ++s) sync();
-            sync();
-            for (int s = 0; s < nchunk3 * k3; ++s) sync();
+            for (int s = 0; s < 9 * s2 + 2 + nchunk3 * k3; ++s) sync();
         }
         asm volatile("" ::: "memory");
         ICNN_WAIT_VMCNT(0);
@@ -210,21 +239,27 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
                     }
                 }
             }
-            islot = (islot + 1) & (kBlkStages - 1);
+            islot = islot + 1 == NS ? 0 : islot + 1;
         };
-        // one K step: stage g has landed (at most kBlkDepth - 1 younger stages still travel), barrier g, refill
+        // One K step g.  The multiply waves fetch stage g + 1's fragments right after barrier g, so that stage has landed
+        // before it: of the stages issued so far (up to g + kBlkDepth - 1) at most kBlkDepth - 2 are younger.  After the
+        // barrier the slot of stage g - 1 is free (its fragments were multiplied before the barrier): stage g + kBlkDepth.
         auto step = [&]() {
             asm volatile("" ::: "memory");
-            if (imore) ICNN_WAIT_VMCNT((kBlkDepth - 1) * NA);
+            if (imore) ICNN_WAIT_VMCNT((kBlkDepth - (AHEAD ? 2 : 1)) * NA);      // without the fetch ahead: stage g
             else ICNN_WAIT_VMCNT(0);                  // the issue side ran out: fewer younger stages than the count assumes
             sync();
             issue_next();
         };
         for (int d = 0; d < kBlkDepth; ++d) issue_next();      // a tile has more than kBlkDepth steps
+        asm volatile("" ::: "memory");
+        ICNN_WAIT_VMCNT((kBlkDepth - 1) * NA);        // stage 0
+        sync();
         for (int v = blockIdx.x; v < n_tiles; v += gridDim.x) {
             for (int k = 0; k < k1; ++k) step();
             sync();
             for (int s = 0; s < 9 * s2; ++s) step();
+            sync();
             sync();
             for (int s = 0; s < nchunk3 * k3; ++s) step();
         }
@@ -241,64 +276,115 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
     const int n1 = MG == 2 ? (wp == 0 ? 3 : 2) : 5;      // pixel groups of this wave in phase 1
     const int pg1_0 = MG == 2 ? (wp == 0 ? 0 : 3) : 0;   // the first of them
     const int co_in_stage = wm * 32 + half * 16;         // this lane's 16 channels inside a stage's MID channels
-    int slot = 0;
+    int slot = 0;                                        // ring slot of the stage the next step multiplies
+    [[maybe_unused]] int trn = 0;
 
-    // tile-invariant addresses.  Phase 1: pixel group j of the wave is patch rows 32 * (pg1_0 + j) .. + 32
-    // (Addresses are rebuilt from these few values inside the K loops, behind an opaque copy of the lane's column:
-    // left alone, the compiler hoists dozens of loop-invariant addresses out of the loops and spills them.)
-    int row1[TP1];
-#pragma unroll
-    for (int j = 0; j < TP1; ++j) row1[j] = 32 * (pg1_0 + j) + col;
+    // the three layers' biases, once per workgroup
+    for (int i = tid; i < 2 * MID + g.nchunk3 * MID; i += 256)
+        btab[i] = i < MID ? a1.bias[i] : (i < 2 * MID ? a2.bias[i - MID] : a3.bias[i - 2 * MID]);
+
+    // Tile-invariant positions.  (Addresses are rebuilt from these few values inside the K loops, behind an opaque
+    // copy: left alone, the compiler hoists dozens of loop-invariant addresses out of the loops and spills them.)
+    // Phase 1: pixel group j of the wave is patch rows 32 * (pg1_0 + j) .. + 32
+    const int row1_0 = 32 * pg1_0 + col;
     // Phases 2 and 3: pixel group j is output slots q = 32 * (wp * TP2 + j) + col, slot q = ty * TW + tx
-    int q2[TP2], rel[TP2], ty2[TP2], tx2[TP2];
+    const int q2_0 = 32 * wp * TP2 + col;
+    int rel[TP2], ty2[TP2], tx2[TP2];
 #pragma unroll
     for (int j = 0; j < TP2; ++j) {
-        q2[j] = 32 * (wp * TP2 + j) + col;
-        const bool in_tile = q2[j] < g.TH * g.TW;
-        ty2[j] = in_tile ? (int)(((unsigned)q2[j] * g.inv_tw) >> 16) : 0;
-        tx2[j] = in_tile ? q2[j] - ty2[j] * g.TW : 0;
+        const int q = q2_0 + 32 * j;
+        const bool in_tile = q < g.TH * g.TW;
+        ty2[j] = in_tile ? (int)(((unsigned)q * g.inv_tw) >> 16) : 0;
+        tx2[j] = in_tile ? q - ty2[j] * g.TW : 0;
         if (!in_tile) ty2[j] = -1;                       // marks a slot beyond the tile
         rel[j] = (max(ty2[j], 0) + 1) * g.PW + tx2[j] + 1;      // patch row of the pixel (centre tap)
     }
 
+    // Fragments.  A: the current step's (afc) and the next step's (afn), fetched one step ahead from the ring.
+    // B: every fragment feeds exactly one MFMA (a wave owns one 32-channel chunk), so its registers are refilled with
+    // the next step's fragment as soon as that MFMA is issued.
+    v4i afc[2], afn[2];
+    auto fetch_a = [&](v4i (&dst)[2], int s) {
+        const uint8_t *S = lds + s * ASZ + wm * 2048 + lane * 16;
+        dst[0] = *(const v4i *)S;
+        dst[1] = *(const v4i *)(S + 1024);
+    };
+    auto next_slot = [&]() { return slot + 1 == NS ? 0 : slot + 1; };
+
+    sync_lds_written();                  // before the first tile: bias table, stage 0 and the first patch are in LDS
+    if (AHEAD) fetch_a(afc, 0);
+
     for (int v = blockIdx.x; v < n_tiles; v += gridDim.x) {
         int n, y0, x0;
         tile_origin(v, n, y0, x0);
+        // output pixels of phase 3 and the first chunk's skip operands (they travel during phases 1 and 2)
+        int p3[TP2];
+        bool ok3[TP2];
+#pragma unroll
+        for (int j = 0; j < TP2; ++j) {
+            const int oy = y0 + ty2[j], ox = x0 + tx2[j];
+            ok3[j] = ty2[j] >= 0 && oy < g.H && ox < g.W;
+            p3[j] = ok3[j] ? (n * g.H + oy) * g.W + ox : 0;
+        }
+        const bool fetch_res = res8_applies(a3);
+        v4i res8[TP2];
+        auto fetch_res8 = [&](int ch) {
+#pragma unroll
+            for (int j = 0; j < TP2; ++j) {
+                res8[j] = v4i{0, 0, 0, 0};
+                if (fetch_res && ok3[j])
+                    res8[j] = *(const v4i *)((const uint8_t *)a3.res + ((size_t)p3[j] * a3.res_cs + ch * MID + co_in_stage));
+            }
+        };
+        fetch_res8(0);
+        BLK_TR(1);
 
         // ---------------- phase 1: a = requant(W1 x + b1) on the patch rows
         {
             v16i acc[TP1];
             {
-                const v16i b = bias16(a1.bias, co_in_stage);
+                const v16i b = bias16(btab + co_in_stage);
 #pragma unroll
                 for (int j = 0; j < TP1; ++j) acc[j] = b;
             }
+            v4i bf[2][TP1];
             for (int k = 0; k < k1; ++k) {
                 sync();
-                const uint8_t *S = lds + slot * ASZ + wm * 2048 + lane * 16;
-                slot = (slot + 1) & (kBlkStages - 1);
-                const uint8_t *X = xbuf + k * SLICE_A;
-                v4i af[2], bf[2][TP1];
-                int r0 = row1[0];
+                BLK_TR(10);
+                int r0 = row1_0;
                 asm volatile("" : "+v"(r0));
+                if (k == 0 || !AHEAD) {                // (the patch is complete only after a tile's first barrier)
+                    const uint8_t *X = xbuf + k * SLICE_A;
 #pragma unroll
-                for (int kq = 0; kq < 2; ++kq) {
-                    af[kq] = *(const v4i *)(S + kq * 1024);
+                    for (int kq = 0; kq < 2; ++kq)
 #pragma unroll
-                    for (int j = 0; j < TP1; ++j)      // rows 32 apart share the swizzle
-                        if (j < n1) bf[kq][j] = *(const v4i *)(X + b_slot_offset(r0, kq * 2 + half) + j * 2048);
+                        for (int j = 0; j < TP1; ++j)     // rows 32 apart share the swizzle
+                            if (j < n1) bf[kq][j] = *(const v4i *)(X + b_slot_offset(r0, kq * 2 + half) + j * 2048);
                 }
+                const int ns = next_slot();
+                if (AHEAD) fetch_a(afn, ns);
+                else fetch_a(afc, slot);
+                const bool more = AHEAD && k + 1 < k1;
+                const uint8_t *Xn = xbuf + (k + 1) * SLICE_A;
 #pragma unroll
                 for (int kq = 0; kq < 2; ++kq)
 #pragma unroll
                     for (int j = 0; j < TP1; ++j)
-                        if (j < n1) acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[kq], bf[kq][j], acc[j], 0, 0, 0);
+                        if (j < n1) {
+                            acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(afc[kq], bf[kq][j], acc[j], 0, 0, 0);
+                            if (more) bf[kq][j] = *(const v4i *)(Xn + b_slot_offset(r0, kq * 2 + half) + j * 2048);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                afc[0] = afn[0];
+                afc[1] = afn[1];
+                slot = ns;
             }
+            BLK_TR(3);
             // rows outside the image are the next layer's zero padding
             static_for<TP1>([&](auto jc) {
                 constexpr int j = decltype(jc)::value;
                 if (j >= n1) return;
-                const int row = row1[j];
+                const int row = row1_0 + 32 * j;
                 const int py = (int)(((unsigned)row * g.inv_pw) >> 16);
                 const int px = row - py * g.PW;
                 const int iy = y0 - 1 + py, ix = x0 - 1 + px;
@@ -312,99 +398,135 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
                 *(v4i *)(abuf + (co_in_stage >> 6) * SLICE_A + row * 64 + (((piece ^ (row >> 2)) & 3) << 4)) = w;
             });
         }
+        BLK_TR(4);
         sync_lds_written();
+        BLK_TR(5);
 
         // ---------------- phase 2: b = requant(W2 (*) a + b2) on the tile's pixel slots
         {
             v16i acc[TP2];
             {
-                const v16i b = bias16(a2.bias, co_in_stage);
+                const v16i b = bias16(btab + MID + co_in_stage);
 #pragma unroll
                 for (int j = 0; j < TP2; ++j) acc[j] = b;
             }
+            // fragment of pixel group j for tap offset toff in slice A: pieces 0, 1 hold k 0..31, pieces 2, 3 k 32..63
+            v4i bf[2][TP2];
+            auto fetch_b2 = [&](const uint8_t *A, int toff) {
+#pragma unroll
+                for (int j = 0; j < TP2; ++j) {
+                    const int row = rel[j] + toff;
+                    const int base = row * 64 + (((half ^ (row >> 2)) & 3) << 4);
+                    bf[0][j] = *(const v4i *)(A + base);
+                    bf[1][j] = *(const v4i *)(A + (base ^ 32));
+                }
+            };
+            if (AHEAD) fetch_b2(abuf, -g.PW - 1);
             for (int c = 0; c < s2; ++c) {
                 const uint8_t *A = abuf + c * SLICE_A;
 #pragma unroll
                 for (int t = 0; t < 9; ++t) {
                     sync();
-                    const uint8_t *S = lds + slot * ASZ + wm * 2048 + lane * 16;
-                    slot = (slot + 1) & (kBlkStages - 1);
-                    int toff = (t / 3 - 1) * g.PW + (t % 3 - 1);
-                    asm volatile("" : "+s"(toff));
-                    v4i af[2], bf[2][TP2];
-                    af[0] = *(const v4i *)S;
-                    af[1] = *(const v4i *)(S + 1024);
+                    BLK_TR(11);
+                    const int ns = next_slot();
+                    if (AHEAD) fetch_a(afn, ns);
+                    else {
+                        fetch_a(afc, slot);
+                        int toff = (t / 3 - 1) * g.PW + (t % 3 - 1);
+                        asm volatile("" : "+s"(toff));
+                        fetch_b2(A, toff);
+                    }
+                    const int tn = t == 8 ? 0 : t + 1;
+                    const bool more = AHEAD && (t < 8 || c + 1 < s2);
+                    const uint8_t *An = t == 8 ? A + SLICE_A : A;
+                    int toffn = (tn / 3 - 1) * g.PW + (tn % 3 - 1);
+                    asm volatile("" : "+s"(toffn));
 #pragma unroll
                     for (int j = 0; j < TP2; ++j) {
-                        const int row = rel[j] + toff;
-                        const int base = row * 64 + (((half ^ (row >> 2)) & 3) << 4);      // pieces 0, 1 hold k 0..31, pieces 2, 3 k 32..63
-                        bf[0][j] = *(const v4i *)(A + base);
-                        bf[1][j] = *(const v4i *)(A + (base ^ 32));
+                        const int row = rel[j] + toffn;
+                        const int base = row * 64 + (((half ^ (row >> 2)) & 3) << 4);
+                        acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(afc[0], bf[0][j], acc[j], 0, 0, 0);
+                        if (more) bf[0][j] = *(const v4i *)(An + base);
+                        if (AHEAD) __builtin_amdgcn_sched_barrier(0);
+                        acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(afc[1], bf[1][j], acc[j], 0, 0, 0);
+                        if (more) bf[1][j] = *(const v4i *)(An + (base ^ 32));
+                        if (AHEAD) __builtin_amdgcn_sched_barrier(0);
                     }
-#pragma unroll
-                    for (int kq = 0; kq < 2; ++kq)
-#pragma unroll
-                        for (int j = 0; j < TP2; ++j) acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[kq], bf[kq][j], acc[j], 0, 0, 0);
+                    if (AHEAD) { afc[0] = afn[0]; afc[1] = afn[1]; }
+                    slot = ns;
                 }
             }
+            BLK_TR(6);
+            sync();                      // every wave has its last fragments of a: b may overwrite it
+            BLK_TR(9);
             static_for<TP2>([&](auto jc) {
                 constexpr int j = decltype(jc)::value;
                 int t[16];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) t[r] = acc[j][r];
                 const v4i w = requant16_any(a2, t);      // slots beyond the tile hold values nobody stores
-                *(v4i *)(bbuf + (co_in_stage >> 6) * SLICE_B + b_slot_offset(q2[j], (co_in_stage & 63) >> 4)) = w;
+                *(v4i *)(bbuf + (co_in_stage >> 6) * SLICE_B + b_slot_offset(q2_0 + 32 * j, (co_in_stage & 63) >> 4)) = w;
             });
         }
+        BLK_TR(7);
         sync_lds_written();
+        BLK_TR(8);
 
         // ---------------- phase 3: y = epilogue(W3 b + b3, skip), MID output channels at a time
-        int p3[TP2];
-        bool ok3[TP2];
-#pragma unroll
-        for (int j = 0; j < TP2; ++j) {
-            const int oy = y0 + ty2[j], ox = x0 + tx2[j];
-            ok3[j] = ty2[j] >= 0 && oy < g.H && ox < g.W;
-            p3[j] = ok3[j] ? (n * g.H + oy) * g.W + ox : 0;
-        }
-        const bool fetch_res = res8_applies(a3);
-        for (int ch = 0; ch < nchunk3; ++ch) {
-            const int co0 = ch * (MG * 32) + co_in_stage;
-            v4i res8[TP2];
-#pragma unroll
-            for (int j = 0; j < TP2; ++j) {
-                res8[j] = v4i{0, 0, 0, 0};
-                if (fetch_res && ok3[j]) res8[j] = *(const v4i *)((const uint8_t *)a3.res + ((size_t)p3[j] * a3.res_cs + co0));
-            }
-            v16i acc[TP2];
-            {
-                const v16i b = bias16(a3.bias, co0);
-#pragma unroll
-                for (int j = 0; j < TP2; ++j) acc[j] = b;
-            }
-            for (int k = 0; k < k3; ++k) {
-                sync();
-                const uint8_t *S = lds + slot * ASZ + wm * 2048 + lane * 16;
-                slot = (slot + 1) & (kBlkStages - 1);
-                const uint8_t *Bq = bbuf + k * SLICE_B;
-                v4i af[2], bf[2][TP2];
-                int qa = q2[0];
+        {
+            v4i bf[2][TP2];
+            auto fetch_b3 = [&](const uint8_t *Bq) {
+                int qa = q2_0;
                 asm volatile("" : "+v"(qa));
-#pragma unroll
-                for (int kq = 0; kq < 2; ++kq) {
-                    af[kq] = *(const v4i *)(S + kq * 1024);
-#pragma unroll
-                    for (int j = 0; j < TP2; ++j) bf[kq][j] = *(const v4i *)(Bq + b_slot_offset(qa, kq * 2 + half) + j * 2048);
-                }
 #pragma unroll
                 for (int kq = 0; kq < 2; ++kq)
 #pragma unroll
-                    for (int j = 0; j < TP2; ++j) acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[kq], bf[kq][j], acc[j], 0, 0, 0);
+                    for (int j = 0; j < TP2; ++j) bf[kq][j] = *(const v4i *)(Bq + b_slot_offset(qa, kq * 2 + half) + j * 2048);
+            };
+            if (AHEAD) fetch_b3(bbuf);
+            for (int ch = 0; ch < nchunk3; ++ch) {
+                const int co0 = ch * MID + co_in_stage;
+                v16i acc[TP2];
+                {
+                    const v16i b = bias16(btab + 2 * MID + co0);
+#pragma unroll
+                    for (int j = 0; j < TP2; ++j) acc[j] = b;
+                }
+                BLK_TR(20);
+#pragma unroll
+                for (int k = 0; k < k3; ++k) {
+                    sync();
+                    BLK_TR(12);
+                    const int ns = next_slot();
+                    if (AHEAD) fetch_a(afn, ns);
+                    else {
+                        fetch_a(afc, slot);
+                        fetch_b3(bbuf + k * SLICE_B);
+                    }
+                    const bool more = AHEAD && (k + 1 < k3 || ch + 1 < nchunk3);
+                    const uint8_t *Bn = bbuf + (k + 1 < k3 ? k + 1 : 0) * SLICE_B;
+                    int qa = q2_0;
+                    asm volatile("" : "+v"(qa));
+#pragma unroll
+                    for (int kq = 0; kq < 2; ++kq)
+#pragma unroll
+                        for (int j = 0; j < TP2; ++j) {
+                            acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(afc[kq], bf[kq][j], acc[j], 0, 0, 0);
+                            if (more) bf[kq][j] = *(const v4i *)(Bn + b_slot_offset(qa, kq * 2 + half) + j * 2048);
+                            if (AHEAD) __builtin_amdgcn_sched_barrier(0);
+                        }
+                    if (AHEAD) { afc[0] = afn[0]; afc[1] = afn[1]; }
+                    slot = ns;
+                }
+                BLK_TR(21);
+                static_for<TP2>([&](auto jc) {
+                    constexpr int j = decltype(jc)::value;
+                    if (ok3[j]) epilogue_px16(a3, acc[j], p3[j], co0, res8[j]);
+                });
+                BLK_TR(22);
+                // the next chunk's skip operands travel during its K steps (the first chunk's during phases 1 and 2)
+                if (ch + 1 < nchunk3) fetch_res8(ch + 1);
             }
-            static_for<TP2>([&](auto jc) {
-                constexpr int j = decltype(jc)::value;
-                if (ok3[j]) epilogue_px16(a3, acc[j], p3[j], co0, res8[j]);
-            });
         }
     }
 #endif
@@ -414,7 +536,7 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
 size_t conv_block_lds_bytes(int mid, int c)
 {
     const int mg = mid / 32, k1 = c / 64, s2 = mid / 64;
-    return (size_t)kBlkStages * mg * 2048 + (size_t)k1 * kBlkRows * 64 + (size_t)s2 * kBlkRows * 64 + (size_t)s2 * kBlkPix * 64;
+    return (size_t)kBlkStages * mg * 2048 + (size_t)k1 * kBlkRows * 64 + (size_t)s2 * kBlkRows * 64 + (size_t)(2 * mid + c) * 4;
 }
 
 // Output tile TH x TW with TH * TW <= 128 and (TH + 2) * (TW + 2) <= 160 that covers the image with the fewest tiles
@@ -463,5 +585,12 @@ hipError_t launch_conv_block(const BlockArgs &g, const ConvArgs &a1, const ConvA
     };
     return mid == 64 ? go(conv_block_kernel<2>) : go(conv_block_kernel<4>);
 }
+
+#ifdef ICNN_BLOCK_TRACE
+extern "C" int icnn_debug_trace(unsigned long long *host, int n)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_blk_trace), sizeof(unsigned long long) * n);
+}
+#endif
 
 }  // namespace icnn
