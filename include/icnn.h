@@ -127,6 +127,7 @@ const char *icnn_last_error(void);
  *   "no_narrow", "no_fc", "no_halo", "no_stream"   1 keeps layers off the respective special kernel
  *   "halo_tile"   0 library's choice; 1 = 128 x 128, 2 = 64 x 256 tiles of the patch-resident 3x3 kernel
  *   "halo_always" 1 lets the patch-resident kernel take layers with several tiles per workgroup
+ *   "ksplit"      0 library's choice; 1 never split the K axis over workgroups; 2..8 that split where it divides the K steps
  *   "reset"       (value ignored) back to the library's choices
  * Unknown names and values outside these ranges return ICNN_E_PARAM and change nothing. */
 int icnn_set_tuning(const char *name, int32_t value);
@@ -141,7 +142,11 @@ int iconv2d_validate(const icnn_conv_desc *desc);
 /* Output height and width of the layer (host only). */
 int iconv2d_out_hw(const icnn_conv_desc *desc, int32_t *ho, int32_t *wo);
 
-/* Bytes of device workspace iconv2d_brelu needs for this layer (may be 0). */
+/* Bytes of device workspace iconv2d_brelu uses for this layer (may be 0): the padded copy of a layer with cin <= 4,
+ * or the partial sums of a layer whose K axis is split over workgroups.  The caller zero-fills a workspace once after
+ * allocating it (its first 4096 bytes are counters that every call leaves at zero); one workspace of the largest size
+ * may serve all layers that run one after the other on a stream.  Layers that split K also run without a workspace
+ * (NULL): then the K axis stays whole. */
 int iconv2d_workspace_bytes(const icnn_conv_desc *desc, size_t *bytes);
 
 /* Bytes of the library's packed weight format for this layer. */
@@ -156,7 +161,8 @@ int iconv2d_prepack_weights(const icnn_conv_desc *desc, const int8_t *w_ohwi,
 /* The integer convolution layer defined above.  x: input activations; w_packed:
  * from iconv2d_prepack_weights; bias: int32 [cout]; res: skip operand over the
  * output pixels (NULL iff res_mode == NONE); y: output; workspace: at least
- * iconv2d_workspace_bytes bytes (may be NULL when that is 0).
+ * iconv2d_workspace_bytes bytes, 16-byte aligned, zero-filled once by the caller (may be NULL when that is 0; a layer
+ * that asked for none does not touch it).
  * Alignment: x, y and res 16-byte aligned with pitches that are multiples of 16
  * select the vector paths; anything else takes slower element-wise paths with
  * identical results. */
@@ -167,11 +173,13 @@ int iconv2d_brelu(const icnn_conv_desc *desc, const void *x, const void *w_packe
 /*
  * iconv2d_brelu for callers that cannot allocate device memory or pass a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and error codes as
- * iconv2d_brelu, without `workspace`: layers that need one (iconv2d_workspace_bytes > 0, i.e. cin <= 4) keep their
- * padded copy of x in a fixed array of ICNN_STATIC_WORKSPACE_BYTES bytes of device memory that the library's code
+ * iconv2d_brelu, without `workspace`: layers that use one (iconv2d_workspace_bytes > 0) keep their
+ * padded copy of x or their partial sums in a fixed array of ICNN_STATIC_WORKSPACE_BYTES bytes of device memory that the library's code
  * object carries (each GPU the library runs on holds its own copy until the process ends).  A layer that needs more
- * returns ICNN_E_SHAPE having launched nothing.  The call allocates and frees nothing, on the host or the device.
- * Nothing in the array has to start at zero (every byte a layer reads it has written in the same call), but all
+ * padded copy returns ICNN_E_SHAPE having launched nothing (partial sums that would not fit are simply not used: the
+ * K axis stays whole).  The call allocates and frees nothing, on the host or the device.  The array's counter block
+ * starts at zero when the library is loaded and every call leaves it at zero; all other bytes a layer reads it has
+ * written in the same call.  All
  * calls on one GPU share it: calls that may overlap in time on one GPU (different streams, different threads)
  * race on it and must be serialised by the caller.
  */

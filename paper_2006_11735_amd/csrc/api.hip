@@ -98,7 +98,7 @@ int check_conv(const icnn_conv_desc *d, ConvGeom *g)
             const int need = (wo - 1) * d->stride_w + g->rp / 4;
             g->wp = d->w + 2 * d->pad_w > need ? d->w + 2 * d->pad_w : need;
             g->K = d->kh * g->rp;
-            const unsigned long long wsb = (unsigned long long)d->n * g->hp * g->wp * 4 + 64;
+            const unsigned long long wsb = (unsigned long long)d->n * g->hp * g->wp * 4 + 64 + kWsCounterBytes;
             if (wsb > 0x7fffffffull) return fail(ICNN_E_SHAPE, "small-cin workspace of %llu bytes exceeds 2 GiB", wsb);
             g->ws_bytes = (size_t)wsb;
         }
@@ -140,6 +140,7 @@ int icnn_set_tuning(const char *name, int32_t value)
         {"no_narrow", &Tuning::no_narrow, 0, 1}, {"no_fc", &Tuning::no_fc, 0, 1},
         {"no_halo", &Tuning::no_halo, 0, 1},     {"halo_tile", &Tuning::halo_tile, 0, 2},
         {"halo_always", &Tuning::halo_always, 0, 1}, {"no_stream", &Tuning::no_stream, 0, 1},
+        {"ksplit", &Tuning::ksplit, 0, 8},
     };
     if (!strcmp(name, "reset")) {
         g_tuning = Tuning();
@@ -168,14 +169,34 @@ int iconv2d_out_hw(const icnn_conv_desc *desc, int32_t *ho, int32_t *wo)
     return ICNN_OK;
 }
 
+static int fill_conv_args(const icnn_conv_desc *d, const ConvGeom &g, const void *x, const void *w_packed,
+                          const int32_t *bias, const void *res, void *y, ConvArgs &a);
+
+// Workspace of a layer: the padded copy of a small-cin layer, or the partial accumulators of a K axis split over
+// workgroups (decided as the launch will decide, for 16-byte aligned tensors), behind the counter block.
+static int workspace_need(const icnn_conv_desc *d, const ConvGeom &g, size_t *bytes)
+{
+    *bytes = g.ws_bytes;
+    if (g.ws_bytes) return ICNN_OK;
+    ConvArgs a;
+    void *const dummy = (void *)(uintptr_t)4096;        // aligned stand-ins: only shapes and parameters matter here
+    const int rc = fill_conv_args(d, g, dummy, dummy, (const int32_t *)dummy, d->res_mode != ICNN_RES_NONE ? dummy : nullptr, dummy, a);
+    if (rc) return rc;
+    const bool vec_in = d->cin % 16 == 0 && d->in_c_stride % 16 == 0;
+    a.ws_cnt = (unsigned *)dummy;
+    a.ws_part = (int32_t *)dummy;
+    const size_t part = conv_split_bytes(a, vec_in);
+    *bytes = part ? part + kWsCounterBytes : 0;
+    return ICNN_OK;
+}
+
 int iconv2d_workspace_bytes(const icnn_conv_desc *desc, size_t *bytes)
 {
     ConvGeom g;
     const int rc = check_conv(desc, &g);
     if (rc) return rc;
     if (!bytes) return fail(ICNN_E_NULL, "bytes is NULL");
-    *bytes = g.ws_bytes;
-    return ICNN_OK;
+    return workspace_need(desc, g, bytes);
 }
 
 int iconv2d_packed_weight_bytes(const icnn_conv_desc *desc, size_t *bytes)
@@ -261,6 +282,9 @@ static int fill_conv_args(const icnn_conv_desc *d, const ConvGeom &g, const void
     a.n_tiles = a.per_xcd = a.n_vtiles = 0;
     a.pc = nullptr;
     a.pc_fast_ok = 0;
+    a.ksplit = 1;
+    a.ws_cnt = nullptr;
+    a.ws_part = nullptr;
     a.rq_fast = 0;
     a.mul_hi = 0;
     if (d->out_mode != ICNN_OUT_RAW_S32 && a.shift >= 1 && a.shift <= 32 &&
@@ -301,7 +325,7 @@ static int conv_layer(const icnn_conv_desc *d, const void *x, const void *w_pack
     int rc = check_conv(d, &g);
     if (rc) return rc;
     if (g.ws_bytes && !workspace) return fail(ICNN_E_NULL, "this layer needs a workspace (iconv2d_workspace_bytes)");
-    if (g.ws_bytes && ((uintptr_t)workspace & 3)) return fail(ICNN_E_ALIGN, "workspace must be 4-byte aligned");
+    if (workspace && ((uintptr_t)workspace & 15)) return fail(ICNN_E_ALIGN, "workspace must be 16-byte aligned");
     ConvArgs a;
     rc = fill_conv_args(d, g, x, w_packed, bias, res, y, a);
     if (rc) return rc;
@@ -316,16 +340,23 @@ static int conv_layer(const icnn_conv_desc *d, const void *x, const void *w_pack
     if (g.rp) {
         // small cin: pad and re-normalise x into the workspace, then run the layer as a kh x 1
         // convolution with "rp channels" over that copy (see pad_small_cin_kernel)
-        const hipError_t e = launch_pad_small_cin(a.x, workspace, d->n, d->h, d->w, d->cin, d->in_c_stride, d->pad_h,
+        uint8_t *padded = (uint8_t *)workspace + kWsCounterBytes;
+        const hipError_t e = launch_pad_small_cin(a.x, padded, d->n, d->h, d->w, d->cin, d->in_c_stride, d->pad_h,
                                                   d->pad_w, g.hp, g.wp, a.in_xor, (hipStream_t)stream);
         if (e != hipSuccess) return launched(e, what);
-        a.x = (const uint8_t *)workspace;
+        a.x = padded;
         a.H = g.hp; a.W = g.wp; a.Cin = g.rp; a.in_cs = 4; a.KW = 1; a.ph = 0; a.pw = 0;
         a.in_xor = 0;
-        a.x_bytes = (unsigned)(g.ws_bytes - 64);
+        a.x_bytes = (unsigned)(g.ws_bytes - 64 - kWsCounterBytes);
         return launched(launch_conv(a, true, true, (hipStream_t)stream), what);
     }
     const bool vec_in = aligned16(x) && d->cin % 16 == 0 && d->in_c_stride % 16 == 0;
+    // layers with few tiles and a long K axis split it over workgroups when the caller brought the workspace
+    // iconv2d_workspace_bytes asked for (a workspace passed to a layer that asked for none is not touched)
+    if (workspace && conv_split_bytes(a, vec_in) != 0) {
+        a.ws_cnt = (unsigned *)workspace;
+        a.ws_part = (int32_t *)((uint8_t *)workspace + kWsCounterBytes);
+    }
     return launched(launch_conv(a, vec_in, vec_in, (hipStream_t)stream), what);
 }
 
@@ -373,8 +404,10 @@ int iconv2d_brelu_static_ws(const icnn_conv_desc *d, const void *x, const void *
     if (g.ws_bytes > kStaticWsBytes)
         return fail(ICNN_E_SHAPE, "this layer needs a workspace of %zu bytes; the static one holds %zu (use iconv2d_brelu)",
                     g.ws_bytes, kStaticWsBytes);
-    void *ws = nullptr;
-    if (g.ws_bytes && (rc = static_workspace(&ws))) return rc;
+    size_t need = 0;
+    if ((rc = workspace_need(d, g, &need))) return rc;
+    void *ws = nullptr;        // a split K axis that would need more than the array holds simply stays whole
+    if (need && need <= kStaticWsBytes && (rc = static_workspace(&ws))) return rc;
     return conv_layer(d, x, w_packed, bias, nullptr, res, y, ws, stream, "iconv2d_brelu_static_ws");
 }
 

@@ -57,7 +57,7 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
     constexpr unsigned OOB = 0x80000000u;            // beyond any buffer this kernel accepts (< 2 GiB)
     static_assert(WAVES_M * WAVES_P == 4 && TM >= 1 && TP >= 1 && NB >= 1, "tile shape");
 
-    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];   // nstages * STAGE bytes
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];   // nstages * STAGE bytes (+ parameter slots) + 16
 
     // Persistent workgroups: this one handles tiles v = blockIdx.x, + gridDim.x, ...  (gridDim.x is a
     // multiple of 8, so all of them map to the same XCD, see tile_of()).
@@ -75,8 +75,9 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
     const int wm = wave % WAVES_M;
     const int wp = wave / WAVES_M;
     const int nstages = a.nstages;
-    const int ksteps = a.ksteps;
-    const int depth = min(nstages - 1, ksteps);      // stages of a tile issued ahead of its K loop
+    const int ksplit = a.ksplit;                     // K ranges per tile (1: no split); a.n_tiles counts units
+    const int ksteps = a.ksteps / ksplit;            // K steps of a unit (the host only splits evenly)
+    const int depth = min(nstages - 1, ksteps);      // stages of a unit issued ahead of its K loop
 
     const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, a.x_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)a.wp, 0, a.wp_bytes, 0x00020000);
@@ -90,6 +91,8 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
     constexpr int PC_SLOT = (PC_BYTES + 1023) & ~1023;       // whole wave-wide copies
     uint8_t *const pc_lds = lds + a.nstages * STAGE;
     int pc_slot = 0;
+    // split K: one word behind everything else tells the workgroup whether its unit arrived last
+    volatile int *const split_flag = (volatile int *)(pc_lds + (PC ? 2 * PC_SLOT : 0));
 
     // ---- state of the tile whose stages are being issued ("load side")
     // A copy q of this wave covers packed pieces [64*m, 64*m + 64), m = (4*q + wave) % A_INSTR;
@@ -127,21 +130,26 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
         kw_init = tap - kh_init * a.KW;
     }
 
-    auto tile_of = [&](int v, int &ct, int &pt) {
-        // workgroups are dealt round-robin to the 8 XCDs; XCD x owns tiles [x*per_xcd, (x+1)*per_xcd)
+    int kbase = 0;           // first K step of the unit whose stages are being issued
+    auto tile_of = [&](int v, int &ct, int &pt, int &ks) {
+        // workgroups are dealt round-robin to the 8 XCDs; XCD x owns units [x*per_xcd, (x+1)*per_xcd): the K ranges
+        // of a tile are neighbours there
         const int logical = (v & 7) * a.per_xcd + (v >> 3);
-        ct = logical % a.n_ct;
-        pt = logical / a.n_ct;
+        const int tile = ksplit == 1 ? logical : logical / ksplit;
+        ks = logical - tile * ksplit;
+        ct = tile % a.n_ct;
+        pt = tile / a.n_ct;
         return logical < a.n_tiles;
     };
 
-    auto setup_load_side = [&](int ct, int pt) {
+    auto setup_load_side = [&](int ct, int pt, int ks) {
         const int pix0 = pt * BP;
         const int chunk0 = ct * (BM / 32);
+        kbase = ks * ksteps;
 #pragma unroll
         for (int q = 0; q < NA; ++q) {
             const int e = a_lds[q] / 16 + lane;
-            a_off[q] = (unsigned)(chunk0 + (e >> 7)) * (unsigned)ksteps * kChunkBytes + (unsigned)(e & 127) * 16;
+            a_off[q] = (unsigned)(chunk0 + (e >> 7)) * (unsigned)a.ksteps * kChunkBytes + (unsigned)(e & 127) * 16;
         }
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
@@ -181,6 +189,13 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
             }
         }
         skh = skw = sc0 = 0;
+        if (MODE == 1 && kbase != 0) {       // a later K range starts inside the tap sequence
+            const int per_tap = a.Cin / kStepK;
+            const int tap = kbase / per_tap;
+            sc0 = (kbase - tap * per_tap) * kStepK;
+            skh = tap / a.KW;
+            skw = tap - skh * a.KW;
+        }
         kh = kh_init; kw = kw_init; ci = ci_init;
         if (MODE == 3) { ku = (unsigned)ls; koff = koff_of(ku); }
     };
@@ -190,15 +205,15 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
     auto issue_copy = [&](int c, int s, uint8_t *stage) {
         if (c < NA) {
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, (__attribute__((address_space(3))) void *)(stage + a_lds[c]),
-                                                     16, a_off[c], s * kChunkBytes, 0, 0);
+                                                     16, a_off[c], (kbase + s) * kChunkBytes, 0, 0);
             return;
         }
         const int j = c - NA;
         uint8_t *dst = stage + A_BYTES + (4 * j + wave) * 1024;
         if (MODE == 0) {
-            const bool kok = s * kStepK + ls * 16 < a.Cin;
+            const bool kok = (kbase + s) * kStepK + ls * 16 < a.Cin;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (__attribute__((address_space(3))) void *)dst, 16,
-                                                     kok ? b_off[j] : OOB, s * kStepK, 0, 0);
+                                                     kok ? b_off[j] : OOB, (kbase + s) * kStepK, 0, 0);
         } else if (MODE == 1) {
             const unsigned bit = 1u << (skh * a.KW + skw);
             // added per lane (not as the scalar offset): b_off may have wrapped below zero and the
@@ -247,16 +262,27 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
     const int b_rd1 = A_BYTES + b_slot_offset(wp * TP * 32 + (lane & 31), 2 + (lane >> 5));
 
     // ---- first tile: its leading stages and its bias
-    tile_of(vtile, ct, pt);
-    setup_load_side(ct, pt);
+    int ks;
+    tile_of(vtile, ct, pt, ks);
+    setup_load_side(ct, pt, ks);
     int buf = 0;        // ring slot of the next K step to compute
     int ibuf = 0;       // ring slot the next issued stage goes to
     for (int s = 0; s < depth; ++s) {
         issue_stage(s, ibuf);
         if (++ibuf == nstages) ibuf = 0;
     }
+    // accumulators start at the bias in a tile's first K range, at zero in the others
     v16i bias_next[TM];
-    load_bias_rows<TM>(a, ct * BM + wm * TM * 32, lane >> 5, bias_next);
+    auto load_unit_bias = [&](int ct_, int ks_) {
+        load_bias_rows<TM>(a, ct_ * BM + wm * TM * 32, lane >> 5, bias_next);
+        if (ks_ != 0) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) bias_next[i][r] = 0;
+        }
+    };
+    load_unit_bias(ct, ks);
 
     for (;;) {
         v16i acc[TM][TP];
@@ -267,8 +293,9 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
         // an 8-bit skip operand travels while the K loop runs
         const int co_wave = ct * BM + wm * TM * 32;
         const int pix_wave = pt * BP + wp * TP * 32;
+        const int unit_tile = ct + pt * a.n_ct, unit_ks = ks;
         v4i res8[TM][TP];
-        prefetch_res8<TM, TP>(a, co_wave, pix_wave, lane, res8);
+        if (ksplit == 1) prefetch_res8<TM, TP>(a, co_wave, pix_wave, lane, res8);
         if constexpr (PC) {
             pc_slot ^= 1;
 #pragma unroll
@@ -349,20 +376,70 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
         // ---- the next tile's leading stages and bias travel while this tile's epilogue runs.
         // They go to ring slots other than the one of the last K step, which slower waves may
         // still be reading (every wave has passed that step's barrier, so all older slots are free).
+        // ---- split K: this unit's accumulators go to the workspace; the unit that arrives last at the tile's counter
+        // adds the others' and finishes the tile.  (No spinning anywhere: a unit never waits for another.)  The partial
+        // sums travel with system-scope accesses (sc0 sc1: written through to memory, read past the caches), so they
+        // are coherent between the chip's L2 caches without any cache-wide write-back or invalidate; a store has reached
+        // memory when the wave's counter of outstanding memory operations says so.
+        bool finish = true;
+        constexpr int UNIT_BYTES = TM * TP * 4 * 256 * 16;                  // a unit's accumulators
+        const __amdgpu_buffer_rsrc_t rs_part = __builtin_amdgcn_make_buffer_rsrc((void *)a.ws_part, 0, 0x7ffffff0, 0x00020000);
+        if (ksplit > 1) {
+            const unsigned mine = (unsigned)(unit_tile * ksplit + unit_ks) * UNIT_BYTES + (wave * (TM * TP * 4 * 64) + lane) * 16;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TP; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        __builtin_amdgcn_raw_buffer_store_b128(v4i{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]},
+                                                               rs_part, mine + ((i * TP + j) * 4 + q) * 1024, 0, 17);
+            asm volatile("" ::: "memory");
+            ICNN_WAIT_VMCNT(0);
+            __syncthreads();                        // every wave's partial sums are in memory
+            if (tid == 0) {
+                const unsigned arrived = atomicAdd(a.ws_cnt + unit_tile, 1u);
+                const bool last = arrived == (unsigned)ksplit - 1;
+                if (last) a.ws_cnt[unit_tile] = 0;  // every range has arrived: ready for the next launch
+                *split_flag = last ? 1 : 0;
+            }
+            __syncthreads();
+            finish = *split_flag != 0;
+        }
+
         vtile += gridDim.x;
-        const bool more = vtile < a.n_vtiles && tile_of(vtile, ct, pt);
+        const bool more = vtile < a.n_vtiles && tile_of(vtile, ct, pt, ks);
         if (more) {
-            setup_load_side(ct, pt);
+            setup_load_side(ct, pt, ks);
             for (int s = 0; s < depth; ++s) {
                 issue_stage(s, ibuf);
                 if (++ibuf == nstages) ibuf = 0;
             }
-            load_bias_rows<TM>(a, ct * BM + wm * TM * 32, lane >> 5, bias_next);
+            load_unit_bias(ct, ks);
         }
-        if constexpr (PC)
-            epilogue_pc_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane, res8,
-                                      (const int32_t *)(pc_lds + pc_slot * PC_SLOT), co_wave - wm * TM * 32);
-        else epilogue_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane, res8);
+        if (ksplit > 1 && finish) {
+            for (int o = 0; o < ksplit; ++o) {
+                if (o == unit_ks) continue;
+                const unsigned theirs = (unsigned)(unit_tile * ksplit + o) * UNIT_BYTES + (wave * (TM * TP * 4 * 64) + lane) * 16;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TP; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const v4i v = __builtin_amdgcn_raw_buffer_load_b128(rs_part, theirs + ((i * TP + j) * 4 + q) * 1024, 0, 17);
+                            acc[i][j][4 * q] += v.x; acc[i][j][4 * q + 1] += v.y; acc[i][j][4 * q + 2] += v.z; acc[i][j][4 * q + 3] += v.w;
+                        }
+            }
+        }
+        if (finish) {
+            // (with a split K axis the skip operand was not fetched ahead: only one range in ksplit needs it)
+            if (ksplit > 1) prefetch_res8<TM, TP>(a, co_wave, pix_wave, lane, res8);
+            if constexpr (PC)
+                epilogue_pc_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane, res8,
+                                          (const int32_t *)(pc_lds + pc_slot * PC_SLOT), co_wave - wm * TM * 32);
+            else epilogue_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane, res8);
+        }
         if (!more) break;
         // This tile's stores (and the skip operands of the next) are younger than the stage copies the
         // next K loop waits for.  Loads retire in order among themselves, so a counted wait that leaves
@@ -557,17 +634,24 @@ hipError_t allow_large_lds(const void *kernel)
 }
 
 template <int BM, int BP, int WAVES_M, int WAVES_P>
-static hipError_t launch_dlds(const ConvArgs &a0, int max_stages, int per_cu, hipStream_t st)
+static hipError_t launch_dlds(const ConvArgs &a0, int max_stages, int per_cu, int ksplit, hipStream_t st)
 {
     ConvArgs a = a0;
     if (!finish_args(a, BM, BP)) return hipErrorInvalidValue;
+    a.ksplit = ksplit;
+    if (ksplit > 1) {                      // units instead of tiles
+        if (a.n_tiles > kWsMaxSplitTiles || a.ksteps % ksplit != 0 || !a.ws_cnt || !a.ws_part) return hipErrorInvalidValue;
+        a.n_tiles *= ksplit;
+        a.per_xcd = (a.n_tiles + 7) / 8;
+    }
     if (g_tuning.stages >= 2 && g_tuning.stages <= 6) max_stages = g_tuning.stages;
-    a.nstages = a.ksteps + 1 < max_stages ? a.ksteps + 1 : max_stages;
+    const int unit_steps = a.ksteps / ksplit;
+    a.nstages = unit_steps + 1 < max_stages ? unit_steps + 1 : max_stages;
     if (a.nstages < 2) a.nstages = 2;
     a.div_howo = make_fast_div((unsigned)(a.Ho * a.Wo));
     a.div_wo = make_fast_div((unsigned)a.Wo);
     // per-channel kernels keep two copies of the tile's packed parameters behind the ring
-    const size_t lds_bytes = (size_t)a.nstages * (BM + BP) * kStepK + (a.pc ? 2 * (((BM / 16) * kPcGroupInts * 4 + 1023) & ~1023) : 0);
+    const size_t lds_bytes = (size_t)a.nstages * (BM + BP) * kStepK + (a.pc ? 2 * (((BM / 16) * kPcGroupInts * 4 + 1023) & ~1023) : 0) + 16;
     const bool pw = a.KH == 1 && a.KW == 1 && a.sh == 1 && a.sw == 1 && a.ph == 0 && a.pw == 0;
     // kh x 1 kernels whose taps all lie inside the image: no masks (the padded small-cin layout)
     const bool dense = a.KW == 1 && a.ph == 0 && a.pw == 0 && (a.Ho - 1) * a.sh + a.KH <= a.H && (a.Wo - 1) * a.sw + 1 <= a.W &&
@@ -620,23 +704,23 @@ static const TileCfg kTiles[] = {
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
-static hipError_t launch_tile(int t, const ConvArgs &a, hipStream_t st)
+static hipError_t launch_tile(int t, const ConvArgs &a, int ksplit, hipStream_t st)
 {
     switch (t) {
-    case 0: return launch_dlds<32, 256, 1, 4>(a, kTiles[0].stages, kTiles[0].per_cu, st);
-    case 1: return launch_dlds<64, 128, 1, 4>(a, kTiles[1].stages, kTiles[1].per_cu, st);
-    case 2: return launch_dlds<64, 256, 1, 4>(a, kTiles[2].stages, kTiles[2].per_cu, st);
-    case 3: return launch_dlds<128, 64, 2, 2>(a, kTiles[3].stages, kTiles[3].per_cu, st);
-    default: return launch_dlds<128, 128, 2, 2>(a, kTiles[4].stages, kTiles[4].per_cu, st);
+    case 0: return launch_dlds<32, 256, 1, 4>(a, kTiles[0].stages, kTiles[0].per_cu, ksplit, st);
+    case 1: return launch_dlds<64, 128, 1, 4>(a, kTiles[1].stages, kTiles[1].per_cu, ksplit, st);
+    case 2: return launch_dlds<64, 256, 1, 4>(a, kTiles[2].stages, kTiles[2].per_cu, ksplit, st);
+    case 3: return launch_dlds<128, 64, 2, 2>(a, kTiles[3].stages, kTiles[3].per_cu, ksplit, st);
+    default: return launch_dlds<128, 128, 2, 2>(a, kTiles[4].stages, kTiles[4].per_cu, ksplit, st);
     }
 }
 
-// Estimated cycles of a launch with tile t: rounds of resident workgroups times the
-// time of one workgroup, whose K loop is bound either by the matrix cores or by
-// the L2 -> LDS traffic of its tiles (bytes per step = 64 * (bm + bp)).
-static double tile_cost(const TileCfg &c, const ConvArgs &a)
+// Estimated cycles of a launch with tile shape c and the K axis cut into ksplit ranges: rounds of resident
+// workgroups times the time of one work unit, whose K loop is bound either by the matrix cores or by the
+// L2 -> LDS traffic of its tiles (bytes per step = 64 * (bm + bp)).
+static double tile_cost(const TileCfg &c, const ConvArgs &a, int ksplit)
 {
-    const double tiles = (double)((a.Cout + c.bm - 1) / c.bm) * (double)((a.M + c.bp - 1) / c.bp);
+    const double tiles = (double)((a.Cout + c.bm - 1) / c.bm) * (double)((a.M + c.bp - 1) / c.bp) * ksplit;
     const double slots = 256.0 * c.per_cu;
     const double rounds = (double)(long long)((tiles + slots - 1) / slots);
     const double resident = tiles < slots ? (tiles / 256.0 > 1 ? tiles / 256.0 : 1) : c.per_cu;   // per CU
@@ -646,15 +730,74 @@ static double tile_cost(const TileCfg &c, const ConvArgs &a)
     const bool pointwise = a.KH == 1 && a.KW == 1 && a.sh == 1 && a.sw == 1;
     const double l2 = 64.0 * (c.bm + (pointwise ? 1.0 : 1.1) * c.bp) / 24.0;
     const double step = resident * (mfma > l2 ? mfma : l2) + 150;
-    const double fixed = 2500 + 1.5 * c.bm * c.bp / 256 * 6;               // prologue + epilogue
-    return rounds * (a.ksteps * step + fixed);
+    double fixed = 2500 + 1.5 * c.bm * c.bp / 256 * 6;                     // prologue + epilogue
+    // partial sums out, their arrival, the counter's round trip, partial sums in: measured 5 to 8 us on layers of
+    // 10 us (64 x 7 x 7 x 2048 -> 512: 16.5 us split in two against 10.8 whole; 64 x 14 x 14 x 256 -> 256 3x3 / 2:
+    // 23.6 against 12.7), whether the sums travel through memory or stay in L2: a chain of memory latencies at the
+    // end of the launch, not bandwidth
+    if (ksplit > 1) fixed += 15000;
+    return rounds * (a.ksteps / ksplit * step + fixed);
+}
+
+// Splits of the K axis the kernel can run for this layer with tile shape c: pointwise and 64-channel-aligned layers
+// only (the other addressing modes track taps per lane), even ranges of at least 8 steps, at most one unit per
+// compute unit.  Layers with few tiles and a long K loop leave most compute units idle otherwise (a 7 x 7 x
+// 512-channel layer at batch 64 has 100 tiles of 128 x 128 for 256 units); whether a split pays is the cost model's
+// business (at the workloads' sizes it does not: see tile_cost).
+static bool split_allowed(const TileCfg &c, const ConvArgs &a, int s, bool forced)
+{
+    if (s == 1) return true;
+    const bool pw = a.KH == 1 && a.KW == 1 && a.sh == 1 && a.sw == 1 && a.ph == 0 && a.pw == 0;
+    if (!(pw || (a.Cin % 64 == 0 && a.KH * a.KW <= 32)) || a.K % kStepK != 0 || a.ksteps % s != 0) return false;
+    const long long tiles = (long long)((a.Cout + c.bm - 1) / c.bm) * ((a.M + c.bp - 1) / c.bp);
+    if (tiles > kWsMaxSplitTiles) return false;
+    return forced ? a.ksteps / s >= 2 : (a.ksteps / s >= 8 && tiles * s <= 256);
+}
+
+// Tile shape and K split of the direct-to-LDS kernel for a layer: the cheapest by the cost model, or what the tuning
+// overrides ask for.  may_split: the caller brought a workspace.
+static void choose_plan(const ConvArgs &a, bool may_split, int &tile, int &ksplit)
+{
+    tile = -1;
+    ksplit = 1;
+    double best_cost = 0;
+    const int s_lo = !may_split || g_tuning.ksplit == 1 ? 1 : (g_tuning.ksplit > 1 ? g_tuning.ksplit : 1);
+    const int s_hi = !may_split || g_tuning.ksplit == 1 ? 1 : (g_tuning.ksplit > 1 ? g_tuning.ksplit : 8);
+    for (int t = 0; t < kNumTiles; ++t) {
+        if (g_tuning.tile >= 0 && g_tuning.tile < kNumTiles ? t != g_tuning.tile : (kTiles[t].bm / 2 >= a.Cout && t != 0))
+            continue;                                                      // forced shape; or more than half the cout tile empty
+        for (int s = 1; s <= s_hi; ++s) {
+            if (s > 1 && s < s_lo) continue;
+            if (!split_allowed(kTiles[t], a, s, g_tuning.ksplit > 1)) continue;
+            double c = tile_cost(kTiles[t], a, s);
+            if (s > 1 && g_tuning.ksplit > 1) c = 0;                       // a forced split wins wherever it is possible
+            if (tile < 0 || c < best_cost) { tile = t; ksplit = s; best_cost = c; }
+        }
+    }
+}
+
+static bool takes_direct(const ConvArgs &a, bool direct_ok)
+{
+    // the direct-to-LDS kernel addresses x and the packed weights with 32-bit byte offsets
+    return direct_ok && a.in_xor == 0 && a.x_bytes < 0x7fffff00u && a.wp_bytes < 0x7fffff00u && a.KH <= 31 && a.KW <= 31;
+}
+
+size_t conv_split_bytes(const ConvArgs &a, bool direct_ok)
+{
+    if (direct_ok && conv_narrow_applies(a) && !g_tuning.no_narrow) return 0;
+    if (direct_ok && conv_fc_applies(a) && !g_tuning.no_fc) return 0;
+    if (!takes_direct(a, direct_ok)) return 0;
+    if (!g_tuning.no_halo && g_tuning.tile < 0 && conv_halo_applies(a)) return 0;
+    int t, s;
+    choose_plan(a, true, t, s);
+    if (s == 1) return 0;
+    const size_t tiles = (size_t)((a.Cout + kTiles[t].bm - 1) / kTiles[t].bm) * ((a.M + kTiles[t].bp - 1) / kTiles[t].bp);
+    return tiles * s * kTiles[t].bm * kTiles[t].bp * sizeof(int32_t);
 }
 
 hipError_t launch_conv(const ConvArgs &a, bool vec_in, bool direct_ok, hipStream_t st)
 {
-    // the direct-to-LDS kernel addresses x and the packed weights with 32-bit byte offsets
-    const bool direct = direct_ok && a.in_xor == 0 && a.x_bytes < 0x7fffff00u && a.wp_bytes < 0x7fffff00u &&
-                        a.KH <= 31 && a.KW <= 31;
+    const bool direct = takes_direct(a, direct_ok);
     // one to four output channels: a lane per pixel and dot products beat tiles that are 7/8 padding
     if (direct_ok && conv_narrow_applies(a) && !g_tuning.no_narrow)
         return launch_conv_narrow(a, st);
@@ -663,16 +806,9 @@ hipError_t launch_conv(const ConvArgs &a, bool vec_in, bool direct_ok, hipStream
     // 3x3 / stride 1 / padding 1 with cin % 64 == 0: the nine taps read one LDS copy of the input
     if (direct && !g_tuning.no_halo && g_tuning.tile < 0 && conv_halo_applies(a)) return launch_conv_halo(a, st);
     if (direct) {
-        const int forced = g_tuning.tile;
-        int best = -1;
-        double best_cost = 0;
-        for (int t = 0; t < kNumTiles; ++t) {
-            if (kTiles[t].bm / 2 >= a.Cout && t != 0) continue;          // more than half the cout tile empty
-            const double c = tile_cost(kTiles[t], a);
-            if (best < 0 || c < best_cost) { best = t; best_cost = c; }
-        }
-        if (forced >= 0 && forced < kNumTiles) best = forced;
-        return launch_tile(best, a, st);
+        int tile, ksplit;
+        choose_plan(a, a.ws_part != nullptr, tile, ksplit);       // without a workspace the K axis stays whole
+        return launch_tile(tile, a, ksplit, st);
     }
     if (a.Cout <= 32) return launch_greg<32, 256, 1, 4>(a, vec_in, st);
     if (a.Cout <= 64) return launch_greg<64, 256, 1, 4>(a, vec_in, st);

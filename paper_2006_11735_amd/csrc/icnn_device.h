@@ -70,7 +70,19 @@ struct ConvArgs {
     // allow the fast epilogue form where a group's parameters do.
     const int32_t *pc;
     int pc_fast_ok;
+    // Split K: the K steps of a tile are cut into ksplit equal ranges, each its own work unit (n_tiles then counts
+    // units: unit u is range u % ksplit of tile u / ksplit).  A unit stores its int32 accumulators in ws_part; the
+    // unit that arrives last at the tile's counter (ws_cnt, zero before the launch and reset by that unit) adds the
+    // others' and runs the epilogue.  1: no split, nothing of this is touched.
+    int ksplit;
+    unsigned *ws_cnt;
+    int32_t *ws_part;
 };
+
+// Workspace layout of a convolution call: counters first (zero-filled by the caller once, left zero by every call),
+// then data (the padded copy of a small-cin layer, or the partial accumulators of a split K axis).
+constexpr size_t kWsCounterBytes = 4096;
+constexpr int kWsMaxSplitTiles = (int)(kWsCounterBytes / sizeof(unsigned));
 
 // Packed per-channel parameters, per group of 16 output channels, int32 each:
 //   [0,16) A  [16,32) L  [32,48) T  [48,64) C     requantisation of channel c, exact for every valid
@@ -143,12 +155,15 @@ struct Tuning {
     int halo_tile = 0;     // patch-resident kernel: 1 = 128 x 128, 2 = 64 x 256
     int halo_always = 0;   // patch-resident kernel also with several tiles per workgroup and short K loops
     int no_stream = 0;     // single-channel 3x3 layers: lane-group kernel instead of the streaming one
+    int ksplit = 0;        // 0 library's choice; 1 never split the K axis; 2..8 this split where it divides the K steps
 };
 extern Tuning g_tuning;
 
 // launchers (host)
 // vec_in: 16-byte pieces of x never straddle a tap (dword aligned); direct_ok: they are also 16-byte aligned
 hipError_t launch_conv(const ConvArgs &a, bool vec_in, bool direct_ok, hipStream_t st);
+// bytes of split-K partial accumulators launch_conv would use for this layer when given a workspace (0: no split)
+size_t conv_split_bytes(const ConvArgs &a, bool direct_ok);
 hipError_t launch_conv_dual(const ConvArgs &a, const ProjArgs &q, hipStream_t st);
 hipError_t allow_large_lds(const void *kernel);   // > 64 KiB of dynamic LDS, once per kernel function
 bool conv_fc_applies(const ConvArgs &a);

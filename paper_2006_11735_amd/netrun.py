@@ -135,7 +135,7 @@ class GpuNet:
         b_np = self.weights[op["name"]][1] if self.weights is not None else W.bias_tensor(op, self.seed)
         bias = torch.from_numpy(np.ascontiguousarray(b_np, dtype=np.int32)).to(self.device)
         ws_bytes = B.iconv2d_workspace_bytes(d)
-        ws = torch.empty(ws_bytes, dtype=torch.uint8, device=self.device) if ws_bytes else None
+        ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=self.device) if ws_bytes else None       # zero-filled once: its counter block
         torch.cuda.synchronize(self.device)       # w_dev may be released after the prepack ran
         if "mul_c" in cal or "res_mul_c" in cal:
             # per-output-channel requantisation: the integers go to the device as they are

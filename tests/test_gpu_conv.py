@@ -604,3 +604,76 @@ def test_random_requantisation_pairs_through_the_conv_epilogue():
                       res_shift=int(g.integers(0, 20)))
         got, want = both(x, wt, b, **kw)
         assert (got == want).all(), kw
+
+
+# ---- layers with few tiles and a long K axis split it over workgroups (partial sums through the workspace, the
+# last range to arrive finishes the tile)
+SPLIT_SHAPES = [(64, 7, 7, 2048, 512, 1, 1, 0),      # stage-4 pointwise layer of the ResNet-50 shape at batch 64: 100 tiles, 32 steps
+                (2, 7, 7, 1024, 256, 1, 1, 0),       # two tiles, ragged pixel tail
+                (4, 14, 14, 256, 256, 3, 2, 1),      # 3x3 / 2: ranges start inside the tap sequence
+                (3, 9, 9, 512, 200, 1, 1, 0),        # cout tail
+                (2, 15, 15, 128, 64, 5, 2, 2)]       # 25 steps: only a forced split of 5 divides them
+
+
+@pytest.mark.parametrize("shape", SPLIT_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("forced", [0, 2, 4, 5, 8])
+def test_split_k_axis(shape, forced):
+    from paper_2006_11735_amd import binding as B
+    n, h, w, cin, cout, k, stride, pad = shape
+    x, wt, b = make(sum(shape) + forced, n, h, w, cin, cout, k)
+    B.icnn_set_tuning("ksplit", forced)
+    try:
+        got, want = both(x, wt, b, stride=stride, pad=pad, out_mode="raw_s32")
+        assert (got == want).all()
+        sigma = 37.0 * 74 * (k * k * cin) ** 0.5
+        mul = max(1, int(round(127 / (3.0 * sigma) * (1 << 25))))
+        r = rnd(5).integers(0, 128, size=want.shape, dtype=np.uint8)
+        got, want = both(x, wt, b, stride=stride, pad=pad, mul=mul, shift=25, res=r, res_mode="pre",
+                         res_mul=int(3.0 * sigma / 127), res_shift=0)
+        assert (got == want).all() and want.max() == 127
+        got, want = both(x, wt, b, stride=stride, pad=pad, bound_q=127, res=r, res_mode="pre", **channel_params(91, cout, res=True))
+        assert (got == want).all()
+        x8 = rnd(8).integers(0, 256, size=x.shape, dtype=np.uint8)          # 8-bit activations: the bias correction joins once
+        got, want = both(x8, wt, b, stride=stride, pad=pad, out_mode="raw_s32")
+        assert (got == want).all()
+        # twice in a row through one workspace: the counters are back at zero
+        got2, _ = both(x8, wt, b, stride=stride, pad=pad, out_mode="raw_s32")
+        assert (got2 == want).all()
+    finally:
+        B.icnn_set_tuning("reset")
+
+
+def test_split_k_workspace_is_asked_for_and_optional():
+    import torch
+    from gpu_util import dev
+    from paper_2006_11735_amd import binding as B
+    d = B.conv_desc(n=64, h=7, w=7, cin=2048, in_c_stride=2048, cout=512, kh=1, kw=1, out_c_stride=512, mul=20000, shift=30)
+    assert B.iconv2d_workspace_bytes(d) == 0                 # at this size the cost model keeps the K axis whole (measured slower split)
+    B.icnn_set_tuning("ksplit", 2)
+    B.icnn_set_tuning("tile", 4)
+    try:
+        _split_workspace_checks(B, d)
+    finally:
+        B.icnn_set_tuning("reset")
+
+
+def _split_workspace_checks(B, d):
+    import torch
+    from gpu_util import dev
+    need = B.iconv2d_workspace_bytes(d)
+    assert need == 4096 + 100 * 2 * 128 * 128 * 4            # counters + two ranges of 100 tiles of 128 x 128 int32
+    x, wt, b = make(3, 64, 7, 7, 2048, 512, 1)
+    want = O.conv2d(x, wt, b, mul=20000, shift=30, bound_q=127)
+    wp = torch.zeros(B.iconv2d_packed_weight_bytes(d), dtype=torch.uint8, device="cuda:0")
+    B.iconv2d_prepack_weights(d, dev(wt), wp)
+    xd, bd = dev(x), dev(b)
+    ws = torch.zeros(need, dtype=torch.uint8, device="cuda:0")
+    for workspace in (ws, None, ws):
+        y = torch.zeros(want.shape, dtype=torch.uint8, device="cuda:0")
+        B.iconv2d_brelu(d, xd, wp, bd, None, y, workspace)
+        torch.cuda.synchronize()
+        assert (y.cpu().numpy() == want).all()
+    assert int(ws[:4096].max()) == 0                         # the counter block is left at zero
+    B.iconv2d_brelu_static_ws(d, xd, wp, bd, None, y)        # the same through the library's own array
+    torch.cuda.synchronize()
+    assert (y.cpu().numpy() == want).all()
