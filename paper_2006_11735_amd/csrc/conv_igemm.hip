@@ -41,7 +41,9 @@ namespace icnn {
 // PC: requantisation and skip rescale per output channel (epilogue_pc_tiles)
 // U8: unsigned inputs up to 255: activation fragments are XORed with 0x80 bytes (x - 128) on their way
 //     from LDS to the matrix cores (the bias rows carry the matching correction, see load_bias_rows)
-template <int BM, int BP, int WAVES_M, int WAVES_P, int MODE, bool PC, bool U8>
+// SPLIT: the K axis of a tile may be cut into ranges that run as separate work units (a.ksplit; instantiated for the
+// 128-channel tiles and modes 0 and 1 only: the bookkeeping costs scalar registers the other kernels are short of)
+template <int BM, int BP, int WAVES_M, int WAVES_P, int MODE, bool PC, bool U8, bool SPLIT = false>
 __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void conv_dlds_kernel(const ConvArgs a)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the buffer-resource type exists in the device pass only
@@ -57,7 +59,7 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
     constexpr unsigned OOB = 0x80000000u;            // beyond any buffer this kernel accepts (< 2 GiB)
     static_assert(WAVES_M * WAVES_P == 4 && TM >= 1 && TP >= 1 && NB >= 1, "tile shape");
 
-    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];   // nstages * STAGE bytes (+ parameter slots) + 16
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];   // nstages * STAGE bytes (+ parameter slots; + 16 with SPLIT)
 
     // Persistent workgroups: this one handles tiles v = blockIdx.x, + gridDim.x, ...  (gridDim.x is a
     // multiple of 8, so all of them map to the same XCD, see tile_of()).
@@ -75,8 +77,8 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
     const int wm = wave % WAVES_M;
     const int wp = wave / WAVES_M;
     const int nstages = a.nstages;
-    const int ksplit = a.ksplit;                     // K ranges per tile (1: no split); a.n_tiles counts units
-    const int ksteps = a.ksteps / ksplit;            // K steps of a unit (the host only splits evenly)
+    const int ksplit = SPLIT ? a.ksplit : 1;         // K ranges per tile (1: no split); a.n_tiles counts units
+    const int ksteps = SPLIT ? a.ksteps / ksplit : a.ksteps;       // K steps of a unit (the host only splits evenly)
     const int depth = min(nstages - 1, ksteps);      // stages of a unit issued ahead of its K loop
 
     const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, a.x_bytes, 0x00020000);
@@ -135,8 +137,8 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
         // workgroups are dealt round-robin to the 8 XCDs; XCD x owns units [x*per_xcd, (x+1)*per_xcd): the K ranges
         // of a tile are neighbours there
         const int logical = (v & 7) * a.per_xcd + (v >> 3);
-        const int tile = ksplit == 1 ? logical : logical / ksplit;
-        ks = logical - tile * ksplit;
+        const int tile = SPLIT ? logical / ksplit : logical;
+        ks = SPLIT ? logical - tile * ksplit : 0;
         ct = tile % a.n_ct;
         pt = tile / a.n_ct;
         return logical < a.n_tiles;
@@ -145,7 +147,7 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
     auto setup_load_side = [&](int ct, int pt, int ks) {
         const int pix0 = pt * BP;
         const int chunk0 = ct * (BM / 32);
-        kbase = ks * ksteps;
+        kbase = SPLIT ? ks * ksteps : 0;
 #pragma unroll
         for (int q = 0; q < NA; ++q) {
             const int e = a_lds[q] / 16 + lane;
@@ -189,7 +191,7 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
             }
         }
         skh = skw = sc0 = 0;
-        if (MODE == 1 && kbase != 0) {       // a later K range starts inside the tap sequence
+        if (SPLIT && MODE == 1 && kbase != 0) {       // a later K range starts inside the tap sequence
             const int per_tap = a.Cin / kStepK;
             const int tap = kbase / per_tap;
             sc0 = (kbase - tap * per_tap) * kStepK;
@@ -275,7 +277,7 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
     v16i bias_next[TM];
     auto load_unit_bias = [&](int ct_, int ks_) {
         load_bias_rows<TM>(a, ct_ * BM + wm * TM * 32, lane >> 5, bias_next);
-        if (ks_ != 0) {
+        if (SPLIT && ks_ != 0) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -295,7 +297,7 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
         const int pix_wave = pt * BP + wp * TP * 32;
         const int unit_tile = ct + pt * a.n_ct, unit_ks = ks;
         v4i res8[TM][TP];
-        if (ksplit == 1) prefetch_res8<TM, TP>(a, co_wave, pix_wave, lane, res8);
+        if (!SPLIT || ksplit == 1) prefetch_res8<TM, TP>(a, co_wave, pix_wave, lane, res8);
         if constexpr (PC) {
             pc_slot ^= 1;
 #pragma unroll
@@ -384,7 +386,7 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
         bool finish = true;
         constexpr int UNIT_BYTES = TM * TP * 4 * 256 * 16;                  // a unit's accumulators
         const __amdgpu_buffer_rsrc_t rs_part = __builtin_amdgcn_make_buffer_rsrc((void *)a.ws_part, 0, 0x7ffffff0, 0x00020000);
-        if (ksplit > 1) {
+        if (SPLIT && ksplit > 1) {
             const unsigned mine = (unsigned)(unit_tile * ksplit + unit_ks) * UNIT_BYTES + (wave * (TM * TP * 4 * 64) + lane) * 16;
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -417,7 +419,7 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
             }
             load_unit_bias(ct, ks);
         }
-        if (ksplit > 1 && finish) {
+        if (SPLIT && ksplit > 1 && finish) {
             for (int o = 0; o < ksplit; ++o) {
                 if (o == unit_ks) continue;
                 const unsigned theirs = (unsigned)(unit_tile * ksplit + o) * UNIT_BYTES + (wave * (TM * TP * 4 * 64) + lane) * 16;
@@ -434,7 +436,7 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
         }
         if (finish) {
             // (with a split K axis the skip operand was not fetched ahead: only one range in ksplit needs it)
-            if (ksplit > 1) prefetch_res8<TM, TP>(a, co_wave, pix_wave, lane, res8);
+            if (SPLIT && ksplit > 1) prefetch_res8<TM, TP>(a, co_wave, pix_wave, lane, res8);
             if constexpr (PC)
                 epilogue_pc_tiles<TM, TP>(a, acc, co_wave, pix_wave, lane, res8,
                                           (const int32_t *)(pc_lds + pc_slot * PC_SLOT), co_wave - wm * TM * 32);
@@ -651,7 +653,7 @@ static hipError_t launch_dlds(const ConvArgs &a0, int max_stages, int per_cu, in
     a.div_howo = make_fast_div((unsigned)(a.Ho * a.Wo));
     a.div_wo = make_fast_div((unsigned)a.Wo);
     // per-channel kernels keep two copies of the tile's packed parameters behind the ring
-    const size_t lds_bytes = (size_t)a.nstages * (BM + BP) * kStepK + (a.pc ? 2 * (((BM / 16) * kPcGroupInts * 4 + 1023) & ~1023) : 0) + 16;
+    const size_t lds_bytes = (size_t)a.nstages * (BM + BP) * kStepK + (a.pc ? 2 * (((BM / 16) * kPcGroupInts * 4 + 1023) & ~1023) : 0) + (ksplit > 1 ? 16 : 0);
     const bool pw = a.KH == 1 && a.KW == 1 && a.sh == 1 && a.sw == 1 && a.ph == 0 && a.pw == 0;
     // kh x 1 kernels whose taps all lie inside the image: no masks (the padded small-cin layout)
     const bool dense = a.KW == 1 && a.ph == 0 && a.pw == 0 && (a.Ho - 1) * a.sh + a.KH <= a.H && (a.Wo - 1) * a.sw + 1 <= a.W &&
@@ -672,6 +674,11 @@ static hipError_t launch_dlds(const ConvArgs &a0, int max_stages, int per_cu, in
     auto pick = [&](auto pc_tag, auto u8_tag) -> hipError_t {
         constexpr bool PC = decltype(pc_tag)::value;
         constexpr bool U8 = decltype(u8_tag)::value;
+        if constexpr (BM == 128) {
+            if (ksplit > 1 && mode == 0) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 0, PC, U8, true>);
+            if (ksplit > 1 && mode == 1) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 1, PC, U8, true>);
+        }
+        if (ksplit > 1) return hipErrorInvalidValue;          // split_allowed() keeps this from happening
         if (mode == 0) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 0, PC, U8>);
         if (mode == 1) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 1, PC, U8>);
         if (mode == 3) return go(conv_dlds_kernel<BM, BP, WAVES_M, WAVES_P, 3, PC, U8>);
@@ -739,8 +746,8 @@ static double tile_cost(const TileCfg &c, const ConvArgs &a, int ksplit)
     return rounds * (a.ksteps / ksplit * step + fixed);
 }
 
-// Splits of the K axis the kernel can run for this layer with tile shape c: pointwise and 64-channel-aligned layers
-// only (the other addressing modes track taps per lane), even ranges of at least 8 steps, at most one unit per
+// Splits of the K axis the kernel can run for this layer with tile shape c: 128-channel tiles, pointwise and
+// 64-channel-aligned layers only (the other addressing modes track taps per lane), even ranges of at least 8 steps, at most one unit per
 // compute unit.  Layers with few tiles and a long K loop leave most compute units idle otherwise (a 7 x 7 x
 // 512-channel layer at batch 64 has 100 tiles of 128 x 128 for 256 units); whether a split pays is the cost model's
 // business (at the workloads' sizes it does not: see tile_cost).
@@ -748,7 +755,7 @@ static bool split_allowed(const TileCfg &c, const ConvArgs &a, int s, bool force
 {
     if (s == 1) return true;
     const bool pw = a.KH == 1 && a.KW == 1 && a.sh == 1 && a.sw == 1 && a.ph == 0 && a.pw == 0;
-    if (!(pw || (a.Cin % 64 == 0 && a.KH * a.KW <= 32)) || a.K % kStepK != 0 || a.ksteps % s != 0) return false;
+    if (!(pw || (a.Cin % 64 == 0 && a.KH * a.KW <= 32)) || a.K % kStepK != 0 || a.ksteps % s != 0 || c.bm != 128) return false;
     const long long tiles = (long long)((a.Cout + c.bm - 1) / c.bm) * ((a.M + c.bp - 1) / c.bp);
     if (tiles > kWsMaxSplitTiles) return false;
     return forced ? a.ksteps / s >= 2 : (a.ksteps / s >= 8 && tiles * s <= 256);
