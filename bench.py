@@ -39,12 +39,18 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def layer_work(net, op, images, fused_proj=None, fused_block=None):
+def layer_work(net, op, images, fused_proj=None, fused_block=None, fused_pool=None):
     """Algorithmic ops and bytes of one conv launch (true sizes, input counted once).  With a
     projection fused into the launch, its ops, input and weights are added and the int32 skip
     tensor is not counted (it never exists).  With a whole bottleneck block in the launch: the ops of its
     three layers (true sizes: the recomputed halo is not work), the block input once (it is also the skip
     operand), all weights and biases, the block output; the middle tensors are not counted (they never exist)."""
+    if fused_pool is not None:
+        # convolution and the max-pool behind it in one launch: the convolution's ops; the picture, the weights and the
+        # pooled tensor as bytes (the convolution's own output never exists)
+        ops, byts, m, k = layer_work(net, op, images)
+        pn, ph, pw, pc = net["buffers"][fused_pool["dst"]]["shape"]
+        return ops, byts - m * op["cout"] + images * ph * pw * pc, m, k
     if fused_block is not None:
         o1, o2 = fused_block
         ops1, b1, m, k1 = layer_work(net, o1, images)
@@ -349,18 +355,20 @@ def main():
     rows = []
     for step, ms in zip(g.steps, layer_ms):
         kind, op = step[0], step[1]
-        if kind not in ("conv", "conv_pc", "dual", "dual_pc", "block"):
+        if kind not in ("conv", "conv_pc", "dual", "dual_pc", "block", "convpool"):
             other_ms += ms
             rows.append({"name": op["dst"], "kind": kind, "ms": ms})
             continue
         ops, byts, m, k = layer_work(net, op, images, g.fused_proj.get(op["name"]) if kind in ("dual", "dual_pc") else None,
-                                     g.fused_block.get(op["name"]) if kind == "block" else None)
+                                     g.fused_block.get(op["name"]) if kind == "block" else None,
+                                     g.fused_pool.get(op["name"]) if kind == "convpool" else None)
         conv_ops += ops
         conv_ms += ms
         conv_bytes += byts
         tops = ops / (ms * 1e-3) / 1e12
         attain = min(INT8_MFMA_PEAK_TOPS, ops / byts * HBM_PEAK_GBS / 1e3)
-        rows.append({"name": (op["name"][:-3] + "_block" if kind == "block" else op["name"]) + ("+proj" if kind in ("dual", "dual_pc") else ""), "kind": "conv", "M": m, "N": op["cout"], "K": k, "ms": ms,
+        rows.append({"name": (op["name"][:-3] + "_block" if kind == "block" else op["name"]) + ("+proj" if kind in ("dual", "dual_pc") else "") +
+                             ("+pool" if kind == "convpool" else ""), "kind": "conv", "M": m, "N": op["cout"], "K": k, "ms": ms,
                      "tops": tops, "pct_mfma_peak": 100 * tops / INT8_MFMA_PEAK_TOPS,
                      "pct_attainable": 100 * tops / attain, "gbs": byts / (ms * 1e-3) / 1e9})
     for r in rows:

@@ -259,6 +259,21 @@ int iconv2d_dual_brelu_pc(const icnn_conv_desc *main_desc, const void *x_main,
                           const int32_t *bias_proj, void *y, void *stream);
 
 /*
+ * The first layer of a classification network together with the max-pool behind it, as one launch (Sections 3.1 and
+ * 3.4.1 for the layer on the raw picture; Section 4.1 mentions the pooling layers of the integer ResNets).  Result:
+ * exactly that of
+ *     iconv2d_brelu(desc, x, w_packed, bias, NULL, t, workspace, ...);
+ *     imaxpool2d_u8(n, ho, wo, cout, pool_k, pool_stride, pool_pad, t, y, ...);
+ * without the convolution's output t or the workspace's padded copy of the picture ever existing.  y is NHWC
+ * [n, hp, wp, desc->out_c_stride] and desc->out_c_stride / out_c_offset describe y (not t).  Shapes it takes: cin <= 4,
+ * kernel 5..8 pixels wide and at most 8 high, stride 2, cout 32 or 64, an unsigned 8-bit output clamped from 0, no skip
+ * operand, unsigned (<= 127) or raw-picture (in_sub128) input, pool 3 / 2 / 1, bias and y 16-byte aligned.  Anything else
+ * returns ICNN_E_UNSUPPORTED having launched nothing, and the caller issues the two calls.
+ */
+int iconv2d_maxpool_brelu(const icnn_conv_desc *desc, int32_t pool_k, int32_t pool_stride, int32_t pool_pad,
+                          const void *x, const void *w_packed, const int32_t *bias, void *y, void *stream);
+
+/*
  * A whole identity bottleneck block of a residual network as one launch (Section 4.1: the block's layers with the
  * skip connection joining the last one before BReLU; Section 3.1 for each layer).  Result: exactly that of
  *     iconv2d_brelu(c1, x,  w1_packed, bias1, NULL, t1, ...);     // 1x1, stride 1, no padding

@@ -63,6 +63,7 @@ _lib.iconv2d_dual_brelu.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp, C.
                                     _vp, _vp]
 _lib.iconv2d_dual_brelu_pc.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp, _vp, C.POINTER(icnn_conv_desc), _vp, _vp,
                                        _vp, _vp, _vp]
+_lib.iconv2d_maxpool_brelu.argtypes = [C.POINTER(icnn_conv_desc), _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp]
 _lib.iconv2d_bottleneck_brelu.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp, C.POINTER(icnn_conv_desc), _vp, _vp,
                                           C.POINTER(icnn_conv_desc), _vp, _vp, _vp, _vp, _vp]
 _lib.iadd_rescale.argtypes = [C.POINTER(icnn_add_desc), _vp, _vp, _vp, _vp]
@@ -77,7 +78,7 @@ _lib.icnn_peak_copy.argtypes = [_vp, _vp, C.c_size_t, _vp]
 EXPORTS = ["icnn_version", "icnn_last_error", "icnn_set_tuning", "iconv2d_validate", "iconv2d_out_hw",
            "iconv2d_workspace_bytes", "iconv2d_packed_weight_bytes", "iconv2d_prepack_weights",
            "iconv2d_brelu", "iconv2d_brelu_static_ws", "iconv2d_packed_channel_params_bytes", "iconv2d_prepack_channel_params", "iconv2d_brelu_pc",
-           "iconv2d_dual_brelu", "iconv2d_dual_brelu_pc", "iconv2d_bottleneck_brelu", "iadd_rescale", "iconcat", "imaxpool2d_u8", "iavgpool_global_u8",
+           "iconv2d_dual_brelu", "iconv2d_dual_brelu_pc", "iconv2d_bottleneck_brelu", "iconv2d_maxpool_brelu", "iadd_rescale", "iconcat", "imaxpool2d_u8", "iavgpool_global_u8",
            "irenormalize_u8", "icnn_peak_mfma_i8", "icnn_peak_copy"]
 
 
@@ -213,6 +214,11 @@ def iconv2d_dual_brelu_pc(main_desc, x_main, w_main_packed, bias_main, pc_packed
     return _check(_lib.iconv2d_dual_brelu_pc(C.byref(main_desc), _ptr(x_main), _ptr(w_main_packed), _ptr(bias_main),
                                              _ptr(pc_packed_main), C.byref(proj_desc), _ptr(x_proj), _ptr(w_proj_packed),
                                              _ptr(bias_proj), _ptr(y), _stream(stream)))
+
+
+def iconv2d_maxpool_brelu(desc, pool_k, pool_stride, pool_pad, x, w_packed, bias, y, stream=None):
+    return _check(_lib.iconv2d_maxpool_brelu(C.byref(desc), pool_k, pool_stride, pool_pad, _ptr(x), _ptr(w_packed), _ptr(bias),
+                                             _ptr(y), _stream(stream)))
 
 
 def iconv2d_bottleneck_brelu(c1, x, w1_packed, bias1, c2, w2_packed, bias2, c3, w3_packed, bias3, res, y, stream=None):

@@ -524,6 +524,32 @@ int iconv2d_dual_brelu_pc(const icnn_conv_desc *m, const void *x_main, const voi
                       "iconv2d_dual_brelu_pc");
 }
 
+int iconv2d_maxpool_brelu(const icnn_conv_desc *d, int32_t pool_k, int32_t pool_stride, int32_t pool_pad, const void *x,
+                          const void *w_packed, const int32_t *bias, void *y, void *stream)
+{
+    ConvGeom g;
+    int rc = check_conv(d, &g);
+    if (rc) return rc;
+    if (pool_k < 1 || pool_stride < 1 || pool_pad < 0 || pool_pad >= pool_k || g.ho + 2 * pool_pad < pool_k || g.wo + 2 * pool_pad < pool_k)
+        return fail(ICNN_E_SHAPE, "bad max-pool geometry");
+    if (pool_k != 3 || pool_stride != 2 || pool_pad != 1)
+        return fail(ICNN_E_UNSUPPORTED, "fused first layer takes a 3x3 / stride 2 / padding 1 max-pool only");
+    if (d->cin > 4 || g.rp != 32 || d->kh > 8 || d->stride_h != 2 || d->stride_w != 2 || (d->cout != 32 && d->cout != 64))
+        return fail(ICNN_E_UNSUPPORTED, "fused first layer needs cin <= 4, a kernel 5 to 8 pixels wide and at most 8 high, stride 2 and 32 or 64 output channels");
+    if ((d->out_mode != ICNN_OUT_BRELU_U8 && d->out_mode != ICNN_OUT_CLAMP_U8) || d->res_mode != ICNN_RES_NONE ||
+        d->in_signed == ICNN_IN_U8_FULL || d->in_signed == ICNN_IN_S8)
+        return fail(ICNN_E_UNSUPPORTED, "fused first layer stores unsigned bytes, takes no skip operand and unsigned or raw-picture input");
+    if (d->out_mode == ICNN_OUT_CLAMP_U8 && d->lo != 0)
+        return fail(ICNN_E_UNSUPPORTED, "fused first layer needs a lower clamp of 0 (the pool's padding is zero)");
+    ConvArgs a;
+    if ((rc = fill_conv_args(d, g, x, w_packed, bias, nullptr, y, a))) return rc;
+    if (!a.vec_out || !a.vec_bias) return fail(ICNN_E_UNSUPPORTED, "fused first layer needs 16-byte aligned output and bias");
+    const unsigned long long xb = ((unsigned long long)d->n * d->h * d->w - 1) * d->in_c_stride + d->cin;
+    if (xb > 0x7fffffffull || g.M > 0x7fffffffLL) return fail(ICNN_E_UNSUPPORTED, "fused first layer needs tensors below 2 GiB");
+    const int hp = (g.ho + 2 * pool_pad - pool_k) / pool_stride + 1, wp = (g.wo + 2 * pool_pad - pool_k) / pool_stride + 1;
+    return launched(launch_conv_stem_pool(a, hp, wp, (hipStream_t)stream), "iconv2d_maxpool_brelu");
+}
+
 int iconv2d_bottleneck_brelu(const icnn_conv_desc *c1, const void *x, const void *w1_packed, const int32_t *bias1,
                              const icnn_conv_desc *c2, const void *w2_packed, const int32_t *bias2,
                              const icnn_conv_desc *c3, const void *w3_packed, const int32_t *bias3, const void *res,

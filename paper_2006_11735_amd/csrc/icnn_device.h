@@ -170,6 +170,7 @@ bool conv_fc_applies(const ConvArgs &a);
 hipError_t launch_conv_fc(const ConvArgs &a, hipStream_t st);
 bool conv_halo_applies(const ConvArgs &a);
 hipError_t launch_conv_halo(const ConvArgs &a, hipStream_t st);
+hipError_t launch_conv_stem_pool(const ConvArgs &a, int hp, int wp, hipStream_t st);
 bool conv_block_tile(int H, int W, BlockArgs &g);
 size_t conv_block_lds_bytes(int mid, int c);
 hipError_t launch_conv_block(const BlockArgs &g, const ConvArgs &a1, const ConvArgs &a2, const ConvArgs &a3, hipStream_t st);

@@ -39,6 +39,7 @@ class GpuNet:
         self.fused = []                     # names of int32 skip buffers that are never written
         self.fused_proj = {}                # main conv name -> the projection op fused into it
         self.fused_block = {}               # last conv name -> (first, middle) conv ops fused into its launch
+        self.fused_pool = {}                # first conv name -> the max-pool op fused into its launch
         pending = {}                        # skip buffer name -> prepared projection step
         for op in net["ops"]:
             if op["op"] == "conv":
@@ -70,7 +71,42 @@ class GpuNet:
                 raise ValueError(op["op"])
         if fuse if fuse_blocks is None else fuse_blocks:
             self._fuse_blocks()
+            self._fuse_first_layer()
         torch.cuda.synchronize(self.device)
+
+    def _fuse_first_layer(self):
+        """A picture convolution followed by the max-pool of its output, nothing else reading that output: one
+        iconv2d_maxpool_brelu launch where the library accepts it (the convolution's buffer then stays untouched)."""
+        readers = {}
+        for op in self.net["ops"]:
+            readers.setdefault(op["src"], []).append(op)
+            if op.get("res") is not None:
+                readers.setdefault(op["res"], []).append(op)
+        steps, i = [], 0
+        while i < len(self.steps):
+            pair = self.steps[i:i + 2]
+            if len(pair) == 2 and pair[0][0] == "conv" and pair[1][0] == "maxpool":
+                oc, op_ = pair[0][1], pair[1][1]
+                if op_["src"] == oc["dst"] and readers.get(oc["dst"]) == [op_] and oc["dst"] not in self.net["outputs"]:
+                    d, x, wp, bias, _res, _y, _ws = pair[0][2]
+                    dd = B.conv_desc(**{k: getattr(d, k) for k, _ in d._fields_})
+                    pooled = self.buf[op_["dst"]]
+                    dd.out_c_stride, dd.out_c_offset = pooled.shape[3], 0
+                    args = (dd, op_["k"], op_["stride"], op_["pad"], x, wp, bias, pooled)
+                    try:
+                        B.iconv2d_maxpool_brelu(*args)
+                    except B.IcnnError as e:
+                        if e.code != B.ICNN_E_UNSUPPORTED:
+                            raise
+                    else:
+                        self.fused.append(oc["dst"])
+                        self.fused_pool[oc["name"]] = op_
+                        steps.append(("convpool", oc, args))
+                        i += 2
+                        continue
+            steps.append(self.steps[i])
+            i += 1
+        self.steps = steps
 
     def _fuse_blocks(self):
         """Replaces every run of three per-layer conv steps that forms an identity bottleneck block by one fused step."""
@@ -197,6 +233,8 @@ class GpuNet:
             B.iconv2d_dual_brelu_pc(*args, stream=stream)
         elif kind == "block":
             B.iconv2d_bottleneck_brelu(*args, stream=stream)
+        elif kind == "convpool":
+            B.iconv2d_maxpool_brelu(*args, stream=stream)
         elif kind == "maxpool":
             B.imaxpool2d_u8(*args, stream=stream)
         else:

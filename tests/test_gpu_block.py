@@ -132,3 +132,54 @@ def test_fused_block_refuses_other_shapes():
         with pytest.raises(B.IcnnError) as e:
             B.iconv2d_bottleneck_brelu(d1, 4096, 8192, 12288, d2, 16384, 20480, d3, 24576, 28672, None, 32768, stream=0)
         assert e.value.code in (B.ICNN_E_UNSUPPORTED, B.ICNN_E_SHAPE), over
+
+
+# ---- first layer + max-pool as one launch
+STEMS = [
+    # n, h, w, cin, cout, k, pad
+    (2, 224, 224, 3, 64, 7, 3),      # the ResNet stem
+    (3, 37, 41, 3, 64, 7, 3),        # ragged pooled tiles, odd sizes
+    (1, 64, 64, 1, 32, 5, 2),        # one channel, 5x5, 32 output channels
+    (2, 19, 150, 4, 64, 8, 3),       # four channels, even kernel
+    (1, 7, 9, 3, 64, 7, 3),          # picture smaller than a tile
+    (70, 32, 32, 3, 64, 7, 3),       # more tiles than resident workgroups
+]
+
+
+@pytest.mark.parametrize("shape", STEMS, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("raw", [True, False])
+def test_first_layer_with_pool_equals_the_two_calls(shape, raw):
+    from gpu_util import dev
+    from paper_2006_11735_amd import binding as B
+    n, h, w, cin, cout, k, pad = shape
+    g = rnd(sum(shape) + raw)
+    x = g.integers(0, 256 if raw else 128, size=(n, h, w, cin), dtype=np.uint8)
+    wt = g.integers(-127, 128, size=(cout, k, k, cin), dtype=np.int8)
+    b = g.integers(-4096, 4097, size=cout).astype(np.int32)
+    t_raw = O.conv2d(x, wt, b, stride=2, pad=pad, in_sub128=raw, out_mode="raw_s32")
+    mul, shift = K.bound_params(K.percentile_999(t_raw))
+    t = O.conv2d(x, wt, b, stride=2, pad=pad, in_sub128=raw, mul=mul, shift=shift, bound_q=127)
+    want = O.maxpool2d(t, 3, 2, 1)
+    d = B.conv_desc(n=n, h=h, w=w, cin=cin, in_c_stride=cin, in_sub128=int(raw), cout=cout, kh=k, kw=k, stride_h=2, stride_w=2,
+                    pad_h=pad, pad_w=pad, out_c_stride=cout + 16, out_c_offset=16, mul=mul, shift=shift, bound_q=127)
+    wp = torch.zeros(B.iconv2d_packed_weight_bytes(d), dtype=torch.uint8, device="cuda:0")
+    B.iconv2d_prepack_weights(d, dev(wt), wp)
+    y = torch.full((n,) + want.shape[1:3] + (cout + 16,), 99, dtype=torch.uint8, device="cuda:0")
+    B.iconv2d_maxpool_brelu(d, 3, 2, 1, dev(x), wp, dev(b), y)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy()
+    assert (got[..., 16:] == want).all(), "%d of %d bytes differ" % (int((got[..., 16:] != want).sum()), want.size)
+    assert (got[..., :16] == 99).all() and want.max() == 127
+
+
+def test_first_layer_with_pool_refuses_other_shapes():
+    from paper_2006_11735_amd import binding as B
+    base = dict(n=1, h=32, w=32, cin=3, in_c_stride=3, cout=64, kh=7, kw=7, stride_h=2, stride_w=2, pad_h=3, pad_w=3,
+                out_c_stride=64, mul=20000, shift=24)
+    for over, pool in ((dict(cin=16, in_c_stride=16), (3, 2, 1)), (dict(kw=3, kh=3, pad_h=1, pad_w=1), (3, 2, 1)),
+                       (dict(stride_h=1, stride_w=1), (3, 2, 1)), (dict(cout=128, out_c_stride=128), (3, 2, 1)), ({}, (2, 2, 0)),
+                       (dict(out_mode=B.ICNN_OUT_RAW_S32), (3, 2, 1))):
+        d = B.conv_desc(**dict(base, **over))
+        with pytest.raises(B.IcnnError) as e:
+            B.iconv2d_maxpool_brelu(d, *pool, 4096, 8192, 12288, 16384, stream=0)
+        assert e.value.code == B.ICNN_E_UNSUPPORTED, (over, pool)

@@ -133,8 +133,9 @@ def test_config3_resnet50_full_batch_sampled_images():
                 continue
             got = g.buf[name][img:img + 1].cpu().numpy()
             assert (got == want[name]).all(), (img, name)
-    # four projection blocks and the five identity blocks of stages 1 and 2 run as single launches
-    assert len(g.fused_proj) == 4 and len(g.fused_block) == 5 and len(g.fused) == 4 + 2 * 5
+    # the first layer with its pool, four projection blocks and the five identity blocks of stages 1 and 2 run as
+    # single launches
+    assert len(g.fused_proj) == 4 and len(g.fused_block) == 5 and len(g.fused_pool) == 1 and len(g.fused) == 4 + 2 * 5 + 1
     logits = g.result("logits")
     assert logits.dtype == np.int32 and logits.shape == (64, 1, 1, 1000)
 
@@ -203,9 +204,12 @@ def test_config5_resnet18_full_batch_sampled_images():
     for img in (3, 60):
         want = ONet.run(net, 0, calib, images=1, x_raw=np.ascontiguousarray(x[img:img + 1]))
         for name in net["buffers"]:
+            if name in g.fused:
+                continue
             got = g.buf[name][img:img + 1].cpu().numpy()
             assert (got == want[name]).all(), (img, name)
-    assert not g.fused
+    # only the first layer's output stays on chip (fused with its max-pool)
+    assert len(g.fused_pool) == 1 and len(g.fused) == 1 and not g.fused_block and not g.fused_proj
 
 
 def test_config6_vrcnn_2560x1600_frame():
