@@ -39,12 +39,18 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def layer_work(net, op, images, fused_proj=None, fused_block=None, fused_pool=None):
+def layer_work(net, op, images, fused_proj=None, fused_block=None, fused_pool=None, fused_pair=None):
     """Algorithmic ops and bytes of one conv launch (true sizes, input counted once).  With a
     projection fused into the launch, its ops, input and weights are added and the int32 skip
     tensor is not counted (it never exists).  With a whole bottleneck block in the launch: the ops of its
     three layers (true sizes: the recomputed halo is not work), the block input once (it is also the skip
     operand), all weights and biases, the block output; the middle tensors are not counted (they never exist)."""
+    if fused_pair is not None:
+        # two pointwise layers in one launch: both layers' ops; the first layer's input, skip operand and output, both
+        # layers' weights, the second layer's output (the second layer's input is not read back from memory)
+        ops3, b3, m, k3 = layer_work(net, op, images)
+        ops1, b1, _, k1 = layer_work(net, fused_pair, images)
+        return ops3 + ops1, b3 + b1 - m * op["cout"], m, k3 + k1
     if fused_pool is not None:
         # convolution and the max-pool behind it in one launch: the convolution's ops; the picture, the weights and the
         # pooled tensor as bytes (the convolution's own output never exists)
@@ -355,20 +361,21 @@ def main():
     rows = []
     for step, ms in zip(g.steps, layer_ms):
         kind, op = step[0], step[1]
-        if kind not in ("conv", "conv_pc", "dual", "dual_pc", "block", "convpool"):
+        if kind not in ("conv", "conv_pc", "dual", "dual_pc", "block", "convpool", "pair"):
             other_ms += ms
             rows.append({"name": op["dst"], "kind": kind, "ms": ms})
             continue
         ops, byts, m, k = layer_work(net, op, images, g.fused_proj.get(op["name"]) if kind in ("dual", "dual_pc") else None,
                                      g.fused_block.get(op["name"]) if kind == "block" else None,
-                                     g.fused_pool.get(op["name"]) if kind == "convpool" else None)
+                                     g.fused_pool.get(op["name"]) if kind == "convpool" else None,
+                                     g.fused_pair.get(op["name"]) if kind == "pair" else None)
         conv_ops += ops
         conv_ms += ms
         conv_bytes += byts
         tops = ops / (ms * 1e-3) / 1e12
         attain = min(INT8_MFMA_PEAK_TOPS, ops / byts * HBM_PEAK_GBS / 1e3)
         rows.append({"name": (op["name"][:-3] + "_block" if kind == "block" else op["name"]) + ("+proj" if kind in ("dual", "dual_pc") else "") +
-                             ("+pool" if kind == "convpool" else ""), "kind": "conv", "M": m, "N": op["cout"], "K": k, "ms": ms,
+                             ("+pool" if kind == "convpool" else "") + ("+next_c1" if kind == "pair" else ""), "kind": "conv", "M": m, "N": op["cout"], "K": k, "ms": ms,
                      "tops": tops, "pct_mfma_peak": 100 * tops / INT8_MFMA_PEAK_TOPS,
                      "pct_attainable": 100 * tops / attain, "gbs": byts / (ms * 1e-3) / 1e9})
     for r in rows:
@@ -408,7 +415,7 @@ def main():
         "conv_tops": conv_tops,
         "pct_int8_mfma_peak": 100 * conv_tops / INT8_MFMA_PEAK_TOPS,
         "whole_step_tops": conv_ops / (ms_per_step * 1e-3) / 1e12,
-        "roofline": {"kernel": "conv kernels (all %d conv launches of a step: conv_dlds / conv_halo / conv_dual / conv_greg, every tile shape)" % n_conv,
+        "roofline": {"kernel": "conv kernels (all %d conv launches of a step: conv_dlds / conv_halo / conv_dual / conv_block / conv_pair / conv_stem_pool, every tile shape)" % n_conv,
                      "bound": "mfma", "achieved": conv_tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": conv_tops / INT8_MFMA_PEAK_TOPS, "traffic": traffic, "traffic_stale": traffic_stale,
                      "peak_measured": peak_tops, "frac_of_peak_measured": conv_tops / peak_tops,

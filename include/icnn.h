@@ -294,6 +294,24 @@ int iconv2d_bottleneck_brelu(const icnn_conv_desc *c1, const void *x, const void
                              void *y, void *stream);
 
 /*
+ * Two pointwise layers as one launch: the 1x1 convolution that closes a residual block, skip operand merged in its
+ * epilogue (Section 4.1; Section 3.1 for each layer), and the 1x1 convolution that opens the next block and reads
+ * that result.  Result: exactly that of
+ *     iconv2d_brelu(c3, t, w3_packed, bias3, res,  y, ...);       // 1x1, stride 1, no padding
+ *     iconv2d_brelu(c1, y, w1_packed, bias1, NULL, z, ...);       // 1x1, stride 1, no padding
+ * Both y and z are written (y is the next block's skip operand); the second layer multiplies y out of on-chip
+ * memory instead of reading it back.  Shapes it takes: c3->cin = c1->cout in {64, 128, 256}; c3->cout = c1->cin a
+ * multiple of 256 up to 2048; c3 stores unsigned bytes bounded by at most 127 from a lower clamp of 0 and takes
+ * either no skip operand or an unsigned 8-bit one joined before requantisation whose rescale fits 32 bits; c1
+ * stores unsigned bytes and takes no skip operand; inputs ICNN_IN_U8_LE127; t, res, y, z, the bias arrays and all
+ * pitches 16-byte aligned.  c1->in_c_stride is not used (y's layout is c3's output layout).  Anything else returns
+ * ICNN_E_UNSUPPORTED having launched nothing, and the caller issues the two layers separately.
+ */
+int iconv2d_pair_brelu(const icnn_conv_desc *c3, const void *t, const void *w3_packed, const int32_t *bias3, const void *res,
+                       void *y, const icnn_conv_desc *c1, const void *w1_packed, const int32_t *bias1, void *z,
+                       void *stream);
+
+/*
  * Rescaled feature-map addition (ratio synchronisation between feature maps,
  * Sections 3.4.2 and 4.1), as a stand-alone pass over memory:
  *   T   = sat32(a + [b * b_mul / 2^b_shift])

@@ -604,6 +604,45 @@ int iconv2d_bottleneck_brelu(const icnn_conv_desc *c1, const void *x, const void
     return launched(launch_conv_block(b, a1, a2, a3, (hipStream_t)stream), "iconv2d_bottleneck_brelu");
 }
 
+int iconv2d_pair_brelu(const icnn_conv_desc *c3, const void *t, const void *w3_packed, const int32_t *bias3, const void *res,
+                       void *y, const icnn_conv_desc *c1, const void *w1_packed, const int32_t *bias1, void *z, void *stream)
+{
+    ConvGeom g3, g1;
+    int rc = check_conv(c3, &g3);
+    if (rc) return rc;
+    if ((rc = check_conv(c1, &g1))) return rc;
+    for (const icnn_conv_desc *d : {c3, c1}) {
+        if (d->n != c3->n || d->h != c3->h || d->w != c3->w) return fail(ICNN_E_SHAPE, "the two layers of a pair must share n, h, w");
+        if (d->kh != 1 || d->kw != 1 || d->pad_h || d->pad_w || d->stride_h != 1 || d->stride_w != 1)
+            return fail(ICNN_E_UNSUPPORTED, "fused pair is two 1x1 layers of stride 1 without padding");
+        if (d->in_signed != ICNN_IN_U8_LE127 || d->in_sub128)
+            return fail(ICNN_E_UNSUPPORTED, "fused pair takes unsigned inputs up to 127 only");
+        if (d->out_mode != ICNN_OUT_BRELU_U8 && d->out_mode != ICNN_OUT_CLAMP_U8)
+            return fail(ICNN_E_UNSUPPORTED, "both layers of a fused pair store unsigned bytes");
+    }
+    if (c1->cin != c3->cout || c1->cout != c3->cin) return fail(ICNN_E_SHAPE, "the widths of the two layers do not match");
+    if ((c3->cin != 64 && c3->cin != 128 && c3->cin != 256) || c3->cout % 256 != 0 || c3->cout > 2048)
+        return fail(ICNN_E_UNSUPPORTED, "fused pair needs a narrow width of 64, 128 or 256 and a wide one that is a multiple of 256 up to 2048");
+    if ((c3->out_mode == ICNN_OUT_BRELU_U8 ? c3->bound_q : c3->hi) > 127 || (c3->out_mode == ICNN_OUT_CLAMP_U8 && c3->lo != 0))
+        return fail(ICNN_E_UNSUPPORTED, "the first layer of a fused pair must store bytes in 0..127 (the second reads them as signed)");
+    if (c1->res_mode != ICNN_RES_NONE) return fail(ICNN_E_UNSUPPORTED, "the second layer of a fused pair takes no skip operand");
+    if (c1->out_mode == ICNN_OUT_CLAMP_U8 && c1->lo != 0) return fail(ICNN_E_UNSUPPORTED, "fused pair needs a lower clamp of 0");
+    if (!aligned16(t) || c3->in_c_stride % 16 != 0) return fail(ICNN_E_UNSUPPORTED, "fused pair needs a 16-byte aligned input");
+    ConvArgs a3, a1;
+    if ((rc = fill_conv_args(c3, g3, t, w3_packed, bias3, res, y, a3))) return rc;
+    if ((rc = fill_conv_args(c1, g1, y, w1_packed, bias1, nullptr, z, a1))) return rc;
+    if (!a3.epi_vec || !a1.epi_vec) return fail(ICNN_E_UNSUPPORTED, "fused pair needs 16-byte aligned output and skip tensors");
+    if (!a3.vec_bias || !a1.vec_bias) return fail(ICNN_E_UNSUPPORTED, "fused pair needs 16-byte aligned bias arrays");
+    // skip operand kinds the byte epilogue covers: none, or unsigned 8-bit joined before requantisation in 32 bits
+    if (a3.epi_mode / 4 == 2) return fail(ICNN_E_UNSUPPORTED, "fused pair takes an unsigned 8-bit skip operand joined before requantisation");
+    if (a3.x_bytes >= 0x7fffff00u || g3.M > 0x7fffffffLL - 64 ||
+        (unsigned long long)g3.M * c3->out_c_stride >= 0x7fffff00ull ||
+        (c3->res_mode != ICNN_RES_NONE && (unsigned long long)g3.M * c3->res_c_stride >= 0x7fffff00ull))
+        return fail(ICNN_E_UNSUPPORTED, "fused pair needs tensors below 2 GiB");
+    if (conv_pair_lds_bytes(c3->cout, c1->cout) > 160 * 1024) return fail(ICNN_E_UNSUPPORTED, "the tile of the wide tensor does not fit the on-chip memory");
+    return launched(launch_conv_pair(a3, a1, g3.M, (hipStream_t)stream), "iconv2d_pair_brelu");
+}
+
 int iadd_rescale(const icnn_add_desc *d, const void *a, const void *b, void *out, void *stream)
 {
     if (!d) return fail(ICNN_E_NULL, "add descriptor is NULL");

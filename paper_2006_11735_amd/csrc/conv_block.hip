@@ -30,38 +30,12 @@
 // barrier that follows phase 1's epilogue.
 #include "conv_common.h"
 
-#include <type_traits>
-
 namespace icnn {
 
 constexpr int kBlkRows = 160;        // patch rows: five pixel groups of 32
 constexpr int kBlkPix = 128;         // output pixel slots of a tile: four groups
 constexpr int kBlkStages = 6;        // weight ring
 [[maybe_unused]] constexpr int kBlkDepth = kBlkStages - 1;      // stages issued ahead of the step being multiplied
-
-// fn(integral_constant<int, 0>) ... fn(integral_constant<int, N - 1>): a loop the compiler cannot leave rolled
-// (register arrays indexed inside it stay in registers)
-template <int N, class F>
-__device__ __forceinline__ void static_for(F &&fn)
-{
-    if constexpr (N > 0) {
-        static_for<N - 1>(fn);
-        fn(std::integral_constant<int, N - 1>{});
-    }
-}
-
-// sixteen consecutive int32 of the bias table in LDS
-__device__ __forceinline__ v16i bias16(const int32_t *tab)
-{
-    const v4i *bp = (const v4i *)tab;
-    v16i b;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const v4i v = bp[q];
-        b[4 * q] = v.x; b[4 * q + 1] = v.y; b[4 * q + 2] = v.z; b[4 * q + 3] = v.w;
-    }
-    return b;
-}
 
 // Development aid, compiled in with -DICNN_BLOCK_TRACE only: multiply wave 0 of one workgroup stamps the clock
 // at the marked points; icnn_debug_trace() copies the stamps out.

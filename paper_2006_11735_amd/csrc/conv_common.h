@@ -441,6 +441,50 @@ __device__ __forceinline__ void epilogue_px16(const ConvArgs &a, const v16i &acc
     default: break;
     }
 }
+// The same arithmetic as epilogue_px16 for a layer that stores unsigned bytes and whose skip operand, if any, is
+// the unsigned 8-bit kind joined before requantisation (RES 0 or 1, RQ 1, 2 or 3): the sixteen bytes are returned,
+// for callers that keep the result on chip as well.
+template <int RES>
+__device__ __forceinline__ v4i epilogue_bytes16(const ConvArgs &a, const v16i &acc, const v4i &res8)
+{
+    int t[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t[r] = acc[r];
+    if (RES == 1) {
+        const int wd[4] = {res8.x, res8.y, res8.z, res8.w};
+        const int half = (1 << a.res_shift) >> 1;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const uint32_t b8 = ((uint32_t)wd[r >> 2] >> ((r & 3) * 8)) & 0xffu;
+            t[r] = __builtin_elementwise_add_sat(t[r], (int)((__umul24(b8, (uint32_t)a.res_mul) + (uint32_t)half) >> a.res_shift));
+        }
+    }
+    return requant16_any(a, t);
+}
+// fn(integral_constant<int, 0>) ... fn(integral_constant<int, N - 1>): a loop the compiler cannot leave rolled
+// (register arrays indexed inside it stay in registers)
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&fn)
+{
+    if constexpr (N > 0) {
+        static_for<N - 1>(fn);
+        fn(std::integral_constant<int, N - 1>{});
+    }
+}
+
+// sixteen consecutive int32 of the bias table in LDS
+__device__ __forceinline__ v16i bias16(const int32_t *tab)
+{
+    const v4i *bp = (const v4i *)tab;
+    v16i b;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const v4i v = bp[q];
+        b[4 * q] = v.x; b[4 * q + 1] = v.y; b[4 * q + 2] = v.z; b[4 * q + 3] = v.w;
+    }
+    return b;
+}
+
 // for callers without a K loop to hide the fetch behind: fetch, then finish
 template <int TM, int TP>
 __device__ __forceinline__ void epilogue_tiles(const ConvArgs &a, const v16i (&acc)[TM][TP], int co_wave, int pix_wave,

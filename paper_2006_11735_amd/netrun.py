@@ -40,6 +40,7 @@ class GpuNet:
         self.fused_proj = {}                # main conv name -> the projection op fused into it
         self.fused_block = {}               # last conv name -> (first, middle) conv ops fused into its launch
         self.fused_pool = {}                # first conv name -> the max-pool op fused into its launch
+        self.fused_pair = {}                # block-closing conv name -> the next block's opening conv op in its launch
         pending = {}                        # skip buffer name -> prepared projection step
         for op in net["ops"]:
             if op["op"] == "conv":
@@ -72,6 +73,7 @@ class GpuNet:
         if fuse if fuse_blocks is None else fuse_blocks:
             self._fuse_blocks()
             self._fuse_first_layer()
+            self._fuse_pairs()
         torch.cuda.synchronize(self.device)
 
     def _fuse_first_layer(self):
@@ -102,6 +104,41 @@ class GpuNet:
                         self.fused.append(oc["dst"])
                         self.fused_pool[oc["name"]] = op_
                         steps.append(("convpool", oc, args))
+                        i += 2
+                        continue
+            steps.append(self.steps[i])
+            i += 1
+        self.steps = steps
+
+    # The fused pair streams both layers' weights through every workgroup's 64-pixel tile: it wins where the tiles
+    # fit the chip in about one round and the wide tensor is at most 1024 channels (measured at batch 64: 17.6 us
+    # against 23.8 us for 12544 pixels of 256 -> 1024 -> 256; level at 50176 pixels of 128 -> 512 -> 128; a loss,
+    # 22.9 us against 19.0 us, at 3136 pixels of 512 -> 2048 -> 512).
+    PAIR_MAX_PIXELS = 64 * 512
+    PAIR_MAX_WIDE = 1024
+
+    def _fuse_pairs(self):
+        """The 1x1 convolution that closes a block followed by the 1x1 convolution that opens the next one: one
+        iconv2d_pair_brelu launch where the library accepts it and the shape is one the fused kernel wins on.  Both
+        outputs are still written (the first is the next block's skip operand)."""
+        steps, i = [], 0
+        while i < len(self.steps):
+            two = self.steps[i:i + 2]
+            if len(two) == 2 and two[0][0] == "conv" and two[1][0] == "conv":
+                o3, o1 = two[0][1], two[1][1]
+                (d3, t, w3, b3, res, y, _ws3), (d1, _y, w1, b1, _r1, z, _ws1) = two[0][2], two[1][2]
+                if (o1["src"] == o3["dst"] and o3["kh"] == 1 and o1["kh"] == 1 and o3["dst_c_offset"] == 0 and
+                        o1["cout"] == o3["cin"] and o1["cin"] == o3["cout"] and
+                        d3.n * d3.h * d3.w <= self.PAIR_MAX_PIXELS and o3["cout"] <= self.PAIR_MAX_WIDE):
+                    args = (d3, t, w3, b3, res, y, d1, w1, b1, z)
+                    try:
+                        B.iconv2d_pair_brelu(*args)                # also a warm-up launch
+                    except B.IcnnError as e:
+                        if e.code != B.ICNN_E_UNSUPPORTED:
+                            raise
+                    else:
+                        self.fused_pair[o3["name"]] = o1
+                        steps.append(("pair", o3, args))
                         i += 2
                         continue
             steps.append(self.steps[i])
@@ -231,6 +268,8 @@ class GpuNet:
             B.iconv2d_dual_brelu(*args, stream=stream)
         elif kind == "dual_pc":
             B.iconv2d_dual_brelu_pc(*args, stream=stream)
+        elif kind == "pair":
+            B.iconv2d_pair_brelu(*args, stream=stream)
         elif kind == "block":
             B.iconv2d_bottleneck_brelu(*args, stream=stream)
         elif kind == "convpool":
