@@ -206,25 +206,25 @@ def other_bandwidth(torch, copy_gbs):
         log("%-38s %6.1f MB: cold %6.1f us, %5.0f GB/s (%.0f%% of %d GB/s, %.0f%% of the measured copy); warm %6.1f us" % (
             name, byts / 1e6, us, gbs, 100 * gbs / HBM_PEAK_GBS, HBM_PEAK_GBS, 100 * gbs / copy_gbs, us_warm))
 
-    def maxpool():
-        x = torch.randint(0, 128, (64, 112, 112, 64), device="cuda").to(torch.uint8)
-        o = torch.empty((64, 56, 56, 64), dtype=torch.uint8, device="cuda")
-        return lambda: B.imaxpool2d_u8(64, 112, 112, 64, 3, 2, 1, x, o)
-    report("imaxpool2d_u8 64x112x112x64 3x3/2", 64 * 112 * 112 * 64 + 64 * 56 * 56 * 64, maxpool)
+    for label, nb in (("64x112x112x64 3x3/2", 64), ("256x112x112x64 3x3/2 (257 MB)", 256)):
+        def maxpool():
+            x = torch.randint(0, 128, (nb, 112, 112, 64), device="cuda").to(torch.uint8)
+            o = torch.empty((nb, 56, 56, 64), dtype=torch.uint8, device="cuda")
+            return lambda: B.imaxpool2d_u8(nb, 112, 112, 64, 3, 2, 1, x, o)
+        report("imaxpool2d_u8 " + label, nb * 112 * 112 * 64 + nb * 56 * 56 * 64, maxpool)
 
     def avgpool():
         x = torch.randint(0, 128, (64, 7, 7, 2048), device="cuda").to(torch.uint8)
         o = torch.empty((64, 1, 1, 2048), dtype=torch.uint8, device="cuda")
         return lambda: B.iavgpool_global_u8(64, 7, 7, 2048, 21400, 20, 127, x, o)
     report("iavgpool_global_u8 64x7x7x2048", 64 * 49 * 2048 + 64 * 2048, avgpool)
-    px = 720 * 1280
-
-    def concat():
-        a = torch.randint(0, 128, (px, 32), device="cuda").to(torch.uint8)
-        b = torch.randint(0, 128, (px, 16), device="cuda").to(torch.uint8)
-        o = torch.empty((px, 48), dtype=torch.uint8, device="cuda")
-        return lambda: B.iconcat([a, b], [32, 16], [32, 16], [20000, 23000], [15, 15], 127, px, o, 48)
-    report("iconcat 720x1280 32+16 channels", 2 * px * 48, concat)
+    for label, px in (("720x1280", 720 * 1280), ("2560x1600 (393 MB)", 2560 * 1600)):
+        def concat():
+            a = torch.randint(0, 128, (px, 32), device="cuda").to(torch.uint8)
+            b = torch.randint(0, 128, (px, 16), device="cuda").to(torch.uint8)
+            o = torch.empty((px, 48), dtype=torch.uint8, device="cuda")
+            return lambda: B.iconcat([a, b], [32, 16], [32, 16], [20000, 23000], [15, 15], 127, px, o, 48)
+        report("iconcat %s 32+16 channels" % label, 2 * px * 48, concat)
     for label, n in (("64x224x224x3", 64 * 224 * 224 * 3), ("128x224x224x3 x4 (77 MB)", 4 * 128 * 224 * 224 * 3)):
         def renorm():
             x = torch.randint(0, 256, (n,), device="cuda").to(torch.uint8)

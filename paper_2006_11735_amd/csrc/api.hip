@@ -599,6 +599,7 @@ int iconv2d_bottleneck_brelu(const icnn_conv_desc *c1, const void *x, const void
     const long long tiles = (long long)b.tiles_per_img * b.N;
     if (tiles > 0x7fffffffLL || g1.M > 0x7fffffffLL) return fail(ICNN_E_SHAPE, "too many tiles");
     b.n_tiles = (int)tiles;
+    b.per_xcd = 0;              // set by the launcher
     b.k1 = c / 64;
     b.nchunk3 = c3->cout / mid;
     return launched(launch_conv_block(b, a1, a2, a3, (hipStream_t)stream), "iconv2d_bottleneck_brelu");

@@ -84,9 +84,16 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
     const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n_tiles = g.n_tiles;
 
+    // Workgroups go to the eight XCDs round-robin and every XCD has an L2 of its own: the workgroups of XCD x walk the
+    // contiguous tile range [x * per_xcd, (x + 1) * per_xcd), so that the patch halos neighbouring tiles share meet in
+    // one L2.  Work slot v (blockIdx.x, + gridDim.x, ...; the grid is a multiple of 8) is tile (v & 7) * per_xcd + (v >> 3);
+    // a workgroup's tiles ascend, so its walk ends at the first slot beyond its XCD's range or beyond the last tile.
+    auto tile_of = [&](int v) { return (v & 7) * g.per_xcd + (v >> 3); };
+    auto valid = [&](int v) { return (v >> 3) < g.per_xcd && tile_of(v) < n_tiles; };
     auto tile_origin = [&](int v, int &n, int &y0, int &x0) {
-        n = v / g.tiles_per_img;
-        const int r = v - n * g.tiles_per_img;
+        const int t = tile_of(v);
+        n = t / g.tiles_per_img;
+        const int r = t - n * g.tiles_per_img;
         const int ty = r / g.tiles_x;
         y0 = ty * g.TH;
         x0 = (r - ty * g.tiles_x) * g.TW;
@@ -142,12 +149,12 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
         asm volatile("" ::: "memory");
         ICNN_WAIT_VMCNT(0);
         sync();                                       // the first tile's patch is in LDS
-        for (int v = blockIdx.x; v < n_tiles; v += gridDim.x) {
+        for (int v = blockIdx.x; valid(v); v += gridDim.x) {
             asm volatile("" ::: "memory");
             ICNN_WAIT_VMCNT(0);                       // this tile's patch is in LDS
             for (int k = 0; k < k1; ++k) sync();
             sync();                                   // phase 1 and its epilogue are over: the patch buffer is free
-            if (v + (int)gridDim.x < n_tiles) {
+            if (valid(v + (int)gridDim.x)) {
                 setup(v + (int)gridDim.x);
                 issue_patch();
             }
@@ -177,7 +184,7 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
         }
         // issue side: tile iv, phase iph (0, 1, 2), position (i0, i1) inside the phase
         int iv = blockIdx.x, iph = 0, i0 = 0, i1 = 0, islot = 0;
-        bool imore = true;
+        bool imore = valid(iv);
         auto issue_next = [&]() {
             if (!imore) return;
             uint8_t *dst = lds + islot * ASZ;
@@ -209,7 +216,7 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
                         i0 = 0;
                         iph = 0;
                         iv += gridDim.x;
-                        imore = iv < n_tiles;
+                        imore = valid(iv);
                     }
                 }
             }
@@ -229,7 +236,7 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
         asm volatile("" ::: "memory");
         ICNN_WAIT_VMCNT((kBlkDepth - 1) * NA);        // stage 0
         sync();
-        for (int v = blockIdx.x; v < n_tiles; v += gridDim.x) {
+        for (int v = blockIdx.x; valid(v); v += gridDim.x) {
             for (int k = 0; k < k1; ++k) step();
             sync();
             for (int s = 0; s < 9 * s2; ++s) step();
@@ -288,7 +295,7 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
     sync_lds_written();                  // before the first tile: bias table, stage 0 and the first patch are in LDS
     if (AHEAD) fetch_a(afc, 0);
 
-    for (int v = blockIdx.x; v < n_tiles; v += gridDim.x) {
+    for (int v = blockIdx.x; valid(v); v += gridDim.x) {
         int n, y0, x0;
         tile_origin(v, n, y0, x0);
         // output pixels of phase 3 and the first chunk's skip operands (they travel during phases 1 and 2)
@@ -548,13 +555,15 @@ hipError_t launch_conv_block(const BlockArgs &g, const ConvArgs &a1, const ConvA
     if (lds_bytes > 160 * 1024 || (mid != 64 && mid != 128) || g.n_tiles < 1) return hipErrorInvalidValue;
     const int per_cu = mid == 64 && 2 * lds_bytes <= 160 * 1024 ? 2 : 1;
     const int slots = 256 * per_cu;
-    const dim3 grid((unsigned)(g.n_tiles < slots ? g.n_tiles : slots)), block(512);
+    BlockArgs gx = g;
+    gx.per_xcd = (g.n_tiles + 7) / 8;
+    const dim3 grid((unsigned)(8 * gx.per_xcd < slots ? 8 * gx.per_xcd : slots)), block(512);
     auto go = [&](auto kernel) -> hipError_t {
         if (lds_bytes > 64 * 1024) {
             const hipError_t e = allow_large_lds((const void *)kernel);
             if (e != hipSuccess) return e;
         }
-        hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, g, a1, a2, a3);
+        hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, gx, a1, a2, a3);
         return hipGetLastError();
     };
     return mid == 64 ? go(conv_block_kernel<2>) : go(conv_block_kernel<4>);

@@ -33,6 +33,7 @@ constexpr int kStemPerThread = (kStemMaxRows * kStemPitch + 255) / 256;
 struct StemArgs {
     int Hp, Wp;                 // pooled size
     int tiles_x, tiles_per_img, n_tiles;
+    int per_xcd;                // tiles handed to each of the 8 XCDs
     int patch_rows;             // 4 PH + KH
     int patch_cols;             // 4 PW + KW  (<= the pitch)
     int ksteps;                 // K steps of the packed weights: ceil(KH * 32 / 64)
@@ -85,9 +86,16 @@ __global__ __launch_bounds__(256, 3) void conv_stem_pool_kernel(const ConvArgs a
     int32_t *const btab = (int32_t *)(cbuf + kStemGroups * 32 * ROW_PITCH);
     for (int i = tid; i < CG * 32; i += 256) btab[i] = a.bias[i];
 
+    // Workgroups go to the eight XCDs round-robin and every XCD has an L2 of its own: the workgroups of XCD x walk the
+    // contiguous tile range [x * per_xcd, (x + 1) * per_xcd), so that the picture rows neighbouring tiles share meet in
+    // one L2.  Work slot v (blockIdx.x, + gridDim.x, ...; the grid is a multiple of 8) is tile (v & 7) * per_xcd + (v >> 3);
+    // a workgroup's tiles ascend, so its walk ends at the first slot beyond its XCD's range or beyond the last tile.
+    auto tile_of = [&](int v) { return (v & 7) * g.per_xcd + (v >> 3); };
+    auto valid = [&](int v) { return (v >> 3) < g.per_xcd && tile_of(v) < g.n_tiles; };
     auto tile_origin = [&](int v, int &n, int &py0, int &px0) {
-        n = v / g.tiles_per_img;
-        const int r = v - n * g.tiles_per_img;
+        const int t = tile_of(v);
+        n = t / g.tiles_per_img;
+        const int r = t - n * g.tiles_per_img;
         const int ty = r / g.tiles_x;
         py0 = ty * kStemPH;
         px0 = (r - ty * g.tiles_x) * kStemPW;
@@ -114,7 +122,7 @@ __global__ __launch_bounds__(256, 3) void conv_stem_pool_kernel(const ConvArgs a
             const int e = tid + 256 * i;
             const int r = e / kStemPitch, c = e - r * kStemPitch;
             const int iy = iy0 + r, ix = ix0 + c;
-            const bool ok = r < g.patch_rows && c < g.patch_cols && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
+            const bool ok = n < a.N && r < g.patch_rows && c < g.patch_cols && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
             const uint8_t *p = ok ? base + rel[i] : a.x;
             const uint32_t m = ok ? a.in_xor & 0xffu : 0u;       // a pixel outside the picture: zero after the "- 128" too
 #pragma unroll
@@ -145,10 +153,10 @@ __global__ __launch_bounds__(256, 3) void conv_stem_pool_kernel(const ConvArgs a
     store_patch(0);
     __syncthreads();
     int buf = 0;
-    for (int v = blockIdx.x; v < g.n_tiles; v += gridDim.x) {
+    for (int v = blockIdx.x; valid(v); v += gridDim.x) {
         int n, py0, px0;
         tile_origin(v, n, py0, px0);
-        const bool more = v + (int)gridDim.x < g.n_tiles;
+        const bool more = valid(v + (int)gridDim.x);
         if (more) fetch_patch(v + (int)gridDim.x);           // travels during the multiplication
 
         // ---- convolution: one K block per kernel row
@@ -252,6 +260,7 @@ hipError_t launch_conv_stem_pool(const ConvArgs &a, int hp, int wp, hipStream_t 
     const long long tiles = (long long)g.tiles_per_img * a.N;
     if (tiles < 1 || tiles > 0x7fffffffLL) return hipErrorInvalidValue;
     g.n_tiles = (int)tiles;
+    g.per_xcd = (g.n_tiles + 7) / 8;
     g.patch_rows = 4 * kStemPH + a.KH;
     g.patch_cols = 4 * kStemPW + a.KW;
     g.ksteps = a.ksteps;
@@ -262,7 +271,7 @@ hipError_t launch_conv_stem_pool(const ConvArgs &a, int hp, int wp, hipStream_t 
     const size_t lds_bytes = (size_t)g.cout_chunks * g.ksteps * kChunkBytes + 2 * (size_t)kStemMaxRows * kStemPitch * 4 +
                              (size_t)kStemGroups * 32 * (a.Cout + 16) + (size_t)a.Cout * 4;
     const int slots = 256 * 3;
-    const dim3 grid((unsigned)(g.n_tiles < slots ? g.n_tiles : slots)), block(256);
+    const dim3 grid((unsigned)(8 * g.per_xcd < slots ? 8 * g.per_xcd : slots)), block(256);
     auto go = [&](auto kernel) -> hipError_t {
         if (lds_bytes > 64 * 1024) {
             const hipError_t e = allow_large_lds((const void *)kernel);

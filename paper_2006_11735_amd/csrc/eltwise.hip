@@ -167,6 +167,40 @@ __global__ __launch_bounds__(256) void add_u8_kernel(const AddArgs a, int groups
     }
 }
 
+// int32 + unsigned 8-bit -> 8-bit on dense tensors, the arithmetic of add_rescale_vec_kernel<true>.  The int32
+// stream is two thirds of the bytes: a lane takes four separate groups of four elements, so that each of a wave's
+// loads of it covers one contiguous KiB (sixteen consecutive elements per lane put every load's 64 pieces 64 bytes
+// apart); the 8-bit operand and the output then move as dwords, 256 contiguous bytes per wave and access.
+__global__ __launch_bounds__(256) void add_s32_u8_dense_kernel(const AddArgs a, long long elements)
+{
+    const long long wave_base = ((long long)blockIdx.x * 4 + (threadIdx.x >> 6)) * 1024 + (threadIdx.x & 63) * 4;
+    v4i av[4];
+    uint32_t bw[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const long long e = wave_base + k * 256;
+        if (e < elements) {
+            av[k] = __builtin_nontemporal_load((const v4i *)((const int32_t *)a.a + e));
+            bw[k] = __builtin_nontemporal_load((const uint32_t *)((const uint8_t *)a.b + e));
+        }
+    }
+    const int half = (1 << a.b_shift) >> 1;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const long long e = wave_base + k * 256;
+        if (e >= elements) continue;
+        uint32_t w = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int bv = (int)((bw[k] >> (8 * r)) & 0xffu);
+            const int t = __builtin_elementwise_add_sat(av[k][r], (__mul24(bv, a.b_mul) + half) >> a.b_shift);
+            const int q = (int)(((int64_t)t * a.mul_hi + 0x80000000LL) >> 32);
+            w |= (uint32_t)(min(max(q, a.lo), a.hi) & 0xff) << (8 * r);
+        }
+        __builtin_nontemporal_store(w, (uint32_t *)((uint8_t *)a.out + e));
+    }
+}
+
 __global__ __launch_bounds__(256) void add_rescale_scalar_kernel(const AddArgs a, long long total)
 {
     const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
@@ -210,7 +244,12 @@ hipError_t launch_add(const AddArgs &a, bool vec, hipStream_t st)
         } else if (b_fast && q_fast) {
             AddArgs f = a;
             f.mul_hi = a.out_mode == 3 ? 0 : (int)((long long)a.mul << (32 - a.shift));
-            hipLaunchKernelGGL(add_rescale_vec_kernel<true>, grid, block, 0, st, f, gpp, total);
+            if (dense && a.a_dt == 2 && a.b_dt == 0 && a.out_mode != 3) {
+                const long long elements = a.px * a.c;
+                hipLaunchKernelGGL(add_s32_u8_dense_kernel, dim3((unsigned)((elements + 4095) / 4096)), block, 0, st, f, elements);
+            } else {
+                hipLaunchKernelGGL(add_rescale_vec_kernel<true>, grid, block, 0, st, f, gpp, total);
+            }
         } else {
             hipLaunchKernelGGL(add_rescale_vec_kernel<false>, grid, block, 0, st, a, gpp, total);
         }
@@ -344,7 +383,12 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const uint8_t *__restrict_
                                                       long long total, int per_px, int h, int w, int c, int k,
                                                       int stride, int pad, int ho_n, int wo_n, int vec)
 {
-    const long long g = (long long)blockIdx.x * 256 + threadIdx.x;
+    // Workgroups go to the eight XCDs round-robin and every XCD has an L2 of its own: workgroup b takes the b/8-th
+    // piece of XCD (b % 8)'s contiguous eighth of the output, so that the input rows two neighbouring output rows share
+    // are fetched into one L2, not two (workgroups in launch order: every shared row crossed the fabric twice).
+    const unsigned nb = gridDim.x, xcd = blockIdx.x & 7, qn = nb >> 3, rn = nb & 7;
+    const unsigned piece = xcd * qn + (xcd < rn ? xcd : rn) + (blockIdx.x >> 3);
+    const long long g = (long long)piece * 256 + threadIdx.x;
     if (g >= total) return;
     long long px = g / per_px;
     const int q = (int)(g - px * per_px);

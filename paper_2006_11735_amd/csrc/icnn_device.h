@@ -116,6 +116,7 @@ struct BlockArgs {
     int N, H, W;
     int TH, TW, PW;               // output tile and patch row width TW + 2
     int tiles_x, tiles_per_img, n_tiles;
+    int per_xcd;                  // tiles handed to each of the 8 XCDs (set by the launcher)
     unsigned inv_tw, inv_pw;      // q / TW = q * inv_tw >> 16 for q < 128; row / PW likewise for row < 160
     int k1;                       // K steps of the first layer: C / 64
     int nchunk3;                  // output channel chunks of the last layer: C / MID
