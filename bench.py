@@ -251,6 +251,7 @@ def summarise_pmc(config, fetch_csv, write_csv):
         ref = [v for k, vs in agg.items() if "stream_copy_kernel" in k for v in vs]
         if not ref:
             sys.exit("no stream_copy_kernel dispatch in the %s run: was --copy-calibration given?" % name)
+        ref = [v for v in ref if v < 1.5 * min(ref)]      # the 256 MiB calibration copies, not the 1 GiB copies of the roof measurement
         scale[name] = 262144.0 / (sum(ref) / len(ref))
     per_pass = {k: len(v) for k, v in f.items() if "maxpool" in k or "avgpool" in k}
     passes = min(per_pass.values()) if per_pass else 1
@@ -274,6 +275,30 @@ def summarise_pmc(config, fetch_csv, write_csv):
     print("written", path)
 
 
+def summarise_trace(stats_csv, passes):
+    """No GPU work: the library's kernels out of a rocprofv3 --kernel-trace --stats `*_kernel_stats.csv`, as a
+    markdown table (calls per pass of the network, average duration, time per pass, share of the library's time)."""
+    import csv
+    rows = []
+    for r in csv.DictReader(open(stats_csv)):
+        name = r["Name"]
+        if "icnn::" not in name:
+            continue
+        short = name.replace("void ", "").replace("icnn::", "").split("(")[0]
+        rows.append((short, int(r["Calls"]), float(r["TotalDurationNs"]), float(r["AverageNs"])))
+    total = sum(t for _, _, t, _ in rows)
+    print("| kernel | calls | calls/pass | avg us | ms/pass | % of the library's GPU time |")
+    print("|---|---|---|---|---|---|")
+    for short, calls, t, avg in sorted(rows, key=lambda x: -x[2]):
+        print("| %s | %d | %.1f | %.2f | %.4f | %.2f |" % (short, calls, calls / passes, avg / 1e3, t / passes / 1e6, 100 * t / total))
+    conv = [(c, t) for s_, c, t, _ in rows if s_.startswith("conv_") and "prepack" not in s_]
+    nc, tc = sum(c for c, _ in conv), sum(t for _, t in conv)
+    print()
+    if nc:
+        print("conv kernels (names starting conv_): %d calls, %.1f per pass, average %.2f us, %.4f ms per pass" % (
+        nc, nc / passes, tc / nc / 1e3, tc / passes / 1e6))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -292,7 +317,12 @@ def main():
     ap.add_argument("--summarise-pmc", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"), default=None,
                     help="no GPU work: turn the counter_collection.csv files of two rocprofv3 --pmc runs of "
                          "`bench.py --copy-calibration --main-only` (FETCH_SIZE, then WRITE_SIZE) into profiles/traffic_<config>.json")
+    ap.add_argument("--summarise-trace", nargs=2, metavar=("STATS_CSV", "PASSES"), default=None,
+                    help="no GPU work: the library's kernels of a rocprofv3 --kernel-trace --stats kernel_stats.csv as a markdown "
+                         "table; PASSES = passes of the network in the profiled process")
     args = ap.parse_args()
+    if args.summarise_trace:
+        return summarise_trace(args.summarise_trace[0], float(args.summarise_trace[1]))
     if args.summarise_pmc:
         return summarise_pmc(args.config, *args.summarise_pmc)
     if args.gpus != 1:
@@ -426,22 +456,32 @@ def main():
     if args.per_channel:
         result["config"]["workload"] += "; per-output-channel requantisation (iconv2d_brelu_pc, iconv2d_dual_brelu_pc)"
     elif os.path.exists(pc_path) and args.config == "cfg3" and not args.main_only:
-        # the same network with one (mul, shift) and skip rescale per output channel
-        g_pc = GpuNet(net, seed, json.load(open(pc_path)))
-        g_pc.set_input()
-        for _ in range(5):
-            g_pc.run()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(30):
-            g_pc.run()
-        torch.cuda.synchronize()
-        ms_pc = (time.perf_counter() - t0) / 30 * 1e3
-        result["per_channel_variant"] = {"ms_per_step": ms_pc, "images_per_s": images / (ms_pc * 1e-3),
-                                         "launches_per_step": len(g_pc.steps),
-                                         "note": "iconv2d_brelu_pc on every BReLU layer, iconv2d_dual_brelu_pc on the four projection blocks"}
-        log("per-channel variant: %.3f ms per step (%d launches)" % (ms_pc, len(g_pc.steps)))
-        del g_pc
+        # the same network with one (mul, shift) and skip rescale per output channel, on both stored calibrations:
+        # channels without a positive calibration value keep the layer's pair ("layer"), or get the wide pair of
+        # their own statistic ("own": parameters that no kernel's fast form had a say in)
+        variants = {}
+        for label, path in (("layer", pc_path), ("own", pc_path.replace("_pc.json", "_pc_own.json"))):
+            if not os.path.exists(path):
+                continue
+            g_pc = GpuNet(net, seed, json.load(open(path)))
+            g_pc.set_input()
+            for _ in range(5):
+                g_pc.run()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(30):
+                g_pc.run()
+            torch.cuda.synchronize()
+            ms_pc = (time.perf_counter() - t0) / 30 * 1e3
+            variants[label] = {"ms_per_step": ms_pc, "images_per_s": images / (ms_pc * 1e-3), "launches_per_step": len(g_pc.steps),
+                               "calibration": os.path.relpath(path, ROOT)}
+            log("per-channel variant (%s): %.3f ms per step (%d launches)" % (label, ms_pc, len(g_pc.steps)))
+            del g_pc
+        result["per_channel_variant"] = dict(variants.get("layer", {}), floor_channels_own=variants.get("own"),
+                                             note="iconv2d_brelu_pc on every BReLU layer, iconv2d_dual_brelu_pc on the four "
+                                                  "projection blocks; the top-level figures are for the calibration in which a "
+                                                  "channel without a positive calibration value keeps the layer's pair, "
+                                                  "floor_channels_own for the one in which it gets the pair of its own statistic")
     result["hbm_copy_measured_gbs"] = copy_gbs
     if not args.main_only:
         del g

@@ -63,7 +63,7 @@ def run(net, seed, calib, images=None, x_raw=None, weights=None):
     return bufs
 
 
-def calibrate(net, seed, per_channel=False, max_int=K.MAX_INT):
+def calibrate(net, seed, per_channel=False, max_int=K.MAX_INT, floor_channels="layer"):
     """Returns (calib, buffers on the calibration images).
 
     calib = {"conv": {name: {...integers...}}, "avgpool": {dst: {...}}, "ratio": {...}}
@@ -71,6 +71,11 @@ def calibrate(net, seed, per_channel=False, max_int=K.MAX_INT):
     rescale per output channel ("mul_c", "shift_c", "res_mul_c", "res_shift_c"), each from
     that channel's own statistic (Section 3.4.3: one weight step per output channel).
     Concatenated branches, regression outputs and raw int32 outputs stay per layer.
+    floor_channels: what a channel without a positive value in the calibration sample gets (its statistic is the
+    floor, 1, and Section 3.3's bound needs positive activations to exist): "layer" = the layer's pair; "own" = the
+    pair of its own statistic all the same, i.e. a ratio of max_int per unit (pairs of 20+ bits, the widest the
+    method produces).  Both are valid integer networks; the second exists so that the per-channel path is also
+    checked and timed on parameters that were not chosen with any kernel in mind.
     max_int: the largest quantised activation (Section 3.3), 2^bits - 1: 127 for the 7-bit
     activations of the main experiments, 255 / 63 / 31 / 15 for the other bit-depths the paper tries.
     """
@@ -160,7 +165,8 @@ def calibrate(net, seed, per_channel=False, max_int=K.MAX_INT):
             if per_channel:
                 # a channel without positive values in the sample (statistic 1, the floor) has no bound
                 # of its own: it keeps the layer's pair instead of a ratio of max_int per unit
-                pairs = [K.bound_params(hc, max_int) if hc > 1 else (m, s) for hc in K.percentile_999_per_channel(t)]
+                pairs = [K.bound_params(hc, max_int) if hc > 1 or floor_channels == "own" else (m, s)
+                         for hc in K.percentile_999_per_channel(t)]
                 cal["mul_c"] = [mc for mc, _ in pairs]
                 cal["shift_c"] = [sc for _, sc in pairs]
             calib["conv"][op["name"]] = cal
@@ -171,22 +177,23 @@ def calibrate(net, seed, per_channel=False, max_int=K.MAX_INT):
     return calib, bufs
 
 
-def stored_calib_path(cfg, seed, per_channel=False, max_int=K.MAX_INT):
+def stored_calib_path(cfg, seed, per_channel=False, max_int=K.MAX_INT, floor_channels="layer"):
     import os
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    tag = ("_pc" if per_channel else "") + ("_a%d" % max_int if max_int != K.MAX_INT else "")
+    tag = ("_pc" if per_channel else "") + ("_own" if per_channel and floor_channels == "own" else "") + (
+        "_a%d" % max_int if max_int != K.MAX_INT else "")
     return os.path.join(root, "workloads", "calib", "%s_seed%d%s.json" % (cfg, seed, tag))
 
 
-def write_stored_calib(cfg, seed, per_channel=False, max_int=K.MAX_INT):
+def write_stored_calib(cfg, seed, per_channel=False, max_int=K.MAX_INT, floor_channels="layer"):
     """Calibrate config `cfg` with the oracle and store the integers for bench and tests."""
     import json
     net = W.CONFIGS[cfg]()
-    calib, _ = calibrate(net, seed, per_channel, max_int)
+    calib, _ = calibrate(net, seed, per_channel, max_int, floor_channels)
     calib["net"] = net["name"]
     calib["seed"] = seed
     calib["written_by"] = "oracle/net.py write_stored_calib (calls only oracle/)"
-    path = stored_calib_path(cfg, seed, per_channel, max_int)
+    path = stored_calib_path(cfg, seed, per_channel, max_int, floor_channels)
     with open(path, "w") as f:
         if per_channel:
             json.dump(calib, f, sort_keys=True, separators=(",", ":"))
@@ -198,10 +205,11 @@ def write_stored_calib(cfg, seed, per_channel=False, max_int=K.MAX_INT):
 if __name__ == "__main__":
     import sys
     import time
-    # `python -m oracle.net [cfgN ...]` writes the per-layer files, `cfgN:pc` the per-channel one,
-    # `cfgN:a255` the one with 8-bit activations
-    for name in sys.argv[1:] or ["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "cfg6", "cfg3:pc", "cfg1:a255"]:
+    # `python -m oracle.net [cfgN ...]` writes the per-layer files, `cfgN:pc` the per-channel one (`cfgN:pc_own`: floor
+    # channels keep a pair of their own), `cfgN:a255` the one with 8-bit activations
+    for name in sys.argv[1:] or ["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "cfg6", "cfg3:pc", "cfg3:pc_own", "cfg1:a255"]:
         t0 = time.time()
         cfg, _, kind = name.partition(":")
         mi = int(kind[1:]) if kind.startswith("a") else K.MAX_INT
-        print(write_stored_calib(cfg, 0, kind == "pc", mi), "%.1fs" % (time.time() - t0), flush=True)
+        print(write_stored_calib(cfg, 0, kind.startswith("pc"), mi, "own" if kind == "pc_own" else "layer"),
+              "%.1fs" % (time.time() - t0), flush=True)

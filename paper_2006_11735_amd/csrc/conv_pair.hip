@@ -11,7 +11,7 @@
 //            17.6 us on 12544 pixels of 256 -> 1024 -> 256); every wave owns C/8 output channels and
 //            streams their packed weights from global memory straight into A fragments (the packed order IS the
 //            fragment order, and no two waves need the same rows, so LDS would only add a copy).  The 16 bytes a
-//            lane produces go to global memory and to the tile's row of y in LDS.
+//            lane produces go to the tile's row of y in LDS; after the phase the tile is stored row by row.
 //   phase 2  z = BReLU/requant(W1 y + b1): K = C, activations from LDS, weights again straight from global memory,
 //            a 32-channel chunk of the MID2 outputs per wave.
 //
@@ -117,12 +117,9 @@ __global__ __launch_bounds__(512, 2) void conv_pair_kernel(const ConvArgs a3, co
     const __amdgpu_buffer_rsrc_t rs_r =
         __builtin_amdgcn_make_buffer_rsrc(has_res ? (void *)a3.res : (void *)a3.out, 0, has_res ? g.res_bytes : 0, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc((void *)a3.out, 0, g.y_bytes, 0x00020000);
-    unsigned r_off[2], y_off[2];
+    unsigned r_off[2];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        r_off[j] = okp[j] ? (unsigned)p[j] * (unsigned)a3.res_cs + half * 16 : OOB;
-        y_off[j] = okp[j] ? (unsigned)p[j] * (unsigned)a3.out_cs + (unsigned)a3.out_co + half * 16 : OOB;
-    }
+    for (int j = 0; j < 2; ++j) r_off[j] = okp[j] ? (unsigned)p[j] * (unsigned)a3.res_cs + half * 16 : OOB;
     const int cpw = C >> 8;                           // 32-channel chunks per wave
     const int chunk0 = wave * cpw, chunk_last = chunk0 + cpw - 1;
     auto load_a3 = [&](v4i (&A)[KF], v4i (&r)[2], int chunk) {
@@ -147,7 +144,6 @@ __global__ __launch_bounds__(512, 2) void conv_pair_kernel(const ConvArgs a3, co
             constexpr int j = decltype(jc)::value;
             const v4i w = has_res ? epilogue_bytes16<1>(a3, acc[j], r[j]) : epilogue_bytes16<0>(a3, acc[j], r[j]);
             *(v4i *)(ybuf + (32 * j + col) * pitch + co0) = w;
-            __builtin_amdgcn_raw_buffer_store_b128(w, rs_y, y_off[j], chunk * 32, 0);
         });
         PAIR_TR(4);
     };
@@ -219,6 +215,18 @@ __global__ __launch_bounds__(512, 2) void conv_pair_kernel(const ConvArgs a3, co
     asm volatile("" ::: "memory");
     PAIR_TR(6);
     PAIR_TW(5);
+    // y goes to memory from LDS, a pixel's whole row of C bytes per wave and pass in 16-byte pieces of consecutive
+    // lanes (stored from the epilogue, 32 bytes per pixel at a time with the rest of the 128-byte line following a
+    // chunk later, the writes reached memory as 1.55 times y's size)
+    {
+        const int pieces = C >> 4;                    // 16-byte pieces of a pixel's row: 16, 32, ... 128
+        for (int e = tid; e < kPairPix * pieces; e += 512) {
+            const int row = e / pieces, piece = e - row * pieces;
+            const v4i w = *(const v4i *)(ybuf + row * pitch + piece * 16);
+            const unsigned off = p0 + row < P ? (unsigned)(p0 + row) * (unsigned)a3.out_cs + (unsigned)a3.out_co + piece * 16 : OOB;
+            __builtin_amdgcn_raw_buffer_store_b128(w, rs_y, off, 0, 0);
+        }
+    }
     if (!active) return;
     v16i acc[NJ2];
     {

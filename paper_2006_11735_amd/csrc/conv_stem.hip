@@ -49,16 +49,6 @@ __device__ __forceinline__ void stem_static_for(F &&fn)
     }
 }
 
-// bytewise maximum of two words: even and odd bytes as 16-bit lanes
-__device__ __forceinline__ uint32_t max_bytes(uint32_t x, uint32_t y)
-{
-    typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
-    const uint32_t xe = x & 0x00ff00ffu, ye = y & 0x00ff00ffu, xo = (x >> 8) & 0x00ff00ffu, yo = (y >> 8) & 0x00ff00ffu;
-    const u16x2 e = __builtin_elementwise_max(__builtin_bit_cast(u16x2, xe), __builtin_bit_cast(u16x2, ye));
-    const u16x2 o = __builtin_elementwise_max(__builtin_bit_cast(u16x2, xo), __builtin_bit_cast(u16x2, yo));
-    return __builtin_bit_cast(uint32_t, e) | (__builtin_bit_cast(uint32_t, o) << 8);
-}
-
 template <int CG>           // cout / 32: 1 or 2
 __global__ __launch_bounds__(256, 3) void conv_stem_pool_kernel(const ConvArgs a, const StemArgs g)
 {

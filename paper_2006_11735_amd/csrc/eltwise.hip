@@ -370,13 +370,7 @@ hipError_t launch_concat_vec(const ConcatArgs &a, int64_t px, hipStream_t st)
 // max over the window positions inside the image; bytewise max of packed words
 __device__ __forceinline__ uint32_t max_u8x4(uint32_t x, uint32_t y)
 {
-    uint32_t r = 0;
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-        const uint32_t xb = (x >> (8 * b)) & 0xff, yb = (y >> (8 * b)) & 0xff;
-        r |= (xb > yb ? xb : yb) << (8 * b);
-    }
-    return r;
+    return max_bytes(x, y);
 }
 
 __global__ __launch_bounds__(256) void maxpool_kernel(const uint8_t *__restrict__ x, uint8_t *__restrict__ out,
@@ -398,7 +392,10 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const uint8_t *__restrict_
     const long long n = t / ho_n;
     if (vec && k == 3) {
         // 3x3 window, branch-free: a position outside the image is replaced by the nearest one inside,
-        // which the window also contains, so the maximum is unchanged and all nine loads are independent
+        // which the window also contains, so the maximum is unchanged and all nine loads are independent.
+        // (A variant in which a lane walks four output rows and carries the shared input row, six loads per output
+        // instead of nine, measured slower, 21.8 us against 17.9 us on 64 x 112 x 112 x 64: a quarter of the
+        // workgroups, all of them waiting for their loads at the same time.)
         uint32_t m[4] = {0, 0, 0, 0};
         const uint8_t *base = x + (size_t)n * h * w * c + q * 16;
 #pragma unroll

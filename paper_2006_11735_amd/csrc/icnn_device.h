@@ -122,6 +122,16 @@ struct BlockArgs {
     int nchunk3;                  // output channel chunks of the last layer: C / MID
 };
 
+// bytewise maximum of two words: even and odd bytes as 16-bit lanes
+__device__ __forceinline__ uint32_t max_bytes(uint32_t x, uint32_t y)
+{
+    typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+    const uint32_t xe = x & 0x00ff00ffu, ye = y & 0x00ff00ffu, xo = (x >> 8) & 0x00ff00ffu, yo = (y >> 8) & 0x00ff00ffu;
+    const u16x2 e = __builtin_elementwise_max(__builtin_bit_cast(u16x2, xe), __builtin_bit_cast(u16x2, ye));
+    const u16x2 o = __builtin_elementwise_max(__builtin_bit_cast(u16x2, xo), __builtin_bit_cast(u16x2, yo));
+    return __builtin_bit_cast(uint32_t, e) | (__builtin_bit_cast(uint32_t, o) << 8);
+}
+
 // [v / 2^s], round half up; arithmetic shift floors for negative values.
 __device__ __forceinline__ int64_t rsr64(int64_t v, int s)
 {

@@ -82,12 +82,17 @@ def test_concat_matches_oracle_and_numpy(cs):
     assert (out.cpu().numpy() == np.concatenate(xs, axis=1)).all()
 
 
-@pytest.mark.parametrize("shape", [(2, 112, 112, 64, 3, 2, 1), (1, 9, 7, 5, 3, 2, 1), (1, 8, 8, 16, 2, 2, 0)])
+@pytest.mark.parametrize("shape", [(2, 112, 112, 64, 3, 2, 1), (1, 9, 7, 5, 3, 2, 1), (1, 8, 8, 16, 2, 2, 0),
+                                   # 3x3 / 2 / 1 beyond the network shape: ragged blocks, odd
+                                   # sizes, rows wider than one workgroup, one-pixel images
+                                   (3, 13, 17, 32, 3, 2, 1), (1, 30, 200, 64, 3, 2, 1), (2, 7, 7, 16, 3, 2, 1),
+                                   (1, 1, 1, 16, 3, 2, 1), (1, 2, 5, 48, 3, 2, 1), (1, 10, 4, 16, 3, 2, 1),
+                                   (1, 9, 9, 16, 3, 1, 1), (1, 9, 9, 16, 3, 2, 0)])
 def test_maxpool(shape):
     from gpu_util import dev
     from paper_2006_11735_amd import binding as B
     n, h, w, c, k, s, p = shape
-    x = rnd(5).integers(0, 128, size=(n, h, w, c), dtype=np.uint8)
+    x = rnd(5).integers(0, 256, size=(n, h, w, c), dtype=np.uint8)
     want = O.maxpool2d(x, k, s, p)
     out = torch.zeros(want.shape, dtype=torch.uint8, device="cuda:0")
     B.imaxpool2d_u8(n, h, w, c, k, s, p, dev(x), out)

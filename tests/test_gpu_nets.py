@@ -72,10 +72,13 @@ def test_resnet50_shape_per_channel_batch_8():
             assert (got == want[name]).all(), (img, name)
 
 
-def test_config3_per_channel_full_batch_sampled_images():
+@pytest.mark.parametrize("floor_channels", ["layer", "own"])
+def test_config3_per_channel_full_batch_sampled_images(floor_channels):
+    # both stored per-channel calibrations: channels without a positive calibration value keep the layer's pair, or
+    # get the wide pair of their own statistic (which only the epilogue's general form takes)
     from paper_2006_11735_amd.netrun import GpuNet
     net = W.CONFIGS["cfg3"]()
-    calib = json.load(open(ONet.stored_calib_path("cfg3", 0, per_channel=True)))
+    calib = json.load(open(ONet.stored_calib_path("cfg3", 0, per_channel=True, floor_channels=floor_channels)))
     g = GpuNet(net, 0, calib)
     g.set_input()
     g.run()
