@@ -140,7 +140,7 @@ int icnn_set_tuning(const char *name, int32_t value)
         {"no_narrow", &Tuning::no_narrow, 0, 1}, {"no_fc", &Tuning::no_fc, 0, 1},
         {"no_halo", &Tuning::no_halo, 0, 1},     {"halo_tile", &Tuning::halo_tile, 0, 2},
         {"halo_always", &Tuning::halo_always, 0, 1}, {"no_stream", &Tuning::no_stream, 0, 1},
-        {"ksplit", &Tuning::ksplit, 0, 8},
+        {"ksplit", &Tuning::ksplit, 0, 8}, {"no_block64", &Tuning::no_block64, 0, 1},
     };
     if (!strcmp(name, "reset")) {
         g_tuning = Tuning();
@@ -602,6 +602,8 @@ int iconv2d_bottleneck_brelu(const icnn_conv_desc *c1, const void *x, const void
     b.per_xcd = 0;              // set by the launcher
     b.k1 = c / 64;
     b.nchunk3 = c3->cout / mid;
+    if (!g_tuning.no_block64 && conv_block64_takes(b, a1, a3) && conv_block64_lds_bytes(c) <= 160 * 1024)
+        return launched(launch_conv_block64(b, a1, a2, a3, (hipStream_t)stream), "iconv2d_bottleneck_brelu");
     return launched(launch_conv_block(b, a1, a2, a3, (hipStream_t)stream), "iconv2d_bottleneck_brelu");
 }
 

@@ -98,8 +98,13 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
         y0 = ty * g.TH;
         x0 = (r - ty * g.tiles_x) * g.TW;
     };
+    // Without the fetch ahead a step's fragment reads are consumed inside the step, and the barrier that ends it lets the
+    // weight waves overwrite their ring slot: the reads must have returned by then (lgkmcnt 0), whatever the compiler did
+    // with the MFMAs that consume them.  With the fetch ahead the reads in flight at a barrier are those of the NEXT step,
+    // whose slot and patch rows nobody writes for another step; they stay in flight on purpose.
     auto sync = [&]() {
         asm volatile("" ::: "memory");
+        if (!AHEAD) __builtin_amdgcn_s_waitcnt(0xC07F);
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
     };
@@ -361,6 +366,7 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
                 slot = ns;
             }
             BLK_TR(3);
+            mfma_drain(acc);
             // rows outside the image are the next layer's zero padding
             static_for<TP1>([&](auto jc) {
                 constexpr int j = decltype(jc)::value;
@@ -439,6 +445,7 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
             }
             BLK_TR(6);
             sync();                      // every wave has its last fragments of a: b may overwrite it
+            mfma_drain(acc);
             BLK_TR(9);
             static_for<TP2>([&](auto jc) {
                 constexpr int j = decltype(jc)::value;
@@ -500,6 +507,7 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
                     slot = ns;
                 }
                 BLK_TR(21);
+                mfma_drain(acc);
                 static_for<TP2>([&](auto jc) {
                     constexpr int j = decltype(jc)::value;
                     if (ok3[j]) epilogue_px16(a3, acc[j], p3[j], co0, res8[j]);

@@ -461,6 +461,38 @@ __device__ __forceinline__ v4i epilogue_bytes16(const ConvArgs &a, const v16i &a
     }
     return requant16_any(a, t);
 }
+// Between the last v_mfma of an accumulation and the first instruction that reads the accumulator.  The compiler's
+// hazard recogniser does not always keep the two apart (seen in a kernel whose epilogue starts two instructions after
+// the last MFMA, behind a branch: the reads returned the sums without the last product, now and then), and the
+// hardware does not hold the reader back.  Twenty wait states, what a 16-pass matrix instruction needs; the empty
+// statements before and after tie every accumulator tile to the wait, so neither an MFMA nor a reader can cross it.
+__device__ __forceinline__ void mfma_drain(v16i &acc)
+{
+    asm volatile("s_nop 15\n\ts_nop 3" : "+v"(acc));
+}
+template <int N>
+__device__ __forceinline__ void mfma_drain(v16i (&acc)[N])
+{
+#pragma unroll
+    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(acc[i]));
+    asm volatile("s_nop 15\n\ts_nop 3");
+#pragma unroll
+    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(acc[i]));
+}
+template <int M, int N>
+__device__ __forceinline__ void mfma_drain(v16i (&acc)[M][N])
+{
+#pragma unroll
+    for (int i = 0; i < M; ++i)
+#pragma unroll
+        for (int j = 0; j < N; ++j) asm volatile("" : "+v"(acc[i][j]));
+    asm volatile("s_nop 15\n\ts_nop 3");
+#pragma unroll
+    for (int i = 0; i < M; ++i)
+#pragma unroll
+        for (int j = 0; j < N; ++j) asm volatile("" : "+v"(acc[i][j]));
+}
+
 // fn(integral_constant<int, 0>) ... fn(integral_constant<int, N - 1>): a loop the compiler cannot leave rolled
 // (register arrays indexed inside it stay in registers)
 template <int N, class F>

@@ -202,6 +202,7 @@ __global__ __launch_bounds__(256, 2) void conv_dual_kernel(const ConvArgs a, con
             buf = buf + 1 == nstages ? 0 : buf + 1;
             if (s == kp - 1) {
                 // the projection sum is complete: bring it to the main path's ratio, add the main bias
+                mfma_drain(acc);
                 if constexpr (PC) {
                     // every wave's parameter copy landed before this step's barrier (see issue_params)
                     const int32_t *groups = (const int32_t *)(pc_lds + pc_slot * PC_SLOT);
@@ -254,6 +255,7 @@ __global__ __launch_bounds__(256, 2) void conv_dual_kernel(const ConvArgs a, con
             }
             load_bias_rows<TM>(pb, ct * BM + wm * TM * 32, lane >> 5, bias_next);
         }
+        mfma_drain(acc);
         if constexpr (PC) {
             v4i no_res[TM][TP];     // the main layer's descriptor carries no skip operand here
 #pragma unroll

@@ -80,6 +80,7 @@ __global__ __launch_bounds__(64 * kFcWaves) void conv_fc_kernel(const ConvArgs a
                 acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[u][1], fb[u][j][1], acc[j], 0, 0, 0);
             }
     }
+    mfma_drain(acc);
     // ---- sum the eight partial accumulators: wave w sums registers 4w .. 4w + 3 of all waves
 #pragma unroll
     for (int j = 0; j < 2; ++j)

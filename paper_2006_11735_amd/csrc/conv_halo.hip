@@ -374,6 +374,7 @@ __global__ __launch_bounds__(512, 1) void conv_halo_kernel(const ConvArgs a, con
         }
         // the skip operands (this wave's only loads) have landed
         ICNN_WAIT_VMCNT(0);
+        mfma_drain(acc);
 
         v += gridDim.x;
         if (more) load_bias_rows<TM>(a, nct * BM + wm * TM * 32, lane >> 5, bias_next);

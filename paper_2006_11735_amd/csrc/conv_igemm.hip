@@ -386,6 +386,7 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
         bool finish = true;
         constexpr int UNIT_BYTES = TM * TP * 4 * 256 * 16;                  // a unit's accumulators
         const __amdgpu_buffer_rsrc_t rs_part = __builtin_amdgcn_make_buffer_rsrc((void *)a.ws_part, 0, 0x7ffffff0, 0x00020000);
+        mfma_drain(acc);
         if (SPLIT && ksplit > 1) {
             const unsigned mine = (unsigned)(unit_tile * ksplit + unit_ks) * UNIT_BYTES + (wave * (TM * TP * 4 * 64) + lane) * 16;
 #pragma unroll
@@ -612,6 +613,7 @@ __global__ __launch_bounds__(256) void conv_greg_kernel(const ConvArgs a)
         __syncthreads();
     }
 
+    mfma_drain(acc);
     if constexpr (PC) {
         v4i res8[TM][TP];
         prefetch_res8<TM, TP>(a, ct * BM + wm * TM * 32, pix0 + wp * TP * 32, lane, res8);

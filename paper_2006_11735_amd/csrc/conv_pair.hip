@@ -139,6 +139,7 @@ __global__ __launch_bounds__(512, 2) void conv_pair_kernel(const ConvArgs a3, co
         for (int f = 0; f < KF; ++f)
 #pragma unroll
             for (int j = 0; j < 2; ++j) acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[f], bt[j][f], acc[j], 0, 0, 0);
+        mfma_drain(acc);
         PAIR_TR(3);
         static_for<2>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
@@ -258,6 +259,7 @@ __global__ __launch_bounds__(512, 2) void conv_pair_kernel(const ConvArgs a3, co
         load_a1(A0, gi + 2);
         mul_group(A1, gi + 1);
     }
+    mfma_drain(acc);
     static_for<NJ2>([&](auto jc) {
         constexpr int j = decltype(jc)::value;
         const int pz = p0 + 32 * (pg + j) + col;

@@ -194,6 +194,7 @@ __global__ __launch_bounds__(256, 3) void conv_stem_pool_kernel(const ConvArgs a
             if (kh + 2 < a.KH) fetch_frags(af, bf, kh + 2);
             if (kh + 1 < a.KH) multiply(afn, bfn);
         }
+        mfma_drain(acc);
         // ---- requantise; outputs outside the convolution's output range are the pool's padding: zeros
         stem_static_for<TPX>([&](auto jc) {
             constexpr int j = decltype(jc)::value;

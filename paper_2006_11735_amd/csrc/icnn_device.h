@@ -166,6 +166,7 @@ struct Tuning {
     int halo_tile = 0;     // patch-resident kernel: 1 = 128 x 128, 2 = 64 x 256
     int halo_always = 0;   // patch-resident kernel also with several tiles per workgroup and short K loops
     int no_stream = 0;     // single-channel 3x3 layers: lane-group kernel instead of the streaming one
+    int no_block64 = 0;    // fused bottleneck blocks with 64 middle channels: the LDS-ring kernel instead of the register-resident one
     int ksplit = 0;        // 0 library's choice; 1 never split the K axis; 2..8 this split where it divides the K steps
 };
 extern Tuning g_tuning;
@@ -185,6 +186,9 @@ hipError_t launch_conv_stem_pool(const ConvArgs &a, int hp, int wp, hipStream_t 
 bool conv_block_tile(int H, int W, BlockArgs &g);
 size_t conv_block_lds_bytes(int mid, int c);
 hipError_t launch_conv_block(const BlockArgs &g, const ConvArgs &a1, const ConvArgs &a2, const ConvArgs &a3, hipStream_t st);
+size_t conv_block64_lds_bytes(int c);
+bool conv_block64_takes(const BlockArgs &g, const ConvArgs &a1, const ConvArgs &a3);
+hipError_t launch_conv_block64(const BlockArgs &g, const ConvArgs &a1, const ConvArgs &a2, const ConvArgs &a3, hipStream_t st);
 size_t conv_pair_lds_bytes(int c, int mid2);
 hipError_t launch_conv_pair(const ConvArgs &a3, const ConvArgs &a1, long long pixels, hipStream_t st);
 bool conv_narrow_applies(const ConvArgs &a);

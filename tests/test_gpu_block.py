@@ -95,13 +95,25 @@ BLOCKS = [
     (40, 14, 14, 256, 128),      # more tiles than resident workgroups: every workgroup walks several
     (1, 1, 200, 128, 128),       # one image row
     (1, 150, 1, 64, 64),         # one image column
+    (12, 56, 56, 256, 64),       # 336 tiles: more than resident workgroups, both patch buffers in turn
+    (3, 30, 41, 128, 64),        # ragged tiles, two slices
 ]
 
 
+@pytest.mark.parametrize("ring", [False, True], ids=["default", "lds_ring"])
 @pytest.mark.parametrize("shape", BLOCKS, ids=lambda s: "x".join(map(str, s)))
-def test_fused_block_equals_three_layers(shape):
+def test_fused_block_equals_three_layers(shape, ring):
+    # blocks with 64 middle channels and 64 / 128 / 256 outer ones take the kernel that keeps the weights in registers;
+    # ring=True keeps them on the kernel that streams the weights through LDS, like the other shapes
+    from paper_2006_11735_amd import binding as B
     n, h, w, c, mid = shape
-    got, want = run_block(sum(shape), n, h, w, c, mid)
+    if ring and mid != 64:
+        pytest.skip("only one kernel takes this shape")
+    B.icnn_set_tuning("no_block64", 1 if ring else 0)
+    try:
+        got, want = run_block(sum(shape), n, h, w, c, mid)
+    finally:
+        B.icnn_set_tuning("no_block64", 0)
     assert got.shape == want.shape
     assert (got == want).all(), "%d of %d bytes differ" % (int((got != want).sum()), want.size)
     assert want.max() == 127 and want.min() == 0
