@@ -546,6 +546,7 @@ int iconv2d_maxpool_brelu(const icnn_conv_desc *d, int32_t pool_k, int32_t pool_
     if (!a.vec_out || !a.vec_bias) return fail(ICNN_E_UNSUPPORTED, "fused first layer needs 16-byte aligned output and bias");
     const unsigned long long xb = ((unsigned long long)d->n * d->h * d->w - 1) * d->in_c_stride + d->cin;
     if (xb > 0x7fffffffull || g.M > 0x7fffffffLL) return fail(ICNN_E_UNSUPPORTED, "fused first layer needs tensors below 2 GiB");
+    if (xb < 4) return fail(ICNN_E_UNSUPPORTED, "fused first layer reads the picture four bytes at a time: it needs at least four");
     const int hp = (g.ho + 2 * pool_pad - pool_k) / pool_stride + 1, wp = (g.wo + 2 * pool_pad - pool_k) / pool_stride + 1;
     return launched(launch_conv_stem_pool(a, hp, wp, (hipStream_t)stream), "iconv2d_maxpool_brelu");
 }

@@ -20,6 +20,19 @@
 
 namespace icnn {
 
+// Development aid, compiled in with -DICNN_B64_TRACE only: wave `ICNN_B64_TRACE` of one workgroup stamps the clock at
+// the marked points; icnn_debug_trace_b64() copies the stamps out.
+#ifdef ICNN_B64_TRACE
+__device__ unsigned long long g_b64_trace[512];
+#define B64_TR(k)                                                                                                  \
+    do {                                                                                                           \
+        if (blockIdx.x == 3 && wave == (ICNN_B64_TRACE) && lane == 0 && trn < 500)                                 \
+            g_b64_trace[trn++] = ((unsigned long long)(k) << 56) | (__builtin_amdgcn_s_memtime() & 0xffffffffffffffULL); \
+    } while (0)
+#else
+#define B64_TR(k)
+#endif
+
 constexpr int kB64Rows = 160;        // patch rows: five pixel groups of 32 (output pixel slots of a tile: 128, four groups)
 
 template <int K1>                    // C / 64: 1, 2 or 4
@@ -132,13 +145,16 @@ __global__ __launch_bounds__(512, 2) void conv_block64_kernel(const BlockArgs g,
     sync_lds_written();                              // ... everybody's, and the bias table is written
 
     int buf = 0;
+    [[maybe_unused]] int trn = 0;
     for (int v = blockIdx.x; valid(v); v += gridDim.x) {
+        B64_TR(1);
         int n, y0, x0;
         tile_origin(v, n, y0, x0);
         const uint8_t *const xb = lds + buf * PATCH;
         // the next tile's patch travels during this tile (its buffer was last read in the previous tile's phase 3,
         // which every wave left before the barrier at the end of that tile)
         if (valid(v + (int)gridDim.x)) issue_patch(v + (int)gridDim.x, buf ^ 1);
+        B64_TR(2);
 
         // ---------------- phase 1: a = requant(W1 x + b1) on patch rows 32 pg .. + 32, chunk c12
 #pragma unroll
@@ -152,6 +168,7 @@ __global__ __launch_bounds__(512, 2) void conv_block64_kernel(const BlockArgs g,
                     acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w1[f], *(const v4i *)(xb + (f >> 1) * SLICE + b_slot_offset(row, (f & 1) * 2 + half)),
                                                                 acc, 0, 0, 0);
                 mfma_drain(acc);
+                B64_TR(3);
                 const int py = (int)(((unsigned)row * g.inv_pw) >> 16);
                 const int px = row - py * g.PW;
                 const int iy = y0 - 1 + py, ix = x0 - 1 + px;
@@ -162,9 +179,11 @@ __global__ __launch_bounds__(512, 2) void conv_block64_kernel(const BlockArgs g,
                 v4i w = requant16_any(a1, t);
                 if (!ok) w = v4i{0, 0, 0, 0};        // outside the image: the next layer's zero padding
                 *(v4i *)(abuf + b_slot_offset(row, c12 * 2 + half)) = w;
+                B64_TR(4);
             }
         }
         sync_lds_written();
+        B64_TR(5);
 
         // ---------------- phase 2: b = requant(W2 (*) a + b2) on output slots 32 pg12 .. + 32, chunk c12
         {
@@ -176,15 +195,19 @@ __global__ __launch_bounds__(512, 2) void conv_block64_kernel(const BlockArgs g,
                 for (int kq = 0; kq < 2; ++kq)
                     acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w2[2 * t + kq], *(const v4i *)(abuf + b_slot_offset(row, kq * 2 + half)), acc, 0, 0, 0);
             }
+            B64_TR(6);
             sync();                                  // every wave has its last fragments of a: b may overwrite it
             mfma_drain(acc);
+            B64_TR(7);
             int t[16];
 #pragma unroll
             for (int r = 0; r < 16; ++r) t[r] = acc[r];
             const v4i w = requant16_any(a2, t);      // slots beyond the tile hold values nobody stores
             *(v4i *)(bbuf + b_slot_offset(32 * pg12 + col, c12 * 2 + half)) = w;
+            B64_TR(8);
         }
         sync_lds_written();
+        B64_TR(9);
 
         // ---------------- phase 3: y = epilogue(W3 b + b3, skip) on chunk ch3, pixel groups pg3_0 .. + NP3
         static_for<NP3>([&](auto jc) {
@@ -206,9 +229,11 @@ __global__ __launch_bounds__(512, 2) void conv_block64_kernel(const BlockArgs g,
             const v4i r8 = *(const v4i *)(xb + (co >> 6) * SLICE + b_slot_offset(prow, (co & 63) >> 4));
             const v4i w = has_res ? epilogue_bytes16<1>(a3, acc, r8) : epilogue_bytes16<0>(a3, acc, r8);
             if (ok) *(v4i *)((uint8_t *)a3.out + (size_t)((n * g.H + oy) * g.W + ox) * a3.out_cs + a3.out_co + co) = w;
+            B64_TR(10);
         });
         asm volatile("" ::: "memory");
         ICNN_WAIT_VMCNT(0);                          // the next tile's patch has landed (this wave's copies of it)
+        B64_TR(11);
         sync();                                      // ... all of it; and nobody reads b or this tile's patch any more
         buf ^= 1;
     }
@@ -251,5 +276,12 @@ hipError_t launch_conv_block64(const BlockArgs &g, const ConvArgs &a1, const Con
     };
     return c == 64 ? go(conv_block64_kernel<1>) : c == 128 ? go(conv_block64_kernel<2>) : go(conv_block64_kernel<4>);
 }
+
+#ifdef ICNN_B64_TRACE
+extern "C" int icnn_debug_trace_b64(unsigned long long *host, int n)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_b64_trace), sizeof(unsigned long long) * n);
+}
+#endif
 
 }  // namespace icnn

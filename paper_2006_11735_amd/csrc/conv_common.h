@@ -466,16 +466,21 @@ __device__ __forceinline__ v4i epilogue_bytes16(const ConvArgs &a, const v16i &a
 // the last MFMA, behind a branch: the reads returned the sums without the last product, now and then), and the
 // hardware does not hold the reader back.  Twenty wait states, what a 16-pass matrix instruction needs; the empty
 // statements before and after tie every accumulator tile to the wait, so neither an MFMA nor a reader can cross it.
+#ifdef ICNN_NO_DRAIN            // measurement only: what the wait states and the register pinning cost
+#define ICNN_DRAIN_NOPS ""
+#else
+#define ICNN_DRAIN_NOPS "s_nop 15\n\ts_nop 3"
+#endif
 __device__ __forceinline__ void mfma_drain(v16i &acc)
 {
-    asm volatile("s_nop 15\n\ts_nop 3" : "+v"(acc));
+    asm volatile(ICNN_DRAIN_NOPS : "+v"(acc));
 }
 template <int N>
 __device__ __forceinline__ void mfma_drain(v16i (&acc)[N])
 {
 #pragma unroll
     for (int i = 0; i < N; ++i) asm volatile("" : "+v"(acc[i]));
-    asm volatile("s_nop 15\n\ts_nop 3");
+    asm volatile(ICNN_DRAIN_NOPS);
 #pragma unroll
     for (int i = 0; i < N; ++i) asm volatile("" : "+v"(acc[i]));
 }
@@ -486,7 +491,7 @@ __device__ __forceinline__ void mfma_drain(v16i (&acc)[M][N])
     for (int i = 0; i < M; ++i)
 #pragma unroll
         for (int j = 0; j < N; ++j) asm volatile("" : "+v"(acc[i][j]));
-    asm volatile("s_nop 15\n\ts_nop 3");
+    asm volatile(ICNN_DRAIN_NOPS);
 #pragma unroll
     for (int i = 0; i < M; ++i)
 #pragma unroll

@@ -94,7 +94,8 @@ __global__ __launch_bounds__(256, 3) void conv_stem_pool_kernel(const ConvArgs a
     // is picture pixel (2 * (2 py0 - 1) - pad_h, 2 * (2 px0 - 1) - pad_w)
     // The channel bytes of a pixel are loaded one by one (a picture's pixels are 1 to 4 bytes apart) and stay in their
     // own registers until store_patch() combines them: the loads of the next tile travel during the multiplication.
-    uint32_t raw[kStemPerThread][4];
+    uint32_t word[kStemPerThread];         // a patch pixel's channels (and what follows them) as one word, fetched a tile ahead
+    int shift_ok[kStemPerThread];          // bit 0: the pixel lies inside the picture; bits 1..: bytes the word was read early
     int rel[kStemPerThread];        // byte offset of the thread's patch pixels from the patch's first pixel (tile-invariant)
 #pragma unroll
     for (int i = 0; i < kStemPerThread; ++i) {
@@ -102,6 +103,8 @@ __global__ __launch_bounds__(256, 3) void conv_stem_pool_kernel(const ConvArgs a
         const int r = e / kStemPitch, c = e - r * kStemPitch;
         rel[i] = (r * a.W + c) * a.in_cs;
     }
+    typedef uint32_t u32_a1 __attribute__((aligned(1)));
+    const uint32_t cmask = a.Cin >= 4 ? 0xffffffffu : (1u << (8 * a.Cin)) - 1u;      // the pixel's own channels
     auto fetch_patch = [&](int v) {
         int n, py0, px0;
         tile_origin(v, n, py0, px0);
@@ -113,10 +116,14 @@ __global__ __launch_bounds__(256, 3) void conv_stem_pool_kernel(const ConvArgs a
             const int r = e / kStemPitch, c = e - r * kStemPitch;
             const int iy = iy0 + r, ix = ix0 + c;
             const bool ok = n < a.N && r < g.patch_rows && c < g.patch_cols && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
+            // One unaligned 4-byte load per pixel (its cin <= 4 bytes and whatever follows them), masked to the pixel's
+            // channels afterwards.  The tensor's last pixels, where four bytes would run past the end, are read one to three
+            // bytes early and shifted down.
             const uint8_t *p = ok ? base + rel[i] : a.x;
-            const uint32_t m = ok ? a.in_xor & 0xffu : 0u;       // a pixel outside the picture: zero after the "- 128" too
-#pragma unroll
-            for (int ch = 0; ch < 4; ++ch) raw[i][ch] = ok && ch < a.Cin ? (uint32_t)p[ch < a.Cin ? ch : 0] ^ m : 0u;
+            const long long room = (long long)a.x_bytes - (p - a.x);               // bytes from p to the end of the tensor
+            const int back = ok && room < 4 ? (int)(4 - room) : 0;
+            word[i] = *(const u32_a1 *)(p - back);
+            shift_ok[i] = (ok ? 1 : 0) | (back << 1);
         }
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -124,7 +131,9 @@ __global__ __launch_bounds__(256, 3) void conv_stem_pool_kernel(const ConvArgs a
 #pragma unroll
         for (int i = 0; i < kStemPerThread; ++i) {
             const int e = tid + 256 * i;
-            if (e < patch_words) patch[buf * patch_words + e] = raw[i][0] | (raw[i][1] << 8) | (raw[i][2] << 16) | (raw[i][3] << 24);
+            const uint32_t v = (word[i] >> (8 * (shift_ok[i] >> 1))) & cmask;
+            // a pixel outside the picture: zero after the "- 128" too
+            if (e < patch_words) patch[buf * patch_words + e] = (shift_ok[i] & 1) ? v ^ (a.in_xor & cmask) : 0u;
         }
     };
 
@@ -221,18 +230,26 @@ __global__ __launch_bounds__(256, 3) void conv_stem_pool_kernel(const ConvArgs a
             const int ty = pp / kStemPW, tx = pp - ty * kStemPW;
             const int py = py0 + ty, px = px0 + tx;
             if (py >= g.Hp || px >= g.Wp) continue;
-            uint32_t m[4] = {0, 0, 0, 0};
+            // bytewise maximum in two halves: even and odd bytes as 16-bit lanes, split once per loaded word
+            typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+            u16x2 me[4] = {}, mo[4] = {};
 #pragma unroll
             for (int i = 0; i < 3; ++i)
 #pragma unroll
                 for (int jx = 0; jx < 3; ++jx) {
                     const int q = (2 * ty + i) * kStemCW + 2 * tx + jx;
                     const v4i w = *(const v4i *)(cbuf + q * ROW_PITCH + cgp * 16);
-                    m[0] = max_bytes(m[0], (uint32_t)w.x); m[1] = max_bytes(m[1], (uint32_t)w.y);
-                    m[2] = max_bytes(m[2], (uint32_t)w.z); m[3] = max_bytes(m[3], (uint32_t)w.w);
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        const uint32_t x = (uint32_t)w[d];
+                        me[d] = __builtin_elementwise_max(me[d], __builtin_bit_cast(u16x2, x & 0x00ff00ffu));
+                        mo[d] = __builtin_elementwise_max(mo[d], __builtin_bit_cast(u16x2, (x >> 8) & 0x00ff00ffu));
+                    }
                 }
-            *(v4i *)((uint8_t *)a.out + ((size_t)(n * g.Hp + py) * g.Wp + px) * a.out_cs + a.out_co + cgp * 16) =
-                v4i{(int)m[0], (int)m[1], (int)m[2], (int)m[3]};
+            v4i o;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) o[d] = (int)(__builtin_bit_cast(uint32_t, me[d]) | (__builtin_bit_cast(uint32_t, mo[d]) << 8));
+            *(v4i *)((uint8_t *)a.out + ((size_t)(n * g.Hp + py) * g.Wp + px) * a.out_cs + a.out_co + cgp * 16) = o;
         }
         __syncthreads();
         buf ^= 1;
@@ -256,7 +273,7 @@ hipError_t launch_conv_stem_pool(const ConvArgs &a, int hp, int wp, hipStream_t 
     g.patch_cols = 4 * kStemPW + a.KW;
     g.ksteps = a.ksteps;
     g.cout_chunks = a.Cout / 32;
-    if (a.KH > 8 || a.KW > 8 || g.patch_cols > kStemPitch || g.patch_rows > kStemMaxRows || (a.Cout != 32 && a.Cout != 64) ||
+    if (a.x_bytes < 4 || a.KH > 8 || a.KW > 8 || g.patch_cols > kStemPitch || g.patch_rows > kStemMaxRows || (a.Cout != 32 && a.Cout != 64) ||
         a.ksteps != (a.KH * 32 + 63) / 64)
         return hipErrorInvalidValue;
     const size_t lds_bytes = (size_t)g.cout_chunks * g.ksteps * kChunkBytes + 2 * (size_t)kStemMaxRows * kStemPitch * 4 +
