@@ -39,12 +39,22 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def layer_work(net, op, images, fused_proj=None, fused_block=None, fused_pool=None, fused_pair=None):
+def layer_work(net, op, images, fused_proj=None, fused_block=None, fused_pool=None, fused_pair=None, fused_projblock=None):
     """Algorithmic ops and bytes of one conv launch (true sizes, input counted once).  With a
     projection fused into the launch, its ops, input and weights are added and the int32 skip
     tensor is not counted (it never exists).  With a whole bottleneck block in the launch: the ops of its
     three layers (true sizes: the recomputed halo is not work), the block input once (it is also the skip
     operand), all weights and biases, the block output; the middle tensors are not counted (they never exist)."""
+    if fused_projblock is not None:
+        # a stage's opening block, projection included, in one launch: the ops of its four layers; the block input once (it
+        # feeds the first layer and the projection), all weights, the output; neither middle tensor nor the int32 skip tensor
+        o1, o2, proj = fused_projblock
+        ops1, b1, m, k1 = layer_work(net, o1, images)
+        ops2, b2, _, k2 = layer_work(net, o2, images)
+        ops3, b3, _, k3 = layer_work(net, op, images, fused_proj=proj)
+        mid = m * o1["cout"]
+        x_bytes = images * net["buffers"][o1["src"]]["shape"][1] * net["buffers"][o1["src"]]["shape"][2] * o1["cin"]
+        return ops1 + ops2 + ops3, (b1 - mid) + (b2 - 2 * mid) + (b3 - mid - x_bytes), m, k1 + k2 + k3
     if fused_pair is not None:
         # two pointwise layers in one launch: both layers' ops; the first layer's input, skip operand and output, both
         # layers' weights, the second layer's output (the second layer's input is not read back from memory)
@@ -391,21 +401,22 @@ def main():
     rows = []
     for step, ms in zip(g.steps, layer_ms):
         kind, op = step[0], step[1]
-        if kind not in ("conv", "conv_pc", "dual", "dual_pc", "block", "convpool", "pair"):
+        if kind not in ("conv", "conv_pc", "dual", "dual_pc", "block", "convpool", "pair", "projblock"):
             other_ms += ms
             rows.append({"name": op["dst"], "kind": kind, "ms": ms})
             continue
         ops, byts, m, k = layer_work(net, op, images, g.fused_proj.get(op["name"]) if kind in ("dual", "dual_pc") else None,
                                      g.fused_block.get(op["name"]) if kind == "block" else None,
                                      g.fused_pool.get(op["name"]) if kind == "convpool" else None,
-                                     g.fused_pair.get(op["name"]) if kind == "pair" else None)
+                                     g.fused_pair.get(op["name"]) if kind == "pair" else None,
+                                     g.fused_projblock.get(op["name"]) if kind == "projblock" else None)
         conv_ops += ops
         conv_ms += ms
         conv_bytes += byts
         tops = ops / (ms * 1e-3) / 1e12
         attain = min(INT8_MFMA_PEAK_TOPS, ops / byts * HBM_PEAK_GBS / 1e3)
         rows.append({"name": (op["name"][:-3] + "_block" if kind == "block" else op["name"]) + ("+proj" if kind in ("dual", "dual_pc") else "") +
-                             ("+pool" if kind == "convpool" else "") + ("+next_c1" if kind == "pair" else ""), "kind": "conv", "M": m, "N": op["cout"], "K": k, "ms": ms,
+                             ("+pool" if kind == "convpool" else "") + ("+next_c1" if kind == "pair" else "") + ("_block+proj" if kind == "projblock" else ""), "kind": "conv", "M": m, "N": op["cout"], "K": k, "ms": ms,
                      "tops": tops, "pct_mfma_peak": 100 * tops / INT8_MFMA_PEAK_TOPS,
                      "pct_attainable": 100 * tops / attain, "gbs": byts / (ms * 1e-3) / 1e9})
     for r in rows:

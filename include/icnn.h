@@ -294,6 +294,23 @@ int iconv2d_bottleneck_brelu(const icnn_conv_desc *c1, const void *x, const void
                              void *y, void *stream);
 
 /*
+ * The bottleneck block that opens a stage, projection skip included, as one launch (Section 4.1, the skip connection
+ * "after convolution"; Section 3.1 for each layer).  Result: exactly that of
+ *     iconv2d_brelu(c1, x,  w1_packed, bias1, NULL, t1, ...);                      // 1x1, stride 1
+ *     iconv2d_brelu(c2, t1, w2_packed, bias2, NULL, t2, ...);                      // 3x3, stride 1, padding 1
+ *     iconv2d_dual_brelu(c3, t2, w3_packed, bias3, cp, x, wp_packed, biasp, y, ...);   // 1x1 + 1x1 projection of x
+ * without t1, t2 or the projection's int32 result ever existing.  c3 and cp as for iconv2d_dual_brelu (c3: res_mode
+ * ICNN_RES_PRE, res_dtype ICNN_S32, its res_mul / res_shift rescale the projection; cp: ICNN_OUT_RAW_S32; |bias| <= 2^28;
+ * the same no-overflow proof), c1 and c2 as for iconv2d_bottleneck_brelu.  Shape it takes: 64 -> 64 -> 64 -> 256 channels
+ * with a 64 -> 256 projection, all strides 1 (the block after the max-pool in the bottleneck ResNets), an 8-bit output.
+ * Anything else returns ICNN_E_UNSUPPORTED having launched nothing.
+ */
+int iconv2d_bottleneck_dual_brelu(const icnn_conv_desc *c1, const void *x, const void *w1_packed, const int32_t *bias1,
+                                  const icnn_conv_desc *c2, const void *w2_packed, const int32_t *bias2,
+                                  const icnn_conv_desc *c3, const void *w3_packed, const int32_t *bias3,
+                                  const icnn_conv_desc *cp, const void *wp_packed, const int32_t *biasp, void *y, void *stream);
+
+/*
  * Two pointwise layers as one launch: the 1x1 convolution that closes a residual block, skip operand merged in its
  * epilogue (Section 4.1; Section 3.1 for each layer), and the 1x1 convolution that opens the next block and reads
  * that result.  Result: exactly that of

@@ -449,6 +449,16 @@ int iconv2d_brelu_pc(const icnn_conv_desc *d, const void *x, const void *w_packe
     return conv_layer(d, x, w_packed, bias, pc_packed, res, y, workspace, stream, "iconv2d_brelu_pc");
 }
 
+// Y_main + [Y_proj * res_mul / 2^res_shift] inside int32?  |Y_proj| <= Kp*128*128 + 2^28, |Y_main| <= Km*128*128 + 2^28
+// under the bias contract (int8 inputs and weights may both be -128)
+static bool merged_sum_fits(long long k_main, long long k_proj, int res_mul, int res_shift)
+{
+    const long long yp = k_proj * 128 * 128 + (1LL << 28);
+    const long long ym = k_main * 128 * 128 + (1LL << 28);
+    const __int128 s_max = (((__int128)yp * res_mul) >> res_shift) + 2;
+    return s_max + ym <= 0x7fffffffLL;
+}
+
 static int dual_layer(const icnn_conv_desc *m, const void *x_main, const void *w_main_packed,
                       const int32_t *bias_main, const void *pc, const icnn_conv_desc *p, const void *x_proj,
                       const void *w_proj_packed, const int32_t *bias_proj, void *y, void *stream, const char *what)
@@ -473,15 +483,8 @@ static int dual_layer(const icnn_conv_desc *m, const void *x_main, const void *w
     }
     if (!aligned16(x_main) || !aligned16(x_proj) || !aligned16(y))
         return fail(ICNN_E_UNSUPPORTED, "fused block needs 16-byte aligned tensors");
-    // |Y_proj| <= Kp*128*128 + 2^28, |Y_main| <= Km*128*128 + 2^28 under the bias contract (int8 inputs and
-    // weights may both be -128)
-    {
-        const long long yp = (long long)gp.K * 128 * 128 + (1LL << 28);
-        const long long ym = (long long)gm.K * 128 * 128 + (1LL << 28);
-        const __int128 s_max = (((__int128)yp * m->res_mul) >> m->res_shift) + 2;
-        if (s_max + ym > 0x7fffffffLL)
-            return fail(ICNN_E_UNSUPPORTED, "cannot prove that the merged sum stays inside int32 for these sizes");
-    }
+    if (!merged_sum_fits(gm.K, gp.K, m->res_mul, m->res_shift))
+        return fail(ICNN_E_UNSUPPORTED, "cannot prove that the merged sum stays inside int32 for these sizes");
     ConvArgs a, b;
     // the main layer's arguments without its skip operand (the projection is accumulated in registers)
     icnn_conv_desc m0 = *m;
@@ -603,9 +606,77 @@ int iconv2d_bottleneck_brelu(const icnn_conv_desc *c1, const void *x, const void
     b.per_xcd = 0;              // set by the launcher
     b.k1 = c / 64;
     b.nchunk3 = c3->cout / mid;
-    if (!g_tuning.no_block64 && conv_block64_takes(b, a1, a3) && conv_block64_lds_bytes(c) <= 160 * 1024)
-        return launched(launch_conv_block64(b, a1, a2, a3, (hipStream_t)stream), "iconv2d_bottleneck_brelu");
+    if (!g_tuning.no_block64 && conv_block64_takes(b, a1, a3) && conv_block64_lds_bytes(c, c, false) <= 160 * 1024)
+        return launched(launch_conv_block64(b, a1, a2, a3, nullptr, (hipStream_t)stream), "iconv2d_bottleneck_brelu");
     return launched(launch_conv_block(b, a1, a2, a3, (hipStream_t)stream), "iconv2d_bottleneck_brelu");
+}
+
+int iconv2d_bottleneck_dual_brelu(const icnn_conv_desc *c1, const void *x, const void *w1_packed, const int32_t *bias1,
+                                  const icnn_conv_desc *c2, const void *w2_packed, const int32_t *bias2,
+                                  const icnn_conv_desc *c3, const void *w3_packed, const int32_t *bias3,
+                                  const icnn_conv_desc *cp, const void *wp_packed, const int32_t *biasp, void *y, void *stream)
+{
+    ConvGeom g1, g2, g3, gp;
+    int rc = check_conv(c1, &g1);
+    if (rc) return rc;
+    if ((rc = check_conv(c2, &g2))) return rc;
+    if ((rc = check_conv(c3, &g3))) return rc;
+    if ((rc = check_conv(cp, &gp))) return rc;
+    if (c3->res_mode != ICNN_RES_PRE || c3->res_dtype != ICNN_S32)
+        return fail(ICNN_E_PARAM, "the last layer must describe an int32 skip operand joined before requantisation");
+    if (cp->out_mode != ICNN_OUT_RAW_S32 || cp->res_mode != ICNN_RES_NONE)
+        return fail(ICNN_E_PARAM, "projection layer must have a raw int32 output and no skip operand");
+    for (const icnn_conv_desc *d : {c1, c2, c3, cp}) {
+        if (d->n != c1->n || d->h != c1->h || d->w != c1->w)
+            return fail(ICNN_E_SHAPE, "the layers of a block must share n, h, w");
+        if (d->in_signed != ICNN_IN_U8_LE127 || d->in_sub128)
+            return fail(ICNN_E_UNSUPPORTED, "fused block takes unsigned inputs up to 127 only");
+        if (d->stride_h != 1 || d->stride_w != 1) return fail(ICNN_E_UNSUPPORTED, "fused block needs stride 1");
+    }
+    for (const icnn_conv_desc *d : {c1, c3, cp})
+        if (d->kh != 1 || d->kw != 1 || d->pad_h || d->pad_w) return fail(ICNN_E_UNSUPPORTED, "fused block is 1x1, then 3x3 with padding 1, then 1x1, with a 1x1 projection");
+    if (c2->kh != 3 || c2->kw != 3 || c2->pad_h != 1 || c2->pad_w != 1)
+        return fail(ICNN_E_UNSUPPORTED, "fused block is 1x1, then 3x3 with padding 1, then 1x1, with a 1x1 projection");
+    if (c1->cin != 64 || c1->cout != 64 || c2->cin != 64 || c2->cout != 64 || c3->cin != 64 || c3->cout != 256 || cp->cin != 64 ||
+        cp->cout != 256)
+        return fail(ICNN_E_UNSUPPORTED, "fused projection block is 64 -> 64 -> 64 -> 256 channels with a 64 -> 256 projection");
+    if (cp->in_c_stride != c1->in_c_stride) return fail(ICNN_E_SHAPE, "the projection reads the block input: same pitch as the first layer's input");
+    for (const icnn_conv_desc *d : {c1, c2})
+        if ((d->out_mode != ICNN_OUT_BRELU_U8 && d->out_mode != ICNN_OUT_CLAMP_U8) || d->res_mode != ICNN_RES_NONE ||
+            (d->out_mode == ICNN_OUT_BRELU_U8 ? d->bound_q : d->hi) > 127)
+            return fail(ICNN_E_UNSUPPORTED, "the first two layers must store unsigned bytes up to 127 and take no skip operand");
+    if (c3->out_mode == ICNN_OUT_RAW_S32) return fail(ICNN_E_UNSUPPORTED, "fused projection block stores 8-bit outputs");
+    if (!aligned16(x) || c1->in_c_stride % 16 != 0) return fail(ICNN_E_UNSUPPORTED, "fused block needs a 16-byte aligned input");
+    if (!merged_sum_fits(g3.K, gp.K, c3->res_mul, c3->res_shift))
+        return fail(ICNN_E_UNSUPPORTED, "cannot prove that the merged sum stays inside int32 for these sizes");
+    ConvArgs a1, a2, a3, ap;
+    int32_t dummy = 0;
+    icnn_conv_desc m0 = *c3;                      // the last layer without its skip operand: the projection is accumulated in registers
+    m0.res_mode = ICNN_RES_NONE;
+    if ((rc = fill_conv_args(c1, g1, x, w1_packed, bias1, nullptr, &dummy, a1))) return rc;
+    if ((rc = fill_conv_args(c2, g2, x, w2_packed, bias2, nullptr, &dummy, a2))) return rc;
+    if ((rc = fill_conv_args(&m0, g3, x, w3_packed, bias3, nullptr, y, a3))) return rc;
+    if ((rc = fill_conv_args(cp, gp, x, wp_packed, biasp, nullptr, &dummy, ap))) return rc;
+    if (!a3.epi_vec) return fail(ICNN_E_UNSUPPORTED, "fused block needs a 16-byte aligned output");
+    if (!a1.vec_bias || !a2.vec_bias || !a3.vec_bias || !ap.vec_bias) return fail(ICNN_E_UNSUPPORTED, "fused block needs 16-byte aligned bias arrays");
+    if (a1.x_bytes >= 0x7fffff00u || g1.M > 0x7fffffffLL) return fail(ICNN_E_UNSUPPORTED, "fused block needs tensors below 2 GiB");
+    ProjArgs q = {};
+    q.x = ap.x; q.wp = ap.wp; q.bias = ap.bias;
+    q.H = cp->h; q.W = cp->w; q.Cin = cp->cin; q.in_cs = cp->in_c_stride; q.sh = 1; q.sw = 1;
+    q.ksteps = gp.ksteps; q.x_bytes = ap.x_bytes; q.wp_bytes = ap.wp_bytes;
+    q.res_mul = c3->res_mul; q.res_shift = c3->res_shift; q.vec_bias = ap.vec_bias;
+    BlockArgs b;
+    b.x = (const uint8_t *)x; b.x_bytes = a1.x_bytes; b.x_cs = c1->in_c_stride;
+    b.N = c1->n; b.H = c1->h; b.W = c1->w;
+    if (!conv_block_tile(b.H, b.W, b)) return fail(ICNN_E_UNSUPPORTED, "no tile shape for this image");
+    const long long tiles = (long long)b.tiles_per_img * b.N;
+    if (tiles > 0x7fffffffLL) return fail(ICNN_E_SHAPE, "too many tiles");
+    b.n_tiles = (int)tiles;
+    b.per_xcd = 0;
+    b.k1 = 1;
+    b.nchunk3 = 4;
+    if (!conv_block64_proj_takes(a1, a3, q)) return fail(ICNN_E_UNSUPPORTED, "fused projection block does not take these layers");
+    return launched(launch_conv_block64(b, a1, a2, a3, &q, (hipStream_t)stream), "iconv2d_bottleneck_dual_brelu");
 }
 
 int iconv2d_pair_brelu(const icnn_conv_desc *c3, const void *t, const void *w3_packed, const int32_t *bias3, const void *res,

@@ -313,6 +313,7 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
             p3[j] = ok3[j] ? (n * g.H + oy) * g.W + ox : 0;
         }
         const bool fetch_res = res8_applies(a3);
+        const bool bytes3 = a3.out_mode != 3 && a3.epi_mode / 4 != 2 && (a3.res_mode == 0 || fetch_res);
         v4i res8[TP2];
         auto fetch_res8 = [&](int ch) {
 #pragma unroll
@@ -508,10 +509,19 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
                 }
                 BLK_TR(21);
                 mfma_drain(acc);
-                static_for<TP2>([&](auto jc) {
-                    constexpr int j = decltype(jc)::value;
-                    if (ok3[j]) epilogue_px16(a3, acc[j], p3[j], co0, res8[j]);
-                });
+                if (bytes3) {
+                    // an 8-bit output whose skip operand, if any, is the 8-bit kind joined before requantisation: the short form
+                    static_for<TP2>([&](auto jc) {
+                        constexpr int j = decltype(jc)::value;
+                        const v4i w = fetch_res ? epilogue_bytes16<1>(a3, acc[j], res8[j]) : epilogue_bytes16<0>(a3, acc[j], res8[j]);
+                        if (ok3[j]) *(v4i *)((uint8_t *)a3.out + (size_t)p3[j] * a3.out_cs + a3.out_co + co0) = w;
+                    });
+                } else {
+                    static_for<TP2>([&](auto jc) {
+                        constexpr int j = decltype(jc)::value;
+                        if (ok3[j]) epilogue_px16(a3, acc[j], p3[j], co0, res8[j]);
+                    });
+                }
                 BLK_TR(22);
                 // the next chunk's skip operands travel during its K steps (the first chunk's during phases 1 and 2)
                 if (ch + 1 < nchunk3) fetch_res8(ch + 1);

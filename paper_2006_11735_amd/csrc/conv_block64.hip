@@ -14,6 +14,10 @@
 //   phase 3  y = epilogue(W3 b + b3, skip): a wave owns one of the C/32 output chunks; the skip operand is the block
 //            input, read from the patch in LDS (it is still there: nothing overwrites a tile's patch before the
 //            tile is finished), so the input crosses the memory system once
+// PROJ: the block that opens a stage instead (Section 4.1, skip connection "after convolution"): its skip operand is a
+// projection convolution of the block input, W_p x + b_p, rescaled to the main path's ratio and added before the last
+// layer's products, exactly as the two-GEMM kernel of the projection blocks does; here its two MFMAs per pixel group
+// read the pixel's own patch row, and the last layer's chunk count no longer follows from the input width.
 // Four workgroup barriers per tile.  Same MFMA instruction, accumulator layout, packed weights and epilogue
 // arithmetic as the other convolution kernels: the result is that of the three separate layers, bit for bit.
 #include "conv_common.h"
@@ -35,20 +39,20 @@ __device__ unsigned long long g_b64_trace[512];
 
 constexpr int kB64Rows = 160;        // patch rows: five pixel groups of 32 (output pixel slots of a tile: 128, four groups)
 
-template <int K1>                    // C / 64: 1, 2 or 4
-__global__ __launch_bounds__(512, 2) void conv_block64_kernel(const BlockArgs g, const ConvArgs a1, const ConvArgs a2, const ConvArgs a3)
+template <int K1, int NCH3, bool PROJ>       // input channels / 64 (1, 2 or 4); output channels / 32 (2, 4 or 8); projection skip
+__global__ __launch_bounds__(512, 2) void conv_block64_kernel(const BlockArgs g, const ConvArgs a1, const ConvArgs a2, const ConvArgs a3,
+                                                              const ProjArgs pj)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int SLICE = kB64Rows * 64;             // one 64-channel slice of a patch
     constexpr int PATCH = K1 * SLICE;
-    constexpr int C = K1 * 64;
-    constexpr int NCH3 = 2 * K1;                     // 32-channel chunks of the last layer
-    constexpr int NP3 = K1;                          // pixel groups of a wave in phase 3 (8 waves, 4 * NCH3 items)
+    constexpr int CO = NCH3 * 32;                    // output channels of the last layer
+    constexpr int NP3 = NCH3 / 2;                    // pixel groups of a wave in phase 3 (8 waves, 4 * NCH3 items)
     constexpr int NCOPY = 10 * K1;                   // 1 KiB copies of a patch (16 rows of a slice each)
     constexpr int CPW = (NCOPY + 7) / 8;             // copies per wave
     constexpr unsigned OOB = 0x80000000u;
 
-    // LDS: two patches of x | a on the patch (later b on the tile) | biases [64] layer 1, [64] layer 2, [C] layer 3
+    // LDS: two patches of x | a on the patch (later b on the tile) | biases [64] layer 1, [64] layer 2, [CO] layer 3, [CO] projection
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     uint8_t *const abuf = lds + 2 * PATCH;
     uint8_t *const bbuf = abuf;                      // b overwrites a once every wave has left phase 2
@@ -114,6 +118,7 @@ __global__ __launch_bounds__(512, 2) void conv_block64_kernel(const BlockArgs g,
     const int ch3 = wave % NCH3;                     // chunk of layer 3
     const int pg3_0 = (wave / NCH3) * NP3;           // its first pixel group there
     v4i w1[2 * K1], w2[18], w3[2];
+    [[maybe_unused]] v4i wq[2 * K1];                 // the projection's chunk ch3
     {
         const v4i *p1 = (const v4i *)(a1.wp + (size_t)c12 * K1 * kChunkBytes) + lane;
         const v4i *p2 = (const v4i *)(a2.wp + (size_t)c12 * 9 * kChunkBytes) + lane;
@@ -124,8 +129,14 @@ __global__ __launch_bounds__(512, 2) void conv_block64_kernel(const BlockArgs g,
         for (int f = 0; f < 18; ++f) w2[f] = p2[f * 64];
 #pragma unroll
         for (int f = 0; f < 2; ++f) w3[f] = p3[f * 64];
+        if constexpr (PROJ) {
+            const v4i *pq = (const v4i *)(pj.wp + (size_t)ch3 * K1 * kChunkBytes) + lane;
+#pragma unroll
+            for (int f = 0; f < 2 * K1; ++f) wq[f] = pq[f * 64];
+        }
     }
-    for (int i = tid; i < 128 + C; i += 512) btab[i] = i < 64 ? a1.bias[i] : (i < 128 ? a2.bias[i - 64] : a3.bias[i - 128]);
+    for (int i = tid; i < 128 + (PROJ ? 2 : 1) * CO; i += 512)
+        btab[i] = i < 64 ? a1.bias[i] : (i < 128 ? a2.bias[i - 64] : (i < 128 + CO ? a3.bias[i - 128] : pj.bias[i - 128 - CO]));
 
     // tile-invariant positions of phase 2: output slot q = 32 pg12 + col is tile pixel (q / TW, q % TW), whose centre
     // tap is patch row (ty + 1) * PW + tx + 1; slots beyond the tile compute on row PW + 1 and are never stored
@@ -213,21 +224,41 @@ __global__ __launch_bounds__(512, 2) void conv_block64_kernel(const BlockArgs g,
         static_for<NP3>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
             const int q = 32 * (pg3_0 + j) + col;
-            v16i acc = bias16(btab + 128 + ch3 * 32 + half * 16);
-#pragma unroll
-            for (int kq = 0; kq < 2; ++kq)
-                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w3[kq], *(const v4i *)(bbuf + b_slot_offset(q, kq * 2 + half)), acc, 0, 0, 0);
-            mfma_drain(acc);
             const bool in_tile = q < g.TH * g.TW;
             const int ty = in_tile ? (int)(((unsigned)q * g.inv_tw) >> 16) : 0;
             const int tx = in_tile ? q - ty * g.TW : 0;
             const int oy = y0 + ty, ox = x0 + tx;
             const bool ok = in_tile && oy < g.H && ox < g.W;
-            // the skip operand: channels 32 ch3 + 16 half .. + 16 of the pixel's own patch row
-            const int prow = (ty + 1) * g.PW + tx + 1;
+            const int prow = (ty + 1) * g.PW + tx + 1;           // the pixel's own patch row
             const int co = ch3 * 32 + half * 16;
-            const v4i r8 = *(const v4i *)(xb + (co >> 6) * SLICE + b_slot_offset(prow, (co & 63) >> 4));
-            const v4i w = has_res ? epilogue_bytes16<1>(a3, acc, r8) : epilogue_bytes16<0>(a3, acc, r8);
+            v16i acc;
+            if constexpr (PROJ) {
+                // the projection's sum on the pixel's own patch row, brought to the main path's ratio; the last layer's bias
+                // and products come on top (the host has proved that the sum stays inside int32)
+                acc = bias16(btab + 128 + CO + co);
+#pragma unroll
+                for (int f = 0; f < 2 * K1; ++f)
+                    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wq[f], *(const v4i *)(xb + (f >> 1) * SLICE + b_slot_offset(prow, (f & 1) * 2 + half)),
+                                                                acc, 0, 0, 0);
+                mfma_drain(acc);
+                const v16i b3 = bias16(btab + 128 + co);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[r] = (int)rsr64((int64_t)acc[r] * pj.res_mul, pj.res_shift) + b3[r];
+            } else {
+                acc = bias16(btab + 128 + co);
+            }
+#pragma unroll
+            for (int kq = 0; kq < 2; ++kq)
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w3[kq], *(const v4i *)(bbuf + b_slot_offset(q, kq * 2 + half)), acc, 0, 0, 0);
+            mfma_drain(acc);
+            v4i w;
+            if constexpr (PROJ) {
+                w = epilogue_bytes16<0>(a3, acc, v4i{0, 0, 0, 0});
+            } else {
+                // the skip operand: channels co .. co + 16 of the pixel's own patch row
+                const v4i r8 = *(const v4i *)(xb + (co >> 6) * SLICE + b_slot_offset(prow, (co & 63) >> 4));
+                w = has_res ? epilogue_bytes16<1>(a3, acc, r8) : epilogue_bytes16<0>(a3, acc, r8);
+            }
             if (ok) *(v4i *)((uint8_t *)a3.out + (size_t)((n * g.H + oy) * g.W + ox) * a3.out_cs + a3.out_co + co) = w;
             B64_TR(10);
         });
@@ -241,9 +272,9 @@ __global__ __launch_bounds__(512, 2) void conv_block64_kernel(const BlockArgs g,
 }
 
 // ------------------------------------------------------------------ dispatch
-size_t conv_block64_lds_bytes(int c)
+size_t conv_block64_lds_bytes(int c_in, int c_out, bool proj)
 {
-    return (size_t)(2 * (c / 64) + 1) * kB64Rows * 64 + (size_t)(128 + c) * 4;
+    return (size_t)(2 * (c_in / 64) + 1) * kB64Rows * 64 + (size_t)(128 + (proj ? 2 : 1) * c_out) * 4;
 }
 
 // true when the register-resident kernel takes the block: 64 middle channels, 64, 128 or 256 outer channels, an
@@ -258,23 +289,35 @@ bool conv_block64_takes(const BlockArgs &g, const ConvArgs &a1, const ConvArgs &
     return true;
 }
 
-hipError_t launch_conv_block64(const BlockArgs &g, const ConvArgs &a1, const ConvArgs &a2, const ConvArgs &a3, hipStream_t st)
+// The block with a projection skip: 64 input and middle channels, 256 output channels (the block that opens the first
+// stage of the bottleneck ResNets); a3 carries no skip operand, pj the projection of the block input
+bool conv_block64_proj_takes(const ConvArgs &a1, const ConvArgs &a3, const ProjArgs &pj)
+{
+    return a1.Cin == 64 && a1.Cout == 64 && a3.Cout == 256 && a3.out_mode != 3 && a3.res_mode == 0 && a3.epi_vec && pj.Cin == 64 &&
+           pj.ksteps == 1 && pj.sh == 1 && pj.sw == 1 && pj.vec_bias;
+}
+
+hipError_t launch_conv_block64(const BlockArgs &g, const ConvArgs &a1, const ConvArgs &a2, const ConvArgs &a3, const ProjArgs *pj,
+                               hipStream_t st)
 {
     const int c = a1.Cin;
-    const size_t lds_bytes = conv_block64_lds_bytes(c);
-    if (!conv_block64_takes(g, a1, a3) || lds_bytes > 160 * 1024 || g.n_tiles < 1) return hipErrorInvalidValue;
+    const size_t lds_bytes = conv_block64_lds_bytes(c, a3.Cout, pj != nullptr);
+    if (!(pj ? conv_block64_proj_takes(a1, a3, *pj) : conv_block64_takes(g, a1, a3)) || lds_bytes > 160 * 1024 || g.n_tiles < 1)
+        return hipErrorInvalidValue;
     BlockArgs gx = g;
     gx.per_xcd = (g.n_tiles + 7) / 8;
     const dim3 grid((unsigned)(8 * gx.per_xcd < 256 ? 8 * gx.per_xcd : 256)), block(512);
+    const ProjArgs none = {};
     auto go = [&](auto kernel) -> hipError_t {
         if (lds_bytes > 64 * 1024) {
             const hipError_t e = allow_large_lds((const void *)kernel);
             if (e != hipSuccess) return e;
         }
-        hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, gx, a1, a2, a3);
+        hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, gx, a1, a2, a3, pj ? *pj : none);
         return hipGetLastError();
     };
-    return c == 64 ? go(conv_block64_kernel<1>) : c == 128 ? go(conv_block64_kernel<2>) : go(conv_block64_kernel<4>);
+    if (pj) return go(conv_block64_kernel<1, 8, true>);
+    return c == 64 ? go(conv_block64_kernel<1, 2, false>) : c == 128 ? go(conv_block64_kernel<2, 4, false>) : go(conv_block64_kernel<4, 8, false>);
 }
 
 #ifdef ICNN_B64_TRACE

@@ -186,9 +186,11 @@ hipError_t launch_conv_stem_pool(const ConvArgs &a, int hp, int wp, hipStream_t 
 bool conv_block_tile(int H, int W, BlockArgs &g);
 size_t conv_block_lds_bytes(int mid, int c);
 hipError_t launch_conv_block(const BlockArgs &g, const ConvArgs &a1, const ConvArgs &a2, const ConvArgs &a3, hipStream_t st);
-size_t conv_block64_lds_bytes(int c);
+size_t conv_block64_lds_bytes(int c_in, int c_out, bool proj);
 bool conv_block64_takes(const BlockArgs &g, const ConvArgs &a1, const ConvArgs &a3);
-hipError_t launch_conv_block64(const BlockArgs &g, const ConvArgs &a1, const ConvArgs &a2, const ConvArgs &a3, hipStream_t st);
+bool conv_block64_proj_takes(const ConvArgs &a1, const ConvArgs &a3, const ProjArgs &pj);
+hipError_t launch_conv_block64(const BlockArgs &g, const ConvArgs &a1, const ConvArgs &a2, const ConvArgs &a3, const ProjArgs *pj,
+                               hipStream_t st);
 size_t conv_pair_lds_bytes(int c, int mid2);
 hipError_t launch_conv_pair(const ConvArgs &a3, const ConvArgs &a1, long long pixels, hipStream_t st);
 bool conv_narrow_applies(const ConvArgs &a);

@@ -41,6 +41,7 @@ class GpuNet:
         self.fused_block = {}               # last conv name -> (first, middle) conv ops fused into its launch
         self.fused_pool = {}                # first conv name -> the max-pool op fused into its launch
         self.fused_pair = {}                # block-closing conv name -> the next block's opening conv op in its launch
+        self.fused_projblock = {}           # last conv name -> (first, middle, projection) conv ops fused into its launch
         pending = {}                        # skip buffer name -> prepared projection step
         for op in net["ops"]:
             if op["op"] == "conv":
@@ -72,6 +73,7 @@ class GpuNet:
                 raise ValueError(op["op"])
         if fuse if fuse_blocks is None else fuse_blocks:
             self._fuse_blocks()
+            self._fuse_projection_blocks()
             self._fuse_first_layer()
             self._fuse_pairs()
         torch.cuda.synchronize(self.device)
@@ -140,6 +142,44 @@ class GpuNet:
                         self.fused_pair[o3["name"]] = o1
                         steps.append(("pair", o3, args))
                         i += 2
+                        continue
+            steps.append(self.steps[i])
+            i += 1
+        self.steps = steps
+
+    def _fuse_projection_blocks(self):
+        """A stage's opening bottleneck block whose last layer already runs with its projection as one dual step: the
+        two layers before it join that launch (iconv2d_bottleneck_dual_brelu) where the library accepts it; the block's
+        two middle buffers then stay untouched as well."""
+        readers = {}
+        for op in self.net["ops"]:
+            readers.setdefault(op["src"], []).append(op)
+            if op.get("res") is not None:
+                readers.setdefault(op["res"], []).append(op)
+        steps, i = [], 0
+        while i < len(self.steps):
+            trio = self.steps[i:i + 3]
+            if len(trio) == 3 and trio[0][0] == "conv" and trio[1][0] == "conv" and trio[2][0] == "dual":
+                o1, o2, o3 = (st[1] for st in trio)
+                proj = self.fused_proj[o3["name"]]
+                chain = (o2["src"] == o1["dst"] and o3["src"] == o2["dst"] and proj["src"] == o1["src"] and
+                         readers.get(o1["dst"]) == [o2] and readers.get(o2["dst"]) == [o3] and
+                         o1["dst"] not in self.net["outputs"] and o2["dst"] not in self.net["outputs"] and
+                         o1["dst_c_offset"] == 0 and o2["dst_c_offset"] == 0)
+                if chain:
+                    (d1, x, w1, b1, _r1, _y1, _ws1), (d2, _x2, w2, b2, _r2, _y2, _ws2) = trio[0][2], trio[1][2]
+                    dm, _xm, wm, bm, dp, _xp, wp, bp, y = trio[2][2]
+                    args = (d1, x, w1, b1, d2, w2, b2, dm, wm, bm, dp, wp, bp, y)
+                    try:
+                        B.iconv2d_bottleneck_dual_brelu(*args)     # also a warm-up launch
+                    except B.IcnnError as e:
+                        if e.code != B.ICNN_E_UNSUPPORTED:
+                            raise
+                    else:
+                        self.fused += [o1["dst"], o2["dst"]]
+                        self.fused_projblock[o3["name"]] = (o1, o2, proj)
+                        steps.append(("projblock", o3, args))
+                        i += 3
                         continue
             steps.append(self.steps[i])
             i += 1
@@ -270,6 +310,8 @@ class GpuNet:
             B.iconv2d_dual_brelu_pc(*args, stream=stream)
         elif kind == "pair":
             B.iconv2d_pair_brelu(*args, stream=stream)
+        elif kind == "projblock":
+            B.iconv2d_bottleneck_dual_brelu(*args, stream=stream)
         elif kind == "block":
             B.iconv2d_bottleneck_brelu(*args, stream=stream)
         elif kind == "convpool":

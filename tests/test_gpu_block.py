@@ -195,3 +195,93 @@ def test_first_layer_with_pool_refuses_other_shapes():
         with pytest.raises(B.IcnnError) as e:
             B.iconv2d_maxpool_brelu(d, *pool, 4096, 8192, 12288, 16384, stream=0)
         assert e.value.code == B.ICNN_E_UNSUPPORTED, (over, pool)
+
+
+# ---------------------------------------------------------------- the block that opens a stage: projection skip included
+def run_proj_block(seed, n, h, w, *, cbuf=64, b3_mag=4096, c3_mode="brelu", res_pair=None):
+    """64 -> 64 -> 64 -> 256 with a 64 -> 256 projection of the block input.  Returns (gpu y, oracle y)."""
+    from gpu_util import dev
+    from paper_2006_11735_amd import binding as B
+    g = rnd(seed)
+    c, mid, co = 64, 64, 256
+    x = g.integers(0, 128, size=(n, h, w, cbuf), dtype=np.uint8)
+    w1 = g.integers(-127, 128, size=(mid, 1, 1, c), dtype=np.int8)
+    w2 = g.integers(-127, 128, size=(mid, 3, 3, mid), dtype=np.int8)
+    w3 = g.integers(-127, 128, size=(co, 1, 1, mid), dtype=np.int8)
+    wq = g.integers(-127, 128, size=(co, 1, 1, c), dtype=np.int8)
+    b1, b2 = (g.integers(-4096, 4097, size=k).astype(np.int32) for k in (mid, mid))
+    b3 = g.integers(-b3_mag, b3_mag + 1, size=co).astype(np.int32)
+    bq = g.integers(-4096, 4097, size=co).astype(np.int32)
+    m1, s1 = K.bound_params(K.percentile_999(O.conv2d(x, w1, b1, cin=c, out_mode="raw_s32")), 127)
+    t1 = O.conv2d(x, w1, b1, cin=c, mul=m1, shift=s1, bound_q=127)
+    m2, s2 = K.bound_params(K.percentile_999(O.conv2d(t1, w2, b2, pad=1, out_mode="raw_s32")), 127)
+    t2 = O.conv2d(t1, w2, b2, pad=1, mul=m2, shift=s2, bound_q=127)
+    yq = O.conv2d(x, wq, bq, cin=c, out_mode="raw_s32")
+    y_main = O.conv2d(t2, w3, b3, out_mode="raw_s32")
+    rm, rs = res_pair or K.mul_shift(K.percentile_999(np.abs(yq)), K.percentile_999(y_main))
+    kw3 = dict(res=yq, res_mode="pre", res_mul=rm, res_shift=rs)
+    m3, s3 = K.bound_params(K.percentile_999(O.conv2d(t2, w3, b3, out_mode="raw_s32", **kw3)), 127)
+    if c3_mode == "linear_s8":
+        want = O.conv2d(t2, w3, b3, mul=m3, shift=s3, out_mode="linear_s8", **kw3)
+    else:
+        want = O.conv2d(t2, w3, b3, mul=m3, shift=s3, bound_q=127, **kw3)
+    d1 = B.conv_desc(n=n, h=h, w=w, cin=c, in_c_stride=cbuf, cout=mid, kh=1, kw=1, out_c_stride=mid, mul=m1, shift=s1, bound_q=127)
+    d2 = B.conv_desc(n=n, h=h, w=w, cin=mid, in_c_stride=mid, cout=mid, kh=3, kw=3, pad_h=1, pad_w=1, out_c_stride=mid, mul=m2,
+                     shift=s2, bound_q=127)
+    d3 = B.conv_desc(n=n, h=h, w=w, cin=mid, in_c_stride=mid, cout=co, kh=1, kw=1, out_c_stride=co, mul=m3, shift=s3, bound_q=127,
+                     out_mode=B.ICNN_OUT_LINEAR_S8 if c3_mode == "linear_s8" else B.ICNN_OUT_BRELU_U8,
+                     res_mode=B.ICNN_RES_PRE, res_dtype=B.ICNN_S32, res_c_stride=co, res_mul=rm, res_shift=rs)
+    dq = B.conv_desc(n=n, h=h, w=w, cin=c, in_c_stride=cbuf, cout=co, kh=1, kw=1, out_c_stride=co, out_mode=B.ICNN_OUT_RAW_S32)
+    packs = []
+    for d, wt in ((d1, w1), (d2, w2), (d3, w3), (dq, wq)):
+        pk = torch.zeros(B.iconv2d_packed_weight_bytes(d), dtype=torch.uint8, device="cuda:0")
+        B.iconv2d_prepack_weights(d, dev(wt), pk)
+        packs.append(pk)
+    y = torch.zeros(want.shape, dtype=torch.int8 if c3_mode == "linear_s8" else torch.uint8, device="cuda:0")
+    B.iconv2d_bottleneck_dual_brelu(d1, dev(x), packs[0], dev(b1), d2, packs[1], dev(b2), d3, packs[2], dev(b3), dq, packs[3],
+                                    dev(bq), y)
+    torch.cuda.synchronize()
+    return y.cpu().numpy(), want
+
+
+@pytest.mark.parametrize("shape", [(2, 56, 56), (1, 17, 23), (1, 5, 6), (14, 56, 56), (1, 1, 1), (1, 1, 150)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_fused_projection_bottleneck_equals_its_layers(shape):
+    got, want = run_proj_block(sum(shape), *shape)
+    assert got.shape == want.shape
+    assert (got == want).all(), "%d of %d bytes differ" % (int((got != want).sum()), want.size)
+    assert want.max() == 127 and want.min() == 0
+
+
+def test_fused_projection_bottleneck_variants():
+    # a wider input buffer; biases near the contract's limit (with a fixed skip ratio the proof accepts); a signed output
+    for kw in (dict(cbuf=96), dict(b3_mag=1 << 27, res_pair=(20011, 15)), dict(c3_mode="linear_s8")):
+        got, want = run_proj_block(31, 2, 11, 13, **kw)
+        assert (got == want).all(), kw
+
+
+def test_fused_projection_bottleneck_refuses_other_shapes():
+    from paper_2006_11735_amd import binding as B
+
+    def descs(**over):
+        d1 = B.conv_desc(n=1, h=8, w=8, cin=64, in_c_stride=64, cout=64, kh=1, kw=1, out_c_stride=64, mul=20000, shift=24)
+        d2 = B.conv_desc(n=1, h=8, w=8, cin=64, in_c_stride=64, cout=64, kh=3, kw=3, pad_h=1, pad_w=1, out_c_stride=64, mul=20000,
+                         shift=26)
+        d3 = B.conv_desc(n=1, h=8, w=8, cin=64, in_c_stride=64, cout=256, kh=1, kw=1, out_c_stride=256, mul=20000, shift=24,
+                         res_mode=B.ICNN_RES_PRE, res_dtype=B.ICNN_S32, res_c_stride=256, res_mul=20000, res_shift=15)
+        dq = B.conv_desc(n=1, h=8, w=8, cin=64, in_c_stride=64, cout=256, kh=1, kw=1, out_c_stride=256, out_mode=B.ICNN_OUT_RAW_S32)
+        ds = {"d1": d1, "d2": d2, "d3": d3, "dq": dq}
+        for k, v in over.items():
+            which, field = k.split("__")
+            setattr(ds[which], field, v)
+        return d1, d2, d3, dq
+    buf = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda:0")
+    bias = torch.zeros(4096, dtype=torch.int32, device="cuda:0")
+    cases = [descs(d3__cout=128, dq__cout=128, d3__out_c_stride=128, d3__res_c_stride=128, dq__out_c_stride=128),
+             descs(dq__stride_h=2, dq__stride_w=2), descs(d3__res_dtype=B.ICNN_U8), descs(dq__out_mode=B.ICNN_OUT_BRELU_U8),
+             descs(d3__out_mode=B.ICNN_OUT_RAW_S32), descs(d3__res_mul=2 ** 30, d3__res_shift=0), descs(d1__bound_q=255),
+             descs(dq__in_c_stride=128)]
+    for d1, d2, d3, dq in cases:
+        with pytest.raises(B.IcnnError):
+            B.iconv2d_bottleneck_dual_brelu(d1, buf, buf, bias, d2, buf, bias, d3, buf, bias, dq, buf, bias, buf)
+    torch.cuda.synchronize()

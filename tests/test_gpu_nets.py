@@ -138,7 +138,8 @@ def test_config3_resnet50_full_batch_sampled_images():
             assert (got == want[name]).all(), (img, name)
     # the first layer with its pool, four projection blocks and the five identity blocks of stages 1 and 2 run as
     # single launches
-    assert len(g.fused_proj) == 4 and len(g.fused_block) == 5 and len(g.fused_pool) == 1 and len(g.fused) == 4 + 2 * 5 + 1
+    assert len(g.fused_proj) == 4 and len(g.fused_block) == 5 and len(g.fused_pool) == 1 and len(g.fused) == 4 + 2 * 5 + 1 + 2
+    assert len(g.fused_projblock) == 1     # stage 1's opening block: stride 1, 64 -> 64 -> 64 -> 256
     assert len(g.fused_pair) == 4          # stage 3: blocks 1..5 share four block boundaries
     logits = g.result("logits")
     assert logits.dtype == np.int32 and logits.shape == (64, 1, 1, 1000)
