@@ -319,6 +319,9 @@ __global__ __launch_bounds__(256, ((BM / 32) * (BP / 32) > 32 ? 1 : 2)) void con
             asm volatile("" ::: "memory");
             if constexpr (LATER >= 0) ICNN_WAIT_VMCNT(LATER * LPS);
             else wait_stages_in_flight<LPS>(later);
+            // (the previous step's fragment reads have returned: lgkmcnt(0) costs nothing here, but it must hold before the
+            // barrier lets other waves refill that step's slot, wherever the compiler put the MFMAs that consumed them)
+            __builtin_amdgcn_s_waitcnt(0xC07F);
             __builtin_amdgcn_s_barrier();  // every wave's part of stage s is in LDS; the slot of step s-1 is drained
             asm volatile("" ::: "memory");
             uint8_t *istage = lds + ibuf * STAGE;
