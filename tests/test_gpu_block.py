@@ -184,6 +184,33 @@ def test_first_layer_with_pool_equals_the_two_calls(shape, raw):
     assert (got[..., :16] == 99).all() and want.max() == 127
 
 
+@pytest.mark.parametrize("cin,pitch", [(3, 4), (3, 7), (1, 2), (2, 2)])
+def test_first_layer_with_pool_picture_pitch_wider_than_cin(cin, pitch):
+    # pictures whose pixels are `pitch` bytes apart (e.g. RGB in RGBA storage): the kernel reads four bytes per pixel
+    # and keeps cin of them; the tensor's last pixels are read early and shifted
+    from gpu_util import dev
+    from paper_2006_11735_amd import binding as B
+    n, h, w, cout, k, pad = 2, 21, 26, 64, 7, 3
+    g = rnd(100 * cin + pitch)
+    xbuf = g.integers(0, 256, size=(n, h, w, pitch), dtype=np.uint8)
+    wt = g.integers(-127, 128, size=(cout, k, k, cin), dtype=np.int8)
+    b = g.integers(-4096, 4097, size=cout).astype(np.int32)
+    x = np.ascontiguousarray(xbuf[..., :cin])
+    t_raw = O.conv2d(x, wt, b, stride=2, pad=pad, in_sub128=True, out_mode="raw_s32")
+    mul, shift = K.bound_params(K.percentile_999(t_raw))
+    want = O.maxpool2d(O.conv2d(x, wt, b, stride=2, pad=pad, in_sub128=True, mul=mul, shift=shift, bound_q=127), 3, 2, 1)
+    d = B.conv_desc(n=n, h=h, w=w, cin=cin, in_c_stride=pitch, in_sub128=1, cout=cout, kh=k, kw=k, stride_h=2, stride_w=2,
+                    pad_h=pad, pad_w=pad, out_c_stride=cout, mul=mul, shift=shift, bound_q=127)
+    wp = torch.zeros(B.iconv2d_packed_weight_bytes(d), dtype=torch.uint8, device="cuda:0")
+    B.iconv2d_prepack_weights(d, dev(wt), wp)
+    # the device buffer ends with the last pixel's cin bytes: nothing behind it may be touched
+    flat = torch.from_numpy(xbuf.reshape(-1)[: xbuf.size - (pitch - cin)].copy()).to("cuda:0")
+    y = torch.zeros(want.shape, dtype=torch.uint8, device="cuda:0")
+    B.iconv2d_maxpool_brelu(d, 3, 2, 1, flat, wp, dev(b), y)
+    torch.cuda.synchronize()
+    assert (y.cpu().numpy() == want).all()
+
+
 def test_first_layer_with_pool_refuses_other_shapes():
     from paper_2006_11735_amd import binding as B
     base = dict(n=1, h=32, w=32, cin=3, in_c_stride=3, cout=64, kh=7, kw=7, stride_h=2, stride_w=2, pad_h=3, pad_w=3,

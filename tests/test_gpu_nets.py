@@ -4,6 +4,7 @@ import json
 import os
 
 import numpy as np
+import torch
 import pytest
 
 from oracle import net as ONet
@@ -248,3 +249,30 @@ def test_config4_resnet152_full_batch_sampled_images():
             assert (got == want[name]).all(), (img, name)
     assert len(g.fused_proj) == 4 and len(g.fused_block) == 2 + 7
     assert g.result("logits").shape == (128, 1, 1, 1000)
+
+
+def test_two_steps_in_flight_on_two_streams():
+    # two instances of the same network (own activation buffers, own copies of the weights) issued alternately on
+    # two streams: the library keeps no per-call state that concurrent launches could share, so both must reproduce
+    # the one-stream result
+    from paper_2006_11735_amd.netrun import GpuNet
+    net, calib = W.CONFIGS["cfg5"](), stored("cfg5")
+    nets = [GpuNet(net, 0, calib, images=16) for _ in range(2)]
+    for g in nets:
+        g.set_input()
+    nets[0].run()
+    torch.cuda.synchronize()
+    ref = {k: v.clone() for k, v in nets[0].buf.items() if k not in nets[0].fused}
+    for g in nets:
+        for k, v in g.buf.items():
+            if k != net["input"] and k not in g.fused:
+                v.zero_()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for i in range(6):
+        with torch.cuda.stream(streams[i & 1]):
+            nets[i & 1].run()
+    torch.cuda.synchronize()
+    for g in nets:
+        for k, v in ref.items():
+            assert torch.equal(v, g.buf[k]), k
