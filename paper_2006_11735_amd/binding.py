@@ -5,6 +5,9 @@ pointers.  Argument marshalling only -- no arithmetic happens here.
 import ctypes as C
 import os
 
+import torch  # noqa: F401  (first, so that the library below binds to the HIP runtime torch has loaded: two runtimes
+#                            in one process do not see the device)
+
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libicnn_mi355.so")
 

@@ -166,6 +166,9 @@ struct Tuning {
     int halo_tile = 0;     // patch-resident kernel: 1 = 128 x 128, 2 = 64 x 256
     int halo_always = 0;   // patch-resident kernel also with several tiles per workgroup and short K loops
     int no_stream = 0;     // single-channel 3x3 layers: lane-group kernel instead of the streaming one
+    int no_deep = 0;       // keep deep 3x3 layers on few pixels off the kernel whose waves split the K axis
+    int deep_plain_walk = 0;   // that kernel with the tile order of the other kernels (measurement)
+    int deep_always = 0;   // that kernel for every layer whose shape it accepts
     int no_block64 = 0;    // fused bottleneck blocks with 64 middle channels: the LDS-ring kernel instead of the register-resident one
     int ksplit = 0;        // 0 library's choice; 1 never split the K axis; 2..8 this split where it divides the K steps
 };
@@ -182,6 +185,8 @@ bool conv_fc_applies(const ConvArgs &a);
 hipError_t launch_conv_fc(const ConvArgs &a, hipStream_t st);
 bool conv_halo_applies(const ConvArgs &a);
 hipError_t launch_conv_halo(const ConvArgs &a, hipStream_t st);
+bool conv_deep_applies(const ConvArgs &a);
+hipError_t launch_conv_deep(const ConvArgs &a, hipStream_t st);
 hipError_t launch_conv_stem_pool(const ConvArgs &a, int hp, int wp, hipStream_t st);
 bool conv_block_tile(int H, int W, BlockArgs &g);
 size_t conv_block_lds_bytes(int mid, int c);

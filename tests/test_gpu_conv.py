@@ -503,6 +503,48 @@ PATCH_SHAPES = [(3, 14, 14, 128, 128, 3, 1, 1), (5, 7, 7, 192, 256, 3, 1, 1), (2
 
 @pytest.mark.parametrize("shape", PATCH_SHAPES, ids=lambda s: "x".join(map(str, s)))
 def test_patch_resident_3x3_kernel(shape):
+    from paper_2006_11735_amd import binding as B
+    B.icnn_set_tuning("no_deep", 1)          # cin % 256 == 0 would go to the kernel whose waves split the K axis
+    try:
+        check_3x3_layer(shape)
+    finally:
+        B.icnn_set_tuning("reset")
+
+
+# ---- 3x3 / stride 1 / padding 1 layers with cin % 256 == 0 on few pixels: the eight waves of a workgroup split the
+# K axis and add their partial tiles up in LDS.  Shapes: the two late-stage shapes of the residual networks (several
+# images per 128-pixel tile, a ragged last tile), cout tails, three 256-channel groups, tiny images (a tile crosses six),
+# one image, wide rows.
+DEEP_SHAPES = [(8, 7, 7, 512, 512, 3, 1, 1), (2, 14, 14, 256, 256, 3, 1, 1), (3, 14, 14, 256, 136, 3, 1, 1),
+               (1, 9, 13, 768, 64, 3, 1, 1), (6, 5, 5, 256, 96, 3, 1, 1), (1, 4, 40, 256, 40, 3, 1, 1),
+               (2, 3, 70, 512, 128, 3, 1, 1)]
+
+
+@pytest.mark.parametrize("shape", DEEP_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_3x3_kernel_whose_waves_split_the_k_axis(shape):
+    from paper_2006_11735_amd import binding as B
+    B.icnn_set_tuning("deep_always", 1)
+    try:
+        check_3x3_layer(shape)
+        n, h, w, cin, cout, k, stride, pad = shape
+        x, wt, b = make(33, n, h, w, cin, cout, k)
+        # a skip operand of each kind, and an output written at a channel offset of a wider buffer
+        sigma = 37.0 * 74 * (k * k * cin) ** 0.5
+        mul = max(1, int(round(127 / (3.0 * sigma) * (1 << 25))))
+        for kind in ("s8", "s32"):
+            r = (rnd(9).integers(-128, 128, size=(n, h, w, cout), dtype=np.int8) if kind == "s8"
+                 else rnd(9).integers(-int(sigma), int(sigma), size=(n, h, w, cout)).astype(np.int32))
+            got, want = both(x, wt, b, stride=stride, pad=pad, mul=mul, shift=25, res=r, res_mode="pre",
+                             res_mul=int(sigma / 64) if kind == "s8" else 5, res_shift=0 if kind == "s8" else 2)
+            assert (got == want).all() and len(np.unique(want)) > 64
+        canvas = rnd(10).integers(0, 256, size=(n, h, w, cout + 48), dtype=np.uint8)
+        got, want = both(x, wt, b, stride=stride, pad=pad, mul=mul, shift=25, out=canvas, out_c_offset=32)
+        assert (got == want).all() and len(np.unique(want[..., 32:32 + cout])) > 64
+    finally:
+        B.icnn_set_tuning("reset")
+
+
+def check_3x3_layer(shape):
     n, h, w, cin, cout, k, stride, pad = shape
     x, wt, b = make(31, n, h, w, cin, cout, k)
     got, want = both(x, wt, b, stride=stride, pad=pad, out_mode="raw_s32")
