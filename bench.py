@@ -309,12 +309,62 @@ def summarise_trace(stats_csv, passes):
         nc, nc / passes, tc / nc / 1e3, tc / passes / 1e6))
 
 
+def summarise_mfma(counter_csv):
+    """No GPU work: matrix-core utilisation per kernel out of one rocprofv3 --pmc run that collected
+    SQ_VALU_MFMA_BUSY_CYCLES GRBM_GUI_ACTIVE SQ_INSTS_VALU_MFMA_MOPS_I8
+    (`*_counter_collection.csv`), as a markdown table.  MFMA-busy cycles are summed over the chip's 1024 SIMDs; they are
+    set against (a) the dispatch's duration from its timestamps at the nominal 2.4 GHz and (b) GRBM_GUI_ACTIVE (summed
+    over the 8 XCCs, hence / 8), which under the profiler also covers the idle time around a short dispatch.
+    SQ_INSTS_VALU_MFMA_MOPS_I8 x 512 = executed int8 operations (padding included)."""
+    import collections
+    import csv
+    per = collections.defaultdict(lambda: collections.defaultdict(float))
+    calls = collections.Counter()
+    dur = collections.defaultdict(float)
+    seen = set()
+    for r in csv.DictReader(open(counter_csv)):
+        name = r["Kernel_Name"]
+        if "icnn::" not in name:
+            continue
+        short = name.replace("void ", "").replace("icnn::", "").split("(")[0]
+        per[short][r["Counter_Name"]] += float(r["Counter_Value"])
+        if r["Dispatch_Id"] not in seen:
+            seen.add(r["Dispatch_Id"])
+            calls[short] += 1
+            dur[short] += float(r["End_Timestamp"]) - float(r["Start_Timestamp"])
+    print("| kernel | dispatches | avg us (under the profiler) | executed int8 TOP/s | MFMA busy % of duration x 2.4 GHz | MFMA busy % of GPU-active cycles |")
+    print("|---|---|---|---|---|---|")
+    tot = collections.defaultdict(float)
+    tot_dur = 0.0
+    for short in sorted(per, key=lambda k: -dur[k]):
+        c = per[short]
+        act = c["GRBM_GUI_ACTIVE"] / 8
+        if act <= 0 or dur[short] <= 0:
+            continue
+        busy = c["SQ_VALU_MFMA_BUSY_CYCLES"] / 1024
+        print("| %s | %d | %.2f | %.0f | %.1f | %.1f |" % (
+            short, calls[short], dur[short] / calls[short] / 1e3, c["SQ_INSTS_VALU_MFMA_MOPS_I8"] * 512 / dur[short] / 1e3,
+            100 * busy / (dur[short] * 2.4), 100 * busy / act))
+        if short.startswith("conv_") and "prepack" not in short:
+            for k, v in c.items():
+                tot[k] += v
+            tot_dur += dur[short]
+    if tot_dur:
+        busy = tot["SQ_VALU_MFMA_BUSY_CYCLES"] / 1024
+        print()
+        print("all conv kernels: executed %.0f int8 TOP/s over their durations; MFMA busy %.1f %% of duration x 2.4 GHz, %.1f %% of "
+              "GPU-active cycles" % (tot["SQ_INSTS_VALU_MFMA_MOPS_I8"] * 512 / tot_dur / 1e3, 100 * busy / (tot_dur * 2.4),
+                                     100 * busy / (tot["GRBM_GUI_ACTIVE"] / 8)))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="cfg3", help="workload (cfg3 = ResNet-50-shaped, batch 64)")
+    ap.add_argument("--summarise-mfma", metavar="COUNTER_CSV", default=None,
+                    help="no GPU work: matrix-core utilisation per kernel from a rocprofv3 --pmc counter file")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers-json", default=None, help="also write the per-layer table to this file")
     ap.add_argument("--layer-reps", type=int, default=20)
@@ -331,6 +381,8 @@ def main():
                     help="no GPU work: the library's kernels of a rocprofv3 --kernel-trace --stats kernel_stats.csv as a markdown "
                          "table; PASSES = passes of the network in the profiled process")
     args = ap.parse_args()
+    if args.summarise_mfma:
+        return summarise_mfma(args.summarise_mfma)
     if args.summarise_trace:
         return summarise_trace(args.summarise_trace[0], float(args.summarise_trace[1]))
     if args.summarise_pmc:
@@ -456,7 +508,7 @@ def main():
         "conv_tops": conv_tops,
         "pct_int8_mfma_peak": 100 * conv_tops / INT8_MFMA_PEAK_TOPS,
         "whole_step_tops": conv_ops / (ms_per_step * 1e-3) / 1e12,
-        "roofline": {"kernel": "conv kernels (all %d conv launches of a step: conv_dlds / conv_halo / conv_dual / conv_block / conv_pair / conv_stem_pool, every tile shape)" % n_conv,
+        "roofline": {"kernel": "conv kernels (all %d conv launches of a step: conv_dlds / conv_halo / conv_deep / conv_dual / conv_block / conv_block64 / conv_pair / conv_stem_pool, every tile shape)" % n_conv,
                      "bound": "mfma", "achieved": conv_tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": conv_tops / INT8_MFMA_PEAK_TOPS, "traffic": traffic, "traffic_stale": traffic_stale,
                      "peak_measured": peak_tops, "frac_of_peak_measured": conv_tops / peak_tops,
