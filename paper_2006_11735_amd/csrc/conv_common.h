@@ -444,7 +444,9 @@ __device__ __forceinline__ void epilogue_px16(const ConvArgs &a, const v16i &acc
 // The same arithmetic as epilogue_px16 for a layer that stores unsigned bytes and whose skip operand, if any, is
 // the unsigned 8-bit kind joined before requantisation (RES 0 or 1, RQ 1, 2 or 3): the sixteen bytes are returned,
 // for callers that keep the result on chip as well.
-template <int RES>
+// RQ: 0 the requantisation form is chosen at run time (wave-uniform branch); 1, 2, 3 that form of requant16, for
+// callers that need the epilogue to be straight-line code.
+template <int RES, int RQ = 0>
 __device__ __forceinline__ v4i epilogue_bytes16(const ConvArgs &a, const v16i &acc, const v4i &res8)
 {
     int t[16];
@@ -459,7 +461,30 @@ __device__ __forceinline__ v4i epilogue_bytes16(const ConvArgs &a, const v16i &a
             t[r] = __builtin_elementwise_add_sat(t[r], (int)((__umul24(b8, (uint32_t)a.res_mul) + (uint32_t)half) >> a.res_shift));
         }
     }
-    return requant16_any(a, t);
+    if constexpr (RQ == 0) return requant16_any(a, t);
+    else return requant16<RQ>(a, t);
+}
+// Outputs R0 .. R0 + N - 1 of epilogue_bytes16<RES, 3> (the 32-bit requantisation form, a.rq24): their bytes go into
+// the words w[R0 / 4 ..], which the caller collects over the sixteen outputs.  For callers that deal the epilogue out
+// in slices between matrix instructions.  R0 and N are multiples of... any; a word is started by its output 4 q.
+template <int RES, int R0, int N>
+__device__ __forceinline__ void epilogue_rq24_slice(const ConvArgs &a, const v16i &acc, const v4i &res8, int (&w)[4])
+{
+    const int wd[4] = {res8.x, res8.y, res8.z, res8.w};
+    const int half = (1 << a.res_shift) >> 1;
+    const int sh_v = a.shift;
+#pragma unroll
+    for (int r = R0; r < R0 + N; ++r) {
+        int t = acc[r];
+        if (RES == 1) {
+            const uint32_t b8 = ((uint32_t)wd[r >> 2] >> ((r & 3) * 8)) & 0xffu;
+            t = __builtin_elementwise_add_sat(t, (int)((__umul24(b8, (uint32_t)a.res_mul) + (uint32_t)half) >> a.res_shift));
+        }
+        const uint32_t tc = (uint32_t)med3_v0s(t, a.t_hi);
+        const uint32_t x = __umul24(tc, (uint32_t)a.mul) + (uint32_t)a.rnd;
+        if ((r & 3) == 0) w[r >> 2] = (int)(x >> a.shift);
+        else shift_into_byte(w[r >> 2], x, sh_v, r & 3);
+    }
 }
 // Between the last v_mfma of an accumulation and the first instruction that reads the accumulator.  The compiler's
 // hazard recogniser does not always keep the two apart (seen in a kernel whose epilogue starts two instructions after

@@ -23,6 +23,8 @@
 // of the other convolution kernels: y and z are the two separate layers' results, bit for bit.
 #include "conv_common.h"
 
+#include <type_traits>
+
 namespace icnn {
 
 constexpr int kPairPix = 64;
@@ -53,8 +55,10 @@ struct PairArgs {
     unsigned res_bytes, y_bytes;
 };
 
-template <int KF, int MG2>           // K3 / 32 (fragments of the first layer's K), MID2 / 32 (chunks of the second's outputs)
-__global__ __launch_bounds__(512, 2) void conv_pair_kernel(const ConvArgs a3, const ConvArgs a1, const PairArgs g)
+// K3 / 32 (fragments of the first layer's K), MID2 / 32 (chunks of the second's outputs); PIPE: the first layer's
+// requantisation has the 32-bit form (a3.rq24) and its epilogue is dealt out between the matrix instructions
+template <int KF, int MG2, bool PIPE>
+__global__ __launch_bounds__(512, KF == 8 ? 1 : 2) void conv_pair_kernel(const ConvArgs a3, const ConvArgs a1, const PairArgs g)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr unsigned OOB = 0x80000000u;
@@ -122,39 +126,70 @@ __global__ __launch_bounds__(512, 2) void conv_pair_kernel(const ConvArgs a3, co
     for (int j = 0; j < 2; ++j) r_off[j] = okp[j] ? (unsigned)p[j] * (unsigned)a3.res_cs + half * 16 : OOB;
     const int cpw = C >> 8;                           // 32-channel chunks per wave
     const int chunk0 = wave * cpw, chunk_last = chunk0 + cpw - 1;
-    auto load_a3 = [&](v4i (&A)[KF], v4i (&r)[2], int chunk) {
-        chunk = chunk < chunk_last ? chunk : chunk_last;          // past the wave's last chunk: fetched again, never used
-        const v4i *src = (const v4i *)(a3.wp + (size_t)chunk * (KF * 1024)) + lane;
+    auto clamp_chunk = [&](int chunk) { return chunk < chunk_last ? chunk : chunk_last; };   // past the wave's last chunk: fetched again, never used
+    auto load_w3 = [&](v4i (&A)[KF], int chunk) __attribute__((always_inline)) {
+        const v4i *src = (const v4i *)(a3.wp + (size_t)clamp_chunk(chunk) * (KF * 1024)) + lane;
 #pragma unroll
         for (int f = 0; f < KF; ++f) A[f] = src[f * 64];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) r[j] = __builtin_amdgcn_raw_buffer_load_b128(rs_r, r_off[j], chunk * 32, 0);
         __builtin_amdgcn_sched_barrier(0);            // issued here, not wherever the scheduler finds their first use
     };
-    auto do_chunk = [&](const v4i (&A)[KF], const v4i (&r)[2], int chunk) {
-        const int co0 = chunk * 32 + half * 16;
-        v16i acc[2];
-        acc[0] = acc[1] = bias16(btab + co0);
+    auto load_r3 = [&](v4i (&r)[2], int chunk) __attribute__((always_inline)) {
 #pragma unroll
-        for (int f = 0; f < KF; ++f)
+        for (int j = 0; j < 2; ++j) r[j] = __builtin_amdgcn_raw_buffer_load_b128(rs_r, r_off[j], clamp_chunk(chunk) * 32, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // The products of one 32 x 32 tile (chunk, pixel group J) ...
+    auto mul_tile = [&](auto j_tag, const v4i (&A)[KF], int chunk, v16i &acc) __attribute__((always_inline)) {
+        constexpr int J = decltype(j_tag)::value;
+        acc = bias16(btab + chunk * 32 + half * 16);
 #pragma unroll
-            for (int j = 0; j < 2; ++j) acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[f], bt[j][f], acc[j], 0, 0, 0);
-        mfma_drain(acc);
-        PAIR_TR(3);
-        static_for<2>([&](auto jc) {
-            constexpr int j = decltype(jc)::value;
-            const v4i w = has_res ? epilogue_bytes16<1>(a3, acc[j], r[j]) : epilogue_bytes16<0>(a3, acc[j], r[j]);
-            *(v4i *)(ybuf + (32 * j + col) * pitch + co0) = w;
-        });
-        PAIR_TR(4);
+        for (int f = 0; f < KF; ++f) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[f], bt[J][f], acc, 0, 0, 0);
+    };
+    // ... and its epilogue: sixteen requantised bytes into the pixel's row of y in LDS.  RQ as in epilogue_bytes16.
+    auto fin_tile = [&](auto j_tag, auto rq_tag, const v16i &acc, const v4i &r, int chunk) __attribute__((always_inline)) {
+        constexpr int J = decltype(j_tag)::value, RQ = decltype(rq_tag)::value;
+        const v4i w = has_res ? epilogue_bytes16<1, RQ>(a3, acc, r) : epilogue_bytes16<0, RQ>(a3, acc, r);
+        *(v4i *)(ybuf + (32 * J + col) * pitch + chunk * 32 + half * 16) = w;
+    };
+    // One step of the software pipeline: a tile's matrix instructions and the previous tile's epilogue are independent.
+    // With the 32-bit requantisation form (RQ = 3, straight-line code) the epilogue is dealt out in slices, one after
+    // every matrix instruction and pinned there, so that the vector ALUs finish one tile while the matrix core
+    // multiplies the next instead of the two waiting for each other (a slice is 16 / KF outputs = about the vector
+    // work that fits beside one matrix instruction).  With the form chosen at run time (RQ = 0) the two simply follow
+    // each other.
+    // JN: pixel group of the new tile (the old one is the other group: of the same chunk for JN = 1, of the chunk
+    // before for JN = 0).
+    auto step = [&](auto jn_tag, auto rq_tag, const v4i (&A)[KF], int chunk, v16i &acc_new, v16i &acc_old, const v4i &r_old) __attribute__((always_inline)) {
+        constexpr int JN = decltype(jn_tag)::value, RQ = decltype(rq_tag)::value;
+        const int chunk_old = JN ? chunk : chunk - 1;
+        mfma_drain(acc_old);
+        if constexpr (RQ == 3) {
+            int w[4];
+            acc_new = bias16(btab + chunk * 32 + half * 16);
+            __builtin_amdgcn_sched_barrier(0);
+            static_for<KF>([&](auto f_tag) {
+                constexpr int f = decltype(f_tag)::value;
+                acc_new = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[f], bt[JN][f], acc_new, 0, 0, 0);
+                epilogue_rq24_slice<1, f * (16 / KF), 16 / KF>(a3, acc_old, r_old, w);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            *(v4i *)(ybuf + (32 * (JN ^ 1) + col) * pitch + chunk_old * 32 + half * 16) = v4i{w[0], w[1], w[2], w[3]};
+        } else {
+            // kept apart: left to the scheduler, the epilogue's byte extractions move up among the matrix instructions
+            // and the registers run out
+            fin_tile(std::integral_constant<int, JN ^ 1>{}, rq_tag, acc_old, r_old, chunk_old);
+            __builtin_amdgcn_sched_barrier(0);
+            mul_tile(jn_tag, A, chunk, acc_new);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
     {
-        // A chunk's weights and skip operands travel while the chunk before it is multiplied and finished.  The loop
-        // takes two chunks per round, both unconditionally (a conditional use would let the compiler move the fetch
-        // down to it); an odd chunk count starts with a single chunk.
+        // Weights travel two chunks ahead of their products, skip operands from the end of one step to the epilogue two
+        // steps later; every fetch is unconditional (a conditional use would let the compiler move the fetch down to it).
         v4i A0[KF], A1[KF], r0[2], r1[2];
-        int i = 0;
-        load_a3(A0, r0, chunk0);
+        v16i accx, accy;                              // tiles of pixel group 0 / 1
+        load_w3(A0, chunk0);
+        load_r3(r0, chunk0);
         PAIR_TR(9);
         PAIR_TW(1);
 #pragma unroll
@@ -177,21 +212,42 @@ __global__ __launch_bounds__(512, 2) void conv_pair_kernel(const ConvArgs a3, co
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int f = 0; f < KF; ++f) bt[j][f] = *(const v4i *)(tbuf + (32 * j + col) * TPITCH + f * 32 + half * 16);
-        if (cpw & 1) {
-            load_a3(A1, r1, chunk0 + 1);
-            do_chunk(A0, r0, chunk0);
-#pragma unroll
-            for (int f = 0; f < KF; ++f) A0[f] = A1[f];
-            r0[0] = r1[0];
-            r0[1] = r1[1];
-            i = 1;
-        }
-        for (; i < cpw; i += 2) {
-            load_a3(A1, r1, chunk0 + i + 1);
-            do_chunk(A0, r0, chunk0 + i);
-            load_a3(A0, r0, chunk0 + i + 2);
-            do_chunk(A1, r1, chunk0 + i + 1);
-        }
+        load_w3(A1, chunk0 + 1);
+        load_r3(r1, chunk0 + 1);
+        using I0 = std::integral_constant<int, 0>;
+        using I1 = std::integral_constant<int, 1>;
+        using I3 = std::integral_constant<int, 3>;
+        mul_tile(I0{}, A0, chunk0, accx);             // the first tile: nothing to finish yet
+        auto rest = [&](auto rq_tag) __attribute__((always_inline)) {
+            // chunk c (weights A_cur, skip operands r_cur): its second tile while its first is finished, then the next
+            // chunk's first tile (weights A_nxt) while its second is finished; r_cur is free after that and takes the
+            // operands of chunk c + 2, A_cur those weights before
+            auto chunk_steps = [&](const v4i (&A_cur)[KF], v4i (&A_cur_w)[KF], const v4i (&A_nxt)[KF], v4i (&r_cur)[2], int c) __attribute__((always_inline)) {
+                step(I1{}, rq_tag, A_cur, c, accy, accx, r_cur[0]);
+                load_w3(A_cur_w, c + 2);
+                step(I0{}, rq_tag, A_nxt, c + 1, accx, accy, r_cur[1]);
+                load_r3(r_cur, c + 2);
+            };
+            int c = 0;                                // relative to chunk0
+            for (; c + 2 < cpw; c += 2) {
+                chunk_steps(A0, A0, A1, r0, chunk0 + c);
+                chunk_steps(A1, A1, A0, r1, chunk0 + c + 1);
+            }
+            if (c + 1 < cpw) {                        // two chunks left: c (A0, r0) and c + 1 (A1, r1)
+                chunk_steps(A0, A0, A1, r0, chunk0 + c);
+                step(I1{}, rq_tag, A1, chunk0 + c + 1, accy, accx, r1[0]);
+                mfma_drain(accy);
+                fin_tile(I1{}, rq_tag, accy, r1[1], chunk0 + c + 1);
+            } else {                                  // one chunk left: c (A0, r0)
+                step(I1{}, rq_tag, A0, chunk0 + c, accy, accx, r0[0]);
+                mfma_drain(accy);
+                fin_tile(I1{}, rq_tag, accy, r0[1], chunk0 + c);
+            }
+        };
+        // the pipelined form always runs the skip operand's arithmetic: without one the empty descriptor delivers zero
+        // bytes and the launcher has set res_mul = 0, res_shift = 0, so that the term is zero
+        if constexpr (PIPE) rest(I3{});
+        else rest(I0{});
     }
 
     // ---------------- phase 2
@@ -301,7 +357,19 @@ hipError_t launch_conv_pair(const ConvArgs &a3, const ConvArgs &a1, long long pi
         hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, a3, a1, g);
         return hipGetLastError();
     };
-    return kf == 2 ? go(conv_pair_kernel<2, 2>) : kf == 4 ? go(conv_pair_kernel<4, 4>) : go(conv_pair_kernel<8, 8>);
+    ConvArgs b3 = a3;
+    if (!b3.res_mode) b3.res_mul = b3.res_shift = 0;      // the pipelined epilogue always runs the skip operand's arithmetic
+    auto go3 = [&](auto kernel) -> hipError_t {
+        if (lds_bytes > 64 * 1024) {
+            const hipError_t e = allow_large_lds((const void *)kernel);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, b3, a1, g);
+        return hipGetLastError();
+    };
+    if (a3.rq24 && (!a3.res_mode || a3.res_fast))
+        return kf == 2 ? go3(conv_pair_kernel<2, 2, true>) : kf == 4 ? go3(conv_pair_kernel<4, 4, true>) : go3(conv_pair_kernel<8, 8, true>);
+    return kf == 2 ? go(conv_pair_kernel<2, 2, false>) : kf == 4 ? go(conv_pair_kernel<4, 4, false>) : go(conv_pair_kernel<8, 8, false>);
 }
 
 #ifdef ICNN_PAIR_TRACE
