@@ -463,12 +463,14 @@ static int halo_choice(const ConvArgs &a, int *rows)
     const int npq = pq * kHaloInst;       // patch buffers are whole instalments
     const size_t lds = (size_t)kHaloStages * bm * kStepK + 2 * (size_t)npq * 4096;
     if (pq > (choice == 1 ? 2 : kHaloMaxPq) || lds > 160 * 1024) return 0;
-    // One workgroup per compute unit: a tile's epilogue is not hidden behind another workgroup's K loop.  Measured
-    // inside whole networks: the kernel wins where a workgroup has one tile and the K loop has 18 steps or more;
-    // with several tiles per workgroup it only ties with the tap-by-tap kernel (two workgroups per unit), and
-    // 9-step tiles lose.  The halo_always override lifts both limits.
+    // One workgroup per compute unit: a tile's epilogue is not hidden behind another workgroup's K loop.  Measured:
+    // the kernel wins clearly where a workgroup has one tile and the K loop has 18 steps or more (12.3 against 17 us
+    // at 64 x 14 x 14 x 256 -> 256); with several tiles per workgroup it is 3-10 % ahead of the tap-by-tap kernel
+    // (two workgroups per unit; 22.8 against 25.5 us at 128 x 14 x 14 x 256 -> 256, 29.2 against 30.6 at
+    // 128 x 28 x 28 x 128 -> 128 stand-alone, but the ResNet-18 shape's 18-step layers on 392 tiles came out 2 % slower
+    // inside the network), and 9-step tiles lose.  The halo_always override lifts both limits.
     const long long tiles = (long long)((a.Cout + bm - 1) / bm) * ((a.M + bp - 1) / bp);
-    if ((tiles > 256 || a.ksteps < 18) && !g_tuning.halo_always) return 0;
+    if (a.ksteps < (tiles > 256 ? 36 : 18) && !g_tuning.halo_always) return 0;
     if (a.pc && tiles > 256) return 0;       // per-channel instantiations: one tile per workgroup
     return choice;
 }
