@@ -128,6 +128,7 @@ const char *icnn_last_error(void);
  *   "halo_tile"   0 library's choice; 1 = 128 x 128, 2 = 64 x 256 tiles of the patch-resident 3x3 kernel
  *   "halo_always" 1 lets the patch-resident kernel take layers with several tiles per workgroup
  *   "deep_always" 1 lets the 3x3 kernel whose waves split the K axis take every layer whose shape it accepts
+ *   "deep_plain_walk" 1 gives that kernel the tile order of the other kernels (pixel tiles, not channel tiles, per XCD)
  *   "ksplit"      0 library's choice; 1 never split the K axis over workgroups; 2..8 that split where it divides the K steps
  *   "reset"       (value ignored) back to the library's choices
  * Unknown names and values outside these ranges return ICNN_E_PARAM and change nothing. */
