@@ -159,19 +159,10 @@ __global__ __launch_bounds__(256, 3) void conv_stem_pool_kernel(const ConvArgs a
         if (more) fetch_patch(v + (int)gridDim.x);           // travels during the multiplication
 
         // ---- convolution: one K block per kernel row
-        v16i acc[CG][TPX];
+        // the biases are the first kernel row's C operands (no copies into the accumulators)
+        v16i acc[CG][TPX], bias[CG];
 #pragma unroll
-        for (int c = 0; c < CG; ++c) {
-            const v4i *bp = (const v4i *)(btab + c * 32 + half * 16);
-            v16i b;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const v4i v = bp[q];
-                b[4 * q] = v.x; b[4 * q + 1] = v.y; b[4 * q + 2] = v.z; b[4 * q + 3] = v.w;
-            }
-#pragma unroll
-            for (int j = 0; j < TPX; ++j) acc[c][j] = b;
-        }
+        for (int c = 0; c < CG; ++c) bias[c] = bias16(btab + c * 32 + half * 16);
         const uint32_t *P = patch + buf * patch_words;
         // fragments of kernel row kh: weights of every chunk, and per pixel group eight pixels from column 2 cx on
         // (this half of the wave the first or the second four)
@@ -197,7 +188,14 @@ __global__ __launch_bounds__(256, 3) void conv_stem_pool_kernel(const ConvArgs a
         };
         // two kernel rows per round: each row's fragments arrive during the previous row's MFMAs, in alternating registers
         fetch_frags(af, bf, 0);
-        for (int kh = 0; kh < a.KH; kh += 2) {
+        if (1 < a.KH) fetch_frags(afn, bfn, 1);
+#pragma unroll
+        for (int c = 0; c < CG; ++c)
+#pragma unroll
+            for (int j = 0; j < TPX; ++j) acc[c][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[c], bf[j], bias[c], 0, 0, 0);
+        if (2 < a.KH) fetch_frags(af, bf, 2);
+        if (1 < a.KH) multiply(afn, bfn);
+        for (int kh = 2; kh < a.KH; kh += 2) {
             if (kh + 1 < a.KH) fetch_frags(afn, bfn, kh + 1);
             multiply(af, bf);
             if (kh + 2 < a.KH) fetch_frags(af, bf, kh + 2);
@@ -230,7 +228,9 @@ __global__ __launch_bounds__(256, 3) void conv_stem_pool_kernel(const ConvArgs a
             const int ty = pp / kStemPW, tx = pp - ty * kStemPW;
             const int py = py0 + ty, px = px0 + tx;
             if (py >= g.Hp || px >= g.Wp) continue;
-            // bytewise maximum in two halves: even and odd bytes as 16-bit lanes, split once per loaded word
+            // bytewise maximum in two halves, as 16-bit lanes: the even bytes masked out of every loaded word; the odd
+            // bytes need no mask, because a lane's maximum is decided by its high byte (the low byte only breaks ties)
+            // and only the high byte of the result is kept
             typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
             u16x2 me[4] = {}, mo[4] = {};
 #pragma unroll
@@ -243,12 +243,12 @@ __global__ __launch_bounds__(256, 3) void conv_stem_pool_kernel(const ConvArgs a
                     for (int d = 0; d < 4; ++d) {
                         const uint32_t x = (uint32_t)w[d];
                         me[d] = __builtin_elementwise_max(me[d], __builtin_bit_cast(u16x2, x & 0x00ff00ffu));
-                        mo[d] = __builtin_elementwise_max(mo[d], __builtin_bit_cast(u16x2, (x >> 8) & 0x00ff00ffu));
+                        mo[d] = __builtin_elementwise_max(mo[d], __builtin_bit_cast(u16x2, x));
                     }
                 }
             v4i o;
 #pragma unroll
-            for (int d = 0; d < 4; ++d) o[d] = (int)(__builtin_bit_cast(uint32_t, me[d]) | (__builtin_bit_cast(uint32_t, mo[d]) << 8));
+            for (int d = 0; d < 4; ++d) o[d] = (int)(__builtin_bit_cast(uint32_t, me[d]) | (__builtin_bit_cast(uint32_t, mo[d]) & 0xff00ff00u));
             *(v4i *)((uint8_t *)a.out + ((size_t)(n * g.Hp + py) * g.Wp + px) * a.out_cs + a.out_co + cgp * 16) = o;
         }
         __syncthreads();
