@@ -799,6 +799,7 @@ size_t conv_split_bytes(const ConvArgs &a, bool direct_ok)
     if (direct_ok && conv_narrow_applies(a) && !g_tuning.no_narrow) return 0;
     if (direct_ok && conv_fc_applies(a) && !g_tuning.no_fc) return 0;
     if (!takes_direct(a, direct_ok)) return 0;
+    if (!g_tuning.no_plane && g_tuning.tile < 0 && conv_plane_applies(a)) return 0;
     if (!g_tuning.no_deep && g_tuning.tile < 0 && conv_deep_applies(a)) return 0;
     if (!g_tuning.no_halo && g_tuning.tile < 0 && conv_halo_applies(a)) return 0;
     int t, s;
@@ -816,6 +817,8 @@ hipError_t launch_conv(const ConvArgs &a, bool vec_in, bool direct_ok, hipStream
         return launch_conv_narrow(a, st);
     // the classifier: a few pixels, long K
     if (direct_ok && conv_fc_applies(a) && !g_tuning.no_fc) return launch_conv_fc(a, st);
+    // few channels on a large picture: two-dimensional tiles, patch and weights resident in LDS
+    if (direct && !g_tuning.no_plane && g_tuning.tile < 0 && conv_plane_applies(a)) return launch_conv_plane(a, st);
     // 3x3 / stride 1 / padding 1 with cin % 256 == 0 on few pixels: the waves of a workgroup split the K axis
     if (direct && !g_tuning.no_deep && g_tuning.tile < 0 && conv_deep_applies(a)) return launch_conv_deep(a, st);
     // 3x3 / stride 1 / padding 1 with cin % 64 == 0: the nine taps read one LDS copy of the input

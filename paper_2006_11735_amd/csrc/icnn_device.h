@@ -166,6 +166,8 @@ struct Tuning {
     int halo_tile = 0;     // patch-resident kernel: 1 = 128 x 128, 2 = 64 x 256
     int halo_always = 0;   // patch-resident kernel also with several tiles per workgroup and short K loops
     int no_stream = 0;     // single-channel 3x3 layers: lane-group kernel instead of the streaming one
+    int no_plane = 0;      // keep few-channel layers on large pictures off the kernel with two-dimensional tiles
+    int plane_always = 0;  // that kernel for every layer whose shape it accepts
     int no_deep = 0;       // keep deep 3x3 layers on few pixels off the kernel whose waves split the K axis
     int deep_plain_walk = 0;   // that kernel with the tile order of the other kernels (measurement)
     int deep_always = 0;   // that kernel for every layer whose shape it accepts
@@ -185,6 +187,8 @@ bool conv_fc_applies(const ConvArgs &a);
 hipError_t launch_conv_fc(const ConvArgs &a, hipStream_t st);
 bool conv_halo_applies(const ConvArgs &a);
 hipError_t launch_conv_halo(const ConvArgs &a, hipStream_t st);
+bool conv_plane_applies(const ConvArgs &a);
+hipError_t launch_conv_plane(const ConvArgs &a, hipStream_t st);
 bool conv_deep_applies(const ConvArgs &a);
 hipError_t launch_conv_deep(const ConvArgs &a, hipStream_t st);
 hipError_t launch_conv_stem_pool(const ConvArgs &a, int hp, int wp, hipStream_t st);

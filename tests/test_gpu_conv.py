@@ -544,6 +544,43 @@ def test_3x3_kernel_whose_waves_split_the_k_axis(shape):
         B.icnn_set_tuning("reset")
 
 
+# ---- few channels on a large picture (the restoration networks' layers): two-dimensional tiles of 16 x 32 pixels, the
+# patch and the layer's weights resident in LDS.  Shapes: every (kernel, cin, chunk count) instantiation; pictures of
+# several tiles in both directions, so that patches cross the picture's border on every side and neighbour each other;
+# channel tails (16, 40, 48 outputs); two images.
+PLANE_SHAPES = [(1, 32, 96, 64, 32, 5, 1, 2), (1, 48, 64, 64, 16, 3, 1, 1), (2, 32, 64, 64, 64, 3, 1, 1), (1, 32, 64, 48, 16, 3, 1, 1),
+                (1, 32, 64, 48, 40, 3, 1, 1), (3, 16, 32, 64, 32, 3, 1, 1), (1, 80, 160, 64, 16, 3, 1, 1), (1, 64, 96, 64, 32, 5, 1, 2)]
+
+
+@pytest.mark.parametrize("shape", PLANE_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_two_dimensional_tile_kernel_for_few_channels(shape):
+    from paper_2006_11735_amd import binding as B
+    B.icnn_set_tuning("plane_always", 1)
+    try:
+        n, h, w, cin, cout, k, stride, pad = shape
+        x, wt, b = make(41, n, h, w, cin, cout, k)
+        got, want = both(x, wt, b, stride=stride, pad=pad, out_mode="raw_s32")
+        assert (got == want).all()
+        sigma = 37.0 * 74 * (k * k * cin) ** 0.5
+        mul = max(1, int(round(127 / (3.0 * sigma) * (1 << 25))))
+        got, want = both(x, wt, b, stride=stride, pad=pad, mul=mul, shift=25)
+        assert (got == want).all() and want.max() == 127 and want.min() == 0
+        # written at a channel offset of a wider buffer (a branch of a concatenation), canary bytes around it
+        canvas = rnd(10).integers(0, 256, size=(n, h, w, cout + 48), dtype=np.uint8)
+        got, want = both(x, wt, b, stride=stride, pad=pad, mul=mul, shift=25, out=canvas, out_c_offset=32)
+        assert (got == want).all()
+        # a skip operand joined before requantisation, and one added after it (the regression output's form)
+        r = rnd(5).integers(0, 128, size=(n, h, w, cout), dtype=np.uint8)
+        got, want = both(x, wt, b, stride=stride, pad=pad, mul=mul, shift=25, res=r, res_mode="pre", res_mul=int(3.0 * sigma / 127), res_shift=0)
+        assert (got == want).all()
+        # a channel slice of a wider input buffer
+        xw = rnd(6).integers(0, 128, size=(n, h, w, cin + 16), dtype=np.uint8)
+        got, want = both(xw, wt, b, stride=stride, pad=pad, mul=mul, shift=25, cin=cin)
+        assert (got == want).all()
+    finally:
+        B.icnn_set_tuning("reset")
+
+
 def check_3x3_layer(shape):
     n, h, w, cin, cout, k, stride, pad = shape
     x, wt, b = make(31, n, h, w, cin, cout, k)
