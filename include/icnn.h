@@ -124,7 +124,7 @@ const char *icnn_last_error(void);
  * synchronised: set it while no other thread is inside the library.  `name` (host string) and the values it takes:
  *   "tile"        -1 library's choice; 0..4 force that tile shape of the tap-by-tap convolution kernel
  *   "stages"      0 library's choice; 2..6 LDS ring depth of that kernel
- *   "no_narrow", "no_fc", "no_halo", "no_stream", "no_block64", "no_deep", "no_plane"   1 keeps layers off the respective special kernel
+ *   "no_narrow", "no_fc", "no_halo", "no_stream", "no_block64", "no_deep", "no_plane", "no_pic"   1 keeps layers off the respective special kernel
  *   "halo_tile"   0 library's choice; 1 = 128 x 128, 2 = 64 x 256 tiles of the patch-resident 3x3 kernel
  *   "halo_always" 1 lets the patch-resident kernel take layers with several tiles per workgroup
  *   "plane_always" 1 lets the kernel with two-dimensional tiles (few channels, large pictures) take every layer it accepts

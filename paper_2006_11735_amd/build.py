@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libicnn_mi355.so")
-SOURCES = ["api.hip", "conv_igemm.hip", "conv_dual.hip", "conv_halo.hip", "conv_deep.hip", "conv_plane.hip", "conv_block.hip", "conv_block64.hip", "conv_pair.hip", "conv_stem.hip", "conv_fc.hip", "conv_narrow.hip", "eltwise.hip", "peaks.hip"]
+SOURCES = ["api.hip", "conv_igemm.hip", "conv_dual.hip", "conv_halo.hip", "conv_deep.hip", "conv_plane.hip", "conv_block.hip", "conv_block64.hip", "conv_pair.hip", "conv_stem.hip", "conv_pic.hip", "conv_fc.hip", "conv_narrow.hip", "eltwise.hip", "peaks.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

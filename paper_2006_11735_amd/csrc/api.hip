@@ -141,7 +141,7 @@ int icnn_set_tuning(const char *name, int32_t value)
         {"no_halo", &Tuning::no_halo, 0, 1},     {"halo_tile", &Tuning::halo_tile, 0, 2},
         {"halo_always", &Tuning::halo_always, 0, 1}, {"no_stream", &Tuning::no_stream, 0, 1},
         {"ksplit", &Tuning::ksplit, 0, 8}, {"no_block64", &Tuning::no_block64, 0, 1},
-        {"no_plane", &Tuning::no_plane, 0, 1}, {"plane_always", &Tuning::plane_always, 0, 1},
+        {"no_plane", &Tuning::no_plane, 0, 1}, {"no_pic", &Tuning::no_pic, 0, 1}, {"plane_always", &Tuning::plane_always, 0, 1},
         {"no_deep", &Tuning::no_deep, 0, 1}, {"deep_always", &Tuning::deep_always, 0, 1}, {"deep_plain_walk", &Tuning::deep_plain_walk, 0, 1},
     };
     if (!strcmp(name, "reset")) {
@@ -339,6 +339,12 @@ static int conv_layer(const icnn_conv_desc *d, const void *x, const void *w_pack
         a.pc_fast_ok = d->out_mode != ICNN_OUT_RAW_S32 && a.epi_vec &&
                        (d->res_mode == ICNN_RES_NONE || (d->res_mode == ICNN_RES_PRE && d->res_dtype == ICNN_U8));
     }
+    if (g.rp == 32 && !pc && !g_tuning.no_pic && d->stride_h == 1 && d->stride_w == 1 && d->kh <= 8 && (d->cout == 32 || d->cout == 64) &&
+        (d->out_mode == ICNN_OUT_BRELU_U8 || d->out_mode == ICNN_OUT_CLAMP_U8) && d->res_mode == ICNN_RES_NONE &&
+        d->in_signed != ICNN_IN_U8_FULL && d->in_signed != ICNN_IN_S8 && a.vec_out && a.vec_bias && a.x_bytes >= 4 &&
+        a.x_bytes <= 0x7fffffffu && g.M <= 0x7fffffffLL)
+        // a picture's first layer at stride 1: straight off the picture, no padded copy
+        return launched(launch_conv_pic(a, (hipStream_t)stream), what);
     if (g.rp) {
         // small cin: pad and re-normalise x into the workspace, then run the layer as a kh x 1
         // convolution with "rp channels" over that copy (see pad_small_cin_kernel)

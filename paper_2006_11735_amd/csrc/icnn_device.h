@@ -168,6 +168,7 @@ struct Tuning {
     int no_stream = 0;     // single-channel 3x3 layers: lane-group kernel instead of the streaming one
     int no_plane = 0;      // keep few-channel layers on large pictures off the kernel with two-dimensional tiles
     int plane_always = 0;  // that kernel for every layer whose shape it accepts
+    int no_pic = 0;        // keep stride-1 first layers (cin <= 4) on the padded copy + tile kernel
     int no_deep = 0;       // keep deep 3x3 layers on few pixels off the kernel whose waves split the K axis
     int deep_plain_walk = 0;   // that kernel with the tile order of the other kernels (measurement)
     int deep_always = 0;   // that kernel for every layer whose shape it accepts
@@ -191,6 +192,7 @@ bool conv_plane_applies(const ConvArgs &a);
 hipError_t launch_conv_plane(const ConvArgs &a, hipStream_t st);
 bool conv_deep_applies(const ConvArgs &a);
 hipError_t launch_conv_deep(const ConvArgs &a, hipStream_t st);
+hipError_t launch_conv_pic(const ConvArgs &a, hipStream_t st);
 hipError_t launch_conv_stem_pool(const ConvArgs &a, int hp, int wp, hipStream_t st);
 bool conv_block_tile(int H, int W, BlockArgs &g);
 size_t conv_block_lds_bytes(int mid, int c);

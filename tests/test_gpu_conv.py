@@ -581,6 +581,46 @@ def test_two_dimensional_tile_kernel_for_few_channels(shape):
         B.icnn_set_tuning("reset")
 
 
+# ---- a picture's first layer at stride 1 (cin <= 4, kernel 5 to 8 wide, 32 or 64 channels, 8-bit output) runs straight
+# off the picture, without the padded copy.  Shapes: one to four channels, kernels 5 to 8, "same" and "valid" borders,
+# pictures smaller than a tile, of exactly whole tiles and with ragged tiles on both sides, several images.
+PICTURE_SHAPES = [(1, 40, 70, 1, 64, 5, 2), (2, 17, 33, 3, 32, 7, 3), (1, 24, 64, 4, 64, 8, 0), (1, 9, 31, 2, 64, 6, 2),
+                  (3, 8, 32, 1, 32, 5, 2), (1, 5, 5, 1, 64, 5, 2), (2, 64, 96, 1, 64, 5, 2)]
+
+
+@pytest.mark.parametrize("shape", PICTURE_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_first_layer_straight_off_the_picture(shape):
+    n, h, w, cin, cout, k, pad = shape
+    x, wt, b = make(51, n, h, w, cin, cout, k, raw=True)
+    sigma = 74.0 * 74 * (k * k * cin) ** 0.5
+    mul = max(1, int(round(127 / (3.0 * sigma) * (1 << 25))))
+    # a raw picture, re-normalised on the way in
+    got, want = both(x, wt, b, pad=pad, in_sub128=True, mul=mul, shift=25)
+    assert (got == want).all()
+    assert want.min() == 0 and (want.max() == 127 or n * h * w < 100)      # both clamps at work
+    # activations below 128, taken as they are
+    xa = x >> 1
+    got, want = both(xa, wt, b, pad=pad, mul=mul, shift=25)
+    assert (got == want).all()
+    # written at a channel offset of a wider buffer, canary bytes around it
+    ho, wo = want.shape[1:3]
+    canvas = rnd(11).integers(0, 256, size=(n, ho, wo, cout + 48), dtype=np.uint8)
+    got, want = both(x, wt, b, pad=pad, in_sub128=True, mul=mul, shift=25, out=canvas, out_c_offset=16)
+    assert (got == want).all()
+    # the picture as a channel slice of a wider buffer (pixels further apart than their channels)
+    xw = rnd(12).integers(0, 256, size=(n, h, w, cin + 3), dtype=np.uint8)
+    got, want = both(xw, wt, b, pad=pad, in_sub128=True, mul=mul, shift=25, cin=cin)
+    assert (got == want).all()
+    # the library's other path for the same layer gives the same bytes
+    from paper_2006_11735_amd import binding as B
+    B.icnn_set_tuning("no_pic", 1)
+    try:
+        got2, _ = both(xw, wt, b, pad=pad, in_sub128=True, mul=mul, shift=25, cin=cin)
+    finally:
+        B.icnn_set_tuning("reset")
+    assert (got2 == want).all()
+
+
 def check_3x3_layer(shape):
     n, h, w, cin, cout, k, stride, pad = shape
     x, wt, b = make(31, n, h, w, cin, cout, k)
