@@ -39,7 +39,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def layer_work(net, op, images, fused_proj=None, fused_block=None, fused_pool=None, fused_pair=None, fused_projblock=None):
+def layer_work(net, op, images, fused_proj=None, fused_block=None, fused_pool=None, fused_pair=None, fused_projblock=None, fused_twin=None):
     """Algorithmic ops and bytes of one conv launch (true sizes, input counted once).  With a
     projection fused into the launch, its ops, input and weights are added and the int32 skip
     tensor is not counted (it never exists).  With a whole bottleneck block in the launch: the ops of its
@@ -55,6 +55,12 @@ def layer_work(net, op, images, fused_proj=None, fused_block=None, fused_pool=No
         mid = m * o1["cout"]
         x_bytes = images * net["buffers"][o1["src"]]["shape"][1] * net["buffers"][o1["src"]]["shape"][2] * o1["cin"]
         return ops1 + ops2 + ops3, (b1 - mid) + (b2 - 2 * mid) + (b3 - mid - x_bytes), m, k1 + k2 + k3
+    if fused_twin is not None:
+        # two branches of one input in one launch: both layers' ops, weights and outputs; the input once
+        opsa, ba, m, ka = layer_work(net, op, images)
+        opsb, bb, _, kb = layer_work(net, fused_twin, images)
+        _, h, w, _ = net["buffers"][op["src"]]["shape"]
+        return opsa + opsb, ba + bb - images * h * w * op["cin"], m, ka + kb
     if fused_pair is not None:
         # two pointwise layers in one launch: both layers' ops; the first layer's input, skip operand and output, both
         # layers' weights, the second layer's output (the second layer's input is not read back from memory)
@@ -453,7 +459,7 @@ def main():
     rows = []
     for step, ms in zip(g.steps, layer_ms):
         kind, op = step[0], step[1]
-        if kind not in ("conv", "conv_pc", "dual", "dual_pc", "block", "convpool", "pair", "projblock"):
+        if kind not in ("conv", "conv_pc", "dual", "dual_pc", "block", "convpool", "pair", "projblock", "twin"):
             other_ms += ms
             rows.append({"name": op["dst"], "kind": kind, "ms": ms})
             continue
@@ -461,14 +467,15 @@ def main():
                                      g.fused_block.get(op["name"]) if kind == "block" else None,
                                      g.fused_pool.get(op["name"]) if kind == "convpool" else None,
                                      g.fused_pair.get(op["name"]) if kind == "pair" else None,
-                                     g.fused_projblock.get(op["name"]) if kind == "projblock" else None)
+                                     g.fused_projblock.get(op["name"]) if kind == "projblock" else None,
+                                     g.fused_twin.get(op["name"]) if kind == "twin" else None)
         conv_ops += ops
         conv_ms += ms
         conv_bytes += byts
         tops = ops / (ms * 1e-3) / 1e12
         attain = min(INT8_MFMA_PEAK_TOPS, ops / byts * HBM_PEAK_GBS / 1e3)
         rows.append({"name": (op["name"][:-3] + "_block" if kind == "block" else op["name"]) + ("+proj" if kind in ("dual", "dual_pc") else "") +
-                             ("+pool" if kind == "convpool" else "") + ("+next_c1" if kind == "pair" else "") + ("_block+proj" if kind == "projblock" else ""), "kind": "conv", "M": m, "N": op["cout"], "K": k, "ms": ms,
+                             ("+pool" if kind == "convpool" else "") + ("+next_c1" if kind == "pair" else "") + ("+" + g.fused_twin[op["name"]]["name"] if kind == "twin" else "") + ("_block+proj" if kind == "projblock" else ""), "kind": "conv", "M": m, "N": op["cout"] + (g.fused_twin[op["name"]]["cout"] if kind == "twin" else 0), "K": k, "ms": ms,
                      "tops": tops, "pct_mfma_peak": 100 * tops / INT8_MFMA_PEAK_TOPS,
                      "pct_attainable": 100 * tops / attain, "gbs": byts / (ms * 1e-3) / 1e9})
     for r in rows:

@@ -332,6 +332,23 @@ int iconv2d_pair_brelu(const icnn_conv_desc *c3, const void *t, const void *w3_p
                        void *stream);
 
 /*
+ * Two branches of one input as one launch: the layers of different kernel sizes whose outputs are concatenated
+ * (Section 4.1, zero-copy concatenation: each branch is calibrated to the shared bound and writes its channel range
+ * of the common buffer; Section 3.1 for each layer).  Result: exactly that of
+ *     iconv2d_brelu(ca, x, wa_packed, bias_a, NULL, ya, ...);
+ *     iconv2d_brelu(cb, x, wb_packed, bias_b, NULL, yb, ...);
+ * with x read once and, where ya == yb and the two channel ranges are neighbours, whole pixels written.  Every argument
+ * is a device pointer; ya and yb may be the same buffer (the descriptors' out_c_stride / out_c_offset place each
+ * branch), the two channel ranges must not overlap, and neither output may overlap x.  Shapes it takes: stride 1,
+ * "same" padding, ca 5x5 with 64 input channels and cb 3x3, or ca 3x3 with 48 or 64 input channels and cb 1x1; at
+ * most 32 output channels each; no skip operands; inputs ICNN_IN_U8_LE127; h a multiple of 16 and w of 32; x and
+ * in_c_stride 16-byte aligned.  Anything else returns ICNN_E_UNSUPPORTED having launched nothing, and the caller issues
+ * the two layers separately.
+ */
+int iconv2d_twin_brelu(const icnn_conv_desc *ca, const void *x, const void *wa_packed, const int32_t *bias_a, void *ya,
+                       const icnn_conv_desc *cb, const void *wb_packed, const int32_t *bias_b, void *yb, void *stream);
+
+/*
  * Rescaled feature-map addition (ratio synchronisation between feature maps,
  * Sections 3.4.2 and 4.1), as a stand-alone pass over memory:
  *   T   = sat32(a + [b * b_mul / 2^b_shift])

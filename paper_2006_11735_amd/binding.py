@@ -72,6 +72,7 @@ _lib.iconv2d_bottleneck_brelu.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _
 _lib.iconv2d_bottleneck_dual_brelu.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp, C.POINTER(icnn_conv_desc), _vp, _vp,
                                                C.POINTER(icnn_conv_desc), _vp, _vp, C.POINTER(icnn_conv_desc), _vp, _vp, _vp, _vp]
 _lib.iconv2d_pair_brelu.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp, _vp, _vp, C.POINTER(icnn_conv_desc), _vp, _vp, _vp, _vp]
+_lib.iconv2d_twin_brelu.argtypes = [C.POINTER(icnn_conv_desc), _vp, _vp, _vp, _vp, C.POINTER(icnn_conv_desc), _vp, _vp, _vp, _vp]
 _lib.iadd_rescale.argtypes = [C.POINTER(icnn_add_desc), _vp, _vp, _vp, _vp]
 _lib.iconcat.argtypes = [_i32, C.POINTER(_vp), C.POINTER(_i32), C.POINTER(_i32), C.POINTER(_i32),
                          C.POINTER(_i32), _i32, _i64, _vp, _i32, _vp]
@@ -84,7 +85,7 @@ _lib.icnn_peak_copy.argtypes = [_vp, _vp, C.c_size_t, _vp]
 EXPORTS = ["icnn_version", "icnn_last_error", "icnn_set_tuning", "iconv2d_validate", "iconv2d_out_hw",
            "iconv2d_workspace_bytes", "iconv2d_packed_weight_bytes", "iconv2d_prepack_weights",
            "iconv2d_brelu", "iconv2d_brelu_static_ws", "iconv2d_packed_channel_params_bytes", "iconv2d_prepack_channel_params", "iconv2d_brelu_pc",
-           "iconv2d_dual_brelu", "iconv2d_dual_brelu_pc", "iconv2d_bottleneck_brelu", "iconv2d_bottleneck_dual_brelu", "iconv2d_pair_brelu", "iconv2d_maxpool_brelu", "iadd_rescale", "iconcat", "imaxpool2d_u8", "iavgpool_global_u8",
+           "iconv2d_dual_brelu", "iconv2d_dual_brelu_pc", "iconv2d_bottleneck_brelu", "iconv2d_bottleneck_dual_brelu", "iconv2d_pair_brelu", "iconv2d_twin_brelu", "iconv2d_maxpool_brelu", "iadd_rescale", "iconcat", "imaxpool2d_u8", "iavgpool_global_u8",
            "irenormalize_u8", "icnn_peak_mfma_i8", "icnn_peak_copy"]
 
 
@@ -242,6 +243,11 @@ def iconv2d_bottleneck_dual_brelu(c1, x, w1_packed, bias1, c2, w2_packed, bias2,
 def iconv2d_pair_brelu(c3, t, w3_packed, bias3, res, y, c1, w1_packed, bias1, z, stream=None):
     return _check(_lib.iconv2d_pair_brelu(C.byref(c3), _ptr(t), _ptr(w3_packed), _ptr(bias3), _ptr(res), _ptr(y), C.byref(c1),
                                           _ptr(w1_packed), _ptr(bias1), _ptr(z), _stream(stream)))
+
+
+def iconv2d_twin_brelu(ca, x, wa_packed, bias_a, ya, cb, wb_packed, bias_b, yb, stream=None):
+    return _check(_lib.iconv2d_twin_brelu(C.byref(ca), _ptr(x), _ptr(wa_packed), _ptr(bias_a), _ptr(ya), C.byref(cb),
+                                          _ptr(wb_packed), _ptr(bias_b), _ptr(yb), _stream(stream)))
 
 
 def iadd_rescale(desc, a, b, out, stream=None):

@@ -726,6 +726,29 @@ int iconv2d_pair_brelu(const icnn_conv_desc *c3, const void *t, const void *w3_p
     return launched(launch_conv_pair(a3, a1, g3.M, (hipStream_t)stream), "iconv2d_pair_brelu");
 }
 
+int iconv2d_twin_brelu(const icnn_conv_desc *ca, const void *x, const void *wa_packed, const int32_t *bias_a, void *ya,
+                       const icnn_conv_desc *cb, const void *wb_packed, const int32_t *bias_b, void *yb, void *stream)
+{
+    ConvGeom ga, gb;
+    int rc = check_conv(ca, &ga);
+    if (rc) return rc;
+    if ((rc = check_conv(cb, &gb))) return rc;
+    if (cb->n != ca->n || cb->h != ca->h || cb->w != ca->w || cb->cin != ca->cin || cb->in_c_stride != ca->in_c_stride ||
+        cb->in_signed != ca->in_signed || cb->in_sub128 != ca->in_sub128)
+        return fail(ICNN_E_SHAPE, "twin layers read the same input: n, h, w, cin, in_c_stride and the input kind must agree");
+    if (ca->res_mode != ICNN_RES_NONE || cb->res_mode != ICNN_RES_NONE)
+        return fail(ICNN_E_UNSUPPORTED, "twin layers take no skip operands");
+    if (ca->in_signed != ICNN_IN_U8_LE127 || ca->in_sub128) return fail(ICNN_E_UNSUPPORTED, "twin layers take unsigned inputs up to 127 only");
+    if (!aligned16(x)) return fail(ICNN_E_UNSUPPORTED, "twin layers need a 16-byte aligned input");
+    ConvArgs a, b;
+    if ((rc = fill_conv_args(ca, ga, x, wa_packed, bias_a, nullptr, ya, a))) return rc;
+    if ((rc = fill_conv_args(cb, gb, x, wb_packed, bias_b, nullptr, yb, b))) return rc;
+    if (!conv_plane_twin_ok(a, b))
+        return fail(ICNN_E_UNSUPPORTED, "twin layers: a 5x5 layer of 64 channels beside a 3x3, or a 3x3 layer of 48 or 64 channels beside a 1x1, "
+                                        "stride 1, \"same\" padding, at most 32 output channels each, h a multiple of 16 and w of 32");
+    return launched(launch_conv_plane_twin(a, b, (hipStream_t)stream), "iconv2d_twin_brelu");
+}
+
 int iadd_rescale(const icnn_add_desc *d, const void *a, const void *b, void *out, void *stream)
 {
     if (!d) return fail(ICNN_E_NULL, "add descriptor is NULL");

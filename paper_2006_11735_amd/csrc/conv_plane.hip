@@ -45,8 +45,27 @@ struct PlaneArgs {
     FastDiv div_tpi, div_tx;    // / tiles_per_img, / tiles_x
 };
 
-template <int KS, int CIN, int NCH>      // kernel size, input channels (48 or 64), 32-channel chunks of the output (1 or 2)
-__global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, const PlaneArgs g)
+// Twin layers: a second convolution `b` of the same input whose kernel is the centre (KS - 2) x (KS - 2) of this one's
+// (the 3x3 branch beside a 5x5 branch, the 1x1 beside a 3x3 of the restoration network's two-branch layers).  Its
+// activation fragments are fragments this layer reads anyway; twin_frag() says which of its weight fragments, if any,
+// multiplies the activation fragment f of the main layer.
+template <int KS, int CIN>
+constexpr int twin_frag(int f)
+{
+    constexpr int KSB = KS - 2;
+    if (CIN == 64) {                                 // two fragments per tap
+        const int t = f / 2, dy = t / KS, dx = t % KS;
+        if (t >= KS * KS || dy < 1 || dy > KSB || dx < 1 || dx > KSB) return -1;
+        return ((dy - 1) * KSB + (dx - 1)) * 2 + (f & 1);
+    }
+    // 48 channels, 3x3 beside 1x1: the centre tap starts at k = 4 * 48 = 6 * 32; its channels 32..47 share fragment 7 with
+    // the next tap's first 16, which meet the zero padding of the twin's K axis
+    return f == 6 ? 0 : (f == 7 ? 1 : -1);
+}
+
+// kernel size, input channels (48 or 64), 32-channel chunks of the output (1 or 2), chunks of the twin layer (0: none, or 1)
+template <int KS, int CIN, int NCH, int NB>
+__global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, const ConvArgs b, const PlaneArgs g)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the buffer-resource type exists in the device pass only
     constexpr unsigned OOB = 0x80000000u;            // beyond any buffer this kernel accepts (< 2 GiB)
@@ -63,13 +82,18 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
     constexpr int CPW = (NCOPY + 7) / 8;             // per wave
     constexpr int PATCH = NCOPY * 1024;
     constexpr int WBYTES = NCH * KSTEPS * kChunkBytes;
+    constexpr int KSB = KS - 2;
+    constexpr int KSTEPSB = NB ? (KSB * KSB * CIN + 63) / 64 : 0, FB = 2 * KSTEPSB;
+    constexpr int WBYTESB = NB * KSTEPSB * kChunkBytes;
     static_assert(CIN == 48 || CIN == 64, "row layouts exist for 48 and 64 channels");
-    static_assert(WBYTES + 2 * PATCH <= 160 * 1024, "LDS");
+    static_assert(NB == 0 || CIN == 64 || KS == 3, "twin_frag() covers 64 channels, and 48 channels at 3x3 beside 1x1");
+    static_assert(WBYTES + WBYTESB + 2 * PATCH <= 160 * 1024, "LDS");
     static_assert((PH + 1) * ROWB < 65536, "fragment reads address rows and taps through the instruction's 16-bit offset");
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     uint8_t *const wbuf = lds;
-    uint8_t *const pbuf = lds + WBYTES;
+    [[maybe_unused]] uint8_t *const wbufB = lds + WBYTES;
+    uint8_t *const pbuf = lds + WBYTES + WBYTESB;
 
     const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, col = lane & 31;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -131,8 +155,11 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
     PLANE_TR(0);
     // weights: a straight copy of the first NCH chunks (the packed order is the fragment order)
     for (int i = tid; i < WBYTES / 16; i += 512) *(v4i *)(wbuf + i * 16) = *(const v4i *)(a.wp + (size_t)i * 16);
+    for (int i = tid; i < WBYTESB / 16; i += 512) *(v4i *)(wbufB + i * 16) = *(const v4i *)(b.wp + (size_t)i * 16);
     v16i bias[NCH];
     load_bias_rows<NCH>(a, 0, half, bias);
+    [[maybe_unused]] v16i biasB[NB ? NB : 1];
+    if constexpr (NB > 0) load_bias_rows<NB>(b, 0, half, biasB);
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_waitcnt(0x0070);              // vmcnt(0), lgkmcnt(0): the first patch and the weights are in LDS
     __builtin_amdgcn_s_barrier();
@@ -146,7 +173,7 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
     const uint8_t *const wlane = wbuf + lane * 16;
     // 3x3 layers with one channel chunk: the weight fragments fit in registers (18 or 14) and stay there for all tiles, which takes a
     // third to a half of the K loop's LDS reads away; 5x5 layers (50 fragments) read them from LDS every time
-    constexpr bool AREG = KS == 3 && NCH == 1;
+    constexpr bool AREG = KS == 3 && NCH == 1 && !(NB > 0 && CIN == 64);      // (with a twin at 64 channels they spill)
     [[maybe_unused]] v4i wreg[AREG ? NCH : 1][AREG ? F : 1];
     if constexpr (AREG) {
 #pragma unroll
@@ -154,6 +181,7 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
 #pragma unroll
             for (int f = 0; f < F; ++f) wreg[c][f] = *(const v4i *)(wlane + (c * F + f) * 1024);
     }
+    [[maybe_unused]] const uint8_t *const wlaneB = wbufB + lane * 16;
     [[maybe_unused]] int ex[KS][2];
     [[maybe_unused]] int lin = 0;
     if constexpr (CIN == 64) {
@@ -169,6 +197,7 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
     // pixel straight from epilogue_bytes16 (the general epilogue's dispatch costs as much as a 3x3 tile's K loop here)
     const bool quick = a.epi_vec && a.out_mode <= 1 && a.epi_mode / 4 != 2 && (a.Cout & 15) == 0;
     const bool has_res = a.res_mode != 0;
+    [[maybe_unused]] const bool quickB = NB && b.epi_vec && b.out_mode <= 1 && b.epi_mode / 4 == 0 && (b.Cout & 15) == 0;
 
     int buf = 0;
     for (int v = blockIdx.x; valid(v); v += gridDim.x) {
@@ -191,7 +220,15 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int c = 0; c < NCH; ++c) acc[j][c][0] = bias[c];
+        [[maybe_unused]] v16i accB[2][NB ? NB : 1][1];
+        if constexpr (NB > 0) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int c = 0; c < NB; ++c) accB[j][c][0] = biasB[c];
+        }
         v4i A[2][NCH], B[2][2];
+        [[maybe_unused]] v4i AB[2][NB ? NB : 1];
         // pieces in the zero-padded tail of K read the last tap again (their weights are zeros)
         auto fetch = [&](auto f_tag, auto set_tag) {
             constexpr int f = decltype(f_tag)::value, S = decltype(set_tag)::value;
@@ -200,6 +237,10 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
             if constexpr (!AREG) {
 #pragma unroll
                 for (int c = 0; c < NCH; ++c) A[S][c] = *(const v4i *)(wlane + (c * F + f) * 1024);
+            }
+            if constexpr (NB > 0 && twin_frag<KS, CIN>(f) >= 0) {       // the twin's few fragments always come from LDS
+#pragma unroll
+                for (int c = 0; c < NB; ++c) AB[S][c] = *(const v4i *)(wlaneB + (c * FB + twin_frag<KS, CIN>(f)) * 1024);
             }
             if constexpr (CIN == 64) {
                 static_assert(CIN != 64 || T0 == T1, "a fragment of a 64-channel layer lies in one tap");
@@ -228,6 +269,13 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
                 for (int j = 0; j < 2; ++j)
                     acc[j][c][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(AREG ? wreg[AREG ? c : 0][AREG ? f : 0] : A[f & 1][c], B[f & 1][j],
                                                                          acc[j][c][0], 0, 0, 0);
+            if constexpr (NB > 0 && twin_frag<KS, CIN>(f) >= 0) {
+#pragma unroll
+                for (int c = 0; c < NB; ++c)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        accB[j][c][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(AB[f & 1][c], B[f & 1][j], accB[j][c][0], 0, 0, 0);
+            }
         });
         PLANE_TR(3);
         static_for<2>([&](auto j_tag) {
@@ -249,6 +297,20 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
                 });
             } else {
                 epilogue_tiles<NCH, 1>(a, acc[j], 0, pix_row, lane);
+            }
+            if constexpr (NB > 0) {
+                mfma_drain(accB[j]);
+                if (quickB) {
+                    const size_t p = (size_t)(pix_row + col);
+                    static_for<NB>([&](auto c_tag) {
+                        constexpr int c = decltype(c_tag)::value;
+                        const int co0 = c * 32 + half * 16;
+                        if (co0 < b.Cout)
+                            *(v4i *)((uint8_t *)b.out + p * b.out_cs + b.out_co + co0) = epilogue_bytes16<0>(b, accB[j][c][0], v4i{0, 0, 0, 0});
+                    });
+                } else {
+                    epilogue_tiles<NB, 1>(b, accB[j], 0, pix_row, lane);
+                }
             }
         });
         PLANE_TR(4);
@@ -294,8 +356,8 @@ bool conv_plane_applies(const ConvArgs &a)
     return (long long)a.N * (a.H / kPlaneTH) * (a.W / kPlaneTW) >= 1024;
 }
 
-template <int KS, int CIN, int NCH>
-static hipError_t launch_plane(const ConvArgs &a, hipStream_t st)
+template <int KS, int CIN, int NCH, int NB = 0>
+static hipError_t launch_plane(const ConvArgs &a, const ConvArgs &b, hipStream_t st)
 {
     PlaneArgs g;
     g.tiles_x = a.W / kPlaneTW;
@@ -309,14 +371,15 @@ static hipError_t launch_plane(const ConvArgs &a, hipStream_t st)
     constexpr int PH = kPlaneTH + KS - 1, PW = kPlaneTW + KS - 1;
     constexpr int NCOPY = (PH * ((PW + 3) & ~3) * (CIN / 16) + 63) / 64;
     constexpr int KSTEPS = (KS * KS * CIN + 63) / 64;
-    const size_t lds_bytes = (size_t)NCH * KSTEPS * kChunkBytes + 2 * (size_t)NCOPY * 1024;
-    const auto kernel = conv_plane_kernel<KS, CIN, NCH>;
+    constexpr int KSTEPSB = NB ? ((KS - 2) * (KS - 2) * CIN + 63) / 64 : 0;
+    const size_t lds_bytes = (size_t)(NCH * KSTEPS + NB * KSTEPSB) * kChunkBytes + 2 * (size_t)NCOPY * 1024;
+    const auto kernel = conv_plane_kernel<KS, CIN, NCH, NB>;
     if (lds_bytes > 64 * 1024) {
         const hipError_t e = allow_large_lds((const void *)kernel);
         if (e != hipSuccess) return e;
     }
     const dim3 grid((unsigned)(8 * g.per_xcd < 256 ? 8 * g.per_xcd : 256)), block(512);
-    hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, a, g);
+    hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, a, b, g);
     return hipGetLastError();
 }
 
@@ -324,9 +387,27 @@ hipError_t launch_conv_plane(const ConvArgs &a, hipStream_t st)
 {
     if (!plane_shape_ok(a)) return hipErrorInvalidValue;
     const int nch = plane_nch(a);
-    if (a.KH == 5) return launch_plane<5, 64, 1>(a, st);
-    if (a.Cin == 64) return nch == 1 ? launch_plane<3, 64, 1>(a, st) : launch_plane<3, 64, 2>(a, st);
-    return nch == 1 ? launch_plane<3, 48, 1>(a, st) : launch_plane<3, 48, 2>(a, st);
+    if (a.KH == 5) return launch_plane<5, 64, 1>(a, a, st);
+    if (a.Cin == 64) return nch == 1 ? launch_plane<3, 64, 1>(a, a, st) : launch_plane<3, 64, 2>(a, a, st);
+    return nch == 1 ? launch_plane<3, 48, 1>(a, a, st) : launch_plane<3, 48, 2>(a, a, st);
+}
+
+// Two layers of one input in one launch: `a` as above with at most 32 output channels, `b` with the kernel two pixels
+// smaller (3x3 beside 5x5, 1x1 beside 3x3), "same" padding, at most 32 output channels, no skip operands.
+bool conv_plane_twin_ok(const ConvArgs &a, const ConvArgs &b)
+{
+    if (!plane_shape_ok(a) || plane_nch(a) != 1 || a.res_mode != 0 || b.res_mode != 0) return false;
+    if (b.x != a.x || b.N != a.N || b.H != a.H || b.W != a.W || b.Cin != a.Cin || b.in_cs != a.in_cs || b.Ho != a.H || b.Wo != a.W) return false;
+    if (b.KH != a.KH - 2 || b.KW != a.KW - 2 || b.sh != 1 || b.sw != 1 || b.ph != b.KH / 2 || b.pw != b.KW / 2) return false;
+    if (b.in_xor || b.frag_xor || b.pc || b.Cout > 32 || b.ksteps != (b.KH * b.KW * b.Cin + 63) / 64) return false;
+    return true;
+}
+
+hipError_t launch_conv_plane_twin(const ConvArgs &a, const ConvArgs &b, hipStream_t st)
+{
+    if (!conv_plane_twin_ok(a, b)) return hipErrorInvalidValue;
+    if (a.KH == 5) return launch_plane<5, 64, 1, 1>(a, b, st);
+    return a.Cin == 64 ? launch_plane<3, 64, 1, 1>(a, b, st) : launch_plane<3, 48, 1, 1>(a, b, st);
 }
 
 }  // namespace icnn

@@ -190,6 +190,8 @@ bool conv_halo_applies(const ConvArgs &a);
 hipError_t launch_conv_halo(const ConvArgs &a, hipStream_t st);
 bool conv_plane_applies(const ConvArgs &a);
 hipError_t launch_conv_plane(const ConvArgs &a, hipStream_t st);
+bool conv_plane_twin_ok(const ConvArgs &a, const ConvArgs &b);
+hipError_t launch_conv_plane_twin(const ConvArgs &a, const ConvArgs &b, hipStream_t st);
 bool conv_deep_applies(const ConvArgs &a);
 hipError_t launch_conv_deep(const ConvArgs &a, hipStream_t st);
 hipError_t launch_conv_pic(const ConvArgs &a, hipStream_t st);

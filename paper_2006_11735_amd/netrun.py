@@ -41,6 +41,7 @@ class GpuNet:
         self.fused_block = {}               # last conv name -> (first, middle) conv ops fused into its launch
         self.fused_pool = {}                # first conv name -> the max-pool op fused into its launch
         self.fused_pair = {}                # block-closing conv name -> the next block's opening conv op in its launch
+        self.fused_twin = {}                # branch name -> the other branch's op in its launch
         self.fused_projblock = {}           # last conv name -> (first, middle, projection) conv ops fused into its launch
         pending = {}                        # skip buffer name -> prepared projection step
         for op in net["ops"]:
@@ -76,6 +77,7 @@ class GpuNet:
             self._fuse_projection_blocks()
             self._fuse_first_layer()
             self._fuse_pairs()
+            self._fuse_twins()
         torch.cuda.synchronize(self.device)
 
     def _fuse_first_layer(self):
@@ -141,6 +143,38 @@ class GpuNet:
                     else:
                         self.fused_pair[o3["name"]] = o1
                         steps.append(("pair", o3, args))
+                        i += 2
+                        continue
+            steps.append(self.steps[i])
+            i += 1
+        self.steps = steps
+
+    # The twin launch reads the input once and writes whole pixels of the shared buffer; below a few tiles per compute
+    # unit the two-dimensional-tile kernel it runs on is not the library's own choice for either branch.
+    TWIN_MIN_PIXELS = 1024 * 512
+
+    def _fuse_twins(self):
+        """Two consecutive convolutions of the same input whose kernels differ by two pixels (the branches of a
+        concatenation): one iconv2d_twin_brelu launch where the library accepts it."""
+        steps, i = [], 0
+        while i < len(self.steps):
+            two = self.steps[i:i + 2]
+            if len(two) == 2 and two[0][0] == "conv" and two[1][0] == "conv":
+                (da, xa, wa, ba, ra, ya, _wsa), (db, xb, wb, bb, rb, yb, _wsb) = two[0][2], two[1][2]
+                oa, ob = two[0][1], two[1][1]
+                if oa["kh"] < ob["kh"]:
+                    (da, wa, ba, ya, oa), (db, wb, bb, yb, ob) = (db, wb, bb, yb, ob), (da, wa, ba, ya, oa)
+                if (oa["src"] == ob["src"] and oa["kh"] == ob["kh"] + 2 and ra is None and rb is None and
+                        oa["dst"] != oa["src"] and ob["dst"] != ob["src"] and da.n * da.h * da.w >= self.TWIN_MIN_PIXELS):
+                    args = (da, xa, wa, ba, ya, db, wb, bb, yb)
+                    try:
+                        B.iconv2d_twin_brelu(*args)                # also a warm-up launch
+                    except B.IcnnError as e:
+                        if e.code != B.ICNN_E_UNSUPPORTED:
+                            raise
+                    else:
+                        self.fused_twin[oa["name"]] = ob
+                        steps.append(("twin", oa, args))
                         i += 2
                         continue
             steps.append(self.steps[i])
@@ -310,6 +344,8 @@ class GpuNet:
             B.iconv2d_dual_brelu_pc(*args, stream=stream)
         elif kind == "pair":
             B.iconv2d_pair_brelu(*args, stream=stream)
+        elif kind == "twin":
+            B.iconv2d_twin_brelu(*args, stream=stream)
         elif kind == "projblock":
             B.iconv2d_bottleneck_dual_brelu(*args, stream=stream)
         elif kind == "block":
