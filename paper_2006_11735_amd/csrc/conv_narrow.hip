@@ -158,6 +158,20 @@ __global__ __launch_bounds__(256) void conv_narrow3x3_kernel(const ConvArgs a, i
 #pragma unroll
         for (int co = 0; co < NCO; ++co) acc[q][co] = 0;
 
+    // The skip operand of an output row is fetched one row step before the row is complete: a load inside emit() would
+    // have to be waited for on the spot, and that wait also covers the next input row's loads issued just before it,
+    // i.e. every row step would expose a full memory latency.
+    int rescur[NCO], resnext[NCO];
+#pragma unroll
+    for (int co = 0; co < NCO; ++co) rescur[co] = resnext[co] = 0;
+    auto fetch_res = [&](int j, int (&r)[NCO]) {      // skip operand of output row r0 + j, where that row exists
+        if (a.res_mode != 0 && j >= 0 && j < rows_out && colv && slice == 0) {
+            const size_t ro = (((size_t)n * a.Ho + r0 + j) * a.Wo + wo) * a.res_cs;
+#pragma unroll
+            for (int co = 0; co < NCO; ++co)
+                if (co < a.Cout) r[co] = load_elem(a.res, ro + co, a.res_dtype);
+        }
+    };
     // input row i of the segment (image row r0 - ph + i) adds tap row kh to output row r0 + i - kh
     auto emit = [&](int j, int (&sum)[NCO]) {         // output row r0 + j is complete
 #pragma unroll
@@ -168,14 +182,14 @@ __global__ __launch_bounds__(256) void conv_narrow3x3_kernel(const ConvArgs a, i
         }
         if (j >= 0 && j < rows_out && colv && slice == 0) {
             const size_t p = ((size_t)n * a.Ho + r0 + j) * a.Wo + wo;
-            const size_t ro = p * a.res_cs, oo = p * a.out_cs + a.out_co;
+            const size_t oo = p * a.out_cs + a.out_co;
 #pragma unroll
             for (int co = 0; co < NCO; ++co) {
                 if (co >= a.Cout) break;
                 int64_t t = (int64_t)sum[co] + a.bias[co];
                 if (a.frag_xor) t += 128LL * a.wsum[co];     // see ConvArgs::frag_xor
                 int64_t skip = 0;
-                if (a.res_mode != 0) skip = rsr64((int64_t)load_elem(a.res, ro + co, a.res_dtype) * a.res_mul, a.res_shift);
+                if (a.res_mode != 0) skip = rsr64((int64_t)rescur[co] * a.res_mul, a.res_shift);
                 if (a.res_mode == 1) t += skip;
                 const int ti = sat32(t);
                 if (a.out_mode == 3) {
@@ -214,6 +228,7 @@ __global__ __launch_bounds__(256) void conv_narrow3x3_kernel(const ConvArgs a, i
     bool oknext = false;
     auto row_step = [&](int i, int (&a0)[NCO], int (&a1)[NCO], int (&a2)[NCO]) {
         fetch_row(i + 1, vnext, oknext);
+        fetch_res(i - 1, resnext);                    // for the row the next step completes
         auto tap_row = [&](int kh, int (&dst)[NCO]) {
 #pragma unroll
             for (int kw = 0; kw < 3; ++kw)
@@ -231,6 +246,8 @@ __global__ __launch_bounds__(256) void conv_narrow3x3_kernel(const ConvArgs a, i
         tap_row(2, a2);        // output row r0 + i - 2: complete
         emit(i - 2, a2);
         finish_row(vnext, oknext, vcur);
+#pragma unroll
+        for (int co = 0; co < NCO; ++co) rescur[co] = resnext[co];
     };
     fetch_row(0, vnext, oknext);
     finish_row(vnext, oknext, vcur);
