@@ -113,9 +113,12 @@ __global__ __launch_bounds__(256) void conv_narrow_kernel(const ConvArgs a)
 // the three output rows it belongs to, whose partial sums rotate through three accumulator sets; the
 // row that just became complete is reduced over the S lanes of each pixel and stored.  x is read once
 // from HBM and three times (instead of nine) through L1.
-template <int NCO>
+// PLAIN: the input bytes are operands as they are (no XOR) and x lies below 2 GiB: the loads go through a buffer
+// descriptor, whose range check returns zeros for the padding (an out-of-range offset) at no instruction.
+template <int NCO, bool PLAIN>
 __global__ __launch_bounds__(256) void conv_narrow3x3_kernel(const ConvArgs a, int rseg, int strips, int segs)
 {
+#if defined(__HIP_DEVICE_COMPILE__)   // the buffer-resource type exists in the device pass only
     extern __shared__ __attribute__((aligned(16))) uint8_t wl_raw[];     // [tap][slice][co] x 16 bytes
     v4i *wl = (v4i *)wl_raw;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -146,12 +149,20 @@ __global__ __launch_bounds__(256) void conv_narrow3x3_kernel(const ConvArgs a, i
         for (int co = 0; co < NCO; ++co) wreg[t][co] = wl[(t * S + slice) * NCO + co];
     bool cok[3];
     size_t coff[3];
+    // PLAIN: offsets from the row's first byte; a column outside the picture gets one beyond any buffer this path takes,
+    // and so does a row outside it (their sum stays below 2^32)
+    [[maybe_unused]] const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, a.x_bytes, 0x00020000);
+    [[maybe_unused]] unsigned boff[3];
 #pragma unroll
     for (int kw = 0; kw < 3; ++kw) {
         const int wi = wo - a.pw + kw;
         cok[kw] = colv && (unsigned)wi < (unsigned)a.W;
         coff[kw] = cok[kw] ? (size_t)wi * a.in_cs + slice * 16 : 0;
+        boff[kw] = cok[kw] ? (unsigned)coff[kw] : 0x7fffff00u;
     }
+    // the epilogue in 32 bits where the layer's parameters allow it (wave-uniform): requantisation as one multiply-add
+    // whose high word is the result, an unsigned 8-bit skip operand whose rescale fits 32 bits
+    const bool quick = a.out_mode != 3 && a.rq_fast && !a.frag_xor && (a.res_mode == 0 || a.res_fast);
     int acc[3][NCO];
 #pragma unroll
     for (int q = 0; q < 3; ++q)
@@ -183,6 +194,18 @@ __global__ __launch_bounds__(256) void conv_narrow3x3_kernel(const ConvArgs a, i
         if (j >= 0 && j < rows_out && colv && slice == 0) {
             const size_t p = ((size_t)n * a.Ho + r0 + j) * a.Wo + wo;
             const size_t oo = p * a.out_cs + a.out_co;
+            if (quick) {
+#pragma unroll
+                for (int co = 0; co < NCO; ++co) {
+                    if (co >= a.Cout) break;
+                    int skip = 0;
+                    if (a.res_mode != 0) skip = (int)(((uint32_t)rescur[co] * (uint32_t)a.res_mul + (uint32_t)((1 << a.res_shift) >> 1)) >> a.res_shift);
+                    const int ti = sat32((int64_t)sum[co] + a.bias[co] + (a.res_mode == 1 ? skip : 0));
+                    int q = (int)(((int64_t)ti * a.mul_hi + 0x80000000LL) >> 32);
+                    if (a.res_mode == 2) q = __builtin_elementwise_add_sat(q, skip);       // the clamp below makes the saturation exact
+                    ((uint8_t *)a.out)[oo + co] = (uint8_t)min(max(q, a.lo), a.hi);
+                }
+            } else
 #pragma unroll
             for (int co = 0; co < NCO; ++co) {
                 if (co >= a.Cout) break;
@@ -208,13 +231,24 @@ __global__ __launch_bounds__(256) void conv_narrow3x3_kernel(const ConvArgs a, i
     auto fetch_row = [&](int i, v4i (&v)[3], bool &rowok) {
         const int hi = r0 - a.ph + i;
         rowok = (unsigned)hi < (unsigned)a.H;
-        const uint8_t *row = a.x + (rowok ? (size_t)(n * a.H + hi) * a.W * a.in_cs : 0);
+        if constexpr (PLAIN) {
+            const unsigned rb = rowok ? (unsigned)((n * a.H + hi) * a.W) * (unsigned)a.in_cs : 0x80000000u;
 #pragma unroll
-        for (int kw = 0; kw < 3; ++kw) v[kw] = *(const v4i *)(row + coff[kw]);
+            for (int kw = 0; kw < 3; ++kw) v[kw] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, rb + boff[kw], 0, 0);
+        } else {
+            const uint8_t *row = a.x + (rowok ? (size_t)(n * a.H + hi) * a.W * a.in_cs : 0);
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) v[kw] = *(const v4i *)(row + coff[kw]);
+        }
     };
     // ... and what makes them operands: outside the image zero after the raw picture's "- 128", -128 for
     // full-range unsigned bytes (which the weight-sum term of the bias turns back into zero)
     auto finish_row = [&](const v4i (&raw)[3], bool rowok, v4i (&v)[3]) {
+        if constexpr (PLAIN) {
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) v[kw] = raw[kw];
+            return;
+        }
 #pragma unroll
         for (int kw = 0; kw < 3; ++kw) {
             const bool ok = rowok && cok[kw];
@@ -257,6 +291,7 @@ __global__ __launch_bounds__(256) void conv_narrow3x3_kernel(const ConvArgs a, i
         if (i + 1 < rows_in) row_step(i + 1, acc[1], acc[0], acc[2]);
         if (i + 2 < rows_in) row_step(i + 2, acc[2], acc[1], acc[0]);
     }
+#endif
 }
 
 bool conv_narrow_applies(const ConvArgs &a)
@@ -285,8 +320,14 @@ hipError_t launch_conv_narrow(const ConvArgs &a0, hipStream_t st)
         const int segs = (int)((a.Ho + rseg - 1) / rseg);
         const long long waves = (long long)a.N * segs * strips;
         const dim3 grid((unsigned)((waves + 3) / 4)), block(256);
-        if (a.Cout == 1) hipLaunchKernelGGL(conv_narrow3x3_kernel<1>, grid, block, lds, st, a, (int)rseg, strips, segs);
-        else hipLaunchKernelGGL(conv_narrow3x3_kernel<4>, grid, block, lds, st, a, (int)rseg, strips, segs);
+        const bool plain = !a.in_xor && !a.frag_xor && a.x_bytes < 0x7fffff00u;
+        if (a.Cout == 1) {
+            if (plain) hipLaunchKernelGGL((conv_narrow3x3_kernel<1, true>), grid, block, lds, st, a, (int)rseg, strips, segs);
+            else hipLaunchKernelGGL((conv_narrow3x3_kernel<1, false>), grid, block, lds, st, a, (int)rseg, strips, segs);
+        } else {
+            if (plain) hipLaunchKernelGGL((conv_narrow3x3_kernel<4, true>), grid, block, lds, st, a, (int)rseg, strips, segs);
+            else hipLaunchKernelGGL((conv_narrow3x3_kernel<4, false>), grid, block, lds, st, a, (int)rseg, strips, segs);
+        }
         return hipGetLastError();
     }
     const dim3 grid((unsigned)((a.M + ppb - 1) / ppb)), block(256);
