@@ -315,8 +315,11 @@ hipError_t launch_conv_narrow(const ConvArgs &a0, hipStream_t st)
         // row segments short enough to give the chip a few thousand waves, long enough to amortise the
         // two halo rows each segment re-reads
         const int strips = (a.Wo + 64 / S - 1) / (64 / S);
-        long long rseg = (long long)a.N * a.Ho * strips / 4096;
-        rseg = rseg < 4 ? 4 : (rseg > 32 ? 32 : rseg);
+        // ... and few enough that all waves are resident at once (five per SIMD with one output channel, two with four:
+        // 256 CUs x 4 SIMDs of them, less a margin for the ragged last segment), or the last ones run alone
+        const long long slots = 1024LL * (a.Cout == 1 ? 5 : 2) * 19 / 20;
+        long long rseg = ((long long)a.N * a.Ho * strips + slots - 1) / slots;
+        rseg = rseg < 4 ? 4 : (rseg > 128 ? 128 : rseg);
         const int segs = (int)((a.Ho + rseg - 1) / rseg);
         const long long waves = (long long)a.N * segs * strips;
         const dim3 grid((unsigned)((waves + 3) / 4)), block(256);
