@@ -7,6 +7,7 @@
 // the patch-resident kernel of conv_halo.hip does not apply either.  Here the tile is two-dimensional:
 //
 //   tile     16 rows x 32 columns of one picture; a pixel group of 32 is one tile row, wave w owns rows 2w and 2w + 1
+//            (8 rows x 32 columns, one row per wave, for 3x3 layers of 64 channels on pictures with too few tiles)
 //   patch    the (16 + k - 1) x (32 + k - 1) input pixels under the tile, all channels, in LDS (zeros outside the picture:
 //            the layer's padding), double-buffered: the next tile's patch travels by direct-to-LDS copies while this
 //            one is multiplied.  The 16-byte pieces of 64-channel pixels are swizzled by the pixel's column; 48-byte
@@ -26,7 +27,7 @@
 
 namespace icnn {
 
-constexpr int kPlaneTH = 16, kPlaneTW = 32;
+constexpr int kPlaneTW = 32;               // tile width; its height is 8 x the rows a wave owns (RPW: 2, or 1 for small pictures)
 
 #ifdef ICNN_PLANE_TRACE      // development aid: one wave of one workgroup stamps the clock; icnn_debug_trace_plane() copies the stamps out
 __device__ unsigned long long g_plane_trace[256];
@@ -63,14 +64,16 @@ constexpr int twin_frag(int f)
     return f == 6 ? 0 : (f == 7 ? 1 : -1);
 }
 
-// kernel size, input channels (48 or 64), 32-channel chunks of the output (1 or 2), chunks of the twin layer (0: none, or 1)
-template <int KS, int CIN, int NCH, int NB>
+// kernel size, input channels (48 or 64), 32-channel chunks of the output (1 or 2), chunks of the twin layer (0: none, or 1),
+// tile rows per wave (2: tiles of 16 x 32 pixels; 1: 8 x 32, twice the tiles for pictures that have too few)
+template <int KS, int CIN, int NCH, int NB, int RPW>
 __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, const ConvArgs b, const PlaneArgs g)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the buffer-resource type exists in the device pass only
     constexpr unsigned OOB = 0x80000000u;            // beyond any buffer this kernel accepts (< 2 GiB)
     constexpr int PAD = KS / 2;
-    constexpr int PH = kPlaneTH + KS - 1, PW = kPlaneTW + KS - 1;
+    constexpr int TH = 8 * RPW;
+    constexpr int PH = TH + KS - 1, PW = kPlaneTW + KS - 1;
     constexpr int PWL = (PW + 3) & ~3;               // pixels per patch row in LDS: whole groups of four
     constexpr int PPT = CIN / 16;                    // 16-byte pieces per pixel (= per tap)
     constexpr int ROWB = PWL * CIN;                  // bytes per patch row
@@ -109,7 +112,7 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
         n = fast_div(t, g.div_tpi);
         const int r = t - n * g.tiles_per_img;
         const int ty = fast_div(r, g.div_tx);
-        y0 = ty * kPlaneTH;
+        y0 = ty * TH;
         x0 = (r - ty * g.tiles_x) * kPlaneTW;
     };
 
@@ -189,9 +192,9 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
         for (int dx = 0; dx < KS; ++dx)
 #pragma unroll
             for (int k = 0; k < 2; ++k)
-                ex[dx][k] = (2 * wave) * ROWB + (col + dx) * 64 + (((2 * k + half) ^ (((col + dx) >> 2) & 3)) << 4);
+                ex[dx][k] = (RPW * wave) * ROWB + (col + dx) * 64 + (((2 * k + half) ^ (((col + dx) >> 2) & 3)) << 4);
     } else {
-        lin = (2 * wave) * ROWB + col * CIN;
+        lin = (RPW * wave) * ROWB + col * CIN;
     }
     // 8-bit output with at most the plain 8-bit skip operand, whole groups of 16 channels: sixteen bytes per lane and
     // pixel straight from epilogue_bytes16 (the general epilogue's dispatch costs as much as a 3x3 tile's K loop here)
@@ -215,19 +218,19 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
         PLANE_TR(2);
         const uint8_t *const P = pbuf + buf * PATCH;
 
-        v16i acc[2][NCH][1];
+        v16i acc[RPW][NCH][1];
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < RPW; ++j)
 #pragma unroll
             for (int c = 0; c < NCH; ++c) acc[j][c][0] = bias[c];
-        [[maybe_unused]] v16i accB[2][NB ? NB : 1][1];
+        [[maybe_unused]] v16i accB[RPW][NB ? NB : 1][1];
         if constexpr (NB > 0) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < RPW; ++j)
 #pragma unroll
                 for (int c = 0; c < NB; ++c) accB[j][c][0] = biasB[c];
         }
-        v4i A[2][NCH], B[2][2];
+        v4i A[2][NCH], B[2][RPW];
         [[maybe_unused]] v4i AB[2][NB ? NB : 1];
         // pieces in the zero-padded tail of K read the last tap again (their weights are zeros)
         auto fetch = [&](auto f_tag, auto set_tag) {
@@ -246,13 +249,13 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
                 static_assert(CIN != 64 || T0 == T1, "a fragment of a 64-channel layer lies in one tap");
                 constexpr int DY = T0 / KS, DX = T0 % KS, KK = (P0 % PPT) / 2;
 #pragma unroll
-                for (int j = 0; j < 2; ++j) B[S][j] = *(const v4i *)(P + ex[DX][KK] + (j + DY) * ROWB);
+                for (int j = 0; j < RPW; ++j) B[S][j] = *(const v4i *)(P + ex[DX][KK] + (j + DY) * ROWB);
             } else {
                 constexpr int O0 = (T0 / KS) * ROWB + (T0 % KS) * CIN + (P0 % PPT) * 16;
                 constexpr int O1 = (T1 / KS) * ROWB + (T1 % KS) * CIN + (P1 % PPT) * 16;
                 const int o = lin + (half ? O1 : O0);
 #pragma unroll
-                for (int j = 0; j < 2; ++j) B[S][j] = *(const v4i *)(P + o + j * ROWB);
+                for (int j = 0; j < RPW; ++j) B[S][j] = *(const v4i *)(P + o + j * ROWB);
             }
         };
         fetch(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
@@ -266,23 +269,23 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
 #pragma unroll
             for (int c = 0; c < NCH; ++c)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < RPW; ++j)
                     acc[j][c][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(AREG ? wreg[AREG ? c : 0][AREG ? f : 0] : A[f & 1][c], B[f & 1][j],
                                                                          acc[j][c][0], 0, 0, 0);
             if constexpr (NB > 0 && twin_frag<KS, CIN>(f) >= 0) {
 #pragma unroll
                 for (int c = 0; c < NB; ++c)
 #pragma unroll
-                    for (int j = 0; j < 2; ++j)
+                    for (int j = 0; j < RPW; ++j)
                         accB[j][c][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(AB[f & 1][c], B[f & 1][j], accB[j][c][0], 0, 0, 0);
             }
         });
         PLANE_TR(3);
-        static_for<2>([&](auto j_tag) {
+        static_for<RPW>([&](auto j_tag) {
             constexpr int j = decltype(j_tag)::value;
             mfma_drain(acc[j]);
             // a tile row's 32 pixels are consecutive pixels of the output tensor
-            const int pix_row = (n * a.H + y0 + 2 * wave + j) * a.W + x0;
+            const int pix_row = (n * a.H + y0 + RPW * wave + j) * a.W + x0;
             if (quick) {
                 const size_t p = (size_t)(pix_row + col);
                 static_for<NCH>([&](auto c_tag) {
@@ -339,41 +342,51 @@ static bool plane_shape_ok(const ConvArgs &a)
 {
     if (a.KH != a.KW || (a.KH != 3 && a.KH != 5) || a.sh != 1 || a.sw != 1 || a.ph != a.KH / 2 || a.pw != a.KW / 2) return false;
     if ((a.Cin != 48 && a.Cin != 64) || a.in_cs % 16 || ((uintptr_t)a.x & 15) || a.in_xor || a.frag_xor || a.pc) return false;
-    if (a.W % kPlaneTW || a.H % kPlaneTH || a.Ho != a.H || a.Wo != a.W || a.x_bytes >= 0x7fffff00u) return false;
+    if (a.W % kPlaneTW || a.H % 8 || a.Ho != a.H || a.Wo != a.W || a.x_bytes >= 0x7fffff00u) return false;
     if (a.ksteps != (a.KH * a.KW * a.Cin + 63) / 64) return false;
     const int nch = plane_nch(a);
     // the instantiations that exist (launch_conv_plane)
-    if (a.KH == 5) return a.Cin == 64 && nch == 1;
-    return nch <= 2;
+    if (a.KH == 5) return a.Cin == 64 && nch == 1 && a.H % 16 == 0;
+    // tiles of 8 rows exist for 3x3 layers of 64 channels only
+    return nch <= 2 && (a.H % 16 == 0 || a.Cin == 64);
+}
+
+// Tile rows per wave: 2 (tiles of 16 x 32 pixels) where the picture gives every compute unit several tiles, else 1 for
+// the 3x3 layers of 64 channels; 0: the layer is not worth this kernel.
+static int plane_rpw(const ConvArgs &a)
+{
+    const long long tiles8 = (long long)a.N * (a.H / 8) * (a.W / kPlaneTW);
+    if (a.H % 16 == 0 && (tiles8 >= 2048 || (g_tuning.plane_always && !(a.KH == 3 && a.Cin == 64 && tiles8 < 512)))) return 2;
+    if (a.KH == 3 && a.Cin == 64 && (tiles8 >= 192 || g_tuning.plane_always)) return 1;
+    return a.H % 16 == 0 && g_tuning.plane_always ? 2 : 0;
 }
 
 bool conv_plane_applies(const ConvArgs &a)
 {
     if (!plane_shape_ok(a)) return false;
-    if (g_tuning.plane_always) return true;
-    // pictures large enough to give every compute unit several tiles (pointwise layers gain nothing from a resident
-    // patch and are not taken at all: 120 against 101 us at 48 -> 32 channels on 2560 x 1600)
-    return (long long)a.N * (a.H / kPlaneTH) * (a.W / kPlaneTW) >= 1024;
+    // (pointwise layers gain nothing from a resident patch and are not taken at all: 120 against 101 us at 48 -> 32
+    // channels on 2560 x 1600)
+    return plane_rpw(a) != 0;
 }
 
-template <int KS, int CIN, int NCH, int NB = 0>
+template <int KS, int CIN, int NCH, int NB = 0, int RPW = 2>
 static hipError_t launch_plane(const ConvArgs &a, const ConvArgs &b, hipStream_t st)
 {
     PlaneArgs g;
     g.tiles_x = a.W / kPlaneTW;
-    g.tiles_per_img = g.tiles_x * (a.H / kPlaneTH);
+    g.tiles_per_img = g.tiles_x * (a.H / (8 * RPW));
     const long long tiles = (long long)g.tiles_per_img * a.N;
     if (tiles < 1 || tiles > 0x7ffffff0LL) return hipErrorInvalidValue;
     g.n_tiles = (int)tiles;
     g.per_xcd = (int)((tiles + 7) / 8);
     g.div_tpi = make_fast_div((unsigned)g.tiles_per_img);
     g.div_tx = make_fast_div((unsigned)g.tiles_x);
-    constexpr int PH = kPlaneTH + KS - 1, PW = kPlaneTW + KS - 1;
+    constexpr int PH = 8 * RPW + KS - 1, PW = kPlaneTW + KS - 1;
     constexpr int NCOPY = (PH * ((PW + 3) & ~3) * (CIN / 16) + 63) / 64;
     constexpr int KSTEPS = (KS * KS * CIN + 63) / 64;
     constexpr int KSTEPSB = NB ? ((KS - 2) * (KS - 2) * CIN + 63) / 64 : 0;
     const size_t lds_bytes = (size_t)(NCH * KSTEPS + NB * KSTEPSB) * kChunkBytes + 2 * (size_t)NCOPY * 1024;
-    const auto kernel = conv_plane_kernel<KS, CIN, NCH, NB>;
+    const auto kernel = conv_plane_kernel<KS, CIN, NCH, NB, RPW>;
     if (lds_bytes > 64 * 1024) {
         const hipError_t e = allow_large_lds((const void *)kernel);
         if (e != hipSuccess) return e;
@@ -386,8 +399,10 @@ static hipError_t launch_plane(const ConvArgs &a, const ConvArgs &b, hipStream_t
 hipError_t launch_conv_plane(const ConvArgs &a, hipStream_t st)
 {
     if (!plane_shape_ok(a)) return hipErrorInvalidValue;
-    const int nch = plane_nch(a);
+    const int nch = plane_nch(a), rpw = plane_rpw(a);
+    if (rpw == 0) return hipErrorInvalidValue;
     if (a.KH == 5) return launch_plane<5, 64, 1>(a, a, st);
+    if (a.Cin == 64 && rpw == 1) return nch == 1 ? launch_plane<3, 64, 1, 0, 1>(a, a, st) : launch_plane<3, 64, 2, 0, 1>(a, a, st);
     if (a.Cin == 64) return nch == 1 ? launch_plane<3, 64, 1>(a, a, st) : launch_plane<3, 64, 2>(a, a, st);
     return nch == 1 ? launch_plane<3, 48, 1>(a, a, st) : launch_plane<3, 48, 2>(a, a, st);
 }
@@ -396,7 +411,7 @@ hipError_t launch_conv_plane(const ConvArgs &a, hipStream_t st)
 // smaller (3x3 beside 5x5, 1x1 beside 3x3), "same" padding, at most 32 output channels, no skip operands.
 bool conv_plane_twin_ok(const ConvArgs &a, const ConvArgs &b)
 {
-    if (!plane_shape_ok(a) || plane_nch(a) != 1 || a.res_mode != 0 || b.res_mode != 0) return false;
+    if (!plane_shape_ok(a) || a.H % 16 || plane_nch(a) != 1 || a.res_mode != 0 || b.res_mode != 0) return false;
     if (b.x != a.x || b.N != a.N || b.H != a.H || b.W != a.W || b.Cin != a.Cin || b.in_cs != a.in_cs || b.Ho != a.H || b.Wo != a.W) return false;
     if (b.KH != a.KH - 2 || b.KW != a.KW - 2 || b.sh != 1 || b.sw != 1 || b.ph != b.KH / 2 || b.pw != b.KW / 2) return false;
     if (b.in_xor || b.frag_xor || b.pc || b.Cout > 32 || b.ksteps != (b.KH * b.KW * b.Cin + 63) / 64) return false;

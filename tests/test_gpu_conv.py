@@ -547,9 +547,10 @@ def test_3x3_kernel_whose_waves_split_the_k_axis(shape):
 # ---- few channels on a large picture (the restoration networks' layers): two-dimensional tiles of 16 x 32 pixels, the
 # patch and the layer's weights resident in LDS.  Shapes: every (kernel, cin, chunk count) instantiation; pictures of
 # several tiles in both directions, so that patches cross the picture's border on every side and neighbour each other;
-# channel tails (16, 40, 48 outputs); two images.
+# channel tails (16, 40, 48 outputs); two images; pictures whose height or tile count selects the tiles of 8 rows.
 PLANE_SHAPES = [(1, 32, 96, 64, 32, 5, 1, 2), (1, 48, 64, 64, 16, 3, 1, 1), (2, 32, 64, 64, 64, 3, 1, 1), (1, 32, 64, 48, 16, 3, 1, 1),
-                (1, 32, 64, 48, 40, 3, 1, 1), (3, 16, 32, 64, 32, 3, 1, 1), (1, 80, 160, 64, 16, 3, 1, 1), (1, 64, 96, 64, 32, 5, 1, 2)]
+                (1, 32, 64, 48, 40, 3, 1, 1), (3, 16, 32, 64, 32, 3, 1, 1), (1, 80, 160, 64, 16, 3, 1, 1), (1, 64, 96, 64, 32, 5, 1, 2),
+                (1, 24, 64, 64, 64, 3, 1, 1), (2, 8, 96, 64, 16, 3, 1, 1), (1, 64, 64, 64, 64, 3, 1, 1)]     # tiles of 8 rows
 
 
 @pytest.mark.parametrize("shape", PLANE_SHAPES, ids=lambda s: "x".join(map(str, s)))
