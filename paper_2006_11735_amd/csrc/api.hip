@@ -339,7 +339,7 @@ static int conv_layer(const icnn_conv_desc *d, const void *x, const void *w_pack
         a.pc_fast_ok = d->out_mode != ICNN_OUT_RAW_S32 && a.epi_vec &&
                        (d->res_mode == ICNN_RES_NONE || (d->res_mode == ICNN_RES_PRE && d->res_dtype == ICNN_U8));
     }
-    if (g.rp == 32 && !pc && !g_tuning.no_pic && d->stride_h == 1 && d->stride_w == 1 && d->kh <= 8 && (d->cout == 32 || d->cout == 64) &&
+    if ((g.rp == 32 || g.rp == 16) && !pc && !g_tuning.no_pic && d->stride_h == 1 && d->stride_w == 1 && d->kh <= 8 && (d->cout == 32 || d->cout == 64) &&
         (d->out_mode == ICNN_OUT_BRELU_U8 || d->out_mode == ICNN_OUT_CLAMP_U8) && d->res_mode == ICNN_RES_NONE &&
         d->in_signed != ICNN_IN_U8_FULL && d->in_signed != ICNN_IN_S8 && a.vec_out && a.vec_bias && a.x_bytes >= 4 &&
         a.x_bytes <= 0x7fffffffu && g.M <= 0x7fffffffLL)

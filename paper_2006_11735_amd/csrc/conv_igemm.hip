@@ -659,7 +659,8 @@ static hipError_t launch_dlds(const ConvArgs &a0, int max_stages, int per_cu, in
     a.div_wo = make_fast_div((unsigned)a.Wo);
     // per-channel kernels keep two copies of the tile's packed parameters behind the ring
     const size_t lds_bytes = (size_t)a.nstages * (BM + BP) * kStepK + (a.pc ? 2 * (((BM / 16) * kPcGroupInts * 4 + 1023) & ~1023) : 0) + (ksplit > 1 ? 16 : 0);
-    const bool pw = a.KH == 1 && a.KW == 1 && a.sh == 1 && a.sw == 1 && a.ph == 0 && a.pw == 0;
+    // (the padded copy of a 1x1 small-cin layer is wider than the output: its pixels are not the output's pixels)
+    const bool pw = a.KH == 1 && a.KW == 1 && a.sh == 1 && a.sw == 1 && a.ph == 0 && a.pw == 0 && a.Ho == a.H && a.Wo == a.W;
     // kh x 1 kernels whose taps all lie inside the image: no masks (the padded small-cin layout)
     const bool dense = a.KW == 1 && a.ph == 0 && a.pw == 0 && (a.Ho - 1) * a.sh + a.KH <= a.H && (a.Wo - 1) * a.sw + 1 <= a.W &&
                        (long long)(a.K / 16 + 8) * (a.Cin / 16) < 65536;   // the kernel's u / rp16 by multiplication
@@ -759,7 +760,8 @@ static double tile_cost(const TileCfg &c, const ConvArgs &a, int ksplit)
 static bool split_allowed(const TileCfg &c, const ConvArgs &a, int s, bool forced)
 {
     if (s == 1) return true;
-    const bool pw = a.KH == 1 && a.KW == 1 && a.sh == 1 && a.sw == 1 && a.ph == 0 && a.pw == 0;
+    // (the padded copy of a 1x1 small-cin layer is wider than the output: its pixels are not the output's pixels)
+    const bool pw = a.KH == 1 && a.KW == 1 && a.sh == 1 && a.sw == 1 && a.ph == 0 && a.pw == 0 && a.Ho == a.H && a.Wo == a.W;
     if (!(pw || (a.Cin % 64 == 0 && a.KH * a.KW <= 32)) || a.K % kStepK != 0 || a.ksteps % s != 0 || c.bm != 128) return false;
     const long long tiles = (long long)((a.Cout + c.bm - 1) / c.bm) * ((a.M + c.bp - 1) / c.bp);
     if (tiles > kWsMaxSplitTiles) return false;

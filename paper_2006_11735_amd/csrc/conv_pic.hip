@@ -1,4 +1,4 @@
-// First layer of a picture-to-picture network at stride 1 (cin <= 4, kernel 5 to 8 pixels wide and at most 8 high,
+// First layer of a picture-to-picture network at stride 1 (cin <= 4, kernel at most 8 pixels wide and high,
 // 32 or 64 output channels; Sections 3.1, 3.2.1, 3.4.1): the convolution straight off the raw picture, BReLU /
 // requantisation, 8-bit store.  The general path first copies the picture into a padded 4-channel tensor and then
 // runs the tile kernel over it with every kernel row padded to a K block of 32; here the picture pixels under a tile
@@ -10,7 +10,8 @@
 //           (as loads into registers) while this tile is multiplied
 //   conv    D[cout][pixel] with v_mfma_i32_32x32x32_i8, one K block of 32 per kernel row: eight pixels of four
 //           channels from column x on (the packed weights of a small-cin layer have exactly this order, zeros in
-//           the padding); the biases are the C operand of the first row's instructions
+//           the padding); kernels at most four pixels wide pack two rows of four pixels into a K block; the
+//           biases are the C operand of the first block's instructions
 //   store   a lane holds 16 consecutive channels of one pixel: one 16-byte store per accumulator tile
 //
 // 256 threads, persistent workgroups (four per CU), weights resident in LDS.
@@ -43,7 +44,9 @@ __device__ __forceinline__ void pic_static_for(F &&fn)
     }
 }
 
-template <int CG>           // cout / 32: 1 or 2
+// CG: cout / 32 (1 or 2).  ROW16: kernels at most four pixels wide, whose packed rows are 16 bytes: a K block of 32 is
+// two kernel rows of four pixels (this half of the wave the first or the second row) instead of one row of eight.
+template <int CG, bool ROW16>
 __global__ __launch_bounds__(256, 4) void conv_pic_kernel(const ConvArgs a, const PicArgs g)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -132,16 +135,17 @@ __global__ __launch_bounds__(256, 4) void conv_pic_kernel(const ConvArgs a, cons
         v16i acc[CG][2], bias[CG];
 #pragma unroll
         for (int c = 0; c < CG; ++c) bias[c] = bias16(btab + c * 32 + half * 16);
-        // fragments of kernel row kh: weights of every chunk, and per pixel group the eight pixels from column x on
+        // fragments of K block kh (one kernel row, or two with ROW16): weights of every chunk, and per pixel group the eight pixels from column x on
         // (this half of the wave the first or the second four) of patch row y + kh
-        const uint32_t *P = patch + buf * kPicWords + (2 * wave) * kPicPitch + col + 4 * half;
+        const uint32_t *P = patch + buf * kPicWords + (2 * wave + (ROW16 ? half : 0)) * kPicPitch + col + (ROW16 ? 0 : 4 * half);
+        const int nblk = ROW16 ? (a.KH + 1) >> 1 : a.KH;          // K blocks of 32
         v4i af[CG], bf[2], afn[CG], bfn[2];
         auto fetch_frags = [&](v4i (&fa)[CG], v4i (&fb)[2], int kh) {
 #pragma unroll
             for (int c = 0; c < CG; ++c) fa[c] = *(const v4i *)(wbuf + ((c * a.ksteps + (kh >> 1)) * 2 + (kh & 1)) * 1024 + lane * 16);
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                const uint32_t *q = P + (j + kh) * kPicPitch;
+                const uint32_t *q = P + (j + (ROW16 ? 2 * kh : kh)) * kPicPitch;
                 const uint2 lo = *(const u2_a4 *)q, hi = *(const u2_a4 *)(q + 2);
                 fb[j] = v4i{(int)lo.x, (int)lo.y, (int)hi.x, (int)hi.y};
             }
@@ -154,18 +158,18 @@ __global__ __launch_bounds__(256, 4) void conv_pic_kernel(const ConvArgs a, cons
         };
         // two kernel rows per round: each row's fragments arrive during the previous row's MFMAs, in alternating registers
         fetch_frags(af, bf, 0);
-        if (1 < a.KH) fetch_frags(afn, bfn, 1);
+        if (1 < nblk) fetch_frags(afn, bfn, 1);
 #pragma unroll
         for (int c = 0; c < CG; ++c)
 #pragma unroll
             for (int j = 0; j < 2; ++j) acc[c][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[c], bf[j], bias[c], 0, 0, 0);
-        if (2 < a.KH) fetch_frags(af, bf, 2);
-        if (1 < a.KH) multiply(afn, bfn);
-        for (int kh = 2; kh < a.KH; kh += 2) {
-            if (kh + 1 < a.KH) fetch_frags(afn, bfn, kh + 1);
+        if (2 < nblk) fetch_frags(af, bf, 2);
+        if (1 < nblk) multiply(afn, bfn);
+        for (int kh = 2; kh < nblk; kh += 2) {
+            if (kh + 1 < nblk) fetch_frags(afn, bfn, kh + 1);
             multiply(af, bf);
-            if (kh + 2 < a.KH) fetch_frags(af, bf, kh + 2);
-            if (kh + 1 < a.KH) multiply(afn, bfn);
+            if (kh + 2 < nblk) fetch_frags(af, bf, kh + 2);
+            if (kh + 1 < nblk) multiply(afn, bfn);
         }
         mfma_drain(acc);
         const int ox = ox0 + col;
@@ -189,8 +193,7 @@ __global__ __launch_bounds__(256, 4) void conv_pic_kernel(const ConvArgs a, cons
 }
 
 // a: a small-cin layer's arguments on the ORIGINAL picture (H, W, Cin, in_cs, KH, KW, pads, Ho, Wo as given; the
-// packed weights in the small-cin order with 32-byte kernel rows).  The caller has checked: stride 1, cin <= 4, kernel
-// 5 to 8 wide and at most 8 high, 32 or 64 output channels, unsigned 8-bit output with 16-byte aligned pixels, no skip
+// packed weights in the small-cin order).  The caller has checked: stride 1, cin <= 4, kernel at most 8 wide and high, 32 or 64 output channels, unsigned 8-bit output with 16-byte aligned pixels, no skip
 // operand, per-layer requantisation, input re-normalised by XOR or not at all.
 hipError_t launch_conv_pic(const ConvArgs &a, hipStream_t st)
 {
@@ -205,13 +208,19 @@ hipError_t launch_conv_pic(const ConvArgs &a, hipStream_t st)
     g.patch_cols = kPicTW + a.KW - 1;
     g.div_tpi = make_fast_div((unsigned)g.tiles_per_img);
     g.div_tx = make_fast_div((unsigned)g.tiles_x);
-    if (a.x_bytes < 4 || a.KH > 8 || a.KW > 8 || (a.Cout != 32 && a.Cout != 64) || a.ksteps != (a.KH * 32 + 63) / 64)
+    const bool row16 = a.KW <= 4;
+    if (a.x_bytes < 4 || a.KH > 8 || a.KW > 8 || (a.Cout != 32 && a.Cout != 64) || a.ksteps != (a.KH * (row16 ? 16 : 32) + 63) / 64)
         return hipErrorInvalidValue;
     const size_t lds_bytes = (size_t)(a.Cout / 32) * a.ksteps * kChunkBytes + 2 * (size_t)kPicWords * 4 + (size_t)a.Cout * 4;
     const int slots = 256 * 4;
     const dim3 grid((unsigned)(8 * g.per_xcd < slots ? 8 * g.per_xcd : slots)), block(256);
-    if (a.Cout == 64) hipLaunchKernelGGL(conv_pic_kernel<2>, grid, block, lds_bytes, st, a, g);
-    else hipLaunchKernelGGL(conv_pic_kernel<1>, grid, block, lds_bytes, st, a, g);
+    if (a.Cout == 64) {
+        if (row16) hipLaunchKernelGGL((conv_pic_kernel<2, true>), grid, block, lds_bytes, st, a, g);
+        else hipLaunchKernelGGL((conv_pic_kernel<2, false>), grid, block, lds_bytes, st, a, g);
+    } else {
+        if (row16) hipLaunchKernelGGL((conv_pic_kernel<1, true>), grid, block, lds_bytes, st, a, g);
+        else hipLaunchKernelGGL((conv_pic_kernel<1, false>), grid, block, lds_bytes, st, a, g);
+    }
     return hipGetLastError();
 }
 

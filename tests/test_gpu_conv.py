@@ -582,11 +582,13 @@ def test_two_dimensional_tile_kernel_for_few_channels(shape):
         B.icnn_set_tuning("reset")
 
 
-# ---- a picture's first layer at stride 1 (cin <= 4, kernel 5 to 8 wide, 32 or 64 channels, 8-bit output) runs straight
+# ---- a picture's first layer at stride 1 (cin <= 4, kernel up to 8 wide, 32 or 64 channels, 8-bit output) runs straight
 # off the picture, without the padded copy.  Shapes: one to four channels, kernels 5 to 8, "same" and "valid" borders,
 # pictures smaller than a tile, of exactly whole tiles and with ragged tiles on both sides, several images.
 PICTURE_SHAPES = [(1, 40, 70, 1, 64, 5, 2), (2, 17, 33, 3, 32, 7, 3), (1, 24, 64, 4, 64, 8, 0), (1, 9, 31, 2, 64, 6, 2),
-                  (3, 8, 32, 1, 32, 5, 2), (1, 5, 5, 1, 64, 5, 2), (2, 64, 96, 1, 64, 5, 2)]
+                  (3, 8, 32, 1, 32, 5, 2), (1, 5, 5, 1, 64, 5, 2), (2, 64, 96, 1, 64, 5, 2),
+                  # kernels at most four pixels wide: two kernel rows per K block
+                  (1, 33, 31, 1, 64, 3, 1), (2, 20, 40, 3, 32, 4, 1), (1, 16, 64, 2, 64, 2, 0), (1, 8, 32, 4, 32, 1, 0), (1, 256, 256, 1, 64, 3, 1)]
 
 
 @pytest.mark.parametrize("shape", PICTURE_SHAPES, ids=lambda s: "x".join(map(str, s)))
