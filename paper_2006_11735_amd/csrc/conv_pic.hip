@@ -125,7 +125,6 @@ __global__ __launch_bounds__(256, 4) void conv_pic_kernel(const ConvArgs a, cons
     store_patch(0);
     __syncthreads();
     int buf = 0;
-    typedef uint2 u2_a4 __attribute__((aligned(4)));
     for (int v = blockIdx.x; valid(v); v += gridDim.x) {
         int n, oy0, ox0;
         tile_origin(v, n, oy0, ox0);
@@ -146,8 +145,7 @@ __global__ __launch_bounds__(256, 4) void conv_pic_kernel(const ConvArgs a, cons
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const uint32_t *q = P + (j + (ROW16 ? 2 * kh : kh)) * kPicPitch;
-                const uint2 lo = *(const u2_a4 *)q, hi = *(const u2_a4 *)(q + 2);
-                fb[j] = v4i{(int)lo.x, (int)lo.y, (int)hi.x, (int)hi.y};
+                fb[j] = v4i{(int)q[0], (int)q[1], (int)q[2], (int)q[3]};      // dword-aligned only: the column is any
             }
         };
         auto multiply = [&](const v4i (&fa)[CG], const v4i (&fb)[2]) {

@@ -65,8 +65,13 @@ constexpr int twin_frag(int f)
 }
 
 // kernel size, input channels (48 or 64), 32-channel chunks of the output (1 or 2), chunks of the twin layer (0: none, or 1),
-// tile rows per wave (2: tiles of 16 x 32 pixels; 1: 8 x 32, twice the tiles for pictures that have too few)
-template <int KS, int CIN, int NCH, int NB, int RPW>
+// tile rows per wave (2: tiles of 16 x 32 pixels; 1: 8 x 32, twice the tiles for pictures that have too few).
+// PIPE (3x3 layers with the weights in registers, outputs stored as unsigned bytes by the 32-bit requantisation form, no
+// skip operand; the host checks): a wave takes its two rows one after the other and deals the first row's epilogue out
+// between the second row's matrix instructions.  With a short K loop the epilogue's vector instructions take as long
+// as the loop, and because the barrier per tile keeps the two waves of a SIMD in step, both multiplied and then both
+// ran epilogues: 2.1 k clocks of matrix work, then 2.9 k of vector work, per tile.
+template <int KS, int CIN, int NCH, int NB, int RPW, bool PIPE>
 __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, const ConvArgs b, const PlaneArgs g)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the buffer-resource type exists in the device pass only
@@ -218,6 +223,76 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
         PLANE_TR(2);
         const uint8_t *const P = pbuf + buf * PATCH;
 
+        if constexpr (PIPE) {
+            static_assert(!PIPE || (AREG && RPW == 2 && NCH == 1), "the pipelined form is for register-resident 3x3 weights");
+            v16i accp[2], accq[2];                   // [row] of the layer and of its twin
+            accp[0] = accp[1] = bias[0];
+            if constexpr (NB > 0) accq[0] = accq[1] = biasB[0];
+            v4i Bf[2];
+            [[maybe_unused]] v4i ABf[2];
+            auto fetch1 = [&](auto f_tag, auto j_tag) {
+                constexpr int f = decltype(f_tag)::value, j = decltype(j_tag)::value, S = f & 1;
+                constexpr int P0 = 2 * f, P1 = 2 * f + 1;
+                constexpr int T0 = P0 / PPT < KS * KS ? P0 / PPT : KS * KS - 1, T1 = P1 / PPT < KS * KS ? P1 / PPT : KS * KS - 1;
+                if constexpr (NB > 0 && twin_frag<KS, CIN>(f) >= 0) ABf[S] = *(const v4i *)(wlaneB + twin_frag<KS, CIN>(f) * 1024);
+                if constexpr (CIN == 64) {
+                    constexpr int DY = T0 / KS, DX = T0 % KS, KK = (P0 % PPT) / 2;
+                    Bf[S] = *(const v4i *)(P + ex[DX][KK] + (j + DY) * ROWB);
+                } else {
+                    constexpr int O0 = (T0 / KS) * ROWB + (T0 % KS) * CIN + (P0 % PPT) * 16;
+                    constexpr int O1 = (T1 / KS) * ROWB + (T1 % KS) * CIN + (P1 % PPT) * 16;
+                    Bf[S] = *(const v4i *)(P + lin + (half ? O1 : O0) + j * ROWB);
+                }
+            };
+            // one K step of row j; g = its position among the 2 F steps of the tile (the next patch's copies are spread over them)
+            auto step1 = [&](auto f_tag, auto j_tag) {
+                constexpr int f = decltype(f_tag)::value, j = decltype(j_tag)::value, g2 = j * F + f;
+                if constexpr (f + 1 < F) fetch1(std::integral_constant<int, f + 1>{}, j_tag);
+                constexpr int EVERY = 2 * F / CPW;
+                if constexpr (g2 % EVERY == 0 && g2 / EVERY < CPW) {
+                    if (more) issue_copy(std::integral_constant<int, g2 / EVERY>{}, nbase, ny0, nx0, buf ^ 1);
+                }
+                accp[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wreg[0][f], Bf[f & 1], accp[j], 0, 0, 0);
+                if constexpr (NB > 0 && twin_frag<KS, CIN>(f) >= 0)
+                    accq[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ABf[f & 1], Bf[f & 1], accq[j], 0, 0, 0);
+            };
+            fetch1(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+            static_for<F>([&](auto f_tag) { step1(f_tag, std::integral_constant<int, 0>{}); });
+            mfma_drain(accp[0]);
+            if constexpr (NB > 0) mfma_drain(accq[0]);
+            // the second row; the first row's 16 (+ 16) outputs are requantised a few at a time behind its matrix instructions
+            int wa[4] = {0, 0, 0, 0};
+            [[maybe_unused]] int wb[4] = {0, 0, 0, 0};
+            const v4i none = {0, 0, 0, 0};
+            fetch1(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{});
+            static_for<F>([&](auto f_tag) {
+                constexpr int f = decltype(f_tag)::value;
+                step1(f_tag, std::integral_constant<int, 1>{});
+                constexpr int NOUT = 16 + 16 * NB, LO = f * NOUT / F, HI = (f + 1) * NOUT / F;
+                constexpr int A0 = LO < 16 ? LO : 16, A1 = HI < 16 ? HI : 16;
+                if constexpr (A1 > A0) epilogue_rq24_slice<0, A0, A1 - A0>(a, accp[0], none, wa);
+                if constexpr (NB > 0 && HI > 16) {
+                    constexpr int B0 = LO > 16 ? LO - 16 : 0, B1 = HI - 16;
+                    if constexpr (B1 > B0) epilogue_rq24_slice<0, B0, B1 - B0>(b, accq[0], none, wb);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            const int co0 = half * 16;
+            {
+                const size_t p = (size_t)((n * a.H + y0 + 2 * wave) * a.W + x0 + col);
+                if (co0 < a.Cout) *(v4i *)((uint8_t *)a.out + p * a.out_cs + a.out_co + co0) = v4i{wa[0], wa[1], wa[2], wa[3]};
+                if constexpr (NB > 0)
+                    if (co0 < b.Cout) *(v4i *)((uint8_t *)b.out + p * b.out_cs + b.out_co + co0) = v4i{wb[0], wb[1], wb[2], wb[3]};
+            }
+            mfma_drain(accp[1]);
+            if constexpr (NB > 0) mfma_drain(accq[1]);
+            {
+                const size_t p = (size_t)((n * a.H + y0 + 2 * wave + 1) * a.W + x0 + col);
+                if (co0 < a.Cout) *(v4i *)((uint8_t *)a.out + p * a.out_cs + a.out_co + co0) = epilogue_bytes16<0, 3>(a, accp[1], none);
+                if constexpr (NB > 0)
+                    if (co0 < b.Cout) *(v4i *)((uint8_t *)b.out + p * b.out_cs + b.out_co + co0) = epilogue_bytes16<0, 3>(b, accq[1], none);
+            }
+        } else {
         v16i acc[RPW][NCH][1];
 #pragma unroll
         for (int j = 0; j < RPW; ++j)
@@ -316,6 +391,7 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
                 }
             }
         });
+        }
         PLANE_TR(4);
         asm volatile("" ::: "memory");
         ICNN_WAIT_VMCNT(0);                          // the next tile's patch has landed (this wave's copies of it)
@@ -369,7 +445,7 @@ bool conv_plane_applies(const ConvArgs &a)
     return plane_rpw(a) != 0;
 }
 
-template <int KS, int CIN, int NCH, int NB = 0, int RPW = 2>
+template <int KS, int CIN, int NCH, int NB = 0, int RPW = 2, bool PIPE = false>
 static hipError_t launch_plane(const ConvArgs &a, const ConvArgs &b, hipStream_t st)
 {
     PlaneArgs g;
@@ -386,7 +462,7 @@ static hipError_t launch_plane(const ConvArgs &a, const ConvArgs &b, hipStream_t
     constexpr int KSTEPS = (KS * KS * CIN + 63) / 64;
     constexpr int KSTEPSB = NB ? ((KS - 2) * (KS - 2) * CIN + 63) / 64 : 0;
     const size_t lds_bytes = (size_t)(NCH * KSTEPS + NB * KSTEPSB) * kChunkBytes + 2 * (size_t)NCOPY * 1024;
-    const auto kernel = conv_plane_kernel<KS, CIN, NCH, NB, RPW>;
+    const auto kernel = conv_plane_kernel<KS, CIN, NCH, NB, RPW, PIPE>;
     if (lds_bytes > 64 * 1024) {
         const hipError_t e = allow_large_lds((const void *)kernel);
         if (e != hipSuccess) return e;
@@ -396,6 +472,13 @@ static hipError_t launch_plane(const ConvArgs &a, const ConvArgs &b, hipStream_t
     return hipGetLastError();
 }
 
+// what the pipelined instantiations assume of a layer: unsigned bytes by the 32-bit requantisation form, whole groups of
+// 16 channels, 16-byte stores, no skip operand
+static bool plane_pipe_ok(const ConvArgs &a)
+{
+    return a.epi_vec && a.out_mode <= 1 && a.res_mode == 0 && (a.Cout & 15) == 0 && a.rq24 && !g_tuning.plane_no_pipe;
+}
+
 hipError_t launch_conv_plane(const ConvArgs &a, hipStream_t st)
 {
     if (!plane_shape_ok(a)) return hipErrorInvalidValue;
@@ -403,6 +486,7 @@ hipError_t launch_conv_plane(const ConvArgs &a, hipStream_t st)
     if (rpw == 0) return hipErrorInvalidValue;
     if (a.KH == 5) return launch_plane<5, 64, 1>(a, a, st);
     if (a.Cin == 64 && rpw == 1) return nch == 1 ? launch_plane<3, 64, 1, 0, 1>(a, a, st) : launch_plane<3, 64, 2, 0, 1>(a, a, st);
+    if (nch == 1 && plane_pipe_ok(a)) return a.Cin == 64 ? launch_plane<3, 64, 1, 0, 2, true>(a, a, st) : launch_plane<3, 48, 1, 0, 2, true>(a, a, st);
     if (a.Cin == 64) return nch == 1 ? launch_plane<3, 64, 1>(a, a, st) : launch_plane<3, 64, 2>(a, a, st);
     return nch == 1 ? launch_plane<3, 48, 1>(a, a, st) : launch_plane<3, 48, 2>(a, a, st);
 }
@@ -422,6 +506,7 @@ hipError_t launch_conv_plane_twin(const ConvArgs &a, const ConvArgs &b, hipStrea
 {
     if (!conv_plane_twin_ok(a, b)) return hipErrorInvalidValue;
     if (a.KH == 5) return launch_plane<5, 64, 1, 1>(a, b, st);
+    if (a.Cin == 48 && plane_pipe_ok(a) && plane_pipe_ok(b)) return launch_plane<3, 48, 1, 1, 2, true>(a, b, st);
     return a.Cin == 64 ? launch_plane<3, 64, 1, 1>(a, b, st) : launch_plane<3, 48, 1, 1>(a, b, st);
 }
 

@@ -167,6 +167,7 @@ struct Tuning {
     int halo_always = 0;   // patch-resident kernel also with several tiles per workgroup and short K loops
     int no_stream = 0;     // single-channel 3x3 layers: lane-group kernel instead of the streaming one
     int no_plane = 0;      // keep few-channel layers on large pictures off the kernel with two-dimensional tiles
+    int plane_no_pipe = 0; // that kernel without the instantiations that deal a row's epilogue out between matrix instructions
     int plane_always = 0;  // that kernel for every layer whose shape it accepts
     int no_pic = 0;        // keep stride-1 first layers (cin <= 4) on the padded copy + tile kernel
     int no_deep = 0;       // keep deep 3x3 layers on few pixels off the kernel whose waves split the K axis

@@ -564,12 +564,14 @@ def test_two_dimensional_tile_kernel_for_few_channels(shape):
         assert (got == want).all()
         sigma = 37.0 * 74 * (k * k * cin) ** 0.5
         mul = max(1, int(round(127 / (3.0 * sigma) * (1 << 25))))
-        got, want = both(x, wt, b, stride=stride, pad=pad, mul=mul, shift=25)
-        assert (got == want).all() and want.max() == 127 and want.min() == 0
-        # written at a channel offset of a wider buffer (a branch of a concatenation), canary bytes around it
-        canvas = rnd(10).integers(0, 256, size=(n, h, w, cout + 48), dtype=np.uint8)
-        got, want = both(x, wt, b, stride=stride, pad=pad, mul=mul, shift=25, out=canvas, out_c_offset=32)
-        assert (got == want).all()
+        for no_pipe in (0, 1):        # with and without the instantiations that pipeline the epilogue (where they exist)
+            B.icnn_set_tuning("plane_no_pipe", no_pipe)
+            got, want = both(x, wt, b, stride=stride, pad=pad, mul=mul, shift=25)
+            assert (got == want).all() and want.max() == 127 and want.min() == 0
+            # written at a channel offset of a wider buffer (a branch of a concatenation), canary bytes around it
+            canvas = rnd(10).integers(0, 256, size=(n, h, w, cout + 48), dtype=np.uint8)
+            got, want = both(x, wt, b, stride=stride, pad=pad, mul=mul, shift=25, out=canvas, out_c_offset=32)
+            assert (got == want).all()
         # a skip operand joined before requantisation, and one added after it (the regression output's form)
         r = rnd(5).integers(0, 128, size=(n, h, w, cout), dtype=np.uint8)
         got, want = both(x, wt, b, stride=stride, pad=pad, mul=mul, shift=25, res=r, res_mode="pre", res_mul=int(3.0 * sigma / 127), res_shift=0)

@@ -80,6 +80,16 @@ def test_twin_branches_match_two_layers(case):
     assert want[..., oa:oa + ca].max() == 127 and want[..., ob:ob + cb].max() == 127 and want.min() == 0
 
 
+def test_twin_without_the_pipelined_epilogue():
+    from paper_2006_11735_amd import binding as B
+    B.icnn_set_tuning("plane_no_pipe", 1)
+    try:
+        got, want = run_twin(12, 2, 32, 64, 48, 3, 16, 32)
+        assert (got == want).all()
+    finally:
+        B.icnn_set_tuning("reset")
+
+
 def test_twin_in_a_wider_buffer_and_from_a_wider_input():
     got, want = run_twin(8, 1, 32, 64, 64, 5, 32, 16, off_a=16, cbuf=96, xbuf=80)
     assert (got == want).all()
