@@ -342,7 +342,7 @@ int iconv2d_pair_brelu(const icnn_conv_desc *c3, const void *t, const void *w3_p
  * is a device pointer; ya and yb may be the same buffer (the descriptors' out_c_stride / out_c_offset place each
  * branch), the two channel ranges must not overlap, and neither output may overlap x.  Shapes it takes: stride 1,
  * "same" padding, ca 5x5 with 64 input channels and cb 3x3, or ca 3x3 with 48 or 64 input channels and cb 1x1; at
- * most 32 output channels each; no skip operands; inputs ICNN_IN_U8_LE127; h a multiple of 16 and w of 32; x and
+ * most 32 output channels each; no skip operands; inputs ICNN_IN_U8_LE127; tensors below 2 GiB; x and
  * in_c_stride 16-byte aligned.  Anything else returns ICNN_E_UNSUPPORTED having launched nothing, and the caller issues
  * the two layers separately.
  */

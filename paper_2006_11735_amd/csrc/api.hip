@@ -745,7 +745,7 @@ int iconv2d_twin_brelu(const icnn_conv_desc *ca, const void *x, const void *wa_p
     if ((rc = fill_conv_args(cb, gb, x, wb_packed, bias_b, nullptr, yb, b))) return rc;
     if (!conv_plane_twin_ok(a, b))
         return fail(ICNN_E_UNSUPPORTED, "twin layers: a 5x5 layer of 64 channels beside a 3x3, or a 3x3 layer of 48 or 64 channels beside a 1x1, "
-                                        "stride 1, \"same\" padding, at most 32 output channels each, h a multiple of 16 and w of 32");
+                                        "stride 1, \"same\" padding, at most 32 output channels each, tensors below 2 GiB");
     return launched(launch_conv_plane_twin(a, b, (hipStream_t)stream), "iconv2d_twin_brelu");
 }
 

@@ -6,7 +6,8 @@
 // times, and on a picture 2560 pixels wide a run of 256 pixels shares no input rows with its own taps' neighbours, so
 // the patch-resident kernel of conv_halo.hip does not apply either.  Here the tile is two-dimensional:
 //
-//   tile     16 rows x 32 columns of one picture; a pixel group of 32 is one tile row, wave w owns rows 2w and 2w + 1
+//   tile     16 rows x 32 columns of one picture (hanging over its right and bottom edges where the picture is no multiple
+//            of that: those outputs are computed and dropped); a pixel group of 32 is one tile row, wave w owns rows 2w and 2w + 1
 //            (8 rows x 32 columns, one row per wave, for 3x3 layers of 64 channels on pictures with too few tiles)
 //   patch    the (16 + k - 1) x (32 + k - 1) input pixels under the tile, all channels, in LDS (zeros outside the picture:
 //            the layer's padding), double-buffered: the next tile's patch travels by direct-to-LDS copies while this
@@ -278,7 +279,8 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
                 __builtin_amdgcn_sched_barrier(0);
             });
             const int co0 = half * 16;
-            {
+            const bool colok = x0 + col < a.W;        // tiles may hang over the picture's right and bottom edges
+            if (colok && y0 + 2 * wave < a.H) {
                 const size_t p = (size_t)((n * a.H + y0 + 2 * wave) * a.W + x0 + col);
                 if (co0 < a.Cout) *(v4i *)((uint8_t *)a.out + p * a.out_cs + a.out_co + co0) = v4i{wa[0], wa[1], wa[2], wa[3]};
                 if constexpr (NB > 0)
@@ -286,7 +288,7 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
             }
             mfma_drain(accp[1]);
             if constexpr (NB > 0) mfma_drain(accq[1]);
-            {
+            if (colok && y0 + 2 * wave + 1 < a.H) {
                 const size_t p = (size_t)((n * a.H + y0 + 2 * wave + 1) * a.W + x0 + col);
                 if (co0 < a.Cout) *(v4i *)((uint8_t *)a.out + p * a.out_cs + a.out_co + co0) = epilogue_bytes16<0, 3>(a, accp[1], none);
                 if constexpr (NB > 0)
@@ -360,21 +362,23 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
             constexpr int j = decltype(j_tag)::value;
             mfma_drain(acc[j]);
             // a tile row's 32 pixels are consecutive pixels of the output tensor
+            // (tiles may hang over the picture's bottom and right edges: those rows and columns are computed and dropped)
             const int pix_row = (n * a.H + y0 + RPW * wave + j) * a.W + x0;
+            const bool rowok = y0 + RPW * wave + j < a.H, pixok = rowok && x0 + col < a.W;
             if (quick) {
                 const size_t p = (size_t)(pix_row + col);
                 static_for<NCH>([&](auto c_tag) {
                     constexpr int c = decltype(c_tag)::value;
                     const int co0 = c * 32 + half * 16;
-                    if (co0 < a.Cout) {
+                    if (co0 < a.Cout && pixok) {
                         v4i r8 = {0, 0, 0, 0};
                         if (has_res) r8 = *(const v4i *)((const uint8_t *)a.res + p * a.res_cs + co0);
                         const v4i w = has_res ? epilogue_bytes16<1>(a, acc[j][c][0], r8) : epilogue_bytes16<0>(a, acc[j][c][0], r8);
                         *(v4i *)((uint8_t *)a.out + p * a.out_cs + a.out_co + co0) = w;
                     }
                 });
-            } else {
-                epilogue_tiles<NCH, 1>(a, acc[j], 0, pix_row, lane);
+            } else if (rowok) {
+                epilogue_tiles<NCH, 1>(a, acc[j], 0, pixok ? pix_row : a.M, lane);      // a pixel index of M or more is skipped
             }
             if constexpr (NB > 0) {
                 mfma_drain(accB[j]);
@@ -383,11 +387,11 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
                     static_for<NB>([&](auto c_tag) {
                         constexpr int c = decltype(c_tag)::value;
                         const int co0 = c * 32 + half * 16;
-                        if (co0 < b.Cout)
+                        if (co0 < b.Cout && pixok)
                             *(v4i *)((uint8_t *)b.out + p * b.out_cs + b.out_co + co0) = epilogue_bytes16<0>(b, accB[j][c][0], v4i{0, 0, 0, 0});
                     });
-                } else {
-                    epilogue_tiles<NB, 1>(b, accB[j], 0, pix_row, lane);
+                } else if (rowok) {
+                    epilogue_tiles<NB, 1>(b, accB[j], 0, pixok ? pix_row : b.M, lane);
                 }
             }
         });
@@ -418,23 +422,26 @@ static bool plane_shape_ok(const ConvArgs &a)
 {
     if (a.KH != a.KW || (a.KH != 3 && a.KH != 5) || a.sh != 1 || a.sw != 1 || a.ph != a.KH / 2 || a.pw != a.KW / 2) return false;
     if ((a.Cin != 48 && a.Cin != 64) || a.in_cs % 16 || ((uintptr_t)a.x & 15) || a.in_xor || a.frag_xor || a.pc) return false;
-    if (a.W % kPlaneTW || a.H % 8 || a.Ho != a.H || a.Wo != a.W || a.x_bytes >= 0x7fffff00u) return false;
+    if (a.Ho != a.H || a.Wo != a.W || a.x_bytes >= 0x7fffff00u) return false;
     if (a.ksteps != (a.KH * a.KW * a.Cin + 63) / 64) return false;
     const int nch = plane_nch(a);
     // the instantiations that exist (launch_conv_plane)
-    if (a.KH == 5) return a.Cin == 64 && nch == 1 && a.H % 16 == 0;
-    // tiles of 8 rows exist for 3x3 layers of 64 channels only
-    return nch <= 2 && (a.H % 16 == 0 || a.Cin == 64);
+    if (a.KH == 5) return a.Cin == 64 && nch == 1;
+    return nch <= 2;
 }
 
 // Tile rows per wave: 2 (tiles of 16 x 32 pixels) where the picture gives every compute unit several tiles, else 1 for
 // the 3x3 layers of 64 channels; 0: the layer is not worth this kernel.
 static int plane_rpw(const ConvArgs &a)
 {
-    const long long tiles8 = (long long)a.N * (a.H / 8) * (a.W / kPlaneTW);
-    if (a.H % 16 == 0 && (tiles8 >= 2048 || (g_tuning.plane_always && !(a.KH == 3 && a.Cin == 64 && tiles8 < 512)))) return 2;
+    const int tx = (a.W + kPlaneTW - 1) / kPlaneTW;
+    const long long tiles8 = (long long)a.N * ((a.H + 7) / 8) * tx;
+    // tiles hang over the right and bottom edges of pictures that are no multiples of them: not where that is more than
+    // a quarter of the work
+    if (!g_tuning.plane_always && (a.W * 4 < tx * kPlaneTW * 3 || a.H < 8)) return 0;
+    if (tiles8 >= 2048 || (g_tuning.plane_always && !(a.KH == 3 && a.Cin == 64 && tiles8 < 512))) return 2;
     if (a.KH == 3 && a.Cin == 64 && (tiles8 >= 192 || g_tuning.plane_always)) return 1;
-    return a.H % 16 == 0 && g_tuning.plane_always ? 2 : 0;
+    return g_tuning.plane_always ? 2 : 0;
 }
 
 bool conv_plane_applies(const ConvArgs &a)
@@ -449,8 +456,8 @@ template <int KS, int CIN, int NCH, int NB = 0, int RPW = 2, bool PIPE = false>
 static hipError_t launch_plane(const ConvArgs &a, const ConvArgs &b, hipStream_t st)
 {
     PlaneArgs g;
-    g.tiles_x = a.W / kPlaneTW;
-    g.tiles_per_img = g.tiles_x * (a.H / (8 * RPW));
+    g.tiles_x = (a.W + kPlaneTW - 1) / kPlaneTW;
+    g.tiles_per_img = g.tiles_x * ((a.H + 8 * RPW - 1) / (8 * RPW));
     const long long tiles = (long long)g.tiles_per_img * a.N;
     if (tiles < 1 || tiles > 0x7ffffff0LL) return hipErrorInvalidValue;
     g.n_tiles = (int)tiles;
@@ -495,7 +502,7 @@ hipError_t launch_conv_plane(const ConvArgs &a, hipStream_t st)
 // smaller (3x3 beside 5x5, 1x1 beside 3x3), "same" padding, at most 32 output channels, no skip operands.
 bool conv_plane_twin_ok(const ConvArgs &a, const ConvArgs &b)
 {
-    if (!plane_shape_ok(a) || a.H % 16 || plane_nch(a) != 1 || a.res_mode != 0 || b.res_mode != 0) return false;
+    if (!plane_shape_ok(a) || plane_nch(a) != 1 || a.res_mode != 0 || b.res_mode != 0) return false;
     if (b.x != a.x || b.N != a.N || b.H != a.H || b.W != a.W || b.Cin != a.Cin || b.in_cs != a.in_cs || b.Ho != a.H || b.Wo != a.W) return false;
     if (b.KH != a.KH - 2 || b.KW != a.KW - 2 || b.sh != 1 || b.sw != 1 || b.ph != b.KH / 2 || b.pw != b.KW / 2) return false;
     if (b.in_xor || b.frag_xor || b.pc || b.Cout > 32 || b.ksteps != (b.KH * b.KW * b.Cin + 63) / 64) return false;

@@ -550,7 +550,12 @@ def test_3x3_kernel_whose_waves_split_the_k_axis(shape):
 # channel tails (16, 40, 48 outputs); two images; pictures whose height or tile count selects the tiles of 8 rows.
 PLANE_SHAPES = [(1, 32, 96, 64, 32, 5, 1, 2), (1, 48, 64, 64, 16, 3, 1, 1), (2, 32, 64, 64, 64, 3, 1, 1), (1, 32, 64, 48, 16, 3, 1, 1),
                 (1, 32, 64, 48, 40, 3, 1, 1), (3, 16, 32, 64, 32, 3, 1, 1), (1, 80, 160, 64, 16, 3, 1, 1), (1, 64, 96, 64, 32, 5, 1, 2),
-                (1, 24, 64, 64, 64, 3, 1, 1), (2, 8, 96, 64, 16, 3, 1, 1), (1, 64, 64, 64, 64, 3, 1, 1)]     # tiles of 8 rows
+                (1, 24, 64, 64, 64, 3, 1, 1), (2, 8, 96, 64, 16, 3, 1, 1), (1, 64, 64, 64, 64, 3, 1, 1),     # tiles of 8 rows
+                # 3x3 layers of 64 channels with enough tiles for the 16-row form
+                (1, 128, 1024, 64, 16, 3, 1, 1), (1, 136, 1000, 64, 64, 3, 1, 1),
+                # pictures that are no multiples of the tile: tiles hang over the right and bottom edges
+                (1, 56, 56, 64, 64, 3, 1, 1), (2, 30, 70, 48, 16, 3, 1, 1), (1, 37, 45, 64, 32, 5, 1, 2), (1, 20, 100, 64, 16, 3, 1, 1),
+                (1, 9, 33, 48, 40, 3, 1, 1)]
 
 
 @pytest.mark.parametrize("shape", PLANE_SHAPES, ids=lambda s: "x".join(map(str, s)))

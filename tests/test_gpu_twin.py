@@ -69,6 +69,8 @@ TWINS = [
     (1, 32, 96, 64, 3, 16, 16, 0, 16),       # 3x3 beside 1x1 on 64 channels
     (1, 64, 64, 64, 5, 24, 8, 8, 32),        # channel counts that are no multiples of 16, a gap before the first branch
     (1, 32, 32, 48, 3, 32, 32, 32, 0),       # the smaller kernel's channels first
+    (1, 37, 70, 64, 5, 32, 16, 0, 32),       # pictures that are no multiples of the tile
+    (2, 21, 45, 48, 3, 16, 32, 0, 16),
 ]
 
 
