@@ -515,7 +515,7 @@ def main():
         "conv_tops": conv_tops,
         "pct_int8_mfma_peak": 100 * conv_tops / INT8_MFMA_PEAK_TOPS,
         "whole_step_tops": conv_ops / (ms_per_step * 1e-3) / 1e12,
-        "roofline": {"kernel": "conv kernels (all %d conv launches of a step: conv_dlds / conv_halo / conv_deep / conv_dual / conv_block / conv_block64 / conv_pair / conv_stem_pool, every tile shape)" % n_conv,
+        "roofline": {"kernel": "conv kernels (all %d conv launches of a step: conv_dlds / conv_halo / conv_deep / conv_plane / conv_pic / conv_narrow / conv_dual / conv_block / conv_block64 / conv_pair / conv_stem_pool, every tile shape)" % n_conv,
                      "bound": "mfma", "achieved": conv_tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": conv_tops / INT8_MFMA_PEAK_TOPS, "traffic": traffic, "traffic_stale": traffic_stale,
                      "peak_measured": peak_tops, "frac_of_peak_measured": conv_tops / peak_tops,
