@@ -121,8 +121,10 @@ __global__ __launch_bounds__(256, 4) void conv_pic_kernel(const ConvArgs a, cons
         }
     };
 
-    fetch_patch(blockIdx.x);
-    store_patch(0);
+    if (valid(blockIdx.x)) {                 // (a workgroup whose first slot is a padding slot has no tile at all)
+        fetch_patch(blockIdx.x);
+        store_patch(0);
+    }
     __syncthreads();
     int buf = 0;
     for (int v = blockIdx.x; valid(v); v += gridDim.x) {
