@@ -150,7 +150,9 @@ int iconv2d_out_hw(const icnn_conv_desc *desc, int32_t *ho, int32_t *wo);
  * or the partial sums of a layer whose K axis is split over workgroups.  The caller zero-fills a workspace once after
  * allocating it (its first 4096 bytes are counters that every call leaves at zero); one workspace of the largest size
  * may serve all layers that run one after the other on a stream.  Layers that split K also run without a workspace
- * (NULL): then the K axis stays whole. */
+ * (NULL): then the K axis stays whole.  A layer with cin <= 4 always needs its workspace passed, although the
+ * stride-1 forms that the library convolves straight off the picture (8-bit output, 32 or 64 channels, kernel up to
+ * 8 x 8, no skip operand) leave it untouched. */
 int iconv2d_workspace_bytes(const icnn_conv_desc *desc, size_t *bytes);
 
 /* Bytes of the library's packed weight format for this layer. */
