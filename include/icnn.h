@@ -127,6 +127,7 @@ const char *icnn_last_error(void);
  *   "no_narrow", "no_fc", "no_halo", "no_stream", "no_block64", "no_deep", "no_plane", "no_pic"   1 keeps layers off the respective special kernel
  *   "halo_tile"   0 library's choice; 1 = 128 x 128, 2 = 64 x 256 tiles of the patch-resident 3x3 kernel
  *   "halo_always" 1 lets the patch-resident kernel take layers with several tiles per workgroup
+ *   "block_any_form" 1 keeps fused bottleneck blocks on the instantiation that holds every epilogue form
  *   "plane_no_pipe" 1 keeps that kernel off its instantiations with the software-pipelined epilogue
  *   "plane_always" 1 lets the kernel with two-dimensional tiles (few channels, large pictures) take every layer it accepts
  *   "deep_always" 1 lets the 3x3 kernel whose waves split the K axis take every layer whose shape it accepts

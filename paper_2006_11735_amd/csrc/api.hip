@@ -141,7 +141,7 @@ int icnn_set_tuning(const char *name, int32_t value)
         {"no_halo", &Tuning::no_halo, 0, 1},     {"halo_tile", &Tuning::halo_tile, 0, 2},
         {"halo_always", &Tuning::halo_always, 0, 1}, {"no_stream", &Tuning::no_stream, 0, 1},
         {"ksplit", &Tuning::ksplit, 0, 8}, {"no_block64", &Tuning::no_block64, 0, 1},
-        {"no_plane", &Tuning::no_plane, 0, 1}, {"no_pic", &Tuning::no_pic, 0, 1}, {"plane_no_pipe", &Tuning::plane_no_pipe, 0, 1}, {"plane_always", &Tuning::plane_always, 0, 1},
+        {"no_plane", &Tuning::no_plane, 0, 1}, {"no_pic", &Tuning::no_pic, 0, 1}, {"block_any_form", &Tuning::block_any_form, 0, 1}, {"plane_no_pipe", &Tuning::plane_no_pipe, 0, 1}, {"plane_always", &Tuning::plane_always, 0, 1},
         {"no_deep", &Tuning::no_deep, 0, 1}, {"deep_always", &Tuning::deep_always, 0, 1}, {"deep_plain_walk", &Tuning::deep_plain_walk, 0, 1},
     };
     if (!strcmp(name, "reset")) {

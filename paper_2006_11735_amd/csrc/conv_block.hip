@@ -50,7 +50,10 @@ __device__ unsigned long long g_blk_trace[4096];
 #define BLK_TR(k)
 #endif
 
-template <int MG>                    // MID / 32: 2 (two workgroups per compute unit) or 4
+// MG: MID / 32: 2 (two workgroups per compute unit) or 4.  RQ24: all three layers requantise by the 32-bit form and the
+// last one stores unsigned bytes with at most the plain 8-bit skip operand (the host checks; every calibrated layer of the
+// workloads): the kernel then holds that one epilogue form instead of every form of every layer (a fifth of the code).
+template <int MG, bool RQ24>
 __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const BlockArgs g, const ConvArgs a1, const ConvArgs a2,
                                                                            const ConvArgs a3)
 {
@@ -380,7 +383,7 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
                 int t[16];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) t[r] = acc[j][r];
-                v4i w = requant16_any(a1, t);
+                v4i w = RQ24 ? requant16<3>(a1, t) : requant16_any(a1, t);
                 if (!ok) w = v4i{0, 0, 0, 0};
                 const int piece = (co_in_stage & 63) >> 4;
                 *(v4i *)(abuf + (co_in_stage >> 6) * SLICE_A + row * 64 + (((piece ^ (row >> 2)) & 3) << 4)) = w;
@@ -453,7 +456,7 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
                 int t[16];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) t[r] = acc[j][r];
-                const v4i w = requant16_any(a2, t);      // slots beyond the tile hold values nobody stores
+                const v4i w = RQ24 ? requant16<3>(a2, t) : requant16_any(a2, t);      // slots beyond the tile hold values nobody stores
                 *(v4i *)(bbuf + (co_in_stage >> 6) * SLICE_B + b_slot_offset(q2_0 + 32 * j, (co_in_stage & 63) >> 4)) = w;
             });
         }
@@ -509,7 +512,13 @@ __global__ __launch_bounds__(512, MG == 2 ? 4 : 2) void conv_block_kernel(const 
                 }
                 BLK_TR(21);
                 mfma_drain(acc);
-                if (bytes3) {
+                if constexpr (RQ24) {
+                    static_for<TP2>([&](auto jc) {
+                        constexpr int j = decltype(jc)::value;
+                        const v4i w = fetch_res ? epilogue_bytes16<1, 3>(a3, acc[j], res8[j]) : epilogue_bytes16<0, 3>(a3, acc[j], res8[j]);
+                        if (ok3[j]) *(v4i *)((uint8_t *)a3.out + (size_t)p3[j] * a3.out_cs + a3.out_co + co0) = w;
+                    });
+                } else if (bytes3) {
                     // an 8-bit output whose skip operand, if any, is the 8-bit kind joined before requantisation: the short form
                     static_for<TP2>([&](auto jc) {
                         constexpr int j = decltype(jc)::value;
@@ -584,7 +593,11 @@ hipError_t launch_conv_block(const BlockArgs &g, const ConvArgs &a1, const ConvA
         hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, gx, a1, a2, a3);
         return hipGetLastError();
     };
-    return mid == 64 ? go(conv_block_kernel<2>) : go(conv_block_kernel<4>);
+    const bool res8 = a3.epi_vec && !(a3.Cout & 15) && a3.res_mode != 0 && a3.res_dtype != 2;       // res8_applies(a3)
+    const bool rq24 = a1.rq24 && a2.rq24 && a3.rq24 && a3.out_mode != 3 && a3.epi_mode / 4 != 2 && (a3.res_mode == 0 || res8) &&
+                      !g_tuning.block_any_form;
+    if (mid == 64) return rq24 ? go(conv_block_kernel<2, true>) : go(conv_block_kernel<2, false>);
+    return rq24 ? go(conv_block_kernel<4, true>) : go(conv_block_kernel<4, false>);
 }
 
 #ifdef ICNN_BLOCK_TRACE

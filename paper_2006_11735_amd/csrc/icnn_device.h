@@ -173,6 +173,7 @@ struct Tuning {
     int no_deep = 0;       // keep deep 3x3 layers on few pixels off the kernel whose waves split the K axis
     int deep_plain_walk = 0;   // that kernel with the tile order of the other kernels (measurement)
     int deep_always = 0;   // that kernel for every layer whose shape it accepts
+    int block_any_form = 0; // LDS-ring block kernel: the instantiation that holds every epilogue form, also where one form would do
     int no_block64 = 0;    // fused bottleneck blocks with 64 middle channels: the LDS-ring kernel instead of the register-resident one
     int ksplit = 0;        // 0 library's choice; 1 never split the K axis; 2..8 this split where it divides the K steps
 };

@@ -119,6 +119,20 @@ def test_fused_block_equals_three_layers(shape, ring):
     assert want.max() == 127 and want.min() == 0
 
 
+@pytest.mark.parametrize("mid,c", [(64, 128), (128, 512)])
+def test_fused_block_on_the_instantiation_that_holds_every_epilogue_form(mid, c):
+    # calibrated layers take the instantiation with the one 32-bit form; the other one must agree on them too
+    from paper_2006_11735_amd import binding as B
+    B.icnn_set_tuning("no_block64", 1)
+    B.icnn_set_tuning("block_any_form", 1)
+    try:
+        for kw in (dict(), dict(skip=None)):
+            got, want = run_block(11 + mid, 3, 14, 14, c, mid, **kw)
+            assert (got == want).all(), kw
+    finally:
+        B.icnn_set_tuning("reset")
+
+
 @pytest.mark.parametrize("mid,c", [(64, 128), (128, 256)])
 def test_fused_block_output_and_skip_modes(mid, c):
     for kw in (dict(skip=None), dict(skip="s32"), dict(c3_mode="raw_s32"), dict(c3_mode="linear_s8", skip=None),
