@@ -344,6 +344,9 @@ def test_narrow_output_layers(cout, geom):
     r32 = g.integers(-300000, 300000, size=(2, ho, wo, cout)).astype(np.int32)
     got, want = both(x, wt, b, stride=stride, pad=pad, mul=23187, shift=25, res=r32, res_mode="pre", res_mul=20011, res_shift=15)
     assert (got == want).all()
+    # an unsigned 8-bit skip operand joined before requantisation (the epilogue's 32-bit form), with a rounding shift
+    got, want = both(x, wt, b, stride=stride, pad=pad, mul=20050, shift=24, res=raw, res_mode="pre", res_mul=100003, res_shift=3)
+    assert (got == want).all() and want.max() > 0
     # int8 input, raw picture input (zero padding after the "- 128"), full-range unsigned input
     xs = g.integers(-128, 128, size=x.shape, dtype=np.int8)
     got, want = both(xs, wt, b, stride=stride, pad=pad, out_mode="linear_s8", mul=20050, shift=24)
