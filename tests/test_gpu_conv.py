@@ -624,6 +624,12 @@ def test_first_layer_straight_off_the_picture(shape):
     xw = rnd(12).integers(0, 256, size=(n, h, w, cin + 3), dtype=np.uint8)
     got, want = both(xw, wt, b, pad=pad, in_sub128=True, mul=mul, shift=25, cin=cin)
     assert (got == want).all()
+    # the other requantisation forms (a shift of 32: one high-word multiply; beyond 32: the general 64-bit form), a clamp
+    # with both ends inside the byte range, a low bound
+    for kw in (dict(mul=mul << 7, shift=32), dict(mul=mul << 10, shift=35), dict(mul=mul, shift=25, out_mode="clamp_u8", lo=5, hi=250),
+               dict(mul=mul, shift=25, bound_q=15)):
+        got_v, want_v = both(x, wt, b, pad=pad, in_sub128=True, **kw)
+        assert (got_v == want_v).all(), kw
     # the library's other path for the same layer gives the same bytes
     from paper_2006_11735_amd import binding as B
     B.icnn_set_tuning("no_pic", 1)
