@@ -46,13 +46,15 @@ def run_twin(seed, n, h, w, cin, ka, cout_a, cout_b, *, off_a=0, off_b=None, cbu
                      out_c_stride=cout_b if separate else cbuf, out_c_offset=0 if separate else off_b, mul=mb, shift=sb, bound_q=127)
     if mode_b == "clamp_u8":
         db.out_mode, db.lo, db.hi = B.ICNN_OUT_CLAMP_U8, 3, 200
+    if mode_b == "raw_s32":
+        db.out_mode = B.ICNN_OUT_RAW_S32
     packs = []
     for d, wt in ((da, wa), (db, wb)):
         pk = torch.zeros(B.iconv2d_packed_weight_bytes(d), dtype=torch.uint8, device="cuda:0")
         B.iconv2d_prepack_weights(d, dev(wt), pk)
         packs.append(pk)
     yd = dev(canvas)
-    yb = torch.zeros((n, h, w, cout_b), dtype=torch.uint8, device="cuda:0") if separate else yd
+    yb = torch.zeros((n, h, w, cout_b), dtype=torch.int32 if mode_b == "raw_s32" else torch.uint8, device="cuda:0") if separate else yd
     B.iconv2d_twin_brelu(da, dev(x), packs[0], dev(ba), yd, db, packs[1], dev(bb), yb)
     torch.cuda.synchronize()
     if separate:
@@ -104,6 +106,10 @@ def test_twin_with_outputs_of_their_own_and_a_clamped_branch():
     assert (ya == wa).all() and (yb == wb).all()
     got, want = run_twin(11, 1, 32, 64, 48, 3, 16, 32, mode_b="clamp_u8")
     assert (got == want).all()
+    # the smaller kernel's branch as raw accumulators (its own int32 buffer), beside a requantised branch
+    for shape in ((1, 32, 64, 64, 5, 32, 16), (2, 19, 40, 48, 3, 16, 32)):
+        (ya, yb), (wa, wb) = run_twin(13, *shape, separate=True, mode_b="raw_s32")
+        assert yb.dtype == np.int32 and (ya == wa).all() and (yb == wb).all()
 
 
 def test_twin_refuses_what_it_does_not_take():
