@@ -49,6 +49,34 @@ __device__ __forceinline__ void epilogue_slow(const ConvArgs &a, const v16i &acc
     }
 }
 
+// One output: y = accumulator with the bias in it, resraw = its skip operand as loaded (any kind), oo = its element index
+// in the output.  quick32 (wave-uniform; the caller checked a.out_mode != raw, a.rq_fast, and a.res_fast where there is a
+// skip operand): the same arithmetic in 32 bits.
+__device__ __forceinline__ void epilogue_one(const ConvArgs &a, int y, int resraw, size_t oo, bool quick32)
+{
+    if (quick32) {
+        int skip = 0;
+        if (a.res_mode != 0) skip = (int)(((uint32_t)resraw * (uint32_t)a.res_mul + (uint32_t)((1 << a.res_shift) >> 1)) >> a.res_shift);
+        const int ti = a.res_mode == 1 ? __builtin_elementwise_add_sat(y, skip) : y;
+        int q = (int)(((int64_t)ti * a.mul_hi + 0x80000000LL) >> 32);
+        if (a.res_mode == 2) q = __builtin_elementwise_add_sat(q, skip);       // the clamp below makes the saturation exact
+        ((uint8_t *)a.out)[oo] = (uint8_t)min(max(q, a.lo), a.hi);
+        return;
+    }
+    int64_t t = y;
+    int64_t skip = 0;
+    if (a.res_mode != 0) skip = rsr64((int64_t)resraw * a.res_mul, a.res_shift);
+    if (a.res_mode == 1) t += skip;
+    const int ti = sat32(t);
+    if (a.out_mode == 3) {
+        ((int32_t *)a.out)[oo] = ti;
+    } else {
+        int64_t q = rsr64((int64_t)ti * a.mul, a.shift);
+        if (a.res_mode == 2) q += skip;
+        ((uint8_t *)a.out)[oo] = (uint8_t)clampi64(q, a.lo, a.hi);
+    }
+}
+
 // min(max(x, lo), hi) as one instruction (the compiler only fuses the pair when it can prove lo <= hi);
 // at most one of the three operands may live in a scalar register
 __device__ __forceinline__ int med3_v0s(int x, int hi_s)

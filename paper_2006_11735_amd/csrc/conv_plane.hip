@@ -206,6 +206,12 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
     // pixel straight from epilogue_bytes16 (the general epilogue's dispatch costs as much as a 3x3 tile's K loop here)
     const bool quick = a.epi_vec && a.out_mode <= 1 && a.epi_mode / 4 != 2 && (a.Cout & 15) == 0;
     const bool has_res = a.res_mode != 0;
+    // One to four output channels (the regression networks' last layer): a lane of the first half holds them in its
+    // first accumulator registers; element-wise epilogue, in 32 bits where the layer's parameters allow, the skip
+    // operand fetched before the K loop (a load inside the epilogue would be waited for on the spot)
+    constexpr bool THIN_OK = NCH == 1 && NB == 0;        // (the twin instantiations have no registers to spare for it)
+    const bool thin = THIN_OK && a.Cout <= 4;
+    const bool thin32 = a.out_mode != 3 && a.rq_fast && (a.res_mode == 0 || a.res_fast);
     [[maybe_unused]] const bool quickB = NB && b.epi_vec && b.out_mode <= 1 && b.epi_mode / 4 == 0 && (b.Cout & 15) == 0;
 
     int buf = 0;
@@ -295,6 +301,17 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
                     if (co0 < b.Cout) *(v4i *)((uint8_t *)b.out + p * b.out_cs + b.out_co + co0) = epilogue_bytes16<0, 3>(b, accq[1], none);
             }
         } else {
+        [[maybe_unused]] int resv[RPW][THIN_OK ? 4 : 1] = {};
+        if (THIN_OK && thin && has_res && half == 0) {
+#pragma unroll
+            for (int j = 0; j < RPW; ++j)
+                if (y0 + RPW * wave + j < a.H && x0 + col < a.W) {
+                    const size_t ro = (size_t)((n * a.H + y0 + RPW * wave + j) * a.W + x0 + col) * a.res_cs;
+#pragma unroll
+                    for (int co = 0; co < 4; ++co)
+                        if (co < a.Cout) resv[j][THIN_OK ? co : 0] = load_elem(a.res, ro + co, a.res_dtype);
+                }
+        }
         v16i acc[RPW][NCH][1];
 #pragma unroll
         for (int j = 0; j < RPW; ++j)
@@ -365,7 +382,15 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
             // (tiles may hang over the picture's bottom and right edges: those rows and columns are computed and dropped)
             const int pix_row = (n * a.H + y0 + RPW * wave + j) * a.W + x0;
             const bool rowok = y0 + RPW * wave + j < a.H, pixok = rowok && x0 + col < a.W;
-            if (quick) {
+            if (thin) {
+                if (pixok && half == 0) {
+                    const size_t oo = (size_t)(pix_row + col) * a.out_cs + a.out_co;
+                    static_for<4>([&](auto co_tag) {
+                        constexpr int co = decltype(co_tag)::value;
+                        if (co < a.Cout) epilogue_one(a, acc[j][0][0][co], resv[j][THIN_OK ? co : 0], oo + co, thin32);
+                    });
+                }
+            } else if (quick) {
                 const size_t p = (size_t)(pix_row + col);
                 static_for<NCH>([&](auto c_tag) {
                     constexpr int c = decltype(c_tag)::value;

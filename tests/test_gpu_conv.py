@@ -328,6 +328,24 @@ def test_unsigned_full_range_worst_case_accumulator():
 def test_narrow_output_layers(cout, geom):
     """One to four output channels (a single one on a large map takes the dot-product kernels, streaming
     for 3x3 stride 1): every epilogue mode, every input kind."""
+    check_narrow_output_layer(cout, geom)
+
+
+@pytest.mark.parametrize("cout", [1, 2, 3, 4])
+@pytest.mark.parametrize("cin", [48, 64])
+def test_narrow_output_layers_on_the_two_dimensional_tile_kernel(cout, cin):
+    """The same layers where that kernel takes them (3x3, stride 1, 48 or 64 input channels, unsigned inputs up to 127):
+    a lane's first accumulator registers are the layer's channels."""
+    from paper_2006_11735_amd import binding as B
+    B.icnn_set_tuning("no_narrow", 1)
+    B.icnn_set_tuning("plane_always", 1)
+    try:
+        check_narrow_output_layer(cout, (3, 1, 1, cin))
+    finally:
+        B.icnn_set_tuning("reset")
+
+
+def check_narrow_output_layer(cout, geom):
     k, stride, pad, cin = geom
     h, w = (521, 419) if cout == 1 else (21, 19)
     x, wt, b = make(40 + cout, 2, h, w, cin, cout, k)
