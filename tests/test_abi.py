@@ -123,6 +123,36 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     assert e.value.code == B.ICNN_E_NULL
 
 
+def test_twin_layers_are_refused_on_the_host_where_the_fused_kernel_does_not_take_them():
+    """iconv2d_twin_brelu checks both descriptors, the pointers and the pair's shape before anything is launched."""
+    B = binding()
+
+    def branch(k, cout, off, **kw):
+        args = dict(h=32, w=64, cout=cout, kh=k, kw=k, pad_h=k // 2, pad_w=k // 2, out_c_stride=48, out_c_offset=off)
+        args.update(kw)
+        return good(B, **args)
+    x, wa, wb, ba, bb, y = 4096, 8192, 12288, 16384, 20480, 24576
+    cases = [
+        ((branch(5, 32, 0), branch(5, 16, 32)), B.ICNN_E_UNSUPPORTED),                      # kernels of one size
+        ((branch(7, 32, 0), branch(5, 16, 32)), B.ICNN_E_UNSUPPORTED),                      # no 7x7 form
+        ((branch(5, 32, 0), branch(3, 16, 32, h=16)), B.ICNN_E_SHAPE),                      # different pictures
+        ((branch(5, 32, 0), branch(3, 16, 32, cin=48, in_c_stride=48)), B.ICNN_E_SHAPE),    # different inputs
+        ((branch(5, 32, 0, res_mode=B.ICNN_RES_PRE, res_c_stride=32), branch(3, 16, 32)), B.ICNN_E_UNSUPPORTED),
+        ((branch(5, 32, 0, in_signed=B.ICNN_IN_U8_FULL), branch(3, 16, 32, in_signed=B.ICNN_IN_U8_FULL)), B.ICNN_E_UNSUPPORTED),
+        ((branch(5, 32, 0, cin=32, in_c_stride=32), branch(3, 16, 32, cin=32, in_c_stride=32)), B.ICNN_E_UNSUPPORTED),
+    ]
+    for (da, db), code in cases:
+        with pytest.raises(B.IcnnError) as e:
+            B.iconv2d_twin_brelu(da, x, wa, ba, y, db, wb, bb, y, stream=0)
+        assert e.value.code == code, (da.kh, db.kh, e.value.code)
+    with pytest.raises(B.IcnnError) as e:
+        B.iconv2d_twin_brelu(branch(5, 32, 0), x, wa, ba, y, branch(3, 16, 32), wb, bb, None, stream=0)
+    assert e.value.code == B.ICNN_E_NULL
+    with pytest.raises(B.IcnnError) as e:
+        B.iconv2d_twin_brelu(branch(5, 32, 0), x + 8, wa, ba, y, branch(3, 16, 32), wb, bb, y, stream=0)
+    assert e.value.code == B.ICNN_E_UNSUPPORTED                                              # misaligned input
+
+
 def test_tuning_overrides_are_validated():
     B = binding()
     try:
