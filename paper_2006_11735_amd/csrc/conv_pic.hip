@@ -59,11 +59,17 @@ __global__ __launch_bounds__(256, 4) void conv_pic_kernel(const ConvArgs a, cons
     const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, col = lane & 31;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    for (int i = tid; i < w_bytes / 16; i += 256) {
-        const int chunk = i / (a.ksteps * 128), r = i - chunk * (a.ksteps * 128);
-        *(v4i *)(wbuf + i * 16) = *(const v4i *)(a.wp + ((size_t)chunk * a.ksteps * kChunkBytes) + (size_t)r * 16);
+    // weights (a straight copy of the first CG chunks: at most 2 chunks x 4 K steps x 2 KiB = 4 pieces per thread) and
+    // biases: these loads and the first patch's are all issued before anything is stored, so the prologue costs one
+    // memory latency, not five
+    constexpr int WPT = 4;
+    v4i wv[WPT];
+#pragma unroll
+    for (int q = 0; q < WPT; ++q) {
+        const int i = tid + 256 * q;
+        wv[q] = i < w_bytes / 16 ? *(const v4i *)(a.wp + (size_t)i * 16) : v4i{0, 0, 0, 0};
     }
-    for (int i = tid; i < CG * 32; i += 256) btab[i] = a.bias[i];
+    const int bv = tid < CG * 32 ? a.bias[tid] : 0;
 
     // Work slot v (blockIdx.x, + gridDim.x, ...; the grid is a multiple of 8) is tile (v & 7) * per_xcd + (v >> 3): the
     // workgroups of one XCD (they are dealt round-robin) walk a contiguous range of tiles, so that the picture rows that
@@ -121,10 +127,13 @@ __global__ __launch_bounds__(256, 4) void conv_pic_kernel(const ConvArgs a, cons
         }
     };
 
-    if (valid(blockIdx.x)) {                 // (a workgroup whose first slot is a padding slot has no tile at all)
-        fetch_patch(blockIdx.x);
-        store_patch(0);
-    }
+    const bool first = valid(blockIdx.x);    // (a workgroup whose first slot is a padding slot has no tile at all)
+    if (first) fetch_patch(blockIdx.x);
+#pragma unroll
+    for (int q = 0; q < WPT; ++q)
+        if (tid + 256 * q < w_bytes / 16) *(v4i *)(wbuf + (tid + 256 * q) * 16) = wv[q];
+    if (tid < CG * 32) btab[tid] = bv;
+    if (first) store_patch(0);
     __syncthreads();
     int buf = 0;
     for (int v = blockIdx.x; valid(v); v += gridDim.x) {
