@@ -163,8 +163,29 @@ __global__ __launch_bounds__(512, 1) void conv_plane_kernel(const ConvArgs a, co
     if (valid(blockIdx.x)) issue_patch(blockIdx.x, 0);
     PLANE_TR(0);
     // weights: a straight copy of the first NCH chunks (the packed order is the fragment order)
-    for (int i = tid; i < WBYTES / 16; i += 512) *(v4i *)(wbuf + i * 16) = *(const v4i *)(a.wp + (size_t)i * 16);
-    for (int i = tid; i < WBYTESB / 16; i += 512) *(v4i *)(wbufB + i * 16) = *(const v4i *)(b.wp + (size_t)i * 16);
+    // (direct-to-LDS copies as well, 1 KiB per wave and copy, all in flight together with the first patch: through
+    // registers the copy loop waited out one memory latency per 8 KiB, five of them for a 3x3 layer of 64 channels, which
+    // is most of the kernel's time on a picture with one tile per workgroup)
+    {
+        const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)a.wp, 0, a.wp_bytes, 0x00020000);
+#pragma unroll
+        for (int e0 = 0; e0 < WBYTES / 1024; e0 += 8) {
+            const int e = e0 + wave;
+            if (e < WBYTES / 1024)                   // wave-uniform
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, (__attribute__((address_space(3))) void *)(wbuf + e * 1024), 16,
+                                                         (unsigned)(e * 1024 + lane * 16), 0, 0, 0);
+        }
+        if constexpr (NB > 0) {
+            const __amdgpu_buffer_rsrc_t rs_wb = __builtin_amdgcn_make_buffer_rsrc((void *)b.wp, 0, b.wp_bytes, 0x00020000);
+#pragma unroll
+            for (int e0 = 0; e0 < WBYTESB / 1024; e0 += 8) {
+                const int e = e0 + wave;
+                if (e < WBYTESB / 1024)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_wb, (__attribute__((address_space(3))) void *)(wbufB + e * 1024), 16,
+                                                             (unsigned)(e * 1024 + lane * 16), 0, 0, 0);
+            }
+        }
+    }
     v16i bias[NCH];
     load_bias_rows<NCH>(a, 0, half, bias);
     [[maybe_unused]] v16i biasB[NB ? NB : 1];
